@@ -1,0 +1,119 @@
+/*
+ * vlo -- plain CPU oracle for register-allocation verification.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This is the slow, obviously-correct reference
+ * that the GPU library is compared against.  Nothing in the product path may
+ * include, link or call it; it shares no code, header or table with the HIP
+ * sources.
+ *
+ * What it decides is the paper's notion of a correct allocation
+ * (Introduction, item (1)/(2); Section 2 "Register Allocation"; Section 3.4
+ * "Verifier-guided Inference": Consistency, Safety, Realizability):
+ *   (1) every occurrence of a virtual register carries the same physical
+ *       register,
+ *   (2) virtual registers whose lifetimes overlap occupy disjoint physical
+ *       registers,
+ *   (3) the assignment is realizable on the hardware: a value of width w
+ *       sits in w consecutive 32-bit registers inside its register file,
+ *       suitably aligned, avoiding reserved registers.
+ * The paper decides these with an SMT solver and remarks (Section 4.6) that
+ * the common case only needs the control and data dependencies; lifetimes
+ * here come from the textbook backward may-liveness over the CFG.
+ *
+ * Parity status: every function below is pinned by tests that do not use the
+ * function itself (path enumeration on tiny CFGs, a literal per-point
+ * all-pairs checker, hand-worked examples, allocator/mutation invariants).
+ * Agreement with the paper's own Z3 verdicts is UNPINNED: the SMT encoding is
+ * not published and no solver or dataset is available.
+ *
+ * Conventions.  Instructions 0..N-1 in one linear order; block b is the
+ * contiguous range [blk_start[b], blk_start[b+1]); occurrences (operand
+ * slots) are numbered in instruction order, then operand order.  A bitset
+ * row has W = ceil(V/32) words; vreg v is bit (v & 31) of word (v >> 5).
+ */
+#ifndef VLO_H
+#define VLO_H
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define VLO_OCC_DEF 1u
+#define VLO_OCC_USE 2u
+
+typedef struct {
+  uint32_t n_instr, n_vreg, n_block, n_occ, n_class, n_edge;
+  const uint32_t *blk_start;     /* [n_block+1] */
+  const uint32_t *succ_off;      /* [n_block+1] CSR into succ */
+  const uint32_t *succ;          /* [n_edge] successor block ids */
+  const uint32_t *instr_occ_off; /* [n_instr+1] CSR into occurrences */
+  const uint32_t *occ_vreg;      /* [n_occ] */
+  const uint8_t *occ_flags;      /* [n_occ] VLO_OCC_DEF | VLO_OCC_USE */
+  const uint8_t *vreg_class;     /* [n_vreg] */
+  const uint8_t *vreg_width;     /* [n_vreg] in 32-bit registers */
+  const uint8_t *vreg_align;     /* [n_vreg] required divisor of the base */
+  const uint16_t *class_size;    /* [n_class] registers in the file */
+  const uint32_t *class_reserved;/* [n_class][16] 512-bit masks or NULL */
+} vlo_mir;
+
+typedef struct { uint32_t status, where, a, b; } vlo_result;
+enum { VLO_OK = 0, VLO_CONSISTENCY = 1, VLO_REALIZABILITY = 2, VLO_SAFETY = 3 };
+enum { VLO_BAD_BOUNDS = 1, VLO_BAD_ALIGN = 2, VLO_BAD_RESERVED = 4 };
+
+typedef struct { uint32_t a, b, first; } vlo_edge; /* a < b, first common point */
+
+/* Block-level liveness: least fixed point of
+ *   out[b] = union of in[s] over successors s,  in[b] = use[b] | (out[b] \ def[b]).
+ * live_in / live_out: [n_block][n_vreg] membership bytes (0/1), caller-owned.
+ * Returns the number of sweeps over the blocks that were needed. */
+int vlo_block_liveness(const vlo_mir *m, uint8_t *live_in, uint8_t *live_out);
+
+/* Per-point liveness: live_after[i] for every instruction, by the backward
+ * walk inside each block from live_out.  Bit-packed rows [n_instr][W]. */
+void vlo_points(const vlo_mir *m, const uint8_t *live_out, uint32_t *live_after);
+
+/* Occupancy rows P(i) = live_after[i] | defs(i), [n_instr][W]. */
+void vlo_occupancy(const vlo_mir *m, const uint32_t *live_after, uint32_t *P);
+
+/* Kill flag of each occurrence: 1 iff it is a USE of v at i and v is not in
+ * P(i); 0 otherwise (in particular for pure DEF occurrences). [n_occ] */
+void vlo_kill_flags(const vlo_mir *m, const uint32_t *P, uint8_t *occ_kill);
+
+/* Live intervals: for each vreg the maximal runs of {i : v in P(i)} in linear
+ * order as half-open [start,end).  seg_off[V+1]; seg holds up to cap pairs.
+ * hull[v] = [min start, max end) or [0,0) if v is never occupied.
+ * Returns the total number of segments (call with cap = 0 to size). */
+uint64_t vlo_segments(const vlo_mir *m, const uint32_t *P, uint32_t *seg_off,
+                      uint32_t *seg, uint64_t cap, uint32_t *hull);
+
+/* Interference relation by the pairwise O(V^2) test: for all a < b of the
+ * same class whose interval lists share a point, the smallest such point.
+ * Returns the number of edges (call with cap = 0 to size). */
+uint64_t vlo_interference(const vlo_mir *m, const uint32_t *seg_off,
+                          const uint32_t *seg, vlo_edge *edges, uint64_t cap,
+                          int n_threads);
+
+/* first[v] = smallest occurrence index of v, or UINT32_MAX. [n_vreg] */
+void vlo_first_occurrence(const vlo_mir *m, uint32_t *first);
+
+/* Verify K candidates (row k at cand + k*ld, one uint16 per occurrence)
+ * against the interference relation.  out[K]. */
+void vlo_verify(const vlo_mir *m, const vlo_edge *edges, uint64_t n_edges,
+                const uint16_t *cand, uint32_t K, uint64_t ld, vlo_result *out,
+                int n_threads);
+
+/* The definition written out with no interference relation: at every point,
+ * every pair of P(i).  One candidate. */
+void vlo_verify_points(const vlo_mir *m, const uint32_t *P, const uint16_t *cand,
+                       vlo_result *out);
+
+/* Input contract used by the tile-parallel GPU walk: 0 if live_in[entry] is
+ * empty and every non-entry block has a predecessor earlier in linear order;
+ * 1 if the entry has live-ins; 2 if some block lacks an earlier predecessor. */
+int vlo_contract(const vlo_mir *m, const uint8_t *live_in);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,166 @@
+"""ctypes wrapper around the C oracle (oracle/vlo.c).  TEST INFRASTRUCTURE ONLY.
+
+Marshals a program description (any object with the array attributes of
+vlgen.mir.Mir) into the oracle's own structures and returns numpy arrays.
+It imports nothing from the GPU package.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import numpy as np
+
+from . import build as _build
+
+RESULT_DTYPE = np.dtype([("status", "<u4"), ("where", "<u4"), ("a", "<u4"), ("b", "<u4")])
+EDGE_DTYPE = np.dtype([("a", "<u4"), ("b", "<u4"), ("first", "<u4")])
+OK, CONSISTENCY, REALIZABILITY, SAFETY = 0, 1, 2, 3
+BAD_BOUNDS, BAD_ALIGN, BAD_RESERVED = 1, 2, 4
+
+
+class _Mir(C.Structure):
+    _fields_ = [(n, C.c_uint32) for n in
+                ("n_instr", "n_vreg", "n_block", "n_occ", "n_class", "n_edge")] + \
+               [(n, C.c_void_p) for n in
+                ("blk_start", "succ_off", "succ", "instr_occ_off", "occ_vreg", "occ_flags",
+                 "vreg_class", "vreg_width", "vreg_align", "class_size", "class_reserved")]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(_build.build())
+        _lib.vlo_block_liveness.restype = C.c_int
+        _lib.vlo_segments.restype = C.c_uint64
+        _lib.vlo_interference.restype = C.c_uint64
+        _lib.vlo_contract.restype = C.c_int
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _marshal(m):
+    keep = dict(
+        blk_start=np.ascontiguousarray(m.blk_start, np.uint32),
+        succ_off=np.ascontiguousarray(m.succ_off, np.uint32),
+        succ=np.ascontiguousarray(m.succ, np.uint32),
+        instr_occ_off=np.ascontiguousarray(m.instr_occ_off, np.uint32),
+        occ_vreg=np.ascontiguousarray(m.occ_vreg, np.uint32),
+        occ_flags=np.ascontiguousarray(m.occ_flags, np.uint8),
+        vreg_class=np.ascontiguousarray(m.vreg_class, np.uint8),
+        vreg_width=np.ascontiguousarray(m.vreg_width, np.uint8),
+        vreg_align=np.ascontiguousarray(m.vreg_align, np.uint8),
+        class_size=np.ascontiguousarray(m.class_size, np.uint16),
+        class_reserved=None if m.class_reserved is None else
+        np.ascontiguousarray(m.class_reserved, np.uint32),
+    )
+    s = _Mir(len(keep["instr_occ_off"]) - 1, len(keep["vreg_class"]), len(keep["blk_start"]) - 1,
+             len(keep["occ_vreg"]), len(keep["class_size"]), len(keep["succ"]),
+             *[_p(keep[k]) for k in ("blk_start", "succ_off", "succ", "instr_occ_off", "occ_vreg",
+                                     "occ_flags", "vreg_class", "vreg_width", "vreg_align",
+                                     "class_size", "class_reserved")])
+    return s, keep
+
+
+@dataclass
+class Analysis:
+    """Everything the oracle derives from a program alone."""
+    live_in: np.ndarray      # uint8 [n_block, V]
+    live_out: np.ndarray     # uint8 [n_block, V]
+    live_after: np.ndarray   # uint32 [N, W] bit-packed
+    P: np.ndarray            # uint32 [N, W] occupancy rows
+    occ_kill: np.ndarray     # uint8 [O]
+    seg_off: np.ndarray      # uint32 [V+1]
+    seg: np.ndarray          # uint32 [S, 2]
+    hull: np.ndarray         # uint32 [V, 2]
+    first: np.ndarray        # uint32 [V]
+    sweeps: int
+    contract: int
+    edges: np.ndarray | None = None  # EDGE_DTYPE [E]
+
+
+def unpack_bits(rows: np.ndarray, n_vreg: int) -> np.ndarray:
+    """[.., W] uint32 -> [.., V] uint8 membership."""
+    b = np.unpackbits(np.ascontiguousarray(rows).view(np.uint8), axis=-1, bitorder="little")
+    return b[..., :n_vreg]
+
+
+def pack_bits(member: np.ndarray) -> np.ndarray:
+    """[.., V] 0/1 -> [.., W] uint32."""
+    V = member.shape[-1]
+    W = (V + 31) // 32
+    pad = np.zeros(member.shape[:-1] + (W * 32,), np.uint8)
+    pad[..., :V] = member
+    return np.packbits(pad, axis=-1, bitorder="little").view(np.uint32).reshape(member.shape[:-1] + (W,))
+
+
+def analyze(m, interference: bool = True, threads: int = 1) -> Analysis:
+    s, keep = _marshal(m)
+    L = lib()
+    N, V, B, O = s.n_instr, s.n_vreg, s.n_block, s.n_occ
+    W = (V + 31) // 32
+    live_in = np.zeros((B, V), np.uint8)
+    live_out = np.zeros((B, V), np.uint8)
+    sweeps = L.vlo_block_liveness(C.byref(s), _p(live_in), _p(live_out))
+    live_after = np.zeros((N, W), np.uint32)
+    L.vlo_points(C.byref(s), _p(live_out), _p(live_after))
+    P = np.zeros((N, W), np.uint32)
+    L.vlo_occupancy(C.byref(s), _p(live_after), _p(P))
+    kill = np.zeros(O, np.uint8)
+    L.vlo_kill_flags(C.byref(s), _p(P), _p(kill))
+    seg_off = np.zeros(V + 1, np.uint32)
+    hull = np.zeros((V, 2), np.uint32)
+    n = L.vlo_segments(C.byref(s), _p(P), _p(seg_off), None, C.c_uint64(0), _p(hull))
+    seg = np.zeros((max(n, 1), 2), np.uint32)
+    L.vlo_segments(C.byref(s), _p(P), _p(seg_off), _p(seg), C.c_uint64(n), _p(hull))
+    seg = seg[:n]
+    first = np.zeros(V, np.uint32)
+    L.vlo_first_occurrence(C.byref(s), _p(first))
+    contract = L.vlo_contract(C.byref(s), _p(live_in))
+    an = Analysis(live_in, live_out, live_after, P, kill, seg_off, seg, hull, first, sweeps, contract)
+    if interference:
+        an.edges = interference_edges(m, an, threads)
+    return an
+
+
+def interference_edges(m, an: Analysis, threads: int = 1) -> np.ndarray:
+    s, keep = _marshal(m)
+    L = lib()
+    seg = np.ascontiguousarray(an.seg if len(an.seg) else np.zeros((1, 2), np.uint32))
+    n = L.vlo_interference(C.byref(s), _p(an.seg_off), _p(seg), None, C.c_uint64(0), C.c_int(threads))
+    edges = np.zeros(max(n, 1), EDGE_DTYPE)
+    L.vlo_interference(C.byref(s), _p(an.seg_off), _p(seg), _p(edges), C.c_uint64(n), C.c_int(threads))
+    return edges[:n]
+
+
+def verify(m, an: Analysis, cand: np.ndarray, threads: int = 1) -> np.ndarray:
+    """cand: uint16 [K, ld] with ld >= n_occ.  Returns RESULT_DTYPE [K]."""
+    s, keep = _marshal(m)
+    cand = np.asarray(cand)
+    assert cand.dtype == np.uint16 and cand.ndim == 2 and cand.shape[1] >= s.n_occ
+    assert cand.strides[1] == 2
+    K, ld = cand.shape[0], cand.strides[0] // 2
+    out = np.zeros(K, RESULT_DTYPE)
+    edges = an.edges if an.edges is not None else interference_edges(m, an, threads)
+    e = np.ascontiguousarray(edges if len(edges) else np.zeros(1, EDGE_DTYPE))
+    lib().vlo_verify(C.byref(s), _p(e), C.c_uint64(len(edges)), _p(cand), C.c_uint32(K),
+                     C.c_uint64(ld), _p(out), C.c_int(threads))
+    return out
+
+
+def verify_points(m, an: Analysis, cand: np.ndarray) -> np.ndarray:
+    """The literal per-point all-pairs definition, one row at a time."""
+    s, keep = _marshal(m)
+    cand = np.ascontiguousarray(np.atleast_2d(cand), np.uint16)
+    out = np.zeros(cand.shape[0], RESULT_DTYPE)
+    P = np.ascontiguousarray(an.P)
+    for k in range(cand.shape[0]):
+        lib().vlo_verify_points(C.byref(s), _p(P), _p(cand[k]), C.c_void_p(out[k:k + 1].ctypes.data))
+    return out

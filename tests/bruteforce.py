@@ -1,0 +1,143 @@
+"""Pure-Python brute force used to pin the C oracle on tiny programs.
+
+Written straight from the definitions, with no fixed point and no interval
+lists: liveness by graph search over instructions, safety by enumerating every
+point and every pair.  Only usable for a few dozen instructions.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+DEF, USE = 1, 2
+
+
+def instr_block(m):
+    blk = np.zeros(m.n_instr, np.int64)
+    for b in range(m.n_block):
+        blk[m.blk_start[b]:m.blk_start[b + 1]] = b
+    return blk
+
+
+def first_instr_of(m, b, seen=None):
+    """Entry points of block b: its first instruction, or (empty block) those of
+    its successors."""
+    seen = set() if seen is None else seen
+    if b in seen:
+        return []
+    seen.add(b)
+    if m.blk_start[b] < m.blk_start[b + 1]:
+        return [int(m.blk_start[b])]
+    out = []
+    for e in range(m.succ_off[b], m.succ_off[b + 1]):
+        out += first_instr_of(m, int(m.succ[e]), seen)
+    return out
+
+
+def instr_succ(m):
+    blk = instr_block(m)
+    succ = []
+    for i in range(m.n_instr):
+        b = blk[i]
+        if i + 1 < m.blk_start[b + 1]:
+            succ.append([i + 1])
+        else:
+            s = []
+            for e in range(m.succ_off[b], m.succ_off[b + 1]):
+                s += first_instr_of(m, int(m.succ[e]))
+            succ.append(sorted(set(s)))
+    return succ
+
+
+def uses_defs(m):
+    uses, defs = [], []
+    for i in range(m.n_instr):
+        u, d = set(), set()
+        for o in range(m.instr_occ_off[i], m.instr_occ_off[i + 1]):
+            if m.occ_flags[o] & USE:
+                u.add(int(m.occ_vreg[o]))
+            if m.occ_flags[o] & DEF:
+                d.add(int(m.occ_vreg[o]))
+        uses.append(u)
+        defs.append(d)
+    return uses, defs
+
+
+def live_after_by_search(m):
+    """v is live after i iff some path leaves i, reaches an instruction that
+    reads v, and no instruction strictly in between writes v."""
+    succ = instr_succ(m)
+    uses, defs = uses_defs(m)
+    res = []
+    for i in range(m.n_instr):
+        live = set()
+        for v in range(m.n_vreg):
+            seen, stack, hit = set(), list(succ[i]), False
+            while stack and not hit:
+                j = stack.pop()
+                if j in seen:
+                    continue
+                seen.add(j)
+                if v in uses[j]:
+                    hit = True
+                elif v not in defs[j]:
+                    stack.extend(succ[j])
+            if hit:
+                live.add(v)
+        res.append(live)
+    return res
+
+
+def occupancy(m, live_after):
+    _, defs = uses_defs(m)
+    return [live_after[i] | defs[i] for i in range(m.n_instr)]
+
+
+def first_occ(m):
+    first = {}
+    for o in range(m.n_occ):
+        first.setdefault(int(m.occ_vreg[o]), o)
+    return first
+
+
+def realizability_bits(m, v, p):
+    c, w, al = int(m.vreg_class[v]), int(m.vreg_width[v]), int(m.vreg_align[v])
+    bad = 0
+    if p + w > int(m.class_size[c]):
+        bad |= 1
+    if p % al:
+        bad |= 2
+    if m.class_reserved is not None:
+        for r in range(p, p + w):
+            if r < 512 and (int(m.class_reserved[c][r >> 5]) >> (r & 31)) & 1:
+                bad |= 4
+    return bad
+
+
+def verify(m, P, row, def_points_only=False):
+    """(status, where, a, b) by the definition.  With def_points_only, a pair is
+    only examined at instructions that define one of its members (the claim
+    that this finds the same first violation is what the GPU walk relies on)."""
+    first = first_occ(m)
+    for o in range(m.n_occ):
+        v = int(m.occ_vreg[o])
+        if row[o] != row[first[v]]:
+            return (1, o, v, first[v])
+    bad = [(first[v], v, realizability_bits(m, v, int(row[first[v]]))) for v in first]
+    bad = [t for t in bad if t[2]]
+    if bad:
+        return (2,) + min(bad)
+    _, defs = uses_defs(m)
+    for i in range(m.n_instr):
+        hits = []
+        for a in sorted(P[i]):
+            for b in sorted(P[i]):
+                if a >= b or m.vreg_class[a] != m.vreg_class[b]:
+                    continue
+                if def_points_only and a not in defs[i] and b not in defs[i]:
+                    continue
+                pa, pb = int(row[first[a]]), int(row[first[b]])
+                if pa < pb + int(m.vreg_width[b]) and pb < pa + int(m.vreg_width[a]):
+                    hits.append((a, b))
+        if hits:
+            return (3, i) + min(hits)
+    return (0, 0, 0, 0)
