@@ -98,26 +98,44 @@ void vlo_kill_flags(const vlo_mir *m, const uint32_t *P, uint8_t *occ_kill) {
 /* ---- live intervals ----------------------------------------------------- */
 uint64_t vlo_segments(const vlo_mir *m, const uint32_t *P, uint32_t *seg_off,
                       uint32_t *seg, uint64_t cap, uint32_t *hull) {
-  const uint32_t W = words_per_row(m), N = m->n_instr;
-  uint64_t n = 0;
-  for (uint32_t v = 0; v < m->n_vreg; ++v) {
-    seg_off[v] = (uint32_t)n;
-    uint32_t lo = 0, hi = 0;
-    int any = 0;
-    uint32_t i = 0;
-    while (i < N) {
-      if (!bit_get(P + (size_t)i * W, v)) { ++i; continue; }
-      uint32_t s = i;
-      while (i < N && bit_get(P + (size_t)i * W, v)) ++i;
-      if (n < cap) { seg[2 * n] = s; seg[2 * n + 1] = i; }
-      ++n;
-      if (!any) { lo = s; any = 1; }
-      hi = i;
+  /* A run of v starts at i when v is in P(i) but not in P(i-1) and ends at the
+   * first later i where v has left.  Rows are visited in order (two passes:
+   * count the runs per vreg, then write them), which only changes the order
+   * in which the same membership tests are made. */
+  const uint32_t W = words_per_row(m), N = m->n_instr, V = m->n_vreg;
+  uint32_t *cnt = (uint32_t *)calloc((size_t)V + 1, 4);
+  for (uint32_t i = 0; i < N; ++i)
+    for (uint32_t v = 0; v < V; ++v) {
+      if ((v & 31) == 0) {  /* skip words with no rising bit */
+        uint32_t now = P[(size_t)i * W + (v >> 5)], was = i ? P[(size_t)(i - 1) * W + (v >> 5)] : 0;
+        if ((now & ~was) == 0) { v += 31; continue; }
+      }
+      if (bit_get(P + (size_t)i * W, v) && !(i && bit_get(P + (size_t)(i - 1) * W, v))) ++cnt[v];
     }
-    hull[2 * v] = lo;
-    hull[2 * v + 1] = hi;
+  uint64_t n = 0;
+  for (uint32_t v = 0; v < V; ++v) { seg_off[v] = (uint32_t)n; n += cnt[v]; cnt[v] = 0; }
+  seg_off[V] = (uint32_t)n;
+  for (uint32_t v = 0; v < V; ++v) { hull[2 * v] = 0; hull[2 * v + 1] = 0; }
+  if (n <= cap && seg) {
+    for (uint32_t i = 0; i <= N; ++i)
+      for (uint32_t v = 0; v < V; ++v) {
+        if ((v & 31) == 0) {  /* skip words where nothing changes */
+          uint32_t now = i < N ? P[(size_t)i * W + (v >> 5)] : 0, was = i ? P[(size_t)(i - 1) * W + (v >> 5)] : 0;
+          if (now == was) { v += 31; continue; }
+        }
+        int in_now = i < N && bit_get(P + (size_t)i * W, v);
+        int in_was = i && bit_get(P + (size_t)(i - 1) * W, v);
+        if (in_now && !in_was) {
+          seg[2 * ((size_t)seg_off[v] + cnt[v])] = i;
+          if (cnt[v] == 0) hull[2 * v] = i;
+        } else if (!in_now && in_was) {
+          seg[2 * ((size_t)seg_off[v] + cnt[v]) + 1] = i;
+          hull[2 * v + 1] = i;
+          ++cnt[v];
+        }
+      }
   }
-  seg_off[m->n_vreg] = (uint32_t)n;
+  free(cnt);
   return n;
 }
 

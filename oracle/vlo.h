@@ -83,7 +83,8 @@ void vlo_kill_flags(const vlo_mir *m, const uint32_t *P, uint8_t *occ_kill);
 /* Live intervals: for each vreg the maximal runs of {i : v in P(i)} in linear
  * order as half-open [start,end).  seg_off[V+1]; seg holds up to cap pairs.
  * hull[v] = [min start, max end) or [0,0) if v is never occupied.
- * Returns the total number of segments (call with cap = 0 to size). */
+ * Returns the total number of segments; seg and hull are only written when
+ * cap is large enough (call with seg = NULL, cap = 0 to size). */
 uint64_t vlo_segments(const vlo_mir *m, const uint32_t *P, uint32_t *seg_off,
                       uint32_t *seg, uint64_t cap, uint32_t *hull);
 
