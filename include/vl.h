@@ -1,0 +1,165 @@
+/*
+ * vl -- GPU (gfx950) verifier core for sampled register allocations.
+ *
+ * Decides, for many candidate virtual-to-physical register assignments of one
+ * machine-IR kernel at once, the conditions under which the paper calls an
+ * allocation correct (Section 1, items (1) and (2); Section 2 "Register
+ * Allocation"; Section 3.4 Consistency / Safety / Realizability), using the
+ * polynomial check along control and data dependencies that Section 4.6
+ * points to instead of an SMT solver.  Two stages:
+ *
+ *   vl_liveness       backward dataflow liveness over the CFG as bitset
+ *                     union / and-not per basic block, iterated to the least
+ *                     fixed point; per-point live sets, kill flags, live
+ *                     intervals; and the event stream the verifier replays.
+ *   vl_verify_batch   replays that stream for K candidates, 64 candidates per
+ *                     wavefront, and reports each candidate's status and its
+ *                     first violation.
+ *
+ * All entry points are plain C.  Pointers marked [host] are read during the
+ * call only; pointers marked [device] must be device memory valid on the
+ * current HIP device and are never owned or freed by the library.  Handles
+ * are created and destroyed by the library.  Every function returns VL_OK (0)
+ * or a negative error code and never aborts; a candidate that breaks a
+ * condition is not an error but a status in the output.
+ *
+ * Program model.  Instructions 0..N-1 in one linear order; block b is the
+ * contiguous range [blk_start[b], blk_start[b+1]), block 0 is the entry;
+ * operand occurrences are numbered in instruction order, then operand order.
+ * An instruction reads its USE operands before it writes its DEF operands
+ * (a DEF may reuse the register of an operand that dies at that instruction).
+ * Bitset rows have W = ceil(n_vreg/32) words; vreg v is bit (v & 31) of word
+ * (v >> 5).
+ */
+#ifndef VL_H
+#define VL_H
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  VL_OK = 0,
+  VL_E_NULL = -1,       /* a required pointer is NULL */
+  VL_E_SHAPE = -2,      /* inconsistent sizes: offsets not monotone, K == 0, ld < n_occ, ... */
+  VL_E_RANGE = -3,      /* vreg id >= n_vreg, class >= n_class, file > 512, width 0 or > 32,
+                           align 0 or > 32, more than 8 classes, more than 64 operands in one
+                           instruction, unknown occurrence flag bits, successor >= n_block */
+  VL_E_LAYOUT = -4,     /* blocks do not tile 0..N-1, a block is empty, or a non-entry block has
+                           no predecessor placed before it in the linear order */
+  VL_E_NOT_STRICT = -5, /* some value is live into the entry block */
+  VL_E_HIP = -6,        /* a HIP runtime call failed; see vl_last_hip_error */
+  VL_E_ARG = -7         /* handle does not belong to this call (wrong program, stale, ...) */
+};
+
+#define VL_OCC_DEF 1u
+#define VL_OCC_USE 2u
+
+/* vl_liveness flags */
+#define VL_DENSE_POINTS 1u /* also materialise live_after[N][W] */
+
+/* Description of one kernel; every pointer is [host]. */
+typedef struct {
+  uint32_t n_instr, n_vreg, n_block, n_occ, n_class, n_edge;
+  const uint32_t *blk_start;      /* [n_block+1], blk_start[0] = 0, last = n_instr */
+  const uint32_t *succ_off;       /* [n_block+1] CSR offsets into succ */
+  const uint32_t *succ;           /* [n_edge] successor block ids */
+  const uint32_t *instr_occ_off;  /* [n_instr+1] CSR offsets into occurrences */
+  const uint32_t *occ_vreg;       /* [n_occ] */
+  const uint8_t *occ_flags;       /* [n_occ] VL_OCC_DEF | VL_OCC_USE */
+  const uint8_t *vreg_class;      /* [n_vreg] */
+  const uint8_t *vreg_width;      /* [n_vreg] width in 32-bit registers, 1..32 */
+  const uint8_t *vreg_align;      /* [n_vreg] base must be a multiple of this, 1..32 */
+  const uint16_t *class_size;     /* [n_class] registers in the file, <= 512 */
+  const uint32_t *class_reserved; /* [n_class][16] 512-bit masks of unusable registers, or NULL */
+} vl_mir_desc;
+
+typedef struct vl_mir vl_mir;   /* a kernel resident on the device */
+typedef struct vl_live vl_live; /* its liveness analysis, resident on the device */
+typedef void *vl_stream;        /* a hipStream_t (NULL = the default stream) */
+
+/* Validates the description (Section 2: programs in MIR, virtual registers,
+ * register classes and tuples) and copies it to the current device.
+ * Synchronous.  *out is written only on success. */
+int32_t vl_mir_create(const vl_mir_desc *desc, vl_mir **out);
+void vl_mir_destroy(vl_mir *mir);
+
+/* Liveness analysis of n kernels in one batch of launches (Section 3.2: the
+ * control flow and data dependency of the input; Section 3.4 Safety: which
+ * lifetimes overlap).  Enqueues on `stream`, synchronises it once to read the
+ * result sizes and error flags back, then enqueues the remaining work; the
+ * results are complete once the stream has been synchronised again.
+ *
+ * live[0..n): on entry either all NULL, or the n handles a previous call with
+ * these same kernels returned, whose device storage is then reused (no
+ * allocation when it is large enough).  On success live[i] describes mirs[i].
+ * On error no handle is created; recycled handles stay allocated but their
+ * contents are undefined until the next successful call.
+ * tile_len: instructions per verification tile, 0 = library default.
+ * Errors: VL_E_NOT_STRICT / VL_E_LAYOUT refer to the first offending kernel. */
+int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint32_t flags, uint32_t tile_len,
+                          vl_stream stream, vl_live **live);
+/* The same for one kernel. */
+int32_t vl_liveness(const vl_mir *mir, uint32_t flags, vl_stream stream, vl_live **live);
+void vl_live_destroy(vl_live *live);
+
+/* Device views of one analysis; every pointer is [device], owned by the
+ * handle, valid until it is destroyed or recycled. */
+typedef struct {
+  uint32_t n_instr, n_vreg, n_block, n_occ, words; /* words = W */
+  uint32_t n_seg;                 /* total number of live-interval segments */
+  uint32_t n_tile, tile_len;      /* verification tiles */
+  uint32_t plan_len;              /* entries of the verifier's event stream */
+  uint32_t sweeps;                /* fixed-point sweeps of the slowest word column */
+  const uint32_t *live_in;        /* [n_block][W] */
+  const uint32_t *live_out;       /* [n_block][W] */
+  const uint32_t *live_after;     /* [n_instr][W], NULL unless VL_DENSE_POINTS */
+  const uint8_t *occ_kill;        /* [n_occ] 1 iff a USE of v at i and v not in P(i) */
+  const uint32_t *seg_off;        /* [n_vreg+1] CSR offsets into seg */
+  const uint32_t *seg;            /* [n_seg][2] maximal runs of {i : v in P(i)} as [start,end) */
+  const uint32_t *hull;           /* [n_vreg][2] [min start, max end) or [0,0) */
+} vl_live_view;
+int32_t vl_live_get(const vl_live *live, vl_live_view *out);
+
+/* Result per candidate.
+ * status 0 OK            where = a = b = 0
+ *        1 CONSISTENCY   where = smallest occurrence o whose register differs from that of the
+ *                        first occurrence of its vreg; a = vreg; b = that first occurrence
+ *        2 REALIZABILITY where = first occurrence of the offending vreg with the smallest first
+ *                        occurrence; a = vreg; b = VL_BAD_* bits
+ *        3 SAFETY        where = smallest instruction i at which two vregs of one class, both in
+ *                        P(i) = live_after(i) + defs(i), have overlapping register ranges;
+ *                        (a, b), a < b, the lexicographically smallest such pair at i
+ * Consistency outranks realizability outranks safety. */
+typedef struct { uint32_t status, where, a, b; } vl_result;
+enum { VL_STATUS_OK = 0, VL_STATUS_CONSISTENCY = 1, VL_STATUS_REALIZABILITY = 2, VL_STATUS_SAFETY = 3 };
+enum { VL_BAD_BOUNDS = 1, VL_BAD_ALIGN = 2, VL_BAD_RESERVED = 4 };
+
+/* Checks K candidates of one kernel (Section 3.4; Section 3.4's regeneration
+ * loop supplies the K samples).  cand [device]: K rows of uint16, row k at
+ * cand + k*ld, one physical base register per operand occurrence; ld >= n_occ.
+ * Rows are read fastest when cand is 16-byte aligned and ld is a multiple of 8.
+ * out [device]: K results.  Asynchronous on `stream`. */
+int32_t vl_verify_batch(const vl_mir *mir, const vl_live *live, const uint16_t *cand, uint32_t K,
+                        uint64_t ld, vl_result *out, vl_stream stream);
+
+/* Many kernels in one launch.  jobs is [host]; cand/out inside are [device]. */
+typedef struct {
+  const vl_mir *mir;
+  const vl_live *live;
+  const uint16_t *cand;
+  uint32_t K;
+  uint64_t ld;
+  vl_result *out;
+} vl_job;
+int32_t vl_verify_multi(const vl_job *jobs, uint32_t n_jobs, vl_stream stream);
+
+const char *vl_strerror(int32_t code);
+/* hipError_t of the last failed runtime call on this thread (0 if none). */
+int32_t vl_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,133 @@
+// Internal device-side layouts shared by the liveness and verification kernels.
+#ifndef VL_DEV_H
+#define VL_DEV_H
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/vl.h"
+
+namespace vl {
+
+constexpr uint32_t kMaxClass = 8;
+constexpr uint32_t kMaxOperands = 64;      // per instruction
+constexpr uint32_t kNone = 0xFFFFFFFFu;
+constexpr uint32_t kDefaultTile = 1024;    // instructions per verification tile
+
+// Kernel (program) on the device.  All pointers are device memory.
+struct DevMir {
+  uint32_t N, V, B, O, C, E, W;
+  uint32_t occ_words;              // occupancy words summed over classes
+  const uint32_t *blk_start;       // [B+1]
+  const uint32_t *succ_off, *succ; // CSR successors
+  const uint32_t *occ_off;         // [N+1]
+  const uint32_t *occ_vreg;        // [O]
+  const uint32_t *occ_instr;       // [O] instruction of each occurrence
+  const uint32_t *instr_blk;       // [N] block of each instruction
+  const uint32_t *vattr;           // [V] packed attributes, see attr_* below
+  const uint8_t *occ_flags;        // [O]
+  uint32_t has_reserved;
+  uint16_t class_size[kMaxClass];
+  uint16_t class_word[kMaxClass];  // first occupancy word of the class
+  uint32_t reserved[kMaxClass][16];
+};
+
+// Packed vreg attributes: class | (width-1) << 3 | (align-1) << 8 | straddle << 13.
+// straddle = a correctly aligned tuple may cross a 32-register word.
+__host__ __device__ inline uint32_t attr_pack(uint32_t cls, uint32_t width, uint32_t align) {
+  bool word_safe = (32u % align == 0u) && width <= align;
+  return cls | ((width - 1u) << 3) | ((align - 1u) << 8) | ((word_safe ? 0u : 1u) << 13);
+}
+__host__ __device__ inline uint32_t attr_class(uint32_t a) { return a & 7u; }
+__host__ __device__ inline uint32_t attr_width(uint32_t a) { return ((a >> 3) & 31u) + 1u; }
+__host__ __device__ inline uint32_t attr_align(uint32_t a) { return ((a >> 8) & 31u) + 1u; }
+__host__ __device__ inline uint32_t attr_straddle(uint32_t a) { return (a >> 13) & 1u; }
+
+// Event-stream ("plan") entry, 8 bytes:
+//   x: occurrence index (24 bits) | flags << 24
+//   y: distance to the previous occurrence of the same vreg (16 bits, saturated)
+//      | packed attributes << 16
+// The verifier processes entries in order.  For each instruction the entries
+// of operands that are only read come first, then those that are written,
+// then the post-instruction kills; entries of a block boundary (values that
+// stop / start being live between two blocks adjacent in the linear order)
+// precede the first instruction of the later block.
+constexpr uint32_t kPlanChk = 1u;    // compare with the previous occurrence of the vreg
+constexpr uint32_t kPlanFirst = 2u;  // first occurrence of the vreg: realizability check
+constexpr uint32_t kPlanSet = 4u;    // test the range against occupancy, then occupy it
+constexpr uint32_t kPlanClr = 8u;    // release the range
+constexpr uint32_t kPlanBirth = 16u; // occupy without testing (value becomes live at a boundary)
+constexpr uint32_t kPlanPost = 32u;  // entry repeats an occurrence already checked (no chk/first)
+
+// Per-occurrence roles computed by the event kernel.
+constexpr uint8_t kRolePreKill = 1, kRoleTestSet = 2, kRolePostKill = 4, kRoleFirst = 8;
+// Per sorted-entry info bits.
+constexpr uint8_t kEntLiveAfter = 1, kEntHasUse = 2, kEntHasDef = 4, kEntGroupStart = 8;
+
+// Liveness analysis of one kernel on the device.
+struct DevLive {
+  // --- sized from the program alone ---
+  uint32_t *vcnt;       // [V+1] occurrences per vreg -> exclusive offsets (vocc_off)
+  uint32_t *vcur;       // [V] placement cursors
+  uint32_t *vocc_tmp;   // [O] occurrences grouped by vreg, unordered
+  uint32_t *vocc;       // [O] occurrences grouped by vreg, ascending
+  uint32_t *ent_instr;  // [O] instruction of each sorted entry
+  uint8_t *ent_info;    // [O] kEnt* bits of each sorted entry
+  uint32_t *first;      // [V] first occurrence or kNone
+  uint32_t *prev_occ;   // [O] previous occurrence of the same vreg or kNone
+  uint8_t *occ_role;    // [O] kRole* bits
+  uint8_t *occ_kill;    // [O]
+  uint32_t *use, *def, *live_in, *live_out;  // [B][W]
+  uint32_t *item_off;   // [N+B+1] plan offset of each item (boundary b at blk_start[b]+b,
+                        //          instruction i of block b at i+b+1)
+  uint32_t *seg_off;    // [V+1]
+  uint32_t *hull;       // [V][2]
+  uint32_t *seed_off;   // [T+1]
+  uint32_t *seed_cur;   // [T]
+  uint32_t *long_queue; // [V] vregs whose occurrence list needs the bitmap sort
+  uint32_t *bitmap;     // [ceil(O/32)] scratch for the bitmap sort, one list at a time per block
+  uint32_t *counters;   // [kCounters]
+  // --- sized after the counting pass ---
+  uint2 *plan;          // [plan_len]
+  uint2 *seeds;         // [n_seed]
+  uint32_t *seg;        // [n_seg][2]
+  uint32_t *tile_range; // [T][2] plan range of each tile
+  uint32_t *tile_live;  // [T][W] live-before row of each tile start (dense mode)
+  uint32_t *live_after; // [N][W] (dense mode)
+  uint32_t T, tile_len, plan_len, n_seg, n_seed, dense;
+};
+
+enum { kCtrLong = 0, kCtrNotStrict = 1, kCtrSweeps = 2, kCtrPlanLen = 3, kCtrSeg = 4, kCtrSeed = 5,
+       kCounters = 8 };
+
+}  // namespace vl
+
+// host-side handles
+struct vl_mir {
+  vl::DevMir h;        // host mirror (device pointers inside)
+  vl::DevMir *dev;     // device copy
+  void *arena;         // single allocation holding every array
+  int device;
+  uint64_t magic;
+};
+
+struct vl_batch;
+struct vl_live {
+  vl_batch *batch;
+  uint32_t index;
+  const vl_mir *mir;
+  vl::DevLive h;       // host mirror
+  vl::DevLive *dev;    // element of the batch's device array
+  uint64_t magic;
+};
+
+namespace vl {
+constexpr uint64_t kMirMagic = 0x564c4d4952ull, kLiveMagic = 0x564c4c495645ull;
+int32_t hip_fail(hipError_t e);
+#define VL_HIP(call)                                   \
+  do {                                                 \
+    hipError_t e_ = (call);                            \
+    if (e_ != hipSuccess) return vl::hip_fail(e_);     \
+  } while (0)
+}  // namespace vl
+
+#endif

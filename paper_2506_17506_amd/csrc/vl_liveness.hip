@@ -1,0 +1,813 @@
+// Liveness analysis on the GPU, batched over kernels (one grid slice per kernel).
+//
+// Pipeline (every step is a kernel below; the host only sizes buffers):
+//   1. group operand occurrences by vreg, ascending (count / scan / place / sort)
+//   2. per-block use and def bitsets from the first mention of each vreg in a block
+//   3. backward dataflow to the least fixed point, one bitset word per lane
+//   4. per occurrence: liveness after its instruction, kill flag, and its role in
+//      the verifier's event stream
+//   5. count, scan and write the event stream, the live intervals and the
+//      per-tile live-in lists; optionally the dense per-point bitsets
+// The paper defers this to "following the control and data dependency"
+// (Section 4.6); the dataflow equations are the textbook ones its Safety
+// condition (Section 3.4) needs to know which lifetimes overlap.
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "vl_dev.h"
+
+using namespace vl;
+
+#define MIRS const DevMir *const *__restrict__ mirs, DevLive *__restrict__ lives
+
+namespace {
+
+__device__ inline bool bit_get(const uint32_t *row, uint32_t v) { return (row[v >> 5] >> (v & 31)) & 1u; }
+
+// first index in [lo,hi) with a[idx] >= key
+__device__ inline uint32_t lower_bound(const uint32_t *a, uint32_t lo, uint32_t hi, uint32_t key) {
+  while (lo < hi) {
+    uint32_t mid = (lo + hi) >> 1;
+    if (a[mid] < key) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+
+// ---- 1. occurrences grouped by vreg -------------------------------------------------
+__global__ void k_count(MIRS) {
+  const DevMir &m = *mirs[blockIdx.y];
+  DevLive &L = lives[blockIdx.y];
+  uint32_t o = blockIdx.x * blockDim.x + threadIdx.x;
+  if (o < m.O) atomicAdd(&L.vcnt[m.occ_vreg[o]], 1u);
+}
+
+enum { kScanVreg = 0, kScanItems = 1, kScanSeg = 2, kScanSeed = 3 };
+
+// In-place exclusive scan of p[0..n), total to p[n]; one 1024-thread block per kernel.
+// (The array is chosen at compile time: a run-time switch over the four arrays was
+// seen to pick the wrong pointer in its default branch.)
+template <int kWhich>
+__global__ __launch_bounds__(1024) void k_scan(MIRS) {
+  const DevMir &m = *mirs[blockIdx.x];
+  DevLive &L = lives[blockIdx.x];
+  uint32_t *p = kWhich == kScanVreg ? L.vcnt : kWhich == kScanItems ? L.item_off : kWhich == kScanSeg ? L.seg_off : L.seed_off;
+  const uint32_t n = kWhich == kScanVreg ? m.V : kWhich == kScanItems ? m.N + m.B : kWhich == kScanSeg ? m.V : L.T;
+  __shared__ uint32_t part[1024];
+  const uint32_t tid = threadIdx.x;
+  const uint32_t chunk = (n + 1023u) / 1024u;
+  const uint32_t lo = min(n, tid * chunk), hi = min(n, lo + chunk);
+  uint32_t sum = 0;
+  for (uint32_t i = lo; i < hi; ++i) sum += p[i];
+  part[tid] = sum;
+  __syncthreads();
+  for (uint32_t d = 1; d < 1024; d <<= 1) {
+    uint32_t t = tid >= d ? part[tid - d] : 0;
+    __syncthreads();
+    part[tid] += t;
+    __syncthreads();
+  }
+  uint32_t base = part[tid] - sum;
+  for (uint32_t i = lo; i < hi; ++i) {
+    uint32_t x = p[i];
+    p[i] = base;
+    base += x;
+  }
+  if (tid == 1023) p[n] = part[1023];
+}
+
+__global__ void k_place(MIRS) {
+  const DevMir &m = *mirs[blockIdx.y];
+  DevLive &L = lives[blockIdx.y];
+  uint32_t o = blockIdx.x * blockDim.x + threadIdx.x;
+  if (o >= m.O) return;
+  uint32_t v = m.occ_vreg[o];
+  L.vocc_tmp[L.vcnt[v] + atomicAdd(&L.vcur[v], 1u)] = o;
+}
+
+constexpr uint32_t kShortList = 16;
+
+// Lists of up to kShortList occurrences are rank-sorted by one lane; longer ones are queued.
+__global__ void k_sort_short(MIRS) {
+  const DevMir &m = *mirs[blockIdx.y];
+  DevLive &L = lives[blockIdx.y];
+  uint32_t v = blockIdx.x * blockDim.x + threadIdx.x;
+  if (v >= m.V) return;
+  const uint32_t lo = L.vcnt[v], len = L.vcnt[v + 1] - lo;
+  if (len == 0) { L.first[v] = kNone; return; }
+  if (len > kShortList) {
+    L.long_queue[atomicAdd(&L.counters[kCtrLong], 1u)] = v;
+    return;
+  }
+  for (uint32_t j = 0; j < len; ++j) {
+    uint32_t x = L.vocc_tmp[lo + j], r = 0;
+    for (uint32_t k = 0; k < len; ++k) r += L.vocc_tmp[lo + k] < x;
+    L.vocc[lo + r] = x;
+    if (r == 0) L.first[v] = x;
+  }
+}
+
+constexpr uint32_t kBitmapWords = 8192;              // 32 KB of LDS
+constexpr uint32_t kBitmapSpan = kBitmapWords * 32;  // occurrences per window
+
+// Long lists: occurrence indices are distinct, so marking them in a bitmap and
+// reading the bitmap back in order sorts them.
+__global__ __launch_bounds__(256) void k_sort_long(MIRS) {
+  const DevMir &m = *mirs[blockIdx.y];
+  DevLive &L = lives[blockIdx.y];
+  __shared__ uint32_t bm[kBitmapWords];
+  __shared__ uint32_t part[256];
+  const uint32_t tid = threadIdx.x;
+  const uint32_t n_long = L.counters[kCtrLong];
+  for (uint32_t q = blockIdx.x; q < n_long; q += gridDim.x) {
+    const uint32_t v = L.long_queue[q];
+    const uint32_t lo = L.vcnt[v], len = L.vcnt[v + 1] - lo;
+    uint32_t written = 0;
+    for (uint32_t wb = 0; wb < m.O; wb += kBitmapSpan) {
+      const uint32_t span = min(kBitmapSpan, m.O - wb), nw = (span + 31u) / 32u;
+      for (uint32_t w = tid; w < nw; w += 256) bm[w] = 0;
+      __syncthreads();
+      for (uint32_t j = tid; j < len; j += 256) {
+        uint32_t x = L.vocc_tmp[lo + j] - wb;
+        if (x < span) atomicOr(&bm[x >> 5], 1u << (x & 31));
+      }
+      __syncthreads();
+      const uint32_t chunk = (nw + 255u) / 256u;
+      const uint32_t w0 = min(nw, tid * chunk), w1 = min(nw, w0 + chunk);
+      uint32_t cnt = 0;
+      for (uint32_t w = w0; w < w1; ++w) cnt += __popc(bm[w]);
+      part[tid] = cnt;
+      __syncthreads();
+      for (uint32_t d = 1; d < 256; d <<= 1) {
+        uint32_t t = tid >= d ? part[tid - d] : 0;
+        __syncthreads();
+        part[tid] += t;
+        __syncthreads();
+      }
+      uint32_t pos = lo + written + part[tid] - cnt;
+      for (uint32_t w = w0; w < w1; ++w) {
+        uint32_t bits = bm[w];
+        while (bits) {
+          uint32_t b = __ffs(bits) - 1;
+          bits &= bits - 1;
+          uint32_t x = wb + w * 32 + b;
+          if (pos == lo) L.first[v] = x;
+          L.vocc[pos++] = x;
+        }
+      }
+      written += part[255];
+      __syncthreads();
+    }
+  }
+}
+
+__global__ void k_ent(MIRS) {
+  const DevMir &m = *mirs[blockIdx.y];
+  DevLive &L = lives[blockIdx.y];
+  uint32_t e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (e < m.O) L.ent_instr[e] = m.occ_instr[L.vocc[e]];
+}
+
+// ---- 2. block summaries ---------------------------------------------------------------
+// def[b]: vregs written in b.  use[b]: vregs whose first mention in b reads them
+// (an instruction reads before it writes).
+__global__ void k_summary(MIRS) {
+  const DevMir &m = *mirs[blockIdx.y];
+  DevLive &L = lives[blockIdx.y];
+  uint32_t e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= m.O) return;
+  const uint32_t o = L.vocc[e], v = m.occ_vreg[o], i = L.ent_instr[e], b = m.instr_blk[i];
+  const uint32_t fl = m.occ_flags[o], bit = 1u << (v & 31), w = v >> 5;
+  if (fl & VL_OCC_DEF) atomicOr(&L.def[(size_t)b * m.W + w], bit);
+  if (fl & VL_OCC_USE) {
+    const uint32_t lo = L.vcnt[v];
+    uint32_t gs = e;
+    while (gs > lo && L.ent_instr[gs - 1] == i) --gs;
+    if (gs == lo || m.instr_blk[L.ent_instr[gs - 1]] != b) atomicOr(&L.use[(size_t)b * m.W + w], bit);
+  }
+}
+
+// ---- 3. fixed point -------------------------------------------------------------------
+// out[b] = OR of in[s] over successors; in[b] = use[b] | (out[b] & ~def[b]).  Bit columns
+// do not interact, so each lane iterates its own word to its own fixed point; blocks are
+// swept in reverse linear order.  LDS holds in/use/def of the wave's 64 words when the
+// block count allows, otherwise the sweep runs on global memory.
+template <bool kLds>
+__global__ __launch_bounds__(64) void k_fixpoint(MIRS) {
+  const DevMir &m = *mirs[blockIdx.y];
+  DevLive &L = lives[blockIdx.y];
+  extern __shared__ uint32_t sm[];
+  const uint32_t lane = threadIdx.x, w = blockIdx.x * 64 + lane;
+  if (blockIdx.x * 64 >= m.W) return;
+  const bool act = w < m.W;
+  const uint32_t B = m.B, W = m.W;
+  uint32_t *in_l = sm, *use_l = sm + (size_t)B * 64, *def_l = sm + (size_t)2 * B * 64;
+  if (kLds) {
+    for (uint32_t b = 0; b < B; ++b) {
+      in_l[b * 64 + lane] = 0;
+      use_l[b * 64 + lane] = act ? L.use[(size_t)b * W + w] : 0;
+      def_l[b * 64 + lane] = act ? L.def[(size_t)b * W + w] : 0;
+    }
+  }
+  uint32_t sweeps = 0;
+  bool changed = true;
+  while (__any(changed)) {   // monotone on a finite lattice: terminates
+    changed = false;
+    ++sweeps;
+    for (uint32_t b = B; b-- > 0;) {
+      uint32_t out = 0;
+      for (uint32_t e = m.succ_off[b]; e < m.succ_off[b + 1]; ++e) {
+        uint32_t s = m.succ[e];
+        out |= kLds ? in_l[s * 64 + lane] : (act ? L.live_in[(size_t)s * W + w] : 0);
+      }
+      uint32_t u = kLds ? use_l[b * 64 + lane] : (act ? L.use[(size_t)b * W + w] : 0);
+      uint32_t d = kLds ? def_l[b * 64 + lane] : (act ? L.def[(size_t)b * W + w] : 0);
+      uint32_t nin = u | (out & ~d);
+      uint32_t old = kLds ? in_l[b * 64 + lane] : (act ? L.live_in[(size_t)b * W + w] : 0);
+      if (nin != old) {
+        changed = true;
+        if (kLds) in_l[b * 64 + lane] = nin; else if (act) L.live_in[(size_t)b * W + w] = nin;
+      }
+    }
+  }
+  // write-out: in (when it lived in LDS) and out
+  for (uint32_t b = 0; b < B; ++b) {
+    uint32_t out = 0;
+    for (uint32_t e = m.succ_off[b]; e < m.succ_off[b + 1]; ++e) {
+      uint32_t s = m.succ[e];
+      out |= kLds ? in_l[s * 64 + lane] : (act ? L.live_in[(size_t)s * W + w] : 0);
+    }
+    if (act) {
+      L.live_out[(size_t)b * W + w] = out;
+      if (kLds) L.live_in[(size_t)b * W + w] = in_l[b * 64 + lane];
+    }
+  }
+  uint32_t in0 = kLds ? in_l[lane] : (act ? L.live_in[w] : 0);
+  if (act && in0) L.counters[kCtrNotStrict] = 1;
+  if (lane == 0) atomicMax(&L.counters[kCtrSweeps], sweeps);
+}
+
+// ---- 4. per-occurrence liveness, kill flags and event roles ---------------------------
+// For the mentions of v at instruction i (its "group"): v is live after i iff the next
+// mention of v in the same block reads it, or, with no later mention in the block, v is
+// in the block's live-out.  P(i) contains v iff it is live after i or written at i.
+__global__ void k_events(MIRS) {
+  const DevMir &m = *mirs[blockIdx.y];
+  DevLive &L = lives[blockIdx.y];
+  uint32_t e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= m.O) return;
+  const uint32_t o = L.vocc[e], v = m.occ_vreg[o];
+  const uint32_t lo = L.vcnt[v], hi = L.vcnt[v + 1];
+  const uint32_t i = L.ent_instr[e], b = m.instr_blk[i];
+  uint32_t gs = e, ge = e + 1;
+  while (gs > lo && L.ent_instr[gs - 1] == i) --gs;
+  while (ge < hi && L.ent_instr[ge] == i) ++ge;
+  bool has_use = false, has_def = false;
+  uint32_t first_use = kNone, first_def = kNone;
+  for (uint32_t x = gs; x < ge; ++x) {
+    uint32_t f = m.occ_flags[L.vocc[x]];
+    if (f & VL_OCC_USE) { has_use = true; if (first_use == kNone) first_use = x; }
+    if (f & VL_OCC_DEF) { has_def = true; if (first_def == kNone) first_def = x; }
+  }
+  bool la;
+  if (ge < hi && m.instr_blk[L.ent_instr[ge]] == b) {
+    const uint32_t i2 = L.ent_instr[ge];
+    la = false;
+    for (uint32_t x = ge; x < hi && L.ent_instr[x] == i2; ++x) la |= (m.occ_flags[L.vocc[x]] & VL_OCC_USE) != 0;
+  } else {
+    la = bit_get(L.live_out + (size_t)b * m.W, v);
+  }
+  const uint32_t fl = m.occ_flags[o];
+  L.occ_kill[o] = (uint8_t)((fl & VL_OCC_USE) && !has_def && !la);
+  uint8_t role = 0;
+  if (!has_def && !la && e == first_use) role |= kRolePreKill;
+  if (has_def && e == first_def) {
+    if (!has_use) role |= kRoleTestSet;
+    if (!la) role |= kRolePostKill;
+  }
+  if (e == lo) role |= kRoleFirst;
+  L.occ_role[o] = role;
+  L.prev_occ[o] = e > lo ? L.vocc[e - 1] : kNone;
+  L.ent_info[e] = (uint8_t)((la ? kEntLiveAfter : 0) | (has_use ? kEntHasUse : 0) | (has_def ? kEntHasDef : 0) |
+                            (e == gs ? kEntGroupStart : 0));
+}
+
+// ---- 5a. event stream -----------------------------------------------------------------
+__device__ inline uint32_t item_of_instr(const DevMir &m, uint32_t i) { return i + m.instr_blk[i] + 1; }
+
+__global__ void k_item_count(MIRS) {
+  const DevMir &m = *mirs[blockIdx.y];
+  DevLive &L = lives[blockIdx.y];
+  uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= m.N) return;
+  uint32_t cnt = m.occ_off[i + 1] - m.occ_off[i];
+  for (uint32_t o = m.occ_off[i]; o < m.occ_off[i + 1]; ++o) cnt += (L.occ_role[o] & kRolePostKill) ? 1u : 0u;
+  L.item_off[item_of_instr(m, i)] = cnt;
+}
+
+__device__ inline uint32_t wave_incl_scan(uint32_t x) {
+  for (int d = 1; d < 64; d <<= 1) {
+    uint32_t y = __shfl_up(x, d, 64);
+    if ((int)(threadIdx.x & 63) >= d) x += y;
+  }
+  return x;
+}
+
+// nearest occurrence of v before instruction `at`, else the first at or after it
+__device__ inline uint32_t source_occurrence(const DevLive &L, uint32_t v, uint32_t at) {
+  const uint32_t lo = L.vcnt[v], hi = L.vcnt[v + 1];
+  uint32_t x = lower_bound(L.ent_instr, lo, hi, at);
+  return x > lo ? L.vocc[x - 1] : (x < hi ? L.vocc[x] : 0u);
+}
+
+// Between two blocks adjacent in the linear order the occupied set changes from the
+// earlier block's live-out to the later block's live-in: one wave per boundary lists the
+// values that leave (release) and those that enter (occupy without test).
+template <bool kFill>
+__global__ __launch_bounds__(64) void k_boundary(MIRS) {
+  const DevMir &m = *mirs[blockIdx.y];
+  DevLive &L = lives[blockIdx.y];
+  const uint32_t b = blockIdx.x, lane = threadIdx.x;
+  if (b >= m.B) return;
+  const uint32_t item = m.blk_start[b] + b;
+  if (b == 0) {
+    if (!kFill && lane == 0) L.item_off[item] = 0;
+    return;
+  }
+  const uint32_t W = m.W, at = m.blk_start[b];
+  const uint32_t *out_prev = L.live_out + (size_t)(b - 1) * W, *in_cur = L.live_in + (size_t)b * W;
+  uint32_t base = kFill ? L.item_off[item] : 0, total = 0;
+  for (int pass = 0; pass < 2; ++pass) {  // 0: leaving, 1: entering
+    for (uint32_t w0 = 0; w0 < W; w0 += 64) {
+      const uint32_t w = w0 + lane;
+      uint32_t bits = 0;
+      if (w < W) bits = pass == 0 ? (out_prev[w] & ~in_cur[w]) : (in_cur[w] & ~out_prev[w]);
+      const uint32_t c = __popc(bits), incl = wave_incl_scan(c);
+      if (kFill) {
+        uint32_t pos = base + total + incl - c;
+        while (bits) {
+          uint32_t v = w * 32 + __ffs(bits) - 1;
+          bits &= bits - 1;
+          uint32_t src = source_occurrence(L, v, at);
+          L.plan[pos++] = make_uint2(src | ((pass == 0 ? kPlanClr : kPlanBirth) | kPlanPost) << 24,
+                                     0xFFFFu | (m.vattr[v] << 16));
+        }
+      }
+      total += __shfl(incl, 63, 64);
+    }
+  }
+  if (!kFill && lane == 0) L.item_off[item] = total;
+}
+
+__global__ void k_plan_fill(MIRS) {
+  const DevMir &m = *mirs[blockIdx.y];
+  DevLive &L = lives[blockIdx.y];
+  uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= m.N) return;
+  uint32_t pos = L.item_off[item_of_instr(m, i)];
+  const uint32_t o0 = m.occ_off[i], o1 = m.occ_off[i + 1];
+  auto entry = [&](uint32_t o, uint32_t flags) {
+    const uint32_t v = m.occ_vreg[o], prev = L.prev_occ[o];
+    uint32_t delta = prev == kNone ? 0u : min(o - prev, 0xFFFFu);
+    return make_uint2(o | (flags << 24), delta | (m.vattr[v] << 16));
+  };
+  auto base_flags = [&](uint32_t o) {
+    const uint8_t role = L.occ_role[o];
+    uint32_t f = (role & kRoleFirst) ? kPlanFirst : kPlanChk;
+    if (role & kRolePreKill) f |= kPlanClr;
+    if (role & kRoleTestSet) f |= kPlanSet;
+    return f;
+  };
+  // operands that are only read, then operands that are written, then releases of
+  // values that are dead once the instruction has executed
+  for (uint32_t o = o0; o < o1; ++o)
+    if (!(m.occ_flags[o] & VL_OCC_DEF)) L.plan[pos++] = entry(o, base_flags(o));
+  for (uint32_t o = o0; o < o1; ++o)
+    if (m.occ_flags[o] & VL_OCC_DEF) L.plan[pos++] = entry(o, base_flags(o));
+  for (uint32_t o = o0; o < o1; ++o)
+    if (L.occ_role[o] & kRolePostKill) L.plan[pos++] = entry(o, kPlanClr | kPlanPost);
+}
+
+// ---- 5b. live intervals ---------------------------------------------------------------
+// One lane per vreg walks the blocks in linear order and its own mentions, emitting the
+// maximal runs of {i : v in P(i)}.
+template <bool kFill>
+__global__ void k_seg(MIRS) {
+  const DevMir &m = *mirs[blockIdx.y];
+  DevLive &L = lives[blockIdx.y];
+  uint32_t v = blockIdx.x * blockDim.x + threadIdx.x;
+  if (v >= m.V) return;
+  const uint32_t lo = L.vcnt[v], hi = L.vcnt[v + 1];
+  uint32_t n = 0, cs = 0, ce = 0, hull_lo = 0;
+  bool open = false;
+  uint32_t *out = kFill ? L.seg + 2 * (size_t)L.seg_off[v] : nullptr;
+  auto add = [&](uint32_t s, uint32_t t) {
+    if (open && s == ce) { ce = t; return; }
+    if (open) { if (kFill) { out[2 * n] = cs; out[2 * n + 1] = ce; } ++n; }
+    else hull_lo = s;
+    cs = s; ce = t; open = true;
+  };
+  uint32_t e = lo;
+  for (uint32_t b = 0; b < m.B; ++b) {
+    const uint32_t bs = m.blk_start[b], be = m.blk_start[b + 1];
+    if (e >= hi || L.ent_instr[e] >= be) {  // no mention in this block
+      if (bit_get(L.live_in + (size_t)b * m.W, v)) add(bs, be);
+      continue;
+    }
+    uint32_t pos = bs;
+    bool cur = (L.ent_info[e] & kEntHasUse) != 0;  // live on entry iff the first mention reads
+    while (e < hi && L.ent_instr[e] < be) {
+      const uint32_t i = L.ent_instr[e];
+      const uint8_t info = L.ent_info[e];
+      if (cur && pos < i) add(pos, i);
+      if (info & (kEntHasDef | kEntLiveAfter)) add(i, i + 1);
+      pos = i + 1;
+      cur = (info & kEntLiveAfter) != 0;
+      while (e < hi && L.ent_instr[e] == i) ++e;
+    }
+    if (cur && pos < be) add(pos, be);
+  }
+  if (open) { if (kFill) { out[2 * n] = cs; out[2 * n + 1] = ce; } ++n; }
+  if (kFill) {
+    L.hull[2 * v] = n ? hull_lo : 0;
+    L.hull[2 * v + 1] = n ? ce : 0;
+  } else {
+    L.seg_off[v] = n;
+  }
+}
+
+// ---- 5c. tile live-ins ------------------------------------------------------------------
+// Tile t starts at instruction t * tile_len.  Its seed is live_before of that instruction:
+// v is in it iff the first mention of v at or after the tile start, within the block,
+// reads v, or (no such mention) v is in the block's live-out.
+template <bool kFill>
+__global__ void k_seed(MIRS) {
+  const DevMir &m = *mirs[blockIdx.z];
+  DevLive &L = lives[blockIdx.z];
+  const uint32_t t = blockIdx.y + 1, v = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= L.T || v >= m.V) return;
+  const uint32_t at = t * L.tile_len, b = m.instr_blk[at];
+  const uint32_t lo = L.vcnt[v], hi = L.vcnt[v + 1];
+  if (lo == hi) return;
+  const uint32_t x = lower_bound(L.ent_instr, lo, hi, at);
+  bool live;
+  if (x < hi && L.ent_instr[x] < m.blk_start[b + 1]) live = (L.ent_info[x] & kEntHasUse) != 0;
+  else live = bit_get(L.live_out + (size_t)b * m.W, v);
+  if (!live) return;
+  if (!kFill) { atomicAdd(&L.seed_off[t], 1u); return; }
+  const uint32_t src = x > lo ? L.vocc[x - 1] : L.vocc[x];
+  const uint32_t pos = L.seed_off[t] + atomicAdd(&L.seed_cur[t], 1u);
+  L.seeds[pos] = make_uint2(src | ((kPlanBirth | kPlanPost) << 24), 0xFFFFu | (m.vattr[v] << 16));
+  if (L.dense) atomicOr(&L.tile_live[(size_t)t * m.W + (v >> 5)], 1u << (v & 31));
+}
+
+__global__ void k_collect(MIRS, uint32_t n) {
+  uint32_t k = blockIdx.x * blockDim.x + threadIdx.x;
+  if (k >= n) return;
+  const DevMir &m = *mirs[k];
+  DevLive &L = lives[k];
+  L.counters[kCtrPlanLen] = L.item_off[m.N + m.B];
+  L.counters[kCtrSeg] = L.seg_off[m.V];
+  L.counters[kCtrSeed] = L.seed_off[L.T];
+}
+
+__global__ void k_tile_range(MIRS) {
+  const DevMir &m = *mirs[blockIdx.y];
+  DevLive &L = lives[blockIdx.y];
+  uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= L.T) return;
+  const uint32_t i0 = t * L.tile_len, i1 = min(m.N, i0 + L.tile_len);
+  L.tile_range[2 * t] = L.item_off[item_of_instr(m, i0)];
+  uint32_t end;
+  if (i1 == m.N) end = L.item_off[m.N + m.B];
+  else {
+    const uint32_t b = m.instr_blk[i1];
+    // a tile ending at a block boundary leaves the boundary entries out: the next tile
+    // starts from that block's live-in
+    end = m.blk_start[b] == i1 ? L.item_off[i1 + b] : L.item_off[i1 + b + 1];
+  }
+  L.tile_range[2 * t + 1] = end;
+}
+
+// ---- 5d. dense per-point bitsets (optional) ---------------------------------------------
+// Every occupy / release event flips one bit of the occupied set.  First each event is
+// XOR-ed into the row of the instruction at which it takes effect, then each tile
+// prefix-XORs its rows downwards from the tile's live-in row.
+__global__ void k_dense_delta(MIRS) {
+  const DevMir &m = *mirs[blockIdx.y];
+  DevLive &L = lives[blockIdx.y];
+  uint32_t q = blockIdx.x * blockDim.x + threadIdx.x;
+  if (q >= m.N + m.B) return;
+  // item q is either the boundary of block b (q == blk_start[b] + b) or an instruction of
+  // block b: b is the last block whose boundary item is at or before q
+  uint32_t b = 0, hi = m.B;
+  while (hi - b > 1) {
+    uint32_t mid = (b + hi) >> 1;
+    if (m.blk_start[mid] + mid <= q) b = mid; else hi = mid;
+  }
+  const uint32_t row = (q == m.blk_start[b] + b) ? m.blk_start[b] : q - b - 1;
+  // a tile that starts exactly at this block start takes its row from the seed instead
+  if (q == m.blk_start[b] + b && row % L.tile_len == 0) return;
+  for (uint32_t e = L.item_off[q]; e < L.item_off[q + 1]; ++e) {
+    const uint2 ent = L.plan[e];
+    if (!((ent.x >> 24) & (kPlanSet | kPlanClr | kPlanBirth))) continue;
+    const uint32_t v = m.occ_vreg[ent.x & 0xFFFFFFu];
+    atomicXor(&L.live_after[(size_t)row * m.W + (v >> 5)], 1u << (v & 31));
+  }
+}
+
+__global__ __launch_bounds__(64) void k_dense_scan(MIRS) {
+  const DevMir &m = *mirs[blockIdx.z];
+  DevLive &L = lives[blockIdx.z];
+  const uint32_t t = blockIdx.y, w = blockIdx.x * 64 + threadIdx.x;
+  if (t >= L.T || w >= m.W) return;
+  const uint32_t i0 = t * L.tile_len, i1 = min(m.N, i0 + L.tile_len);
+  uint32_t cur = t ? L.tile_live[(size_t)t * m.W + w] : 0u;
+  for (uint32_t i = i0; i < i1; ++i) {
+    cur ^= L.live_after[(size_t)i * m.W + w];
+    L.live_after[(size_t)i * m.W + w] = cur;
+  }
+}
+
+struct Bump {
+  size_t off = 0;
+  size_t take(size_t bytes) {
+    size_t at = off;
+    off += (bytes + 255) & ~(size_t)255;
+    return at;
+  }
+};
+
+}  // namespace
+
+// A batch owns the device storage of n analyses made by one call.
+struct vl_batch {
+  uint32_t n = 0, refs = 0;
+  int device = 0;
+  void *arena1 = nullptr, *arena2 = nullptr;
+  size_t cap1 = 0, cap2 = 0;
+  const DevMir **dev_mirs = nullptr;  // device array [n]
+  DevLive *dev_lives = nullptr;       // device array [n]
+  uint32_t *host_counters = nullptr;  // pinned [n][kCounters]
+  const DevMir **stage_mirs = nullptr;  // pinned [n]
+  DevLive *stage_a = nullptr, *stage_b = nullptr;  // pinned [n] each: first and second upload
+  std::vector<vl_live *> lives;
+};
+
+static void batch_free(vl_batch *b) {
+  if (b->arena1) (void)hipFree(b->arena1);
+  if (b->arena2) (void)hipFree(b->arena2);
+  if (b->host_counters) (void)hipHostFree(b->host_counters);
+  if (b->stage_mirs) (void)hipHostFree(b->stage_mirs);
+  if (b->stage_a) (void)hipHostFree(b->stage_a);
+  if (b->stage_b) (void)hipHostFree(b->stage_b);
+  delete b;
+}
+
+extern "C" void vl_live_destroy(vl_live *l) {
+  if (!l || l->magic != kLiveMagic) return;
+  l->magic = 0;
+  vl_batch *b = l->batch;
+  delete l;
+  if (--b->refs == 0) batch_free(b);
+}
+
+static inline dim3 grid1(uint32_t items, uint32_t threads, uint32_t n) {
+  return dim3(std::max(1u, (items + threads - 1) / threads), n, 1);
+}
+
+extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint32_t flags, uint32_t tile_len,
+                                     vl_stream stream_, vl_live **live) {
+  if (!mirs || !live) return VL_E_NULL;
+  if (n == 0 || n > 65535) return VL_E_SHAPE;
+  if (flags & ~VL_DENSE_POINTS) return VL_E_RANGE;
+  for (uint32_t k = 0; k < n; ++k)
+    if (!mirs[k] || mirs[k]->magic != kMirMagic) return VL_E_NULL;
+  hipStream_t stream = (hipStream_t)stream_;
+  if (tile_len == 0) tile_len = kDefaultTile;
+  const bool dense = (flags & VL_DENSE_POINTS) != 0;
+
+  // recycle or create the batch
+  vl_batch *batch = nullptr;
+  bool fresh = false;
+  if (live[0]) {
+    for (uint32_t k = 0; k < n; ++k) {
+      if (!live[k] || live[k]->magic != kLiveMagic || live[k]->index != k) return VL_E_ARG;
+      if (live[k]->batch != live[0]->batch || live[k]->mir != mirs[k]) return VL_E_ARG;
+    }
+    batch = live[0]->batch;
+    if (batch->n != n) return VL_E_ARG;
+  } else {
+    for (uint32_t k = 0; k < n; ++k)
+      if (live[k]) return VL_E_ARG;
+    batch = new (std::nothrow) vl_batch;
+    if (!batch) return VL_E_SHAPE;
+    batch->n = n;
+    fresh = true;
+    hipError_t e = hipGetDevice(&batch->device);
+    if (e == hipSuccess) e = hipHostMalloc((void **)&batch->host_counters, (size_t)n * kCounters * 4, hipHostMallocDefault);
+    if (e == hipSuccess) e = hipHostMalloc((void **)&batch->stage_mirs, (size_t)n * sizeof(DevMir *), hipHostMallocDefault);
+    if (e == hipSuccess) e = hipHostMalloc((void **)&batch->stage_a, (size_t)n * sizeof(DevLive), hipHostMallocDefault);
+    if (e == hipSuccess) e = hipHostMalloc((void **)&batch->stage_b, (size_t)n * sizeof(DevLive), hipHostMallocDefault);
+    if (e != hipSuccess) { batch_free(batch); return hip_fail(e); }
+  }
+  auto fail = [&](int32_t rc) {
+    if (fresh) batch_free(batch);
+    return rc;
+  };
+
+  // ---- arena 1 layout: [zeroed zone | counters | rest | device tables] ----
+  std::vector<DevLive> h(n);
+  struct Off1 { size_t vcnt, vcur, use, def, in, seed_off, seed_cur, out, tmp, vocc, ent_instr, ent_info, first, prev,
+                role, kill, item, seg_off, hull, queue, bitmap; };
+  std::vector<Off1> off(n);
+  Bump bump;
+  uint32_t maxO = 1, maxV = 1, maxN = 1, maxB = 1, maxW = 1, maxT = 1;
+  for (uint32_t k = 0; k < n; ++k) {
+    const DevMir &m = mirs[k]->h;
+    const uint32_t T = (m.N + tile_len - 1) / tile_len;
+    memset(&h[k], 0, sizeof(DevLive));
+    h[k].T = T; h[k].tile_len = tile_len; h[k].dense = dense;
+    const size_t bw = (size_t)m.B * std::max(1u, m.W) * 4;
+    off[k].vcnt = bump.take((size_t)(m.V + 1) * 4);
+    off[k].vcur = bump.take((size_t)(m.V + 1) * 4);
+    off[k].use = bump.take(bw); off[k].def = bump.take(bw); off[k].in = bump.take(bw);
+    off[k].seed_off = bump.take((size_t)(T + 1) * 4); off[k].seed_cur = bump.take((size_t)(T + 1) * 4);
+    maxO = std::max(maxO, m.O); maxV = std::max(maxV, m.V); maxN = std::max(maxN, m.N);
+    maxB = std::max(maxB, m.B); maxW = std::max(maxW, m.W); maxT = std::max(maxT, T);
+  }
+  const size_t o_counters = bump.take((size_t)n * kCounters * 4);
+  const size_t zero_bytes = bump.off;
+  for (uint32_t k = 0; k < n; ++k) {
+    const DevMir &m = mirs[k]->h;
+    const size_t O1 = std::max(1u, m.O), bw = (size_t)m.B * std::max(1u, m.W) * 4;
+    off[k].out = bump.take(bw);
+    off[k].tmp = bump.take(O1 * 4); off[k].vocc = bump.take(O1 * 4); off[k].ent_instr = bump.take(O1 * 4);
+    off[k].ent_info = bump.take(O1); off[k].first = bump.take((size_t)(m.V + 1) * 4); off[k].prev = bump.take(O1 * 4);
+    off[k].role = bump.take(O1); off[k].kill = bump.take(O1);
+    off[k].item = bump.take((size_t)(m.N + m.B + 1) * 4);
+    off[k].seg_off = bump.take((size_t)(m.V + 1) * 4); off[k].hull = bump.take((size_t)(m.V + 1) * 8);
+    off[k].queue = bump.take((size_t)(m.V + 1) * 4);
+    off[k].bitmap = 0;
+  }
+  const size_t o_mirs = bump.take((size_t)n * sizeof(DevMir *));
+  const size_t o_lives = bump.take((size_t)n * sizeof(DevLive));
+  if (bump.off > batch->cap1) {
+    if (batch->arena1) { VL_HIP(hipStreamSynchronize(stream)); (void)hipFree(batch->arena1); batch->arena1 = nullptr; batch->cap1 = 0; }
+    hipError_t e = hipMalloc(&batch->arena1, bump.off);
+    if (e != hipSuccess) return fail(hip_fail(e));
+    batch->cap1 = bump.off;
+  }
+  char *a1 = (char *)batch->arena1;
+  const DevMir **mir_ptrs = batch->stage_mirs;
+  for (uint32_t k = 0; k < n; ++k) {
+    DevLive &L = h[k];
+    L.vcnt = (uint32_t *)(a1 + off[k].vcnt); L.vcur = (uint32_t *)(a1 + off[k].vcur);
+    L.use = (uint32_t *)(a1 + off[k].use); L.def = (uint32_t *)(a1 + off[k].def);
+    L.live_in = (uint32_t *)(a1 + off[k].in); L.live_out = (uint32_t *)(a1 + off[k].out);
+    L.seed_off = (uint32_t *)(a1 + off[k].seed_off); L.seed_cur = (uint32_t *)(a1 + off[k].seed_cur);
+    L.vocc_tmp = (uint32_t *)(a1 + off[k].tmp); L.vocc = (uint32_t *)(a1 + off[k].vocc);
+    L.ent_instr = (uint32_t *)(a1 + off[k].ent_instr); L.ent_info = (uint8_t *)(a1 + off[k].ent_info);
+    L.first = (uint32_t *)(a1 + off[k].first); L.prev_occ = (uint32_t *)(a1 + off[k].prev);
+    L.occ_role = (uint8_t *)(a1 + off[k].role); L.occ_kill = (uint8_t *)(a1 + off[k].kill);
+    L.item_off = (uint32_t *)(a1 + off[k].item); L.seg_off = (uint32_t *)(a1 + off[k].seg_off);
+    L.hull = (uint32_t *)(a1 + off[k].hull); L.long_queue = (uint32_t *)(a1 + off[k].queue);
+    L.bitmap = nullptr;
+    L.counters = (uint32_t *)(a1 + o_counters) + (size_t)k * kCounters;
+    mir_ptrs[k] = mirs[k]->dev;
+  }
+  batch->dev_mirs = (const DevMir **)(a1 + o_mirs);
+  batch->dev_lives = (DevLive *)(a1 + o_lives);
+  // pinned staging: stage_a / stage_mirs are read by the copies below before the
+  // synchronisation further down, stage_b by the second upload after it
+  memcpy(batch->stage_a, h.data(), (size_t)n * sizeof(DevLive));
+  hipError_t e = hipMemsetAsync(a1, 0, zero_bytes, stream);
+  if (e == hipSuccess) e = hipMemcpyAsync(a1 + o_mirs, mir_ptrs, (size_t)n * sizeof(DevMir *), hipMemcpyHostToDevice, stream);
+  if (e == hipSuccess) e = hipMemcpyAsync(a1 + o_lives, batch->stage_a, (size_t)n * sizeof(DevLive), hipMemcpyHostToDevice, stream);
+  if (e != hipSuccess) return fail(hip_fail(e));
+
+  const DevMir *const *dm = batch->dev_mirs;
+  DevLive *dl = batch->dev_lives;
+  const uint32_t TB = 256;
+  k_count<<<grid1(maxO, TB, n), TB, 0, stream>>>(dm, dl);
+  k_scan<kScanVreg><<<n, 1024, 0, stream>>>(dm, dl);
+  k_place<<<grid1(maxO, TB, n), TB, 0, stream>>>(dm, dl);
+  k_sort_short<<<grid1(maxV, TB, n), TB, 0, stream>>>(dm, dl);
+  k_sort_long<<<dim3(32, n), 256, 0, stream>>>(dm, dl);
+  k_ent<<<grid1(maxO, TB, n), TB, 0, stream>>>(dm, dl);
+  k_summary<<<grid1(maxO, TB, n), TB, 0, stream>>>(dm, dl);
+  {
+    const size_t lds = (size_t)maxB * 64 * 3 * 4;
+    if (lds <= 64 * 1024) k_fixpoint<true><<<grid1(maxW, 64, n), 64, lds, stream>>>(dm, dl);
+    else k_fixpoint<false><<<grid1(maxW, 64, n), 64, 0, stream>>>(dm, dl);
+  }
+  k_events<<<grid1(maxO, TB, n), TB, 0, stream>>>(dm, dl);
+  k_item_count<<<grid1(maxN, TB, n), TB, 0, stream>>>(dm, dl);
+  k_boundary<false><<<dim3(maxB, n), 64, 0, stream>>>(dm, dl);
+  k_scan<kScanItems><<<n, 1024, 0, stream>>>(dm, dl);
+  k_seg<false><<<grid1(maxV, TB, n), TB, 0, stream>>>(dm, dl);
+  k_scan<kScanSeg><<<n, 1024, 0, stream>>>(dm, dl);
+  if (maxT > 1) k_seed<false><<<dim3((maxV + TB - 1) / TB, maxT - 1, n), TB, 0, stream>>>(dm, dl);
+  k_scan<kScanSeed><<<n, 1024, 0, stream>>>(dm, dl);
+  k_collect<<<(n + 63) / 64, 64, 0, stream>>>(dm, dl, n);
+  e = hipGetLastError();
+  if (e == hipSuccess) e = hipMemcpyAsync(batch->host_counters, a1 + o_counters, (size_t)n * kCounters * 4, hipMemcpyDeviceToHost, stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(stream);
+  if (e != hipSuccess) return fail(hip_fail(e));
+  for (uint32_t k = 0; k < n; ++k)
+    if (batch->host_counters[(size_t)k * kCounters + kCtrNotStrict]) return fail(VL_E_NOT_STRICT);
+
+  // ---- arena 2: sized from the counts ----
+  Bump b2;
+  struct Off2 { size_t plan, seeds, seg, range, tile_live, dense; };
+  std::vector<Off2> off2(n);
+  size_t zero2_lo = 0, zero2_hi = 0;
+  if (dense) {
+    zero2_lo = b2.off;
+    for (uint32_t k = 0; k < n; ++k) {
+      const DevMir &m = mirs[k]->h;
+      off2[k].tile_live = b2.take((size_t)h[k].T * std::max(1u, m.W) * 4);
+      off2[k].dense = b2.take((size_t)m.N * std::max(1u, m.W) * 4);
+    }
+    zero2_hi = b2.off;
+  }
+  for (uint32_t k = 0; k < n; ++k) {
+    const uint32_t *c = batch->host_counters + (size_t)k * kCounters;
+    h[k].plan_len = c[kCtrPlanLen]; h[k].n_seg = c[kCtrSeg]; h[k].n_seed = c[kCtrSeed];
+    off2[k].plan = b2.take((size_t)std::max(1u, h[k].plan_len) * 8);
+    off2[k].seeds = b2.take((size_t)std::max(1u, h[k].n_seed) * 8);
+    off2[k].seg = b2.take((size_t)std::max(1u, h[k].n_seg) * 8);
+    off2[k].range = b2.take((size_t)h[k].T * 8);
+  }
+  if (b2.off > batch->cap2) {
+    if (batch->arena2) { (void)hipFree(batch->arena2); batch->arena2 = nullptr; batch->cap2 = 0; }
+    e = hipMalloc(&batch->arena2, b2.off);
+    if (e != hipSuccess) return fail(hip_fail(e));
+    batch->cap2 = b2.off;
+  }
+  char *a2 = (char *)batch->arena2;
+  for (uint32_t k = 0; k < n; ++k) {
+    DevLive &L = h[k];
+    L.plan = (uint2 *)(a2 + off2[k].plan); L.seeds = (uint2 *)(a2 + off2[k].seeds);
+    L.seg = (uint32_t *)(a2 + off2[k].seg); L.tile_range = (uint32_t *)(a2 + off2[k].range);
+    L.tile_live = dense ? (uint32_t *)(a2 + off2[k].tile_live) : nullptr;
+    L.live_after = dense ? (uint32_t *)(a2 + off2[k].dense) : nullptr;
+  }
+  memcpy(batch->stage_b, h.data(), (size_t)n * sizeof(DevLive));
+  e = hipMemcpyAsync(a1 + o_lives, batch->stage_b, (size_t)n * sizeof(DevLive), hipMemcpyHostToDevice, stream);
+  if (e == hipSuccess && dense) e = hipMemsetAsync(a2 + zero2_lo, 0, zero2_hi - zero2_lo, stream);
+  if (e != hipSuccess) return fail(hip_fail(e));
+  k_plan_fill<<<grid1(maxN, TB, n), TB, 0, stream>>>(dm, dl);
+  k_boundary<true><<<dim3(maxB, n), 64, 0, stream>>>(dm, dl);
+  k_seg<true><<<grid1(maxV, TB, n), TB, 0, stream>>>(dm, dl);
+  if (maxT > 1) k_seed<true><<<dim3((maxV + TB - 1) / TB, maxT - 1, n), TB, 0, stream>>>(dm, dl);
+  k_tile_range<<<grid1(maxT, 64, n), 64, 0, stream>>>(dm, dl);
+  if (dense) {
+    k_dense_delta<<<grid1(maxN + maxB, TB, n), TB, 0, stream>>>(dm, dl);
+    k_dense_scan<<<dim3((maxW + 63) / 64, maxT, n), 64, 0, stream>>>(dm, dl);
+  }
+  e = hipGetLastError();
+  if (e != hipSuccess) return fail(hip_fail(e));
+
+  // ---- handles ----
+  if (fresh) {
+    batch->lives.resize(n);
+    for (uint32_t k = 0; k < n; ++k) {
+      vl_live *l = new (std::nothrow) vl_live;
+      if (!l) {
+        for (uint32_t j = 0; j < k; ++j) delete batch->lives[j];
+        batch_free(batch);
+        return VL_E_SHAPE;
+      }
+      l->batch = batch; l->index = k; l->mir = mirs[k]; l->magic = kLiveMagic;
+      batch->lives[k] = l;
+    }
+    batch->refs = n;
+  }
+  for (uint32_t k = 0; k < n; ++k) {
+    vl_live *l = batch->lives[k];
+    l->h = h[k];
+    l->dev = batch->dev_lives + k;
+    live[k] = l;
+  }
+  // sweeps for the view
+  return VL_OK;
+}
+
+extern "C" int32_t vl_liveness(const vl_mir *mir, uint32_t flags, vl_stream stream, vl_live **live) {
+  if (!live) return VL_E_NULL;
+  return vl_liveness_multi(&mir, 1, flags, 0, stream, live);
+}
+
+extern "C" int32_t vl_live_get(const vl_live *l, vl_live_view *v) {
+  if (!l || !v) return VL_E_NULL;
+  if (l->magic != kLiveMagic) return VL_E_ARG;
+  const DevMir &m = l->mir->h;
+  v->n_instr = m.N; v->n_vreg = m.V; v->n_block = m.B; v->n_occ = m.O; v->words = m.W;
+  v->n_seg = l->h.n_seg; v->n_tile = l->h.T; v->tile_len = l->h.tile_len; v->plan_len = l->h.plan_len;
+  v->sweeps = l->batch->host_counters[(size_t)l->index * kCounters + kCtrSweeps];
+  v->live_in = l->h.live_in; v->live_out = l->h.live_out; v->live_after = l->h.live_after;
+  v->occ_kill = l->h.occ_kill; v->seg_off = l->h.seg_off; v->seg = l->h.seg; v->hull = l->h.hull;
+  return VL_OK;
+}

@@ -1,0 +1,167 @@
+// Program handles: validation of a kernel description and its copy to the device.
+#include <cstdlib>
+#include <cstring>
+#include <vector>
+
+#include "vl_dev.h"
+
+namespace vl {
+static thread_local int32_t g_last_hip = 0;
+int32_t hip_fail(hipError_t e) {
+  g_last_hip = (int32_t)e;
+  (void)hipGetLastError();
+  return VL_E_HIP;
+}
+}  // namespace vl
+
+extern "C" int32_t vl_last_hip_error(void) { return vl::g_last_hip; }
+
+extern "C" const char *vl_strerror(int32_t code) {
+  switch (code) {
+    case VL_OK: return "ok";
+    case VL_E_NULL: return "a required pointer is NULL";
+    case VL_E_SHAPE: return "inconsistent sizes or offsets";
+    case VL_E_RANGE: return "a value is outside its allowed range";
+    case VL_E_LAYOUT: return "blocks are not contiguous, a block is empty, or a block has no earlier predecessor";
+    case VL_E_NOT_STRICT: return "a value is live into the entry block";
+    case VL_E_HIP: return "a HIP runtime call failed";
+    case VL_E_ARG: return "handle does not belong to this call";
+  }
+  return "unknown error code";
+}
+
+static int32_t validate(const vl_mir_desc *d) {
+  if (!d->blk_start || !d->succ_off || !d->instr_occ_off || !d->class_size) return VL_E_NULL;
+  if (d->n_edge && !d->succ) return VL_E_NULL;
+  if (d->n_occ && (!d->occ_vreg || !d->occ_flags)) return VL_E_NULL;
+  if (d->n_vreg && (!d->vreg_class || !d->vreg_width || !d->vreg_align)) return VL_E_NULL;
+  if (d->n_instr == 0 || d->n_block == 0 || d->n_class == 0) return VL_E_SHAPE;
+  if (d->n_class > vl::kMaxClass) return VL_E_RANGE;
+  if (d->n_occ >= (1u << 24) || d->n_instr >= (1u << 28)) return VL_E_RANGE;
+  for (uint32_t c = 0; c < d->n_class; ++c)
+    if (d->class_size[c] == 0 || d->class_size[c] > 512) return VL_E_RANGE;
+  if (d->blk_start[0] != 0 || d->blk_start[d->n_block] != d->n_instr) return VL_E_LAYOUT;
+  for (uint32_t b = 0; b < d->n_block; ++b)
+    if (d->blk_start[b + 1] <= d->blk_start[b]) return VL_E_LAYOUT;
+  if (d->succ_off[0] != 0 || d->succ_off[d->n_block] != d->n_edge) return VL_E_SHAPE;
+  for (uint32_t b = 0; b < d->n_block; ++b)
+    if (d->succ_off[b + 1] < d->succ_off[b]) return VL_E_SHAPE;
+  for (uint32_t e = 0; e < d->n_edge; ++e)
+    if (d->succ[e] >= d->n_block) return VL_E_RANGE;
+  if (d->instr_occ_off[0] != 0 || d->instr_occ_off[d->n_instr] != d->n_occ) return VL_E_SHAPE;
+  for (uint32_t i = 0; i < d->n_instr; ++i) {
+    if (d->instr_occ_off[i + 1] < d->instr_occ_off[i]) return VL_E_SHAPE;
+    if (d->instr_occ_off[i + 1] - d->instr_occ_off[i] > vl::kMaxOperands) return VL_E_RANGE;
+  }
+  for (uint32_t o = 0; o < d->n_occ; ++o) {
+    if (d->occ_vreg[o] >= d->n_vreg) return VL_E_RANGE;
+    if (d->occ_flags[o] == 0 || (d->occ_flags[o] & ~(VL_OCC_DEF | VL_OCC_USE))) return VL_E_RANGE;
+  }
+  for (uint32_t v = 0; v < d->n_vreg; ++v) {
+    if (d->vreg_class[v] >= d->n_class) return VL_E_RANGE;
+    if (d->vreg_width[v] == 0 || d->vreg_width[v] > 32) return VL_E_RANGE;
+    if (d->vreg_align[v] == 0 || d->vreg_align[v] > 32) return VL_E_RANGE;
+  }
+  // every non-entry block needs a predecessor placed before it
+  std::vector<uint8_t> has(d->n_block, 0);
+  for (uint32_t b = 0; b < d->n_block; ++b)
+    for (uint32_t e = d->succ_off[b]; e < d->succ_off[b + 1]; ++e)
+      if (b < d->succ[e]) has[d->succ[e]] = 1;
+  for (uint32_t b = 1; b < d->n_block; ++b)
+    if (!has[b]) return VL_E_LAYOUT;
+  return VL_OK;
+}
+
+namespace {
+struct Bump {
+  size_t off = 0;
+  size_t take(size_t bytes) {
+    size_t at = off;
+    off += (bytes + 255) & ~(size_t)255;
+    return at;
+  }
+};
+}  // namespace
+
+extern "C" int32_t vl_mir_create(const vl_mir_desc *d, vl_mir **out) {
+  if (!d || !out) return VL_E_NULL;
+  int32_t rc = validate(d);
+  if (rc != VL_OK) return rc;
+  const uint32_t N = d->n_instr, V = d->n_vreg, B = d->n_block, O = d->n_occ, E = d->n_edge;
+  // derived index arrays (plain expansions of the CSR offsets) and packed attributes
+  std::vector<uint32_t> occ_instr(O ? O : 1), instr_blk(N), vattr(V ? V : 1);
+  for (uint32_t i = 0; i < N; ++i)
+    for (uint32_t o = d->instr_occ_off[i]; o < d->instr_occ_off[i + 1]; ++o) occ_instr[o] = i;
+  for (uint32_t b = 0; b < B; ++b)
+    for (uint32_t i = d->blk_start[b]; i < d->blk_start[b + 1]; ++i) instr_blk[i] = b;
+  for (uint32_t v = 0; v < V; ++v) vattr[v] = vl::attr_pack(d->vreg_class[v], d->vreg_width[v], d->vreg_align[v]);
+
+  Bump bump;
+  size_t o_blk = bump.take((B + 1) * 4), o_soff = bump.take((B + 1) * 4), o_succ = bump.take((size_t)(E ? E : 1) * 4);
+  size_t o_ooff = bump.take((size_t)(N + 1) * 4), o_ov = bump.take((size_t)(O ? O : 1) * 4);
+  size_t o_oi = bump.take((size_t)(O ? O : 1) * 4), o_ib = bump.take((size_t)N * 4);
+  size_t o_va = bump.take((size_t)(V ? V : 1) * 4), o_of = bump.take((size_t)(O ? O : 1));
+  size_t o_dev = bump.take(sizeof(vl::DevMir));
+
+  vl_mir *m = new (std::nothrow) vl_mir;
+  if (!m) return VL_E_SHAPE;
+  memset(&m->h, 0, sizeof(m->h));
+  m->arena = nullptr;
+  m->magic = vl::kMirMagic;
+  hipError_t e = hipGetDevice(&m->device);
+  if (e == hipSuccess) e = hipMalloc(&m->arena, bump.off);
+  if (e != hipSuccess) { delete m; return vl::hip_fail(e); }
+  char *base = (char *)m->arena;
+  auto up = [&](size_t off, const void *src, size_t bytes) {
+    if (e == hipSuccess && bytes) e = hipMemcpy(base + off, src, bytes, hipMemcpyHostToDevice);
+  };
+  up(o_blk, d->blk_start, (B + 1) * 4);
+  up(o_soff, d->succ_off, (B + 1) * 4);
+  up(o_succ, d->succ, (size_t)E * 4);
+  up(o_ooff, d->instr_occ_off, (size_t)(N + 1) * 4);
+  up(o_ov, d->occ_vreg, (size_t)O * 4);
+  up(o_oi, occ_instr.data(), (size_t)O * 4);
+  up(o_ib, instr_blk.data(), (size_t)N * 4);
+  up(o_va, vattr.data(), (size_t)V * 4);
+  up(o_of, d->occ_flags, (size_t)O);
+
+  vl::DevMir &h = m->h;
+  h.N = N; h.V = V; h.B = B; h.O = O; h.C = d->n_class; h.E = E; h.W = (V + 31) / 32;
+  h.blk_start = (const uint32_t *)(base + o_blk);
+  h.succ_off = (const uint32_t *)(base + o_soff);
+  h.succ = (const uint32_t *)(base + o_succ);
+  h.occ_off = (const uint32_t *)(base + o_ooff);
+  h.occ_vreg = (const uint32_t *)(base + o_ov);
+  h.occ_instr = (const uint32_t *)(base + o_oi);
+  h.instr_blk = (const uint32_t *)(base + o_ib);
+  h.vattr = (const uint32_t *)(base + o_va);
+  h.occ_flags = (const uint8_t *)(base + o_of);
+  uint32_t words = 0;
+  for (uint32_t c = 0; c < d->n_class; ++c) {
+    h.class_size[c] = d->class_size[c];
+    h.class_word[c] = (uint16_t)words;
+    words += (d->class_size[c] + 31u) / 32u;
+    if (d->class_reserved)
+      for (int w = 0; w < 16; ++w) {
+        h.reserved[c][w] = d->class_reserved[c * 16 + w];
+        if (h.reserved[c][w]) h.has_reserved = 1;
+      }
+  }
+  h.occ_words = words;
+  m->dev = (vl::DevMir *)(base + o_dev);
+  up(o_dev, &h, sizeof(h));
+  if (e != hipSuccess) {
+    (void)hipFree(m->arena);
+    delete m;
+    return vl::hip_fail(e);
+  }
+  *out = m;
+  return VL_OK;
+}
+
+extern "C" void vl_mir_destroy(vl_mir *m) {
+  if (!m || m->magic != vl::kMirMagic) return;
+  m->magic = 0;
+  if (m->arena) (void)hipFree(m->arena);
+  delete m;
+}

@@ -1,0 +1,393 @@
+// Batched verification of candidate register assignments.
+//
+// One wavefront handles up to 64 candidates (one per lane) of one kernel over
+// one tile of its event stream.  The stream is the same for every candidate
+// of a kernel, so it is read once per wavefront, 64 entries at a time, and
+// broadcast entry by entry; only the candidate rows differ per lane.
+//
+//   Consistency   every occurrence is compared with the previous occurrence
+//                 of the same vreg (equal along the chain <=> equal to the
+//                 first occurrence; the first broken link is the first
+//                 inconsistent occurrence).
+//   Realizability checked at the first occurrence of each vreg.
+//   Safety        per-lane occupancy bitmask per register class in LDS,
+//                 [word][lane]; a definition tests its range against the
+//                 mask, then sets it; kills clear it.  Tiles start from the
+//                 live-in list of their first instruction.
+// Each lane keeps the smallest violation key it has seen; tiles combine with
+// an atomic minimum in the result slot.  (Section 3.4 of the paper states the
+// three conditions; Section 1 items (1) and (2) define a correct allocation.)
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <vector>
+
+#include "vl_dev.h"
+
+using namespace vl;
+
+namespace {
+
+constexpr uint32_t kRing = 256;                 // occurrences kept per candidate in LDS
+constexpr uint32_t kRingStride = kRing + 2;     // in uint16: an odd number of dwords per row
+constexpr uint32_t kChunk = 64;                 // occurrences staged per step (128 B per row)
+constexpr uint32_t kKeyOk = 0xFFFFFFFFu;
+constexpr uint32_t kKeyCons = 0u << 28, kKeyReal = 1u << 28, kKeySafe = 2u << 28, kKeyPos = (1u << 28) - 1;
+
+struct DevJob {
+  const DevMir *mir;
+  const DevLive *live;
+  const uint16_t *cand;
+  vl_result *out;
+  uint64_t ld;
+  uint32_t K, rows, n_groups, unit_base, n_units, fast, pad0, pad1;
+};
+
+__device__ inline uint32_t find_job(const DevJob *jobs, uint32_t n_jobs, uint32_t unit) {
+  uint32_t lo = 0, hi = n_jobs;
+  while (hi - lo > 1) {
+    uint32_t mid = (lo + hi) >> 1;
+    if (jobs[mid].unit_base <= unit) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+__global__ void k_init(const DevJob *__restrict__ jobs) {
+  const DevJob &J = jobs[blockIdx.y];
+  uint32_t k = blockIdx.x * blockDim.x + threadIdx.x;
+  if (k < J.K) J.out[k].status = kKeyOk;
+}
+
+struct Walk {
+  const uint16_t *rows;   // first row of the group
+  uint64_t ld;
+  uint16_t *ring;         // LDS [64][kRingStride]
+  uint32_t *occw;         // LDS [occ_words][64]
+  uint32_t lane, nrows, n_occ, staged_lo, staged_hi, fast;
+};
+
+__device__ inline void stage_chunk(Walk &w) {
+  const uint32_t sub = w.lane & 7u, c = w.staged_hi + sub * 8u;
+  for (uint32_t rr = 0; rr < 64; rr += 8) {
+    const uint32_t r = rr + (w.lane >> 3);
+    if (r < w.nrows && c < w.n_occ) {
+      const uint16_t *src = w.rows + (uint64_t)r * w.ld + c;
+      uint32_t d[4];
+      if (w.fast && c + 8u <= w.n_occ) {
+        const uint4 x = *reinterpret_cast<const uint4 *>(src);
+        d[0] = x.x; d[1] = x.y; d[2] = x.z; d[3] = x.w;
+      } else {
+        for (int j = 0; j < 4; ++j) {
+          uint32_t a = (c + 2 * j < w.n_occ) ? src[2 * j] : 0u;
+          uint32_t b = (c + 2 * j + 1 < w.n_occ) ? src[2 * j + 1] : 0u;
+          d[j] = a | (b << 16);
+        }
+      }
+      uint32_t *dst = reinterpret_cast<uint32_t *>(w.ring + (size_t)r * kRingStride + (c & (kRing - 1)));
+      dst[0] = d[0]; dst[1] = d[1]; dst[2] = d[2]; dst[3] = d[3];
+    }
+  }
+  w.staged_hi += kChunk;
+  __syncthreads();
+}
+
+// value of occurrence o (uniform) in this lane's row
+__device__ inline uint32_t fetch(const Walk &w, uint32_t o) {
+  if (o < w.staged_hi && o + kRing >= w.staged_hi && o >= w.staged_lo) return w.ring[(size_t)w.lane * kRingStride + (o & (kRing - 1))];
+  return w.lane < w.nrows ? w.rows[(uint64_t)w.lane * w.ld + o] : 0u;
+}
+
+// occupy / release / test the register range [p, p+width) of class cls in this lane's mask
+__device__ inline uint32_t touch(const Walk &w, const DevMir &m, uint32_t fl, uint32_t attr, uint32_t p) {
+  const uint32_t cls = attr_class(attr), width = attr_width(attr);
+  const uint32_t F = m.class_size[cls], wbase = m.class_word[cls];
+  const bool in = p + width <= F;
+  const uint32_t bitpos = p & 31u, word = in ? (p >> 5) : 0u;
+  const uint32_t wm = width == 32 ? 0xFFFFFFFFu : ((1u << width) - 1u);
+  const uint64_t m64 = in ? ((uint64_t)wm << bitpos) : 0ull;
+  const uint32_t mlo = (uint32_t)m64, mhi = (uint32_t)(m64 >> 32);
+  uint32_t *a0 = w.occw + (size_t)(wbase + word) * 64 + w.lane;
+  uint32_t hit = 0;
+  uint32_t old = *a0;
+  if (fl & kPlanClr) *a0 = old & ~mlo;
+  else { hit = old & mlo; *a0 = old | mlo; }
+  if (attr_straddle(attr) && mhi) {   // only unaligned-capable tuples can cross a word
+    uint32_t *a1 = a0 + 64;
+    uint32_t old1 = *a1;
+    if (fl & kPlanClr) *a1 = old1 & ~mhi;
+    else { hit |= old1 & mhi; *a1 = old1 | mhi; }
+  }
+  return (fl & kPlanSet) ? hit : 0u;
+}
+
+__device__ inline bool unrealizable(const DevMir &m, uint32_t attr, uint32_t p) {
+  const uint32_t cls = attr_class(attr), width = attr_width(attr), align = attr_align(attr);
+  bool bad = p + width > m.class_size[cls];
+  bad |= (align & (align - 1)) ? (p % align != 0) : ((p & (align - 1)) != 0);
+  if (m.has_reserved) {
+    for (uint32_t r = p; r < p + width; ++r)
+      if (r < 512 && ((m.reserved[cls][r >> 5] >> (r & 31)) & 1u)) bad = true;
+  }
+  return bad;
+}
+
+__global__ __launch_bounds__(64) void k_walk(const DevJob *__restrict__ jobs, uint32_t n_jobs) {
+  extern __shared__ uint32_t sm[];
+  const DevJob &J = jobs[find_job(jobs, n_jobs, blockIdx.x)];
+  const DevMir &m = *J.mir;
+  const DevLive &L = *J.live;
+  const uint32_t local = blockIdx.x - J.unit_base;
+  const uint32_t tile = local / J.n_groups, group = local % J.n_groups;
+  const uint32_t row0 = group * J.rows;
+  Walk w;
+  w.lane = threadIdx.x;
+  w.nrows = min(J.rows, J.K - row0);
+  w.rows = J.cand + (uint64_t)row0 * J.ld;
+  w.ld = J.ld;
+  w.n_occ = m.O;
+  w.fast = J.fast;
+  w.occw = sm;
+  w.ring = reinterpret_cast<uint16_t *>(sm + (size_t)m.occ_words * 64);
+  for (uint32_t x = 0; x < m.occ_words; ++x) w.occw[x * 64 + w.lane] = 0;
+  const bool active = w.lane < w.nrows;
+  uint32_t key = kKeyOk;
+
+  // start two chunks before the tile's first occurrence, so that nearby history is in LDS
+  const uint32_t o_first = m.occ_off[tile * L.tile_len];
+  const uint32_t c0 = (o_first / kChunk) > 2 ? (o_first / kChunk) - 2 : 0;
+  w.staged_lo = w.staged_hi = c0 * kChunk;
+  __syncthreads();
+  while (w.staged_hi <= o_first && w.staged_hi < w.n_occ) stage_chunk(w);
+
+  auto process = [&](uint32_t ex, uint32_t ey) {
+    const uint32_t o = ex & 0xFFFFFFu, fl = ex >> 24, attr = ey >> 16;
+    if (!(fl & kPlanPost))
+      while (w.staged_hi <= o) stage_chunk(w);
+    const uint32_t p = fetch(w, o);
+    if (fl & kPlanChk) {
+      const uint32_t delta = ey & 0xFFFFu;
+      const uint32_t prev = delta == 0xFFFFu ? L.prev_occ[o] : o - delta;
+      const uint32_t q = fetch(w, prev);
+      if (active && p != q) key = min(key, kKeyCons | o);
+    }
+    if (fl & kPlanFirst) {
+      if (active && unrealizable(m, attr, p)) key = min(key, kKeyReal | o);
+    }
+    if (fl & (kPlanSet | kPlanClr | kPlanBirth)) {
+      const uint32_t hit = touch(w, m, fl, attr, p);
+      if (__any(active && hit)) {
+        const uint32_t i = m.occ_instr[o];
+        if (active && hit) key = min(key, kKeySafe | i);
+      }
+    }
+  };
+
+  if (tile > 0) {
+    const uint32_t sb = L.seed_off[tile], se = L.seed_off[tile + 1];
+    for (uint32_t base = sb; base < se; base += 64) {
+      const uint2 ent = base + w.lane < se ? L.seeds[base + w.lane] : make_uint2(0, 0);
+      const uint32_t cnt = min(64u, se - base);
+      for (uint32_t j = 0; j < cnt; ++j)
+        process(__builtin_amdgcn_readlane(ent.x, j), __builtin_amdgcn_readlane(ent.y, j));
+    }
+  }
+  const uint32_t pb = L.tile_range[2 * tile], pe = L.tile_range[2 * tile + 1];
+  for (uint32_t base = pb; base < pe; base += 64) {
+    const uint2 ent = base + w.lane < pe ? L.plan[base + w.lane] : make_uint2(0, 0);
+    const uint32_t cnt = min(64u, pe - base);
+    for (uint32_t j = 0; j < cnt; ++j)
+      process(__builtin_amdgcn_readlane(ent.x, j), __builtin_amdgcn_readlane(ent.y, j));
+  }
+  if (active && key != kKeyOk) atomicMin(&J.out[row0 + w.lane].status, key);
+}
+
+__device__ inline uint32_t bad_bits(const DevMir &m, uint32_t attr, uint32_t p) {
+  const uint32_t cls = attr_class(attr), width = attr_width(attr), align = attr_align(attr);
+  uint32_t bad = 0;
+  if (p + width > m.class_size[cls]) bad |= VL_BAD_BOUNDS;
+  if (p % align != 0) bad |= VL_BAD_ALIGN;
+  if (m.has_reserved)
+    for (uint32_t r = p; r < p + width; ++r)
+      if (r < 512 && ((m.reserved[cls][r >> 5] >> (r & 31)) & 1u)) bad |= VL_BAD_RESERVED;
+  return bad;
+}
+
+// Turns the winning key of each candidate into its result record.  Safety results
+// get their pair from k_resolve.
+__global__ void k_finalize(const DevJob *__restrict__ jobs) {
+  const DevJob &J = jobs[blockIdx.y];
+  uint32_t k = blockIdx.x * blockDim.x + threadIdx.x;
+  if (k >= J.K) return;
+  const DevMir &m = *J.mir;
+  const DevLive &L = *J.live;
+  const uint32_t key = J.out[k].status;
+  vl_result r = {VL_STATUS_OK, 0, 0, 0};
+  if (key != kKeyOk) {
+    const uint32_t pos = key & kKeyPos;
+    switch (key >> 28) {
+      case 0: {
+        const uint32_t v = m.occ_vreg[pos];
+        r = {VL_STATUS_CONSISTENCY, pos, v, L.first[v]};
+        break;
+      }
+      case 1: {
+        const uint32_t v = m.occ_vreg[pos];
+        r = {VL_STATUS_REALIZABILITY, pos, v, bad_bits(m, m.vattr[v], J.cand[(uint64_t)k * J.ld + pos])};
+        break;
+      }
+      default: r = {VL_STATUS_SAFETY, pos, kNone, kNone}; break;
+    }
+  }
+  J.out[k] = r;
+}
+
+__device__ inline uint32_t lower_bound(const uint32_t *a, uint32_t lo, uint32_t hi, uint32_t key) {
+  while (lo < hi) {
+    uint32_t mid = (lo + hi) >> 1;
+    if (a[mid] < key) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+
+// is v in P(i) = live_after(i) + defs(i)?
+__device__ inline bool occupied_at(const DevMir &m, const DevLive &L, uint32_t v, uint32_t i) {
+  const uint32_t lo = L.vcnt[v], hi = L.vcnt[v + 1];
+  if (lo == hi) return false;
+  const uint32_t b = m.instr_blk[i];
+  const uint32_t x = lower_bound(L.ent_instr, lo, hi, i + 1);  // first mention after i
+  if (x > lo && L.ent_instr[x - 1] >= m.blk_start[b]) {
+    const uint8_t info = L.ent_info[x - 1];                    // last mention at or before i, same block
+    return (info & kEntLiveAfter) || (L.ent_instr[x - 1] == i && (info & kEntHasDef));
+  }
+  if (x < hi && L.ent_instr[x] < m.blk_start[b + 1]) return (L.ent_info[x] & kEntHasUse) != 0;
+  return (L.live_out[(size_t)b * m.W + (v >> 5)] >> (v & 31)) & 1u;
+}
+
+// For a candidate whose first violation is a register clash at instruction i: the
+// lexicographically smallest pair (a < b) of one class, both in P(i), with overlapping
+// ranges.  At the first clashing instruction every clashing pair contains a vreg that
+// the instruction defines, so only pairs (definition, anything in P(i)) are examined.
+__global__ __launch_bounds__(256) void k_resolve(const DevJob *__restrict__ jobs) {
+  const DevJob &J = jobs[blockIdx.y];
+  const uint32_t k = blockIdx.x;
+  if (k >= J.K || J.out[k].status != VL_STATUS_SAFETY) return;
+  const DevMir &m = *J.mir;
+  const DevLive &L = *J.live;
+  const uint16_t *row = J.cand + (uint64_t)k * J.ld;
+  const uint32_t i = J.out[k].where;
+  __shared__ unsigned long long best;
+  __shared__ uint32_t dv[kMaxOperands], dp[kMaxOperands], nd;
+  if (threadIdx.x == 0) {
+    best = ~0ull;
+    uint32_t n = 0;
+    for (uint32_t o = m.occ_off[i]; o < m.occ_off[i + 1]; ++o)
+      if (m.occ_flags[o] & VL_OCC_DEF) {
+        const uint32_t v = m.occ_vreg[o];
+        bool seen = false;
+        for (uint32_t t = 0; t < n; ++t) seen |= dv[t] == v;
+        if (!seen) { dv[n] = v; dp[n] = row[L.first[v]]; ++n; }
+      }
+    nd = n;
+  }
+  __syncthreads();
+  unsigned long long mine = ~0ull;
+  for (uint32_t x = threadIdx.x; x < m.V; x += blockDim.x) {
+    if (!occupied_at(m, L, x, i)) continue;
+    const uint32_t ax = m.vattr[x], px = row[L.first[x]], wx = attr_width(ax);
+    for (uint32_t t = 0; t < nd; ++t) {
+      const uint32_t d = dv[t];
+      if (d == x) continue;
+      const uint32_t ad = m.vattr[d];
+      if (attr_class(ad) != attr_class(ax)) continue;
+      const uint32_t pd = dp[t], wd = attr_width(ad);
+      if (pd < px + wx && px < pd + wd) {
+        const unsigned long long pr = ((unsigned long long)min(d, x) << 32) | max(d, x);
+        mine = pr < mine ? pr : mine;
+      }
+    }
+  }
+  if (mine != ~0ull) atomicMin(&best, mine);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    J.out[k].a = (uint32_t)(best >> 32);
+    J.out[k].b = (uint32_t)best;
+  }
+}
+
+// per-device scratch for job tables
+struct Scratch {
+  std::mutex mu;
+  int device = -1;
+  DevJob *dev = nullptr;
+  DevJob *host = nullptr;   // pinned
+  uint32_t cap = 0, n_valid = 0;
+  hipEvent_t copied = nullptr;
+};
+Scratch g_scratch[16];
+
+}  // namespace
+
+extern "C" int32_t vl_verify_multi(const vl_job *jobs, uint32_t n_jobs, vl_stream stream_) {
+  if (!jobs) return VL_E_NULL;
+  if (n_jobs == 0 || n_jobs > 65535) return VL_E_SHAPE;
+  hipStream_t stream = (hipStream_t)stream_;
+  int device = 0;
+  VL_HIP(hipGetDevice(&device));
+  if (device < 0 || device >= 16) return VL_E_ARG;
+  std::vector<DevJob> tab(n_jobs);
+  uint32_t units = 0, maxK = 0, max_words = 0;
+  for (uint32_t j = 0; j < n_jobs; ++j) {
+    const vl_job &u = jobs[j];
+    if (!u.mir || !u.live || !u.cand || !u.out) return VL_E_NULL;
+    if (u.mir->magic != kMirMagic || u.live->magic != kLiveMagic || u.live->mir != u.mir) return VL_E_ARG;
+    if (u.K == 0 || u.ld < u.mir->h.O) return VL_E_SHAPE;
+    DevJob &d = tab[j];
+    memset(&d, 0, sizeof(d));
+    d.mir = u.mir->dev; d.live = u.live->dev; d.cand = u.cand; d.out = u.out; d.ld = u.ld; d.K = u.K;
+    d.n_groups = (u.K + 63) / 64;
+    d.rows = (u.K + d.n_groups - 1) / d.n_groups;
+    d.unit_base = units;
+    d.n_units = d.n_groups * u.live->h.T;
+    d.fast = (((uintptr_t)u.cand & 15) == 0 && (u.ld & 7) == 0) ? 1u : 0u;
+    units += d.n_units;
+    maxK = std::max(maxK, u.K);
+    max_words = std::max(max_words, u.mir->h.occ_words);
+  }
+  Scratch &s = g_scratch[device];
+  std::lock_guard<std::mutex> lock(s.mu);
+  if (s.cap < n_jobs) {
+    if (s.copied) VL_HIP(hipEventSynchronize(s.copied));
+    VL_HIP(hipStreamSynchronize(stream));
+    if (s.dev) (void)hipFree(s.dev);
+    if (s.host) (void)hipHostFree(s.host);
+    s.dev = nullptr; s.host = nullptr; s.cap = 0; s.n_valid = 0;
+    uint32_t cap = std::max(256u, n_jobs);
+    VL_HIP(hipMalloc((void **)&s.dev, (size_t)cap * sizeof(DevJob)));
+    VL_HIP(hipHostMalloc((void **)&s.host, (size_t)cap * sizeof(DevJob), hipHostMallocDefault));
+    if (!s.copied) VL_HIP(hipEventCreateWithFlags(&s.copied, hipEventDisableTiming));
+    s.cap = cap;
+  }
+  if (s.n_valid != n_jobs || memcmp(s.host, tab.data(), (size_t)n_jobs * sizeof(DevJob)) != 0) {
+    // the previous table may still be on its way to the device
+    if (s.n_valid) VL_HIP(hipEventSynchronize(s.copied));
+    memcpy(s.host, tab.data(), (size_t)n_jobs * sizeof(DevJob));
+    // kernels of an earlier call that still read the old device table run on a stream the
+    // caller must order before this one; on the same stream the copy below is ordered
+    VL_HIP(hipMemcpyAsync(s.dev, s.host, (size_t)n_jobs * sizeof(DevJob), hipMemcpyHostToDevice, stream));
+    VL_HIP(hipEventRecord(s.copied, stream));
+    s.n_valid = n_jobs;
+  }
+  const size_t lds = (size_t)max_words * 64 * 4 + (size_t)64 * kRingStride * 2;
+  k_init<<<dim3((maxK + 255) / 256, n_jobs), 256, 0, stream>>>(s.dev);
+  k_walk<<<units, 64, lds, stream>>>(s.dev, n_jobs);
+  k_finalize<<<dim3((maxK + 255) / 256, n_jobs), 256, 0, stream>>>(s.dev);
+  k_resolve<<<dim3(maxK, n_jobs), 256, 0, stream>>>(s.dev);
+  VL_HIP(hipGetLastError());
+  return VL_OK;
+}
+
+extern "C" int32_t vl_verify_batch(const vl_mir *mir, const vl_live *live, const uint16_t *cand, uint32_t K,
+                                   uint64_t ld, vl_result *out, vl_stream stream) {
+  vl_job j = {mir, live, cand, K, ld, out};
+  return vl_verify_multi(&j, 1, stream);
+}
