@@ -155,6 +155,12 @@ typedef struct {
 } vl_job;
 int32_t vl_verify_multi(const vl_job *jobs, uint32_t n_jobs, vl_stream stream);
 
+/* Measurement aid for callers that cannot allocate inside the timed region: the next
+ * vl_verify_multi / vl_verify_batch call on this thread records the two hipEvent_t
+ * (caller-owned, either may be NULL) on its stream immediately before and after the
+ * candidate-walk kernel, the one that reads the candidate rows.  One-shot. */
+int32_t vl_verify_time_next(void *start_event, void *stop_event);
+
 const char *vl_strerror(int32_t code);
 /* hipError_t of the last failed runtime call on this thread (0 if none). */
 int32_t vl_last_hip_error(void);

@@ -55,6 +55,9 @@ def load():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: build it with "
                                "`python -m paper_2506_17506_amd.build` (hipcc, gfx950)")
+        # torch first: the library must bind to the HIP runtime torch has loaded, so that
+        # both see the same device context and allocations
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         L.vl_mir_create.restype = C.c_int32
         L.vl_mir_create.argtypes = [C.c_void_p, C.POINTER(C.c_void_p)]
@@ -72,6 +75,8 @@ def load():
         L.vl_verify_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint64, C.c_void_p, C.c_void_p]
         L.vl_verify_multi.restype = C.c_int32
         L.vl_verify_multi.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p]
+        L.vl_verify_time_next.restype = C.c_int32
+        L.vl_verify_time_next.argtypes = [C.c_void_p, C.c_void_p]
         L.vl_strerror.restype = C.c_char_p
         L.vl_strerror.argtypes = [C.c_int32]
         L.vl_last_hip_error.restype = C.c_int32
@@ -193,6 +198,11 @@ def vl_verify_multi(jobs, stream=None) -> None:
         raise VlError(rc, "vl_verify_multi")
 
 
+def vl_verify_time_next(start_event, stop_event) -> None:
+    """start_event / stop_event: raw hipEvent_t handles (ints) or None."""
+    load().vl_verify_time_next(C.c_void_p(start_event), C.c_void_p(stop_event))
+
+
 def _dev_ptr(x) -> int:
     return int(x.data_ptr()) if hasattr(x, "data_ptr") else int(x)
 
@@ -214,12 +224,33 @@ def rows_to_device(rows: np.ndarray, device="cuda"):
     return torch.from_numpy(host.view(np.int16)).to(device), ld
 
 
+_hip = None
+
+
+def hip_runtime():
+    """The HIP runtime library already mapped into this process (torch's)."""
+    global _hip
+    if _hip is None:
+        import torch  # noqa: F401
+        path = "libamdhip64.so"
+        with open("/proc/self/maps") as f:
+            for line in f:
+                if "libamdhip64" in line:
+                    path = line.split()[-1]
+                    break
+        _hip = C.CDLL(path)
+        _hip.hipMemcpy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int]
+        _hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        _hip.hipEventDestroy.argtypes = [C.c_void_p]
+        _hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+    return _hip
+
+
 def view_to_numpy(v: _View) -> dict:
     """Copies the device arrays of a live view to numpy (synchronises)."""
     import torch
     torch.cuda.synchronize()
-    hip = C.CDLL("libamdhip64.so")
-    hip.hipMemcpy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int]
+    hip = hip_runtime()
 
     def grab(ptr, shape, dtype):
         a = np.zeros(shape, dtype)

@@ -58,18 +58,25 @@ __global__ void k_init(const DevJob *__restrict__ jobs) {
   if (k < J.K) J.out[k].status = kKeyOk;
 }
 
+// ---- the candidate walk -----------------------------------------------------------------
+// Workgroup = 4 wavefronts over the same 64 candidate rows and the same tile.  All four
+// stage row chunks into one LDS ring; wavefront 0 replays the occupancy events (the
+// sequential part), wavefronts 1-3 share the consistency and realizability checks, which
+// are independent per entry.  Lanes beyond the last row mirror row 0 and never report.
 struct Walk {
   const uint16_t *rows;   // first row of the group
   uint64_t ld;
   uint16_t *ring;         // LDS [64][kRingStride]
   uint32_t *occw;         // LDS [occ_words][64]
-  uint32_t lane, nrows, n_occ, staged_lo, staged_hi, fast;
+  uint32_t tid, lane, row, nrows, n_occ, staged_lo, staged_hi, fast;
 };
 
+// 256 threads stage occurrences [staged_hi, staged_hi + 64) of all rows: 8 threads per
+// row read one 128-byte line, 32 rows per pass.
 __device__ inline void stage_chunk(Walk &w) {
-  const uint32_t sub = w.lane & 7u, c = w.staged_hi + sub * 8u;
-  for (uint32_t rr = 0; rr < 64; rr += 8) {
-    const uint32_t r = rr + (w.lane >> 3);
+  const uint32_t sub = w.tid & 7u, c = w.staged_hi + sub * 8u;
+  for (uint32_t rr = 0; rr < 64; rr += 32) {
+    const uint32_t r = rr + (w.tid >> 3);
     if (r < w.nrows && c < w.n_occ) {
       const uint16_t *src = w.rows + (uint64_t)r * w.ld + c;
       uint32_t d[4];
@@ -88,41 +95,47 @@ __device__ inline void stage_chunk(Walk &w) {
     }
   }
   w.staged_hi += kChunk;
-  __syncthreads();
 }
 
 // value of occurrence o (uniform) in this lane's row
 __device__ inline uint32_t fetch(const Walk &w, uint32_t o) {
-  if (o < w.staged_hi && o + kRing >= w.staged_hi && o >= w.staged_lo) return w.ring[(size_t)w.lane * kRingStride + (o & (kRing - 1))];
-  return w.lane < w.nrows ? w.rows[(uint64_t)w.lane * w.ld + o] : 0u;
+  if (o < w.staged_hi && o + kRing >= w.staged_hi && o >= w.staged_lo)
+    return w.ring[(size_t)w.row * kRingStride + (o & (kRing - 1))];
+  return w.rows[(uint64_t)w.row * w.ld + o];
 }
 
-// occupy / release / test the register range [p, p+width) of class cls in this lane's mask
-__device__ inline uint32_t touch(const Walk &w, const DevMir &m, uint32_t fl, uint32_t attr, uint32_t p) {
-  const uint32_t cls = attr_class(attr), width = attr_width(attr);
-  const uint32_t F = m.class_size[cls], wbase = m.class_word[cls];
-  const bool in = p + width <= F;
-  const uint32_t bitpos = p & 31u, word = in ? (p >> 5) : 0u;
+// Occupy / release / test the register range [p, p+width) in this lane's mask.  The word
+// index is clamped to the class, so a base outside the file cannot leave the mask; such a
+// base is reported as unrealizable (or inconsistent), which outranks whatever this returns.
+__device__ inline uint32_t touch(const Walk &w, uint32_t fl, uint32_t attr, uint32_t cls_tab, uint32_t p) {
+  const uint32_t width = attr_width(attr);
+  const uint32_t F = cls_tab & 0xFFFFu, wbase = cls_tab >> 16;
+  const uint32_t last_word = (F - 1u) >> 5;
+  const uint32_t word = min(p >> 5, last_word), bitpos = p & 31u;
   const uint32_t wm = width == 32 ? 0xFFFFFFFFu : ((1u << width) - 1u);
-  const uint64_t m64 = in ? ((uint64_t)wm << bitpos) : 0ull;
-  const uint32_t mlo = (uint32_t)m64, mhi = (uint32_t)(m64 >> 32);
   uint32_t *a0 = w.occw + (size_t)(wbase + word) * 64 + w.lane;
   uint32_t hit = 0;
-  uint32_t old = *a0;
-  if (fl & kPlanClr) *a0 = old & ~mlo;
-  else { hit = old & mlo; *a0 = old | mlo; }
-  if (attr_straddle(attr) && mhi) {   // only unaligned-capable tuples can cross a word
-    uint32_t *a1 = a0 + 64;
-    uint32_t old1 = *a1;
-    if (fl & kPlanClr) *a1 = old1 & ~mhi;
-    else { hit |= old1 & mhi; *a1 = old1 | mhi; }
+  if (!attr_straddle(attr)) {
+    const uint32_t m = wm << bitpos;
+    if (fl & kPlanClr) __hip_atomic_fetch_and(a0, ~m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+    else hit = __hip_atomic_fetch_or(a0, m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT) & m;
+  } else {
+    const uint64_t m64 = (uint64_t)wm << bitpos;
+    const uint32_t mlo = (uint32_t)m64, mhi = word < last_word ? (uint32_t)(m64 >> 32) : 0u;
+    if (fl & kPlanClr) {
+      __hip_atomic_fetch_and(a0, ~mlo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+      __hip_atomic_fetch_and(a0 + 64, ~mhi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+    } else {
+      hit = __hip_atomic_fetch_or(a0, mlo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT) & mlo;
+      hit |= __hip_atomic_fetch_or(a0 + 64, mhi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT) & mhi;
+    }
   }
   return (fl & kPlanSet) ? hit : 0u;
 }
 
-__device__ inline bool unrealizable(const DevMir &m, uint32_t attr, uint32_t p) {
+__device__ inline bool unrealizable(const DevMir &m, uint32_t attr, uint32_t F, uint32_t p) {
   const uint32_t cls = attr_class(attr), width = attr_width(attr), align = attr_align(attr);
-  bool bad = p + width > m.class_size[cls];
+  bool bad = p + width > F;
   bad |= (align & (align - 1)) ? (p % align != 0) : ((p & (align - 1)) != 0);
   if (m.has_reserved) {
     for (uint32_t r = p; r < p + width; ++r)
@@ -131,7 +144,7 @@ __device__ inline bool unrealizable(const DevMir &m, uint32_t attr, uint32_t p) 
   return bad;
 }
 
-__global__ __launch_bounds__(64) void k_walk(const DevJob *__restrict__ jobs, uint32_t n_jobs) {
+__global__ __launch_bounds__(256) void k_walk(const DevJob *__restrict__ jobs, uint32_t n_jobs) {
   extern __shared__ uint32_t sm[];
   const DevJob &J = jobs[find_job(jobs, n_jobs, blockIdx.x)];
   const DevMir &m = *J.mir;
@@ -140,63 +153,94 @@ __global__ __launch_bounds__(64) void k_walk(const DevJob *__restrict__ jobs, ui
   const uint32_t tile = local / J.n_groups, group = local % J.n_groups;
   const uint32_t row0 = group * J.rows;
   Walk w;
-  w.lane = threadIdx.x;
+  w.tid = threadIdx.x;
+  w.lane = threadIdx.x & 63u;
+  const uint32_t wave = threadIdx.x >> 6;
   w.nrows = min(J.rows, J.K - row0);
+  const bool active = w.lane < w.nrows;
+  w.row = active ? w.lane : 0u;
   w.rows = J.cand + (uint64_t)row0 * J.ld;
   w.ld = J.ld;
   w.n_occ = m.O;
   w.fast = J.fast;
   w.occw = sm;
   w.ring = reinterpret_cast<uint16_t *>(sm + (size_t)m.occ_words * 64);
-  for (uint32_t x = 0; x < m.occ_words; ++x) w.occw[x * 64 + w.lane] = 0;
-  const bool active = w.lane < w.nrows;
+  for (uint32_t x = w.tid; x < m.occ_words * 64; x += 256) w.occw[x] = 0;
+  // per-class file size and first mask word, one class per lane, read back with readlane
+  const uint32_t cls_tab_v = w.lane < m.C ? ((uint32_t)m.class_size[w.lane] | ((uint32_t)m.class_word[w.lane] << 16)) : 0u;
   uint32_t key = kKeyOk;
 
   // start two chunks before the tile's first occurrence, so that nearby history is in LDS
   const uint32_t o_first = m.occ_off[tile * L.tile_len];
   const uint32_t c0 = (o_first / kChunk) > 2 ? (o_first / kChunk) - 2 : 0;
   w.staged_lo = w.staged_hi = c0 * kChunk;
-  __syncthreads();
   while (w.staged_hi <= o_first && w.staged_hi < w.n_occ) stage_chunk(w);
+  __syncthreads();
 
-  auto process = [&](uint32_t ex, uint32_t ey) {
+  auto safety = [&](uint32_t ex, uint32_t ey) {
     const uint32_t o = ex & 0xFFFFFFu, fl = ex >> 24, attr = ey >> 16;
-    if (!(fl & kPlanPost))
-      while (w.staged_hi <= o) stage_chunk(w);
+    const uint32_t p = fetch(w, o);
+    const uint32_t hit = touch(w, fl, attr, __builtin_amdgcn_readlane(cls_tab_v, attr_class(attr)), p);
+    if (__any(hit != 0)) {
+      const uint32_t i = m.occ_instr[o];
+      if (hit) key = min(key, kKeySafe | i);
+    }
+  };
+  auto check = [&](uint32_t ex, uint32_t ey) {
+    const uint32_t o = ex & 0xFFFFFFu, fl = ex >> 24, attr = ey >> 16;
     const uint32_t p = fetch(w, o);
     if (fl & kPlanChk) {
       const uint32_t delta = ey & 0xFFFFu;
       const uint32_t prev = delta == 0xFFFFu ? L.prev_occ[o] : o - delta;
       const uint32_t q = fetch(w, prev);
-      if (active && p != q) key = min(key, kKeyCons | o);
-    }
-    if (fl & kPlanFirst) {
-      if (active && unrealizable(m, attr, p)) key = min(key, kKeyReal | o);
-    }
-    if (fl & (kPlanSet | kPlanClr | kPlanBirth)) {
-      const uint32_t hit = touch(w, m, fl, attr, p);
-      if (__any(active && hit)) {
-        const uint32_t i = m.occ_instr[o];
-        if (active && hit) key = min(key, kKeySafe | i);
-      }
+      if (__any(p != q)) { if (p != q) key = min(key, kKeyCons | o); }
+    } else {
+      const uint32_t F = __builtin_amdgcn_readlane(cls_tab_v, attr_class(attr)) & 0xFFFFu;
+      const bool bad = unrealizable(m, attr, F, p);
+      if (__any(bad)) { if (bad) key = min(key, kKeyReal | o); }
     }
   };
 
-  if (tile > 0) {
+  if (tile > 0 && wave == 0) {   // occupy the tile's live-in values
     const uint32_t sb = L.seed_off[tile], se = L.seed_off[tile + 1];
     for (uint32_t base = sb; base < se; base += 64) {
       const uint2 ent = base + w.lane < se ? L.seeds[base + w.lane] : make_uint2(0, 0);
       const uint32_t cnt = min(64u, se - base);
       for (uint32_t j = 0; j < cnt; ++j)
-        process(__builtin_amdgcn_readlane(ent.x, j), __builtin_amdgcn_readlane(ent.y, j));
+        safety(__builtin_amdgcn_readlane(ent.x, j), __builtin_amdgcn_readlane(ent.y, j));
     }
   }
   const uint32_t pb = L.tile_range[2 * tile], pe = L.tile_range[2 * tile + 1];
   for (uint32_t base = pb; base < pe; base += 64) {
-    const uint2 ent = base + w.lane < pe ? L.plan[base + w.lane] : make_uint2(0, 0);
-    const uint32_t cnt = min(64u, pe - base);
-    for (uint32_t j = 0; j < cnt; ++j)
-      process(__builtin_amdgcn_readlane(ent.x, j), __builtin_amdgcn_readlane(ent.y, j));
+    const bool valid = base + w.lane < pe;
+    const uint2 ent = valid ? L.plan[base + w.lane] : make_uint2(0, 0);
+    const uint32_t fl = ent.x >> 24;
+    // stage up to the largest occurrence this batch reads at its own position
+    uint32_t need = (valid && !(fl & kPlanPost)) ? (ent.x & 0xFFFFFFu) : 0u;
+    for (int d = 32; d >= 1; d >>= 1) need = max(need, (uint32_t)__shfl_xor((int)need, d, 64));
+    need = __builtin_amdgcn_readfirstlane(need);
+    if (w.staged_hi <= need) {
+      __syncthreads();   // everyone is done with the slots about to be overwritten
+      while (w.staged_hi <= need) stage_chunk(w);
+      __syncthreads();
+    }
+    if (wave == 0) {
+      uint64_t todo = __ballot((fl & (kPlanSet | kPlanClr | kPlanBirth)) != 0);
+      while (todo) {
+        const uint32_t j = __builtin_ctzll(todo);
+        todo &= todo - 1;
+        safety(__builtin_amdgcn_readlane(ent.x, j), __builtin_amdgcn_readlane(ent.y, j));
+      }
+    } else {
+      uint64_t todo = __ballot((fl & (kPlanChk | kPlanFirst)) != 0 && !(fl & kPlanPost));
+      const uint32_t lo = wave == 1 ? 0u : (wave == 2 ? 22u : 43u), hi = wave == 1 ? 22u : (wave == 2 ? 43u : 64u);
+      todo &= (hi == 64 ? ~0ull : ((1ull << hi) - 1ull)) & ~((1ull << lo) - 1ull);
+      while (todo) {
+        const uint32_t j = __builtin_ctzll(todo);
+        todo &= todo - 1;
+        check(__builtin_amdgcn_readlane(ent.x, j), __builtin_amdgcn_readlane(ent.y, j));
+      }
+    }
   }
   if (active && key != kKeyOk) atomicMin(&J.out[row0 + w.lane].status, key);
 }
@@ -325,7 +369,15 @@ struct Scratch {
 };
 Scratch g_scratch[16];
 
+thread_local hipEvent_t g_time_start = nullptr, g_time_stop = nullptr;
+
 }  // namespace
+
+extern "C" int32_t vl_verify_time_next(void *start, void *stop) {
+  g_time_start = (hipEvent_t)start;
+  g_time_stop = (hipEvent_t)stop;
+  return VL_OK;
+}
 
 extern "C" int32_t vl_verify_multi(const vl_job *jobs, uint32_t n_jobs, vl_stream stream_) {
   if (!jobs) return VL_E_NULL;
@@ -379,7 +431,10 @@ extern "C" int32_t vl_verify_multi(const vl_job *jobs, uint32_t n_jobs, vl_strea
   }
   const size_t lds = (size_t)max_words * 64 * 4 + (size_t)64 * kRingStride * 2;
   k_init<<<dim3((maxK + 255) / 256, n_jobs), 256, 0, stream>>>(s.dev);
-  k_walk<<<units, 64, lds, stream>>>(s.dev, n_jobs);
+  if (g_time_start) VL_HIP(hipEventRecord(g_time_start, stream));
+  k_walk<<<units, 256, lds, stream>>>(s.dev, n_jobs);
+  if (g_time_stop) VL_HIP(hipEventRecord(g_time_stop, stream));
+  g_time_start = g_time_stop = nullptr;
   k_finalize<<<dim3((maxK + 255) / 256, n_jobs), 256, 0, stream>>>(s.dev);
   k_resolve<<<dim3(maxK, n_jobs), 256, 0, stream>>>(s.dev);
   VL_HIP(hipGetLastError());
