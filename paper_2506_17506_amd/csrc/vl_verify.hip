@@ -60,39 +60,52 @@ __global__ void k_init(const DevJob *__restrict__ jobs) {
 
 // ---- the candidate walk -----------------------------------------------------------------
 // Workgroup = 4 wavefronts over the same 64 candidate rows and the same tile.  All four
-// stage row chunks into one LDS ring; wavefront 0 replays the occupancy events (the
-// sequential part), wavefronts 1-3 share the consistency and realizability checks, which
-// are independent per entry.  Lanes beyond the last row mirror row 0 and never report.
+// stage row chunks into one LDS ring (the next chunk is already on its way from memory
+// while the current one is processed); one wavefront replays the occupancy events (the
+// sequential part), the other three share the consistency and realizability checks,
+// which are independent per entry.  Lanes beyond the last row mirror row 0 and never
+// report.
 struct Walk {
   const uint16_t *rows;   // first row of the group
   uint64_t ld;
   uint16_t *ring;         // LDS [64][kRingStride]
   uint32_t *occw;         // LDS [occ_words][64]
   uint32_t tid, lane, row, nrows, n_occ, staged_lo, staged_hi, fast;
+  uint32_t pre[2][4];     // the chunk after staged_hi, in flight
 };
 
-// 256 threads stage occurrences [staged_hi, staged_hi + 64) of all rows: 8 threads per
-// row read one 128-byte line, 32 rows per pass.
-__device__ inline void stage_chunk(Walk &w) {
-  const uint32_t sub = w.tid & 7u, c = w.staged_hi + sub * 8u;
-  for (uint32_t rr = 0; rr < 64; rr += 32) {
-    const uint32_t r = rr + (w.tid >> 3);
+// Each of the 256 threads owns 8 consecutive occurrences of two rows (r, r + 32) of a
+// 64-occurrence chunk: 8 threads per row read one 128-byte line.
+__device__ inline void load_chunk(Walk &w, uint32_t c0) {
+  const uint32_t c = c0 + (w.tid & 7u) * 8u;
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const uint32_t r = h * 32 + (w.tid >> 3);
+    w.pre[h][0] = w.pre[h][1] = w.pre[h][2] = w.pre[h][3] = 0;
     if (r < w.nrows && c < w.n_occ) {
       const uint16_t *src = w.rows + (uint64_t)r * w.ld + c;
-      uint32_t d[4];
       if (w.fast && c + 8u <= w.n_occ) {
         const uint4 x = *reinterpret_cast<const uint4 *>(src);
-        d[0] = x.x; d[1] = x.y; d[2] = x.z; d[3] = x.w;
+        w.pre[h][0] = x.x; w.pre[h][1] = x.y; w.pre[h][2] = x.z; w.pre[h][3] = x.w;
       } else {
         for (int j = 0; j < 4; ++j) {
           uint32_t a = (c + 2 * j < w.n_occ) ? src[2 * j] : 0u;
           uint32_t b = (c + 2 * j + 1 < w.n_occ) ? src[2 * j + 1] : 0u;
-          d[j] = a | (b << 16);
+          w.pre[h][j] = a | (b << 16);
         }
       }
-      uint32_t *dst = reinterpret_cast<uint32_t *>(w.ring + (size_t)r * kRingStride + (c & (kRing - 1)));
-      dst[0] = d[0]; dst[1] = d[1]; dst[2] = d[2]; dst[3] = d[3];
     }
+  }
+}
+
+// writes the chunk held in registers into the ring as chunk [staged_hi, staged_hi + 64)
+__device__ inline void store_chunk(Walk &w) {
+  const uint32_t c = w.staged_hi + (w.tid & 7u) * 8u;
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const uint32_t r = h * 32 + (w.tid >> 3);
+    uint32_t *dst = reinterpret_cast<uint32_t *>(w.ring + (size_t)r * kRingStride + (c & (kRing - 1)));
+    dst[0] = w.pre[h][0]; dst[1] = w.pre[h][1]; dst[2] = w.pre[h][2]; dst[3] = w.pre[h][3];
   }
   w.staged_hi += kChunk;
 }
@@ -104,33 +117,35 @@ __device__ inline uint32_t fetch(const Walk &w, uint32_t o) {
   return w.rows[(uint64_t)w.row * w.ld + o];
 }
 
-// Occupy / release / test the register range [p, p+width) in this lane's mask.  The word
-// index is clamped to the class, so a base outside the file cannot leave the mask; such a
-// base is reported as unrealizable (or inconsistent), which outranks whatever this returns.
-__device__ inline uint32_t touch(const Walk &w, uint32_t fl, uint32_t attr, uint32_t cls_tab, uint32_t p) {
+// Address of the mask word holding register p of a class, and the mask of the tuple.
+// The word index is clamped to the class, so a base outside the file cannot leave the
+// mask; such a base is reported as unrealizable (or inconsistent), which outranks
+// whatever the occupancy test says.
+struct Touch { uint32_t *addr; uint32_t mlo, mhi; };
+__device__ inline Touch locate(const Walk &w, uint32_t attr, uint32_t cls_tab, uint32_t p) {
   const uint32_t width = attr_width(attr);
   const uint32_t F = cls_tab & 0xFFFFu, wbase = cls_tab >> 16;
   const uint32_t last_word = (F - 1u) >> 5;
   const uint32_t word = min(p >> 5, last_word), bitpos = p & 31u;
   const uint32_t wm = width == 32 ? 0xFFFFFFFFu : ((1u << width) - 1u);
-  uint32_t *a0 = w.occw + (size_t)(wbase + word) * 64 + w.lane;
-  uint32_t hit = 0;
-  if (!attr_straddle(attr)) {
-    const uint32_t m = wm << bitpos;
-    if (fl & kPlanClr) __hip_atomic_fetch_and(a0, ~m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
-    else hit = __hip_atomic_fetch_or(a0, m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT) & m;
-  } else {
+  Touch t;
+  t.addr = w.occw + (size_t)(wbase + word) * 64 + w.lane;
+  if (!attr_straddle(attr)) { t.mlo = wm << bitpos; t.mhi = 0; }
+  else {
     const uint64_t m64 = (uint64_t)wm << bitpos;
-    const uint32_t mlo = (uint32_t)m64, mhi = word < last_word ? (uint32_t)(m64 >> 32) : 0u;
-    if (fl & kPlanClr) {
-      __hip_atomic_fetch_and(a0, ~mlo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
-      __hip_atomic_fetch_and(a0 + 64, ~mhi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
-    } else {
-      hit = __hip_atomic_fetch_or(a0, mlo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT) & mlo;
-      hit |= __hip_atomic_fetch_or(a0 + 64, mhi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT) & mhi;
-    }
+    t.mlo = (uint32_t)m64;
+    t.mhi = word < last_word ? (uint32_t)(m64 >> 32) : 0u;
   }
-  return (fl & kPlanSet) ? hit : 0u;
+  return t;
+}
+
+// Every event flips the bits of its range: an occupy on free bits and a release of held
+// bits are both an exclusive-or, exact up to the first clash, which is all that is
+// reported.  Returns the bits that were already set (meaningful for occupy-with-test).
+__device__ inline uint32_t flip(const Touch &t, bool straddle) {
+  uint32_t hit = __hip_atomic_fetch_xor(t.addr, t.mlo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT) & t.mlo;
+  if (straddle) hit |= __hip_atomic_fetch_xor(t.addr + 64, t.mhi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT) & t.mhi;
+  return hit;
 }
 
 __device__ inline bool unrealizable(const DevMir &m, uint32_t attr, uint32_t F, uint32_t p) {
@@ -155,7 +170,9 @@ __global__ __launch_bounds__(256) void k_walk(const DevJob *__restrict__ jobs, u
   Walk w;
   w.tid = threadIdx.x;
   w.lane = threadIdx.x & 63u;
-  const uint32_t wave = threadIdx.x >> 6;
+  // the occupancy role moves from wavefront to wavefront with the workgroup index, so
+  // that neighbouring workgroups do not all put it on the same SIMD
+  const uint32_t role = ((threadIdx.x >> 6) + blockIdx.x) & 3u;
   w.nrows = min(J.rows, J.K - row0);
   const bool active = w.lane < w.nrows;
   w.row = active ? w.lane : 0u;
@@ -174,19 +191,28 @@ __global__ __launch_bounds__(256) void k_walk(const DevJob *__restrict__ jobs, u
   const uint32_t o_first = m.occ_off[tile * L.tile_len];
   const uint32_t c0 = (o_first / kChunk) > 2 ? (o_first / kChunk) - 2 : 0;
   w.staged_lo = w.staged_hi = c0 * kChunk;
-  while (w.staged_hi <= o_first && w.staged_hi < w.n_occ) stage_chunk(w);
+  load_chunk(w, w.staged_hi);
+  while (w.staged_hi <= o_first && w.staged_hi < w.n_occ) {
+    store_chunk(w);
+    load_chunk(w, w.staged_hi);
+  }
   __syncthreads();
 
-  auto safety = [&](uint32_t ex, uint32_t ey) {
+  auto in_ring = [&](uint32_t o) { return o < w.staged_hi && o + kRing >= w.staged_hi && o >= w.staged_lo; };
+  const uint16_t *my_ring = w.ring + (size_t)w.row * kRingStride;
+
+  // one entry at a time: any source (ring or global memory)
+  auto safety1 = [&](uint32_t ex, uint32_t ey) {
     const uint32_t o = ex & 0xFFFFFFu, fl = ex >> 24, attr = ey >> 16;
     const uint32_t p = fetch(w, o);
-    const uint32_t hit = touch(w, fl, attr, __builtin_amdgcn_readlane(cls_tab_v, attr_class(attr)), p);
+    const Touch t = locate(w, attr, __builtin_amdgcn_readlane(cls_tab_v, attr_class(attr)), p);
+    const uint32_t hit = (fl & kPlanSet) ? flip(t, attr_straddle(attr)) : (flip(t, attr_straddle(attr)), 0u);
     if (__any(hit != 0)) {
       const uint32_t i = m.occ_instr[o];
       if (hit) key = min(key, kKeySafe | i);
     }
   };
-  auto check = [&](uint32_t ex, uint32_t ey) {
+  auto check1 = [&](uint32_t ex, uint32_t ey) {
     const uint32_t o = ex & 0xFFFFFFu, fl = ex >> 24, attr = ey >> 16;
     const uint32_t p = fetch(w, o);
     if (fl & kPlanChk) {
@@ -201,13 +227,109 @@ __global__ __launch_bounds__(256) void k_walk(const DevJob *__restrict__ jobs, u
     }
   };
 
-  if (tile > 0 && wave == 0) {   // occupy the tile's live-in values
+  constexpr int G = 8;   // entries in flight: their LDS reads and atomics overlap
+  // Up to G occupancy events whose registers all come from the ring and cannot cross a
+  // mask word: read the G values, issue the G mask updates back to back (LDS executes
+  // them in order), and only then look at what they returned.
+  auto safety_group = [&](uint64_t &todo, const uint2 ent) {
+    uint32_t ex[G], ey[G];
+    int n = 0;
+    bool quick = true;
+#pragma unroll
+    for (int t = 0; t < G; ++t) {
+      ex[t] = 0; ey[t] = 0;
+      if (todo) {
+        const uint32_t j = __builtin_ctzll(todo);
+        todo &= todo - 1;
+        ex[t] = __builtin_amdgcn_readlane(ent.x, j);
+        ey[t] = __builtin_amdgcn_readlane(ent.y, j);
+        quick = quick && in_ring(ex[t] & 0xFFFFFFu) && !attr_straddle(ey[t] >> 16);
+        n = t + 1;
+      }
+    }
+    if (!quick) {
+#pragma unroll
+      for (int t = 0; t < G; ++t) if (t < n) safety1(ex[t], ey[t]);
+      return;
+    }
+    uint32_t p[G], old[G], msk[G];
+#pragma unroll
+    for (int t = 0; t < G; ++t) p[t] = my_ring[ex[t] & (kRing - 1)];   // unused slots read slot 0
+#pragma unroll
+    for (int t = 0; t < G; ++t) {
+      const uint32_t attr = ey[t] >> 16;
+      const Touch tc = locate(w, attr, __builtin_amdgcn_readlane(cls_tab_v, attr_class(attr)), p[t]);
+      msk[t] = t < n ? tc.mlo : 0u;    // an empty slot flips nothing
+      old[t] = __hip_atomic_fetch_xor(tc.addr, msk[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+    }
+    uint32_t any_hit = 0;
+#pragma unroll
+    for (int t = 0; t < G; ++t) {
+      old[t] = ((ex[t] >> 24) & kPlanSet) ? (old[t] & msk[t]) : 0u;
+      any_hit |= old[t];
+    }
+    if (__any(any_hit != 0)) {
+#pragma unroll
+      for (int t = 0; t < G; ++t)
+        if (__any(old[t] != 0)) {
+          const uint32_t i = m.occ_instr[ex[t] & 0xFFFFFFu];
+          if (old[t]) key = min(key, kKeySafe | i);
+        }
+    }
+  };
+  auto check_group = [&](uint64_t &todo, const uint2 ent) {
+    uint32_t ex[G], ey[G];
+    int n = 0;
+    bool quick = true;
+#pragma unroll
+    for (int t = 0; t < G; ++t) {
+      ex[t] = 0; ey[t] = 0;
+      if (todo) {
+        const uint32_t j = __builtin_ctzll(todo);
+        todo &= todo - 1;
+        ex[t] = __builtin_amdgcn_readlane(ent.x, j);
+        ey[t] = __builtin_amdgcn_readlane(ent.y, j);
+        const uint32_t o = ex[t] & 0xFFFFFFu, delta = ey[t] & 0xFFFFu;
+        quick = quick && in_ring(o);
+        if ((ex[t] >> 24) & kPlanChk) quick = quick && delta != 0xFFFFu && in_ring(o - delta);
+        n = t + 1;
+      }
+    }
+    if (!quick) {
+#pragma unroll
+      for (int t = 0; t < G; ++t) if (t < n) check1(ex[t], ey[t]);
+      return;
+    }
+    uint32_t p[G], q[G];
+#pragma unroll
+    for (int t = 0; t < G; ++t) {
+      const uint32_t o = ex[t] & 0xFFFFFFu;
+      const bool chk = ((ex[t] >> 24) & kPlanChk) != 0;
+      p[t] = my_ring[o & (kRing - 1)];
+      q[t] = my_ring[(chk ? o - (ey[t] & 0xFFFFu) : o) & (kRing - 1)];
+    }
+    bool wrong = false;
+#pragma unroll
+    for (int t = 0; t < G; ++t) {
+      if ((ex[t] >> 24) & kPlanFirst) {
+        const uint32_t attr = ey[t] >> 16;
+        wrong |= unrealizable(m, attr, __builtin_amdgcn_readlane(cls_tab_v, attr_class(attr)) & 0xFFFFu, p[t]);
+      } else {
+        wrong |= p[t] != q[t];   // empty slots compare a value with itself
+      }
+    }
+    if (__any(wrong)) {   // rare: redo the group one entry at a time to attribute it
+#pragma unroll
+      for (int t = 0; t < G; ++t) if (t < n) check1(ex[t], ey[t]);
+    }
+  };
+
+  if (tile > 0 && role == 0) {   // occupy the tile's live-in values
     const uint32_t sb = L.seed_off[tile], se = L.seed_off[tile + 1];
     for (uint32_t base = sb; base < se; base += 64) {
       const uint2 ent = base + w.lane < se ? L.seeds[base + w.lane] : make_uint2(0, 0);
-      const uint32_t cnt = min(64u, se - base);
-      for (uint32_t j = 0; j < cnt; ++j)
-        safety(__builtin_amdgcn_readlane(ent.x, j), __builtin_amdgcn_readlane(ent.y, j));
+      uint64_t todo = __ballot(base + w.lane < se);
+      while (todo) safety_group(todo, ent);
     }
   }
   const uint32_t pb = L.tile_range[2 * tile], pe = L.tile_range[2 * tile + 1];
@@ -221,25 +343,20 @@ __global__ __launch_bounds__(256) void k_walk(const DevJob *__restrict__ jobs, u
     need = __builtin_amdgcn_readfirstlane(need);
     if (w.staged_hi <= need) {
       __syncthreads();   // everyone is done with the slots about to be overwritten
-      while (w.staged_hi <= need) stage_chunk(w);
+      while (w.staged_hi <= need) {
+        store_chunk(w);
+        load_chunk(w, w.staged_hi);
+      }
       __syncthreads();
     }
-    if (wave == 0) {
+    if (role == 0) {
       uint64_t todo = __ballot((fl & (kPlanSet | kPlanClr | kPlanBirth)) != 0);
-      while (todo) {
-        const uint32_t j = __builtin_ctzll(todo);
-        todo &= todo - 1;
-        safety(__builtin_amdgcn_readlane(ent.x, j), __builtin_amdgcn_readlane(ent.y, j));
-      }
+      while (todo) safety_group(todo, ent);
     } else {
       uint64_t todo = __ballot((fl & (kPlanChk | kPlanFirst)) != 0 && !(fl & kPlanPost));
-      const uint32_t lo = wave == 1 ? 0u : (wave == 2 ? 22u : 43u), hi = wave == 1 ? 22u : (wave == 2 ? 43u : 64u);
+      const uint32_t lo = role == 1 ? 0u : (role == 2 ? 22u : 43u), hi = role == 1 ? 22u : (role == 2 ? 43u : 64u);
       todo &= (hi == 64 ? ~0ull : ((1ull << hi) - 1ull)) & ~((1ull << lo) - 1ull);
-      while (todo) {
-        const uint32_t j = __builtin_ctzll(todo);
-        todo &= todo - 1;
-        check(__builtin_amdgcn_readlane(ent.x, j), __builtin_amdgcn_readlane(ent.y, j));
-      }
+      while (todo) check_group(todo, ent);
     }
   }
   if (active && key != kKeyOk) atomicMin(&J.out[row0 + w.lane].status, key);
