@@ -80,9 +80,11 @@ struct DevLive {
   uint32_t *item_off;   // [N+B+1] plan offset of each item (boundary b at blk_start[b]+b,
                         //          instruction i of block b at i+b+1)
   uint32_t *seg_off;    // [V+1]
+  uint32_t *ent_seg;    // [O+1] runs starting in each mention group's stretch -> prefix sums
   uint32_t *hull;       // [V][2]
   uint32_t *seed_off;   // [T+1]
   uint32_t *seed_cur;   // [T]
+  uint32_t *blk_live;   // [V][ceil(B/32)] blocks each vreg is live into
   uint32_t *long_queue; // [V] vregs whose occurrence list needs the bitmap sort
   uint32_t *bitmap;     // [ceil(O/32)] scratch for the bitmap sort, one list at a time per block
   uint32_t *counters;   // [kCounters]

@@ -36,14 +36,32 @@ __device__ inline uint32_t lower_bound(const uint32_t *a, uint32_t lo, uint32_t 
 }
 
 // ---- 1. occurrences grouped by vreg -------------------------------------------------
-__global__ void k_count(MIRS) {
+constexpr uint32_t kSlice = 8192;   // occurrences per workgroup in the counting kernels
+
+// Occurrences per vreg.  A few vregs (base addresses, accumulators) are mentioned
+// thousands of times, so each workgroup first counts its slice in an LDS histogram and
+// then adds the non-zero bins to the global counters once.
+template <bool kLds>
+__global__ __launch_bounds__(1024) void k_count(MIRS) {
   const DevMir &m = *mirs[blockIdx.y];
   DevLive &L = lives[blockIdx.y];
-  uint32_t o = blockIdx.x * blockDim.x + threadIdx.x;
-  if (o < m.O) atomicAdd(&L.vcnt[m.occ_vreg[o]], 1u);
+  extern __shared__ uint32_t sm[];
+  const uint32_t o0 = blockIdx.x * kSlice;
+  if (o0 >= m.O) return;
+  const uint32_t o1 = min(m.O, o0 + kSlice);
+  if (!kLds) {
+    for (uint32_t o = o0 + threadIdx.x; o < o1; o += 1024) atomicAdd(&L.vcnt[m.occ_vreg[o]], 1u);
+    return;
+  }
+  for (uint32_t v = threadIdx.x; v < m.V; v += 1024) sm[v] = 0;
+  __syncthreads();
+  for (uint32_t o = o0 + threadIdx.x; o < o1; o += 1024) atomicAdd(&sm[m.occ_vreg[o]], 1u);
+  __syncthreads();
+  for (uint32_t v = threadIdx.x; v < m.V; v += 1024)
+    if (sm[v]) atomicAdd(&L.vcnt[v], sm[v]);
 }
 
-enum { kScanVreg = 0, kScanItems = 1, kScanSeg = 2, kScanSeed = 3 };
+enum { kScanVreg = 0, kScanItems = 1, kScanSeg = 2, kScanSeed = 3 };   // kScanSeg: per-entry run counts
 
 // In-place exclusive scan of p[0..n), total to p[n]; one 1024-thread block per kernel.
 // (The array is chosen at compile time: a run-time switch over the four arrays was
@@ -52,8 +70,8 @@ template <int kWhich>
 __global__ __launch_bounds__(1024) void k_scan(MIRS) {
   const DevMir &m = *mirs[blockIdx.x];
   DevLive &L = lives[blockIdx.x];
-  uint32_t *p = kWhich == kScanVreg ? L.vcnt : kWhich == kScanItems ? L.item_off : kWhich == kScanSeg ? L.seg_off : L.seed_off;
-  const uint32_t n = kWhich == kScanVreg ? m.V : kWhich == kScanItems ? m.N + m.B : kWhich == kScanSeg ? m.V : L.T;
+  uint32_t *p = kWhich == kScanVreg ? L.vcnt : kWhich == kScanItems ? L.item_off : kWhich == kScanSeg ? L.ent_seg : L.seed_off;
+  const uint32_t n = kWhich == kScanVreg ? m.V : kWhich == kScanItems ? m.N + m.B : kWhich == kScanSeg ? m.O : L.T;
   __shared__ uint32_t part[1024];
   const uint32_t tid = threadIdx.x;
   const uint32_t chunk = (n + 1023u) / 1024u;
@@ -77,13 +95,39 @@ __global__ __launch_bounds__(1024) void k_scan(MIRS) {
   if (tid == 1023) p[n] = part[1023];
 }
 
-__global__ void k_place(MIRS) {
+// Places each occurrence into its vreg's range (order inside a range is fixed later).
+// Same privatisation: the slice reserves a sub-range per vreg with one global atomic,
+// then ranks its own occurrences in LDS.
+template <bool kLds>
+__global__ __launch_bounds__(1024) void k_place(MIRS) {
   const DevMir &m = *mirs[blockIdx.y];
   DevLive &L = lives[blockIdx.y];
-  uint32_t o = blockIdx.x * blockDim.x + threadIdx.x;
-  if (o >= m.O) return;
-  uint32_t v = m.occ_vreg[o];
-  L.vocc_tmp[L.vcnt[v] + atomicAdd(&L.vcur[v], 1u)] = o;
+  extern __shared__ uint32_t sm[];
+  const uint32_t o0 = blockIdx.x * kSlice;
+  if (o0 >= m.O) return;
+  const uint32_t o1 = min(m.O, o0 + kSlice);
+  if (!kLds) {
+    for (uint32_t o = o0 + threadIdx.x; o < o1; o += 1024) {
+      const uint32_t v = m.occ_vreg[o];
+      L.vocc_tmp[L.vcnt[v] + atomicAdd(&L.vcur[v], 1u)] = o;
+    }
+    return;
+  }
+  uint32_t *cnt = sm, *base = sm + m.V;
+  for (uint32_t v = threadIdx.x; v < m.V; v += 1024) cnt[v] = 0;
+  __syncthreads();
+  for (uint32_t o = o0 + threadIdx.x; o < o1; o += 1024) atomicAdd(&cnt[m.occ_vreg[o]], 1u);
+  __syncthreads();
+  for (uint32_t v = threadIdx.x; v < m.V; v += 1024) {
+    const uint32_t c = cnt[v];
+    if (c) base[v] = L.vcnt[v] + atomicAdd(&L.vcur[v], c);
+    cnt[v] = 0;
+  }
+  __syncthreads();
+  for (uint32_t o = o0 + threadIdx.x; o < o1; o += 1024) {
+    const uint32_t v = m.occ_vreg[o];
+    L.vocc_tmp[base[v] + atomicAdd(&cnt[v], 1u)] = o;
+  }
 }
 
 constexpr uint32_t kShortList = 16;
@@ -95,6 +139,8 @@ __global__ void k_sort_short(MIRS) {
   uint32_t v = blockIdx.x * blockDim.x + threadIdx.x;
   if (v >= m.V) return;
   const uint32_t lo = L.vcnt[v], len = L.vcnt[v + 1] - lo;
+  L.hull[2 * v] = kNone;   // min / max targets of the interval kernel
+  L.hull[2 * v + 1] = 0;
   if (len == 0) { L.first[v] = kNone; return; }
   if (len > kShortList) {
     L.long_queue[atomicAdd(&L.counters[kCtrLong], 1u)] = v;
@@ -176,15 +222,36 @@ __global__ void k_summary(MIRS) {
   const DevMir &m = *mirs[blockIdx.y];
   DevLive &L = lives[blockIdx.y];
   uint32_t e = blockIdx.x * blockDim.x + threadIdx.x;
-  if (e >= m.O) return;
-  const uint32_t o = L.vocc[e], v = m.occ_vreg[o], i = L.ent_instr[e], b = m.instr_blk[i];
-  const uint32_t fl = m.occ_flags[o], bit = 1u << (v & 31), w = v >> 5;
-  if (fl & VL_OCC_DEF) atomicOr(&L.def[(size_t)b * m.W + w], bit);
-  if (fl & VL_OCC_USE) {
-    const uint32_t lo = L.vcnt[v];
-    uint32_t gs = e;
-    while (gs > lo && L.ent_instr[gs - 1] == i) --gs;
-    if (gs == lo || m.instr_blk[L.ent_instr[gs - 1]] != b) atomicOr(&L.use[(size_t)b * m.W + w], bit);
+  uint32_t b = kNone, w = 0, dbits = 0, ubits = 0;
+  if (e < m.O) {
+    const uint32_t o = L.vocc[e], v = m.occ_vreg[o], i = L.ent_instr[e];
+    const uint32_t fl = m.occ_flags[o], bit = 1u << (v & 31);
+    b = m.instr_blk[i];
+    w = v >> 5;
+    if (fl & VL_OCC_DEF) dbits = bit;
+    if (fl & VL_OCC_USE) {
+      const uint32_t lo = L.vcnt[v];
+      uint32_t gs = e;
+      while (gs > lo && L.ent_instr[gs - 1] == i) --gs;
+      if (gs == lo || m.instr_blk[L.ent_instr[gs - 1]] != b) ubits = bit;
+    }
+  }
+  // entries are sorted by vreg, then instruction: neighbours in a wavefront mostly hit
+  // the same word of the same block.  OR them together along runs of equal (block, word)
+  // and let the last lane of each run issue the atomics.
+  const int lane = threadIdx.x & 63;
+  for (int d = 1; d < 64; d <<= 1) {
+    const uint32_t pb = __shfl_up(b, d, 64), pw = __shfl_up(w, d, 64);
+    const uint32_t pd = __shfl_up(dbits, d, 64), pu = __shfl_up(ubits, d, 64);
+    // a run of equal keys is contiguous, so equality with the lane d below means the
+    // whole span in between belongs to the run
+    if (lane >= d && pb == b && pw == w) { dbits |= pd; ubits |= pu; }
+  }
+  const uint32_t nb = __shfl_down(b, 1, 64), nw = __shfl_down(w, 1, 64);
+  const bool last = lane == 63 || nb != b || nw != w;
+  if (b != kNone && last) {
+    if (dbits) atomicOr(&L.def[(size_t)b * m.W + w], dbits);
+    if (ubits) atomicOr(&L.use[(size_t)b * m.W + w], ubits);
   }
 }
 
@@ -390,76 +457,122 @@ __global__ void k_plan_fill(MIRS) {
 }
 
 // ---- 5b. live intervals ---------------------------------------------------------------
-// One lane per vreg walks the blocks in linear order and its own mentions, emitting the
-// maximal runs of {i : v in P(i)}.
+// blk_live[v] = bitmask over blocks b with v in live_in[b] (the transpose of live_in), so
+// that a vreg finds the blocks it is live through without testing every block.
+__global__ void k_blk_transpose(MIRS) {
+  const DevMir &m = *mirs[blockIdx.z];
+  DevLive &L = lives[blockIdx.z];
+  const uint32_t b = blockIdx.y, w = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= m.B || w >= m.W) return;
+  uint32_t bits = L.live_in[(size_t)b * m.W + w];
+  const uint32_t WB = (m.B + 31) / 32;
+  while (bits) {
+    const uint32_t v = w * 32 + __ffs(bits) - 1;
+    bits &= bits - 1;
+    atomicOr(&L.blk_live[(size_t)v * WB + (b >> 5)], 1u << (b & 31));
+  }
+}
+
+// Membership of v in P(.) changes only at instructions that mention v and at block
+// boundaries.  The lane of each mention group (all mentions of v at one instruction) owns
+// the stretch from its instruction up to the next mention of v (the last group: up to the
+// end of the program) and finds the run starts and ends inside it; what holds just before
+// the stretch is known locally.  Groups are sorted by (vreg, instruction), so a prefix sum
+// of the start counts numbers the runs in CSR order; the j-th end belongs to the j-th start.
 template <bool kFill>
 __global__ void k_seg(MIRS) {
   const DevMir &m = *mirs[blockIdx.y];
   DevLive &L = lives[blockIdx.y];
-  uint32_t v = blockIdx.x * blockDim.x + threadIdx.x;
-  if (v >= m.V) return;
+  const uint32_t e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= m.O) return;
+  const uint8_t info = L.ent_info[e];
+  if (!(info & kEntGroupStart)) { if (!kFill) L.ent_seg[e] = 0; return; }
+  const uint32_t v = m.occ_vreg[L.vocc[e]];
   const uint32_t lo = L.vcnt[v], hi = L.vcnt[v + 1];
-  uint32_t n = 0, cs = 0, ce = 0, hull_lo = 0;
-  bool open = false;
-  uint32_t *out = kFill ? L.seg + 2 * (size_t)L.seg_off[v] : nullptr;
-  auto add = [&](uint32_t s, uint32_t t) {
-    if (open && s == ce) { ce = t; return; }
-    if (open) { if (kFill) { out[2 * n] = cs; out[2 * n + 1] = ce; } ++n; }
-    else hull_lo = s;
-    cs = s; ce = t; open = true;
+  const uint32_t i = L.ent_instr[e], b = m.instr_blk[i];
+  const uint32_t WB = (m.B + 31) / 32;
+  const uint32_t *live_blocks = L.blk_live + (size_t)v * WB;
+  // was v occupied just before this stretch?
+  bool cur;
+  if (i == 0) cur = false;
+  else if (e > lo && L.ent_instr[e - 1] == i - 1) cur = (L.ent_info[e - 1] & (kEntHasDef | kEntLiveAfter)) != 0;
+  else if (i > m.blk_start[b]) cur = (info & kEntHasUse) != 0;
+  else cur = bit_get(L.live_out + (size_t)(b - 1) * m.W, v);
+  // runs that started before this stretch and ended before it: the end index lags the
+  // start index by one exactly while a run is open
+  uint32_t n_start = kFill ? L.ent_seg[e] : 0;
+  uint32_t n_end = kFill ? n_start - (cur ? 1u : 0u) : 0;
+  uint32_t first_start = kNone, last_end = 0;
+  auto span = [&](uint32_t s, uint32_t t, bool member) {
+    if (t <= s) return;
+    if (member && !cur) { if (kFill) L.seg[2 * (size_t)n_start] = s; ++n_start; first_start = min(first_start, s); }
+    if (!member && cur) { if (kFill) L.seg[2 * (size_t)n_end + 1] = s; ++n_end; last_end = s; }
+    cur = member;
   };
-  uint32_t e = lo;
-  for (uint32_t b = 0; b < m.B; ++b) {
-    const uint32_t bs = m.blk_start[b], be = m.blk_start[b + 1];
-    if (e >= hi || L.ent_instr[e] >= be) {  // no mention in this block
-      if (bit_get(L.live_in + (size_t)b * m.W, v)) add(bs, be);
-      continue;
-    }
-    uint32_t pos = bs;
-    bool cur = (L.ent_info[e] & kEntHasUse) != 0;  // live on entry iff the first mention reads
-    while (e < hi && L.ent_instr[e] < be) {
-      const uint32_t i = L.ent_instr[e];
-      const uint8_t info = L.ent_info[e];
-      if (cur && pos < i) add(pos, i);
-      if (info & (kEntHasDef | kEntLiveAfter)) add(i, i + 1);
-      pos = i + 1;
-      cur = (info & kEntLiveAfter) != 0;
-      while (e < hi && L.ent_instr[e] == i) ++e;
-    }
-    if (cur && pos < be) add(pos, be);
-  }
-  if (open) { if (kFill) { out[2 * n] = cs; out[2 * n + 1] = ce; } ++n; }
-  if (kFill) {
-    L.hull[2 * v] = n ? hull_lo : 0;
-    L.hull[2 * v + 1] = n ? ce : 0;
+  uint32_t ge = e + 1;
+  while (ge < hi && L.ent_instr[ge] == i) ++ge;
+  const bool la = (info & kEntLiveAfter) != 0;
+  span(i, i + 1, (info & kEntHasDef) || la);
+  const uint32_t i2 = ge < hi ? L.ent_instr[ge] : m.N;
+  const uint32_t b2 = ge < hi ? m.instr_blk[i2] : m.B;
+  if (b2 == b) {
+    span(i + 1, i2, la);
   } else {
-    L.seg_off[v] = n;
+    span(i + 1, m.blk_start[b + 1], la);
+    for (uint32_t x = b + 1; x < b2; ++x)
+      span(m.blk_start[x], m.blk_start[x + 1], (live_blocks[x >> 5] >> (x & 31)) & 1u);
+    if (ge < hi) span(m.blk_start[b2], i2, (L.ent_info[ge] & kEntHasUse) != 0);
   }
+  if (ge >= hi && cur) { if (kFill) L.seg[2 * (size_t)n_end + 1] = m.N; ++n_end; last_end = m.N; }
+  if (!kFill) {
+    L.ent_seg[e] = n_start;
+    if (first_start != kNone) atomicMin(&L.hull[2 * v], first_start);
+    if (last_end) atomicMax(&L.hull[2 * v + 1], last_end);
+  }
+}
+
+// seg_off per vreg from the per-entry prefix sums; hulls of never-occupied vregs to [0,0)
+__global__ void k_seg_off(MIRS) {
+  const DevMir &m = *mirs[blockIdx.y];
+  DevLive &L = lives[blockIdx.y];
+  const uint32_t v = blockIdx.x * blockDim.x + threadIdx.x;
+  if (v > m.V) return;
+  L.seg_off[v] = L.ent_seg[v < m.V ? L.vcnt[v] : m.O];
+  if (v < m.V && L.hull[2 * v + 1] == 0) L.hull[2 * v] = 0;
 }
 
 // ---- 5c. tile live-ins ------------------------------------------------------------------
 // Tile t starts at instruction t * tile_len.  Its seed is live_before of that instruction:
 // v is in it iff the first mention of v at or after the tile start, within the block,
-// reads v, or (no such mention) v is in the block's live-out.
+// reads v, or (no such mention) v is in the block's live-out.  One lane per vreg looks
+// only at the tile starts between its first and last point of interest: a value live
+// before `at` is occupied at `at` or at `at - 1`, or is read (and dies) at `at` itself,
+// so `at` lies within the hull widened to the first and last mention.
 template <bool kFill>
 __global__ void k_seed(MIRS) {
-  const DevMir &m = *mirs[blockIdx.z];
-  DevLive &L = lives[blockIdx.z];
-  const uint32_t t = blockIdx.y + 1, v = blockIdx.x * blockDim.x + threadIdx.x;
-  if (t >= L.T || v >= m.V) return;
-  const uint32_t at = t * L.tile_len, b = m.instr_blk[at];
+  const DevMir &m = *mirs[blockIdx.y];
+  DevLive &L = lives[blockIdx.y];
+  const uint32_t v = blockIdx.x * blockDim.x + threadIdx.x;
+  if (v >= m.V) return;
   const uint32_t lo = L.vcnt[v], hi = L.vcnt[v + 1];
+  const uint32_t h0 = L.hull[2 * v], h1 = L.hull[2 * v + 1];
   if (lo == hi) return;
-  const uint32_t x = lower_bound(L.ent_instr, lo, hi, at);
-  bool live;
-  if (x < hi && L.ent_instr[x] < m.blk_start[b + 1]) live = (L.ent_info[x] & kEntHasUse) != 0;
-  else live = bit_get(L.live_out + (size_t)b * m.W, v);
-  if (!live) return;
-  if (!kFill) { atomicAdd(&L.seed_off[t], 1u); return; }
-  const uint32_t src = x > lo ? L.vocc[x - 1] : L.vocc[x];
-  const uint32_t pos = L.seed_off[t] + atomicAdd(&L.seed_cur[t], 1u);
-  L.seeds[pos] = make_uint2(src | ((kPlanBirth | kPlanPost) << 24), 0xFFFFu | (m.vattr[v] << 16));
-  if (L.dense) atomicOr(&L.tile_live[(size_t)t * m.W + (v >> 5)], 1u << (v & 31));
+  const uint32_t r0 = h1 > h0 ? min(h0, L.ent_instr[lo]) : L.ent_instr[lo];
+  const uint32_t r1 = h1 > h0 ? max(h1, L.ent_instr[hi - 1]) : L.ent_instr[hi - 1];
+  // tile starts `at` with r0 <= at <= r1 (tile 0 starts with nothing live)
+  for (uint32_t t = max(1u, (r0 + L.tile_len - 1) / L.tile_len); t < L.T && t * L.tile_len <= r1; ++t) {
+    const uint32_t at = t * L.tile_len, b = m.instr_blk[at];
+    const uint32_t x = lower_bound(L.ent_instr, lo, hi, at);
+    bool live;
+    if (x < hi && L.ent_instr[x] < m.blk_start[b + 1]) live = (L.ent_info[x] & kEntHasUse) != 0;
+    else live = bit_get(L.live_out + (size_t)b * m.W, v);
+    if (!live) continue;
+    if (!kFill) { atomicAdd(&L.seed_off[t], 1u); continue; }
+    const uint32_t src = x > lo ? L.vocc[x - 1] : L.vocc[x];
+    const uint32_t pos = L.seed_off[t] + atomicAdd(&L.seed_cur[t], 1u);
+    L.seeds[pos] = make_uint2(src | ((kPlanBirth | kPlanPost) << 24), 0xFFFFu | (m.vattr[v] << 16));
+    if (L.dense) atomicOr(&L.tile_live[(size_t)t * m.W + (v >> 5)], 1u << (v & 31));
+  }
 }
 
 __global__ void k_collect(MIRS, uint32_t n) {
@@ -468,7 +581,7 @@ __global__ void k_collect(MIRS, uint32_t n) {
   const DevMir &m = *mirs[k];
   DevLive &L = lives[k];
   L.counters[kCtrPlanLen] = L.item_off[m.N + m.B];
-  L.counters[kCtrSeg] = L.seg_off[m.V];
+  L.counters[kCtrSeg] = L.ent_seg[m.O];
   L.counters[kCtrSeed] = L.seed_off[L.T];
 }
 
@@ -619,8 +732,8 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
 
   // ---- arena 1 layout: [zeroed zone | counters | rest | device tables] ----
   std::vector<DevLive> h(n);
-  struct Off1 { size_t vcnt, vcur, use, def, in, seed_off, seed_cur, out, tmp, vocc, ent_instr, ent_info, first, prev,
-                role, kill, item, seg_off, hull, queue, bitmap; };
+  struct Off1 { size_t vcnt, vcur, use, def, in, seed_off, seed_cur, blk_live, out, tmp, vocc, ent_instr, ent_info, first, prev,
+                role, kill, item, seg_off, hull, queue, bitmap, ent_seg; };
   std::vector<Off1> off(n);
   Bump bump;
   uint32_t maxO = 1, maxV = 1, maxN = 1, maxB = 1, maxW = 1, maxT = 1;
@@ -634,6 +747,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     off[k].vcur = bump.take((size_t)(m.V + 1) * 4);
     off[k].use = bump.take(bw); off[k].def = bump.take(bw); off[k].in = bump.take(bw);
     off[k].seed_off = bump.take((size_t)(T + 1) * 4); off[k].seed_cur = bump.take((size_t)(T + 1) * 4);
+    off[k].blk_live = bump.take((size_t)(m.V + 1) * ((m.B + 31) / 32) * 4);
     maxO = std::max(maxO, m.O); maxV = std::max(maxV, m.V); maxN = std::max(maxN, m.N);
     maxB = std::max(maxB, m.B); maxW = std::max(maxW, m.W); maxT = std::max(maxT, T);
   }
@@ -649,6 +763,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     off[k].item = bump.take((size_t)(m.N + m.B + 1) * 4);
     off[k].seg_off = bump.take((size_t)(m.V + 1) * 4); off[k].hull = bump.take((size_t)(m.V + 1) * 8);
     off[k].queue = bump.take((size_t)(m.V + 1) * 4);
+    off[k].ent_seg = bump.take((O1 + 1) * 4);
     off[k].bitmap = 0;
   }
   const size_t o_mirs = bump.take((size_t)n * sizeof(DevMir *));
@@ -667,12 +782,14 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     L.use = (uint32_t *)(a1 + off[k].use); L.def = (uint32_t *)(a1 + off[k].def);
     L.live_in = (uint32_t *)(a1 + off[k].in); L.live_out = (uint32_t *)(a1 + off[k].out);
     L.seed_off = (uint32_t *)(a1 + off[k].seed_off); L.seed_cur = (uint32_t *)(a1 + off[k].seed_cur);
+    L.blk_live = (uint32_t *)(a1 + off[k].blk_live);
     L.vocc_tmp = (uint32_t *)(a1 + off[k].tmp); L.vocc = (uint32_t *)(a1 + off[k].vocc);
     L.ent_instr = (uint32_t *)(a1 + off[k].ent_instr); L.ent_info = (uint8_t *)(a1 + off[k].ent_info);
     L.first = (uint32_t *)(a1 + off[k].first); L.prev_occ = (uint32_t *)(a1 + off[k].prev);
     L.occ_role = (uint8_t *)(a1 + off[k].role); L.occ_kill = (uint8_t *)(a1 + off[k].kill);
     L.item_off = (uint32_t *)(a1 + off[k].item); L.seg_off = (uint32_t *)(a1 + off[k].seg_off);
     L.hull = (uint32_t *)(a1 + off[k].hull); L.long_queue = (uint32_t *)(a1 + off[k].queue);
+    L.ent_seg = (uint32_t *)(a1 + off[k].ent_seg);
     L.bitmap = nullptr;
     L.counters = (uint32_t *)(a1 + o_counters) + (size_t)k * kCounters;
     mir_ptrs[k] = mirs[k]->dev;
@@ -690,9 +807,19 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
   const DevMir *const *dm = batch->dev_mirs;
   DevLive *dl = batch->dev_lives;
   const uint32_t TB = 256;
-  k_count<<<grid1(maxO, TB, n), TB, 0, stream>>>(dm, dl);
+  // LDS histograms over the vregs when they fit (4 bytes per vreg to count, 8 to place)
+  static const bool lds_ok = [] {
+    hipError_t a = hipFuncSetAttribute((const void *)k_count<true>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+    hipError_t b = hipFuncSetAttribute((const void *)k_place<true>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+    return a == hipSuccess && b == hipSuccess;
+  }();
+  const bool hist_lds = lds_ok && (size_t)maxV * 8 <= 128 * 1024;
+  const dim3 slices((maxO + kSlice - 1) / kSlice, n);
+  if (hist_lds) k_count<true><<<slices, 1024, (size_t)maxV * 4, stream>>>(dm, dl);
+  else k_count<false><<<slices, 1024, 0, stream>>>(dm, dl);
   k_scan<kScanVreg><<<n, 1024, 0, stream>>>(dm, dl);
-  k_place<<<grid1(maxO, TB, n), TB, 0, stream>>>(dm, dl);
+  if (hist_lds) k_place<true><<<slices, 1024, (size_t)maxV * 8, stream>>>(dm, dl);
+  else k_place<false><<<slices, 1024, 0, stream>>>(dm, dl);
   k_sort_short<<<grid1(maxV, TB, n), TB, 0, stream>>>(dm, dl);
   k_sort_long<<<dim3(32, n), 256, 0, stream>>>(dm, dl);
   k_ent<<<grid1(maxO, TB, n), TB, 0, stream>>>(dm, dl);
@@ -706,9 +833,11 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
   k_item_count<<<grid1(maxN, TB, n), TB, 0, stream>>>(dm, dl);
   k_boundary<false><<<dim3(maxB, n), 64, 0, stream>>>(dm, dl);
   k_scan<kScanItems><<<n, 1024, 0, stream>>>(dm, dl);
-  k_seg<false><<<grid1(maxV, TB, n), TB, 0, stream>>>(dm, dl);
+  k_blk_transpose<<<dim3((maxW + 63) / 64, maxB, n), 64, 0, stream>>>(dm, dl);
+  k_seg<false><<<grid1(maxO, TB, n), TB, 0, stream>>>(dm, dl);
   k_scan<kScanSeg><<<n, 1024, 0, stream>>>(dm, dl);
-  if (maxT > 1) k_seed<false><<<dim3((maxV + TB - 1) / TB, maxT - 1, n), TB, 0, stream>>>(dm, dl);
+  k_seg_off<<<grid1(maxV + 1, TB, n), TB, 0, stream>>>(dm, dl);
+  if (maxT > 1) k_seed<false><<<grid1(maxV, TB, n), TB, 0, stream>>>(dm, dl);
   k_scan<kScanSeed><<<n, 1024, 0, stream>>>(dm, dl);
   k_collect<<<(n + 63) / 64, 64, 0, stream>>>(dm, dl, n);
   e = hipGetLastError();
@@ -760,8 +889,8 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
   if (e != hipSuccess) return fail(hip_fail(e));
   k_plan_fill<<<grid1(maxN, TB, n), TB, 0, stream>>>(dm, dl);
   k_boundary<true><<<dim3(maxB, n), 64, 0, stream>>>(dm, dl);
-  k_seg<true><<<grid1(maxV, TB, n), TB, 0, stream>>>(dm, dl);
-  if (maxT > 1) k_seed<true><<<dim3((maxV + TB - 1) / TB, maxT - 1, n), TB, 0, stream>>>(dm, dl);
+  k_seg<true><<<grid1(maxO, TB, n), TB, 0, stream>>>(dm, dl);
+  if (maxT > 1) k_seed<true><<<grid1(maxV, TB, n), TB, 0, stream>>>(dm, dl);
   k_tile_range<<<grid1(maxT, 64, n), 64, 0, stream>>>(dm, dl);
   if (dense) {
     k_dense_delta<<<grid1(maxN + maxB, TB, n), TB, 0, stream>>>(dm, dl);
