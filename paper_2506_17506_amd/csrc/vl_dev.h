@@ -42,21 +42,23 @@ __host__ __device__ inline uint32_t attr_width(uint32_t a) { return ((a >> 3) & 
 __host__ __device__ inline uint32_t attr_align(uint32_t a) { return ((a >> 8) & 31u) + 1u; }
 __host__ __device__ inline uint32_t attr_straddle(uint32_t a) { return (a >> 13) & 1u; }
 
-// Event-stream ("plan") entry, 8 bytes:
+// The verifier reads two streams of 8-byte entries
 //   x: occurrence index (24 bits) | flags << 24
 //   y: distance to the previous occurrence of the same vreg (16 bits, saturated)
 //      | packed attributes << 16
-// The verifier processes entries in order.  For each instruction the entries
-// of operands that are only read come first, then those that are written,
-// then the post-instruction kills; entries of a block boundary (values that
-// stop / start being live between two blocks adjacent in the linear order)
-// precede the first instruction of the later block.
+// "chk": one entry per occurrence, in occurrence order (kPlanChk or kPlanFirst).
+// "plan": the occupancy events in the order they take effect.  For each instruction:
+// releases of operands that die there, then test-and-occupy of the values it writes,
+// then releases of values dead once it has executed; the events of a block boundary
+// (values that stop / start being live between two blocks adjacent in the linear order)
+// precede those of the later block's first instruction.  x names the occurrence that
+// carries the register.
 constexpr uint32_t kPlanChk = 1u;    // compare with the previous occurrence of the vreg
 constexpr uint32_t kPlanFirst = 2u;  // first occurrence of the vreg: realizability check
 constexpr uint32_t kPlanSet = 4u;    // test the range against occupancy, then occupy it
 constexpr uint32_t kPlanClr = 8u;    // release the range
 constexpr uint32_t kPlanBirth = 16u; // occupy without testing (value becomes live at a boundary)
-constexpr uint32_t kPlanPost = 32u;  // entry repeats an occurrence already checked (no chk/first)
+constexpr uint32_t kPlanPost = 32u;  // the occurrence named is not at the event's own position
 
 // Per-occurrence roles computed by the event kernel.
 constexpr uint8_t kRolePreKill = 1, kRoleTestSet = 2, kRolePostKill = 4, kRoleFirst = 8;
@@ -80,6 +82,8 @@ struct DevLive {
   uint32_t *item_off;   // [N+B+1] plan offset of each item (boundary b at blk_start[b]+b,
                         //          instruction i of block b at i+b+1)
   uint32_t *seg_off;    // [V+1]
+  uint2 *chk;           // [O] check stream
+  uint32_t *evt_cut;    // [ceil(O/64)+1] first event replayable once chunk c is staged
   uint32_t *ent_seg;    // [O+1] runs starting in each mention group's stretch -> prefix sums
   uint32_t *hull;       // [V][2]
   uint32_t *seed_off;   // [T+1]
@@ -89,7 +93,7 @@ struct DevLive {
   uint32_t *bitmap;     // [ceil(O/32)] scratch for the bitmap sort, one list at a time per block
   uint32_t *counters;   // [kCounters]
   // --- sized after the counting pass ---
-  uint2 *plan;          // [plan_len]
+  uint2 *plan;          // [plan_len] occupancy events
   uint2 *seeds;         // [n_seed]
   uint32_t *seg;        // [n_seg][2]
   uint32_t *tile_range; // [T][2] plan range of each tile
@@ -97,6 +101,17 @@ struct DevLive {
   uint32_t *live_after; // [N][W] (dense mode)
   uint32_t T, tile_len, plan_len, n_seg, n_seed, dense;
 };
+
+// Pointers read out of device structures are generic to the compiler; these casts tell
+// it they point to global memory, so that loads become global / scalar loads instead of
+// flat ones.
+#define VL_GLOBAL __attribute__((address_space(1)))
+template <class T> __device__ inline const T VL_GLOBAL *as_global(const T *p) {
+  return (const T VL_GLOBAL *)p;
+}
+template <class T> __device__ inline T VL_GLOBAL *as_global_rw(T *p) {
+  return (T VL_GLOBAL *)p;
+}
 
 enum { kCtrLong = 0, kCtrNotStrict = 1, kCtrSweeps = 2, kCtrPlanLen = 3, kCtrSeg = 4, kCtrSeed = 5,
        kCounters = 8 };

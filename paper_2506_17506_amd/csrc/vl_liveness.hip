@@ -368,8 +368,9 @@ __global__ void k_item_count(MIRS) {
   DevLive &L = lives[blockIdx.y];
   uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= m.N) return;
-  uint32_t cnt = m.occ_off[i + 1] - m.occ_off[i];
-  for (uint32_t o = m.occ_off[i]; o < m.occ_off[i + 1]; ++o) cnt += (L.occ_role[o] & kRolePostKill) ? 1u : 0u;
+  uint32_t cnt = 0;
+  for (uint32_t o = m.occ_off[i]; o < m.occ_off[i + 1]; ++o)
+    cnt += __popc(L.occ_role[o] & (kRolePreKill | kRoleTestSet | kRolePostKill));
   L.item_off[item_of_instr(m, i)] = cnt;
 }
 
@@ -427,6 +428,9 @@ __global__ __launch_bounds__(64) void k_boundary(MIRS) {
   if (!kFill && lane == 0) L.item_off[item] = total;
 }
 
+// Occupancy events of each instruction, in the order they take effect: releases of
+// operands that die here, then test-and-occupy of the values written, then releases of
+// values that are dead once the instruction has executed.
 __global__ void k_plan_fill(MIRS) {
   const DevMir &m = *mirs[blockIdx.y];
   DevLive &L = lives[blockIdx.y];
@@ -435,25 +439,50 @@ __global__ void k_plan_fill(MIRS) {
   uint32_t pos = L.item_off[item_of_instr(m, i)];
   const uint32_t o0 = m.occ_off[i], o1 = m.occ_off[i + 1];
   auto entry = [&](uint32_t o, uint32_t flags) {
-    const uint32_t v = m.occ_vreg[o], prev = L.prev_occ[o];
-    uint32_t delta = prev == kNone ? 0u : min(o - prev, 0xFFFFu);
-    return make_uint2(o | (flags << 24), delta | (m.vattr[v] << 16));
+    return make_uint2(o | (flags << 24), 0xFFFFu | (m.vattr[m.occ_vreg[o]] << 16));
   };
-  auto base_flags = [&](uint32_t o) {
-    const uint8_t role = L.occ_role[o];
-    uint32_t f = (role & kRoleFirst) ? kPlanFirst : kPlanChk;
-    if (role & kRolePreKill) f |= kPlanClr;
-    if (role & kRoleTestSet) f |= kPlanSet;
-    return f;
-  };
-  // operands that are only read, then operands that are written, then releases of
-  // values that are dead once the instruction has executed
   for (uint32_t o = o0; o < o1; ++o)
-    if (!(m.occ_flags[o] & VL_OCC_DEF)) L.plan[pos++] = entry(o, base_flags(o));
+    if (L.occ_role[o] & kRolePreKill) L.plan[pos++] = entry(o, kPlanClr);
   for (uint32_t o = o0; o < o1; ++o)
-    if (m.occ_flags[o] & VL_OCC_DEF) L.plan[pos++] = entry(o, base_flags(o));
+    if (L.occ_role[o] & kRoleTestSet) L.plan[pos++] = entry(o, kPlanSet);
   for (uint32_t o = o0; o < o1; ++o)
     if (L.occ_role[o] & kRolePostKill) L.plan[pos++] = entry(o, kPlanClr | kPlanPost);
+}
+
+// The check stream has one entry per occurrence, in occurrence order: compare with the
+// previous occurrence of the vreg, or (first occurrence) test realizability.
+__global__ void k_chk_fill(MIRS) {
+  const DevMir &m = *mirs[blockIdx.y];
+  DevLive &L = lives[blockIdx.y];
+  uint32_t o = blockIdx.x * blockDim.x + threadIdx.x;
+  if (o >= m.O) return;
+  const uint32_t prev = L.prev_occ[o];
+  const uint32_t delta = prev == kNone ? 0u : min(o - prev, 0xFFFFu);
+  const uint32_t flags = (L.occ_role[o] & kRoleFirst) ? kPlanFirst : kPlanChk;
+  L.chk[o] = make_uint2(o | (flags << 24), delta | (m.vattr[m.occ_vreg[o]] << 16));
+}
+
+// evt_cut[c] = index of the first event of the first item whose operands end in chunk c or
+// later (an item's events may be replayed once occurrences [0, 64 (c + 1)) are staged).
+__global__ void k_evt_cut(MIRS) {
+  const DevMir &m = *mirs[blockIdx.y];
+  DevLive &L = lives[blockIdx.y];
+  const uint32_t c = blockIdx.x * blockDim.x + threadIdx.x;
+  const uint32_t n_chunk = (m.O + 63) / 64;
+  if (c > n_chunk) return;
+  // first instruction i with occ_off[i + 1] > 64 c
+  uint32_t lo = 0, hi = m.N;
+  while (lo < hi) {
+    const uint32_t mid = (lo + hi) >> 1;
+    if (m.occ_off[mid + 1] > 64 * c) hi = mid; else lo = mid + 1;
+  }
+  uint32_t cut;
+  if (lo >= m.N || c == n_chunk) cut = L.item_off[m.N + m.B];
+  else {
+    const uint32_t b = m.instr_blk[lo];
+    cut = L.item_off[m.blk_start[b] == lo ? lo + b : lo + b + 1];   // boundary events go with their block's first instruction
+  }
+  L.evt_cut[c] = cut;
 }
 
 // ---- 5b. live intervals ---------------------------------------------------------------
@@ -624,7 +653,6 @@ __global__ void k_dense_delta(MIRS) {
   if (q == m.blk_start[b] + b && row % L.tile_len == 0) return;
   for (uint32_t e = L.item_off[q]; e < L.item_off[q + 1]; ++e) {
     const uint2 ent = L.plan[e];
-    if (!((ent.x >> 24) & (kPlanSet | kPlanClr | kPlanBirth))) continue;
     const uint32_t v = m.occ_vreg[ent.x & 0xFFFFFFu];
     atomicXor(&L.live_after[(size_t)row * m.W + (v >> 5)], 1u << (v & 31));
   }
@@ -733,7 +761,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
   // ---- arena 1 layout: [zeroed zone | counters | rest | device tables] ----
   std::vector<DevLive> h(n);
   struct Off1 { size_t vcnt, vcur, use, def, in, seed_off, seed_cur, blk_live, out, tmp, vocc, ent_instr, ent_info, first, prev,
-                role, kill, item, seg_off, hull, queue, bitmap, ent_seg; };
+                role, kill, item, seg_off, hull, queue, bitmap, ent_seg, chk, evt_cut; };
   std::vector<Off1> off(n);
   Bump bump;
   uint32_t maxO = 1, maxV = 1, maxN = 1, maxB = 1, maxW = 1, maxT = 1;
@@ -764,6 +792,8 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     off[k].seg_off = bump.take((size_t)(m.V + 1) * 4); off[k].hull = bump.take((size_t)(m.V + 1) * 8);
     off[k].queue = bump.take((size_t)(m.V + 1) * 4);
     off[k].ent_seg = bump.take((O1 + 1) * 4);
+    off[k].chk = bump.take(O1 * 8);
+    off[k].evt_cut = bump.take(((size_t)(m.O + 63) / 64 + 2) * 4);
     off[k].bitmap = 0;
   }
   const size_t o_mirs = bump.take((size_t)n * sizeof(DevMir *));
@@ -790,6 +820,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     L.item_off = (uint32_t *)(a1 + off[k].item); L.seg_off = (uint32_t *)(a1 + off[k].seg_off);
     L.hull = (uint32_t *)(a1 + off[k].hull); L.long_queue = (uint32_t *)(a1 + off[k].queue);
     L.ent_seg = (uint32_t *)(a1 + off[k].ent_seg);
+    L.chk = (uint2 *)(a1 + off[k].chk); L.evt_cut = (uint32_t *)(a1 + off[k].evt_cut);
     L.bitmap = nullptr;
     L.counters = (uint32_t *)(a1 + o_counters) + (size_t)k * kCounters;
     mir_ptrs[k] = mirs[k]->dev;
@@ -833,6 +864,8 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
   k_item_count<<<grid1(maxN, TB, n), TB, 0, stream>>>(dm, dl);
   k_boundary<false><<<dim3(maxB, n), 64, 0, stream>>>(dm, dl);
   k_scan<kScanItems><<<n, 1024, 0, stream>>>(dm, dl);
+  k_evt_cut<<<grid1(maxO / 64 + 2, TB, n), TB, 0, stream>>>(dm, dl);
+  k_chk_fill<<<grid1(maxO, TB, n), TB, 0, stream>>>(dm, dl);
   k_blk_transpose<<<dim3((maxW + 63) / 64, maxB, n), 64, 0, stream>>>(dm, dl);
   k_seg<false><<<grid1(maxO, TB, n), TB, 0, stream>>>(dm, dl);
   k_scan<kScanSeg><<<n, 1024, 0, stream>>>(dm, dl);
@@ -934,7 +967,8 @@ extern "C" int32_t vl_live_get(const vl_live *l, vl_live_view *v) {
   if (l->magic != kLiveMagic) return VL_E_ARG;
   const DevMir &m = l->mir->h;
   v->n_instr = m.N; v->n_vreg = m.V; v->n_block = m.B; v->n_occ = m.O; v->words = m.W;
-  v->n_seg = l->h.n_seg; v->n_tile = l->h.T; v->tile_len = l->h.tile_len; v->plan_len = l->h.plan_len;
+  v->n_seg = l->h.n_seg; v->n_tile = l->h.T; v->tile_len = l->h.tile_len;
+  v->plan_len = l->h.plan_len + m.O;   // occupancy events + one check per occurrence
   v->sweeps = l->batch->host_counters[(size_t)l->index * kCounters + kCtrSweeps];
   v->live_in = l->h.live_in; v->live_out = l->h.live_out; v->live_after = l->h.live_after;
   v->occ_kill = l->h.occ_kill; v->seg_off = l->h.seg_off; v->seg = l->h.seg; v->hull = l->h.hull;

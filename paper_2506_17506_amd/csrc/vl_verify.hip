@@ -59,17 +59,29 @@ __global__ void k_init(const DevJob *__restrict__ jobs) {
 }
 
 // ---- the candidate walk -----------------------------------------------------------------
-// Workgroup = 4 wavefronts over the same 64 candidate rows and the same tile.  All four
-// stage row chunks into one LDS ring (the next chunk is already on its way from memory
-// while the current one is processed); one wavefront replays the occupancy events (the
-// sequential part), the other three share the consistency and realizability checks,
-// which are independent per entry.  Lanes beyond the last row mirror row 0 and never
-// report.
+// A workgroup of 4 wavefronts takes up to 64 candidate rows of one kernel over one tile
+// (a range of instructions).  Occurrences are staged 64 at a time (one 128-byte line per
+// row, the next chunk already in flight) into an LDS ring [row][256 occurrences].  After
+// each chunk
+//   * one wavefront replays the occupancy events that chunk releases, one candidate per
+//     lane, the lane's occupancy mask in LDS as [word][lane];
+//   * three wavefronts run the chunk's 64 consistency / realizability checks with one
+//     check per lane, looping over their share of the rows: what is uniform per check
+//     (ring offsets, class limits) is then computed once per lane instead of once per
+//     check and candidate.
+// Violations go to a per-row key in LDS (smallest wins) and from there to the result slot.
+// LDS layout (indices into the dynamic shared array, kept as integers so that every
+// access is a DS instruction rather than a flat one):
+//   [0, occ_words * 64)            occupancy masks [word][lane]
+//   [keys, keys + 64)              per-row violation keys
+//   [ring32, ...)                  the ring, addressed in uint16 from ring16 = 2 * ring32
+extern __shared__ uint32_t vl_lds[];
+#define VL_LDS16 (reinterpret_cast<uint16_t *>(vl_lds))
+
 struct Walk {
-  const uint16_t *rows;   // first row of the group
+  const uint16_t VL_GLOBAL *rows;   // first row of the group
   uint64_t ld;
-  uint16_t *ring;         // LDS [64][kRingStride]
-  uint32_t *occw;         // LDS [occ_words][64]
+  uint32_t keys, ring16;  // LDS indices
   uint32_t tid, lane, row, nrows, n_occ, staged_lo, staged_hi, fast;
   uint32_t pre[2][4];     // the chunk after staged_hi, in flight
 };
@@ -83,9 +95,10 @@ __device__ inline void load_chunk(Walk &w, uint32_t c0) {
     const uint32_t r = h * 32 + (w.tid >> 3);
     w.pre[h][0] = w.pre[h][1] = w.pre[h][2] = w.pre[h][3] = 0;
     if (r < w.nrows && c < w.n_occ) {
-      const uint16_t *src = w.rows + (uint64_t)r * w.ld + c;
+      const uint16_t VL_GLOBAL *src = w.rows + (uint64_t)r * w.ld + c;
       if (w.fast && c + 8u <= w.n_occ) {
-        const uint4 x = *reinterpret_cast<const uint4 *>(src);
+        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+        const u32x4 x = *reinterpret_cast<const u32x4 VL_GLOBAL *>(src);
         w.pre[h][0] = x.x; w.pre[h][1] = x.y; w.pre[h][2] = x.z; w.pre[h][3] = x.w;
       } else {
         for (int j = 0; j < 4; ++j) {
@@ -104,16 +117,19 @@ __device__ inline void store_chunk(Walk &w) {
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     const uint32_t r = h * 32 + (w.tid >> 3);
-    uint32_t *dst = reinterpret_cast<uint32_t *>(w.ring + (size_t)r * kRingStride + (c & (kRing - 1)));
-    dst[0] = w.pre[h][0]; dst[1] = w.pre[h][1]; dst[2] = w.pre[h][2]; dst[3] = w.pre[h][3];
+    const uint32_t dst = (w.ring16 + r * kRingStride + (c & (kRing - 1))) >> 1;   // even: a dword index
+    vl_lds[dst] = w.pre[h][0]; vl_lds[dst + 1] = w.pre[h][1]; vl_lds[dst + 2] = w.pre[h][2]; vl_lds[dst + 3] = w.pre[h][3];
   }
   w.staged_hi += kChunk;
 }
 
+__device__ inline bool in_ring(const Walk &w, uint32_t o) {
+  return o < w.staged_hi && o + kRing >= w.staged_hi && o >= w.staged_lo;
+}
+
 // value of occurrence o (uniform) in this lane's row
 __device__ inline uint32_t fetch(const Walk &w, uint32_t o) {
-  if (o < w.staged_hi && o + kRing >= w.staged_hi && o >= w.staged_lo)
-    return w.ring[(size_t)w.row * kRingStride + (o & (kRing - 1))];
+  if (in_ring(w, o)) return VL_LDS16[w.ring16 + w.row * kRingStride + (o & (kRing - 1))];
   return w.rows[(uint64_t)w.row * w.ld + o];
 }
 
@@ -121,7 +137,7 @@ __device__ inline uint32_t fetch(const Walk &w, uint32_t o) {
 // The word index is clamped to the class, so a base outside the file cannot leave the
 // mask; such a base is reported as unrealizable (or inconsistent), which outranks
 // whatever the occupancy test says.
-struct Touch { uint32_t *addr; uint32_t mlo, mhi; };
+struct Touch { uint32_t addr; uint32_t mlo, mhi; };   // addr: index into the LDS array
 __device__ inline Touch locate(const Walk &w, uint32_t attr, uint32_t cls_tab, uint32_t p) {
   const uint32_t width = attr_width(attr);
   const uint32_t F = cls_tab & 0xFFFFu, wbase = cls_tab >> 16;
@@ -129,7 +145,7 @@ __device__ inline Touch locate(const Walk &w, uint32_t attr, uint32_t cls_tab, u
   const uint32_t word = min(p >> 5, last_word), bitpos = p & 31u;
   const uint32_t wm = width == 32 ? 0xFFFFFFFFu : ((1u << width) - 1u);
   Touch t;
-  t.addr = w.occw + (size_t)(wbase + word) * 64 + w.lane;
+  t.addr = (wbase + word) * 64 + w.lane;
   if (!attr_straddle(attr)) { t.mlo = wm << bitpos; t.mhi = 0; }
   else {
     const uint64_t m64 = (uint64_t)wm << bitpos;
@@ -143,12 +159,12 @@ __device__ inline Touch locate(const Walk &w, uint32_t attr, uint32_t cls_tab, u
 // bits are both an exclusive-or, exact up to the first clash, which is all that is
 // reported.  Returns the bits that were already set (meaningful for occupy-with-test).
 __device__ inline uint32_t flip(const Touch &t, bool straddle) {
-  uint32_t hit = __hip_atomic_fetch_xor(t.addr, t.mlo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT) & t.mlo;
-  if (straddle) hit |= __hip_atomic_fetch_xor(t.addr + 64, t.mhi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT) & t.mhi;
+  uint32_t hit = __hip_atomic_fetch_xor(&vl_lds[t.addr], t.mlo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT) & t.mlo;
+  if (straddle) hit |= __hip_atomic_fetch_xor(&vl_lds[t.addr + 64], t.mhi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT) & t.mhi;
   return hit;
 }
 
-__device__ inline bool unrealizable(const DevMir &m, uint32_t attr, uint32_t F, uint32_t p) {
+__device__ inline bool unrealizable(const DevMir VL_GLOBAL &m, uint32_t attr, uint32_t F, uint32_t p) {
   const uint32_t cls = attr_class(attr), width = attr_width(attr), align = attr_align(attr);
   bool bad = p + width > F;
   bad |= (align & (align - 1)) ? (p % align != 0) : ((p & (align - 1)) != 0);
@@ -160,10 +176,17 @@ __device__ inline bool unrealizable(const DevMir &m, uint32_t attr, uint32_t F, 
 }
 
 __global__ __launch_bounds__(256) void k_walk(const DevJob *__restrict__ jobs, uint32_t n_jobs) {
-  extern __shared__ uint32_t sm[];
-  const DevJob &J = jobs[find_job(jobs, n_jobs, blockIdx.x)];
-  const DevMir &m = *J.mir;
-  const DevLive &L = *J.live;
+  const DevJob VL_GLOBAL &J = as_global(jobs)[find_job(jobs, n_jobs, blockIdx.x)];
+  const DevMir VL_GLOBAL &m = *as_global(J.mir);
+  const DevLive VL_GLOBAL &L = *as_global(J.live);
+  // arrays of the kernel and of its analysis, as global pointers
+  const auto g_occ_off = as_global(m.occ_off), g_occ_instr = as_global(m.occ_instr);
+  const auto g_prev_occ = as_global(L.prev_occ), g_evt_cut = as_global(L.evt_cut);
+  const auto g_seed_off = as_global(L.seed_off), g_tile_range = as_global(L.tile_range);
+  // 8-byte stream entries are read as one 64-bit word: x in the low half, y in the high half
+  const auto g_chk = as_global((const uint64_t *)L.chk), g_plan = as_global((const uint64_t *)L.plan),
+             g_seeds = as_global((const uint64_t *)L.seeds);
+  const uint32_t has_reserved = m.has_reserved;
   const uint32_t local = blockIdx.x - J.unit_base;
   const uint32_t tile = local / J.n_groups, group = local % J.n_groups;
   const uint32_t row0 = group * J.rows;
@@ -176,62 +199,48 @@ __global__ __launch_bounds__(256) void k_walk(const DevJob *__restrict__ jobs, u
   w.nrows = min(J.rows, J.K - row0);
   const bool active = w.lane < w.nrows;
   w.row = active ? w.lane : 0u;
-  w.rows = J.cand + (uint64_t)row0 * J.ld;
+  w.rows = as_global(J.cand) + (uint64_t)row0 * J.ld;
   w.ld = J.ld;
   w.n_occ = m.O;
   w.fast = J.fast;
-  w.occw = sm;
-  w.ring = reinterpret_cast<uint16_t *>(sm + (size_t)m.occ_words * 64);
-  for (uint32_t x = w.tid; x < m.occ_words * 64; x += 256) w.occw[x] = 0;
-  // per-class file size and first mask word, one class per lane, read back with readlane
+  w.keys = m.occ_words * 64;
+  w.ring16 = (w.keys + 64) * 2;
+  for (uint32_t x = w.tid; x < m.occ_words * 64; x += 256) vl_lds[x] = 0;
+  if (w.tid < 64) vl_lds[w.keys + w.tid] = kKeyOk;
+  // per-class file size and first mask word, one class per lane, read back by lane index
   const uint32_t cls_tab_v = w.lane < m.C ? ((uint32_t)m.class_size[w.lane] | ((uint32_t)m.class_word[w.lane] << 16)) : 0u;
-  uint32_t key = kKeyOk;
+  uint32_t key = kKeyOk;   // event role and far checks: this lane's row
 
+  const uint32_t i0 = tile * L.tile_len, i1 = min(m.N, i0 + L.tile_len);
+  const uint32_t oa = g_occ_off[i0], ob = g_occ_off[i1];      // the tile's occurrences
+  const uint32_t ea = g_tile_range[2 * tile], eb = g_tile_range[2 * tile + 1];   // its events
+  const uint32_t ca = oa / kChunk;
+  const uint32_t c_end = ob > oa ? (ob - 1) / kChunk + 1 : ca;   // chunks [ca, c_end)
   // start two chunks before the tile's first occurrence, so that nearby history is in LDS
-  const uint32_t o_first = m.occ_off[tile * L.tile_len];
-  const uint32_t c0 = (o_first / kChunk) > 2 ? (o_first / kChunk) - 2 : 0;
+  const uint32_t c0 = ca > 2 ? ca - 2 : 0;
   w.staged_lo = w.staged_hi = c0 * kChunk;
   load_chunk(w, w.staged_hi);
-  while (w.staged_hi <= o_first && w.staged_hi < w.n_occ) {
+  while (w.staged_hi < ca * kChunk) {
     store_chunk(w);
     load_chunk(w, w.staged_hi);
   }
   __syncthreads();
 
-  auto in_ring = [&](uint32_t o) { return o < w.staged_hi && o + kRing >= w.staged_hi && o >= w.staged_lo; };
-  const uint16_t *my_ring = w.ring + (size_t)w.row * kRingStride;
-
-  // one entry at a time: any source (ring or global memory)
-  auto safety1 = [&](uint32_t ex, uint32_t ey) {
+  // ---- occupancy events (lane = candidate) ----
+  auto event1 = [&](uint32_t ex, uint32_t ey) __attribute__((always_inline)) {   // any source: ring or global memory
     const uint32_t o = ex & 0xFFFFFFu, fl = ex >> 24, attr = ey >> 16;
     const uint32_t p = fetch(w, o);
     const Touch t = locate(w, attr, __builtin_amdgcn_readlane(cls_tab_v, attr_class(attr)), p);
-    const uint32_t hit = (fl & kPlanSet) ? flip(t, attr_straddle(attr)) : (flip(t, attr_straddle(attr)), 0u);
+    uint32_t hit = flip(t, attr_straddle(attr));
+    if (!(fl & kPlanSet)) hit = 0;
     if (__any(hit != 0)) {
-      const uint32_t i = m.occ_instr[o];
+      const uint32_t i = g_occ_instr[o];
       if (hit) key = min(key, kKeySafe | i);
     }
   };
-  auto check1 = [&](uint32_t ex, uint32_t ey) {
-    const uint32_t o = ex & 0xFFFFFFu, fl = ex >> 24, attr = ey >> 16;
-    const uint32_t p = fetch(w, o);
-    if (fl & kPlanChk) {
-      const uint32_t delta = ey & 0xFFFFu;
-      const uint32_t prev = delta == 0xFFFFu ? L.prev_occ[o] : o - delta;
-      const uint32_t q = fetch(w, prev);
-      if (__any(p != q)) { if (p != q) key = min(key, kKeyCons | o); }
-    } else {
-      const uint32_t F = __builtin_amdgcn_readlane(cls_tab_v, attr_class(attr)) & 0xFFFFu;
-      const bool bad = unrealizable(m, attr, F, p);
-      if (__any(bad)) { if (bad) key = min(key, kKeyReal | o); }
-    }
-  };
-
-  constexpr int G = 8;   // entries in flight: their LDS reads and atomics overlap
-  // Up to G occupancy events whose registers all come from the ring and cannot cross a
-  // mask word: read the G values, issue the G mask updates back to back (LDS executes
-  // them in order), and only then look at what they returned.
-  auto safety_group = [&](uint64_t &todo, const uint2 ent) {
+  constexpr int G = 8;   // events in flight: their LDS reads and atomics overlap
+  const uint32_t my_ring = w.ring16 + w.row * kRingStride;
+  auto event_group = [&](uint64_t &todo, const uint2 ent) __attribute__((always_inline)) {
     uint32_t ex[G], ey[G];
     int n = 0;
     bool quick = true;
@@ -243,24 +252,24 @@ __global__ __launch_bounds__(256) void k_walk(const DevJob *__restrict__ jobs, u
         todo &= todo - 1;
         ex[t] = __builtin_amdgcn_readlane(ent.x, j);
         ey[t] = __builtin_amdgcn_readlane(ent.y, j);
-        quick = quick && in_ring(ex[t] & 0xFFFFFFu) && !attr_straddle(ey[t] >> 16);
+        quick = quick && in_ring(w, ex[t] & 0xFFFFFFu) && !attr_straddle(ey[t] >> 16);
         n = t + 1;
       }
     }
     if (!quick) {
 #pragma unroll
-      for (int t = 0; t < G; ++t) if (t < n) safety1(ex[t], ey[t]);
+      for (int t = 0; t < G; ++t) if (t < n) event1(ex[t], ey[t]);
       return;
     }
     uint32_t p[G], old[G], msk[G];
 #pragma unroll
-    for (int t = 0; t < G; ++t) p[t] = my_ring[ex[t] & (kRing - 1)];   // unused slots read slot 0
+    for (int t = 0; t < G; ++t) p[t] = VL_LDS16[my_ring + (ex[t] & (kRing - 1))];   // unused slots read slot 0
 #pragma unroll
     for (int t = 0; t < G; ++t) {
       const uint32_t attr = ey[t] >> 16;
       const Touch tc = locate(w, attr, __builtin_amdgcn_readlane(cls_tab_v, attr_class(attr)), p[t]);
       msk[t] = t < n ? tc.mlo : 0u;    // an empty slot flips nothing
-      old[t] = __hip_atomic_fetch_xor(tc.addr, msk[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+      old[t] = __hip_atomic_fetch_xor(&vl_lds[tc.addr], msk[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
     }
     uint32_t any_hit = 0;
 #pragma unroll
@@ -272,94 +281,94 @@ __global__ __launch_bounds__(256) void k_walk(const DevJob *__restrict__ jobs, u
 #pragma unroll
       for (int t = 0; t < G; ++t)
         if (__any(old[t] != 0)) {
-          const uint32_t i = m.occ_instr[ex[t] & 0xFFFFFFu];
+          const uint32_t i = g_occ_instr[ex[t] & 0xFFFFFFu];
           if (old[t]) key = min(key, kKeySafe | i);
         }
     }
   };
-  auto check_group = [&](uint64_t &todo, const uint2 ent) {
-    uint32_t ex[G], ey[G];
-    int n = 0;
-    bool quick = true;
-#pragma unroll
-    for (int t = 0; t < G; ++t) {
-      ex[t] = 0; ey[t] = 0;
-      if (todo) {
-        const uint32_t j = __builtin_ctzll(todo);
-        todo &= todo - 1;
-        ex[t] = __builtin_amdgcn_readlane(ent.x, j);
-        ey[t] = __builtin_amdgcn_readlane(ent.y, j);
-        const uint32_t o = ex[t] & 0xFFFFFFu, delta = ey[t] & 0xFFFFu;
-        quick = quick && in_ring(o);
-        if ((ex[t] >> 24) & kPlanChk) quick = quick && delta != 0xFFFFu && in_ring(o - delta);
-        n = t + 1;
-      }
-    }
-    if (!quick) {
-#pragma unroll
-      for (int t = 0; t < G; ++t) if (t < n) check1(ex[t], ey[t]);
-      return;
-    }
-    uint32_t p[G], q[G];
-#pragma unroll
-    for (int t = 0; t < G; ++t) {
-      const uint32_t o = ex[t] & 0xFFFFFFu;
-      const bool chk = ((ex[t] >> 24) & kPlanChk) != 0;
-      p[t] = my_ring[o & (kRing - 1)];
-      q[t] = my_ring[(chk ? o - (ey[t] & 0xFFFFu) : o) & (kRing - 1)];
-    }
-    bool wrong = false;
-#pragma unroll
-    for (int t = 0; t < G; ++t) {
-      if ((ex[t] >> 24) & kPlanFirst) {
-        const uint32_t attr = ey[t] >> 16;
-        wrong |= unrealizable(m, attr, __builtin_amdgcn_readlane(cls_tab_v, attr_class(attr)) & 0xFFFFu, p[t]);
-      } else {
-        wrong |= p[t] != q[t];   // empty slots compare a value with itself
-      }
-    }
-    if (__any(wrong)) {   // rare: redo the group one entry at a time to attribute it
-#pragma unroll
-      for (int t = 0; t < G; ++t) if (t < n) check1(ex[t], ey[t]);
+  auto events = [&](const uint64_t VL_GLOBAL *stream, uint32_t from, uint32_t to) __attribute__((always_inline)) {
+    for (uint32_t base = from; base < to; base += 64) {
+      const uint64_t raw = base + w.lane < to ? stream[base + w.lane] : 0ull;
+      const uint2 ent = make_uint2((uint32_t)raw, (uint32_t)(raw >> 32));
+      uint64_t todo = __ballot(base + w.lane < to);
+      while (todo) event_group(todo, ent);
     }
   };
 
-  if (tile > 0 && role == 0) {   // occupy the tile's live-in values
-    const uint32_t sb = L.seed_off[tile], se = L.seed_off[tile + 1];
-    for (uint32_t base = sb; base < se; base += 64) {
-      const uint2 ent = base + w.lane < se ? L.seeds[base + w.lane] : make_uint2(0, 0);
-      uint64_t todo = __ballot(base + w.lane < se);
-      while (todo) safety_group(todo, ent);
-    }
-  }
-  const uint32_t pb = L.tile_range[2 * tile], pe = L.tile_range[2 * tile + 1];
-  for (uint32_t base = pb; base < pe; base += 64) {
-    const bool valid = base + w.lane < pe;
-    const uint2 ent = valid ? L.plan[base + w.lane] : make_uint2(0, 0);
-    const uint32_t fl = ent.x >> 24;
-    // stage up to the largest occurrence this batch reads at its own position
-    uint32_t need = (valid && !(fl & kPlanPost)) ? (ent.x & 0xFFFFFFu) : 0u;
-    for (int d = 32; d >= 1; d >>= 1) need = max(need, (uint32_t)__shfl_xor((int)need, d, 64));
-    need = __builtin_amdgcn_readfirstlane(need);
-    if (w.staged_hi <= need) {
-      __syncthreads();   // everyone is done with the slots about to be overwritten
-      while (w.staged_hi <= need) {
-        store_chunk(w);
-        load_chunk(w, w.staged_hi);
+  // ---- checks of one chunk (lane = check, loop over rows) ----
+  auto checks = [&](uint32_t c, uint32_t part) __attribute__((always_inline)) {
+    const uint32_t o = c * kChunk + w.lane;
+    const bool valid = o >= oa && o < ob;
+    const uint64_t raw = valid ? g_chk[o] : 0ull;
+    const uint2 ent = make_uint2((uint32_t)raw, (uint32_t)(raw >> 32));
+    const uint32_t fl = ent.x >> 24, attr = ent.y >> 16, delta = ent.y & 0xFFFFu;
+    const bool is_chk = valid && (fl & kPlanChk), is_first = valid && (fl & kPlanFirst);
+    const uint32_t prev = o - delta;
+    const bool near = is_chk && delta != 0xFFFFu && in_ring(w, prev);
+    const bool far = is_chk && !near;
+    const uint32_t off_p = o & (kRing - 1), off_q = near ? (prev & (kRing - 1)) : off_p;
+    const uint32_t cls = attr_class(attr), width = attr_width(attr), align = attr_align(attr);
+    const uint32_t F = (uint32_t)__shfl((int)cls_tab_v, (int)cls, 64) & 0xFFFFu;
+    const bool pow2 = (align & (align - 1)) == 0;
+    const bool generic = is_first && (!pow2 || has_reserved);   // rare shapes: one by one below
+    const uint32_t limit = F - width;                             // p <= limit (width <= F checked at creation? no: guard)
+    const bool fits = width <= F;
+    for (uint32_t r = part; r < w.nrows; r += 3) {
+      const uint32_t base = w.ring16 + r * kRingStride;
+      const uint32_t p = VL_LDS16[base + off_p], q = VL_LDS16[base + off_q];
+      bool bad = p != q;
+      if (is_first) bad = generic ? unrealizable(m, attr, F, p) : (!fits || p > limit || (p & (align - 1)) != 0);
+      if (__any(bad)) {
+        // the smallest failing key of this row among the chunk's checks
+        uint32_t k = bad ? ((is_chk ? kKeyCons : kKeyReal) | o) : kKeyOk;
+        for (int d = 32; d >= 1; d >>= 1) k = min(k, (uint32_t)__shfl_xor((int)k, d, 64));
+        if (w.lane == 0) atomicMin(&vl_lds[w.keys + r], k);
       }
+    }
+    // links that reach back beyond the ring: one candidate per lane, value from memory
+    uint64_t todo = __ballot(far);
+    for (uint32_t n = 0; todo; ++n) {
+      const uint32_t j = __builtin_ctzll(todo);
+      todo &= todo - 1;
+      if (n % 3 != part) continue;
+      const uint32_t oj = c * kChunk + j;
+      const uint32_t dj = __builtin_amdgcn_readlane(delta, j);
+      const uint32_t pj = dj == 0xFFFFu ? g_prev_occ[oj] : oj - dj;
+      const uint32_t p = fetch(w, oj), q = fetch(w, pj);
+      if (p != q) key = min(key, kKeyCons | oj);
+    }
+  };
+
+  // step -1 occupies the tile's live-in values; steps ca .. c_end-1 stage one chunk each
+  // and process what it releases (a tile without operands still replays its events once)
+  const uint32_t c_stop = c_end > ca ? c_end : ca + 1;
+  for (uint32_t c = ca - 1; c != c_stop; ++c) {
+    const bool seeding = c == ca - 1, staging = !seeding && c < c_end;
+    if (staging) {
+      __syncthreads();   // everyone is done with the slots about to be overwritten
+      store_chunk(w);
+      load_chunk(w, w.staged_hi);
       __syncthreads();
     }
     if (role == 0) {
-      uint64_t todo = __ballot((fl & (kPlanSet | kPlanClr | kPlanBirth)) != 0);
-      while (todo) safety_group(todo, ent);
-    } else {
-      uint64_t todo = __ballot((fl & (kPlanChk | kPlanFirst)) != 0 && !(fl & kPlanPost));
-      const uint32_t lo = role == 1 ? 0u : (role == 2 ? 22u : 43u), hi = role == 1 ? 22u : (role == 2 ? 43u : 64u);
-      todo &= (hi == 64 ? ~0ull : ((1ull << hi) - 1ull)) & ~((1ull << lo) - 1ull);
-      while (todo) check_group(todo, ent);
+      const uint64_t VL_GLOBAL *stream = seeding ? g_seeds : g_plan;
+      uint32_t from, to;
+      if (seeding) {
+        from = tile > 0 ? g_seed_off[tile] : 0u;
+        to = tile > 0 ? g_seed_off[tile + 1] : 0u;
+      } else {
+        from = c == ca ? ea : min(eb, max(ea, g_evt_cut[c]));
+        to = c + 1 >= c_end ? eb : min(eb, max(ea, g_evt_cut[c + 1]));
+      }
+      events(stream, from, to);
+    } else if (staging) {
+      checks(c, role - 1);
     }
   }
-  if (active && key != kKeyOk) atomicMin(&J.out[row0 + w.lane].status, key);
+  __syncthreads();
+  if (active && key != kKeyOk) atomicMin(&vl_lds[w.keys + w.lane], key);
+  __syncthreads();
+  if (w.tid < w.nrows && vl_lds[w.keys + w.tid] != kKeyOk) atomicMin(&J.out[row0 + w.tid].status, vl_lds[w.keys + w.tid]);
 }
 
 __device__ inline uint32_t bad_bits(const DevMir &m, uint32_t attr, uint32_t p) {
@@ -546,7 +555,7 @@ extern "C" int32_t vl_verify_multi(const vl_job *jobs, uint32_t n_jobs, vl_strea
     VL_HIP(hipEventRecord(s.copied, stream));
     s.n_valid = n_jobs;
   }
-  const size_t lds = (size_t)max_words * 64 * 4 + (size_t)64 * kRingStride * 2;
+  const size_t lds = (size_t)max_words * 64 * 4 + 64 * 4 + (size_t)64 * kRingStride * 2;
   k_init<<<dim3((maxK + 255) / 256, n_jobs), 256, 0, stream>>>(s.dev);
   if (g_time_start) VL_HIP(hipEventRecord(g_time_start, stream));
   k_walk<<<units, 256, lds, stream>>>(s.dev, n_jobs);
