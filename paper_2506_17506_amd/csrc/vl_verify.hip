@@ -240,62 +240,69 @@ __global__ __launch_bounds__(256) void k_walk(const DevJob *__restrict__ jobs, u
   };
   constexpr int G = 8;   // events in flight: their LDS reads and atomics overlap
   const uint32_t my_ring = w.ring16 + w.row * kRingStride;
-  auto event_group = [&](uint64_t &todo, const uint2 ent) __attribute__((always_inline)) {
-    uint32_t ex[G], ey[G];
-    int n = 0;
-    bool quick = true;
-#pragma unroll
-    for (int t = 0; t < G; ++t) {
-      ex[t] = 0; ey[t] = 0;
-      if (todo) {
-        const uint32_t j = __builtin_ctzll(todo);
-        todo &= todo - 1;
-        ex[t] = __builtin_amdgcn_readlane(ent.x, j);
-        ey[t] = __builtin_amdgcn_readlane(ent.y, j);
-        quick = quick && in_ring(w, ex[t] & 0xFFFFFFu) && !attr_straddle(ey[t] >> 16);
-        n = t + 1;
-      }
-    }
-    if (!quick) {
-#pragma unroll
-      for (int t = 0; t < G; ++t) if (t < n) event1(ex[t], ey[t]);
-      return;
-    }
-    uint32_t p[G], old[G], msk[G];
-#pragma unroll
-    for (int t = 0; t < G; ++t) p[t] = VL_LDS16[my_ring + (ex[t] & (kRing - 1))];   // unused slots read slot 0
-#pragma unroll
-    for (int t = 0; t < G; ++t) {
-      const uint32_t attr = ey[t] >> 16;
-      const Touch tc = locate(w, attr, __builtin_amdgcn_readlane(cls_tab_v, attr_class(attr)), p[t]);
-      msk[t] = t < n ? tc.mlo : 0u;    // an empty slot flips nothing
-      old[t] = __hip_atomic_fetch_xor(&vl_lds[tc.addr], msk[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
-    }
-    uint32_t any_hit = 0;
-#pragma unroll
-    for (int t = 0; t < G; ++t) {
-      old[t] = ((ex[t] >> 24) & kPlanSet) ? (old[t] & msk[t]) : 0u;
-      any_hit |= old[t];
-    }
-    if (__any(any_hit != 0)) {
-#pragma unroll
-      for (int t = 0; t < G; ++t)
-        if (__any(old[t] != 0)) {
-          const uint32_t i = g_occ_instr[ex[t] & 0xFFFFFFu];
-          if (old[t]) key = min(key, kKeySafe | i);
-        }
-    }
-  };
+  const uint32_t my_occ = w.lane * 4;   // byte offset of this lane's column of mask words
+  // A batch of up to 64 events is first decoded with one event per lane (everything that
+  // does not depend on the candidate: ring offset, tuple mask, mask-word base and limit),
+  // then replayed in order with one candidate per lane, eight events at a time: the eight
+  // register values are read from the ring, the eight mask updates are issued back to back
+  // (LDS executes them in order) and only then are the returned old bits examined.
   auto events = [&](const uint64_t VL_GLOBAL *stream, uint32_t from, uint32_t to) __attribute__((always_inline)) {
     for (uint32_t base = from; base < to; base += 64) {
-      const uint64_t raw = base + w.lane < to ? stream[base + w.lane] : 0ull;
+      const uint32_t cnt = min(64u, to - base);
+      const uint64_t raw = w.lane < cnt ? stream[base + w.lane] : 0ull;
       const uint2 ent = make_uint2((uint32_t)raw, (uint32_t)(raw >> 32));
-      uint64_t todo = __ballot(base + w.lane < to);
-      while (todo) event_group(todo, ent);
+      const uint32_t o = ent.x & 0xFFFFFFu, fl = ent.x >> 24, attr = ent.y >> 16;
+      const uint32_t width = attr_width(attr);
+      const uint32_t tab = (uint32_t)__shfl((int)cls_tab_v, (int)attr_class(attr), 64);
+      const uint32_t F = tab & 0xFFFFu, wbase = tab >> 16;
+      const uint32_t dx = w.lane >= cnt ? 0u : (width == 32 ? 0xFFFFFFFFu : ((1u << width) - 1u));   // tuple mask at bit 0
+      // ring offset (uint16 index) | last word of the class << 9 | tested << 13 | mask-word byte base << 16
+      const uint32_t dy = (o & (kRing - 1)) | (((F - 1u) >> 5) << 9) | ((fl & kPlanSet) ? (1u << 13) : 0u) |
+                          ((wbase * 256u) << 16);
+      const bool slow = w.lane < cnt && (!in_ring(w, o) || attr_straddle(attr));
+      const uint64_t slow_mask = __ballot(slow);
+      for (uint32_t g0 = 0; g0 < cnt; g0 += G) {
+        if ((slow_mask >> g0) & 0xFFull) {   // rare: a value outside the ring or a tuple that may cross a word
+          for (uint32_t j = g0; j < min(cnt, g0 + G); ++j)
+            event1(__builtin_amdgcn_readlane(ent.x, j), __builtin_amdgcn_readlane(ent.y, j));
+          continue;
+        }
+        uint32_t sx[G], sy[G], p[G], old[G], msk[G];
+#pragma unroll
+        for (int t = 0; t < G; ++t) {   // lanes past cnt hold zeros: a zero mask flips nothing
+          sx[t] = __builtin_amdgcn_readlane(dx, g0 + t);
+          sy[t] = __builtin_amdgcn_readlane(dy, g0 + t);
+          p[t] = VL_LDS16[my_ring + (sy[t] & 0x1FFu)];
+        }
+#pragma unroll
+        for (int t = 0; t < G; ++t) {
+          const uint32_t word = min(p[t] >> 5, (sy[t] >> 9) & 15u);
+          msk[t] = sx[t] << (p[t] & 31u);
+          const uint32_t byte_addr = (word << 8) + my_occ + (sy[t] >> 16);
+          old[t] = __hip_atomic_fetch_xor(&vl_lds[byte_addr >> 2], msk[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+        }
+        uint32_t any_hit = 0;
+#pragma unroll
+        for (int t = 0; t < G; ++t) {
+          old[t] = (sy[t] & (1u << 13)) ? (old[t] & msk[t]) : 0u;
+          any_hit |= old[t];
+        }
+        if (__any(any_hit != 0)) {
+#pragma unroll
+          for (int t = 0; t < G; ++t)
+            if (__any(old[t] != 0)) {
+              const uint32_t i = g_occ_instr[__builtin_amdgcn_readlane(o, g0 + t)];
+              if (old[t]) key = min(key, kKeySafe | i);
+            }
+        }
+      }
     }
   };
 
   // ---- checks of one chunk (lane = check, loop over rows) ----
+  // Per lane: ring offsets of the occurrence and of the previous occurrence of its vreg,
+  // and for a first occurrence the alignment mask and the largest base that fits.  Per row:
+  // two reads and three compares, identical for every lane.
   auto checks = [&](uint32_t c, uint32_t part) __attribute__((always_inline)) {
     const uint32_t o = c * kChunk + w.lane;
     const bool valid = o >= oa && o < ob;
@@ -306,23 +313,38 @@ __global__ __launch_bounds__(256) void k_walk(const DevJob *__restrict__ jobs, u
     const uint32_t prev = o - delta;
     const bool near = is_chk && delta != 0xFFFFu && in_ring(w, prev);
     const bool far = is_chk && !near;
-    const uint32_t off_p = o & (kRing - 1), off_q = near ? (prev & (kRing - 1)) : off_p;
     const uint32_t cls = attr_class(attr), width = attr_width(attr), align = attr_align(attr);
     const uint32_t F = (uint32_t)__shfl((int)cls_tab_v, (int)cls, 64) & 0xFFFFu;
-    const bool pow2 = (align & (align - 1)) == 0;
-    const bool generic = is_first && (!pow2 || has_reserved);   // rare shapes: one by one below
-    const uint32_t limit = F - width;                             // p <= limit (width <= F checked at creation? no: guard)
-    const bool fits = width <= F;
-    for (uint32_t r = part; r < w.nrows; r += 3) {
-      const uint32_t base = w.ring16 + r * kRingStride;
-      const uint32_t p = VL_LDS16[base + off_p], q = VL_LDS16[base + off_q];
-      bool bad = p != q;
-      if (is_first) bad = generic ? unrealizable(m, attr, F, p) : (!fits || p > limit || (p & (align - 1)) != 0);
-      if (__any(bad)) {
-        // the smallest failing key of this row among the chunk's checks
-        uint32_t k = bad ? ((is_chk ? kKeyCons : kKeyReal) | o) : kKeyOk;
-        for (int d = 32; d >= 1; d >>= 1) k = min(k, (uint32_t)__shfl_xor((int)k, d, 64));
-        if (w.lane == 0) atomicMin(&vl_lds[w.keys + r], k);
+    // shapes the three compares do not cover: alignment not a power of two, reserved
+    // registers, a tuple wider than its file
+    const bool generic = is_first && ((align & (align - 1)) != 0 || has_reserved || width > F);
+    const bool simple = is_first && !generic;
+    const uint32_t amask = simple ? align - 1u : 0u, limit = simple ? F - width : 0xFFFFFFFFu;
+    const bool any_generic = __any(generic);
+    const uint32_t a_p = w.ring16 + part * kRingStride + (o & (kRing - 1));
+    const uint32_t a_q = w.ring16 + part * kRingStride + ((near ? prev : o) & (kRing - 1));
+    constexpr int R = 4;   // rows in flight
+    for (uint32_t r0 = part; r0 < w.nrows; r0 += 3 * R) {
+      uint32_t p[R], q[R];
+#pragma unroll
+      for (int t = 0; t < R; ++t) {
+        // rows past the last one re-read row r0 (in bounds) and are not looked at
+        const uint32_t ro = (r0 + 3 * t < w.nrows ? (r0 - part) + 3 * t : (r0 - part)) * kRingStride;
+        p[t] = VL_LDS16[a_p + ro];
+        q[t] = VL_LDS16[a_q + ro];
+      }
+#pragma unroll
+      for (int t = 0; t < R; ++t) {
+        const uint32_t r = r0 + 3 * t;
+        if (r >= w.nrows) break;
+        bool bad = (p[t] != q[t]) | ((p[t] & amask) != 0) | (p[t] > limit);
+        if (any_generic && generic) bad = unrealizable(m, attr, F, p[t]);
+        if (__any(bad)) {
+          // the smallest failing key of this row among the chunk's checks
+          uint32_t k = bad ? ((is_chk ? kKeyCons : kKeyReal) | o) : kKeyOk;
+          for (int d = 32; d >= 1; d >>= 1) k = min(k, (uint32_t)__shfl_xor((int)k, d, 64));
+          if (w.lane == 0) atomicMin(&vl_lds[w.keys + r], k);
+        }
       }
     }
     // links that reach back beyond the ring: one candidate per lane, value from memory
@@ -334,8 +356,8 @@ __global__ __launch_bounds__(256) void k_walk(const DevJob *__restrict__ jobs, u
       const uint32_t oj = c * kChunk + j;
       const uint32_t dj = __builtin_amdgcn_readlane(delta, j);
       const uint32_t pj = dj == 0xFFFFu ? g_prev_occ[oj] : oj - dj;
-      const uint32_t p = fetch(w, oj), q = fetch(w, pj);
-      if (p != q) key = min(key, kKeyCons | oj);
+      const uint32_t pv = fetch(w, oj), qv = fetch(w, pj);
+      if (pv != qv) key = min(key, kKeyCons | oj);
     }
   };
 
