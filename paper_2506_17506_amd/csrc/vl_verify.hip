@@ -29,7 +29,7 @@ using namespace vl;
 namespace {
 
 constexpr uint32_t kRing = 256;                 // occurrences kept per candidate in LDS
-constexpr uint32_t kRingStride = kRing + 2;     // in uint16: an odd number of dwords per row
+constexpr uint32_t kRingStride = 64 + 4;        // uint16 per occurrence: 64 rows + padding (136 bytes)
 constexpr uint32_t kChunk = 64;                 // occurrences staged per step (128 B per row)
 constexpr uint32_t kKeyOk = 0xFFFFFFFFu;
 constexpr uint32_t kKeyCons = 0u << 28, kKeyReal = 1u << 28, kKeySafe = 2u << 28, kKeyPos = (1u << 28) - 1;
@@ -74,7 +74,9 @@ __global__ void k_init(const DevJob *__restrict__ jobs) {
 // access is a DS instruction rather than a flat one):
 //   [0, occ_words * 64)            occupancy masks [word][lane]
 //   [keys, keys + 64)              per-row violation keys
-//   [ring32, ...)                  the ring, addressed in uint16 from ring16 = 2 * ring32
+//   [ring32, ...)                  the ring [occurrence & 255][row], addressed in uint16 from
+//                                  ring16 = 2 * ring32; a lane of the check wavefronts reads four
+//                                  rows of one occurrence with one 8-byte read
 extern __shared__ uint32_t vl_lds[];
 #define VL_LDS16 (reinterpret_cast<uint16_t *>(vl_lds))
 
@@ -117,8 +119,12 @@ __device__ inline void store_chunk(Walk &w) {
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     const uint32_t r = h * 32 + (w.tid >> 3);
-    const uint32_t dst = (w.ring16 + r * kRingStride + (c & (kRing - 1))) >> 1;   // even: a dword index
-    vl_lds[dst] = w.pre[h][0]; vl_lds[dst + 1] = w.pre[h][1]; vl_lds[dst + 2] = w.pre[h][2]; vl_lds[dst + 3] = w.pre[h][3];
+    const uint32_t dst = w.ring16 + (c & (kRing - 1)) * kRingStride + r;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      VL_LDS16[dst + (2 * j) * kRingStride] = (uint16_t)w.pre[h][j];
+      VL_LDS16[dst + (2 * j + 1) * kRingStride] = (uint16_t)(w.pre[h][j] >> 16);
+    }
   }
   w.staged_hi += kChunk;
 }
@@ -129,7 +135,7 @@ __device__ inline bool in_ring(const Walk &w, uint32_t o) {
 
 // value of occurrence o (uniform) in this lane's row
 __device__ inline uint32_t fetch(const Walk &w, uint32_t o) {
-  if (in_ring(w, o)) return VL_LDS16[w.ring16 + w.row * kRingStride + (o & (kRing - 1))];
+  if (in_ring(w, o)) return VL_LDS16[w.ring16 + (o & (kRing - 1)) * kRingStride + w.row];
   return w.rows[(uint64_t)w.row * w.ld + o];
 }
 
@@ -239,7 +245,7 @@ __global__ __launch_bounds__(256) void k_walk(const DevJob *__restrict__ jobs, u
     }
   };
   constexpr int G = 8;   // events in flight: their LDS reads and atomics overlap
-  const uint32_t my_ring = w.ring16 + w.row * kRingStride;
+  const uint32_t my_ring = w.ring16 + w.row;
   const uint32_t my_occ = w.lane * 4;   // byte offset of this lane's column of mask words
   // A batch of up to 64 events is first decoded with one event per lane (everything that
   // does not depend on the candidate: ring offset, tuple mask, mask-word base and limit),
@@ -272,7 +278,7 @@ __global__ __launch_bounds__(256) void k_walk(const DevJob *__restrict__ jobs, u
         for (int t = 0; t < G; ++t) {   // lanes past cnt hold zeros: a zero mask flips nothing
           sx[t] = __builtin_amdgcn_readlane(dx, g0 + t);
           sy[t] = __builtin_amdgcn_readlane(dy, g0 + t);
-          p[t] = VL_LDS16[my_ring + (sy[t] & 0x1FFu)];
+          p[t] = VL_LDS16[my_ring + (sy[t] & 0x1FFu) * kRingStride];
         }
 #pragma unroll
         for (int t = 0; t < G; ++t) {
@@ -320,30 +326,40 @@ __global__ __launch_bounds__(256) void k_walk(const DevJob *__restrict__ jobs, u
     const bool generic = is_first && ((align & (align - 1)) != 0 || has_reserved || width > F);
     const bool simple = is_first && !generic;
     const uint32_t amask = simple ? align - 1u : 0u, limit = simple ? F - width : 0xFFFFFFFFu;
-    const bool any_generic = __any(generic);
-    const uint32_t a_p = w.ring16 + part * kRingStride + (o & (kRing - 1));
-    const uint32_t a_q = w.ring16 + part * kRingStride + ((near ? prev : o) & (kRing - 1));
-    constexpr int R = 4;   // rows in flight
-    for (uint32_t r0 = part; r0 < w.nrows; r0 += 3 * R) {
-      uint32_t p[R], q[R];
-#pragma unroll
-      for (int t = 0; t < R; ++t) {
-        // rows past the last one re-read row r0 (in bounds) and are not looked at
-        const uint32_t ro = (r0 + 3 * t < w.nrows ? (r0 - part) + 3 * t : (r0 - part)) * kRingStride;
-        p[t] = VL_LDS16[a_p + ro];
-        q[t] = VL_LDS16[a_q + ro];
-      }
-#pragma unroll
-      for (int t = 0; t < R; ++t) {
-        const uint32_t r = r0 + 3 * t;
-        if (r >= w.nrows) break;
-        bool bad = (p[t] != q[t]) | ((p[t] & amask) != 0) | (p[t] > limit);
-        if (any_generic && generic) bad = unrealizable(m, attr, F, p[t]);
-        if (__any(bad)) {
-          // the smallest failing key of this row among the chunk's checks
-          uint32_t k = bad ? ((is_chk ? kKeyCons : kKeyReal) | o) : kKeyOk;
-          for (int d = 32; d >= 1; d >>= 1) k = min(k, (uint32_t)__shfl_xor((int)k, d, 64));
-          if (w.lane == 0) atomicMin(&vl_lds[w.keys + r], k);
+    // Four rows per 8-byte read, two rows per 32-bit operation.  What is wrong in a row
+    // leaves a non-zero half-word: p ^ q (differs from the previous occurrence),
+    // p & (align - 1), and p ^ min(p, limit) (beyond the last base that fits).  Rows past
+    // the last candidate hold zeros.  Only when something is non-zero are the rows looked
+    // at one by one.
+    typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
+    const uint32_t amask2 = amask * 0x10001u, limit2 = min(limit, 0xFFFFu) * 0x10001u;
+    const uint32_t a_p = (w.ring16 + (o & (kRing - 1)) * kRingStride) >> 2;          // in 8-byte units
+    const uint32_t a_q = (w.ring16 + ((near ? prev : o) & (kRing - 1)) * kRingStride) >> 2;
+    const uint64_t *lds64 = reinterpret_cast<const uint64_t *>(vl_lds);
+    auto wrong2 = [&](uint32_t pp, uint32_t qq) __attribute__((always_inline)) {
+      const u16x2 mn = __builtin_elementwise_min(__builtin_bit_cast(u16x2, pp), __builtin_bit_cast(u16x2, limit2));
+      return (pp ^ qq) | (pp & amask2) | (pp ^ __builtin_bit_cast(uint32_t, mn));
+    };
+    uint32_t acc = 0;
+    const uint32_t n_quad = (w.nrows + 3) / 4;
+    for (uint32_t qd = part; qd < n_quad; qd += 3) {
+      const uint64_t pv = lds64[a_p + qd], qv = lds64[a_q + qd];
+      acc |= wrong2((uint32_t)pv, (uint32_t)qv) | wrong2((uint32_t)(pv >> 32), (uint32_t)(qv >> 32));
+    }
+    if (__any(acc != 0 || generic)) {
+      // rare: attribute row by row
+      for (uint32_t qd = part; qd < n_quad; qd += 3) {
+        for (uint32_t r = 4 * qd; r < min(w.nrows, 4 * qd + 4); ++r) {
+          const uint32_t pr = VL_LDS16[w.ring16 + (o & (kRing - 1)) * kRingStride + r];
+          const uint32_t qr = VL_LDS16[w.ring16 + ((near ? prev : o) & (kRing - 1)) * kRingStride + r];
+          bool bad = (pr != qr) | ((pr & amask) != 0) | (pr > limit);
+          if (generic) bad = unrealizable(m, attr, F, pr);
+          if (__any(bad)) {
+            // the smallest failing key of this row among the chunk's checks
+            uint32_t k = bad ? ((is_chk ? kKeyCons : kKeyReal) | o) : kKeyOk;
+            for (int d = 32; d >= 1; d >>= 1) k = min(k, (uint32_t)__shfl_xor((int)k, d, 64));
+            if (w.lane == 0) atomicMin(&vl_lds[w.keys + r], k);
+          }
         }
       }
     }
@@ -577,7 +593,7 @@ extern "C" int32_t vl_verify_multi(const vl_job *jobs, uint32_t n_jobs, vl_strea
     VL_HIP(hipEventRecord(s.copied, stream));
     s.n_valid = n_jobs;
   }
-  const size_t lds = (size_t)max_words * 64 * 4 + 64 * 4 + (size_t)64 * kRingStride * 2;
+  const size_t lds = (size_t)max_words * 64 * 4 + 64 * 4 + (size_t)kRing * kRingStride * 2;
   k_init<<<dim3((maxK + 255) / 256, n_jobs), 256, 0, stream>>>(s.dev);
   if (g_time_start) VL_HIP(hipEventRecord(g_time_start, stream));
   k_walk<<<units, 256, lds, stream>>>(s.dev, n_jobs);
