@@ -6,6 +6,10 @@
 
 #include "../../include/vl.h"
 
+// Device arrays reached through the structures below are declared as pointers into global
+// memory, so that the compiler emits global / scalar loads for them rather than flat ones.
+#define VL_GLOBAL __attribute__((address_space(1)))
+
 namespace vl {
 
 constexpr uint32_t kMaxClass = 8;
@@ -17,14 +21,15 @@ constexpr uint32_t kDefaultTile = 1024;    // instructions per verification tile
 struct DevMir {
   uint32_t N, V, B, O, C, E, W;
   uint32_t occ_words;              // occupancy words summed over classes
-  const uint32_t *blk_start;       // [B+1]
-  const uint32_t *succ_off, *succ; // CSR successors
-  const uint32_t *occ_off;         // [N+1]
-  const uint32_t *occ_vreg;        // [O]
-  const uint32_t *occ_instr;       // [O] instruction of each occurrence
-  const uint32_t *instr_blk;       // [N] block of each instruction
-  const uint32_t *vattr;           // [V] packed attributes, see attr_* below
-  const uint8_t *occ_flags;        // [O]
+  const uint32_t VL_GLOBAL *blk_start;       // [B+1]
+  const uint32_t VL_GLOBAL *succ_off;        // CSR successors
+  const uint32_t VL_GLOBAL *succ;
+  const uint32_t VL_GLOBAL *occ_off;         // [N+1]
+  const uint32_t VL_GLOBAL *occ_vreg;        // [O]
+  const uint32_t VL_GLOBAL *occ_instr;       // [O] instruction of each occurrence
+  const uint32_t VL_GLOBAL *instr_blk;       // [N] block of each instruction
+  const uint32_t VL_GLOBAL *vattr;           // [V] packed attributes, see attr_* below
+  const uint8_t VL_GLOBAL *occ_flags;        // [O]
   uint32_t has_reserved;
   uint16_t class_size[kMaxClass];
   uint16_t class_word[kMaxClass];  // first occupancy word of the class
@@ -41,6 +46,7 @@ __host__ __device__ inline uint32_t attr_class(uint32_t a) { return a & 7u; }
 __host__ __device__ inline uint32_t attr_width(uint32_t a) { return ((a >> 3) & 31u) + 1u; }
 __host__ __device__ inline uint32_t attr_align(uint32_t a) { return ((a >> 8) & 31u) + 1u; }
 __host__ __device__ inline uint32_t attr_straddle(uint32_t a) { return (a >> 13) & 1u; }
+__host__ __device__ inline uint64_t entry_pack(uint32_t x, uint32_t y) { return (uint64_t)x | ((uint64_t)y << 32); }
 
 // The verifier reads two streams of 8-byte entries
 //   x: occurrence index (24 bits) | flags << 24
@@ -68,50 +74,61 @@ constexpr uint8_t kEntLiveAfter = 1, kEntHasUse = 2, kEntHasDef = 4, kEntGroupSt
 // Liveness analysis of one kernel on the device.
 struct DevLive {
   // --- sized from the program alone ---
-  uint32_t *vcnt;       // [V+1] occurrences per vreg -> exclusive offsets (vocc_off)
-  uint32_t *vcur;       // [V] placement cursors
-  uint32_t *vocc_tmp;   // [O] occurrences grouped by vreg, unordered
-  uint32_t *vocc;       // [O] occurrences grouped by vreg, ascending
-  uint32_t *ent_instr;  // [O] instruction of each sorted entry
-  uint8_t *ent_info;    // [O] kEnt* bits of each sorted entry
-  uint32_t *first;      // [V] first occurrence or kNone
-  uint32_t *prev_occ;   // [O] previous occurrence of the same vreg or kNone
-  uint8_t *occ_role;    // [O] kRole* bits
-  uint8_t *occ_kill;    // [O]
-  uint32_t *use, *def, *live_in, *live_out;  // [B][W]
-  uint32_t *item_off;   // [N+B+1] plan offset of each item (boundary b at blk_start[b]+b,
+  uint32_t VL_GLOBAL *vcnt;       // [V+1] occurrences per vreg -> exclusive offsets (vocc_off)
+  uint32_t VL_GLOBAL *vcur;       // [V] placement cursors
+  uint32_t VL_GLOBAL *vocc_tmp;   // [O] occurrences grouped by vreg, unordered
+  uint32_t VL_GLOBAL *vocc;       // [O] occurrences grouped by vreg, ascending
+  uint32_t VL_GLOBAL *ent_instr;  // [O] instruction of each sorted entry
+  uint8_t VL_GLOBAL *ent_info;    // [O] kEnt* bits of each sorted entry
+  uint32_t VL_GLOBAL *first;      // [V] first occurrence or kNone
+  uint32_t VL_GLOBAL *prev_occ;   // [O] previous occurrence of the same vreg or kNone
+  uint8_t VL_GLOBAL *occ_role;    // [O] kRole* bits
+  uint8_t VL_GLOBAL *occ_kill;    // [O]
+  uint32_t VL_GLOBAL *use;        // [B][W] block bitsets
+  uint32_t VL_GLOBAL *def;
+  uint32_t VL_GLOBAL *live_in;
+  uint32_t VL_GLOBAL *live_out;
+  uint32_t VL_GLOBAL *item_off;   // [N+B+1] plan offset of each item (boundary b at blk_start[b]+b,
                         //          instruction i of block b at i+b+1)
-  uint32_t *seg_off;    // [V+1]
-  uint2 *chk;           // [O] check stream
-  uint32_t *evt_cut;    // [ceil(O/64)+1] first event replayable once chunk c is staged
-  uint32_t *ent_seg;    // [O+1] runs starting in each mention group's stretch -> prefix sums
-  uint32_t *hull;       // [V][2]
-  uint32_t *seed_off;   // [T+1]
-  uint32_t *seed_cur;   // [T]
-  uint32_t *blk_live;   // [V][ceil(B/32)] blocks each vreg is live into
-  uint32_t *long_queue; // [V] vregs whose occurrence list needs the bitmap sort
-  uint32_t *bitmap;     // [ceil(O/32)] scratch for the bitmap sort, one list at a time per block
-  uint32_t *counters;   // [kCounters]
+  uint32_t VL_GLOBAL *seg_off;    // [V+1]
+  uint64_t VL_GLOBAL *chk;        // [O] check stream (x | y << 32)
+  uint32_t VL_GLOBAL *evt_cut;    // [ceil(O/64)+1] first event replayable once chunk c is staged
+  uint32_t VL_GLOBAL *ent_seg;    // [O+1] runs starting in each mention group's stretch -> prefix sums
+  uint32_t VL_GLOBAL *hull;       // [V][2]
+  uint32_t VL_GLOBAL *seed_off;   // [T+1]
+  uint32_t VL_GLOBAL *seed_cur;   // [T]
+  uint32_t VL_GLOBAL *blk_live;   // [V][ceil(B/32)] blocks each vreg is live into
+  uint32_t VL_GLOBAL *long_queue; // [V] vregs whose occurrence list needs the bitmap sort
+  uint32_t VL_GLOBAL *bitmap;     // [ceil(O/32)] scratch for the bitmap sort, one list at a time per block
+  uint32_t VL_GLOBAL *counters;   // [kCounters]
   // --- sized after the counting pass ---
-  uint2 *plan;          // [plan_len] occupancy events
-  uint2 *seeds;         // [n_seed]
-  uint32_t *seg;        // [n_seg][2]
-  uint32_t *tile_range; // [T][2] plan range of each tile
-  uint32_t *tile_live;  // [T][W] live-before row of each tile start (dense mode)
-  uint32_t *live_after; // [N][W] (dense mode)
+  uint64_t VL_GLOBAL *plan;       // [plan_len] occupancy events (x | y << 32)
+  uint64_t VL_GLOBAL *seeds;      // [n_seed] (x | y << 32)
+  uint32_t VL_GLOBAL *seg;        // [n_seg][2]
+  uint32_t VL_GLOBAL *tile_range; // [T][2] plan range of each tile
+  uint32_t VL_GLOBAL *tile_live;  // [T][W] live-before row of each tile start (dense mode)
+  uint32_t VL_GLOBAL *live_after; // [N][W] (dense mode)
   uint32_t T, tile_len, plan_len, n_seg, n_seed, dense;
 };
 
-// Pointers read out of device structures are generic to the compiler; these casts tell
-// it they point to global memory, so that loads become global / scalar loads instead of
-// flat ones.
-#define VL_GLOBAL __attribute__((address_space(1)))
-template <class T> __device__ inline const T VL_GLOBAL *as_global(const T *p) {
+template <class T> __host__ __device__ inline const T VL_GLOBAL *as_global(const T *p) {
   return (const T VL_GLOBAL *)p;
 }
-template <class T> __device__ inline T VL_GLOBAL *as_global_rw(T *p) {
+template <class T> __host__ __device__ inline T VL_GLOBAL *as_global_rw(T *p) {
   return (T VL_GLOBAL *)p;
 }
+
+// atomics on global-memory pointers (the HIP header ones take generic pointers)
+#define VL_ATOMIC(name, builtin)                                                        \
+  __device__ inline uint32_t name(uint32_t VL_GLOBAL *p, uint32_t v) {                  \
+    return builtin(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);                   \
+  }
+VL_ATOMIC(atomicAdd, __hip_atomic_fetch_add)
+VL_ATOMIC(atomicOr, __hip_atomic_fetch_or)
+VL_ATOMIC(atomicXor, __hip_atomic_fetch_xor)
+VL_ATOMIC(atomicMin, __hip_atomic_fetch_min)
+VL_ATOMIC(atomicMax, __hip_atomic_fetch_max)
+#undef VL_ATOMIC
 
 enum { kCtrLong = 0, kCtrNotStrict = 1, kCtrSweeps = 2, kCtrPlanLen = 3, kCtrSeg = 4, kCtrSeed = 5,
        kCounters = 8 };

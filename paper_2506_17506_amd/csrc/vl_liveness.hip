@@ -24,10 +24,10 @@ using namespace vl;
 
 namespace {
 
-__device__ inline bool bit_get(const uint32_t *row, uint32_t v) { return (row[v >> 5] >> (v & 31)) & 1u; }
+template <class P> __device__ inline bool bit_get(P row, uint32_t v) { return (row[v >> 5] >> (v & 31)) & 1u; }
 
 // first index in [lo,hi) with a[idx] >= key
-__device__ inline uint32_t lower_bound(const uint32_t *a, uint32_t lo, uint32_t hi, uint32_t key) {
+template <class P> __device__ inline uint32_t lower_bound(P a, uint32_t lo, uint32_t hi, uint32_t key) {
   while (lo < hi) {
     uint32_t mid = (lo + hi) >> 1;
     if (a[mid] < key) lo = mid + 1; else hi = mid;
@@ -43,8 +43,8 @@ constexpr uint32_t kSlice = 8192;   // occurrences per workgroup in the counting
 // then adds the non-zero bins to the global counters once.
 template <bool kLds>
 __global__ __launch_bounds__(1024) void k_count(MIRS) {
-  const DevMir &m = *mirs[blockIdx.y];
-  DevLive &L = lives[blockIdx.y];
+  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
+  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
   extern __shared__ uint32_t sm[];
   const uint32_t o0 = blockIdx.x * kSlice;
   if (o0 >= m.O) return;
@@ -68,9 +68,9 @@ enum { kScanVreg = 0, kScanItems = 1, kScanSeg = 2, kScanSeed = 3 };   // kScanS
 // seen to pick the wrong pointer in its default branch.)
 template <int kWhich>
 __global__ __launch_bounds__(1024) void k_scan(MIRS) {
-  const DevMir &m = *mirs[blockIdx.x];
-  DevLive &L = lives[blockIdx.x];
-  uint32_t *p = kWhich == kScanVreg ? L.vcnt : kWhich == kScanItems ? L.item_off : kWhich == kScanSeg ? L.ent_seg : L.seed_off;
+  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.x]);
+  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.x]);
+  uint32_t VL_GLOBAL *p = kWhich == kScanVreg ? L.vcnt : kWhich == kScanItems ? L.item_off : kWhich == kScanSeg ? L.ent_seg : L.seed_off;
   const uint32_t n = kWhich == kScanVreg ? m.V : kWhich == kScanItems ? m.N + m.B : kWhich == kScanSeg ? m.O : L.T;
   __shared__ uint32_t part[1024];
   const uint32_t tid = threadIdx.x;
@@ -100,8 +100,8 @@ __global__ __launch_bounds__(1024) void k_scan(MIRS) {
 // then ranks its own occurrences in LDS.
 template <bool kLds>
 __global__ __launch_bounds__(1024) void k_place(MIRS) {
-  const DevMir &m = *mirs[blockIdx.y];
-  DevLive &L = lives[blockIdx.y];
+  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
+  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
   extern __shared__ uint32_t sm[];
   const uint32_t o0 = blockIdx.x * kSlice;
   if (o0 >= m.O) return;
@@ -134,8 +134,8 @@ constexpr uint32_t kShortList = 16;
 
 // Lists of up to kShortList occurrences are rank-sorted by one lane; longer ones are queued.
 __global__ void k_sort_short(MIRS) {
-  const DevMir &m = *mirs[blockIdx.y];
-  DevLive &L = lives[blockIdx.y];
+  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
+  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
   uint32_t v = blockIdx.x * blockDim.x + threadIdx.x;
   if (v >= m.V) return;
   const uint32_t lo = L.vcnt[v], len = L.vcnt[v + 1] - lo;
@@ -160,8 +160,8 @@ constexpr uint32_t kBitmapSpan = kBitmapWords * 32;  // occurrences per window
 // Long lists: occurrence indices are distinct, so marking them in a bitmap and
 // reading the bitmap back in order sorts them.
 __global__ __launch_bounds__(256) void k_sort_long(MIRS) {
-  const DevMir &m = *mirs[blockIdx.y];
-  DevLive &L = lives[blockIdx.y];
+  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
+  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
   __shared__ uint32_t bm[kBitmapWords];
   __shared__ uint32_t part[256];
   const uint32_t tid = threadIdx.x;
@@ -209,8 +209,8 @@ __global__ __launch_bounds__(256) void k_sort_long(MIRS) {
 }
 
 __global__ void k_ent(MIRS) {
-  const DevMir &m = *mirs[blockIdx.y];
-  DevLive &L = lives[blockIdx.y];
+  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
+  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
   uint32_t e = blockIdx.x * blockDim.x + threadIdx.x;
   if (e < m.O) L.ent_instr[e] = m.occ_instr[L.vocc[e]];
 }
@@ -219,8 +219,8 @@ __global__ void k_ent(MIRS) {
 // def[b]: vregs written in b.  use[b]: vregs whose first mention in b reads them
 // (an instruction reads before it writes).
 __global__ void k_summary(MIRS) {
-  const DevMir &m = *mirs[blockIdx.y];
-  DevLive &L = lives[blockIdx.y];
+  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
+  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
   uint32_t e = blockIdx.x * blockDim.x + threadIdx.x;
   uint32_t b = kNone, w = 0, dbits = 0, ubits = 0;
   if (e < m.O) {
@@ -262,8 +262,8 @@ __global__ void k_summary(MIRS) {
 // block count allows, otherwise the sweep runs on global memory.
 template <bool kLds>
 __global__ __launch_bounds__(64) void k_fixpoint(MIRS) {
-  const DevMir &m = *mirs[blockIdx.y];
-  DevLive &L = lives[blockIdx.y];
+  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
+  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
   extern __shared__ uint32_t sm[];
   const uint32_t lane = threadIdx.x, w = blockIdx.x * 64 + lane;
   if (blockIdx.x * 64 >= m.W) return;
@@ -320,8 +320,8 @@ __global__ __launch_bounds__(64) void k_fixpoint(MIRS) {
 // mention of v in the same block reads it, or, with no later mention in the block, v is
 // in the block's live-out.  P(i) contains v iff it is live after i or written at i.
 __global__ void k_events(MIRS) {
-  const DevMir &m = *mirs[blockIdx.y];
-  DevLive &L = lives[blockIdx.y];
+  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
+  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
   uint32_t e = blockIdx.x * blockDim.x + threadIdx.x;
   if (e >= m.O) return;
   const uint32_t o = L.vocc[e], v = m.occ_vreg[o];
@@ -361,11 +361,11 @@ __global__ void k_events(MIRS) {
 }
 
 // ---- 5a. event stream -----------------------------------------------------------------
-__device__ inline uint32_t item_of_instr(const DevMir &m, uint32_t i) { return i + m.instr_blk[i] + 1; }
+__device__ inline uint32_t item_of_instr(const DevMir VL_GLOBAL &m, uint32_t i) { return i + m.instr_blk[i] + 1; }
 
 __global__ void k_item_count(MIRS) {
-  const DevMir &m = *mirs[blockIdx.y];
-  DevLive &L = lives[blockIdx.y];
+  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
+  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
   uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= m.N) return;
   uint32_t cnt = 0;
@@ -383,7 +383,7 @@ __device__ inline uint32_t wave_incl_scan(uint32_t x) {
 }
 
 // nearest occurrence of v before instruction `at`, else the first at or after it
-__device__ inline uint32_t source_occurrence(const DevLive &L, uint32_t v, uint32_t at) {
+__device__ inline uint32_t source_occurrence(const DevLive VL_GLOBAL &L, uint32_t v, uint32_t at) {
   const uint32_t lo = L.vcnt[v], hi = L.vcnt[v + 1];
   uint32_t x = lower_bound(L.ent_instr, lo, hi, at);
   return x > lo ? L.vocc[x - 1] : (x < hi ? L.vocc[x] : 0u);
@@ -394,8 +394,8 @@ __device__ inline uint32_t source_occurrence(const DevLive &L, uint32_t v, uint3
 // values that leave (release) and those that enter (occupy without test).
 template <bool kFill>
 __global__ __launch_bounds__(64) void k_boundary(MIRS) {
-  const DevMir &m = *mirs[blockIdx.y];
-  DevLive &L = lives[blockIdx.y];
+  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
+  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
   const uint32_t b = blockIdx.x, lane = threadIdx.x;
   if (b >= m.B) return;
   const uint32_t item = m.blk_start[b] + b;
@@ -404,7 +404,8 @@ __global__ __launch_bounds__(64) void k_boundary(MIRS) {
     return;
   }
   const uint32_t W = m.W, at = m.blk_start[b];
-  const uint32_t *out_prev = L.live_out + (size_t)(b - 1) * W, *in_cur = L.live_in + (size_t)b * W;
+  const uint32_t VL_GLOBAL *out_prev = L.live_out + (size_t)(b - 1) * W;
+  const uint32_t VL_GLOBAL *in_cur = L.live_in + (size_t)b * W;
   uint32_t base = kFill ? L.item_off[item] : 0, total = 0;
   for (int pass = 0; pass < 2; ++pass) {  // 0: leaving, 1: entering
     for (uint32_t w0 = 0; w0 < W; w0 += 64) {
@@ -418,7 +419,7 @@ __global__ __launch_bounds__(64) void k_boundary(MIRS) {
           uint32_t v = w * 32 + __ffs(bits) - 1;
           bits &= bits - 1;
           uint32_t src = source_occurrence(L, v, at);
-          L.plan[pos++] = make_uint2(src | ((pass == 0 ? kPlanClr : kPlanBirth) | kPlanPost) << 24,
+          L.plan[pos++] = entry_pack(src | ((pass == 0 ? kPlanClr : kPlanBirth) | kPlanPost) << 24,
                                      0xFFFFu | (m.vattr[v] << 16));
         }
       }
@@ -432,14 +433,14 @@ __global__ __launch_bounds__(64) void k_boundary(MIRS) {
 // operands that die here, then test-and-occupy of the values written, then releases of
 // values that are dead once the instruction has executed.
 __global__ void k_plan_fill(MIRS) {
-  const DevMir &m = *mirs[blockIdx.y];
-  DevLive &L = lives[blockIdx.y];
+  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
+  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
   uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= m.N) return;
   uint32_t pos = L.item_off[item_of_instr(m, i)];
   const uint32_t o0 = m.occ_off[i], o1 = m.occ_off[i + 1];
   auto entry = [&](uint32_t o, uint32_t flags) {
-    return make_uint2(o | (flags << 24), 0xFFFFu | (m.vattr[m.occ_vreg[o]] << 16));
+    return entry_pack(o | (flags << 24), 0xFFFFu | (m.vattr[m.occ_vreg[o]] << 16));
   };
   for (uint32_t o = o0; o < o1; ++o)
     if (L.occ_role[o] & kRolePreKill) L.plan[pos++] = entry(o, kPlanClr);
@@ -452,21 +453,21 @@ __global__ void k_plan_fill(MIRS) {
 // The check stream has one entry per occurrence, in occurrence order: compare with the
 // previous occurrence of the vreg, or (first occurrence) test realizability.
 __global__ void k_chk_fill(MIRS) {
-  const DevMir &m = *mirs[blockIdx.y];
-  DevLive &L = lives[blockIdx.y];
+  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
+  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
   uint32_t o = blockIdx.x * blockDim.x + threadIdx.x;
   if (o >= m.O) return;
   const uint32_t prev = L.prev_occ[o];
   const uint32_t delta = prev == kNone ? 0u : min(o - prev, 0xFFFFu);
   const uint32_t flags = (L.occ_role[o] & kRoleFirst) ? kPlanFirst : kPlanChk;
-  L.chk[o] = make_uint2(o | (flags << 24), delta | (m.vattr[m.occ_vreg[o]] << 16));
+  L.chk[o] = entry_pack(o | (flags << 24), delta | (m.vattr[m.occ_vreg[o]] << 16));
 }
 
 // evt_cut[c] = index of the first event of the first item whose operands end in chunk c or
 // later (an item's events may be replayed once occurrences [0, 64 (c + 1)) are staged).
 __global__ void k_evt_cut(MIRS) {
-  const DevMir &m = *mirs[blockIdx.y];
-  DevLive &L = lives[blockIdx.y];
+  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
+  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
   const uint32_t c = blockIdx.x * blockDim.x + threadIdx.x;
   const uint32_t n_chunk = (m.O + 63) / 64;
   if (c > n_chunk) return;
@@ -489,8 +490,8 @@ __global__ void k_evt_cut(MIRS) {
 // blk_live[v] = bitmask over blocks b with v in live_in[b] (the transpose of live_in), so
 // that a vreg finds the blocks it is live through without testing every block.
 __global__ void k_blk_transpose(MIRS) {
-  const DevMir &m = *mirs[blockIdx.z];
-  DevLive &L = lives[blockIdx.z];
+  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.z]);
+  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.z]);
   const uint32_t b = blockIdx.y, w = blockIdx.x * blockDim.x + threadIdx.x;
   if (b >= m.B || w >= m.W) return;
   uint32_t bits = L.live_in[(size_t)b * m.W + w];
@@ -510,8 +511,8 @@ __global__ void k_blk_transpose(MIRS) {
 // of the start counts numbers the runs in CSR order; the j-th end belongs to the j-th start.
 template <bool kFill>
 __global__ void k_seg(MIRS) {
-  const DevMir &m = *mirs[blockIdx.y];
-  DevLive &L = lives[blockIdx.y];
+  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
+  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
   const uint32_t e = blockIdx.x * blockDim.x + threadIdx.x;
   if (e >= m.O) return;
   const uint8_t info = L.ent_info[e];
@@ -520,7 +521,7 @@ __global__ void k_seg(MIRS) {
   const uint32_t lo = L.vcnt[v], hi = L.vcnt[v + 1];
   const uint32_t i = L.ent_instr[e], b = m.instr_blk[i];
   const uint32_t WB = (m.B + 31) / 32;
-  const uint32_t *live_blocks = L.blk_live + (size_t)v * WB;
+  const uint32_t VL_GLOBAL *live_blocks = L.blk_live + (size_t)v * WB;
   // was v occupied just before this stretch?
   bool cur;
   if (i == 0) cur = false;
@@ -562,8 +563,8 @@ __global__ void k_seg(MIRS) {
 
 // seg_off per vreg from the per-entry prefix sums; hulls of never-occupied vregs to [0,0)
 __global__ void k_seg_off(MIRS) {
-  const DevMir &m = *mirs[blockIdx.y];
-  DevLive &L = lives[blockIdx.y];
+  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
+  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
   const uint32_t v = blockIdx.x * blockDim.x + threadIdx.x;
   if (v > m.V) return;
   L.seg_off[v] = L.ent_seg[v < m.V ? L.vcnt[v] : m.O];
@@ -579,8 +580,8 @@ __global__ void k_seg_off(MIRS) {
 // so `at` lies within the hull widened to the first and last mention.
 template <bool kFill>
 __global__ void k_seed(MIRS) {
-  const DevMir &m = *mirs[blockIdx.y];
-  DevLive &L = lives[blockIdx.y];
+  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
+  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
   const uint32_t v = blockIdx.x * blockDim.x + threadIdx.x;
   if (v >= m.V) return;
   const uint32_t lo = L.vcnt[v], hi = L.vcnt[v + 1];
@@ -599,7 +600,7 @@ __global__ void k_seed(MIRS) {
     if (!kFill) { atomicAdd(&L.seed_off[t], 1u); continue; }
     const uint32_t src = x > lo ? L.vocc[x - 1] : L.vocc[x];
     const uint32_t pos = L.seed_off[t] + atomicAdd(&L.seed_cur[t], 1u);
-    L.seeds[pos] = make_uint2(src | ((kPlanBirth | kPlanPost) << 24), 0xFFFFu | (m.vattr[v] << 16));
+    L.seeds[pos] = entry_pack(src | ((kPlanBirth | kPlanPost) << 24), 0xFFFFu | (m.vattr[v] << 16));
     if (L.dense) atomicOr(&L.tile_live[(size_t)t * m.W + (v >> 5)], 1u << (v & 31));
   }
 }
@@ -607,16 +608,16 @@ __global__ void k_seed(MIRS) {
 __global__ void k_collect(MIRS, uint32_t n) {
   uint32_t k = blockIdx.x * blockDim.x + threadIdx.x;
   if (k >= n) return;
-  const DevMir &m = *mirs[k];
-  DevLive &L = lives[k];
+  const DevMir VL_GLOBAL &m = *as_global(mirs[k]);
+  DevLive VL_GLOBAL &L = *as_global_rw(&lives[k]);
   L.counters[kCtrPlanLen] = L.item_off[m.N + m.B];
   L.counters[kCtrSeg] = L.ent_seg[m.O];
   L.counters[kCtrSeed] = L.seed_off[L.T];
 }
 
 __global__ void k_tile_range(MIRS) {
-  const DevMir &m = *mirs[blockIdx.y];
-  DevLive &L = lives[blockIdx.y];
+  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
+  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
   uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
   if (t >= L.T) return;
   const uint32_t i0 = t * L.tile_len, i1 = min(m.N, i0 + L.tile_len);
@@ -637,8 +638,8 @@ __global__ void k_tile_range(MIRS) {
 // XOR-ed into the row of the instruction at which it takes effect, then each tile
 // prefix-XORs its rows downwards from the tile's live-in row.
 __global__ void k_dense_delta(MIRS) {
-  const DevMir &m = *mirs[blockIdx.y];
-  DevLive &L = lives[blockIdx.y];
+  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
+  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
   uint32_t q = blockIdx.x * blockDim.x + threadIdx.x;
   if (q >= m.N + m.B) return;
   // item q is either the boundary of block b (q == blk_start[b] + b) or an instruction of
@@ -652,15 +653,15 @@ __global__ void k_dense_delta(MIRS) {
   // a tile that starts exactly at this block start takes its row from the seed instead
   if (q == m.blk_start[b] + b && row % L.tile_len == 0) return;
   for (uint32_t e = L.item_off[q]; e < L.item_off[q + 1]; ++e) {
-    const uint2 ent = L.plan[e];
-    const uint32_t v = m.occ_vreg[ent.x & 0xFFFFFFu];
+    const uint32_t ex = (uint32_t)L.plan[e];
+    const uint32_t v = m.occ_vreg[ex & 0xFFFFFFu];
     atomicXor(&L.live_after[(size_t)row * m.W + (v >> 5)], 1u << (v & 31));
   }
 }
 
 __global__ __launch_bounds__(64) void k_dense_scan(MIRS) {
-  const DevMir &m = *mirs[blockIdx.z];
-  DevLive &L = lives[blockIdx.z];
+  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.z]);
+  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.z]);
   const uint32_t t = blockIdx.y, w = blockIdx.x * 64 + threadIdx.x;
   if (t >= L.T || w >= m.W) return;
   const uint32_t i0 = t * L.tile_len, i1 = min(m.N, i0 + L.tile_len);
@@ -808,21 +809,21 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
   const DevMir **mir_ptrs = batch->stage_mirs;
   for (uint32_t k = 0; k < n; ++k) {
     DevLive &L = h[k];
-    L.vcnt = (uint32_t *)(a1 + off[k].vcnt); L.vcur = (uint32_t *)(a1 + off[k].vcur);
-    L.use = (uint32_t *)(a1 + off[k].use); L.def = (uint32_t *)(a1 + off[k].def);
-    L.live_in = (uint32_t *)(a1 + off[k].in); L.live_out = (uint32_t *)(a1 + off[k].out);
-    L.seed_off = (uint32_t *)(a1 + off[k].seed_off); L.seed_cur = (uint32_t *)(a1 + off[k].seed_cur);
-    L.blk_live = (uint32_t *)(a1 + off[k].blk_live);
-    L.vocc_tmp = (uint32_t *)(a1 + off[k].tmp); L.vocc = (uint32_t *)(a1 + off[k].vocc);
-    L.ent_instr = (uint32_t *)(a1 + off[k].ent_instr); L.ent_info = (uint8_t *)(a1 + off[k].ent_info);
-    L.first = (uint32_t *)(a1 + off[k].first); L.prev_occ = (uint32_t *)(a1 + off[k].prev);
-    L.occ_role = (uint8_t *)(a1 + off[k].role); L.occ_kill = (uint8_t *)(a1 + off[k].kill);
-    L.item_off = (uint32_t *)(a1 + off[k].item); L.seg_off = (uint32_t *)(a1 + off[k].seg_off);
-    L.hull = (uint32_t *)(a1 + off[k].hull); L.long_queue = (uint32_t *)(a1 + off[k].queue);
-    L.ent_seg = (uint32_t *)(a1 + off[k].ent_seg);
-    L.chk = (uint2 *)(a1 + off[k].chk); L.evt_cut = (uint32_t *)(a1 + off[k].evt_cut);
-    L.bitmap = nullptr;
-    L.counters = (uint32_t *)(a1 + o_counters) + (size_t)k * kCounters;
+    L.vcnt = (uint32_t VL_GLOBAL *)(a1 + off[k].vcnt); L.vcur = (uint32_t VL_GLOBAL *)(a1 + off[k].vcur);
+    L.use = (uint32_t VL_GLOBAL *)(a1 + off[k].use); L.def = (uint32_t VL_GLOBAL *)(a1 + off[k].def);
+    L.live_in = (uint32_t VL_GLOBAL *)(a1 + off[k].in); L.live_out = (uint32_t VL_GLOBAL *)(a1 + off[k].out);
+    L.seed_off = (uint32_t VL_GLOBAL *)(a1 + off[k].seed_off); L.seed_cur = (uint32_t VL_GLOBAL *)(a1 + off[k].seed_cur);
+    L.blk_live = (uint32_t VL_GLOBAL *)(a1 + off[k].blk_live);
+    L.vocc_tmp = (uint32_t VL_GLOBAL *)(a1 + off[k].tmp); L.vocc = (uint32_t VL_GLOBAL *)(a1 + off[k].vocc);
+    L.ent_instr = (uint32_t VL_GLOBAL *)(a1 + off[k].ent_instr); L.ent_info = (uint8_t VL_GLOBAL *)(a1 + off[k].ent_info);
+    L.first = (uint32_t VL_GLOBAL *)(a1 + off[k].first); L.prev_occ = (uint32_t VL_GLOBAL *)(a1 + off[k].prev);
+    L.occ_role = (uint8_t VL_GLOBAL *)(a1 + off[k].role); L.occ_kill = (uint8_t VL_GLOBAL *)(a1 + off[k].kill);
+    L.item_off = (uint32_t VL_GLOBAL *)(a1 + off[k].item); L.seg_off = (uint32_t VL_GLOBAL *)(a1 + off[k].seg_off);
+    L.hull = (uint32_t VL_GLOBAL *)(a1 + off[k].hull); L.long_queue = (uint32_t VL_GLOBAL *)(a1 + off[k].queue);
+    L.ent_seg = (uint32_t VL_GLOBAL *)(a1 + off[k].ent_seg);
+    L.chk = (uint64_t VL_GLOBAL *)(a1 + off[k].chk); L.evt_cut = (uint32_t VL_GLOBAL *)(a1 + off[k].evt_cut);
+    L.bitmap = (uint32_t VL_GLOBAL *)nullptr;
+    L.counters = (uint32_t VL_GLOBAL *)(a1 + o_counters) + (size_t)k * kCounters;
     mir_ptrs[k] = mirs[k]->dev;
   }
   batch->dev_mirs = (const DevMir **)(a1 + o_mirs);
@@ -911,10 +912,10 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
   char *a2 = (char *)batch->arena2;
   for (uint32_t k = 0; k < n; ++k) {
     DevLive &L = h[k];
-    L.plan = (uint2 *)(a2 + off2[k].plan); L.seeds = (uint2 *)(a2 + off2[k].seeds);
-    L.seg = (uint32_t *)(a2 + off2[k].seg); L.tile_range = (uint32_t *)(a2 + off2[k].range);
-    L.tile_live = dense ? (uint32_t *)(a2 + off2[k].tile_live) : nullptr;
-    L.live_after = dense ? (uint32_t *)(a2 + off2[k].dense) : nullptr;
+    L.plan = (uint64_t VL_GLOBAL *)(a2 + off2[k].plan); L.seeds = (uint64_t VL_GLOBAL *)(a2 + off2[k].seeds);
+    L.seg = (uint32_t VL_GLOBAL *)(a2 + off2[k].seg); L.tile_range = (uint32_t VL_GLOBAL *)(a2 + off2[k].range);
+    L.tile_live = dense ? (uint32_t VL_GLOBAL *)(a2 + off2[k].tile_live) : (uint32_t VL_GLOBAL *)nullptr;
+    L.live_after = dense ? (uint32_t VL_GLOBAL *)(a2 + off2[k].dense) : (uint32_t VL_GLOBAL *)nullptr;
   }
   memcpy(batch->stage_b, h.data(), (size_t)n * sizeof(DevLive));
   e = hipMemcpyAsync(a1 + o_lives, batch->stage_b, (size_t)n * sizeof(DevLive), hipMemcpyHostToDevice, stream);
@@ -970,7 +971,8 @@ extern "C" int32_t vl_live_get(const vl_live *l, vl_live_view *v) {
   v->n_seg = l->h.n_seg; v->n_tile = l->h.T; v->tile_len = l->h.tile_len;
   v->plan_len = l->h.plan_len + m.O;   // occupancy events + one check per occurrence
   v->sweeps = l->batch->host_counters[(size_t)l->index * kCounters + kCtrSweeps];
-  v->live_in = l->h.live_in; v->live_out = l->h.live_out; v->live_after = l->h.live_after;
-  v->occ_kill = l->h.occ_kill; v->seg_off = l->h.seg_off; v->seg = l->h.seg; v->hull = l->h.hull;
+  v->live_in = (const uint32_t *)l->h.live_in; v->live_out = (const uint32_t *)l->h.live_out;
+  v->live_after = (const uint32_t *)l->h.live_after; v->occ_kill = (const uint8_t *)l->h.occ_kill;
+  v->seg_off = (const uint32_t *)l->h.seg_off; v->seg = (const uint32_t *)l->h.seg; v->hull = (const uint32_t *)l->h.hull;
   return VL_OK;
 }

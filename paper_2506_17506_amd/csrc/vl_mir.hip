@@ -127,15 +127,15 @@ extern "C" int32_t vl_mir_create(const vl_mir_desc *d, vl_mir **out) {
 
   vl::DevMir &h = m->h;
   h.N = N; h.V = V; h.B = B; h.O = O; h.C = d->n_class; h.E = E; h.W = (V + 31) / 32;
-  h.blk_start = (const uint32_t *)(base + o_blk);
-  h.succ_off = (const uint32_t *)(base + o_soff);
-  h.succ = (const uint32_t *)(base + o_succ);
-  h.occ_off = (const uint32_t *)(base + o_ooff);
-  h.occ_vreg = (const uint32_t *)(base + o_ov);
-  h.occ_instr = (const uint32_t *)(base + o_oi);
-  h.instr_blk = (const uint32_t *)(base + o_ib);
-  h.vattr = (const uint32_t *)(base + o_va);
-  h.occ_flags = (const uint8_t *)(base + o_of);
+  h.blk_start = (const uint32_t VL_GLOBAL *)(base + o_blk);
+  h.succ_off = (const uint32_t VL_GLOBAL *)(base + o_soff);
+  h.succ = (const uint32_t VL_GLOBAL *)(base + o_succ);
+  h.occ_off = (const uint32_t VL_GLOBAL *)(base + o_ooff);
+  h.occ_vreg = (const uint32_t VL_GLOBAL *)(base + o_ov);
+  h.occ_instr = (const uint32_t VL_GLOBAL *)(base + o_oi);
+  h.instr_blk = (const uint32_t VL_GLOBAL *)(base + o_ib);
+  h.vattr = (const uint32_t VL_GLOBAL *)(base + o_va);
+  h.occ_flags = (const uint8_t VL_GLOBAL *)(base + o_of);
   uint32_t words = 0;
   for (uint32_t c = 0; c < d->n_class; ++c) {
     h.class_size[c] = d->class_size[c];

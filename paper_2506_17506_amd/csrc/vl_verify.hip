@@ -186,12 +186,11 @@ __global__ __launch_bounds__(256) void k_walk(const DevJob *__restrict__ jobs, u
   const DevMir VL_GLOBAL &m = *as_global(J.mir);
   const DevLive VL_GLOBAL &L = *as_global(J.live);
   // arrays of the kernel and of its analysis, as global pointers
-  const auto g_occ_off = as_global(m.occ_off), g_occ_instr = as_global(m.occ_instr);
-  const auto g_prev_occ = as_global(L.prev_occ), g_evt_cut = as_global(L.evt_cut);
-  const auto g_seed_off = as_global(L.seed_off), g_tile_range = as_global(L.tile_range);
+  const auto g_occ_off = m.occ_off, g_occ_instr = m.occ_instr;
+  const auto g_prev_occ = L.prev_occ, g_evt_cut = L.evt_cut;
+  const auto g_seed_off = L.seed_off, g_tile_range = L.tile_range;
   // 8-byte stream entries are read as one 64-bit word: x in the low half, y in the high half
-  const auto g_chk = as_global((const uint64_t *)L.chk), g_plan = as_global((const uint64_t *)L.plan),
-             g_seeds = as_global((const uint64_t *)L.seeds);
+  const uint64_t VL_GLOBAL *g_chk = L.chk, *g_plan = L.plan, *g_seeds = L.seeds;
   const uint32_t has_reserved = m.has_reserved;
   const uint32_t local = blockIdx.x - J.unit_base;
   const uint32_t tile = local / J.n_groups, group = local % J.n_groups;
@@ -409,7 +408,7 @@ __global__ __launch_bounds__(256) void k_walk(const DevJob *__restrict__ jobs, u
   if (w.tid < w.nrows && vl_lds[w.keys + w.tid] != kKeyOk) atomicMin(&J.out[row0 + w.tid].status, vl_lds[w.keys + w.tid]);
 }
 
-__device__ inline uint32_t bad_bits(const DevMir &m, uint32_t attr, uint32_t p) {
+__device__ inline uint32_t bad_bits(const DevMir VL_GLOBAL &m, uint32_t attr, uint32_t p) {
   const uint32_t cls = attr_class(attr), width = attr_width(attr), align = attr_align(attr);
   uint32_t bad = 0;
   if (p + width > m.class_size[cls]) bad |= VL_BAD_BOUNDS;
@@ -426,8 +425,8 @@ __global__ void k_finalize(const DevJob *__restrict__ jobs) {
   const DevJob &J = jobs[blockIdx.y];
   uint32_t k = blockIdx.x * blockDim.x + threadIdx.x;
   if (k >= J.K) return;
-  const DevMir &m = *J.mir;
-  const DevLive &L = *J.live;
+  const DevMir VL_GLOBAL &m = *as_global(J.mir);
+  const DevLive VL_GLOBAL &L = *as_global(J.live);
   const uint32_t key = J.out[k].status;
   vl_result r = {VL_STATUS_OK, 0, 0, 0};
   if (key != kKeyOk) {
@@ -449,7 +448,7 @@ __global__ void k_finalize(const DevJob *__restrict__ jobs) {
   J.out[k] = r;
 }
 
-__device__ inline uint32_t lower_bound(const uint32_t *a, uint32_t lo, uint32_t hi, uint32_t key) {
+template <class P> __device__ inline uint32_t lower_bound(P a, uint32_t lo, uint32_t hi, uint32_t key) {
   while (lo < hi) {
     uint32_t mid = (lo + hi) >> 1;
     if (a[mid] < key) lo = mid + 1; else hi = mid;
@@ -458,7 +457,7 @@ __device__ inline uint32_t lower_bound(const uint32_t *a, uint32_t lo, uint32_t 
 }
 
 // is v in P(i) = live_after(i) + defs(i)?
-__device__ inline bool occupied_at(const DevMir &m, const DevLive &L, uint32_t v, uint32_t i) {
+__device__ inline bool occupied_at(const DevMir VL_GLOBAL &m, const DevLive VL_GLOBAL &L, uint32_t v, uint32_t i) {
   const uint32_t lo = L.vcnt[v], hi = L.vcnt[v + 1];
   if (lo == hi) return false;
   const uint32_t b = m.instr_blk[i];
@@ -479,8 +478,8 @@ __global__ __launch_bounds__(256) void k_resolve(const DevJob *__restrict__ jobs
   const DevJob &J = jobs[blockIdx.y];
   const uint32_t k = blockIdx.x;
   if (k >= J.K || J.out[k].status != VL_STATUS_SAFETY) return;
-  const DevMir &m = *J.mir;
-  const DevLive &L = *J.live;
+  const DevMir VL_GLOBAL &m = *as_global(J.mir);
+  const DevLive VL_GLOBAL &L = *as_global(J.live);
   const uint16_t *row = J.cand + (uint64_t)k * J.ld;
   const uint32_t i = J.out[k].where;
   __shared__ unsigned long long best;
