@@ -72,27 +72,35 @@ __global__ __launch_bounds__(1024) void k_scan(MIRS) {
   DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.x]);
   uint32_t VL_GLOBAL *p = kWhich == kScanVreg ? L.vcnt : kWhich == kScanItems ? L.item_off : kWhich == kScanSeg ? L.ent_seg : L.seed_off;
   const uint32_t n = kWhich == kScanVreg ? m.V : kWhich == kScanItems ? m.N + m.B : kWhich == kScanSeg ? m.O : L.T;
-  __shared__ uint32_t part[1024];
-  const uint32_t tid = threadIdx.x;
-  const uint32_t chunk = (n + 1023u) / 1024u;
-  const uint32_t lo = min(n, tid * chunk), hi = min(n, lo + chunk);
+  // Each of the 16 wavefronts owns a contiguous sixteenth of the array and walks it 64
+  // elements at a time (coalesced): first to total its part, then, once the parts'
+  // totals are prefixed, to write the exclusive sums.
+  __shared__ uint32_t part[16];
+  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+  const uint32_t per = ((n + 15u) / 16u + 63u) & ~63u;
+  const uint32_t lo = min(n, wave * per), hi = min(n, lo + per);
   uint32_t sum = 0;
-  for (uint32_t i = lo; i < hi; ++i) sum += p[i];
-  part[tid] = sum;
+  for (uint32_t i = lo + lane; i < hi; i += 64) sum += p[i];
+  for (int d = 32; d >= 1; d >>= 1) sum += (uint32_t)__shfl_xor((int)sum, d, 64);
+  if (lane == 0) part[wave] = sum;
   __syncthreads();
-  for (uint32_t d = 1; d < 1024; d <<= 1) {
-    uint32_t t = tid >= d ? part[tid - d] : 0;
-    __syncthreads();
-    part[tid] += t;
-    __syncthreads();
+  uint32_t base = 0, total = 0;
+  for (uint32_t k = 0; k < 16; ++k) {
+    if (k < wave) base += part[k];
+    total += part[k];
   }
-  uint32_t base = part[tid] - sum;
-  for (uint32_t i = lo; i < hi; ++i) {
-    uint32_t x = p[i];
-    p[i] = base;
-    base += x;
+  for (uint32_t i0 = lo; i0 < hi; i0 += 64) {
+    const uint32_t i = i0 + lane;
+    const uint32_t x = i < hi ? p[i] : 0u;
+    uint32_t incl = x;
+    for (int d = 1; d < 64; d <<= 1) {
+      const uint32_t y = (uint32_t)__shfl_up((int)incl, d, 64);
+      if ((int)lane >= d) incl += y;
+    }
+    if (i < hi) p[i] = base + incl - x;
+    base += (uint32_t)__shfl((int)incl, 63, 64);
   }
-  if (tid == 1023) p[n] = part[1023];
+  if (threadIdx.x == 0) p[n] = total;
 }
 
 // Places each occurrence into its vreg's range (order inside a range is fixed later).

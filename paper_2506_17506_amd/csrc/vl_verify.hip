@@ -499,6 +499,8 @@ __global__ __launch_bounds__(256) void k_resolve(const DevJob *__restrict__ jobs
   __syncthreads();
   unsigned long long mine = ~0ull;
   for (uint32_t x = threadIdx.x; x < m.V; x += blockDim.x) {
+    // cheap reject first: i outside the hull of x (coalesced reads), then the exact test
+    if (i < L.hull[2 * x] || i >= L.hull[2 * x + 1]) continue;
     if (!occupied_at(m, L, x, i)) continue;
     const uint32_t ax = m.vattr[x], px = row[L.first[x]], wx = attr_width(ax);
     for (uint32_t t = 0; t < nd; ++t) {
