@@ -580,37 +580,81 @@ __global__ void k_seg_off(MIRS) {
 }
 
 // ---- 5c. tile live-ins ------------------------------------------------------------------
-// Tile t starts at instruction t * tile_len.  Its seed is live_before of that instruction:
-// v is in it iff the first mention of v at or after the tile start, within the block,
-// reads v, or (no such mention) v is in the block's live-out.  One lane per vreg looks
-// only at the tile starts between its first and last point of interest: a value live
-// before `at` is occupied at `at` or at `at - 1`, or is read (and dies) at `at` itself,
-// so `at` lies within the hull widened to the first and last mention.
-template <bool kFill>
-__global__ void k_seed(MIRS) {
+// Tile t starts at instruction t * tile_len; its seed is the set live before that
+// instruction.  Replaying every occupancy event of the program from the start (nothing is
+// live into the entry) gives exactly that set, and every event flips one bit, so the seed
+// of tile t is the exclusive-or of all flips of the tiles before it.
+// k_tile_delta: one workgroup per tile XORs the tile's flips into an LDS row: the events
+// of its instructions (an occurrence with an odd number of roles flips its vreg) and of
+// the block boundaries right after its instructions (live-out of the earlier block XOR
+// live-in of the later one).
+__global__ __launch_bounds__(256) void k_tile_delta(MIRS) {
   const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
   DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
-  const uint32_t v = blockIdx.x * blockDim.x + threadIdx.x;
-  if (v >= m.V) return;
-  const uint32_t lo = L.vcnt[v], hi = L.vcnt[v + 1];
-  const uint32_t h0 = L.hull[2 * v], h1 = L.hull[2 * v + 1];
-  if (lo == hi) return;
-  const uint32_t r0 = h1 > h0 ? min(h0, L.ent_instr[lo]) : L.ent_instr[lo];
-  const uint32_t r1 = h1 > h0 ? max(h1, L.ent_instr[hi - 1]) : L.ent_instr[hi - 1];
-  // tile starts `at` with r0 <= at <= r1 (tile 0 starts with nothing live)
-  for (uint32_t t = max(1u, (r0 + L.tile_len - 1) / L.tile_len); t < L.T && t * L.tile_len <= r1; ++t) {
-    const uint32_t at = t * L.tile_len, b = m.instr_blk[at];
-    const uint32_t x = lower_bound(L.ent_instr, lo, hi, at);
-    bool live;
-    if (x < hi && L.ent_instr[x] < m.blk_start[b + 1]) live = (L.ent_info[x] & kEntHasUse) != 0;
-    else live = bit_get(L.live_out + (size_t)b * m.W, v);
-    if (!live) continue;
-    if (!kFill) { atomicAdd(&L.seed_off[t], 1u); continue; }
-    const uint32_t src = x > lo ? L.vocc[x - 1] : L.vocc[x];
-    const uint32_t pos = L.seed_off[t] + atomicAdd(&L.seed_cur[t], 1u);
-    L.seeds[pos] = entry_pack(src | ((kPlanBirth | kPlanPost) << 24), 0xFFFFu | (m.vattr[v] << 16));
-    if (L.dense) atomicOr(&L.tile_live[(size_t)t * m.W + (v >> 5)], 1u << (v & 31));
+  extern __shared__ uint32_t row[];
+  const uint32_t t = blockIdx.x;
+  if (t >= L.T) return;
+  const uint32_t W = m.W, i0 = t * L.tile_len, i1 = min(m.N, i0 + L.tile_len);
+  for (uint32_t w = threadIdx.x; w < W; w += 256) row[w] = 0;
+  __syncthreads();
+  for (uint32_t o = m.occ_off[i0] + threadIdx.x; o < m.occ_off[i1]; o += 256) {
+    if (__popc(L.occ_role[o] & (kRolePreKill | kRoleTestSet | kRolePostKill)) & 1) {
+      const uint32_t v = m.occ_vreg[o];
+      atomicXor(&row[v >> 5], 1u << (v & 31));
+    }
   }
+  // boundaries b whose last earlier instruction (blk_start[b] - 1) lies in this tile
+  const uint32_t b_lo = m.instr_blk[i0] + 1, b_hi = m.instr_blk[i1 - 1] + 1;   // blocks starting in (i0, i1]
+  for (uint32_t b = b_lo; b <= b_hi && b < m.B; ++b) {
+    if (m.blk_start[b] - 1 < i0 || m.blk_start[b] - 1 >= i1) continue;
+    for (uint32_t w = threadIdx.x; w < W; w += 256)
+      atomicXor(&row[w], L.live_out[(size_t)(b - 1) * W + w] ^ L.live_in[(size_t)b * W + w]);
+  }
+  __syncthreads();
+  for (uint32_t w = threadIdx.x; w < W; w += 256) L.tile_live[(size_t)t * W + w] = row[w];
+}
+
+// exclusive prefix-XOR over the tiles, one bitset word per lane
+__global__ void k_tile_prefix(MIRS) {
+  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
+  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
+  const uint32_t w = blockIdx.x * blockDim.x + threadIdx.x;
+  if (w >= m.W) return;
+  uint32_t acc = 0;
+  for (uint32_t t = 0; t < L.T; ++t) {
+    const uint32_t d = L.tile_live[(size_t)t * m.W + w];
+    L.tile_live[(size_t)t * m.W + w] = acc;
+    acc ^= d;
+  }
+}
+
+// One wavefront per tile lists the members of its seed row as occupy-without-test entries
+// whose register is taken from the nearest earlier occurrence of the vreg.
+template <bool kFill>
+__global__ __launch_bounds__(64) void k_seed(MIRS) {
+  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
+  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
+  const uint32_t t = blockIdx.x, lane = threadIdx.x;
+  if (t >= L.T) return;
+  const uint32_t W = m.W, at = t * L.tile_len;
+  uint32_t total = 0;
+  const uint32_t base = kFill ? L.seed_off[t] : 0;
+  for (uint32_t w0 = 0; w0 < W; w0 += 64) {
+    const uint32_t w = w0 + lane;
+    uint32_t bits = (w < W && t > 0) ? L.tile_live[(size_t)t * W + w] : 0u;
+    const uint32_t c = __popc(bits), incl = wave_incl_scan(c);
+    if (kFill) {
+      uint32_t pos = base + total + incl - c;
+      while (bits) {
+        const uint32_t v = w * 32 + __ffs(bits) - 1;
+        bits &= bits - 1;
+        L.seeds[pos++] = entry_pack(source_occurrence(L, v, at) | ((kPlanBirth | kPlanPost) << 24),
+                                    0xFFFFu | (m.vattr[v] << 16));
+      }
+    }
+    total += __shfl(incl, 63, 64);
+  }
+  if (!kFill && lane == 0) L.seed_off[t] = total;
 }
 
 __global__ void k_collect(MIRS, uint32_t n) {
@@ -770,7 +814,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
   // ---- arena 1 layout: [zeroed zone | counters | rest | device tables] ----
   std::vector<DevLive> h(n);
   struct Off1 { size_t vcnt, vcur, use, def, in, seed_off, seed_cur, blk_live, out, tmp, vocc, ent_instr, ent_info, first, prev,
-                role, kill, item, seg_off, hull, queue, bitmap, ent_seg, chk, evt_cut; };
+                role, kill, item, seg_off, hull, queue, bitmap, ent_seg, chk, evt_cut, tile_live; };
   std::vector<Off1> off(n);
   Bump bump;
   uint32_t maxO = 1, maxV = 1, maxN = 1, maxB = 1, maxW = 1, maxT = 1;
@@ -802,6 +846,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     off[k].queue = bump.take((size_t)(m.V + 1) * 4);
     off[k].ent_seg = bump.take((O1 + 1) * 4);
     off[k].chk = bump.take(O1 * 8);
+    off[k].tile_live = bump.take((size_t)h[k].T * std::max(1u, m.W) * 4);
     off[k].evt_cut = bump.take(((size_t)(m.O + 63) / 64 + 2) * 4);
     off[k].bitmap = 0;
   }
@@ -829,7 +874,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     L.item_off = (uint32_t VL_GLOBAL *)(a1 + off[k].item); L.seg_off = (uint32_t VL_GLOBAL *)(a1 + off[k].seg_off);
     L.hull = (uint32_t VL_GLOBAL *)(a1 + off[k].hull); L.long_queue = (uint32_t VL_GLOBAL *)(a1 + off[k].queue);
     L.ent_seg = (uint32_t VL_GLOBAL *)(a1 + off[k].ent_seg);
-    L.chk = (uint64_t VL_GLOBAL *)(a1 + off[k].chk); L.evt_cut = (uint32_t VL_GLOBAL *)(a1 + off[k].evt_cut);
+    L.chk = (uint64_t VL_GLOBAL *)(a1 + off[k].chk); L.tile_live = (uint32_t VL_GLOBAL *)(a1 + off[k].tile_live); L.evt_cut = (uint32_t VL_GLOBAL *)(a1 + off[k].evt_cut);
     L.bitmap = (uint32_t VL_GLOBAL *)nullptr;
     L.counters = (uint32_t VL_GLOBAL *)(a1 + o_counters) + (size_t)k * kCounters;
     mir_ptrs[k] = mirs[k]->dev;
@@ -879,7 +924,9 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
   k_seg<false><<<grid1(maxO, TB, n), TB, 0, stream>>>(dm, dl);
   k_scan<kScanSeg><<<n, 1024, 0, stream>>>(dm, dl);
   k_seg_off<<<grid1(maxV + 1, TB, n), TB, 0, stream>>>(dm, dl);
-  if (maxT > 1) k_seed<false><<<grid1(maxV, TB, n), TB, 0, stream>>>(dm, dl);
+  k_tile_delta<<<dim3(maxT, n), 256, (size_t)maxW * 4, stream>>>(dm, dl);
+  k_tile_prefix<<<grid1(maxW, 64, n), 64, 0, stream>>>(dm, dl);
+  k_seed<false><<<dim3(maxT, n), 64, 0, stream>>>(dm, dl);
   k_scan<kScanSeed><<<n, 1024, 0, stream>>>(dm, dl);
   k_collect<<<(n + 63) / 64, 64, 0, stream>>>(dm, dl, n);
   e = hipGetLastError();
@@ -891,14 +938,13 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
 
   // ---- arena 2: sized from the counts ----
   Bump b2;
-  struct Off2 { size_t plan, seeds, seg, range, tile_live, dense; };
+  struct Off2 { size_t plan, seeds, seg, range, dense; };
   std::vector<Off2> off2(n);
   size_t zero2_lo = 0, zero2_hi = 0;
   if (dense) {
     zero2_lo = b2.off;
     for (uint32_t k = 0; k < n; ++k) {
       const DevMir &m = mirs[k]->h;
-      off2[k].tile_live = b2.take((size_t)h[k].T * std::max(1u, m.W) * 4);
       off2[k].dense = b2.take((size_t)m.N * std::max(1u, m.W) * 4);
     }
     zero2_hi = b2.off;
@@ -922,7 +968,6 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     DevLive &L = h[k];
     L.plan = (uint64_t VL_GLOBAL *)(a2 + off2[k].plan); L.seeds = (uint64_t VL_GLOBAL *)(a2 + off2[k].seeds);
     L.seg = (uint32_t VL_GLOBAL *)(a2 + off2[k].seg); L.tile_range = (uint32_t VL_GLOBAL *)(a2 + off2[k].range);
-    L.tile_live = dense ? (uint32_t VL_GLOBAL *)(a2 + off2[k].tile_live) : (uint32_t VL_GLOBAL *)nullptr;
     L.live_after = dense ? (uint32_t VL_GLOBAL *)(a2 + off2[k].dense) : (uint32_t VL_GLOBAL *)nullptr;
   }
   memcpy(batch->stage_b, h.data(), (size_t)n * sizeof(DevLive));
@@ -932,7 +977,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
   k_plan_fill<<<grid1(maxN, TB, n), TB, 0, stream>>>(dm, dl);
   k_boundary<true><<<dim3(maxB, n), 64, 0, stream>>>(dm, dl);
   k_seg<true><<<grid1(maxO, TB, n), TB, 0, stream>>>(dm, dl);
-  if (maxT > 1) k_seed<true><<<grid1(maxV, TB, n), TB, 0, stream>>>(dm, dl);
+  k_seed<true><<<dim3(maxT, n), 64, 0, stream>>>(dm, dl);
   k_tile_range<<<grid1(maxT, 64, n), 64, 0, stream>>>(dm, dl);
   if (dense) {
     k_dense_delta<<<grid1(maxN + maxB, TB, n), TB, 0, stream>>>(dm, dl);
