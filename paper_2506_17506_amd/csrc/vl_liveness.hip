@@ -216,13 +216,6 @@ __global__ __launch_bounds__(256) void k_sort_long(MIRS) {
   }
 }
 
-__global__ void k_ent(MIRS) {
-  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
-  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
-  uint32_t e = blockIdx.x * blockDim.x + threadIdx.x;
-  if (e < m.O) L.ent_instr[e] = m.occ_instr[L.vocc[e]];
-}
-
 // ---- 2. block summaries ---------------------------------------------------------------
 // def[b]: vregs written in b.  use[b]: vregs whose first mention in b reads them
 // (an instruction reads before it writes).
@@ -232,7 +225,10 @@ __global__ void k_summary(MIRS) {
   uint32_t e = blockIdx.x * blockDim.x + threadIdx.x;
   uint32_t b = kNone, w = 0, dbits = 0, ubits = 0;
   if (e < m.O) {
-    const uint32_t o = L.vocc[e], v = m.occ_vreg[o], i = L.ent_instr[e];
+    // also records the instruction of each sorted entry for the kernels that follow;
+    // neighbours are looked up through the occurrence list here
+    const uint32_t o = L.vocc[e], v = m.occ_vreg[o], i = m.occ_instr[o];
+    L.ent_instr[e] = i;
     const uint32_t fl = m.occ_flags[o], bit = 1u << (v & 31);
     b = m.instr_blk[i];
     w = v >> 5;
@@ -240,8 +236,8 @@ __global__ void k_summary(MIRS) {
     if (fl & VL_OCC_USE) {
       const uint32_t lo = L.vcnt[v];
       uint32_t gs = e;
-      while (gs > lo && L.ent_instr[gs - 1] == i) --gs;
-      if (gs == lo || m.instr_blk[L.ent_instr[gs - 1]] != b) ubits = bit;
+      while (gs > lo && m.occ_instr[L.vocc[gs - 1]] == i) --gs;
+      if (gs == lo || m.instr_blk[m.occ_instr[L.vocc[gs - 1]]] != b) ubits = bit;
     }
   }
   // entries are sorted by vreg, then instruction: neighbours in a wavefront mostly hit
@@ -363,24 +359,19 @@ __global__ void k_events(MIRS) {
   }
   if (e == lo) role |= kRoleFirst;
   L.occ_role[o] = role;
-  L.prev_occ[o] = e > lo ? L.vocc[e - 1] : kNone;
+  const uint32_t prev = e > lo ? L.vocc[e - 1] : kNone;
+  L.prev_occ[o] = prev;
+  // the occurrence's check entry, and its events counted into its instruction's item
+  L.chk[o] = entry_pack(o | (((role & kRoleFirst) ? kPlanFirst : kPlanChk) << 24),
+                        (prev == kNone ? 0u : min(o - prev, 0xFFFFu)) | (m.vattr[v] << 16));
+  const uint32_t n_evt = __popc(role & (kRolePreKill | kRoleTestSet | kRolePostKill));
+  if (n_evt) atomicAdd(&L.item_off[i + b + 1], n_evt);
   L.ent_info[e] = (uint8_t)((la ? kEntLiveAfter : 0) | (has_use ? kEntHasUse : 0) | (has_def ? kEntHasDef : 0) |
                             (e == gs ? kEntGroupStart : 0));
 }
 
 // ---- 5a. event stream -----------------------------------------------------------------
 __device__ inline uint32_t item_of_instr(const DevMir VL_GLOBAL &m, uint32_t i) { return i + m.instr_blk[i] + 1; }
-
-__global__ void k_item_count(MIRS) {
-  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
-  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
-  uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= m.N) return;
-  uint32_t cnt = 0;
-  for (uint32_t o = m.occ_off[i]; o < m.occ_off[i + 1]; ++o)
-    cnt += __popc(L.occ_role[o] & (kRolePreKill | kRoleTestSet | kRolePostKill));
-  L.item_off[item_of_instr(m, i)] = cnt;
-}
 
 __device__ inline uint32_t wave_incl_scan(uint32_t x) {
   for (int d = 1; d < 64; d <<= 1) {
@@ -456,19 +447,6 @@ __global__ void k_plan_fill(MIRS) {
     if (L.occ_role[o] & kRoleTestSet) L.plan[pos++] = entry(o, kPlanSet);
   for (uint32_t o = o0; o < o1; ++o)
     if (L.occ_role[o] & kRolePostKill) L.plan[pos++] = entry(o, kPlanClr | kPlanPost);
-}
-
-// The check stream has one entry per occurrence, in occurrence order: compare with the
-// previous occurrence of the vreg, or (first occurrence) test realizability.
-__global__ void k_chk_fill(MIRS) {
-  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
-  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
-  uint32_t o = blockIdx.x * blockDim.x + threadIdx.x;
-  if (o >= m.O) return;
-  const uint32_t prev = L.prev_occ[o];
-  const uint32_t delta = prev == kNone ? 0u : min(o - prev, 0xFFFFu);
-  const uint32_t flags = (L.occ_role[o] & kRoleFirst) ? kPlanFirst : kPlanChk;
-  L.chk[o] = entry_pack(o | (flags << 24), delta | (m.vattr[m.occ_vreg[o]] << 16));
 }
 
 // evt_cut[c] = index of the first event of the first item whose operands end in chunk c or
@@ -636,7 +614,7 @@ __global__ __launch_bounds__(64) void k_seed(MIRS) {
   DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
   const uint32_t t = blockIdx.x, lane = threadIdx.x;
   if (t >= L.T) return;
-  const uint32_t W = m.W, at = t * L.tile_len;
+  const uint32_t W = m.W;
   uint32_t total = 0;
   const uint32_t base = kFill ? L.seed_off[t] : 0;
   for (uint32_t w0 = 0; w0 < W; w0 += 64) {
@@ -648,13 +626,24 @@ __global__ __launch_bounds__(64) void k_seed(MIRS) {
       while (bits) {
         const uint32_t v = w * 32 + __ffs(bits) - 1;
         bits &= bits - 1;
-        L.seeds[pos++] = entry_pack(source_occurrence(L, v, at) | ((kPlanBirth | kPlanPost) << 24),
-                                    0xFFFFu | (m.vattr[v] << 16));
+        L.seeds[pos++] = entry_pack(v, t);   // completed by k_seed_src
       }
     }
     total += __shfl(incl, 63, 64);
   }
   if (!kFill && lane == 0) L.seed_off[t] = total;
+}
+
+// completes each seed entry: the register comes from the nearest earlier occurrence
+__global__ void k_seed_src(MIRS) {
+  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
+  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
+  const uint32_t k = blockIdx.x * blockDim.x + threadIdx.x;
+  if (k >= L.n_seed) return;
+  const uint64_t raw = L.seeds[k];
+  const uint32_t v = (uint32_t)raw, t = (uint32_t)(raw >> 32);
+  L.seeds[k] = entry_pack(source_occurrence(L, v, t * L.tile_len) | ((kPlanBirth | kPlanPost) << 24),
+                          0xFFFFu | (m.vattr[v] << 16));
 }
 
 __global__ void k_collect(MIRS, uint32_t n) {
@@ -829,6 +818,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     off[k].use = bump.take(bw); off[k].def = bump.take(bw); off[k].in = bump.take(bw);
     off[k].seed_off = bump.take((size_t)(T + 1) * 4); off[k].seed_cur = bump.take((size_t)(T + 1) * 4);
     off[k].blk_live = bump.take((size_t)(m.V + 1) * ((m.B + 31) / 32) * 4);
+    off[k].item = bump.take((size_t)(m.N + m.B + 1) * 4);   // event counts are accumulated with atomics
     maxO = std::max(maxO, m.O); maxV = std::max(maxV, m.V); maxN = std::max(maxN, m.N);
     maxB = std::max(maxB, m.B); maxW = std::max(maxW, m.W); maxT = std::max(maxT, T);
   }
@@ -841,7 +831,6 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     off[k].tmp = bump.take(O1 * 4); off[k].vocc = bump.take(O1 * 4); off[k].ent_instr = bump.take(O1 * 4);
     off[k].ent_info = bump.take(O1); off[k].first = bump.take((size_t)(m.V + 1) * 4); off[k].prev = bump.take(O1 * 4);
     off[k].role = bump.take(O1); off[k].kill = bump.take(O1);
-    off[k].item = bump.take((size_t)(m.N + m.B + 1) * 4);
     off[k].seg_off = bump.take((size_t)(m.V + 1) * 4); off[k].hull = bump.take((size_t)(m.V + 1) * 8);
     off[k].queue = bump.take((size_t)(m.V + 1) * 4);
     off[k].ent_seg = bump.take((O1 + 1) * 4);
@@ -907,7 +896,6 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
   else k_place<false><<<slices, 1024, 0, stream>>>(dm, dl);
   k_sort_short<<<grid1(maxV, TB, n), TB, 0, stream>>>(dm, dl);
   k_sort_long<<<dim3(32, n), 256, 0, stream>>>(dm, dl);
-  k_ent<<<grid1(maxO, TB, n), TB, 0, stream>>>(dm, dl);
   k_summary<<<grid1(maxO, TB, n), TB, 0, stream>>>(dm, dl);
   {
     const size_t lds = (size_t)maxB * 64 * 3 * 4;
@@ -915,11 +903,9 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     else k_fixpoint<false><<<grid1(maxW, 64, n), 64, 0, stream>>>(dm, dl);
   }
   k_events<<<grid1(maxO, TB, n), TB, 0, stream>>>(dm, dl);
-  k_item_count<<<grid1(maxN, TB, n), TB, 0, stream>>>(dm, dl);
   k_boundary<false><<<dim3(maxB, n), 64, 0, stream>>>(dm, dl);
   k_scan<kScanItems><<<n, 1024, 0, stream>>>(dm, dl);
   k_evt_cut<<<grid1(maxO / 64 + 2, TB, n), TB, 0, stream>>>(dm, dl);
-  k_chk_fill<<<grid1(maxO, TB, n), TB, 0, stream>>>(dm, dl);
   k_blk_transpose<<<dim3((maxW + 63) / 64, maxB, n), 64, 0, stream>>>(dm, dl);
   k_seg<false><<<grid1(maxO, TB, n), TB, 0, stream>>>(dm, dl);
   k_scan<kScanSeg><<<n, 1024, 0, stream>>>(dm, dl);
@@ -939,6 +925,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
   // ---- arena 2: sized from the counts ----
   Bump b2;
   struct Off2 { size_t plan, seeds, seg, range, dense; };
+  uint32_t max_seed = 0;
   std::vector<Off2> off2(n);
   size_t zero2_lo = 0, zero2_hi = 0;
   if (dense) {
@@ -952,6 +939,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
   for (uint32_t k = 0; k < n; ++k) {
     const uint32_t *c = batch->host_counters + (size_t)k * kCounters;
     h[k].plan_len = c[kCtrPlanLen]; h[k].n_seg = c[kCtrSeg]; h[k].n_seed = c[kCtrSeed];
+    max_seed = std::max(max_seed, h[k].n_seed);
     off2[k].plan = b2.take((size_t)std::max(1u, h[k].plan_len) * 8);
     off2[k].seeds = b2.take((size_t)std::max(1u, h[k].n_seed) * 8);
     off2[k].seg = b2.take((size_t)std::max(1u, h[k].n_seg) * 8);
@@ -978,6 +966,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
   k_boundary<true><<<dim3(maxB, n), 64, 0, stream>>>(dm, dl);
   k_seg<true><<<grid1(maxO, TB, n), TB, 0, stream>>>(dm, dl);
   k_seed<true><<<dim3(maxT, n), 64, 0, stream>>>(dm, dl);
+  if (max_seed) k_seed_src<<<grid1(max_seed, TB, n), TB, 0, stream>>>(dm, dl);
   k_tile_range<<<grid1(maxT, 64, n), 64, 0, stream>>>(dm, dl);
   if (dense) {
     k_dense_delta<<<grid1(maxN + maxB, TB, n), TB, 0, stream>>>(dm, dl);
