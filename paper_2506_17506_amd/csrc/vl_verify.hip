@@ -232,20 +232,25 @@ __global__ __launch_bounds__(256) void k_walk(const DevJob *__restrict__ jobs, u
   __syncthreads();
 
   // ---- occupancy events (lane = candidate) ----
+  // Events are replayed in instruction order, so the first clash of a row is the one to
+  // report; after it the row's mask is no longer exact and its later clashes are ignored.
+  uint32_t alive = 0xFFFFFFFFu;
   auto event1 = [&](uint32_t ex, uint32_t ey) __attribute__((always_inline)) {   // any source: ring or global memory
     const uint32_t o = ex & 0xFFFFFFu, fl = ex >> 24, attr = ey >> 16;
     const uint32_t p = fetch(w, o);
     const Touch t = locate(w, attr, __builtin_amdgcn_readlane(cls_tab_v, attr_class(attr)), p);
     uint32_t hit = flip(t, attr_straddle(attr));
     if (!(fl & kPlanSet)) hit = 0;
+    hit &= alive;
     if (__any(hit != 0)) {
       const uint32_t i = g_occ_instr[o];
-      if (hit) key = min(key, kKeySafe | i);
+      if (hit) { key = min(key, kKeySafe | i); alive = 0; }
     }
   };
   constexpr int G = 8;   // events in flight: their LDS reads and atomics overlap
   const uint32_t my_ring = w.ring16 + w.row;
   const uint32_t my_occ = w.lane * 4;   // byte offset of this lane's column of mask words
+  char *const lds_bytes = reinterpret_cast<char *>(vl_lds);
   // A batch of up to 64 events is first decoded with one event per lane (everything that
   // does not depend on the candidate: ring offset, tuple mask, mask-word base and limit),
   // then replayed in order with one candidate per lane, eight events at a time: the eight
@@ -261,9 +266,10 @@ __global__ __launch_bounds__(256) void k_walk(const DevJob *__restrict__ jobs, u
       const uint32_t tab = (uint32_t)__shfl((int)cls_tab_v, (int)attr_class(attr), 64);
       const uint32_t F = tab & 0xFFFFu, wbase = tab >> 16;
       const uint32_t dx = w.lane >= cnt ? 0u : (width == 32 ? 0xFFFFFFFFu : ((1u << width) - 1u));   // tuple mask at bit 0
-      // ring offset (uint16 index) | last word of the class << 9 | tested << 13 | mask-word byte base << 16
-      const uint32_t dy = (o & (kRing - 1)) | (((F - 1u) >> 5) << 9) | ((fl & kPlanSet) ? (1u << 13) : 0u) |
-                          ((wbase * 256u) << 16);
+      // byte offset of the occurrence's ring slot | last word of the class << 16 | tested << 20 |
+      // first mask word of the class << 21
+      const uint32_t dy = ((o & (kRing - 1)) * (kRingStride * 2u)) | (((F - 1u) >> 5) << 16) |
+                          ((fl & kPlanSet) ? (1u << 20) : 0u) | (wbase << 21);
       const bool slow = w.lane < cnt && (!in_ring(w, o) || attr_straddle(attr));
       const uint64_t slow_mask = __ballot(slow);
       for (uint32_t g0 = 0; g0 < cnt; g0 += G) {
@@ -277,27 +283,27 @@ __global__ __launch_bounds__(256) void k_walk(const DevJob *__restrict__ jobs, u
         for (int t = 0; t < G; ++t) {   // lanes past cnt hold zeros: a zero mask flips nothing
           sx[t] = __builtin_amdgcn_readlane(dx, g0 + t);
           sy[t] = __builtin_amdgcn_readlane(dy, g0 + t);
-          p[t] = VL_LDS16[my_ring + (sy[t] & 0x1FFu) * kRingStride];
+          p[t] = *reinterpret_cast<const uint16_t *>(lds_bytes + my_ring * 2u + (sy[t] & 0xFFFFu));
         }
 #pragma unroll
         for (int t = 0; t < G; ++t) {
-          const uint32_t word = min(p[t] >> 5, (sy[t] >> 9) & 15u);
+          const uint32_t word = min(p[t] >> 5, (sy[t] >> 16) & 15u) + (sy[t] >> 21);
           msk[t] = sx[t] << (p[t] & 31u);
-          const uint32_t byte_addr = (word << 8) + my_occ + (sy[t] >> 16);
-          old[t] = __hip_atomic_fetch_xor(&vl_lds[byte_addr >> 2], msk[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+          old[t] = __hip_atomic_fetch_xor(reinterpret_cast<uint32_t *>(lds_bytes + ((word << 8) + my_occ)), msk[t],
+                                          __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
         }
         uint32_t any_hit = 0;
 #pragma unroll
         for (int t = 0; t < G; ++t) {
-          old[t] = (sy[t] & (1u << 13)) ? (old[t] & msk[t]) : 0u;
+          old[t] = (sy[t] & (1u << 20)) ? (old[t] & msk[t]) : 0u;
           any_hit |= old[t];
         }
-        if (__any(any_hit != 0)) {
+        if (__any((any_hit & alive) != 0)) {
 #pragma unroll
           for (int t = 0; t < G; ++t)
-            if (__any(old[t] != 0)) {
+            if (__any((old[t] & alive) != 0)) {
               const uint32_t i = g_occ_instr[__builtin_amdgcn_readlane(o, g0 + t)];
-              if (old[t]) key = min(key, kKeySafe | i);
+              if (old[t] & alive) { key = min(key, kKeySafe | i); alive = 0; }
             }
         }
       }
