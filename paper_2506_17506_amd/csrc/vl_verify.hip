@@ -28,7 +28,9 @@ using namespace vl;
 
 namespace {
 
-constexpr uint32_t kRing = 256;                 // occurrences kept per candidate in LDS
+// Occurrences kept per candidate in LDS: three chunks.  With two register classes a
+// workgroup then needs about 31 KB, so five workgroups share a compute unit's 160 KB.
+constexpr uint32_t kRing = 192;
 constexpr uint32_t kRingStride = 64 + 4;        // uint16 per occurrence: 64 rows + padding (136 bytes)
 constexpr uint32_t kChunk = 64;                 // occurrences staged per step (128 B per row)
 constexpr uint32_t kKeyOk = 0xFFFFFFFFu;
@@ -61,7 +63,7 @@ __global__ void k_init(const DevJob *__restrict__ jobs) {
 // ---- the candidate walk -----------------------------------------------------------------
 // A workgroup of 4 wavefronts takes up to 64 candidate rows of one kernel over one tile
 // (a range of instructions).  Occurrences are staged 64 at a time (one 128-byte line per
-// row, the next chunk already in flight) into an LDS ring [row][256 occurrences].  After
+// row, the next chunk already in flight) into an LDS ring [occurrence % 192][row].  After
 // each chunk
 //   * one wavefront replays the occupancy events that chunk releases, one candidate per
 //     lane, the lane's occupancy mask in LDS as [word][lane];
@@ -74,7 +76,7 @@ __global__ void k_init(const DevJob *__restrict__ jobs) {
 // access is a DS instruction rather than a flat one):
 //   [0, occ_words * 64)            occupancy masks [word][lane]
 //   [keys, keys + 64)              per-row violation keys
-//   [ring32, ...)                  the ring [occurrence & 255][row], addressed in uint16 from
+//   [ring32, ...)                  the ring [occurrence % 192][row], addressed in uint16 from
 //                                  ring16 = 2 * ring32; a lane of the check wavefronts reads four
 //                                  rows of one occurrence with one 8-byte read
 extern __shared__ uint32_t vl_lds[];
@@ -119,7 +121,7 @@ __device__ inline void store_chunk(Walk &w) {
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     const uint32_t r = h * 32 + (w.tid >> 3);
-    const uint32_t dst = w.ring16 + (c & (kRing - 1)) * kRingStride + r;
+    const uint32_t dst = w.ring16 + (c % kRing) * kRingStride + r;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       VL_LDS16[dst + (2 * j) * kRingStride] = (uint16_t)w.pre[h][j];
@@ -135,7 +137,7 @@ __device__ inline bool in_ring(const Walk &w, uint32_t o) {
 
 // value of occurrence o (uniform) in this lane's row
 __device__ inline uint32_t fetch(const Walk &w, uint32_t o) {
-  if (in_ring(w, o)) return VL_LDS16[w.ring16 + (o & (kRing - 1)) * kRingStride + w.row];
+  if (in_ring(w, o)) return VL_LDS16[w.ring16 + (o % kRing) * kRingStride + w.row];
   return w.rows[(uint64_t)w.row * w.ld + o];
 }
 
@@ -268,7 +270,7 @@ __global__ __launch_bounds__(256) void k_walk(const DevJob *__restrict__ jobs, u
       const uint32_t dx = w.lane >= cnt ? 0u : (width == 32 ? 0xFFFFFFFFu : ((1u << width) - 1u));   // tuple mask at bit 0
       // byte offset of the occurrence's ring slot | last word of the class << 16 | tested << 20 |
       // first mask word of the class << 21
-      const uint32_t dy = ((o & (kRing - 1)) * (kRingStride * 2u)) | (((F - 1u) >> 5) << 16) |
+      const uint32_t dy = ((o % kRing) * (kRingStride * 2u)) | (((F - 1u) >> 5) << 16) |
                           ((fl & kPlanSet) ? (1u << 20) : 0u) | (wbase << 21);
       const bool slow = w.lane < cnt && (!in_ring(w, o) || attr_straddle(attr));
       const uint64_t slow_mask = __ballot(slow);
@@ -338,8 +340,8 @@ __global__ __launch_bounds__(256) void k_walk(const DevJob *__restrict__ jobs, u
     // at one by one.
     typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
     const uint32_t amask2 = amask * 0x10001u, limit2 = min(limit, 0xFFFFu) * 0x10001u;
-    const uint32_t a_p = (w.ring16 + (o & (kRing - 1)) * kRingStride) >> 2;          // in 8-byte units
-    const uint32_t a_q = (w.ring16 + ((near ? prev : o) & (kRing - 1)) * kRingStride) >> 2;
+    const uint32_t a_p = (w.ring16 + (o % kRing) * kRingStride) >> 2;          // in 8-byte units
+    const uint32_t a_q = (w.ring16 + ((near ? prev : o) % kRing) * kRingStride) >> 2;
     const uint64_t *lds64 = reinterpret_cast<const uint64_t *>(vl_lds);
     auto wrong2 = [&](uint32_t pp, uint32_t qq) __attribute__((always_inline)) {
       const u16x2 mn = __builtin_elementwise_min(__builtin_bit_cast(u16x2, pp), __builtin_bit_cast(u16x2, limit2));
@@ -355,8 +357,8 @@ __global__ __launch_bounds__(256) void k_walk(const DevJob *__restrict__ jobs, u
       // rare: attribute row by row
       for (uint32_t qd = part; qd < n_quad; qd += 3) {
         for (uint32_t r = 4 * qd; r < min(w.nrows, 4 * qd + 4); ++r) {
-          const uint32_t pr = VL_LDS16[w.ring16 + (o & (kRing - 1)) * kRingStride + r];
-          const uint32_t qr = VL_LDS16[w.ring16 + ((near ? prev : o) & (kRing - 1)) * kRingStride + r];
+          const uint32_t pr = VL_LDS16[w.ring16 + (o % kRing) * kRingStride + r];
+          const uint32_t qr = VL_LDS16[w.ring16 + ((near ? prev : o) % kRing) * kRingStride + r];
           bool bad = (pr != qr) | ((pr & amask) != 0) | (pr > limit);
           if (generic) bad = unrealizable(m, attr, F, pr);
           if (__any(bad)) {
