@@ -65,6 +65,13 @@ constexpr uint32_t kPlanSet = 4u;    // test the range against occupancy, then o
 constexpr uint32_t kPlanClr = 8u;    // release the range
 constexpr uint32_t kPlanBirth = 16u; // occupy without testing (value becomes live at a boundary)
 constexpr uint32_t kPlanPost = 32u;  // the occurrence named is not at the event's own position
+constexpr uint32_t kPlanKeep = 64u;  // (chk) the next occurrence of the vreg is likely beyond the verifier's
+                                     // LDS window: worth keeping this one's registers at hand
+
+// Geometry of the verifier's LDS window, which the analysis needs for kPlanKeep: occurrences
+// are staged kWalkChunk at a time into a ring of kWalkRing.
+constexpr uint32_t kWalkChunk = 64, kWalkRing = 192;
+constexpr uint32_t kKeepMaxGap = 4096;   // longer gaps are not worth a slot
 
 // Per-occurrence roles computed by the event kernel.
 constexpr uint8_t kRolePreKill = 1, kRoleTestSet = 2, kRolePostKill = 4, kRoleFirst = 8;

@@ -362,7 +362,10 @@ __global__ void k_events(MIRS) {
   const uint32_t prev = e > lo ? L.vocc[e - 1] : kNone;
   L.prev_occ[o] = prev;
   // the occurrence's check entry, and its events counted into its instruction's item
-  L.chk[o] = entry_pack(o | (((role & kRoleFirst) ? kPlanFirst : kPlanChk) << 24),
+  // when the next occurrence is checked the ring ends with that occurrence's chunk
+  const uint32_t next = e + 1 < hi ? L.vocc[e + 1] : o;
+  const uint32_t keep = (o + kWalkRing < (next / kWalkChunk + 1u) * kWalkChunk && next - o <= kKeepMaxGap) ? kPlanKeep : 0u;
+  L.chk[o] = entry_pack(o | ((((role & kRoleFirst) ? kPlanFirst : kPlanChk) | keep) << 24),
                         (prev == kNone ? 0u : min(o - prev, 0xFFFFu)) | (m.vattr[v] << 16));
   const uint32_t n_evt = __popc(role & (kRolePreKill | kRoleTestSet | kRolePostKill));
   if (n_evt) atomicAdd(&L.item_off[i + b + 1], n_evt);

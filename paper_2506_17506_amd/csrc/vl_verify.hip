@@ -30,9 +30,9 @@ namespace {
 
 // Occurrences kept per candidate in LDS: three chunks.  With two register classes a
 // workgroup then needs about 31 KB, so five workgroups share a compute unit's 160 KB.
-constexpr uint32_t kRing = 192;
+constexpr uint32_t kRing = kWalkRing;
 constexpr uint32_t kRingStride = 64 + 4;        // uint16 per occurrence: 64 rows + padding (136 bytes)
-constexpr uint32_t kChunk = 64;                 // occurrences staged per step (128 B per row)
+constexpr uint32_t kChunk = kWalkChunk;                 // occurrences staged per step (128 B per row)
 constexpr uint32_t kKeyOk = 0xFFFFFFFFu;
 constexpr uint32_t kKeyCons = 0u << 28, kKeyReal = 1u << 28, kKeySafe = 2u << 28, kKeyPos = (1u << 28) - 1;
 
@@ -183,7 +183,7 @@ __device__ inline bool unrealizable(const DevMir VL_GLOBAL &m, uint32_t attr, ui
   return bad;
 }
 
-__global__ __launch_bounds__(256) void k_walk(const DevJob *__restrict__ jobs, uint32_t n_jobs) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k_walk(const DevJob *__restrict__ jobs, uint32_t n_jobs) {
   const DevJob VL_GLOBAL &J = as_global(jobs)[find_job(jobs, n_jobs, blockIdx.x)];
   const DevMir VL_GLOBAL &m = *as_global(J.mir);
   const DevLive VL_GLOBAL &L = *as_global(J.live);
@@ -312,6 +312,14 @@ __global__ __launch_bounds__(256) void k_walk(const DevJob *__restrict__ jobs, u
     }
   };
 
+  // Register cache of a check wavefront: slot s holds, one candidate per lane (16 bits, two
+  // slots per register), the registers of the occurrence named by lane s of cache_tag.  Direct-mapped; a stale or foreign tag
+  // only means the value is fetched from memory instead.
+  constexpr uint32_t kCacheSlots = 32;   // two per register
+  typedef uint32_t cache_t __attribute__((ext_vector_type(kCacheSlots / 2)));   // a vector, so that it stays in registers
+  cache_t cache = 0;
+  uint32_t cache_tag = kNone;
+
   // ---- checks of one chunk (lane = check, loop over rows) ----
   // Per lane: ring offsets of the occurrence and of the previous occurrence of its vreg,
   // and for a first occurrence the alignment mask and the largest base that fits.  Per row:
@@ -370,17 +378,37 @@ __global__ __launch_bounds__(256) void k_walk(const DevJob *__restrict__ jobs, u
         }
       }
     }
-    // links that reach back beyond the ring: one candidate per lane, value from memory
-    uint64_t todo = __ballot(far);
-    for (uint32_t n = 0; todo; ++n) {
+    // Links that reach back beyond the ring, one candidate per lane.  The earlier value is
+    // taken from the wavefront's register cache when its tag still names that occurrence,
+    // otherwise from memory.  A link belongs to the wavefront that owns its earlier
+    // occurrence (index modulo three), which is also the one that cached it.
+    const bool sat = delta == 0xFFFFu;
+    uint64_t todo = __ballot(far && (sat ? w.lane % 3u == part : prev % 3u == part));
+    while (todo) {
       const uint32_t j = __builtin_ctzll(todo);
       todo &= todo - 1;
-      if (n % 3 != part) continue;
       const uint32_t oj = c * kChunk + j;
       const uint32_t dj = __builtin_amdgcn_readlane(delta, j);
-      const uint32_t pj = dj == 0xFFFFu ? g_prev_occ[oj] : oj - dj;
-      const uint32_t pv = fetch(w, oj), qv = fetch(w, pj);
+      const uint32_t pv = VL_LDS16[w.ring16 + (oj % kRing) * kRingStride + w.row];
+      uint32_t qv;
+      if (dj != 0xFFFFu) {
+        const uint32_t pj = oj - dj, slot = (pj / 3u) % kCacheSlots;
+        if ((uint32_t)__builtin_amdgcn_readlane(cache_tag, slot) == pj) qv = (cache[slot >> 1] >> (16u * (slot & 1u))) & 0xFFFFu;
+        else qv = w.rows[(uint64_t)w.row * w.ld + pj];
+      } else {
+        qv = w.rows[(uint64_t)w.row * w.ld + g_prev_occ[oj]];
+      }
       if (pv != qv) key = min(key, kKeyCons | oj);
+    }
+    // occurrences whose successor is likely out of reach: keep their registers
+    uint64_t keep = __ballot(valid && (fl & kPlanKeep) && o % 3u == part);
+    while (keep) {
+      const uint32_t j = __builtin_ctzll(keep);
+      keep &= keep - 1;
+      const uint32_t oj = c * kChunk + j, slot = (oj / 3u) % kCacheSlots;
+      const uint32_t val = VL_LDS16[w.ring16 + (oj % kRing) * kRingStride + w.row], both = cache[slot >> 1];
+      cache[slot >> 1] = (slot & 1u) ? ((both & 0xFFFFu) | (val << 16)) : ((both & 0xFFFF0000u) | val);
+      if (w.lane == slot) cache_tag = oj;
     }
   };
 
