@@ -20,7 +20,9 @@ constexpr uint32_t kDefaultTile = 1024;    // instructions per verification tile
 // Kernel (program) on the device.  All pointers are device memory.
 struct DevMir {
   uint32_t N, V, B, O, C, E, W;
-  uint32_t occ_words;              // occupancy words summed over classes
+  uint32_t occ_words;              // occupancy words per candidate: every class may address 16 words from its
+                                   // first one (classes are laid out smallest first, so this is rarely more
+                                   // than the words the files need)
   const uint32_t VL_GLOBAL *blk_start;       // [B+1]
   const uint32_t VL_GLOBAL *succ_off;        // CSR successors
   const uint32_t VL_GLOBAL *succ;
@@ -48,17 +50,18 @@ __host__ __device__ inline uint32_t attr_align(uint32_t a) { return ((a >> 8) & 
 __host__ __device__ inline uint32_t attr_straddle(uint32_t a) { return (a >> 13) & 1u; }
 __host__ __device__ inline uint64_t entry_pack(uint32_t x, uint32_t y) { return (uint64_t)x | ((uint64_t)y << 32); }
 
-// The verifier reads two streams of 8-byte entries
-//   x: occurrence index (24 bits) | flags << 24
+// The verifier reads
+// "chk": one 8-byte entry per occurrence, in occurrence order
+//   x: occurrence index (24 bits) | flags << 24 (kPlanChk or kPlanFirst, kPlanKeep)
 //   y: distance to the previous occurrence of the same vreg (16 bits, saturated)
 //      | packed attributes << 16
-// "chk": one entry per occurrence, in occurrence order (kPlanChk or kPlanFirst).
-// "plan": the occupancy events in the order they take effect.  For each instruction:
-// releases of operands that die there, then test-and-occupy of the values it writes,
-// then releases of values dead once it has executed; the events of a block boundary
-// (values that stop / start being live between two blocks adjacent in the linear order)
-// precede those of the later block's first instruction.  x names the occurrence that
-// carries the register.
+// "seeds": per tile, the values live into it, as 8-byte entries of the same form
+//   (kPlanBirth; x names the occurrence whose register the value has)
+// "plan": the occupancy events in the order they take effect, as 16-byte records (below).
+// For each instruction: releases of operands that die there, then test-and-occupy of the
+// values it writes, then releases of values dead once it has executed; the events of a
+// block boundary (values that stop / start being live between two blocks adjacent in the
+// linear order) precede those of the later block's first instruction.
 constexpr uint32_t kPlanChk = 1u;    // compare with the previous occurrence of the vreg
 constexpr uint32_t kPlanFirst = 2u;  // first occurrence of the vreg: realizability check
 constexpr uint32_t kPlanSet = 4u;    // test the range against occupancy, then occupy it
@@ -71,7 +74,21 @@ constexpr uint32_t kPlanKeep = 64u;  // (chk) the next occurrence of the vreg is
 // Geometry of the verifier's LDS window, which the analysis needs for kPlanKeep: occurrences
 // are staged kWalkChunk at a time into a ring of kWalkRing.
 constexpr uint32_t kWalkChunk = 64, kWalkRing = 192;
+constexpr uint32_t kWalkRingStride = 64 + 4;   // uint16 per ring slot: 64 candidate rows + padding (136 bytes)
 constexpr uint32_t kKeepMaxGap = 4096;   // longer gaps are not worth a slot
+
+// An occupancy event in the form the verifier's occupancy wavefront consumes it, four
+// scalar registers that need no further decoding:
+//   x  byte offset, inside the ring, of the slot of the occurrence that carries the register
+//   y  the tuple's mask at bit 0 (width ones)
+//   z  byte offset of the first mask word of the vreg's class (class_word * 256)
+//   w  that occurrence (24 bits) | kEvtSlow | kEvtTested
+// The mask word of register p is word (p >> 5) & 15 of the class: every class can address
+// 16 words, so no clamp is needed (see DevMir::occ_words).
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+constexpr uint32_t kEvtSlow = 1u << 30;    // not for the fast path: the tuple may cross a mask word, is 32 wide,
+                                           // or its register has to come from outside the ring
+constexpr uint32_t kEvtTested = 1u << 31;  // occupy with test (a definition); otherwise a plain flip
 
 // Per-occurrence roles computed by the event kernel.
 constexpr uint8_t kRolePreKill = 1, kRoleTestSet = 2, kRolePostKill = 4, kRoleFirst = 8;
@@ -100,6 +117,7 @@ struct DevLive {
   uint32_t VL_GLOBAL *seg_off;    // [V+1]
   uint64_t VL_GLOBAL *chk;        // [O] check stream (x | y << 32)
   uint32_t VL_GLOBAL *evt_cut;    // [ceil(O/64)+1] first event replayable once chunk c is staged
+  uint32_t VL_GLOBAL *evt_slow;   // [ceil(O/64)+1] kEvtSlow events among those chunk c releases
   uint32_t VL_GLOBAL *ent_seg;    // [O+1] runs starting in each mention group's stretch -> prefix sums
   uint32_t VL_GLOBAL *hull;       // [V][2]
   uint32_t VL_GLOBAL *seed_off;   // [T+1]
@@ -109,7 +127,7 @@ struct DevLive {
   uint32_t VL_GLOBAL *bitmap;     // [ceil(O/32)] scratch for the bitmap sort, one list at a time per block
   uint32_t VL_GLOBAL *counters;   // [kCounters]
   // --- sized after the counting pass ---
-  uint64_t VL_GLOBAL *plan;       // [plan_len] occupancy events (x | y << 32)
+  u32x4 VL_GLOBAL *plan;          // [plan_len + 8] occupancy events (the last 8 are padding, never applied)
   uint64_t VL_GLOBAL *seeds;      // [n_seed] (x | y << 32)
   uint32_t VL_GLOBAL *seg;        // [n_seg][2]
   uint32_t VL_GLOBAL *tile_range; // [T][2] plan range of each tile

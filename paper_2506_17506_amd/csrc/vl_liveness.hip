@@ -391,6 +391,30 @@ __device__ inline uint32_t source_occurrence(const DevLive VL_GLOBAL &L, uint32_
   return x > lo ? L.vocc[x - 1] : (x < hi ? L.vocc[x] : 0u);
 }
 
+// The record of one occupancy event (layout in vl_dev.h).  `near`: the occurrence is
+// certainly inside the verifier's ring when the event is replayed.
+__device__ inline u32x4 event_record(const DevMir VL_GLOBAL &m, uint32_t o, uint32_t attr, bool tested, bool near, bool &slow) {
+  const uint32_t width = attr_width(attr);
+  slow = !near || attr_straddle(attr) || width == 32;
+  u32x4 r;
+  r.x = (o % kWalkRing) * (kWalkRingStride * 2u);
+  r.y = width == 32 ? 0xFFFFFFFFu : ((1u << width) - 1u);
+  r.z = (uint32_t)m.class_word[attr_class(attr)] * 256u;
+  r.w = o | (slow ? kEvtSlow : 0u) | (tested ? kEvtTested : 0u);
+  return r;
+}
+
+// a slow event at plan index e is counted for the chunk that releases it: the last c with
+// evt_cut[c] <= e
+__device__ inline void count_slow(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L, uint32_t e) {
+  uint32_t lo = 0, hi = (m.O + 63) / 64 + 1;   // evt_cut has entries 0 .. ceil(O/64)
+  while (hi - lo > 1) {
+    const uint32_t mid = (lo + hi) >> 1;
+    if (L.evt_cut[mid] <= e) lo = mid; else hi = mid;
+  }
+  atomicAdd(&L.evt_slow[lo], 1u);
+}
+
 // Between two blocks adjacent in the linear order the occupied set changes from the
 // earlier block's live-out to the later block's live-in: one wave per boundary lists the
 // values that leave (release) and those that enter (occupy without test).
@@ -420,9 +444,14 @@ __global__ __launch_bounds__(64) void k_boundary(MIRS) {
         while (bits) {
           uint32_t v = w * 32 + __ffs(bits) - 1;
           bits &= bits - 1;
-          uint32_t src = source_occurrence(L, v, at);
-          L.plan[pos++] = entry_pack(src | ((pass == 0 ? kPlanClr : kPlanBirth) | kPlanPost) << 24,
-                                     0xFFFFu | (m.vattr[v] << 16));
+          const uint32_t src = source_occurrence(L, v, at);
+          // replayed with the block's first instruction, when the ring ends at most 127
+          // occurrences after that instruction's first operand
+          const bool near = src < m.occ_off[at] && src + (kWalkRing - 2 * kWalkChunk + 1) >= m.occ_off[at];
+          bool slow;
+          L.plan[pos] = event_record(m, src, m.vattr[v], false, near, slow);
+          if (slow) count_slow(m, L, pos);
+          ++pos;
         }
       }
       total += __shfl(incl, 63, 64);
@@ -441,15 +470,19 @@ __global__ void k_plan_fill(MIRS) {
   if (i >= m.N) return;
   uint32_t pos = L.item_off[item_of_instr(m, i)];
   const uint32_t o0 = m.occ_off[i], o1 = m.occ_off[i + 1];
-  auto entry = [&](uint32_t o, uint32_t flags) {
-    return entry_pack(o | (flags << 24), 0xFFFFu | (m.vattr[m.occ_vreg[o]] << 16));
+  // an instruction's own operands are always inside the ring when its events are replayed
+  auto put = [&](uint32_t o, bool tested) {
+    bool slow;
+    L.plan[pos] = event_record(m, o, m.vattr[m.occ_vreg[o]], tested, true, slow);
+    if (slow) count_slow(m, L, pos);
+    ++pos;
   };
   for (uint32_t o = o0; o < o1; ++o)
-    if (L.occ_role[o] & kRolePreKill) L.plan[pos++] = entry(o, kPlanClr);
+    if (L.occ_role[o] & kRolePreKill) put(o, false);
   for (uint32_t o = o0; o < o1; ++o)
-    if (L.occ_role[o] & kRoleTestSet) L.plan[pos++] = entry(o, kPlanSet);
+    if (L.occ_role[o] & kRoleTestSet) put(o, true);
   for (uint32_t o = o0; o < o1; ++o)
-    if (L.occ_role[o] & kRolePostKill) L.plan[pos++] = entry(o, kPlanClr | kPlanPost);
+    if (L.occ_role[o] & kRolePostKill) put(o, false);
 }
 
 // evt_cut[c] = index of the first event of the first item whose operands end in chunk c or
@@ -697,8 +730,7 @@ __global__ void k_dense_delta(MIRS) {
   // a tile that starts exactly at this block start takes its row from the seed instead
   if (q == m.blk_start[b] + b && row % L.tile_len == 0) return;
   for (uint32_t e = L.item_off[q]; e < L.item_off[q + 1]; ++e) {
-    const uint32_t ex = (uint32_t)L.plan[e];
-    const uint32_t v = m.occ_vreg[ex & 0xFFFFFFu];
+    const uint32_t v = m.occ_vreg[L.plan[e].w & 0xFFFFFFu];
     atomicXor(&L.live_after[(size_t)row * m.W + (v >> 5)], 1u << (v & 31));
   }
 }
@@ -806,7 +838,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
   // ---- arena 1 layout: [zeroed zone | counters | rest | device tables] ----
   std::vector<DevLive> h(n);
   struct Off1 { size_t vcnt, vcur, use, def, in, seed_off, seed_cur, blk_live, out, tmp, vocc, ent_instr, ent_info, first, prev,
-                role, kill, item, seg_off, hull, queue, bitmap, ent_seg, chk, evt_cut, tile_live; };
+                role, kill, item, seg_off, hull, queue, bitmap, ent_seg, chk, evt_cut, evt_slow, tile_live; };
   std::vector<Off1> off(n);
   Bump bump;
   uint32_t maxO = 1, maxV = 1, maxN = 1, maxB = 1, maxW = 1, maxT = 1;
@@ -822,6 +854,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     off[k].seed_off = bump.take((size_t)(T + 1) * 4); off[k].seed_cur = bump.take((size_t)(T + 1) * 4);
     off[k].blk_live = bump.take((size_t)(m.V + 1) * ((m.B + 31) / 32) * 4);
     off[k].item = bump.take((size_t)(m.N + m.B + 1) * 4);   // event counts are accumulated with atomics
+    off[k].evt_slow = bump.take(((size_t)(m.O + 63) / 64 + 2) * 4);
     maxO = std::max(maxO, m.O); maxV = std::max(maxV, m.V); maxN = std::max(maxN, m.N);
     maxB = std::max(maxB, m.B); maxW = std::max(maxW, m.W); maxT = std::max(maxT, T);
   }
@@ -867,6 +900,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     L.hull = (uint32_t VL_GLOBAL *)(a1 + off[k].hull); L.long_queue = (uint32_t VL_GLOBAL *)(a1 + off[k].queue);
     L.ent_seg = (uint32_t VL_GLOBAL *)(a1 + off[k].ent_seg);
     L.chk = (uint64_t VL_GLOBAL *)(a1 + off[k].chk); L.tile_live = (uint32_t VL_GLOBAL *)(a1 + off[k].tile_live); L.evt_cut = (uint32_t VL_GLOBAL *)(a1 + off[k].evt_cut);
+    L.evt_slow = (uint32_t VL_GLOBAL *)(a1 + off[k].evt_slow);
     L.bitmap = (uint32_t VL_GLOBAL *)nullptr;
     L.counters = (uint32_t VL_GLOBAL *)(a1 + o_counters) + (size_t)k * kCounters;
     mir_ptrs[k] = mirs[k]->dev;
@@ -943,7 +977,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     const uint32_t *c = batch->host_counters + (size_t)k * kCounters;
     h[k].plan_len = c[kCtrPlanLen]; h[k].n_seg = c[kCtrSeg]; h[k].n_seed = c[kCtrSeed];
     max_seed = std::max(max_seed, h[k].n_seed);
-    off2[k].plan = b2.take((size_t)std::max(1u, h[k].plan_len) * 8);
+    off2[k].plan = b2.take(((size_t)h[k].plan_len + 8) * sizeof(u32x4));
     off2[k].seeds = b2.take((size_t)std::max(1u, h[k].n_seed) * 8);
     off2[k].seg = b2.take((size_t)std::max(1u, h[k].n_seg) * 8);
     off2[k].range = b2.take((size_t)h[k].T * 8);
@@ -957,7 +991,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
   char *a2 = (char *)batch->arena2;
   for (uint32_t k = 0; k < n; ++k) {
     DevLive &L = h[k];
-    L.plan = (uint64_t VL_GLOBAL *)(a2 + off2[k].plan); L.seeds = (uint64_t VL_GLOBAL *)(a2 + off2[k].seeds);
+    L.plan = (u32x4 VL_GLOBAL *)(a2 + off2[k].plan); L.seeds = (uint64_t VL_GLOBAL *)(a2 + off2[k].seeds);
     L.seg = (uint32_t VL_GLOBAL *)(a2 + off2[k].seg); L.tile_range = (uint32_t VL_GLOBAL *)(a2 + off2[k].range);
     L.live_after = dense ? (uint32_t VL_GLOBAL *)(a2 + off2[k].dense) : (uint32_t VL_GLOBAL *)nullptr;
   }

@@ -1,4 +1,5 @@
 // Program handles: validation of a kernel description and its copy to the device.
+#include <algorithm>
 #include <cstdlib>
 #include <cstring>
 #include <vector>
@@ -136,18 +137,26 @@ extern "C" int32_t vl_mir_create(const vl_mir_desc *d, vl_mir **out) {
   h.instr_blk = (const uint32_t VL_GLOBAL *)(base + o_ib);
   h.vattr = (const uint32_t VL_GLOBAL *)(base + o_va);
   h.occ_flags = (const uint8_t VL_GLOBAL *)(base + o_of);
-  uint32_t words = 0;
+  // mask words: classes smallest first, so that the 16 words every class may address from
+  // its first one mostly fall on words of later classes
+  std::vector<uint32_t> order(d->n_class);
+  for (uint32_t c = 0; c < d->n_class; ++c) order[c] = c;
+  std::stable_sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) { return d->class_size[a] < d->class_size[b]; });
+  uint32_t words = 0, reach = 0;
+  for (uint32_t c : order) {
+    h.class_word[c] = (uint16_t)words;
+    reach = std::max(reach, words + 16u);
+    words += (d->class_size[c] + 31u) / 32u;
+  }
+  h.occ_words = reach;
   for (uint32_t c = 0; c < d->n_class; ++c) {
     h.class_size[c] = d->class_size[c];
-    h.class_word[c] = (uint16_t)words;
-    words += (d->class_size[c] + 31u) / 32u;
     if (d->class_reserved)
       for (int w = 0; w < 16; ++w) {
         h.reserved[c][w] = d->class_reserved[c * 16 + w];
         if (h.reserved[c][w]) h.has_reserved = 1;
       }
   }
-  h.occ_words = words;
   m->dev = (vl::DevMir *)(base + o_dev);
   up(o_dev, &h, sizeof(h));
   if (e != hipSuccess) {

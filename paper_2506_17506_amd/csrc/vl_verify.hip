@@ -22,6 +22,8 @@
 #include <new>
 #include <vector>
 
+#include <type_traits>
+
 #include "vl_dev.h"
 
 using namespace vl;
@@ -31,7 +33,7 @@ namespace {
 // Occurrences kept per candidate in LDS: three chunks.  With two register classes a
 // workgroup then needs about 31 KB, so five workgroups share a compute unit's 160 KB.
 constexpr uint32_t kRing = kWalkRing;
-constexpr uint32_t kRingStride = 64 + 4;        // uint16 per occurrence: 64 rows + padding (136 bytes)
+constexpr uint32_t kRingStride = kWalkRingStride;
 constexpr uint32_t kChunk = kWalkChunk;                 // occurrences staged per step (128 B per row)
 constexpr uint32_t kKeyOk = 0xFFFFFFFFu;
 constexpr uint32_t kKeyCons = 0u << 28, kKeyReal = 1u << 28, kKeySafe = 2u << 28, kKeyPos = (1u << 28) - 1;
@@ -79,29 +81,37 @@ __global__ void k_init(const DevJob *__restrict__ jobs) {
 //   [ring32, ...)                  the ring [occurrence % 192][row], addressed in uint16 from
 //                                  ring16 = 2 * ring32; a lane of the check wavefronts reads four
 //                                  rows of one occurrence with one 8-byte read
+//   [park, park + 256)             a batch of 64 occupancy event records
 extern __shared__ uint32_t vl_lds[];
 #define VL_LDS16 (reinterpret_cast<uint16_t *>(vl_lds))
 
 struct Walk {
   const uint16_t VL_GLOBAL *rows;   // first row of the group
   uint64_t ld;
-  uint32_t keys, ring16;  // LDS indices
+  uint32_t keys, ring16, park;  // LDS indices
   uint32_t tid, lane, row, nrows, n_occ, staged_lo, staged_hi, fast;
   uint32_t pre[2][4];     // the chunk after staged_hi, in flight
 };
 
-// Each of the 256 threads owns 8 consecutive occurrences of two rows (r, r + 32) of a
-// 64-occurrence chunk: 8 threads per row read one 128-byte line.
+// Each of the 256 threads owns 8 consecutive occurrences (16 bytes) of two rows of a
+// 64-occurrence chunk.  Lane bits: k = lane & 7 picks the 16 bytes inside the row's 128-byte
+// line, rr = lane >> 3 the row pair; the two halves of a line (k < 4, k >= 4) belong to rows
+// 16 apart.  With this assignment the 64 lanes of every LDS store below fall into 64
+// different banks (slot stride 34 dwords: bank = 16 (k & 3) + 8 (row bit 4) + rr + const).
+__device__ inline uint32_t staged_row(uint32_t tid, int h) {
+  const uint32_t k = tid & 7u, rr = (tid >> 3) & 7u, wave = tid >> 6;
+  return (uint32_t)h + 2u * rr + 16u * ((k >> 2) ^ (wave >> 1)) + 32u * (wave & 1u);
+}
+
 __device__ inline void load_chunk(Walk &w, uint32_t c0) {
   const uint32_t c = c0 + (w.tid & 7u) * 8u;
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
-    const uint32_t r = h * 32 + (w.tid >> 3);
+    const uint32_t r = staged_row(w.tid, h);
     w.pre[h][0] = w.pre[h][1] = w.pre[h][2] = w.pre[h][3] = 0;
     if (r < w.nrows && c < w.n_occ) {
       const uint16_t VL_GLOBAL *src = w.rows + (uint64_t)r * w.ld + c;
       if (w.fast && c + 8u <= w.n_occ) {
-        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
         const u32x4 x = *reinterpret_cast<const u32x4 VL_GLOBAL *>(src);
         w.pre[h][0] = x.x; w.pre[h][1] = x.y; w.pre[h][2] = x.z; w.pre[h][3] = x.w;
       } else {
@@ -120,7 +130,7 @@ __device__ inline void store_chunk(Walk &w) {
   const uint32_t c = w.staged_hi + (w.tid & 7u) * 8u;
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
-    const uint32_t r = h * 32 + (w.tid >> 3);
+    const uint32_t r = staged_row(w.tid, h);
     const uint32_t dst = w.ring16 + (c % kRing) * kRingStride + r;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -192,7 +202,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k
   const auto g_prev_occ = L.prev_occ, g_evt_cut = L.evt_cut;
   const auto g_seed_off = L.seed_off, g_tile_range = L.tile_range;
   // 8-byte stream entries are read as one 64-bit word: x in the low half, y in the high half
-  const uint64_t VL_GLOBAL *g_chk = L.chk, *g_plan = L.plan, *g_seeds = L.seeds;
+  const uint64_t VL_GLOBAL *g_chk = L.chk, *g_seeds = L.seeds;
+  const u32x4 VL_GLOBAL *g_plan = L.plan;
+  const auto g_evt_slow = L.evt_slow;
   const uint32_t has_reserved = m.has_reserved;
   const uint32_t local = blockIdx.x - J.unit_base;
   const uint32_t tile = local / J.n_groups, group = local % J.n_groups;
@@ -202,7 +214,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k
   w.lane = threadIdx.x & 63u;
   // the occupancy role moves from wavefront to wavefront with the workgroup index, so
   // that neighbouring workgroups do not all put it on the same SIMD
-  const uint32_t role = ((threadIdx.x >> 6) + blockIdx.x) & 3u;
+  const uint32_t role = __builtin_amdgcn_readfirstlane(((threadIdx.x >> 6) + blockIdx.x) & 3u);
   w.nrows = min(J.rows, J.K - row0);
   const bool active = w.lane < w.nrows;
   w.row = active ? w.lane : 0u;
@@ -212,6 +224,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k
   w.fast = J.fast;
   w.keys = m.occ_words * 64;
   w.ring16 = (w.keys + 64) * 2;
+  w.park = w.keys + 64 + kRing * kRingStride / 2;
   for (uint32_t x = w.tid; x < m.occ_words * 64; x += 256) vl_lds[x] = 0;
   if (w.tid < 64) vl_lds[w.keys + w.tid] = kKeyOk;
   // per-class file size and first mask word, one class per lane, read back by lane index
@@ -237,78 +250,98 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k
   // Events are replayed in instruction order, so the first clash of a row is the one to
   // report; after it the row's mask is no longer exact and its later clashes are ignored.
   uint32_t alive = 0xFFFFFFFFu;
-  auto event1 = [&](uint32_t ex, uint32_t ey) __attribute__((always_inline)) {   // any source: ring or global memory
-    const uint32_t o = ex & 0xFFFFFFu, fl = ex >> 24, attr = ey >> 16;
-    const uint32_t p = fetch(w, o);
-    const Touch t = locate(w, attr, __builtin_amdgcn_readlane(cls_tab_v, attr_class(attr)), p);
-    uint32_t hit = flip(t, attr_straddle(attr));
-    if (!(fl & kPlanSet)) hit = 0;
+  auto clash = [&](uint32_t hit, uint32_t o) __attribute__((always_inline)) {
     hit &= alive;
     if (__any(hit != 0)) {
       const uint32_t i = g_occ_instr[o];
       if (hit) { key = min(key, kKeySafe | i); alive = 0; }
     }
   };
-  constexpr int G = 8;   // events in flight: their LDS reads and atomics overlap
-  const uint32_t my_ring = w.ring16 + w.row;
-  const uint32_t my_occ = w.lane * 4;   // byte offset of this lane's column of mask words
+  // any event, its register from the ring or from memory
+  auto event1 = [&](uint32_t o, uint32_t attr, bool tested) __attribute__((always_inline)) {
+    const uint32_t p = fetch(w, o);
+    const Touch t = locate(w, attr, __builtin_amdgcn_readlane(cls_tab_v, attr_class(attr)), p);
+    const uint32_t hit = flip(t, attr_straddle(attr));
+    if (tested) clash(hit, o);
+  };
+  const uint32_t my_ring = (w.ring16 + w.row) * 2u;   // byte offset of this lane's row in ring slot 0
+  const uint32_t my_occ = w.lane * 4;                 // byte offset of this lane's column of mask words
   char *const lds_bytes = reinterpret_cast<char *>(vl_lds);
-  // A batch of up to 64 events is first decoded with one event per lane (everything that
-  // does not depend on the candidate: ring offset, tuple mask, mask-word base and limit),
-  // then replayed in order with one candidate per lane, eight events at a time: the eight
-  // register values are read from the ring, the eight mask updates are issued back to back
-  // (LDS executes them in order) and only then are the returned old bits examined.
-  auto events = [&](const uint64_t VL_GLOBAL *stream, uint32_t from, uint32_t to) __attribute__((always_inline)) {
+  // one event record, whatever it is
+  auto event_any = [&](const u32x4 r) __attribute__((always_inline)) {
+    const uint32_t o = r.w & 0xFFFFFFu;
+    if (r.w & kEvtSlow) {
+      event1(o, (uint32_t)(g_chk[o] >> 48), (r.w & kEvtTested) != 0);
+    } else {
+      const uint32_t p = *reinterpret_cast<const uint16_t *>(lds_bytes + my_ring + r.x);
+      const uint32_t msk = r.y << (p & 31u);
+      const uint32_t old = __hip_atomic_fetch_xor(reinterpret_cast<uint32_t *>(lds_bytes + ((((p >> 5) & 15u) << 8) + my_occ + r.z)),
+                                                  msk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+      if (r.w & kEvtTested) clash(old & msk, o);
+    }
+  };
+  // A batch of up to 64 records, one per lane, fetched one chunk ahead, is parked in LDS and
+  // read back one record at a time by all lanes at once (a broadcast read), which puts the
+  // wave-uniform fields where vector instructions can use them without any scalar work.
+  // Lanes past the batch park zero records: those flip nothing.  Eight events are in
+  // flight: their eight registers are read from the ring, the eight mask updates are issued
+  // back to back (LDS executes them in order) and only then are the returned old bits
+  // examined.
+  constexpr int G = 8;
+  const uint32_t park = w.park * 4u;   // byte offset of the parked records
+  auto replay_parked = [&](uint32_t cnt) __attribute__((always_inline)) {
+    for (uint32_t g0 = 0; g0 < cnt; g0 += G) {
+      u32x4 r[G];
+      uint32_t p[G], old[G], msk[G];
+#pragma unroll
+      for (int t = 0; t < G; ++t) {
+        r[t] = *reinterpret_cast<const u32x4 *>(lds_bytes + park + (g0 + t) * 16u);
+        p[t] = *reinterpret_cast<const uint16_t *>(lds_bytes + my_ring + r[t].x);
+      }
+#pragma unroll
+      for (int t = 0; t < G; ++t) {
+        msk[t] = r[t].y << (p[t] & 31u);
+        old[t] = __hip_atomic_fetch_xor(reinterpret_cast<uint32_t *>(lds_bytes + ((((p[t] >> 5) & 15u) << 8) + my_occ + r[t].z)),
+                                        msk[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+      }
+      uint32_t any_hit = 0;
+#pragma unroll
+      for (int t = 0; t < G; ++t) {
+        old[t] &= msk[t] & (uint32_t)((int32_t)r[t].w >> 31);   // kEvtTested is the sign bit
+        any_hit |= old[t];
+      }
+      if (__any((any_hit & alive) != 0)) {
+#pragma unroll
+        for (int t = 0; t < G; ++t) clash(old[t], __builtin_amdgcn_readfirstlane(r[t].w) & 0xFFFFFFu);
+      }
+    }
+  };
+  auto fetch_records = [&](uint32_t from, uint32_t to) __attribute__((always_inline)) {
+    u32x4 r = 0;
+    if (from + w.lane < to) r = g_plan[from + w.lane];
+    return r;
+  };
+  // events [from, to); `first` holds the records [from, from + 64) when fetched ahead
+  auto events = [&](uint32_t from, uint32_t to, bool careful, u32x4 first) __attribute__((always_inline)) {
+    if (careful) {
+      for (uint32_t e = from; e < to; ++e) event_any(g_plan[e]);
+      return;
+    }
+    for (uint32_t e = from; e < to; e += 64) {
+      u32x4 r = e == from ? first : fetch_records(e, to);
+      if (e + w.lane >= to) r = 0;
+      *reinterpret_cast<u32x4 *>(lds_bytes + park + w.lane * 16u) = r;
+      replay_parked(min(64u, to - e));
+    }
+  };
+  // the values live into the tile: their registers mostly lie before the ring
+  auto seed_events = [&](uint32_t from, uint32_t to) __attribute__((always_inline)) {
     for (uint32_t base = from; base < to; base += 64) {
       const uint32_t cnt = min(64u, to - base);
-      const uint64_t raw = w.lane < cnt ? stream[base + w.lane] : 0ull;
-      const uint2 ent = make_uint2((uint32_t)raw, (uint32_t)(raw >> 32));
-      const uint32_t o = ent.x & 0xFFFFFFu, fl = ent.x >> 24, attr = ent.y >> 16;
-      const uint32_t width = attr_width(attr);
-      const uint32_t tab = (uint32_t)__shfl((int)cls_tab_v, (int)attr_class(attr), 64);
-      const uint32_t F = tab & 0xFFFFu, wbase = tab >> 16;
-      const uint32_t dx = w.lane >= cnt ? 0u : (width == 32 ? 0xFFFFFFFFu : ((1u << width) - 1u));   // tuple mask at bit 0
-      // byte offset of the occurrence's ring slot | last word of the class << 16 | tested << 20 |
-      // first mask word of the class << 21
-      const uint32_t dy = ((o % kRing) * (kRingStride * 2u)) | (((F - 1u) >> 5) << 16) |
-                          ((fl & kPlanSet) ? (1u << 20) : 0u) | (wbase << 21);
-      const bool slow = w.lane < cnt && (!in_ring(w, o) || attr_straddle(attr));
-      const uint64_t slow_mask = __ballot(slow);
-      for (uint32_t g0 = 0; g0 < cnt; g0 += G) {
-        if ((slow_mask >> g0) & 0xFFull) {   // rare: a value outside the ring or a tuple that may cross a word
-          for (uint32_t j = g0; j < min(cnt, g0 + G); ++j)
-            event1(__builtin_amdgcn_readlane(ent.x, j), __builtin_amdgcn_readlane(ent.y, j));
-          continue;
-        }
-        uint32_t sx[G], sy[G], p[G], old[G], msk[G];
-#pragma unroll
-        for (int t = 0; t < G; ++t) {   // lanes past cnt hold zeros: a zero mask flips nothing
-          sx[t] = __builtin_amdgcn_readlane(dx, g0 + t);
-          sy[t] = __builtin_amdgcn_readlane(dy, g0 + t);
-          p[t] = *reinterpret_cast<const uint16_t *>(lds_bytes + my_ring * 2u + (sy[t] & 0xFFFFu));
-        }
-#pragma unroll
-        for (int t = 0; t < G; ++t) {
-          const uint32_t word = min(p[t] >> 5, (sy[t] >> 16) & 15u) + (sy[t] >> 21);
-          msk[t] = sx[t] << (p[t] & 31u);
-          old[t] = __hip_atomic_fetch_xor(reinterpret_cast<uint32_t *>(lds_bytes + ((word << 8) + my_occ)), msk[t],
-                                          __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
-        }
-        uint32_t any_hit = 0;
-#pragma unroll
-        for (int t = 0; t < G; ++t) {
-          old[t] = (sy[t] & (1u << 20)) ? (old[t] & msk[t]) : 0u;
-          any_hit |= old[t];
-        }
-        if (__any((any_hit & alive) != 0)) {
-#pragma unroll
-          for (int t = 0; t < G; ++t)
-            if (__any((old[t] & alive) != 0)) {
-              const uint32_t i = g_occ_instr[__builtin_amdgcn_readlane(o, g0 + t)];
-              if (old[t] & alive) { key = min(key, kKeySafe | i); alive = 0; }
-            }
-        }
-      }
+      const uint64_t raw = w.lane < cnt ? g_seeds[base + w.lane] : 0ull;
+      const uint32_t ex = (uint32_t)raw, ey = (uint32_t)(raw >> 32);
+      for (uint32_t j = 0; j < cnt; ++j)
+        event1(__builtin_amdgcn_readlane(ex, j) & 0xFFFFFFu, __builtin_amdgcn_readlane(ey, j) >> 16, false);
     }
   };
 
@@ -324,10 +357,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k
   // Per lane: ring offsets of the occurrence and of the previous occurrence of its vreg,
   // and for a first occurrence the alignment mask and the largest base that fits.  Per row:
   // two reads and three compares, identical for every lane.
-  auto checks = [&](uint32_t c, uint32_t part) __attribute__((always_inline)) {
+  auto load_chk = [&](uint32_t c) __attribute__((always_inline)) {
+    const uint32_t o = c * kChunk + w.lane;
+    return (o >= oa && o < ob) ? g_chk[o] : 0ull;
+  };
+  auto checks = [&](uint32_t c, uint32_t part, const uint64_t raw) __attribute__((always_inline)) {
     const uint32_t o = c * kChunk + w.lane;
     const bool valid = o >= oa && o < ob;
-    const uint64_t raw = valid ? g_chk[o] : 0ull;
     const uint2 ent = make_uint2((uint32_t)raw, (uint32_t)(raw >> 32));
     const uint32_t fl = ent.x >> 24, attr = ent.y >> 16, delta = ent.y & 0xFFFFu;
     const bool is_chk = valid && (fl & kPlanChk), is_first = valid && (fl & kPlanFirst);
@@ -412,30 +448,57 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k
     }
   };
 
-  // step -1 occupies the tile's live-in values; steps ca .. c_end-1 stage one chunk each
-  // and process what it releases (a tile without operands still replays its events once)
+  // first the tile's live-in values are occupied; steps ca .. c_end-1 then stage one chunk
+  // each and process what it releases (a tile without operands still replays its events once)
   const uint32_t c_stop = c_end > ca ? c_end : ca + 1;
-  for (uint32_t c = ca - 1; c != c_stop; ++c) {
-    const bool seeding = c == ca - 1, staging = !seeding && c < c_end;
-    if (staging) {
-      __syncthreads();   // everyone is done with the slots about to be overwritten
-      store_chunk(w);
-      load_chunk(w, w.staged_hi);
-      __syncthreads();
+  // occupancy wavefront: limits of the current chunk's batch, clamped to the tile, and the
+  // next chunk's records.  The limits are read with vector loads (the lane-dependent index
+  // keeps them off the scalar unit, whose loads would share a counter with the LDS reads).
+  const uint32_t n_chunk = (w.n_occ + kChunk - 1) / kChunk;
+  uint32_t lane_zero;   // zero in a vector register the compiler cannot see through
+  asm volatile("v_mov_b32 %0, 0" : "=v"(lane_zero));
+  auto clamp_cut = [&](uint32_t e) __attribute__((always_inline)) { return min(eb, max(ea, e)); };
+  // All four wavefronts stage; after that the occupancy wavefront and the check wavefronts
+  // run loops of their own (the same number of barriers in each), so that neither carries
+  // the other's registers.
+  auto stage = [&]() __attribute__((always_inline)) {
+    __syncthreads();   // everyone is done with the slots about to be overwritten
+    store_chunk(w);
+    load_chunk(w, w.staged_hi);
+    __syncthreads();
+  };
+  if (role == 0) {
+    uint32_t cut_lo = clamp_cut(g_evt_cut[min(ca, n_chunk)]);
+    uint32_t v_cut_next = g_evt_cut[min(ca + 1, n_chunk) + lane_zero];
+    uint32_t v_slow_next = g_evt_slow[min(ca, n_chunk) + lane_zero];
+    u32x4 rec_next = 0;
+    if (tile > 0) seed_events(g_seed_off[tile], g_seed_off[tile + 1]);
+    for (uint32_t c = ca; c != c_stop; ++c) {
+      if (c < c_end) stage();
+      // what was fetched ahead during the previous chunk has arrived by now (staging
+      // waited for every outstanding load)
+      const uint32_t cut_hi = clamp_cut(__builtin_amdgcn_readfirstlane(v_cut_next));
+      const uint32_t slow_cur = __builtin_amdgcn_readfirstlane(v_slow_next);
+      const uint32_t from = c == ca ? ea : cut_lo, to = c + 1 >= c_end ? eb : cut_hi;
+      // the tile's first and last batch may hold events that other chunks release
+      const bool careful = c == ca || c + 1 >= c_end || slow_cur != 0;
+      const u32x4 first = rec_next;
+      // fetch ahead for the next chunk, without waiting: its upper limit, its slow count
+      // and the 64 records from its lower limit on (those past its upper limit are dropped
+      // when the batch is parked)
+      cut_lo = cut_hi;
+      v_cut_next = g_evt_cut[min(c + 2, n_chunk) + lane_zero];
+      v_slow_next = g_evt_slow[min(c + 1, n_chunk) + lane_zero];
+      rec_next = fetch_records(cut_lo, eb);
+      events(from, to, careful, first);
     }
-    if (role == 0) {
-      const uint64_t VL_GLOBAL *stream = seeding ? g_seeds : g_plan;
-      uint32_t from, to;
-      if (seeding) {
-        from = tile > 0 ? g_seed_off[tile] : 0u;
-        to = tile > 0 ? g_seed_off[tile + 1] : 0u;
-      } else {
-        from = c == ca ? ea : min(eb, max(ea, g_evt_cut[c]));
-        to = c + 1 >= c_end ? eb : min(eb, max(ea, g_evt_cut[c + 1]));
-      }
-      events(stream, from, to);
-    } else if (staging) {
-      checks(c, role - 1);
+  } else {
+    uint64_t chk_next = load_chk(ca);
+    for (uint32_t c = ca; c < c_end; ++c) {
+      stage();
+      const uint64_t raw = chk_next;
+      chk_next = load_chk(c + 1);   // in flight while this chunk is checked
+      checks(c, role - 1, raw);
     }
   }
   __syncthreads();
@@ -630,7 +693,7 @@ extern "C" int32_t vl_verify_multi(const vl_job *jobs, uint32_t n_jobs, vl_strea
     VL_HIP(hipEventRecord(s.copied, stream));
     s.n_valid = n_jobs;
   }
-  const size_t lds = (size_t)max_words * 64 * 4 + 64 * 4 + (size_t)kRing * kRingStride * 2;
+  const size_t lds = (size_t)max_words * 64 * 4 + 64 * 4 + (size_t)kRing * kRingStride * 2 + 64 * sizeof(u32x4);
   k_init<<<dim3((maxK + 255) / 256, n_jobs), 256, 0, stream>>>(s.dev);
   if (g_time_start) VL_HIP(hipEventRecord(g_time_start, stream));
   k_walk<<<units, 256, lds, stream>>>(s.dev, n_jobs);
