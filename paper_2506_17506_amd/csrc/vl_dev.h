@@ -12,6 +12,8 @@
 
 namespace vl {
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 constexpr uint32_t kMaxClass = 8;
 constexpr uint32_t kMaxOperands = 64;      // per instruction
 constexpr uint32_t kNone = 0xFFFFFFFFu;
@@ -51,12 +53,16 @@ __host__ __device__ inline uint32_t attr_straddle(uint32_t a) { return (a >> 13)
 __host__ __device__ inline uint64_t entry_pack(uint32_t x, uint32_t y) { return (uint64_t)x | ((uint64_t)y << 32); }
 
 // The verifier reads
-// "chk": one 8-byte entry per occurrence, in occurrence order
-//   x: occurrence index (24 bits) | flags << 24 (kPlanChk or kPlanFirst, kPlanKeep)
-//   y: distance to the previous occurrence of the same vreg (16 bits, saturated)
-//      | packed attributes << 16
-// "seeds": per tile, the values live into it, as 8-byte entries of the same form
-//   (kPlanBirth; x names the occurrence whose register the value has)
+// "chk": one 16-byte record per occurrence, in occurrence order, everything a consistency /
+//   realizability check needs that does not depend on the candidate:
+//   x: flags (kPlanChk or kPlanFirst, kPlanKeep, kChkNear, kChkGeneric)
+//      | ring offset of the occurrence << 8 | ring offset of the previous occurrence of the
+//      same vreg << 20, both in 8-byte units: (index % kWalkRing) * kWalkRingStride / 4
+//   y: distance to that previous occurrence (16 bits, saturated) | packed attributes << 16
+//   z: alignment - 1 in both halves (two candidates per 32-bit operation); 0 when nothing is to be tested
+//   w: the largest base that fits, in both halves; all ones when there is no limit
+// "seeds": per tile, the values live into it, as 8-byte entries
+//   occurrence whose register the value has (24 bits) | flags << 24, then 0xFFFF | attributes << 16
 // "plan": the occupancy events in the order they take effect, as 16-byte records (below).
 // For each instruction: releases of operands that die there, then test-and-occupy of the
 // values it writes, then releases of values dead once it has executed; the events of a
@@ -64,8 +70,10 @@ __host__ __device__ inline uint64_t entry_pack(uint32_t x, uint32_t y) { return 
 // linear order) precede those of the later block's first instruction.
 constexpr uint32_t kPlanChk = 1u;    // compare with the previous occurrence of the vreg
 constexpr uint32_t kPlanFirst = 2u;  // first occurrence of the vreg: realizability check
-constexpr uint32_t kPlanSet = 4u;    // test the range against occupancy, then occupy it
-constexpr uint32_t kPlanClr = 8u;    // release the range
+constexpr uint32_t kChkNear = 4u;    // the previous occurrence is still in the ring when this one is checked
+                                     // (unless the tile starts in between)
+constexpr uint32_t kChkGeneric = 8u; // realizability needs the general test: alignment not a power of two,
+                                     // reserved registers, or a tuple wider than its file
 constexpr uint32_t kPlanBirth = 16u; // occupy without testing (value becomes live at a boundary)
 constexpr uint32_t kPlanPost = 32u;  // the occurrence named is not at the event's own position
 constexpr uint32_t kPlanKeep = 64u;  // (chk) the next occurrence of the vreg is likely beyond the verifier's
@@ -85,7 +93,6 @@ constexpr uint32_t kKeepMaxGap = 4096;   // longer gaps are not worth a slot
 //   w  that occurrence (24 bits) | kEvtSlow | kEvtTested
 // The mask word of register p is word (p >> 5) & 15 of the class: every class can address
 // 16 words, so no clamp is needed (see DevMir::occ_words).
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr uint32_t kEvtSlow = 1u << 30;    // not for the fast path: the tuple may cross a mask word, is 32 wide,
                                            // or its register has to come from outside the ring
 constexpr uint32_t kEvtTested = 1u << 31;  // occupy with test (a definition); otherwise a plain flip
@@ -115,9 +122,8 @@ struct DevLive {
   uint32_t VL_GLOBAL *item_off;   // [N+B+1] plan offset of each item (boundary b at blk_start[b]+b,
                         //          instruction i of block b at i+b+1)
   uint32_t VL_GLOBAL *seg_off;    // [V+1]
-  uint64_t VL_GLOBAL *chk;        // [O] check stream (x | y << 32)
+  u32x4 VL_GLOBAL *chk;           // [O] check records
   uint32_t VL_GLOBAL *evt_cut;    // [ceil(O/64)+1] first event replayable once chunk c is staged
-  uint32_t VL_GLOBAL *evt_slow;   // [ceil(O/64)+1] kEvtSlow events among those chunk c releases
   uint32_t VL_GLOBAL *ent_seg;    // [O+1] runs starting in each mention group's stretch -> prefix sums
   uint32_t VL_GLOBAL *hull;       // [V][2]
   uint32_t VL_GLOBAL *seed_off;   // [T+1]

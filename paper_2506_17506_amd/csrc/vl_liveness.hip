@@ -361,12 +361,27 @@ __global__ void k_events(MIRS) {
   L.occ_role[o] = role;
   const uint32_t prev = e > lo ? L.vocc[e - 1] : kNone;
   L.prev_occ[o] = prev;
-  // the occurrence's check entry, and its events counted into its instruction's item
-  // when the next occurrence is checked the ring ends with that occurrence's chunk
-  const uint32_t next = e + 1 < hi ? L.vocc[e + 1] : o;
-  const uint32_t keep = (o + kWalkRing < (next / kWalkChunk + 1u) * kWalkChunk && next - o <= kKeepMaxGap) ? kPlanKeep : 0u;
-  L.chk[o] = entry_pack(o | ((((role & kRoleFirst) ? kPlanFirst : kPlanChk) | keep) << 24),
-                        (prev == kNone ? 0u : min(o - prev, 0xFFFFu)) | (m.vattr[v] << 16));
+  // the occurrence's check record; its events are counted into its instruction's item further down
+  {
+    // when an occurrence is checked the ring ends with that occurrence's chunk
+    const uint32_t next = e + 1 < hi ? L.vocc[e + 1] : o;
+    const bool keep = o + kWalkRing < (next / kWalkChunk + 1u) * kWalkChunk && next - o <= kKeepMaxGap;
+    const uint32_t delta = prev == kNone ? 0u : min(o - prev, 0xFFFFu);
+    const bool near = prev != kNone && delta != 0xFFFFu && prev + kWalkRing >= (o / kWalkChunk + 1u) * kWalkChunk;
+    const uint32_t attr = m.vattr[v];
+    const uint32_t width = attr_width(attr), align = attr_align(attr), F = m.class_size[attr_class(attr)];
+    const bool is_first = (role & kRoleFirst) != 0;
+    const bool generic = is_first && ((align & (align - 1u)) != 0 || m.has_reserved || width > F);
+    const bool simple = is_first && !generic;
+    constexpr uint32_t slot8 = kWalkRingStride / 4;
+    u32x4 r;
+    r.x = (is_first ? kPlanFirst : kPlanChk) | (keep ? kPlanKeep : 0u) | (near ? kChkNear : 0u) | (generic ? kChkGeneric : 0u) |
+          (((o % kWalkRing) * slot8) << 8) | ((((near ? prev : o) % kWalkRing) * slot8) << 20);
+    r.y = delta | (attr << 16);
+    r.z = simple ? (align - 1u) * 0x10001u : 0u;
+    r.w = simple ? min(F - width, 0xFFFFu) * 0x10001u : 0xFFFFFFFFu;
+    L.chk[o] = r;
+  }
   const uint32_t n_evt = __popc(role & (kRolePreKill | kRoleTestSet | kRolePostKill));
   if (n_evt) atomicAdd(&L.item_off[i + b + 1], n_evt);
   L.ent_info[e] = (uint8_t)((la ? kEntLiveAfter : 0) | (has_use ? kEntHasUse : 0) | (has_def ? kEntHasDef : 0) |
@@ -393,26 +408,15 @@ __device__ inline uint32_t source_occurrence(const DevLive VL_GLOBAL &L, uint32_
 
 // The record of one occupancy event (layout in vl_dev.h).  `near`: the occurrence is
 // certainly inside the verifier's ring when the event is replayed.
-__device__ inline u32x4 event_record(const DevMir VL_GLOBAL &m, uint32_t o, uint32_t attr, bool tested, bool near, bool &slow) {
+__device__ inline u32x4 event_record(const DevMir VL_GLOBAL &m, uint32_t o, uint32_t attr, bool tested, bool near) {
   const uint32_t width = attr_width(attr);
-  slow = !near || attr_straddle(attr) || width == 32;
+  const bool slow = !near || attr_straddle(attr) || width == 32;
   u32x4 r;
   r.x = (o % kWalkRing) * (kWalkRingStride * 2u);
   r.y = width == 32 ? 0xFFFFFFFFu : ((1u << width) - 1u);
   r.z = (uint32_t)m.class_word[attr_class(attr)] * 256u;
   r.w = o | (slow ? kEvtSlow : 0u) | (tested ? kEvtTested : 0u);
   return r;
-}
-
-// a slow event at plan index e is counted for the chunk that releases it: the last c with
-// evt_cut[c] <= e
-__device__ inline void count_slow(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L, uint32_t e) {
-  uint32_t lo = 0, hi = (m.O + 63) / 64 + 1;   // evt_cut has entries 0 .. ceil(O/64)
-  while (hi - lo > 1) {
-    const uint32_t mid = (lo + hi) >> 1;
-    if (L.evt_cut[mid] <= e) lo = mid; else hi = mid;
-  }
-  atomicAdd(&L.evt_slow[lo], 1u);
 }
 
 // Between two blocks adjacent in the linear order the occupied set changes from the
@@ -448,10 +452,7 @@ __global__ __launch_bounds__(64) void k_boundary(MIRS) {
           // replayed with the block's first instruction, when the ring ends at most 127
           // occurrences after that instruction's first operand
           const bool near = src < m.occ_off[at] && src + (kWalkRing - 2 * kWalkChunk + 1) >= m.occ_off[at];
-          bool slow;
-          L.plan[pos] = event_record(m, src, m.vattr[v], false, near, slow);
-          if (slow) count_slow(m, L, pos);
-          ++pos;
+          L.plan[pos++] = event_record(m, src, m.vattr[v], false, near);
         }
       }
       total += __shfl(incl, 63, 64);
@@ -471,12 +472,7 @@ __global__ void k_plan_fill(MIRS) {
   uint32_t pos = L.item_off[item_of_instr(m, i)];
   const uint32_t o0 = m.occ_off[i], o1 = m.occ_off[i + 1];
   // an instruction's own operands are always inside the ring when its events are replayed
-  auto put = [&](uint32_t o, bool tested) {
-    bool slow;
-    L.plan[pos] = event_record(m, o, m.vattr[m.occ_vreg[o]], tested, true, slow);
-    if (slow) count_slow(m, L, pos);
-    ++pos;
-  };
+  auto put = [&](uint32_t o, bool tested) { L.plan[pos++] = event_record(m, o, m.vattr[m.occ_vreg[o]], tested, true); };
   for (uint32_t o = o0; o < o1; ++o)
     if (L.occ_role[o] & kRolePreKill) put(o, false);
   for (uint32_t o = o0; o < o1; ++o)
@@ -838,7 +834,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
   // ---- arena 1 layout: [zeroed zone | counters | rest | device tables] ----
   std::vector<DevLive> h(n);
   struct Off1 { size_t vcnt, vcur, use, def, in, seed_off, seed_cur, blk_live, out, tmp, vocc, ent_instr, ent_info, first, prev,
-                role, kill, item, seg_off, hull, queue, bitmap, ent_seg, chk, evt_cut, evt_slow, tile_live; };
+                role, kill, item, seg_off, hull, queue, bitmap, ent_seg, chk, evt_cut, tile_live; };
   std::vector<Off1> off(n);
   Bump bump;
   uint32_t maxO = 1, maxV = 1, maxN = 1, maxB = 1, maxW = 1, maxT = 1;
@@ -854,7 +850,6 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     off[k].seed_off = bump.take((size_t)(T + 1) * 4); off[k].seed_cur = bump.take((size_t)(T + 1) * 4);
     off[k].blk_live = bump.take((size_t)(m.V + 1) * ((m.B + 31) / 32) * 4);
     off[k].item = bump.take((size_t)(m.N + m.B + 1) * 4);   // event counts are accumulated with atomics
-    off[k].evt_slow = bump.take(((size_t)(m.O + 63) / 64 + 2) * 4);
     maxO = std::max(maxO, m.O); maxV = std::max(maxV, m.V); maxN = std::max(maxN, m.N);
     maxB = std::max(maxB, m.B); maxW = std::max(maxW, m.W); maxT = std::max(maxT, T);
   }
@@ -870,7 +865,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     off[k].seg_off = bump.take((size_t)(m.V + 1) * 4); off[k].hull = bump.take((size_t)(m.V + 1) * 8);
     off[k].queue = bump.take((size_t)(m.V + 1) * 4);
     off[k].ent_seg = bump.take((O1 + 1) * 4);
-    off[k].chk = bump.take(O1 * 8);
+    off[k].chk = bump.take(O1 * sizeof(u32x4));
     off[k].tile_live = bump.take((size_t)h[k].T * std::max(1u, m.W) * 4);
     off[k].evt_cut = bump.take(((size_t)(m.O + 63) / 64 + 2) * 4);
     off[k].bitmap = 0;
@@ -899,8 +894,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     L.item_off = (uint32_t VL_GLOBAL *)(a1 + off[k].item); L.seg_off = (uint32_t VL_GLOBAL *)(a1 + off[k].seg_off);
     L.hull = (uint32_t VL_GLOBAL *)(a1 + off[k].hull); L.long_queue = (uint32_t VL_GLOBAL *)(a1 + off[k].queue);
     L.ent_seg = (uint32_t VL_GLOBAL *)(a1 + off[k].ent_seg);
-    L.chk = (uint64_t VL_GLOBAL *)(a1 + off[k].chk); L.tile_live = (uint32_t VL_GLOBAL *)(a1 + off[k].tile_live); L.evt_cut = (uint32_t VL_GLOBAL *)(a1 + off[k].evt_cut);
-    L.evt_slow = (uint32_t VL_GLOBAL *)(a1 + off[k].evt_slow);
+    L.chk = (u32x4 VL_GLOBAL *)(a1 + off[k].chk); L.tile_live = (uint32_t VL_GLOBAL *)(a1 + off[k].tile_live); L.evt_cut = (uint32_t VL_GLOBAL *)(a1 + off[k].evt_cut);
     L.bitmap = (uint32_t VL_GLOBAL *)nullptr;
     L.counters = (uint32_t VL_GLOBAL *)(a1 + o_counters) + (size_t)k * kCounters;
     mir_ptrs[k] = mirs[k]->dev;

@@ -81,14 +81,13 @@ __global__ void k_init(const DevJob *__restrict__ jobs) {
 //   [ring32, ...)                  the ring [occurrence % 192][row], addressed in uint16 from
 //                                  ring16 = 2 * ring32; a lane of the check wavefronts reads four
 //                                  rows of one occurrence with one 8-byte read
-//   [park, park + 256)             a batch of 64 occupancy event records
 extern __shared__ uint32_t vl_lds[];
 #define VL_LDS16 (reinterpret_cast<uint16_t *>(vl_lds))
 
 struct Walk {
   const uint16_t VL_GLOBAL *rows;   // first row of the group
   uint64_t ld;
-  uint32_t keys, ring16, park;  // LDS indices
+  uint32_t keys, ring16;  // LDS indices
   uint32_t tid, lane, row, nrows, n_occ, staged_lo, staged_hi, fast;
   uint32_t pre[2][4];     // the chunk after staged_hi, in flight
 };
@@ -202,10 +201,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k
   const auto g_prev_occ = L.prev_occ, g_evt_cut = L.evt_cut;
   const auto g_seed_off = L.seed_off, g_tile_range = L.tile_range;
   // 8-byte stream entries are read as one 64-bit word: x in the low half, y in the high half
-  const uint64_t VL_GLOBAL *g_chk = L.chk, *g_seeds = L.seeds;
+  const uint64_t VL_GLOBAL *g_seeds = L.seeds;
+  const u32x4 VL_GLOBAL *g_chk = L.chk;
   const u32x4 VL_GLOBAL *g_plan = L.plan;
-  const auto g_evt_slow = L.evt_slow;
-  const uint32_t has_reserved = m.has_reserved;
   const uint32_t local = blockIdx.x - J.unit_base;
   const uint32_t tile = local / J.n_groups, group = local % J.n_groups;
   const uint32_t row0 = group * J.rows;
@@ -224,7 +222,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k
   w.fast = J.fast;
   w.keys = m.occ_words * 64;
   w.ring16 = (w.keys + 64) * 2;
-  w.park = w.keys + 64 + kRing * kRingStride / 2;
   for (uint32_t x = w.tid; x < m.occ_words * 64; x += 256) vl_lds[x] = 0;
   if (w.tid < 64) vl_lds[w.keys + w.tid] = kKeyOk;
   // per-class file size and first mask word, one class per lane, read back by lane index
@@ -257,9 +254,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k
       if (hit) { key = min(key, kKeySafe | i); alive = 0; }
     }
   };
-  // any event, its register from the ring or from memory
-  auto event1 = [&](uint32_t o, uint32_t attr, bool tested) __attribute__((always_inline)) {
-    const uint32_t p = fetch(w, o);
+  // flips the range of a tuple whose base register is p (any shape of tuple)
+  auto apply1 = [&](uint32_t o, uint32_t attr, bool tested, uint32_t p) __attribute__((always_inline)) {
     const Touch t = locate(w, attr, __builtin_amdgcn_readlane(cls_tab_v, attr_class(attr)), p);
     const uint32_t hit = flip(t, attr_straddle(attr));
     if (tested) clash(hit, o);
@@ -267,81 +263,94 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k
   const uint32_t my_ring = (w.ring16 + w.row) * 2u;   // byte offset of this lane's row in ring slot 0
   const uint32_t my_occ = w.lane * 4;                 // byte offset of this lane's column of mask words
   char *const lds_bytes = reinterpret_cast<char *>(vl_lds);
-  // one event record, whatever it is
-  auto event_any = [&](const u32x4 r) __attribute__((always_inline)) {
-    const uint32_t o = r.w & 0xFFFFFFu;
-    if (r.w & kEvtSlow) {
-      event1(o, (uint32_t)(g_chk[o] >> 48), (r.w & kEvtTested) != 0);
-    } else {
-      const uint32_t p = *reinterpret_cast<const uint16_t *>(lds_bytes + my_ring + r.x);
-      const uint32_t msk = r.y << (p & 31u);
-      const uint32_t old = __hip_atomic_fetch_xor(reinterpret_cast<uint32_t *>(lds_bytes + ((((p >> 5) & 15u) << 8) + my_occ + r.z)),
-                                                  msk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
-      if (r.w & kEvtTested) clash(old & msk, o);
-    }
-  };
-  // A batch of up to 64 records, one per lane, fetched one chunk ahead, is parked in LDS and
-  // read back one record at a time by all lanes at once (a broadcast read), which puts the
-  // wave-uniform fields where vector instructions can use them without any scalar work.
-  // Lanes past the batch park zero records: those flip nothing.  Eight events are in
-  // flight: their eight registers are read from the ring, the eight mask updates are issued
-  // back to back (LDS executes them in order) and only then are the returned old bits
-  // examined.
-  constexpr int G = 8;
-  const uint32_t park = w.park * 4u;   // byte offset of the parked records
-  auto replay_parked = [&](uint32_t cnt) __attribute__((always_inline)) {
-    for (uint32_t g0 = 0; g0 < cnt; g0 += G) {
-      u32x4 r[G];
-      uint32_t p[G], old[G], msk[G];
-#pragma unroll
-      for (int t = 0; t < G; ++t) {
-        r[t] = *reinterpret_cast<const u32x4 *>(lds_bytes + park + (g0 + t) * 16u);
-        p[t] = *reinterpret_cast<const uint16_t *>(lds_bytes + my_ring + r[t].x);
-      }
-#pragma unroll
-      for (int t = 0; t < G; ++t) {
-        msk[t] = r[t].y << (p[t] & 31u);
-        old[t] = __hip_atomic_fetch_xor(reinterpret_cast<uint32_t *>(lds_bytes + ((((p[t] >> 5) & 15u) << 8) + my_occ + r[t].z)),
-                                        msk[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
-      }
-      uint32_t any_hit = 0;
-#pragma unroll
-      for (int t = 0; t < G; ++t) {
-        old[t] &= msk[t] & (uint32_t)((int32_t)r[t].w >> 31);   // kEvtTested is the sign bit
-        any_hit |= old[t];
-      }
-      if (__any((any_hit & alive) != 0)) {
-#pragma unroll
-        for (int t = 0; t < G; ++t) clash(old[t], __builtin_amdgcn_readfirstlane(r[t].w) & 0xFFFFFFu);
-      }
-    }
-  };
   auto fetch_records = [&](uint32_t from, uint32_t to) __attribute__((always_inline)) {
     u32x4 r = 0;
     if (from + w.lane < to) r = g_plan[from + w.lane];
     return r;
   };
-  // events [from, to); `first` holds the records [from, from + 64) when fetched ahead
-  auto events = [&](uint32_t from, uint32_t to, bool careful, u32x4 first) __attribute__((always_inline)) {
-    if (careful) {
-      for (uint32_t e = from; e < to; ++e) event_any(g_plan[e]);
+  // Replays a batch of up to 64 records held one per lane (lanes past the batch hold zero
+  // records, which flip nothing).  The fields of event j are read out of lane j; they are
+  // ready to use.  Eight events at a time: the eight mask updates are issued back to back
+  // (LDS executes them in order), and before their old bits are awaited the eight registers
+  // of the next group are already requested from the ring, so that one LDS round trip per
+  // group is exposed instead of two.
+  constexpr int G = 8;
+  auto replay = [&](const u32x4 r, uint32_t cnt) __attribute__((always_inline)) {
+    if (__any((r.w & kEvtSlow) != 0)) {
+      // rare: a tuple that may cross a mask word, or a register from outside the ring
+      for (uint32_t j = 0; j < cnt; ++j) {
+        const uint32_t sw = __builtin_amdgcn_readlane(r.w, j), o = sw & 0xFFFFFFu;
+        const bool slow = (sw & kEvtSlow) != 0;
+        const uint32_t attr = slow ? g_chk[o].y >> 16 : 0u;
+        const uint32_t p = slow ? fetch(w, o) : *reinterpret_cast<const uint16_t *>(lds_bytes + my_ring + __builtin_amdgcn_readlane(r.x, j));
+        if (slow) {
+          apply1(o, attr, (sw & kEvtTested) != 0, p);
+        } else {
+          const uint32_t msk = (uint32_t)__builtin_amdgcn_readlane(r.y, j) << (p & 31u);
+          const uint32_t old = __hip_atomic_fetch_xor(
+              reinterpret_cast<uint32_t *>(lds_bytes + ((((p >> 5) & 15u) << 8) + my_occ + __builtin_amdgcn_readlane(r.z, j))), msk,
+              __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+          if (sw & kEvtTested) clash(old & msk, o);
+        }
+      }
       return;
     }
+    uint32_t pc[G], pn[G] = {};
+    auto ring_reads = [&](uint32_t g0, uint32_t (&p)[G]) __attribute__((always_inline)) {
+#pragma unroll
+      for (int t = 0; t < G; ++t)
+        p[t] = *reinterpret_cast<const uint16_t *>(lds_bytes + my_ring + __builtin_amdgcn_readlane(r.x, g0 + t));
+    };
+    ring_reads(0, pc);
+    for (uint32_t g0 = 0; g0 < cnt; g0 += G) {
+      uint32_t old[G], msk[G];
+#pragma unroll
+      for (int t = 0; t < G; ++t) {
+        msk[t] = (uint32_t)__builtin_amdgcn_readlane(r.y, g0 + t) << (pc[t] & 31u);
+        old[t] = __hip_atomic_fetch_xor(
+            reinterpret_cast<uint32_t *>(lds_bytes + ((((pc[t] >> 5) & 15u) << 8) + my_occ + __builtin_amdgcn_readlane(r.z, g0 + t))),
+            msk[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+      }
+      if (g0 + G < cnt) ring_reads(g0 + G, pn);
+      uint32_t any_hit = 0;
+#pragma unroll
+      for (int t = 0; t < G; ++t) {
+        old[t] &= msk[t] & (uint32_t)((int32_t)__builtin_amdgcn_readlane(r.w, g0 + t) >> 31);   // kEvtTested is the sign bit
+        any_hit |= old[t];
+      }
+      if (__any((any_hit & alive) != 0)) {
+#pragma unroll
+        for (int t = 0; t < G; ++t) clash(old[t], __builtin_amdgcn_readlane(r.w, g0 + t) & 0xFFFFFFu);
+      }
+#pragma unroll
+      for (int t = 0; t < G; ++t) pc[t] = pn[t];
+    }
+  };
+  // events [from, to); `first` holds the records [from, from + 64) fetched ahead
+  auto events = [&](uint32_t from, uint32_t to, u32x4 first) __attribute__((always_inline)) {
     for (uint32_t e = from; e < to; e += 64) {
       u32x4 r = e == from ? first : fetch_records(e, to);
       if (e + w.lane >= to) r = 0;
-      *reinterpret_cast<u32x4 *>(lds_bytes + park + w.lane * 16u) = r;
-      replay_parked(min(64u, to - e));
+      replay(r, min(64u, to - e));
     }
   };
-  // the values live into the tile: their registers mostly lie before the ring
+  // The values live into the tile: their registers mostly lie before the ring and are
+  // gathered from memory, eight gathers in flight.  Lanes past the list hold occurrence 0.
   auto seed_events = [&](uint32_t from, uint32_t to) __attribute__((always_inline)) {
     for (uint32_t base = from; base < to; base += 64) {
       const uint32_t cnt = min(64u, to - base);
       const uint64_t raw = w.lane < cnt ? g_seeds[base + w.lane] : 0ull;
       const uint32_t ex = (uint32_t)raw, ey = (uint32_t)(raw >> 32);
-      for (uint32_t j = 0; j < cnt; ++j)
-        event1(__builtin_amdgcn_readlane(ex, j) & 0xFFFFFFu, __builtin_amdgcn_readlane(ey, j) >> 16, false);
+      for (uint32_t g0 = 0; g0 < cnt; g0 += G) {
+        uint32_t p[G];
+#pragma unroll
+        for (int t = 0; t < G; ++t)
+          p[t] = w.rows[(uint64_t)w.row * w.ld + (__builtin_amdgcn_readlane(ex, (g0 + t) & 63u) & 0xFFFFFFu)];
+#pragma unroll
+        for (int t = 0; t < G; ++t)
+          if (g0 + t < cnt)
+            apply1(__builtin_amdgcn_readlane(ex, (g0 + t) & 63u) & 0xFFFFFFu, __builtin_amdgcn_readlane(ey, (g0 + t) & 63u) >> 16, false, p[t]);
+      }
     }
   };
 
@@ -359,52 +368,53 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k
   // two reads and three compares, identical for every lane.
   auto load_chk = [&](uint32_t c) __attribute__((always_inline)) {
     const uint32_t o = c * kChunk + w.lane;
-    return (o >= oa && o < ob) ? g_chk[o] : 0ull;
+    u32x4 r = {0u, 0u, 0u, 0xFFFFFFFFu};   // outside the tile: nothing to test
+    if (o >= oa && o < ob) r = g_chk[o];
+    return r;
   };
-  auto checks = [&](uint32_t c, uint32_t part, const uint64_t raw) __attribute__((always_inline)) {
+  auto checks = [&](uint32_t c, uint32_t part, const u32x4 rec) __attribute__((always_inline)) {
     const uint32_t o = c * kChunk + w.lane;
-    const bool valid = o >= oa && o < ob;
-    const uint2 ent = make_uint2((uint32_t)raw, (uint32_t)(raw >> 32));
-    const uint32_t fl = ent.x >> 24, attr = ent.y >> 16, delta = ent.y & 0xFFFFu;
-    const bool is_chk = valid && (fl & kPlanChk), is_first = valid && (fl & kPlanFirst);
+    const uint32_t fl = rec.x & 0xFFu, attr = rec.y >> 16, delta = rec.y & 0xFFFFu;
+    const bool is_chk = (fl & kPlanChk) != 0;
     const uint32_t prev = o - delta;
-    const bool near = is_chk && delta != 0xFFFFu && in_ring(w, prev);
+    const bool near = (fl & kChkNear) && prev >= w.staged_lo;   // the ring starts at the tile's first staged chunk
     const bool far = is_chk && !near;
-    const uint32_t cls = attr_class(attr), width = attr_width(attr), align = attr_align(attr);
-    const uint32_t F = (uint32_t)__shfl((int)cls_tab_v, (int)cls, 64) & 0xFFFFu;
-    // shapes the three compares do not cover: alignment not a power of two, reserved
-    // registers, a tuple wider than its file
-    const bool generic = is_first && ((align & (align - 1)) != 0 || has_reserved || width > F);
-    const bool simple = is_first && !generic;
-    const uint32_t amask = simple ? align - 1u : 0u, limit = simple ? F - width : 0xFFFFFFFFu;
+    const bool generic = (fl & kChkGeneric) != 0;
     // Four rows per 8-byte read, two rows per 32-bit operation.  What is wrong in a row
     // leaves a non-zero half-word: p ^ q (differs from the previous occurrence),
     // p & (align - 1), and p ^ min(p, limit) (beyond the last base that fits).  Rows past
     // the last candidate hold zeros.  Only when something is non-zero are the rows looked
     // at one by one.
     typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
-    const uint32_t amask2 = amask * 0x10001u, limit2 = min(limit, 0xFFFFu) * 0x10001u;
-    const uint32_t a_p = (w.ring16 + (o % kRing) * kRingStride) >> 2;          // in 8-byte units
-    const uint32_t a_q = (w.ring16 + ((near ? prev : o) % kRing) * kRingStride) >> 2;
+    const uint32_t amask2 = rec.z, limit2 = rec.w;
+    const uint32_t a_p = (w.ring16 >> 2) + ((rec.x >> 8) & 0xFFFu);          // in 8-byte units
+    const uint32_t a_q = near ? (w.ring16 >> 2) + (rec.x >> 20) : a_p;
     const uint64_t *lds64 = reinterpret_cast<const uint64_t *>(vl_lds);
     auto wrong2 = [&](uint32_t pp, uint32_t qq) __attribute__((always_inline)) {
       const u16x2 mn = __builtin_elementwise_min(__builtin_bit_cast(u16x2, pp), __builtin_bit_cast(u16x2, limit2));
       return (pp ^ qq) | (pp & amask2) | (pp ^ __builtin_bit_cast(uint32_t, mn));
     };
     uint32_t acc = 0;
+    // this wavefront's third of the row quads, two quads (one 16-byte read) at a time
     const uint32_t n_quad = (w.nrows + 3) / 4;
-    for (uint32_t qd = part; qd < n_quad; qd += 3) {
+    const uint32_t q_lo = part * n_quad / 3, q_hi = (part + 1) * n_quad / 3;
+    uint32_t qd = q_lo;
+    for (; qd + 2 <= q_hi; qd += 2) {
+      const uint64_t pv0 = lds64[a_p + qd], pv1 = lds64[a_p + qd + 1], qv0 = lds64[a_q + qd], qv1 = lds64[a_q + qd + 1];
+      acc |= wrong2((uint32_t)pv0, (uint32_t)qv0) | wrong2((uint32_t)(pv0 >> 32), (uint32_t)(qv0 >> 32)) |
+             wrong2((uint32_t)pv1, (uint32_t)qv1) | wrong2((uint32_t)(pv1 >> 32), (uint32_t)(qv1 >> 32));
+    }
+    if (qd < q_hi) {
       const uint64_t pv = lds64[a_p + qd], qv = lds64[a_q + qd];
       acc |= wrong2((uint32_t)pv, (uint32_t)qv) | wrong2((uint32_t)(pv >> 32), (uint32_t)(qv >> 32));
     }
     if (__any(acc != 0 || generic)) {
       // rare: attribute row by row
-      for (uint32_t qd = part; qd < n_quad; qd += 3) {
+      for (uint32_t qd = q_lo; qd < q_hi; ++qd) {
         for (uint32_t r = 4 * qd; r < min(w.nrows, 4 * qd + 4); ++r) {
-          const uint32_t pr = VL_LDS16[w.ring16 + (o % kRing) * kRingStride + r];
-          const uint32_t qr = VL_LDS16[w.ring16 + ((near ? prev : o) % kRing) * kRingStride + r];
-          bool bad = (pr != qr) | ((pr & amask) != 0) | (pr > limit);
-          if (generic) bad = unrealizable(m, attr, F, pr);
+          const uint32_t pr = VL_LDS16[a_p * 4 + r], qr = VL_LDS16[a_q * 4 + r];
+          bool bad = (pr != qr) | ((pr & amask2 & 0xFFFFu) != 0) | (pr > (limit2 & 0xFFFFu));
+          if (generic) bad = unrealizable(m, attr, m.class_size[attr_class(attr)], pr);
           if (__any(bad)) {
             // the smallest failing key of this row among the chunk's checks
             uint32_t k = bad ? ((is_chk ? kKeyCons : kKeyReal) | o) : kKeyOk;
@@ -437,7 +447,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k
       if (pv != qv) key = min(key, kKeyCons | oj);
     }
     // occurrences whose successor is likely out of reach: keep their registers
-    uint64_t keep = __ballot(valid && (fl & kPlanKeep) && o % 3u == part);
+    uint64_t keep = __ballot((fl & kPlanKeep) && o % 3u == part);
     while (keep) {
       const uint32_t j = __builtin_ctzll(keep);
       keep &= keep - 1;
@@ -468,35 +478,29 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k
     __syncthreads();
   };
   if (role == 0) {
-    uint32_t cut_lo = clamp_cut(g_evt_cut[min(ca, n_chunk)]);
+    uint32_t cut_lo = ea;
     uint32_t v_cut_next = g_evt_cut[min(ca + 1, n_chunk) + lane_zero];
-    uint32_t v_slow_next = g_evt_slow[min(ca, n_chunk) + lane_zero];
-    u32x4 rec_next = 0;
+    u32x4 rec_next = fetch_records(ea, eb);   // the first batch, in flight during the seeds
     if (tile > 0) seed_events(g_seed_off[tile], g_seed_off[tile + 1]);
     for (uint32_t c = ca; c != c_stop; ++c) {
       if (c < c_end) stage();
       // what was fetched ahead during the previous chunk has arrived by now (staging
       // waited for every outstanding load)
       const uint32_t cut_hi = clamp_cut(__builtin_amdgcn_readfirstlane(v_cut_next));
-      const uint32_t slow_cur = __builtin_amdgcn_readfirstlane(v_slow_next);
-      const uint32_t from = c == ca ? ea : cut_lo, to = c + 1 >= c_end ? eb : cut_hi;
-      // the tile's first and last batch may hold events that other chunks release
-      const bool careful = c == ca || c + 1 >= c_end || slow_cur != 0;
+      const uint32_t from = cut_lo, to = c + 1 >= c_end ? eb : cut_hi;
       const u32x4 first = rec_next;
-      // fetch ahead for the next chunk, without waiting: its upper limit, its slow count
-      // and the 64 records from its lower limit on (those past its upper limit are dropped
-      // when the batch is parked)
+      // fetch ahead for the next chunk, without waiting: its upper limit and the 64 records
+      // from its lower limit on (those past its upper limit are dropped before the replay)
       cut_lo = cut_hi;
       v_cut_next = g_evt_cut[min(c + 2, n_chunk) + lane_zero];
-      v_slow_next = g_evt_slow[min(c + 1, n_chunk) + lane_zero];
       rec_next = fetch_records(cut_lo, eb);
-      events(from, to, careful, first);
+      events(from, to, first);
     }
   } else {
-    uint64_t chk_next = load_chk(ca);
+    u32x4 chk_next = load_chk(ca);
     for (uint32_t c = ca; c < c_end; ++c) {
       stage();
-      const uint64_t raw = chk_next;
+      const u32x4 raw = chk_next;
       chk_next = load_chk(c + 1);   // in flight while this chunk is checked
       checks(c, role - 1, raw);
     }
@@ -693,7 +697,7 @@ extern "C" int32_t vl_verify_multi(const vl_job *jobs, uint32_t n_jobs, vl_strea
     VL_HIP(hipEventRecord(s.copied, stream));
     s.n_valid = n_jobs;
   }
-  const size_t lds = (size_t)max_words * 64 * 4 + 64 * 4 + (size_t)kRing * kRingStride * 2 + 64 * sizeof(u32x4);
+  const size_t lds = (size_t)max_words * 64 * 4 + 64 * 4 + (size_t)kRing * kRingStride * 2;
   k_init<<<dim3((maxK + 255) / 256, n_jobs), 256, 0, stream>>>(s.dev);
   if (g_time_start) VL_HIP(hipEventRecord(g_time_start, stream));
   k_walk<<<units, 256, lds, stream>>>(s.dev, n_jobs);
