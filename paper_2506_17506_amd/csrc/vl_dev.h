@@ -61,8 +61,8 @@ __host__ __device__ inline uint64_t entry_pack(uint32_t x, uint32_t y) { return 
 //   y: distance to that previous occurrence (16 bits, saturated) | packed attributes << 16
 //   z: alignment - 1 in both halves (two candidates per 32-bit operation); 0 when nothing is to be tested
 //   w: the largest base that fits, in both halves; all ones when there is no limit
-// "seeds": per tile, the values live into it, as 8-byte entries
-//   occurrence whose register the value has (24 bits) | flags << 24, then 0xFFFF | attributes << 16
+// "seeds": per tile, the values live into it, as event records (below) whose x is unused:
+//   w names an occurrence of the vreg, from which the candidate's register is taken
 // "plan": the occupancy events in the order they take effect, as 16-byte records (below).
 // For each instruction: releases of operands that die there, then test-and-occupy of the
 // values it writes, then releases of values dead once it has executed; the events of a
@@ -74,8 +74,6 @@ constexpr uint32_t kChkNear = 4u;    // the previous occurrence is still in the 
                                      // (unless the tile starts in between)
 constexpr uint32_t kChkGeneric = 8u; // realizability needs the general test: alignment not a power of two,
                                      // reserved registers, or a tuple wider than its file
-constexpr uint32_t kPlanBirth = 16u; // occupy without testing (value becomes live at a boundary)
-constexpr uint32_t kPlanPost = 32u;  // the occurrence named is not at the event's own position
 constexpr uint32_t kPlanKeep = 64u;  // (chk) the next occurrence of the vreg is likely beyond the verifier's
                                      // LDS window: worth keeping this one's registers at hand
 
@@ -134,7 +132,7 @@ struct DevLive {
   uint32_t VL_GLOBAL *counters;   // [kCounters]
   // --- sized after the counting pass ---
   u32x4 VL_GLOBAL *plan;          // [plan_len + 8] occupancy events (the last 8 are padding, never applied)
-  uint64_t VL_GLOBAL *seeds;      // [n_seed] (x | y << 32)
+  u32x4 VL_GLOBAL *seeds;         // [n_seed] event records
   uint32_t VL_GLOBAL *seg;        // [n_seg][2]
   uint32_t VL_GLOBAL *tile_range; // [T][2] plan range of each tile
   uint32_t VL_GLOBAL *tile_live;  // [T][W] live-before row of each tile start (dense mode)

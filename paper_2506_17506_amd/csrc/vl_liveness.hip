@@ -658,7 +658,8 @@ __global__ __launch_bounds__(64) void k_seed(MIRS) {
       while (bits) {
         const uint32_t v = w * 32 + __ffs(bits) - 1;
         bits &= bits - 1;
-        L.seeds[pos++] = entry_pack(v, t);   // completed by k_seed_src
+        u32x4 r = {v, t, 0u, 0u};   // completed by k_seed_src
+        L.seeds[pos++] = r;
       }
     }
     total += __shfl(incl, 63, 64);
@@ -672,10 +673,12 @@ __global__ void k_seed_src(MIRS) {
   DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
   const uint32_t k = blockIdx.x * blockDim.x + threadIdx.x;
   if (k >= L.n_seed) return;
-  const uint64_t raw = L.seeds[k];
-  const uint32_t v = (uint32_t)raw, t = (uint32_t)(raw >> 32);
-  L.seeds[k] = entry_pack(source_occurrence(L, v, t * L.tile_len) | ((kPlanBirth | kPlanPost) << 24),
-                          0xFFFFu | (m.vattr[v] << 16));
+  const u32x4 raw = L.seeds[k];
+  const uint32_t v = raw.x, t = raw.y;
+  // the register is always gathered from memory: the ring offset stays unused
+  u32x4 r = event_record(m, source_occurrence(L, v, t * L.tile_len), m.vattr[v], false, true);
+  r.x = 0;
+  L.seeds[k] = r;
 }
 
 __global__ void k_collect(MIRS, uint32_t n) {
@@ -972,7 +975,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     h[k].plan_len = c[kCtrPlanLen]; h[k].n_seg = c[kCtrSeg]; h[k].n_seed = c[kCtrSeed];
     max_seed = std::max(max_seed, h[k].n_seed);
     off2[k].plan = b2.take(((size_t)h[k].plan_len + 8) * sizeof(u32x4));
-    off2[k].seeds = b2.take((size_t)std::max(1u, h[k].n_seed) * 8);
+    off2[k].seeds = b2.take((size_t)std::max(1u, h[k].n_seed) * sizeof(u32x4));
     off2[k].seg = b2.take((size_t)std::max(1u, h[k].n_seg) * 8);
     off2[k].range = b2.take((size_t)h[k].T * 8);
   }
@@ -985,7 +988,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
   char *a2 = (char *)batch->arena2;
   for (uint32_t k = 0; k < n; ++k) {
     DevLive &L = h[k];
-    L.plan = (u32x4 VL_GLOBAL *)(a2 + off2[k].plan); L.seeds = (uint64_t VL_GLOBAL *)(a2 + off2[k].seeds);
+    L.plan = (u32x4 VL_GLOBAL *)(a2 + off2[k].plan); L.seeds = (u32x4 VL_GLOBAL *)(a2 + off2[k].seeds);
     L.seg = (uint32_t VL_GLOBAL *)(a2 + off2[k].seg); L.tile_range = (uint32_t VL_GLOBAL *)(a2 + off2[k].range);
     L.live_after = dense ? (uint32_t VL_GLOBAL *)(a2 + off2[k].dense) : (uint32_t VL_GLOBAL *)nullptr;
   }

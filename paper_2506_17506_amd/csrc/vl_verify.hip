@@ -201,8 +201,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k
   const auto g_prev_occ = L.prev_occ, g_evt_cut = L.evt_cut;
   const auto g_seed_off = L.seed_off, g_tile_range = L.tile_range;
   // 8-byte stream entries are read as one 64-bit word: x in the low half, y in the high half
-  const uint64_t VL_GLOBAL *g_seeds = L.seeds;
-  const u32x4 VL_GLOBAL *g_chk = L.chk;
+  const u32x4 VL_GLOBAL *g_chk = L.chk, *g_seeds = L.seeds;
   const u32x4 VL_GLOBAL *g_plan = L.plan;
   const uint32_t local = blockIdx.x - J.unit_base;
   const uint32_t tile = local / J.n_groups, group = local % J.n_groups;
@@ -335,21 +334,34 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k
     }
   };
   // The values live into the tile: their registers mostly lie before the ring and are
-  // gathered from memory, eight gathers in flight.  Lanes past the list hold occurrence 0.
+  // gathered from memory, eight gathers in flight.  Lanes past the list hold zero records.
   auto seed_events = [&](uint32_t from, uint32_t to) __attribute__((always_inline)) {
     for (uint32_t base = from; base < to; base += 64) {
       const uint32_t cnt = min(64u, to - base);
-      const uint64_t raw = w.lane < cnt ? g_seeds[base + w.lane] : 0ull;
-      const uint32_t ex = (uint32_t)raw, ey = (uint32_t)(raw >> 32);
+      u32x4 r = 0;
+      if (w.lane < cnt) r = g_seeds[base + w.lane];
+      const bool any_slow = __any((r.w & kEvtSlow) != 0);
       for (uint32_t g0 = 0; g0 < cnt; g0 += G) {
         uint32_t p[G];
 #pragma unroll
         for (int t = 0; t < G; ++t)
-          p[t] = w.rows[(uint64_t)w.row * w.ld + (__builtin_amdgcn_readlane(ex, (g0 + t) & 63u) & 0xFFFFFFu)];
+          p[t] = w.rows[(uint64_t)w.row * w.ld + (__builtin_amdgcn_readlane(r.w, (g0 + t) & 63u) & 0xFFFFFFu)];
+        if (any_slow) {
 #pragma unroll
-        for (int t = 0; t < G; ++t)
-          if (g0 + t < cnt)
-            apply1(__builtin_amdgcn_readlane(ex, (g0 + t) & 63u) & 0xFFFFFFu, __builtin_amdgcn_readlane(ey, (g0 + t) & 63u) >> 16, false, p[t]);
+          for (int t = 0; t < G; ++t)
+            if (g0 + t < cnt) {
+              const uint32_t o = __builtin_amdgcn_readlane(r.w, (g0 + t) & 63u) & 0xFFFFFFu;
+              apply1(o, g_chk[o].y >> 16, false, p[t]);
+            }
+        } else {
+#pragma unroll
+          for (int t = 0; t < G; ++t) {
+            const uint32_t msk = (uint32_t)__builtin_amdgcn_readlane(r.y, (g0 + t) & 63u) << (p[t] & 31u);
+            __hip_atomic_fetch_xor(reinterpret_cast<uint32_t *>(lds_bytes + ((((p[t] >> 5) & 15u) << 8) + my_occ +
+                                                                               __builtin_amdgcn_readlane(r.z, (g0 + t) & 63u))),
+                                   msk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+          }
+        }
       }
     }
   };
