@@ -45,7 +45,8 @@ enum {
   VL_E_SHAPE = -2,      /* inconsistent sizes: offsets not monotone, K == 0, ld < n_occ, ... */
   VL_E_RANGE = -3,      /* vreg id >= n_vreg, class >= n_class, file > 512, width 0 or > 32,
                            align 0 or > 32, more than 8 classes, more than 64 operands in one
-                           instruction, unknown occurrence flag bits, successor >= n_block */
+                           instruction, unknown occurrence flag bits, successor >= n_block,
+                           2^24 or more occurrences, 2^28 or more instructions, more than 2^19 vregs */
   VL_E_LAYOUT = -4,     /* blocks do not tile 0..N-1, a block is empty, or a non-entry block has
                            no predecessor placed before it in the linear order */
   VL_E_NOT_STRICT = -5, /* some value is live into the entry block */

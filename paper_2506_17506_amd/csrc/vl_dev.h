@@ -88,9 +88,11 @@ constexpr uint32_t kKeepMaxGap = 4096;   // longer gaps are not worth a slot
 //   x  byte offset, inside the ring, of the slot of the occurrence that carries the register
 //   y  the tuple's mask at bit 0 (width ones)
 //   z  byte offset of the first mask word of the vreg's class (class_word * 256)
-//   w  that occurrence (24 bits) | kEvtSlow | kEvtTested
+//   w  that occurrence (24 bits) | kEvtPost | kEvtSlow | kEvtTested
 // The mask word of register p is word (p >> 5) & 15 of the class: every class can address
 // 16 words, so no clamp is needed (see DevMir::occ_words).
+constexpr uint32_t kEvtPost = 1u << 29;    // release of a value that is dead once its instruction has executed
+                                           // (the value still belongs to P of that instruction)
 constexpr uint32_t kEvtSlow = 1u << 30;    // not for the fast path: the tuple may cross a mask word, is 32 wide,
                                            // or its register has to come from outside the ring
 constexpr uint32_t kEvtTested = 1u << 31;  // occupy with test (a definition); otherwise a plain flip

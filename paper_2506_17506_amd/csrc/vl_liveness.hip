@@ -472,13 +472,17 @@ __global__ void k_plan_fill(MIRS) {
   uint32_t pos = L.item_off[item_of_instr(m, i)];
   const uint32_t o0 = m.occ_off[i], o1 = m.occ_off[i + 1];
   // an instruction's own operands are always inside the ring when its events are replayed
-  auto put = [&](uint32_t o, bool tested) { L.plan[pos++] = event_record(m, o, m.vattr[m.occ_vreg[o]], tested, true); };
+  auto put = [&](uint32_t o, bool tested, uint32_t extra) {
+    u32x4 r = event_record(m, o, m.vattr[m.occ_vreg[o]], tested, true);
+    r.w |= extra;
+    L.plan[pos++] = r;
+  };
   for (uint32_t o = o0; o < o1; ++o)
-    if (L.occ_role[o] & kRolePreKill) put(o, false);
+    if (L.occ_role[o] & kRolePreKill) put(o, false, 0u);
   for (uint32_t o = o0; o < o1; ++o)
-    if (L.occ_role[o] & kRoleTestSet) put(o, true);
+    if (L.occ_role[o] & kRoleTestSet) put(o, true, 0u);
   for (uint32_t o = o0; o < o1; ++o)
-    if (L.occ_role[o] & kRolePostKill) put(o, false);
+    if (L.occ_role[o] & kRolePostKill) put(o, false, kEvtPost);
 }
 
 // evt_cut[c] = index of the first event of the first item whose operands end in chunk c or

@@ -563,32 +563,14 @@ __global__ void k_finalize(const DevJob *__restrict__ jobs) {
   J.out[k] = r;
 }
 
-template <class P> __device__ inline uint32_t lower_bound(P a, uint32_t lo, uint32_t hi, uint32_t key) {
-  while (lo < hi) {
-    uint32_t mid = (lo + hi) >> 1;
-    if (a[mid] < key) lo = mid + 1; else hi = mid;
-  }
-  return lo;
-}
-
-// is v in P(i) = live_after(i) + defs(i)?
-__device__ inline bool occupied_at(const DevMir VL_GLOBAL &m, const DevLive VL_GLOBAL &L, uint32_t v, uint32_t i) {
-  const uint32_t lo = L.vcnt[v], hi = L.vcnt[v + 1];
-  if (lo == hi) return false;
-  const uint32_t b = m.instr_blk[i];
-  const uint32_t x = lower_bound(L.ent_instr, lo, hi, i + 1);  // first mention after i
-  if (x > lo && L.ent_instr[x - 1] >= m.blk_start[b]) {
-    const uint8_t info = L.ent_info[x - 1];                    // last mention at or before i, same block
-    return (info & kEntLiveAfter) || (L.ent_instr[x - 1] == i && (info & kEntHasDef));
-  }
-  if (x < hi && L.ent_instr[x] < m.blk_start[b + 1]) return (L.ent_info[x] & kEntHasUse) != 0;
-  return (L.live_out[(size_t)b * m.W + (v >> 5)] >> (v & 31)) & 1u;
-}
-
 // For a candidate whose first violation is a register clash at instruction i: the
-// lexicographically smallest pair (a < b) of one class, both in P(i), with overlapping
-// ranges.  At the first clashing instruction every clashing pair contains a vreg that
-// the instruction defines, so only pairs (definition, anything in P(i)) are examined.
+// lexicographically smallest pair (a < b) of one class, both in P(i) = live_after(i) + defs(i),
+// with overlapping ranges.  At the first clashing instruction every clashing pair contains a
+// vreg that the instruction defines, so only pairs (definition, anything in P(i)) are
+// examined.  P(i) is rebuilt as a bitset in LDS the way the walk builds occupancy, but over
+// vregs instead of registers: the live-in list of i's tile, then every event up to those of
+// i, flips one bit each (in any order); the releases of values dead after i are left out,
+// since such values still belong to P(i).
 __global__ __launch_bounds__(256) void k_resolve(const DevJob *__restrict__ jobs) {
   const DevJob &J = jobs[blockIdx.y];
   const uint32_t k = blockIdx.x;
@@ -597,8 +579,10 @@ __global__ __launch_bounds__(256) void k_resolve(const DevJob *__restrict__ jobs
   const DevLive VL_GLOBAL &L = *as_global(J.live);
   const uint16_t *row = J.cand + (uint64_t)k * J.ld;
   const uint32_t i = J.out[k].where;
+  extern __shared__ uint32_t in_p[];   // [W]
   __shared__ unsigned long long best;
   __shared__ uint32_t dv[kMaxOperands], dp[kMaxOperands], nd;
+  for (uint32_t x = threadIdx.x; x < m.W; x += blockDim.x) in_p[x] = 0;
   if (threadIdx.x == 0) {
     best = ~0ull;
     uint32_t n = 0;
@@ -612,21 +596,38 @@ __global__ __launch_bounds__(256) void k_resolve(const DevJob *__restrict__ jobs
     nd = n;
   }
   __syncthreads();
+  const uint32_t tile = i / L.tile_len;
+  auto flip_vreg = [&](uint32_t o) {
+    const uint32_t v = m.occ_vreg[o];
+    atomicXor(&in_p[v >> 5], 1u << (v & 31));
+  };
+  if (tile > 0)
+    for (uint32_t s = L.seed_off[tile] + threadIdx.x; s < L.seed_off[tile + 1]; s += blockDim.x) flip_vreg(L.seeds[s].w & 0xFFFFFFu);
+  const uint32_t item = i + m.instr_blk[i] + 1;   // boundary items come before their block's instructions
+  const uint32_t e_own = L.item_off[item], e_end = L.item_off[item + 1];
+  for (uint32_t e = L.tile_range[2 * tile] + threadIdx.x; e < e_end; e += blockDim.x) {
+    const uint32_t w = L.plan[e].w;
+    if (e >= e_own && (w & kEvtPost)) continue;
+    flip_vreg(w & 0xFFFFFFu);
+  }
+  __syncthreads();
   unsigned long long mine = ~0ull;
-  for (uint32_t x = threadIdx.x; x < m.V; x += blockDim.x) {
-    // cheap reject first: i outside the hull of x (coalesced reads), then the exact test
-    if (i < L.hull[2 * x] || i >= L.hull[2 * x + 1]) continue;
-    if (!occupied_at(m, L, x, i)) continue;
-    const uint32_t ax = m.vattr[x], px = row[L.first[x]], wx = attr_width(ax);
-    for (uint32_t t = 0; t < nd; ++t) {
-      const uint32_t d = dv[t];
-      if (d == x) continue;
-      const uint32_t ad = m.vattr[d];
-      if (attr_class(ad) != attr_class(ax)) continue;
-      const uint32_t pd = dp[t], wd = attr_width(ad);
-      if (pd < px + wx && px < pd + wd) {
-        const unsigned long long pr = ((unsigned long long)min(d, x) << 32) | max(d, x);
-        mine = pr < mine ? pr : mine;
+  for (uint32_t xw = threadIdx.x; xw < m.W; xw += blockDim.x) {
+    uint32_t word = in_p[xw];
+    while (word) {
+      const uint32_t x = xw * 32 + __ffs(word) - 1;
+      word &= word - 1;
+      const uint32_t ax = m.vattr[x], px = row[L.first[x]], wx = attr_width(ax);
+      for (uint32_t t = 0; t < nd; ++t) {
+        const uint32_t d = dv[t];
+        if (d == x) continue;
+        const uint32_t ad = m.vattr[d];
+        if (attr_class(ad) != attr_class(ax)) continue;
+        const uint32_t pd = dp[t], wd = attr_width(ad);
+        if (pd < px + wx && px < pd + wd) {
+          const unsigned long long pr = ((unsigned long long)min(d, x) << 32) | max(d, x);
+          mine = pr < mine ? pr : mine;
+        }
       }
     }
   }
@@ -667,7 +668,7 @@ extern "C" int32_t vl_verify_multi(const vl_job *jobs, uint32_t n_jobs, vl_strea
   VL_HIP(hipGetDevice(&device));
   if (device < 0 || device >= 16) return VL_E_ARG;
   std::vector<DevJob> tab(n_jobs);
-  uint32_t units = 0, maxK = 0, max_words = 0;
+  uint32_t units = 0, maxK = 0, max_words = 0, max_w = 1;
   for (uint32_t j = 0; j < n_jobs; ++j) {
     const vl_job &u = jobs[j];
     if (!u.mir || !u.live || !u.cand || !u.out) return VL_E_NULL;
@@ -684,6 +685,7 @@ extern "C" int32_t vl_verify_multi(const vl_job *jobs, uint32_t n_jobs, vl_strea
     units += d.n_units;
     maxK = std::max(maxK, u.K);
     max_words = std::max(max_words, u.mir->h.occ_words);
+    max_w = std::max(max_w, u.mir->h.W);
   }
   Scratch &s = g_scratch[device];
   std::lock_guard<std::mutex> lock(s.mu);
@@ -716,7 +718,7 @@ extern "C" int32_t vl_verify_multi(const vl_job *jobs, uint32_t n_jobs, vl_strea
   if (g_time_stop) VL_HIP(hipEventRecord(g_time_stop, stream));
   g_time_start = g_time_stop = nullptr;
   k_finalize<<<dim3((maxK + 255) / 256, n_jobs), 256, 0, stream>>>(s.dev);
-  k_resolve<<<dim3(maxK, n_jobs), 256, 0, stream>>>(s.dev);
+  k_resolve<<<dim3(maxK, n_jobs), 256, (size_t)max_w * 4, stream>>>(s.dev);
   VL_HIP(hipGetLastError());
   return VL_OK;
 }
