@@ -300,3 +300,31 @@ int vlo_contract(const vlo_mir *m, const uint8_t *live_in) {
   free(has);
   return bad;
 }
+
+/* ---- regeneration-loop reductions (Section 3.4 last paragraph, Section 4.2 metrics) ---- */
+void vlo_summarize(const vlo_result *res, uint32_t K, vlo_summary *out) {
+  out->first_ok = K;
+  out->passed = 0;
+  for (int s = 0; s < 4; ++s) out->hist[s] = 0;
+  for (uint32_t k = 0; k < K; ++k) {
+    out->hist[res[k].status] += 1;
+    if (res[k].status == VLO_OK && !out->passed) {
+      out->first_ok = k;
+      out->passed = 1;
+    }
+  }
+}
+
+void vlo_loop(const vlo_summary *s, const uint32_t *K, uint32_t n, vlo_loop_stats *out) {
+  out->n_passed = 0;
+  out->max_tries = 0;
+  out->sum_tries = 0;
+  for (int t = 0; t < 4; ++t) out->hist[t] = 0;
+  for (uint32_t j = 0; j < n; ++j) {
+    uint32_t tries = s[j].passed ? s[j].first_ok + 1 : K[j];
+    out->n_passed += s[j].passed;
+    if (tries > out->max_tries) out->max_tries = tries;
+    out->sum_tries += tries;
+    for (int t = 0; t < 4; ++t) out->hist[t] += s[j].hist[t];
+  }
+}

@@ -114,6 +114,21 @@ void vlo_verify_points(const vlo_mir *m, const uint32_t *P, const uint16_t *cand
  * 1 if the entry has live-ins; 2 if some block lacks an earlier predecessor. */
 int vlo_contract(const vlo_mir *m, const uint8_t *live_in);
 
+/* The regeneration loop of Section 3.4 tries samples one after the other until
+ * the verifier accepts one or the attempts are exhausted; Section 4.2 reports
+ * the number of attempts (average, maximum) and whether any of K samples
+ * passes (Pass@K).  Over the verdicts of one kernel's K samples, in sampling
+ * order: first_ok = index of the first accepted sample, K if none;
+ * passed = 1 iff some sample is accepted; hist[s] = samples with status s. */
+typedef struct { uint32_t first_ok, passed, hist[4]; } vlo_summary;
+void vlo_summarize(const vlo_result *res, uint32_t K, vlo_summary *out);
+
+/* Over n kernels: n_passed kernels with an accepted sample; tries of a kernel =
+ * first_ok + 1 if it passed, else all its K samples; max_tries and sum_tries
+ * over the kernels; hist summed. */
+typedef struct { uint32_t n_passed, max_tries; uint64_t sum_tries; uint64_t hist[4]; } vlo_loop_stats;
+void vlo_loop(const vlo_summary *s, const uint32_t *K, uint32_t n, vlo_loop_stats *out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -164,3 +164,26 @@ def verify_points(m, an: Analysis, cand: np.ndarray) -> np.ndarray:
     for k in range(cand.shape[0]):
         lib().vlo_verify_points(C.byref(s), _p(P), _p(cand[k]), C.c_void_p(out[k:k + 1].ctypes.data))
     return out
+
+
+SUMMARY_DTYPE = np.dtype([("first_ok", "<u4"), ("passed", "<u4"), ("hist", "<u4", (4,))])
+LOOP_DTYPE = np.dtype([("n_passed", "<u4"), ("max_tries", "<u4"), ("sum_tries", "<u8"), ("hist", "<u8", (4,))])
+
+
+def summarize(results: np.ndarray) -> np.ndarray:
+    """Regeneration-loop reduction over one kernel's verdicts, in sampling order
+    (Section 3.4; metrics of Section 4.2).  Returns SUMMARY_DTYPE [1]."""
+    res = np.ascontiguousarray(results, RESULT_DTYPE)
+    out = np.zeros(1, SUMMARY_DTYPE)
+    lib().vlo_summarize(C.c_void_p(res.ctypes.data), C.c_uint32(len(res)), C.c_void_p(out.ctypes.data))
+    return out
+
+
+def loop_stats(summaries: np.ndarray, Ks) -> np.ndarray:
+    """Over n kernels: passed kernels, maximum and summed attempts, histogram."""
+    s = np.ascontiguousarray(summaries, SUMMARY_DTYPE)
+    K = np.ascontiguousarray(Ks, np.uint32)
+    assert len(s) == len(K)
+    out = np.zeros(1, LOOP_DTYPE)
+    lib().vlo_loop(C.c_void_p(s.ctypes.data), C.c_void_p(K.ctypes.data), C.c_uint32(len(s)), C.c_void_p(out.ctypes.data))
+    return out

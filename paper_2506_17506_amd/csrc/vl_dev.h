@@ -34,6 +34,7 @@ struct DevMir {
   const uint32_t VL_GLOBAL *instr_blk;       // [N] block of each instruction
   const uint32_t VL_GLOBAL *vattr;           // [V] packed attributes, see attr_* below
   const uint8_t VL_GLOBAL *occ_flags;        // [O]
+  const uint64_t VL_GLOBAL *occ_rec;         // [O] vreg | (instruction << 2 | flags) << 32: one read instead of three
   uint32_t has_reserved;
   uint16_t class_size[kMaxClass];
   uint16_t class_word[kMaxClass];  // first occupancy word of the class
@@ -99,6 +100,7 @@ constexpr uint32_t kEvtTested = 1u << 31;  // occupy with test (a definition); o
 
 // Per-occurrence roles computed by the event kernel.
 constexpr uint8_t kRolePreKill = 1, kRoleTestSet = 2, kRolePostKill = 4, kRoleFirst = 8;
+constexpr uint8_t kRoleKill = 16;   // the occurrence's kill flag, copied to occ_kill in occurrence order later
 // Per sorted-entry info bits.
 constexpr uint8_t kEntLiveAfter = 1, kEntHasUse = 2, kEntHasDef = 4, kEntGroupStart = 8;
 
@@ -109,11 +111,12 @@ struct DevLive {
   uint32_t VL_GLOBAL *vcur;       // [V] placement cursors
   uint32_t VL_GLOBAL *vocc_tmp;   // [O] occurrences grouped by vreg, unordered
   uint32_t VL_GLOBAL *vocc;       // [O] occurrences grouped by vreg, ascending
-  uint32_t VL_GLOBAL *ent_instr;  // [O] instruction of each sorted entry
+  uint32_t VL_GLOBAL *ent_instr;  // [O] instruction << 2 | occurrence flags of each sorted entry (ascending per vreg)
   uint8_t VL_GLOBAL *ent_info;    // [O] kEnt* bits of each sorted entry
   uint32_t VL_GLOBAL *first;      // [V] first occurrence or kNone
-  uint32_t VL_GLOBAL *prev_occ;   // [O] previous occurrence of the same vreg or kNone
-  uint8_t VL_GLOBAL *occ_role;    // [O] kRole* bits
+  uint32_t VL_GLOBAL *prev_occ;   // [O] previous occurrence of the same vreg, written only where the 16-bit
+                                  //     distance of the check record is saturated
+  uint8_t VL_GLOBAL *occ_role;    // [O] kRole* bits, kRoleKill
   uint8_t VL_GLOBAL *occ_kill;    // [O]
   uint32_t VL_GLOBAL *use;        // [B][W] block bitsets
   uint32_t VL_GLOBAL *def;

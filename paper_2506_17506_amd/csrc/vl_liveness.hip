@@ -223,27 +223,40 @@ __global__ void k_summary(MIRS) {
   const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
   DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
   uint32_t e = blockIdx.x * blockDim.x + threadIdx.x;
-  uint32_t b = kNone, w = 0, dbits = 0, ubits = 0;
+  uint32_t b = kNone, w = 0, dbits = 0, ubits = 0, v = kNone, i = kNone, fl = 0;
+  const int lane = threadIdx.x & 63;
   if (e < m.O) {
-    // also records the instruction of each sorted entry for the kernels that follow;
-    // neighbours are looked up through the occurrence list here
-    const uint32_t o = L.vocc[e], v = m.occ_vreg[o], i = m.occ_instr[o];
-    L.ent_instr[e] = i;
-    const uint32_t fl = m.occ_flags[o], bit = 1u << (v & 31);
+    // also records instruction and flags of each sorted entry for the kernels that follow
+    const uint64_t rec = m.occ_rec[L.vocc[e]];
+    v = (uint32_t)rec;
+    const uint32_t ifl = (uint32_t)(rec >> 32);
+    L.ent_instr[e] = ifl;
+    i = ifl >> 2;
+    fl = ifl & 3u;
     b = m.instr_blk[i];
     w = v >> 5;
-    if (fl & VL_OCC_DEF) dbits = bit;
-    if (fl & VL_OCC_USE) {
-      const uint32_t lo = L.vcnt[v];
-      uint32_t gs = e;
-      while (gs > lo && m.occ_instr[L.vocc[gs - 1]] == i) --gs;
-      if (gs == lo || m.instr_blk[m.occ_instr[L.vocc[gs - 1]]] != b) ubits = bit;
+    if (fl & VL_OCC_DEF) dbits = 1u << (v & 31);
+  }
+  // Is this mention group the first of its vreg in the block?  The nearest earlier entry
+  // with another instruction decides; it usually sits a lane or two below.
+  bool decided = !(fl & VL_OCC_USE), first_in_block = false;
+  for (int d = 1; d <= 3; ++d) {
+    const uint32_t pv = __shfl_up(v, d, 64), pi = __shfl_up(i, d, 64), pb = __shfl_up(b, d, 64);
+    if (!decided && lane >= d) {
+      if (pv != v) { first_in_block = true; decided = true; }
+      else if (pi != i) { first_in_block = pb != b; decided = true; }
     }
   }
+  if (!decided) {   // the group reaches below this wavefront's first lane, or is long: look it up
+    const uint32_t lo = L.vcnt[v];
+    uint32_t gs = e;
+    while (gs > lo && (uint32_t)(m.occ_rec[L.vocc[gs - 1]] >> 34) == i) --gs;
+    first_in_block = gs == lo || m.instr_blk[(uint32_t)(m.occ_rec[L.vocc[gs - 1]] >> 34)] != b;
+  }
+  if ((fl & VL_OCC_USE) && first_in_block) ubits = 1u << (v & 31);
   // entries are sorted by vreg, then instruction: neighbours in a wavefront mostly hit
   // the same word of the same block.  OR them together along runs of equal (block, word)
   // and let the last lane of each run issue the atomics.
-  const int lane = threadIdx.x & 63;
   for (int d = 1; d < 64; d <<= 1) {
     const uint32_t pb = __shfl_up(b, d, 64), pw = __shfl_up(w, d, 64);
     const uint32_t pd = __shfl_up(dbits, d, 64), pu = __shfl_up(ubits, d, 64);
@@ -330,27 +343,27 @@ __global__ void k_events(MIRS) {
   if (e >= m.O) return;
   const uint32_t o = L.vocc[e], v = m.occ_vreg[o];
   const uint32_t lo = L.vcnt[v], hi = L.vcnt[v + 1];
-  const uint32_t i = L.ent_instr[e], b = m.instr_blk[i];
+  const uint32_t ifl = L.ent_instr[e], i = ifl >> 2, b = m.instr_blk[i];
   uint32_t gs = e, ge = e + 1;
-  while (gs > lo && L.ent_instr[gs - 1] == i) --gs;
-  while (ge < hi && L.ent_instr[ge] == i) ++ge;
+  while (gs > lo && (L.ent_instr[gs - 1] >> 2) == i) --gs;
+  while (ge < hi && (L.ent_instr[ge] >> 2) == i) ++ge;
   bool has_use = false, has_def = false;
   uint32_t first_use = kNone, first_def = kNone;
   for (uint32_t x = gs; x < ge; ++x) {
-    uint32_t f = m.occ_flags[L.vocc[x]];
+    const uint32_t f = x == e ? ifl : L.ent_instr[x];
     if (f & VL_OCC_USE) { has_use = true; if (first_use == kNone) first_use = x; }
     if (f & VL_OCC_DEF) { has_def = true; if (first_def == kNone) first_def = x; }
   }
   bool la;
-  if (ge < hi && m.instr_blk[L.ent_instr[ge]] == b) {
-    const uint32_t i2 = L.ent_instr[ge];
-    la = false;
-    for (uint32_t x = ge; x < hi && L.ent_instr[x] == i2; ++x) la |= (m.occ_flags[L.vocc[x]] & VL_OCC_USE) != 0;
+  const uint32_t nxt = ge < hi ? L.ent_instr[ge] : 0u;
+  if (ge < hi && m.instr_blk[nxt >> 2] == b) {
+    la = (nxt & VL_OCC_USE) != 0;
+    for (uint32_t x = ge + 1; x < hi && (L.ent_instr[x] >> 2) == (nxt >> 2); ++x) la |= (L.ent_instr[x] & VL_OCC_USE) != 0;
   } else {
     la = bit_get(L.live_out + (size_t)b * m.W, v);
   }
-  const uint32_t fl = m.occ_flags[o];
-  L.occ_kill[o] = (uint8_t)((fl & VL_OCC_USE) && !has_def && !la);
+  const uint32_t fl = ifl & 3u;
+  const bool kill = (fl & VL_OCC_USE) && !has_def && !la;
   uint8_t role = 0;
   if (!has_def && !la && e == first_use) role |= kRolePreKill;
   if (has_def && e == first_def) {
@@ -358,9 +371,9 @@ __global__ void k_events(MIRS) {
     if (!la) role |= kRolePostKill;
   }
   if (e == lo) role |= kRoleFirst;
-  L.occ_role[o] = role;
+  L.occ_role[o] = role | (kill ? kRoleKill : 0);
   const uint32_t prev = e > lo ? L.vocc[e - 1] : kNone;
-  L.prev_occ[o] = prev;
+  if (prev != kNone && o - prev >= 0xFFFFu) L.prev_occ[o] = prev;
   // the occurrence's check record; its events are counted into its instruction's item further down
   {
     // when an occurrence is checked the ring ends with that occurrence's chunk
@@ -402,7 +415,7 @@ __device__ inline uint32_t wave_incl_scan(uint32_t x) {
 // nearest occurrence of v before instruction `at`, else the first at or after it
 __device__ inline uint32_t source_occurrence(const DevLive VL_GLOBAL &L, uint32_t v, uint32_t at) {
   const uint32_t lo = L.vcnt[v], hi = L.vcnt[v + 1];
-  uint32_t x = lower_bound(L.ent_instr, lo, hi, at);
+  uint32_t x = lower_bound(L.ent_instr, lo, hi, at << 2);   // entries hold instruction << 2 | flags
   return x > lo ? L.vocc[x - 1] : (x < hi ? L.vocc[x] : 0u);
 }
 
@@ -471,6 +484,7 @@ __global__ void k_plan_fill(MIRS) {
   if (i >= m.N) return;
   uint32_t pos = L.item_off[item_of_instr(m, i)];
   const uint32_t o0 = m.occ_off[i], o1 = m.occ_off[i + 1];
+  for (uint32_t o = o0; o < o1; ++o) L.occ_kill[o] = (L.occ_role[o] & kRoleKill) ? 1 : 0;   // kill flags, in occurrence order
   // an instruction's own operands are always inside the ring when its events are replayed
   auto put = [&](uint32_t o, bool tested, uint32_t extra) {
     u32x4 r = event_record(m, o, m.vattr[m.occ_vreg[o]], tested, true);
@@ -541,13 +555,13 @@ __global__ void k_seg(MIRS) {
   if (!(info & kEntGroupStart)) { if (!kFill) L.ent_seg[e] = 0; return; }
   const uint32_t v = m.occ_vreg[L.vocc[e]];
   const uint32_t lo = L.vcnt[v], hi = L.vcnt[v + 1];
-  const uint32_t i = L.ent_instr[e], b = m.instr_blk[i];
+  const uint32_t i = L.ent_instr[e] >> 2, b = m.instr_blk[i];
   const uint32_t WB = (m.B + 31) / 32;
   const uint32_t VL_GLOBAL *live_blocks = L.blk_live + (size_t)v * WB;
   // was v occupied just before this stretch?
   bool cur;
   if (i == 0) cur = false;
-  else if (e > lo && L.ent_instr[e - 1] == i - 1) cur = (L.ent_info[e - 1] & (kEntHasDef | kEntLiveAfter)) != 0;
+  else if (e > lo && (L.ent_instr[e - 1] >> 2) == i - 1) cur = (L.ent_info[e - 1] & (kEntHasDef | kEntLiveAfter)) != 0;
   else if (i > m.blk_start[b]) cur = (info & kEntHasUse) != 0;
   else cur = bit_get(L.live_out + (size_t)(b - 1) * m.W, v);
   // runs that started before this stretch and ended before it: the end index lags the
@@ -562,10 +576,10 @@ __global__ void k_seg(MIRS) {
     cur = member;
   };
   uint32_t ge = e + 1;
-  while (ge < hi && L.ent_instr[ge] == i) ++ge;
+  while (ge < hi && (L.ent_instr[ge] >> 2) == i) ++ge;
   const bool la = (info & kEntLiveAfter) != 0;
   span(i, i + 1, (info & kEntHasDef) || la);
-  const uint32_t i2 = ge < hi ? L.ent_instr[ge] : m.N;
+  const uint32_t i2 = ge < hi ? L.ent_instr[ge] >> 2 : m.N;
   const uint32_t b2 = ge < hi ? m.instr_blk[i2] : m.B;
   if (b2 == b) {
     span(i + 1, i2, la);

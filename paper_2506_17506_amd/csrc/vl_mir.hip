@@ -96,12 +96,16 @@ extern "C" int32_t vl_mir_create(const vl_mir_desc *d, vl_mir **out) {
   for (uint32_t b = 0; b < B; ++b)
     for (uint32_t i = d->blk_start[b]; i < d->blk_start[b + 1]; ++i) instr_blk[i] = b;
   for (uint32_t v = 0; v < V; ++v) vattr[v] = vl::attr_pack(d->vreg_class[v], d->vreg_width[v], d->vreg_align[v]);
+  std::vector<uint64_t> occ_rec(O ? O : 1);
+  for (uint32_t o = 0; o < O; ++o)
+    occ_rec[o] = (uint64_t)d->occ_vreg[o] | ((uint64_t)((occ_instr[o] << 2) | d->occ_flags[o]) << 32);
 
   Bump bump;
   size_t o_blk = bump.take((B + 1) * 4), o_soff = bump.take((B + 1) * 4), o_succ = bump.take((size_t)(E ? E : 1) * 4);
   size_t o_ooff = bump.take((size_t)(N + 1) * 4), o_ov = bump.take((size_t)(O ? O : 1) * 4);
   size_t o_oi = bump.take((size_t)(O ? O : 1) * 4), o_ib = bump.take((size_t)N * 4);
   size_t o_va = bump.take((size_t)(V ? V : 1) * 4), o_of = bump.take((size_t)(O ? O : 1));
+  size_t o_rec = bump.take((size_t)(O ? O : 1) * 8);
   size_t o_dev = bump.take(sizeof(vl::DevMir));
 
   vl_mir *m = new (std::nothrow) vl_mir;
@@ -125,6 +129,7 @@ extern "C" int32_t vl_mir_create(const vl_mir_desc *d, vl_mir **out) {
   up(o_ib, instr_blk.data(), (size_t)N * 4);
   up(o_va, vattr.data(), (size_t)V * 4);
   up(o_of, d->occ_flags, (size_t)O);
+  up(o_rec, occ_rec.data(), (size_t)O * 8);
 
   vl::DevMir &h = m->h;
   h.N = N; h.V = V; h.B = B; h.O = O; h.C = d->n_class; h.E = E; h.W = (V + 31) / 32;
@@ -137,6 +142,7 @@ extern "C" int32_t vl_mir_create(const vl_mir_desc *d, vl_mir **out) {
   h.instr_blk = (const uint32_t VL_GLOBAL *)(base + o_ib);
   h.vattr = (const uint32_t VL_GLOBAL *)(base + o_va);
   h.occ_flags = (const uint8_t VL_GLOBAL *)(base + o_of);
+  h.occ_rec = (const uint64_t VL_GLOBAL *)(base + o_rec);
   // mask words: classes smallest first, so that the 16 words every class may address from
   // its first one mostly fall on words of later classes
   std::vector<uint32_t> order(d->n_class);
