@@ -156,6 +156,19 @@ typedef struct {
 } vl_job;
 int32_t vl_verify_multi(const vl_job *jobs, uint32_t n_jobs, vl_stream stream);
 
+/* Regeneration-loop reductions (Section 3.4, last paragraph: samples are tried until the
+ * verifier accepts one or the attempts are exhausted; Section 4.2: Pass@K, average and
+ * maximum number of attempts).  Reads the results a preceding vl_verify_multi /
+ * vl_verify_batch on the same stream wrote into jobs[j].out, in sampling order k = 0..K-1.
+ * summaries [device]: n_jobs records, first_ok = index of the first accepted candidate
+ * (K if none), passed = 1 iff one is accepted, hist[s] = candidates with status s.
+ * stats [device], may be NULL: one record over all jobs; a job's attempts are
+ * first_ok + 1 if it passed, else all its K candidates.  Asynchronous on `stream`. */
+typedef struct { uint32_t first_ok, passed, hist[4]; } vl_summary;
+typedef struct { uint32_t n_passed, max_tries; uint64_t sum_tries; uint64_t hist[4]; } vl_loop_stats;
+int32_t vl_summarize_multi(const vl_job *jobs, uint32_t n_jobs, vl_summary *summaries, vl_loop_stats *stats,
+                           vl_stream stream);
+
 /* Measurement aid for callers that cannot allocate inside the timed region: the next
  * vl_verify_multi / vl_verify_batch call on this thread records the two hipEvent_t
  * (caller-owned, either may be NULL) on its stream immediately before and after the

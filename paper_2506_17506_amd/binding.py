@@ -16,6 +16,8 @@ LIB_PATH = os.path.join(HERE, "libvl.so")
 
 VL_DENSE_POINTS = 1
 RESULT_DTYPE = np.dtype([("status", "<u4"), ("where", "<u4"), ("a", "<u4"), ("b", "<u4")])
+SUMMARY_DTYPE = np.dtype([("first_ok", "<u4"), ("passed", "<u4"), ("hist", "<u4", (4,))])                       # vl_summary
+LOOP_DTYPE = np.dtype([("n_passed", "<u4"), ("max_tries", "<u4"), ("sum_tries", "<u8"), ("hist", "<u8", (4,))])  # vl_loop_stats
 
 
 class VlError(RuntimeError):
@@ -75,6 +77,8 @@ def load():
         L.vl_verify_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint64, C.c_void_p, C.c_void_p]
         L.vl_verify_multi.restype = C.c_int32
         L.vl_verify_multi.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p]
+        L.vl_summarize_multi.restype = C.c_int32
+        L.vl_summarize_multi.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.vl_verify_time_next.restype = C.c_int32
         L.vl_verify_time_next.argtypes = [C.c_void_p, C.c_void_p]
         L.vl_strerror.restype = C.c_char_p
@@ -196,6 +200,16 @@ def vl_verify_multi(jobs, stream=None) -> None:
     rc = load().vl_verify_multi(arr, len(arr), _stream_ptr(stream))
     if rc != 0:
         raise VlError(rc, "vl_verify_multi")
+
+
+def vl_summarize_multi(jobs, summaries, stats=None, stream=None) -> None:
+    """summaries: device buffer of len(jobs) vl_summary records (24 bytes each); stats:
+    device buffer of one vl_loop_stats record (48 bytes) or None."""
+    arr = jobs if isinstance(jobs, C.Array) else make_jobs(jobs)
+    rc = load().vl_summarize_multi(arr, len(arr), C.c_void_p(_dev_ptr(summaries)),
+                                   C.c_void_p(_dev_ptr(stats)) if stats is not None else None, _stream_ptr(stream))
+    if rc != 0:
+        raise VlError(rc, "vl_summarize_multi")
 
 
 def vl_verify_time_next(start_event, stop_event) -> None:

@@ -660,15 +660,17 @@ extern "C" int32_t vl_verify_time_next(void *start, void *stop) {
   return VL_OK;
 }
 
-extern "C" int32_t vl_verify_multi(const vl_job *jobs, uint32_t n_jobs, vl_stream stream_) {
-  if (!jobs) return VL_E_NULL;
-  if (n_jobs == 0 || n_jobs > 65535) return VL_E_SHAPE;
-  hipStream_t stream = (hipStream_t)stream_;
-  int device = 0;
-  VL_HIP(hipGetDevice(&device));
-  if (device < 0 || device >= 16) return VL_E_ARG;
-  std::vector<DevJob> tab(n_jobs);
+namespace {
+struct Launch {
+  DevJob *dev = nullptr;
   uint32_t units = 0, maxK = 0, max_words = 0, max_w = 1;
+};
+
+// Validates the jobs, lays out the device job table and makes sure the device copy is
+// current (the copy is skipped when the table is the one already there).  Called with the
+// device's scratch locked.
+int32_t prepare_jobs(const vl_job *jobs, uint32_t n_jobs, hipStream_t stream, Scratch &s, Launch &out) {
+  std::vector<DevJob> tab(n_jobs);
   for (uint32_t j = 0; j < n_jobs; ++j) {
     const vl_job &u = jobs[j];
     if (!u.mir || !u.live || !u.cand || !u.out) return VL_E_NULL;
@@ -679,16 +681,14 @@ extern "C" int32_t vl_verify_multi(const vl_job *jobs, uint32_t n_jobs, vl_strea
     d.mir = u.mir->dev; d.live = u.live->dev; d.cand = u.cand; d.out = u.out; d.ld = u.ld; d.K = u.K;
     d.n_groups = (u.K + 63) / 64;
     d.rows = (u.K + d.n_groups - 1) / d.n_groups;
-    d.unit_base = units;
+    d.unit_base = out.units;
     d.n_units = d.n_groups * u.live->h.T;
     d.fast = (((uintptr_t)u.cand & 15) == 0 && (u.ld & 7) == 0) ? 1u : 0u;
-    units += d.n_units;
-    maxK = std::max(maxK, u.K);
-    max_words = std::max(max_words, u.mir->h.occ_words);
-    max_w = std::max(max_w, u.mir->h.W);
+    out.units += d.n_units;
+    out.maxK = std::max(out.maxK, u.K);
+    out.max_words = std::max(out.max_words, u.mir->h.occ_words);
+    out.max_w = std::max(out.max_w, u.mir->h.W);
   }
-  Scratch &s = g_scratch[device];
-  std::lock_guard<std::mutex> lock(s.mu);
   if (s.cap < n_jobs) {
     if (s.copied) VL_HIP(hipEventSynchronize(s.copied));
     VL_HIP(hipStreamSynchronize(stream));
@@ -711,14 +711,87 @@ extern "C" int32_t vl_verify_multi(const vl_job *jobs, uint32_t n_jobs, vl_strea
     VL_HIP(hipEventRecord(s.copied, stream));
     s.n_valid = n_jobs;
   }
-  const size_t lds = (size_t)max_words * 64 * 4 + 64 * 4 + (size_t)kRing * kRingStride * 2;
-  k_init<<<dim3((maxK + 255) / 256, n_jobs), 256, 0, stream>>>(s.dev);
+  out.dev = s.dev;
+  return VL_OK;
+}
+
+// ---- regeneration-loop reductions ----------------------------------------------------
+__global__ void k_stats_clear(vl_loop_stats *stats) {
+  if (threadIdx.x == 0) *stats = vl_loop_stats{0, 0, 0, {0, 0, 0, 0}};
+}
+
+// one workgroup per job: histogram of the statuses and the first accepted candidate
+__global__ __launch_bounds__(256) void k_summarize(const DevJob *__restrict__ jobs, vl_summary *__restrict__ summaries,
+                                                   vl_loop_stats *stats) {
+  const DevJob &J = jobs[blockIdx.x];
+  __shared__ uint32_t hist[4], first;
+  if (threadIdx.x < 4) hist[threadIdx.x] = 0;
+  if (threadIdx.x == 0) first = J.K;
+  __syncthreads();
+  uint32_t mine[4] = {0, 0, 0, 0}, my_first = J.K;
+  for (uint32_t k = threadIdx.x; k < J.K; k += blockDim.x) {
+    const uint32_t st = J.out[k].status & 3u;
+    mine[0] += st == 0; mine[1] += st == 1; mine[2] += st == 2; mine[3] += st == 3;
+    if (st == VL_STATUS_OK) my_first = min(my_first, k);
+  }
+  for (int t = 0; t < 4; ++t)
+    if (mine[t]) atomicAdd(&hist[t], mine[t]);
+  if (my_first != J.K) atomicMin(&first, my_first);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const uint32_t passed = first < J.K ? 1u : 0u;
+    summaries[blockIdx.x] = vl_summary{first, passed, {hist[0], hist[1], hist[2], hist[3]}};
+    if (stats) {
+      const uint32_t tries = passed ? first + 1 : J.K;
+      atomicAdd(&stats->n_passed, passed);
+      atomicMax(&stats->max_tries, tries);
+      atomicAdd((unsigned long long *)&stats->sum_tries, (unsigned long long)tries);
+      for (int t = 0; t < 4; ++t) atomicAdd((unsigned long long *)&stats->hist[t], (unsigned long long)hist[t]);
+    }
+  }
+}
+}  // namespace
+
+extern "C" int32_t vl_summarize_multi(const vl_job *jobs, uint32_t n_jobs, vl_summary *summaries, vl_loop_stats *stats,
+                                      vl_stream stream_) {
+  if (!jobs || !summaries) return VL_E_NULL;
+  if (n_jobs == 0 || n_jobs > 65535) return VL_E_SHAPE;
+  hipStream_t stream = (hipStream_t)stream_;
+  int device = 0;
+  VL_HIP(hipGetDevice(&device));
+  if (device < 0 || device >= 16) return VL_E_ARG;
+  Scratch &s = g_scratch[device];
+  std::lock_guard<std::mutex> lock(s.mu);
+  Launch L;
+  const int32_t rc = prepare_jobs(jobs, n_jobs, stream, s, L);
+  if (rc != VL_OK) return rc;
+  // the totals are cleared by a kernel, not a memset, so that the call can be captured
+  if (stats) k_stats_clear<<<1, 64, 0, stream>>>(stats);
+  k_summarize<<<n_jobs, 256, 0, stream>>>(L.dev, summaries, stats);
+  VL_HIP(hipGetLastError());
+  return VL_OK;
+}
+
+extern "C" int32_t vl_verify_multi(const vl_job *jobs, uint32_t n_jobs, vl_stream stream_) {
+  if (!jobs) return VL_E_NULL;
+  if (n_jobs == 0 || n_jobs > 65535) return VL_E_SHAPE;
+  hipStream_t stream = (hipStream_t)stream_;
+  int device = 0;
+  VL_HIP(hipGetDevice(&device));
+  if (device < 0 || device >= 16) return VL_E_ARG;
+  Scratch &s = g_scratch[device];
+  std::lock_guard<std::mutex> lock(s.mu);
+  Launch L;
+  const int32_t rc = prepare_jobs(jobs, n_jobs, stream, s, L);
+  if (rc != VL_OK) return rc;
+  const size_t lds = (size_t)L.max_words * 64 * 4 + 64 * 4 + (size_t)kRing * kRingStride * 2;
+  k_init<<<dim3((L.maxK + 255) / 256, n_jobs), 256, 0, stream>>>(L.dev);
   if (g_time_start) VL_HIP(hipEventRecord(g_time_start, stream));
-  k_walk<<<units, 256, lds, stream>>>(s.dev, n_jobs);
+  k_walk<<<L.units, 256, lds, stream>>>(L.dev, n_jobs);
   if (g_time_stop) VL_HIP(hipEventRecord(g_time_stop, stream));
   g_time_start = g_time_stop = nullptr;
-  k_finalize<<<dim3((maxK + 255) / 256, n_jobs), 256, 0, stream>>>(s.dev);
-  k_resolve<<<dim3(maxK, n_jobs), 256, (size_t)max_w * 4, stream>>>(s.dev);
+  k_finalize<<<dim3((L.maxK + 255) / 256, n_jobs), 256, 0, stream>>>(L.dev);
+  k_resolve<<<dim3(L.maxK, n_jobs), 256, (size_t)L.max_w * 4, stream>>>(L.dev);
   VL_HIP(hipGetLastError());
   return VL_OK;
 }
