@@ -131,7 +131,6 @@ struct DevLive {
   uint32_t VL_GLOBAL *hull;       // [V][2]
   uint32_t VL_GLOBAL *seed_off;   // [T+1]
   uint32_t VL_GLOBAL *seed_cur;   // [T]
-  uint32_t VL_GLOBAL *blk_live;   // [V][ceil(B/32)] blocks each vreg is live into
   uint32_t VL_GLOBAL *long_queue; // [V] vregs whose occurrence list needs the bitmap sort
   uint32_t VL_GLOBAL *bitmap;     // [ceil(O/32)] scratch for the bitmap sort, one list at a time per block
   uint32_t VL_GLOBAL *counters;   // [kCounters]

@@ -523,22 +523,6 @@ __global__ void k_evt_cut(MIRS) {
 }
 
 // ---- 5b. live intervals ---------------------------------------------------------------
-// blk_live[v] = bitmask over blocks b with v in live_in[b] (the transpose of live_in), so
-// that a vreg finds the blocks it is live through without testing every block.
-__global__ void k_blk_transpose(MIRS) {
-  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.z]);
-  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.z]);
-  const uint32_t b = blockIdx.y, w = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b >= m.B || w >= m.W) return;
-  uint32_t bits = L.live_in[(size_t)b * m.W + w];
-  const uint32_t WB = (m.B + 31) / 32;
-  while (bits) {
-    const uint32_t v = w * 32 + __ffs(bits) - 1;
-    bits &= bits - 1;
-    atomicOr(&L.blk_live[(size_t)v * WB + (b >> 5)], 1u << (b & 31));
-  }
-}
-
 // Membership of v in P(.) changes only at instructions that mention v and at block
 // boundaries.  The lane of each mention group (all mentions of v at one instruction) owns
 // the stretch from its instruction up to the next mention of v (the last group: up to the
@@ -556,8 +540,6 @@ __global__ void k_seg(MIRS) {
   const uint32_t v = m.occ_vreg[L.vocc[e]];
   const uint32_t lo = L.vcnt[v], hi = L.vcnt[v + 1];
   const uint32_t i = L.ent_instr[e] >> 2, b = m.instr_blk[i];
-  const uint32_t WB = (m.B + 31) / 32;
-  const uint32_t VL_GLOBAL *live_blocks = L.blk_live + (size_t)v * WB;
   // was v occupied just before this stretch?
   bool cur;
   if (i == 0) cur = false;
@@ -586,7 +568,7 @@ __global__ void k_seg(MIRS) {
   } else {
     span(i + 1, m.blk_start[b + 1], la);
     for (uint32_t x = b + 1; x < b2; ++x)
-      span(m.blk_start[x], m.blk_start[x + 1], (live_blocks[x >> 5] >> (x & 31)) & 1u);
+      span(m.blk_start[x], m.blk_start[x + 1], bit_get(L.live_in + (size_t)x * m.W, v));
     if (ge < hi) span(m.blk_start[b2], i2, (L.ent_info[ge] & kEntHasUse) != 0);
   }
   if (ge >= hi && cur) { if (kFill) L.seg[2 * (size_t)n_end + 1] = m.N; ++n_end; last_end = m.N; }
@@ -854,7 +836,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
 
   // ---- arena 1 layout: [zeroed zone | counters | rest | device tables] ----
   std::vector<DevLive> h(n);
-  struct Off1 { size_t vcnt, vcur, use, def, in, seed_off, seed_cur, blk_live, out, tmp, vocc, ent_instr, ent_info, first, prev,
+  struct Off1 { size_t vcnt, vcur, use, def, in, seed_off, seed_cur, out, tmp, vocc, ent_instr, ent_info, first, prev,
                 role, kill, item, seg_off, hull, queue, bitmap, ent_seg, chk, evt_cut, tile_live; };
   std::vector<Off1> off(n);
   Bump bump;
@@ -869,7 +851,6 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     off[k].vcur = bump.take((size_t)(m.V + 1) * 4);
     off[k].use = bump.take(bw); off[k].def = bump.take(bw); off[k].in = bump.take(bw);
     off[k].seed_off = bump.take((size_t)(T + 1) * 4); off[k].seed_cur = bump.take((size_t)(T + 1) * 4);
-    off[k].blk_live = bump.take((size_t)(m.V + 1) * ((m.B + 31) / 32) * 4);
     off[k].item = bump.take((size_t)(m.N + m.B + 1) * 4);   // event counts are accumulated with atomics
     maxO = std::max(maxO, m.O); maxV = std::max(maxV, m.V); maxN = std::max(maxN, m.N);
     maxB = std::max(maxB, m.B); maxW = std::max(maxW, m.W); maxT = std::max(maxT, T);
@@ -907,7 +888,6 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     L.use = (uint32_t VL_GLOBAL *)(a1 + off[k].use); L.def = (uint32_t VL_GLOBAL *)(a1 + off[k].def);
     L.live_in = (uint32_t VL_GLOBAL *)(a1 + off[k].in); L.live_out = (uint32_t VL_GLOBAL *)(a1 + off[k].out);
     L.seed_off = (uint32_t VL_GLOBAL *)(a1 + off[k].seed_off); L.seed_cur = (uint32_t VL_GLOBAL *)(a1 + off[k].seed_cur);
-    L.blk_live = (uint32_t VL_GLOBAL *)(a1 + off[k].blk_live);
     L.vocc_tmp = (uint32_t VL_GLOBAL *)(a1 + off[k].tmp); L.vocc = (uint32_t VL_GLOBAL *)(a1 + off[k].vocc);
     L.ent_instr = (uint32_t VL_GLOBAL *)(a1 + off[k].ent_instr); L.ent_info = (uint8_t VL_GLOBAL *)(a1 + off[k].ent_info);
     L.first = (uint32_t VL_GLOBAL *)(a1 + off[k].first); L.prev_occ = (uint32_t VL_GLOBAL *)(a1 + off[k].prev);
@@ -958,7 +938,6 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
   k_boundary<false><<<dim3(maxB, n), 64, 0, stream>>>(dm, dl);
   k_scan<kScanItems><<<n, 1024, 0, stream>>>(dm, dl);
   k_evt_cut<<<grid1(maxO / 64 + 2, TB, n), TB, 0, stream>>>(dm, dl);
-  k_blk_transpose<<<dim3((maxW + 63) / 64, maxB, n), 64, 0, stream>>>(dm, dl);
   k_seg<false><<<grid1(maxO, TB, n), TB, 0, stream>>>(dm, dl);
   k_scan<kScanSeg><<<n, 1024, 0, stream>>>(dm, dl);
   k_seg_off<<<grid1(maxV + 1, TB, n), TB, 0, stream>>>(dm, dl);

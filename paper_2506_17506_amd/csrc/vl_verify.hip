@@ -716,13 +716,8 @@ int32_t prepare_jobs(const vl_job *jobs, uint32_t n_jobs, hipStream_t stream, Sc
 }
 
 // ---- regeneration-loop reductions ----------------------------------------------------
-__global__ void k_stats_clear(vl_loop_stats *stats) {
-  if (threadIdx.x == 0) *stats = vl_loop_stats{0, 0, 0, {0, 0, 0, 0}};
-}
-
 // one workgroup per job: histogram of the statuses and the first accepted candidate
-__global__ __launch_bounds__(256) void k_summarize(const DevJob *__restrict__ jobs, vl_summary *__restrict__ summaries,
-                                                   vl_loop_stats *stats) {
+__global__ __launch_bounds__(256) void k_summarize(const DevJob *__restrict__ jobs, vl_summary *__restrict__ summaries) {
   const DevJob &J = jobs[blockIdx.x];
   __shared__ uint32_t hist[4], first;
   if (threadIdx.x < 4) hist[threadIdx.x] = 0;
@@ -738,17 +733,35 @@ __global__ __launch_bounds__(256) void k_summarize(const DevJob *__restrict__ jo
     if (mine[t]) atomicAdd(&hist[t], mine[t]);
   if (my_first != J.K) atomicMin(&first, my_first);
   __syncthreads();
-  if (threadIdx.x == 0) {
-    const uint32_t passed = first < J.K ? 1u : 0u;
-    summaries[blockIdx.x] = vl_summary{first, passed, {hist[0], hist[1], hist[2], hist[3]}};
-    if (stats) {
-      const uint32_t tries = passed ? first + 1 : J.K;
-      atomicAdd(&stats->n_passed, passed);
-      atomicMax(&stats->max_tries, tries);
-      atomicAdd((unsigned long long *)&stats->sum_tries, (unsigned long long)tries);
-      for (int t = 0; t < 4; ++t) atomicAdd((unsigned long long *)&stats->hist[t], (unsigned long long)hist[t]);
-    }
+  if (threadIdx.x == 0)
+    summaries[blockIdx.x] = vl_summary{first, first < J.K ? 1u : 0u, {hist[0], hist[1], hist[2], hist[3]}};
+}
+
+// one workgroup: the totals over the jobs' summaries (every field is written, nothing needs
+// clearing beforehand)
+__global__ __launch_bounds__(256) void k_loop_stats(const DevJob *__restrict__ jobs, uint32_t n_jobs,
+                                                    const vl_summary *__restrict__ summaries, vl_loop_stats *stats) {
+  __shared__ unsigned long long acc[5];   // sum of tries, histogram
+  __shared__ uint32_t n_passed, max_tries;
+  if (threadIdx.x < 5) acc[threadIdx.x] = 0;
+  if (threadIdx.x == 0) { n_passed = 0; max_tries = 0; }
+  __syncthreads();
+  unsigned long long mine[5] = {0, 0, 0, 0, 0};
+  uint32_t my_passed = 0, my_max = 0;
+  for (uint32_t j = threadIdx.x; j < n_jobs; j += blockDim.x) {
+    const vl_summary s = summaries[j];
+    const uint32_t tries = s.passed ? s.first_ok + 1 : jobs[j].K;
+    my_passed += s.passed;
+    my_max = max(my_max, tries);
+    mine[0] += tries;
+    for (int t = 0; t < 4; ++t) mine[1 + t] += s.hist[t];
   }
+  for (int t = 0; t < 5; ++t)
+    if (mine[t]) atomicAdd(&acc[t], mine[t]);
+  if (my_passed) atomicAdd(&n_passed, my_passed);
+  if (my_max) atomicMax(&max_tries, my_max);
+  __syncthreads();
+  if (threadIdx.x == 0) *stats = vl_loop_stats{n_passed, max_tries, acc[0], {acc[1], acc[2], acc[3], acc[4]}};
 }
 }  // namespace
 
@@ -765,9 +778,8 @@ extern "C" int32_t vl_summarize_multi(const vl_job *jobs, uint32_t n_jobs, vl_su
   Launch L;
   const int32_t rc = prepare_jobs(jobs, n_jobs, stream, s, L);
   if (rc != VL_OK) return rc;
-  // the totals are cleared by a kernel, not a memset, so that the call can be captured
-  if (stats) k_stats_clear<<<1, 64, 0, stream>>>(stats);
-  k_summarize<<<n_jobs, 256, 0, stream>>>(L.dev, summaries, stats);
+  k_summarize<<<n_jobs, 256, 0, stream>>>(L.dev, summaries);
+  if (stats) k_loop_stats<<<1, 256, 0, stream>>>(L.dev, n_jobs, summaries, stats);
   VL_HIP(hipGetLastError());
   return VL_OK;
 }

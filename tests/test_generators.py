@@ -83,3 +83,23 @@ def test_generator_is_deterministic():
     assert gen.sweep_sizes(4) == gen.sweep_sizes(4)
     s = gen.sweep_sizes(256)
     assert min(s) >= 1000 and max(s) <= 20000
+
+
+def test_mixed_shape_programs_meet_the_input_contract():
+    """The mixed-shape generator writes every value before it is read on every path
+    (nothing live into the entry) and covers the shapes it is there for."""
+    from vlgen.mixed import mixed_mir
+    for seed in range(6):
+        m = mixed_mir(0xA000 + seed, n_instr=700, reserved=seed % 2 == 1)
+        an = vlo.analyze(m, interference=False)
+        assert an.contract == 0, seed
+        assert not an.live_in[0].any()
+        assert m.vreg_width.max() == 32 and (m.vreg_align == 3).any() and len(m.class_size) == 3
+        assert np.diff(m.instr_occ_off).max() >= 30
+    m = mixed_mir(0xC001, n_instr=700, stretch=23000)
+    last, worst = {}, 0
+    for o, v in enumerate(m.occ_vreg):
+        if v in last:
+            worst = max(worst, o - last[v])
+        last[v] = o
+    assert worst > 65535
