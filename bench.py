@@ -137,6 +137,7 @@ def main():
     t0 = time.perf_counter()
     for i in range(args.steps):
         step(events[i])
+    dt_enqueue = time.perf_counter() - t0   # host time to enqueue the steps (they run asynchronously)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
@@ -189,7 +190,7 @@ def main():
                    "kernels": len(w.kernels), "candidates": w.n_candidates,
                    "instr_x_candidate_checks": w.n_checks, "tile_len": args.tile or 1024},
         "checks_per_s": w.n_checks * args.steps / dt,
-        "liveness_ms": live_ms, "verify_ms": verify_ms,
+        "liveness_ms": live_ms, "verify_ms": verify_ms, "host_enqueue_ms_per_step": dt_enqueue / args.steps * 1e3,
         "status_histogram": np.bincount(status, minlength=4).tolist(),
         "regeneration_loop": {"kernels_passed": int(loop["n_passed"]), "avg_tries": float(loop["sum_tries"]) / len(mirs),
                               "max_tries": int(loop["max_tries"]), "summarize_us": summarize_us},

@@ -94,7 +94,9 @@ void vl_mir_destroy(vl_mir *mir);
  *
  * live[0..n): on entry either all NULL, or the n handles a previous call with
  * these same kernels returned, whose device storage is then reused (no
- * allocation when it is large enough).  On success live[i] describes mirs[i].
+ * allocation when it is large enough).  When that call also had the same flags
+ * and tile_len, the result sizes are known from it: nothing is read back and
+ * the call does not synchronise at all.  On success live[i] describes mirs[i].
  * On error no handle is created; recycled handles stay allocated but their
  * contents are undefined until the next successful call.
  * tile_len: instructions per verification tile, 0 = library default.
