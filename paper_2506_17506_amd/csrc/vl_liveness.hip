@@ -67,9 +67,7 @@ enum { kScanVreg = 0, kScanItems = 1, kScanSeg = 2, kScanSeed = 3 };   // kScanS
 // (The array is chosen at compile time: a run-time switch over the four arrays was
 // seen to pick the wrong pointer in its default branch.)
 template <int kWhich>
-__global__ __launch_bounds__(1024) void k_scan(MIRS) {
-  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.x]);
-  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.x]);
+__device__ inline void f_scan(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L) {
   uint32_t VL_GLOBAL *p = kWhich == kScanVreg ? L.vcnt : kWhich == kScanItems ? L.item_off : kWhich == kScanSeg ? L.ent_seg : L.seed_off;
   const uint32_t n = kWhich == kScanVreg ? m.V : kWhich == kScanItems ? m.N + m.B : kWhich == kScanSeg ? m.O : L.T;
   // Each of the 16 wavefronts owns a contiguous sixteenth of the array and walks it 64
@@ -101,6 +99,11 @@ __global__ __launch_bounds__(1024) void k_scan(MIRS) {
     base += (uint32_t)__shfl((int)incl, 63, 64);
   }
   if (threadIdx.x == 0) p[n] = total;
+}
+
+template <int kWhich>
+__global__ __launch_bounds__(1024) void k_scan(MIRS) {
+  f_scan<kWhich>(*as_global(mirs[blockIdx.x]), *as_global_rw(&lives[blockIdx.x]));
 }
 
 // Places each occurrence into its vreg's range (order inside a range is fixed later).
@@ -436,10 +439,9 @@ __device__ inline u32x4 event_record(const DevMir VL_GLOBAL &m, uint32_t o, uint
 // earlier block's live-out to the later block's live-in: one wave per boundary lists the
 // values that leave (release) and those that enter (occupy without test).
 template <bool kFill>
-__global__ __launch_bounds__(64) void k_boundary(MIRS) {
-  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
-  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
-  const uint32_t b = blockIdx.x, lane = threadIdx.x;
+__device__ inline void f_boundary(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L, const uint32_t bx, const uint32_t tx,
+                                  const uint32_t bdim) {
+  const uint32_t b = bx, lane = tx;
   if (b >= m.B) return;
   const uint32_t item = m.blk_start[b] + b;
   if (b == 0) {
@@ -477,10 +479,9 @@ __global__ __launch_bounds__(64) void k_boundary(MIRS) {
 // Occupancy events of each instruction, in the order they take effect: releases of
 // operands that die here, then test-and-occupy of the values written, then releases of
 // values that are dead once the instruction has executed.
-__global__ void k_plan_fill(MIRS) {
-  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
-  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
-  uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+__device__ inline void f_plan_fill(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L, const uint32_t bx, const uint32_t tx,
+                                   const uint32_t bdim) {
+  uint32_t i = bx * bdim + tx;
   if (i >= m.N) return;
   uint32_t pos = L.item_off[item_of_instr(m, i)];
   const uint32_t o0 = m.occ_off[i], o1 = m.occ_off[i + 1];
@@ -501,10 +502,9 @@ __global__ void k_plan_fill(MIRS) {
 
 // evt_cut[c] = index of the first event of the first item whose operands end in chunk c or
 // later (an item's events may be replayed once occurrences [0, 64 (c + 1)) are staged).
-__global__ void k_evt_cut(MIRS) {
-  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
-  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
-  const uint32_t c = blockIdx.x * blockDim.x + threadIdx.x;
+__device__ inline void f_evt_cut(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L, const uint32_t bx, const uint32_t tx,
+                                 const uint32_t bdim) {
+  const uint32_t c = bx * bdim + tx;
   const uint32_t n_chunk = (m.O + 63) / 64;
   if (c > n_chunk) return;
   // first instruction i with occ_off[i + 1] > 64 c
@@ -530,10 +530,9 @@ __global__ void k_evt_cut(MIRS) {
 // the stretch is known locally.  Groups are sorted by (vreg, instruction), so a prefix sum
 // of the start counts numbers the runs in CSR order; the j-th end belongs to the j-th start.
 template <bool kFill>
-__global__ void k_seg(MIRS) {
-  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
-  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
-  const uint32_t e = blockIdx.x * blockDim.x + threadIdx.x;
+__device__ inline void f_seg(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L, const uint32_t bx, const uint32_t tx,
+                             const uint32_t bdim) {
+  const uint32_t e = bx * bdim + tx;
   if (e >= m.O) return;
   const uint8_t info = L.ent_info[e];
   if (!(info & kEntGroupStart)) { if (!kFill) L.ent_seg[e] = 0; return; }
@@ -580,10 +579,9 @@ __global__ void k_seg(MIRS) {
 }
 
 // seg_off per vreg from the per-entry prefix sums; hulls of never-occupied vregs to [0,0)
-__global__ void k_seg_off(MIRS) {
-  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
-  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
-  const uint32_t v = blockIdx.x * blockDim.x + threadIdx.x;
+__device__ inline void f_seg_off(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L, const uint32_t bx, const uint32_t tx,
+                                 const uint32_t bdim) {
+  const uint32_t v = bx * bdim + tx;
   if (v > m.V) return;
   L.seg_off[v] = L.ent_seg[v < m.V ? L.vcnt[v] : m.O];
   if (v < m.V && L.hull[2 * v + 1] == 0) L.hull[2 * v] = 0;
@@ -598,16 +596,15 @@ __global__ void k_seg_off(MIRS) {
 // of its instructions (an occurrence with an odd number of roles flips its vreg) and of
 // the block boundaries right after its instructions (live-out of the earlier block XOR
 // live-in of the later one).
-__global__ __launch_bounds__(256) void k_tile_delta(MIRS) {
-  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
-  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
+__device__ inline void f_tile_delta(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L, const uint32_t bx, const uint32_t tx,
+                                    const uint32_t bdim) {
   extern __shared__ uint32_t row[];
-  const uint32_t t = blockIdx.x;
+  const uint32_t t = bx;
   if (t >= L.T) return;
   const uint32_t W = m.W, i0 = t * L.tile_len, i1 = min(m.N, i0 + L.tile_len);
-  for (uint32_t w = threadIdx.x; w < W; w += 256) row[w] = 0;
+  for (uint32_t w = tx; w < W; w += 256) row[w] = 0;
   __syncthreads();
-  for (uint32_t o = m.occ_off[i0] + threadIdx.x; o < m.occ_off[i1]; o += 256) {
+  for (uint32_t o = m.occ_off[i0] + tx; o < m.occ_off[i1]; o += 256) {
     if (__popc(L.occ_role[o] & (kRolePreKill | kRoleTestSet | kRolePostKill)) & 1) {
       const uint32_t v = m.occ_vreg[o];
       atomicXor(&row[v >> 5], 1u << (v & 31));
@@ -617,18 +614,17 @@ __global__ __launch_bounds__(256) void k_tile_delta(MIRS) {
   const uint32_t b_lo = m.instr_blk[i0] + 1, b_hi = m.instr_blk[i1 - 1] + 1;   // blocks starting in (i0, i1]
   for (uint32_t b = b_lo; b <= b_hi && b < m.B; ++b) {
     if (m.blk_start[b] - 1 < i0 || m.blk_start[b] - 1 >= i1) continue;
-    for (uint32_t w = threadIdx.x; w < W; w += 256)
+    for (uint32_t w = tx; w < W; w += 256)
       atomicXor(&row[w], L.live_out[(size_t)(b - 1) * W + w] ^ L.live_in[(size_t)b * W + w]);
   }
   __syncthreads();
-  for (uint32_t w = threadIdx.x; w < W; w += 256) L.tile_live[(size_t)t * W + w] = row[w];
+  for (uint32_t w = tx; w < W; w += 256) L.tile_live[(size_t)t * W + w] = row[w];
 }
 
 // exclusive prefix-XOR over the tiles, one bitset word per lane
-__global__ void k_tile_prefix(MIRS) {
-  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
-  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
-  const uint32_t w = blockIdx.x * blockDim.x + threadIdx.x;
+__device__ inline void f_tile_prefix(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L, const uint32_t bx, const uint32_t tx,
+                                     const uint32_t bdim) {
+  const uint32_t w = bx * bdim + tx;
   if (w >= m.W) return;
   uint32_t acc = 0;
   for (uint32_t t = 0; t < L.T; ++t) {
@@ -641,10 +637,9 @@ __global__ void k_tile_prefix(MIRS) {
 // One wavefront per tile lists the members of its seed row as occupy-without-test entries
 // whose register is taken from the nearest earlier occurrence of the vreg.
 template <bool kFill>
-__global__ __launch_bounds__(64) void k_seed(MIRS) {
-  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
-  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
-  const uint32_t t = blockIdx.x, lane = threadIdx.x;
+__device__ inline void f_seed(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L, const uint32_t bx, const uint32_t tx,
+                              const uint32_t bdim) {
+  const uint32_t t = bx, lane = tx;
   if (t >= L.T) return;
   const uint32_t W = m.W;
   uint32_t total = 0;
@@ -668,10 +663,9 @@ __global__ __launch_bounds__(64) void k_seed(MIRS) {
 }
 
 // completes each seed entry: the register comes from the nearest earlier occurrence
-__global__ void k_seed_src(MIRS) {
-  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
-  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
-  const uint32_t k = blockIdx.x * blockDim.x + threadIdx.x;
+__device__ inline void f_seed_src(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L, const uint32_t bx, const uint32_t tx,
+                                  const uint32_t bdim) {
+  const uint32_t k = bx * bdim + tx;
   if (k >= L.n_seed) return;
   const u32x4 raw = L.seeds[k];
   const uint32_t v = raw.x, t = raw.y;
@@ -691,10 +685,9 @@ __global__ void k_collect(MIRS, uint32_t n) {
   L.counters[kCtrSeed] = L.seed_off[L.T];
 }
 
-__global__ void k_tile_range(MIRS) {
-  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
-  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
-  uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
+__device__ inline void f_tile_range(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L, const uint32_t bx, const uint32_t tx,
+                                    const uint32_t bdim) {
+  uint32_t t = bx * bdim + tx;
   if (t >= L.T) return;
   const uint32_t i0 = t * L.tile_len, i1 = min(m.N, i0 + L.tile_len);
   L.tile_range[2 * t] = L.item_off[item_of_instr(m, i0)];
@@ -707,6 +700,60 @@ __global__ void k_tile_range(MIRS) {
     end = m.blk_start[b] == i1 ? L.item_off[i1 + b] : L.item_off[i1 + b + 1];
   }
   L.tile_range[2 * t + 1] = end;
+}
+
+// ---- stages ---------------------------------------------------------------------------
+// After the per-occurrence pass three chains are independent: the event stream (boundary
+// counts, scan, chunk cuts, fill), the intervals (count, scan, offsets, fill) and the tile
+// live-ins (flips, prefix, count, scan, fill, sources).  Each stage below runs one step of
+// every chain in one launch, the block index selecting the part, so that the short serial
+// steps of one chain (scans, prefixes) overlap the bandwidth-heavy steps of another.  A
+// part made of one wavefront per item gets four items per 256-thread block.
+struct StageGrid { uint32_t a, b, c; };   // blocks of the three parts, in launch order
+
+__global__ __launch_bounds__(256) void k_stage_count(MIRS, StageGrid g) {
+  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
+  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
+  const uint32_t bx = blockIdx.x, tx = threadIdx.x;
+  if (bx < g.a) f_tile_delta(m, L, bx, tx, 256);
+  else if (bx < g.a + g.b) f_boundary<false>(m, L, (bx - g.a) * 4 + (tx >> 6), tx & 63u, 64);
+  else f_seg<false>(m, L, bx - g.a - g.b, tx, 256);
+}
+
+__global__ __launch_bounds__(1024) void k_stage_scan(MIRS, StageGrid g) {
+  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
+  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
+  const uint32_t bx = blockIdx.x;
+  if (bx == 0) f_scan<kScanSeg>(m, L);
+  else if (bx == 1) f_scan<kScanItems>(m, L);
+  else f_tile_prefix(m, L, bx - 2, threadIdx.x, 1024);
+}
+
+__global__ __launch_bounds__(256) void k_stage_offsets(MIRS, StageGrid g) {
+  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
+  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
+  const uint32_t bx = blockIdx.x, tx = threadIdx.x;
+  if (bx < g.a) f_seed<false>(m, L, bx * 4 + (tx >> 6), tx & 63u, 64);
+  else if (bx < g.a + g.b) f_evt_cut(m, L, bx - g.a, tx, 256);
+  else f_seg_off(m, L, bx - g.a - g.b, tx, 256);
+}
+
+__global__ __launch_bounds__(256) void k_stage_fill(MIRS, StageGrid g) {
+  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
+  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
+  const uint32_t bx = blockIdx.x, tx = threadIdx.x;
+  if (bx < g.a) f_seed<true>(m, L, bx * 4 + (tx >> 6), tx & 63u, 64);
+  else if (bx < g.a + g.b) f_plan_fill(m, L, bx - g.a, tx, 256);
+  else f_seg<true>(m, L, bx - g.a - g.b, tx, 256);
+}
+
+__global__ __launch_bounds__(256) void k_stage_finish(MIRS, StageGrid g) {
+  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
+  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
+  const uint32_t bx = blockIdx.x, tx = threadIdx.x;
+  if (bx < g.a) f_boundary<true>(m, L, bx * 4 + (tx >> 6), tx & 63u, 64);
+  else if (bx < g.a + g.b) f_tile_range(m, L, bx - g.a, tx, 256);
+  else f_seed_src(m, L, bx - g.a - g.b, tx, 256);
 }
 
 // ---- 5d. dense per-point bitsets (optional) ---------------------------------------------
@@ -992,15 +1039,13 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     else k_fixpoint<false><<<grid1(maxW, 64, n), 64, 0, stream>>>(dm, dl);
   }
   k_events<<<grid1(maxO, TB, n), TB, 0, stream>>>(dm, dl);
-  k_boundary<false><<<dim3(maxB, n), 64, 0, stream>>>(dm, dl);
-  k_scan<kScanItems><<<n, 1024, 0, stream>>>(dm, dl);
-  k_evt_cut<<<grid1(maxO / 64 + 2, TB, n), TB, 0, stream>>>(dm, dl);
-  k_seg<false><<<grid1(maxO, TB, n), TB, 0, stream>>>(dm, dl);
-  k_scan<kScanSeg><<<n, 1024, 0, stream>>>(dm, dl);
-  k_seg_off<<<grid1(maxV + 1, TB, n), TB, 0, stream>>>(dm, dl);
-  k_tile_delta<<<dim3(maxT, n), 256, (size_t)maxW * 4, stream>>>(dm, dl);
-  k_tile_prefix<<<grid1(maxW, 64, n), 64, 0, stream>>>(dm, dl);
-  k_seed<false><<<dim3(maxT, n), 64, 0, stream>>>(dm, dl);
+  auto blocks = [](uint32_t items, uint32_t per) { return std::max(1u, (items + per - 1) / per); };
+  const StageGrid g_count = {maxT, blocks(maxB, 4), blocks(maxO, TB)};
+  const StageGrid g_scan = {1, 1, blocks(maxW, 1024)};
+  const StageGrid g_off = {blocks(maxT, 4), blocks(maxO / 64 + 2, TB), blocks(maxV + 1, TB)};
+  k_stage_count<<<dim3(g_count.a + g_count.b + g_count.c, n), 256, (size_t)maxW * 4, stream>>>(dm, dl, g_count);
+  k_stage_scan<<<dim3(g_scan.a + g_scan.b + g_scan.c, n), 1024, 0, stream>>>(dm, dl, g_scan);
+  k_stage_offsets<<<dim3(g_off.a + g_off.b + g_off.c, n), 256, 0, stream>>>(dm, dl, g_off);
   k_scan<kScanSeed><<<n, 1024, 0, stream>>>(dm, dl);
   e = hipGetLastError();
   if (e != hipSuccess) return fail(hip_fail(e));
@@ -1026,12 +1071,10 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     e = hipMemsetAsync((char *)batch->arena2 + zero2_lo, 0, zero2_hi - zero2_lo, stream);
     if (e != hipSuccess) return fail(hip_fail(e));
   }
-  k_plan_fill<<<grid1(maxN, TB, n), TB, 0, stream>>>(dm, dl);
-  k_boundary<true><<<dim3(maxB, n), 64, 0, stream>>>(dm, dl);
-  k_tile_range<<<grid1(maxT, 64, n), 64, 0, stream>>>(dm, dl);
-  k_seg<true><<<grid1(maxO, TB, n), TB, 0, stream>>>(dm, dl);
-  k_seed<true><<<dim3(maxT, n), 64, 0, stream>>>(dm, dl);
-  if (max_seed) k_seed_src<<<grid1(max_seed, TB, n), TB, 0, stream>>>(dm, dl);
+  const StageGrid g_fill = {blocks(maxT, 4), blocks(maxN, TB), blocks(maxO, TB)};
+  const StageGrid g_fin = {blocks(maxB, 4), blocks(maxT, TB), blocks(max_seed, TB)};
+  k_stage_fill<<<dim3(g_fill.a + g_fill.b + g_fill.c, n), 256, 0, stream>>>(dm, dl, g_fill);
+  k_stage_finish<<<dim3(g_fin.a + g_fin.b + g_fin.c, n), 256, 0, stream>>>(dm, dl, g_fin);
   if (dense) {
     k_dense_delta<<<grid1(maxN + maxB, TB, n), TB, 0, stream>>>(dm, dl);
     k_dense_scan<<<dim3((maxW + 63) / 64, maxT, n), 64, 0, stream>>>(dm, dl);
