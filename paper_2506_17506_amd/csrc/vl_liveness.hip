@@ -70,15 +70,28 @@ template <int kWhich>
 __device__ inline void f_scan(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L) {
   uint32_t VL_GLOBAL *p = kWhich == kScanVreg ? L.vcnt : kWhich == kScanItems ? L.item_off : kWhich == kScanSeg ? L.ent_seg : L.seed_off;
   const uint32_t n = kWhich == kScanVreg ? m.V : kWhich == kScanItems ? m.N + m.B : kWhich == kScanSeg ? m.O : L.T;
-  // Each of the 16 wavefronts owns a contiguous sixteenth of the array and walks it 64
-  // elements at a time (coalesced): first to total its part, then, once the parts'
-  // totals are prefixed, to write the exclusive sums.
+  // Each of the 16 wavefronts owns a contiguous sixteenth of the array and walks it 256
+  // elements at a time (four consecutive elements per lane, one 16-byte access): first to
+  // total its part, then, once the parts' totals are prefixed, to write the exclusive sums.
   __shared__ uint32_t part[16];
   const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-  const uint32_t per = ((n + 15u) / 16u + 63u) & ~63u;
+  const uint32_t per = ((n + 15u) / 16u + 255u) & ~255u;
   const uint32_t lo = min(n, wave * per), hi = min(n, lo + per);
+  auto load4 = [&](uint32_t i) {
+    u32x4 x = 0;
+    if (i + 4 <= hi) x = *reinterpret_cast<const u32x4 VL_GLOBAL *>(p + i);
+    else {
+      if (i < hi) x.x = p[i];
+      if (i + 1 < hi) x.y = p[i + 1];
+      if (i + 2 < hi) x.z = p[i + 2];
+    }
+    return x;
+  };
   uint32_t sum = 0;
-  for (uint32_t i = lo + lane; i < hi; i += 64) sum += p[i];
+  for (uint32_t i = lo + lane * 4; i < hi; i += 256) {
+    const u32x4 x = load4(i);
+    sum += x.x + x.y + x.z + x.w;
+  }
   for (int d = 32; d >= 1; d >>= 1) sum += (uint32_t)__shfl_xor((int)sum, d, 64);
   if (lane == 0) part[wave] = sum;
   __syncthreads();
@@ -87,15 +100,23 @@ __device__ inline void f_scan(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L) {
     if (k < wave) base += part[k];
     total += part[k];
   }
-  for (uint32_t i0 = lo; i0 < hi; i0 += 64) {
-    const uint32_t i = i0 + lane;
-    const uint32_t x = i < hi ? p[i] : 0u;
-    uint32_t incl = x;
+  for (uint32_t i0 = lo; i0 < hi; i0 += 256) {
+    const uint32_t i = i0 + lane * 4;
+    const u32x4 x = load4(i);
+    const uint32_t s4 = x.x + x.y + x.z + x.w;
+    uint32_t incl = s4;
     for (int d = 1; d < 64; d <<= 1) {
       const uint32_t y = (uint32_t)__shfl_up((int)incl, d, 64);
       if ((int)lane >= d) incl += y;
     }
-    if (i < hi) p[i] = base + incl - x;
+    const uint32_t e0 = base + incl - s4;
+    const u32x4 out = {e0, e0 + x.x, e0 + x.x + x.y, e0 + x.x + x.y + x.z};
+    if (i + 4 <= hi) *reinterpret_cast<u32x4 VL_GLOBAL *>(p + i) = out;
+    else {
+      if (i < hi) p[i] = out.x;
+      if (i + 1 < hi) p[i + 1] = out.y;
+      if (i + 2 < hi) p[i + 2] = out.z;
+    }
     base += (uint32_t)__shfl((int)incl, 63, 64);
   }
   if (threadIdx.x == 0) p[n] = total;
@@ -1031,7 +1052,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
   if (hist_lds) k_place<true><<<slices, 1024, (size_t)maxV * 8, stream>>>(dm, dl);
   else k_place<false><<<slices, 1024, 0, stream>>>(dm, dl);
   k_sort_short<<<grid1(maxV, TB, n), TB, 0, stream>>>(dm, dl);
-  k_sort_long<<<dim3(32, n), 256, 0, stream>>>(dm, dl);
+  k_sort_long<<<dim3(64, n), 256, 0, stream>>>(dm, dl);
   k_summary<<<grid1(maxO, TB, n), TB, 0, stream>>>(dm, dl);
   {
     const size_t lds = (size_t)maxB * 64 * 3 * 4;
