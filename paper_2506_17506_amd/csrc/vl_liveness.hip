@@ -178,6 +178,24 @@ __global__ void k_sort_short(MIRS) {
     L.long_queue[atomicAdd(&L.counters[kCtrLong], 1u)] = v;
     return;
   }
+  if (len <= 8) {
+    // the common case: all loads issued at once, ranks computed in registers (absent
+    // elements are larger than any occurrence index)
+    uint32_t a[8];
+#pragma unroll
+    for (uint32_t k = 0; k < 8; ++k) a[k] = k < len ? L.vocc_tmp[lo + k] : kNone;
+#pragma unroll
+    for (uint32_t j = 0; j < 8; ++j) {
+      uint32_t r = 0;
+#pragma unroll
+      for (uint32_t k = 0; k < 8; ++k) r += a[k] < a[j];
+      if (j < len) {
+        L.vocc[lo + r] = a[j];
+        if (r == 0) L.first[v] = a[j];
+      }
+    }
+    return;
+  }
   for (uint32_t j = 0; j < len; ++j) {
     uint32_t x = L.vocc_tmp[lo + j], r = 0;
     for (uint32_t k = 0; k < len; ++k) r += L.vocc_tmp[lo + k] < x;
