@@ -61,6 +61,8 @@ __global__ __launch_bounds__(1024) void k_count(MIRS) {
     if (sm[v]) atomicAdd(&L.vcnt[v], sm[v]);
 }
 
+constexpr uint32_t kShortList = 16;   // longer occurrence lists go to the bitmap sort
+
 enum { kScanVreg = 0, kScanItems = 1, kScanSeg = 2, kScanSeed = 3 };   // kScanSeg: per-entry run counts
 
 // In-place exclusive scan of p[0..n), total to p[n]; one 1024-thread block per kernel.
@@ -111,6 +113,12 @@ __device__ inline void f_scan(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L) {
     }
     const uint32_t e0 = base + incl - s4;
     const u32x4 out = {e0, e0 + x.x, e0 + x.x + x.y, e0 + x.x + x.y + x.z};
+    if (kWhich == kScanVreg) {   // the counts are list lengths: queue the lists the bitmap sort will take
+      if (x.x > kShortList) L.long_queue[atomicAdd(&L.counters[kCtrLong], 1u)] = i;
+      if (x.y > kShortList) L.long_queue[atomicAdd(&L.counters[kCtrLong], 1u)] = i + 1;
+      if (x.z > kShortList) L.long_queue[atomicAdd(&L.counters[kCtrLong], 1u)] = i + 2;
+      if (x.w > kShortList) L.long_queue[atomicAdd(&L.counters[kCtrLong], 1u)] = i + 3;
+    }
     if (i + 4 <= hi) *reinterpret_cast<u32x4 VL_GLOBAL *>(p + i) = out;
     else {
       if (i < hi) p[i] = out.x;
@@ -162,22 +170,16 @@ __global__ __launch_bounds__(1024) void k_place(MIRS) {
   }
 }
 
-constexpr uint32_t kShortList = 16;
-
-// Lists of up to kShortList occurrences are rank-sorted by one lane; longer ones are queued.
-__global__ void k_sort_short(MIRS) {
-  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
-  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
-  uint32_t v = blockIdx.x * blockDim.x + threadIdx.x;
+// Lists of up to kShortList occurrences are rank-sorted by one lane (the longer ones were
+// queued by the scan of the list lengths).
+__device__ inline void f_sort_short(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L, const uint32_t bx, const uint32_t tx) {
+  const uint32_t v = bx * 256 + tx;
   if (v >= m.V) return;
   const uint32_t lo = L.vcnt[v], len = L.vcnt[v + 1] - lo;
   L.hull[2 * v] = kNone;   // min / max targets of the interval kernel
   L.hull[2 * v + 1] = 0;
   if (len == 0) { L.first[v] = kNone; return; }
-  if (len > kShortList) {
-    L.long_queue[atomicAdd(&L.counters[kCtrLong], 1u)] = v;
-    return;
-  }
+  if (len > kShortList) return;
   if (len <= 8) {
     // the common case: all loads issued at once, ranks computed in registers (absent
     // elements are larger than any occurrence index)
@@ -204,19 +206,18 @@ __global__ void k_sort_short(MIRS) {
   }
 }
 
-constexpr uint32_t kBitmapWords = 8192;              // 32 KB of LDS
+constexpr uint32_t kBitmapWords = 2048;              // 8 KB of LDS
 constexpr uint32_t kBitmapSpan = kBitmapWords * 32;  // occurrences per window
+constexpr uint32_t kLongBlocks = 64;                 // workgroups per kernel that take long lists
 
-// Long lists: occurrence indices are distinct, so marking them in a bitmap and
-// reading the bitmap back in order sorts them.
-__global__ __launch_bounds__(256) void k_sort_long(MIRS) {
-  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
-  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
+// Long lists: occurrence indices are distinct, so marking them in a bitmap and reading
+// the bitmap back in order sorts them, one window of kBitmapSpan occurrences at a time.
+__device__ inline void f_sort_long(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L, const uint32_t bx, const uint32_t tid) {
   __shared__ uint32_t bm[kBitmapWords];
-  __shared__ uint32_t part[256];
-  const uint32_t tid = threadIdx.x;
+  __shared__ uint32_t wave_total[4];
   const uint32_t n_long = L.counters[kCtrLong];
-  for (uint32_t q = blockIdx.x; q < n_long; q += gridDim.x) {
+  const uint32_t lane = tid & 63u, wave = tid >> 6;
+  for (uint32_t q = bx; q < n_long; q += kLongBlocks) {
     const uint32_t v = L.long_queue[q];
     const uint32_t lo = L.vcnt[v], len = L.vcnt[v + 1] - lo;
     uint32_t written = 0;
@@ -233,15 +234,21 @@ __global__ __launch_bounds__(256) void k_sort_long(MIRS) {
       const uint32_t w0 = min(nw, tid * chunk), w1 = min(nw, w0 + chunk);
       uint32_t cnt = 0;
       for (uint32_t w = w0; w < w1; ++w) cnt += __popc(bm[w]);
-      part[tid] = cnt;
-      __syncthreads();
-      for (uint32_t d = 1; d < 256; d <<= 1) {
-        uint32_t t = tid >= d ? part[tid - d] : 0;
-        __syncthreads();
-        part[tid] += t;
-        __syncthreads();
+      // exclusive prefix of cnt over the 256 threads: within the wavefront by shuffles,
+      // across the four wavefronts through LDS
+      uint32_t incl = cnt;
+      for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t y = (uint32_t)__shfl_up((int)incl, d, 64);
+        if ((int)lane >= d) incl += y;
       }
-      uint32_t pos = lo + written + part[tid] - cnt;
+      if (lane == 63) wave_total[wave] = incl;
+      __syncthreads();
+      uint32_t before = 0, total = 0;
+      for (uint32_t k = 0; k < 4; ++k) {
+        if (k < wave) before += wave_total[k];
+        total += wave_total[k];
+      }
+      uint32_t pos = lo + written + before + incl - cnt;
       for (uint32_t w = w0; w < w1; ++w) {
         uint32_t bits = bm[w];
         while (bits) {
@@ -252,10 +259,18 @@ __global__ __launch_bounds__(256) void k_sort_long(MIRS) {
           L.vocc[pos++] = x;
         }
       }
-      written += part[255];
+      written += total;
       __syncthreads();
     }
   }
+}
+
+// both sorts in one launch: the first kLongBlocks workgroups of each kernel take the long lists
+__global__ __launch_bounds__(256) void k_sort(MIRS) {
+  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
+  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
+  if (blockIdx.x < kLongBlocks) f_sort_long(m, L, blockIdx.x, threadIdx.x);
+  else f_sort_short(m, L, blockIdx.x - kLongBlocks, threadIdx.x);
 }
 
 // ---- 2. block summaries ---------------------------------------------------------------
@@ -1069,8 +1084,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
   k_scan<kScanVreg><<<n, 1024, 0, stream>>>(dm, dl);
   if (hist_lds) k_place<true><<<slices, 1024, (size_t)maxV * 8, stream>>>(dm, dl);
   else k_place<false><<<slices, 1024, 0, stream>>>(dm, dl);
-  k_sort_short<<<grid1(maxV, TB, n), TB, 0, stream>>>(dm, dl);
-  k_sort_long<<<dim3(64, n), 256, 0, stream>>>(dm, dl);
+  k_sort<<<dim3(kLongBlocks + (maxV + 255) / 256, n), 256, 0, stream>>>(dm, dl);
   k_summary<<<grid1(maxO, TB, n), TB, 0, stream>>>(dm, dl);
   {
     const size_t lds = (size_t)maxB * 64 * 3 * 4;
