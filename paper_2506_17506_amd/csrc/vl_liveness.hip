@@ -876,6 +876,7 @@ struct vl_batch {
   bool sized = false, sized_dense = false;
   uint32_t sized_tile_len = 0;
   std::vector<uint32_t> sizes;   // [n][3]: events, interval segments, tile live-ins
+  std::vector<char> uploaded;    // the DevLive table as it stands on the device after the last successful call
 };
 
 static void batch_free(vl_batch *b) {
@@ -1062,10 +1063,16 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
 
   // pinned staging: stage_a / stage_mirs are read by the copies below; when the sizes are not
   // known yet the host waits further down and stage_b carries the second upload after that
-  memcpy(batch->stage_a, h.data(), (size_t)n * sizeof(DevLive));
   hipError_t e = hipMemsetAsync(a1, 0, zero_bytes, stream);
-  if (e == hipSuccess) e = hipMemcpyAsync(a1 + o_mirs, mir_ptrs, (size_t)n * sizeof(DevMir *), hipMemcpyHostToDevice, stream);
-  if (e == hipSuccess) e = hipMemcpyAsync(a1 + o_lives, batch->stage_a, (size_t)n * sizeof(DevLive), hipMemcpyHostToDevice, stream);
+  // with known sizes the tables on the device are usually the ones this call would upload
+  const bool tables_current = known && batch->uploaded.size() == (size_t)n * sizeof(DevLive) &&
+                              memcmp(batch->uploaded.data(), h.data(), batch->uploaded.size()) == 0;
+  if (!tables_current) {
+    batch->uploaded.clear();
+    memcpy(batch->stage_a, h.data(), (size_t)n * sizeof(DevLive));
+    if (e == hipSuccess) e = hipMemcpyAsync(a1 + o_mirs, mir_ptrs, (size_t)n * sizeof(DevMir *), hipMemcpyHostToDevice, stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(a1 + o_lives, batch->stage_a, (size_t)n * sizeof(DevLive), hipMemcpyHostToDevice, stream);
+  }
   if (e != hipSuccess) return fail(hip_fail(e));
 
   const DevMir *const *dm = batch->dev_mirs;
@@ -1156,6 +1163,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     l->dev = batch->dev_lives + k;
     live[k] = l;
   }
+  batch->uploaded.assign((const char *)h.data(), (const char *)h.data() + (size_t)n * sizeof(DevLive));
   batch->sized = true;
   batch->sized_tile_len = tile_len;
   batch->sized_dense = dense;
