@@ -128,6 +128,7 @@ struct DevLive {
   u32x4 VL_GLOBAL *chk;           // [O] check records
   uint32_t VL_GLOBAL *evt_cut;    // [ceil(O/64)+1] first event replayable once chunk c is staged
   uint32_t VL_GLOBAL *ent_seg;    // [O+1] runs starting in each mention group's stretch -> prefix sums
+  uint8_t VL_GLOBAL *ent_sf;      // [O] where membership changes in the stretch, for the interval filling pass
   uint32_t VL_GLOBAL *hull;       // [V][2]
   uint32_t VL_GLOBAL *seed_off;   // [T+1]
   uint32_t VL_GLOBAL *seed_cur;   // [T]

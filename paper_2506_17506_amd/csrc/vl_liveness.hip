@@ -588,8 +588,31 @@ __device__ inline void f_seg(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L, co
                              const uint32_t bdim) {
   const uint32_t e = bx * bdim + tx;
   if (e >= m.O) return;
+  // The counting pass leaves a one-byte summary per entry.  Nearly every stretch changes
+  // membership only at its own instruction i, at i + 1 or at the end of the program, and
+  // then the summary says everything the filling pass needs; the other stretches (those
+  // with changes at block boundaries) are worked out again.
+  constexpr uint8_t kStartI = 1, kStartI1 = 2, kEndI = 4, kEndI1 = 8, kEndN = 16, kAgain = 32, kOpenBefore = 64;
+  if (kFill) {
+    const uint8_t sf = L.ent_sf[e];
+    if (!(sf & (kStartI | kStartI1 | kEndI | kEndI1 | kEndN | kAgain))) return;
+    if (!(sf & kAgain)) {
+      const uint32_t i = L.ent_instr[e] >> 2;
+      const size_t n_start = L.ent_seg[e];
+      size_t n_end = n_start - ((sf & kOpenBefore) ? 1u : 0u);
+      if (sf & kStartI) L.seg[2 * n_start] = i;
+      if (sf & kStartI1) L.seg[2 * n_start] = i + 1;
+      if (sf & kEndI) L.seg[2 * n_end++ + 1] = i;
+      if (sf & kEndI1) L.seg[2 * n_end++ + 1] = i + 1;
+      if (sf & kEndN) L.seg[2 * n_end + 1] = m.N;
+      return;
+    }
+  }
   const uint8_t info = L.ent_info[e];
-  if (!(info & kEntGroupStart)) { if (!kFill) L.ent_seg[e] = 0; return; }
+  if (!(info & kEntGroupStart)) {
+    if (!kFill) { L.ent_seg[e] = 0; L.ent_sf[e] = 0; }
+    return;
+  }
   const uint32_t v = m.occ_vreg[L.vocc[e]];
   const uint32_t lo = L.vcnt[v], hi = L.vcnt[v + 1];
   const uint32_t i = L.ent_instr[e] >> 2, b = m.instr_blk[i];
@@ -599,6 +622,7 @@ __device__ inline void f_seg(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L, co
   else if (e > lo && (L.ent_instr[e - 1] >> 2) == i - 1) cur = (L.ent_info[e - 1] & (kEntHasDef | kEntLiveAfter)) != 0;
   else if (i > m.blk_start[b]) cur = (info & kEntHasUse) != 0;
   else cur = bit_get(L.live_out + (size_t)(b - 1) * m.W, v);
+  uint8_t sf = cur ? kOpenBefore : 0;
   // runs that started before this stretch and ended before it: the end index lags the
   // start index by one exactly while a run is open
   uint32_t n_start = kFill ? L.ent_seg[e] : 0;
@@ -606,8 +630,18 @@ __device__ inline void f_seg(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L, co
   uint32_t first_start = kNone, last_end = 0;
   auto span = [&](uint32_t s, uint32_t t, bool member) {
     if (t <= s) return;
-    if (member && !cur) { if (kFill) L.seg[2 * (size_t)n_start] = s; ++n_start; first_start = min(first_start, s); }
-    if (!member && cur) { if (kFill) L.seg[2 * (size_t)n_end + 1] = s; ++n_end; last_end = s; }
+    if (member && !cur) {
+      if (kFill) L.seg[2 * (size_t)n_start] = s;
+      ++n_start;
+      first_start = min(first_start, s);
+      sf |= s == i ? kStartI : s == i + 1 ? kStartI1 : kAgain;
+    }
+    if (!member && cur) {
+      if (kFill) L.seg[2 * (size_t)n_end + 1] = s;
+      ++n_end;
+      last_end = s;
+      sf |= s == i ? kEndI : s == i + 1 ? kEndI1 : kAgain;
+    }
     cur = member;
   };
   uint32_t ge = e + 1;
@@ -624,9 +658,17 @@ __device__ inline void f_seg(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L, co
       span(m.blk_start[x], m.blk_start[x + 1], bit_get(L.live_in + (size_t)x * m.W, v));
     if (ge < hi) span(m.blk_start[b2], i2, (L.ent_info[ge] & kEntHasUse) != 0);
   }
-  if (ge >= hi && cur) { if (kFill) L.seg[2 * (size_t)n_end + 1] = m.N; ++n_end; last_end = m.N; }
+  if (ge >= hi && cur) {
+    if (kFill) L.seg[2 * (size_t)n_end + 1] = m.N;
+    ++n_end;
+    last_end = m.N;
+    sf |= kEndN;
+  }
   if (!kFill) {
     L.ent_seg[e] = n_start;
+    // two starts in one stretch cannot be told apart by the summary
+    if (n_start > 1) sf |= kAgain;
+    L.ent_sf[e] = sf;
     if (first_start != kNone) atomicMin(&L.hull[2 * v], first_start);
     if (last_end) atomicMax(&L.hull[2 * v + 1], last_end);
   }
@@ -944,7 +986,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
   // ---- arena 1 layout: [zeroed zone | counters | rest | device tables] ----
   std::vector<DevLive> h(n);
   struct Off1 { size_t vcnt, vcur, use, def, in, seed_off, seed_cur, out, tmp, vocc, ent_instr, ent_info, first, prev,
-                role, kill, item, seg_off, hull, queue, bitmap, ent_seg, chk, evt_cut, tile_live; };
+                role, kill, item, seg_off, hull, queue, bitmap, ent_seg, ent_sf, chk, evt_cut, tile_live; };
   std::vector<Off1> off(n);
   Bump bump;
   uint32_t maxO = 1, maxV = 1, maxN = 1, maxB = 1, maxW = 1, maxT = 1;
@@ -974,6 +1016,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     off[k].seg_off = bump.take((size_t)(m.V + 1) * 4); off[k].hull = bump.take((size_t)(m.V + 1) * 8);
     off[k].queue = bump.take((size_t)(m.V + 1) * 4);
     off[k].ent_seg = bump.take((O1 + 1) * 4);
+    off[k].ent_sf = bump.take(O1);
     off[k].chk = bump.take(O1 * sizeof(u32x4));
     off[k].tile_live = bump.take((size_t)h[k].T * std::max(1u, m.W) * 4);
     off[k].evt_cut = bump.take(((size_t)(m.O + 63) / 64 + 2) * 4);
@@ -1002,6 +1045,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     L.item_off = (uint32_t VL_GLOBAL *)(a1 + off[k].item); L.seg_off = (uint32_t VL_GLOBAL *)(a1 + off[k].seg_off);
     L.hull = (uint32_t VL_GLOBAL *)(a1 + off[k].hull); L.long_queue = (uint32_t VL_GLOBAL *)(a1 + off[k].queue);
     L.ent_seg = (uint32_t VL_GLOBAL *)(a1 + off[k].ent_seg);
+    L.ent_sf = (uint8_t VL_GLOBAL *)(a1 + off[k].ent_sf);
     L.chk = (u32x4 VL_GLOBAL *)(a1 + off[k].chk); L.tile_live = (uint32_t VL_GLOBAL *)(a1 + off[k].tile_live); L.evt_cut = (uint32_t VL_GLOBAL *)(a1 + off[k].evt_cut);
     L.bitmap = (uint32_t VL_GLOBAL *)nullptr;
     L.counters = (uint32_t VL_GLOBAL *)(a1 + o_counters) + (size_t)k * kCounters;

@@ -581,19 +581,26 @@ __global__ __launch_bounds__(256) void k_resolve(const DevJob *__restrict__ jobs
   const uint32_t i = J.out[k].where;
   extern __shared__ uint32_t in_p[];   // [W]
   __shared__ unsigned long long best;
-  __shared__ uint32_t dv[kMaxOperands], dp[kMaxOperands], nd;
+  __shared__ uint32_t dv[kMaxOperands], dp[kMaxOperands], all_v[kMaxOperands], nd;
   for (uint32_t x = threadIdx.x; x < m.W; x += blockDim.x) in_p[x] = 0;
-  if (threadIdx.x == 0) {
-    best = ~0ull;
-    uint32_t n = 0;
-    for (uint32_t o = m.occ_off[i]; o < m.occ_off[i + 1]; ++o)
-      if (m.occ_flags[o] & VL_OCC_DEF) {
-        const uint32_t v = m.occ_vreg[o];
-        bool seen = false;
-        for (uint32_t t = 0; t < n; ++t) seen |= dv[t] == v;
-        if (!seen) { dv[n] = v; dp[n] = row[L.first[v]]; ++n; }
-      }
-    nd = n;
+  // the vregs the instruction writes (each once) and their registers: one operand per lane
+  const uint32_t o_lo = m.occ_off[i], n_ops = m.occ_off[i + 1] - o_lo;
+  uint32_t my_v = kNone, my_p = 0;
+  if (threadIdx.x < n_ops && (m.occ_flags[o_lo + threadIdx.x] & VL_OCC_DEF)) {
+    my_v = m.occ_vreg[o_lo + threadIdx.x];
+    my_p = row[L.first[my_v]];
+  }
+  if (threadIdx.x < kMaxOperands) all_v[threadIdx.x] = my_v;
+  if (threadIdx.x == 0) { best = ~0ull; nd = 0; }
+  __syncthreads();
+  if (my_v != kNone) {
+    bool seen = false;
+    for (uint32_t t = 0; t < threadIdx.x; ++t) seen |= all_v[t] == my_v;
+    if (!seen) {
+      const uint32_t slot = atomicAdd(&nd, 1u);
+      dv[slot] = my_v;
+      dp[slot] = my_p;
+    }
   }
   __syncthreads();
   const uint32_t tile = i / L.tile_len;
