@@ -176,8 +176,6 @@ __device__ inline void f_sort_short(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL
   const uint32_t v = bx * 256 + tx;
   if (v >= m.V) return;
   const uint32_t lo = L.vcnt[v], len = L.vcnt[v + 1] - lo;
-  L.hull[2 * v] = kNone;   // min / max targets of the interval kernel
-  L.hull[2 * v + 1] = 0;
   if (len == 0) { L.first[v] = kNone; return; }
   if (len > kShortList) return;
   if (len <= 8) {
@@ -389,6 +387,9 @@ __global__ __launch_bounds__(64) void k_fixpoint(MIRS) {
   if (lane == 0) atomicMax(&L.counters[kCtrSweeps], sweeps);
 }
 
+// one-byte summary of where membership in P(.) changes inside a mention group's stretch
+constexpr uint8_t kStartI = 1, kStartI1 = 2, kEndI = 4, kEndI1 = 8, kEndN = 16, kAgain = 32, kOpenBefore = 64;
+
 // ---- 4. per-occurrence liveness, kill flags and event roles ---------------------------
 // For the mentions of v at instruction i (its "group"): v is live after i iff the next
 // mention of v in the same block reads it, or, with no later mention in the block, v is
@@ -456,6 +457,53 @@ __global__ void k_events(MIRS) {
   if (n_evt) atomicAdd(&L.item_off[i + b + 1], n_evt);
   L.ent_info[e] = (uint8_t)((la ? kEntLiveAfter : 0) | (has_use ? kEntHasUse : 0) | (has_def ? kEntHasDef : 0) |
                             (e == gs ? kEntGroupStart : 0));
+
+  // ---- live intervals, counting pass (the filling pass and the reasoning are at f_seg) ----
+  // The first entry of each mention group owns the stretch from i up to the next mention of v
+  // and counts the run starts in it; what the neighbouring groups contribute is worked out
+  // from their flags here, since their own threads may not have run yet.
+  if (e != gs) { L.ent_seg[e] = 0; L.ent_sf[e] = 0; return; }
+  bool cur;   // was v occupied just before this stretch?
+  if (i == 0) cur = false;
+  else if (gs > lo && (L.ent_instr[gs - 1] >> 2) == i - 1) {
+    bool prev_def = false;
+    for (uint32_t x = gs; x-- > lo && (L.ent_instr[x] >> 2) == i - 1;) prev_def |= (L.ent_instr[x] & VL_OCC_DEF) != 0;
+    const uint32_t pb = m.instr_blk[i - 1];
+    // live after i - 1: this group is the next mention; in another block the block's live-out decides
+    const bool prev_la = pb == b ? has_use : bit_get(L.live_out + (size_t)pb * m.W, v);
+    cur = prev_def || prev_la;
+  } else if (i > m.blk_start[b]) cur = has_use;
+  else cur = bit_get(L.live_out + (size_t)(b - 1) * m.W, v);
+  uint8_t sf = cur ? kOpenBefore : 0;
+  uint32_t n_start = 0;
+  auto span = [&](uint32_t s, uint32_t t, bool member) {
+    if (t <= s) return;
+    if (member && !cur) {
+      ++n_start;
+      sf |= s == i ? kStartI : s == i + 1 ? kStartI1 : kAgain;
+    }
+    if (!member && cur) sf |= s == i ? kEndI : s == i + 1 ? kEndI1 : kAgain;
+    cur = member;
+  };
+  span(i, i + 1, has_def || la);
+  const uint32_t i2 = ge < hi ? L.ent_instr[ge] >> 2 : m.N;
+  const uint32_t b2 = ge < hi ? m.instr_blk[i2] : m.B;
+  if (b2 == b) {
+    span(i + 1, i2, la);
+  } else {
+    span(i + 1, m.blk_start[b + 1], la);
+    for (uint32_t x = b + 1; x < b2; ++x)
+      span(m.blk_start[x], m.blk_start[x + 1], bit_get(L.live_in + (size_t)x * m.W, v));
+    if (ge < hi) {
+      bool next_use = false;
+      for (uint32_t x = ge; x < hi && (L.ent_instr[x] >> 2) == i2; ++x) next_use |= (L.ent_instr[x] & VL_OCC_USE) != 0;
+      span(m.blk_start[b2], i2, next_use);
+    }
+  }
+  if (ge >= hi && cur) sf |= kEndN;
+  if (n_start > 1) sf |= kAgain;   // two starts in one stretch cannot be told apart by the summary
+  L.ent_seg[e] = n_start;
+  L.ent_sf[e] = sf;
 }
 
 // ---- 5a. event stream -----------------------------------------------------------------
@@ -583,65 +631,37 @@ __device__ inline void f_evt_cut(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L
 // end of the program) and finds the run starts and ends inside it; what holds just before
 // the stretch is known locally.  Groups are sorted by (vreg, instruction), so a prefix sum
 // of the start counts numbers the runs in CSR order; the j-th end belongs to the j-th start.
-template <bool kFill>
-__device__ inline void f_seg(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L, const uint32_t bx, const uint32_t tx,
-                             const uint32_t bdim) {
+__device__ inline void f_seg_fill(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L, const uint32_t bx, const uint32_t tx,
+                                  const uint32_t bdim) {
   const uint32_t e = bx * bdim + tx;
   if (e >= m.O) return;
-  // The counting pass leaves a one-byte summary per entry.  Nearly every stretch changes
-  // membership only at its own instruction i, at i + 1 or at the end of the program, and
-  // then the summary says everything the filling pass needs; the other stretches (those
-  // with changes at block boundaries) are worked out again.
-  constexpr uint8_t kStartI = 1, kStartI1 = 2, kEndI = 4, kEndI1 = 8, kEndN = 16, kAgain = 32, kOpenBefore = 64;
-  if (kFill) {
-    const uint8_t sf = L.ent_sf[e];
-    if (!(sf & (kStartI | kStartI1 | kEndI | kEndI1 | kEndN | kAgain))) return;
-    if (!(sf & kAgain)) {
-      const uint32_t i = L.ent_instr[e] >> 2;
-      const size_t n_start = L.ent_seg[e];
-      size_t n_end = n_start - ((sf & kOpenBefore) ? 1u : 0u);
-      if (sf & kStartI) L.seg[2 * n_start] = i;
-      if (sf & kStartI1) L.seg[2 * n_start] = i + 1;
-      if (sf & kEndI) L.seg[2 * n_end++ + 1] = i;
-      if (sf & kEndI1) L.seg[2 * n_end++ + 1] = i + 1;
-      if (sf & kEndN) L.seg[2 * n_end + 1] = m.N;
-      return;
-    }
-  }
-  const uint8_t info = L.ent_info[e];
-  if (!(info & kEntGroupStart)) {
-    if (!kFill) { L.ent_seg[e] = 0; L.ent_sf[e] = 0; }
-    return;
-  }
-  const uint32_t v = m.occ_vreg[L.vocc[e]];
-  const uint32_t lo = L.vcnt[v], hi = L.vcnt[v + 1];
-  const uint32_t i = L.ent_instr[e] >> 2, b = m.instr_blk[i];
-  // was v occupied just before this stretch?
-  bool cur;
-  if (i == 0) cur = false;
-  else if (e > lo && (L.ent_instr[e - 1] >> 2) == i - 1) cur = (L.ent_info[e - 1] & (kEntHasDef | kEntLiveAfter)) != 0;
-  else if (i > m.blk_start[b]) cur = (info & kEntHasUse) != 0;
-  else cur = bit_get(L.live_out + (size_t)(b - 1) * m.W, v);
-  uint8_t sf = cur ? kOpenBefore : 0;
+  // The counting pass (in the per-occurrence kernel) left a one-byte summary per entry.
+  // Nearly every stretch changes membership only at its own instruction i, at i + 1 or at
+  // the end of the program, and then the summary says everything needed here; the other
+  // stretches (those with changes at block boundaries) are worked out again.
+  const uint8_t sf = L.ent_sf[e];
+  if (!(sf & (kStartI | kStartI1 | kEndI | kEndI1 | kEndN | kAgain))) return;
+  const uint32_t i = L.ent_instr[e] >> 2;
   // runs that started before this stretch and ended before it: the end index lags the
   // start index by one exactly while a run is open
-  uint32_t n_start = kFill ? L.ent_seg[e] : 0;
-  uint32_t n_end = kFill ? n_start - (cur ? 1u : 0u) : 0;
-  uint32_t first_start = kNone, last_end = 0;
+  size_t n_start = L.ent_seg[e];
+  size_t n_end = n_start - ((sf & kOpenBefore) ? 1u : 0u);
+  if (!(sf & kAgain)) {
+    if (sf & kStartI) L.seg[2 * n_start] = i;
+    if (sf & kStartI1) L.seg[2 * n_start] = i + 1;
+    if (sf & kEndI) L.seg[2 * n_end++ + 1] = i;
+    if (sf & kEndI1) L.seg[2 * n_end++ + 1] = i + 1;
+    if (sf & kEndN) L.seg[2 * n_end + 1] = m.N;
+    return;
+  }
+  const uint8_t info = L.ent_info[e];
+  const uint32_t v = m.occ_vreg[L.vocc[e]];
+  const uint32_t hi = L.vcnt[v + 1], b = m.instr_blk[i];
+  bool cur = (sf & kOpenBefore) != 0;
   auto span = [&](uint32_t s, uint32_t t, bool member) {
     if (t <= s) return;
-    if (member && !cur) {
-      if (kFill) L.seg[2 * (size_t)n_start] = s;
-      ++n_start;
-      first_start = min(first_start, s);
-      sf |= s == i ? kStartI : s == i + 1 ? kStartI1 : kAgain;
-    }
-    if (!member && cur) {
-      if (kFill) L.seg[2 * (size_t)n_end + 1] = s;
-      ++n_end;
-      last_end = s;
-      sf |= s == i ? kEndI : s == i + 1 ? kEndI1 : kAgain;
-    }
+    if (member && !cur) L.seg[2 * n_start++] = s;
+    if (!member && cur) L.seg[2 * n_end++ + 1] = s;
     cur = member;
   };
   uint32_t ge = e + 1;
@@ -658,29 +678,25 @@ __device__ inline void f_seg(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L, co
       span(m.blk_start[x], m.blk_start[x + 1], bit_get(L.live_in + (size_t)x * m.W, v));
     if (ge < hi) span(m.blk_start[b2], i2, (L.ent_info[ge] & kEntHasUse) != 0);
   }
-  if (ge >= hi && cur) {
-    if (kFill) L.seg[2 * (size_t)n_end + 1] = m.N;
-    ++n_end;
-    last_end = m.N;
-    sf |= kEndN;
-  }
-  if (!kFill) {
-    L.ent_seg[e] = n_start;
-    // two starts in one stretch cannot be told apart by the summary
-    if (n_start > 1) sf |= kAgain;
-    L.ent_sf[e] = sf;
-    if (first_start != kNone) atomicMin(&L.hull[2 * v], first_start);
-    if (last_end) atomicMax(&L.hull[2 * v + 1], last_end);
-  }
+  if (ge >= hi && cur) L.seg[2 * n_end + 1] = m.N;
 }
 
-// seg_off per vreg from the per-entry prefix sums; hulls of never-occupied vregs to [0,0)
+// seg_off per vreg from the per-entry prefix sums
 __device__ inline void f_seg_off(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L, const uint32_t bx, const uint32_t tx,
                                  const uint32_t bdim) {
   const uint32_t v = bx * bdim + tx;
   if (v > m.V) return;
   L.seg_off[v] = L.ent_seg[v < m.V ? L.vcnt[v] : m.O];
-  if (v < m.V && L.hull[2 * v + 1] == 0) L.hull[2 * v] = 0;
+}
+
+// hull of each vreg from its (ascending) runs: [first start, last end), or [0,0) without runs
+__device__ inline void f_hull(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L, const uint32_t bx, const uint32_t tx,
+                              const uint32_t bdim) {
+  const uint32_t v = bx * bdim + tx;
+  if (v >= m.V) return;
+  const uint32_t s0 = L.seg_off[v], s1 = L.seg_off[v + 1];
+  L.hull[2 * v] = s1 > s0 ? L.seg[2 * (size_t)s0] : 0u;
+  L.hull[2 * v + 1] = s1 > s0 ? L.seg[2 * (size_t)s1 - 1] : 0u;
 }
 
 // ---- 5c. tile live-ins ------------------------------------------------------------------
@@ -812,8 +828,7 @@ __global__ __launch_bounds__(256) void k_stage_count(MIRS, StageGrid g) {
   DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
   const uint32_t bx = blockIdx.x, tx = threadIdx.x;
   if (bx < g.a) f_tile_delta(m, L, bx, tx, 256);
-  else if (bx < g.a + g.b) f_boundary<false>(m, L, (bx - g.a) * 4 + (tx >> 6), tx & 63u, 64);
-  else f_seg<false>(m, L, bx - g.a - g.b, tx, 256);
+  else f_boundary<false>(m, L, (bx - g.a) * 4 + (tx >> 6), tx & 63u, 64);
 }
 
 __global__ __launch_bounds__(1024) void k_stage_scan(MIRS, StageGrid g) {
@@ -840,7 +855,7 @@ __global__ __launch_bounds__(256) void k_stage_fill(MIRS, StageGrid g) {
   const uint32_t bx = blockIdx.x, tx = threadIdx.x;
   if (bx < g.a) f_seed<true>(m, L, bx * 4 + (tx >> 6), tx & 63u, 64);
   else if (bx < g.a + g.b) f_plan_fill(m, L, bx - g.a, tx, 256);
-  else f_seg<true>(m, L, bx - g.a - g.b, tx, 256);
+  else f_seg_fill(m, L, bx - g.a - g.b, tx, 256);
 }
 
 __global__ __launch_bounds__(256) void k_stage_finish(MIRS, StageGrid g) {
@@ -849,7 +864,8 @@ __global__ __launch_bounds__(256) void k_stage_finish(MIRS, StageGrid g) {
   const uint32_t bx = blockIdx.x, tx = threadIdx.x;
   if (bx < g.a) f_boundary<true>(m, L, bx * 4 + (tx >> 6), tx & 63u, 64);
   else if (bx < g.a + g.b) f_tile_range(m, L, bx - g.a, tx, 256);
-  else f_seed_src(m, L, bx - g.a - g.b, tx, 256);
+  else if (bx < g.a + g.b + g.c) f_seed_src(m, L, bx - g.a - g.b, tx, 256);
+  else f_hull(m, L, bx - g.a - g.b - g.c, tx, 256);
 }
 
 // ---- 5d. dense per-point bitsets (optional) ---------------------------------------------
@@ -1144,7 +1160,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
   }
   k_events<<<grid1(maxO, TB, n), TB, 0, stream>>>(dm, dl);
   auto blocks = [](uint32_t items, uint32_t per) { return std::max(1u, (items + per - 1) / per); };
-  const StageGrid g_count = {maxT, blocks(maxB, 4), blocks(maxO, TB)};
+  const StageGrid g_count = {maxT, blocks(maxB, 4), 0};
   const StageGrid g_scan = {1, 1, blocks(maxW, 1024)};
   const StageGrid g_off = {blocks(maxT, 4), blocks(maxO / 64 + 2, TB), blocks(maxV + 1, TB)};
   k_stage_count<<<dim3(g_count.a + g_count.b + g_count.c, n), 256, (size_t)maxW * 4, stream>>>(dm, dl, g_count);
@@ -1178,7 +1194,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
   const StageGrid g_fill = {blocks(maxT, 4), blocks(maxN, TB), blocks(maxO, TB)};
   const StageGrid g_fin = {blocks(maxB, 4), blocks(maxT, TB), blocks(max_seed, TB)};
   k_stage_fill<<<dim3(g_fill.a + g_fill.b + g_fill.c, n), 256, 0, stream>>>(dm, dl, g_fill);
-  k_stage_finish<<<dim3(g_fin.a + g_fin.b + g_fin.c, n), 256, 0, stream>>>(dm, dl, g_fin);
+  k_stage_finish<<<dim3(g_fin.a + g_fin.b + g_fin.c + blocks(maxV, TB), n), 256, 0, stream>>>(dm, dl, g_fin);
   if (dense) {
     k_dense_delta<<<grid1(maxN + maxB, TB, n), TB, 0, stream>>>(dm, dl);
     k_dense_scan<<<dim3((maxW + 63) / 64, maxT, n), 64, 0, stream>>>(dm, dl);
