@@ -109,6 +109,7 @@ struct DevLive {
   // --- sized from the program alone ---
   uint32_t VL_GLOBAL *vcnt;       // [V+1] occurrences per vreg -> exclusive offsets (vocc_off)
   uint32_t VL_GLOBAL *vcur;       // [V] placement cursors
+  uint32_t VL_GLOBAL *last_live;  // [V] last block the vreg is live into (0: none after the entry)
   uint32_t VL_GLOBAL *vocc_tmp;   // [O] occurrences grouped by vreg, unordered
   uint32_t VL_GLOBAL *vocc;       // [O] occurrences grouped by vreg, ascending
   uint32_t VL_GLOBAL *ent_instr;  // [O] instruction << 2 | occurrence flags of each sorted entry (ascending per vreg)

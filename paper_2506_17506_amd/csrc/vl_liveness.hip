@@ -382,6 +382,19 @@ __global__ __launch_bounds__(64) void k_fixpoint(MIRS) {
       if (kLds) L.live_in[(size_t)b * W + w] = in_l[b * 64 + lane];
     }
   }
+  // last block each vreg is live into (0 when there is none after the entry): lets the interval
+  // kernels stop looking at later blocks.  Blocks in descending order; a lane owns its 32 vregs.
+  uint32_t seen = 0;
+  for (uint32_t b = B; b-- > 1;) {
+    const uint32_t in_b = kLds ? in_l[b * 64 + lane] : (act ? L.live_in[(size_t)b * W + w] : 0);
+    uint32_t fresh = in_b & ~seen;
+    seen |= in_b;
+    while (act && fresh) {
+      const uint32_t v = w * 32 + __ffs(fresh) - 1;
+      fresh &= fresh - 1;
+      if (v < m.V) L.last_live[v] = b;
+    }
+  }
   uint32_t in0 = kLds ? in_l[lane] : (act ? L.live_in[w] : 0);
   if (act && in0) L.counters[kCtrNotStrict] = 1;
   if (lane == 0) atomicMax(&L.counters[kCtrSweeps], sweeps);
@@ -492,8 +505,11 @@ __global__ void k_events(MIRS) {
     span(i + 1, i2, la);
   } else {
     span(i + 1, m.blk_start[b + 1], la);
-    for (uint32_t x = b + 1; x < b2; ++x)
+    // blocks in between: v is live into none of them after its last live block
+    const uint32_t xe = min(b2, max(b + 1, L.last_live[v] + 1));
+    for (uint32_t x = b + 1; x < xe; ++x)
       span(m.blk_start[x], m.blk_start[x + 1], bit_get(L.live_in + (size_t)x * m.W, v));
+    if (xe < b2) span(m.blk_start[xe], m.blk_start[xe + 1], false);
     if (ge < hi) {
       bool next_use = false;
       for (uint32_t x = ge; x < hi && (L.ent_instr[x] >> 2) == i2; ++x) next_use |= (L.ent_instr[x] & VL_OCC_USE) != 0;
@@ -674,8 +690,10 @@ __device__ inline void f_seg_fill(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &
     span(i + 1, i2, la);
   } else {
     span(i + 1, m.blk_start[b + 1], la);
-    for (uint32_t x = b + 1; x < b2; ++x)
+    const uint32_t xe = min(b2, max(b + 1, L.last_live[v] + 1));
+    for (uint32_t x = b + 1; x < xe; ++x)
       span(m.blk_start[x], m.blk_start[x + 1], bit_get(L.live_in + (size_t)x * m.W, v));
+    if (xe < b2) span(m.blk_start[xe], m.blk_start[xe + 1], false);
     if (ge < hi) span(m.blk_start[b2], i2, (L.ent_info[ge] & kEntHasUse) != 0);
   }
   if (ge >= hi && cur) L.seg[2 * n_end + 1] = m.N;
@@ -1001,7 +1019,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
 
   // ---- arena 1 layout: [zeroed zone | counters | rest | device tables] ----
   std::vector<DevLive> h(n);
-  struct Off1 { size_t vcnt, vcur, use, def, in, seed_off, seed_cur, out, tmp, vocc, ent_instr, ent_info, first, prev,
+  struct Off1 { size_t last_live, vcnt, vcur, use, def, in, seed_off, seed_cur, out, tmp, vocc, ent_instr, ent_info, first, prev,
                 role, kill, item, seg_off, hull, queue, bitmap, ent_seg, ent_sf, chk, evt_cut, tile_live; };
   std::vector<Off1> off(n);
   Bump bump;
@@ -1014,6 +1032,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     const size_t bw = (size_t)m.B * std::max(1u, m.W) * 4;
     off[k].vcnt = bump.take((size_t)(m.V + 1) * 4);
     off[k].vcur = bump.take((size_t)(m.V + 1) * 4);
+    off[k].last_live = bump.take((size_t)(m.V + 1) * 4);
     off[k].use = bump.take(bw); off[k].def = bump.take(bw); off[k].in = bump.take(bw);
     off[k].seed_off = bump.take((size_t)(T + 1) * 4); off[k].seed_cur = bump.take((size_t)(T + 1) * 4);
     off[k].item = bump.take((size_t)(m.N + m.B + 1) * 4);   // event counts are accumulated with atomics
@@ -1051,6 +1070,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
   for (uint32_t k = 0; k < n; ++k) {
     DevLive &L = h[k];
     L.vcnt = (uint32_t VL_GLOBAL *)(a1 + off[k].vcnt); L.vcur = (uint32_t VL_GLOBAL *)(a1 + off[k].vcur);
+    L.last_live = (uint32_t VL_GLOBAL *)(a1 + off[k].last_live);
     L.use = (uint32_t VL_GLOBAL *)(a1 + off[k].use); L.def = (uint32_t VL_GLOBAL *)(a1 + off[k].def);
     L.live_in = (uint32_t VL_GLOBAL *)(a1 + off[k].in); L.live_out = (uint32_t VL_GLOBAL *)(a1 + off[k].out);
     L.seed_off = (uint32_t VL_GLOBAL *)(a1 + off[k].seed_off); L.seed_cur = (uint32_t VL_GLOBAL *)(a1 + off[k].seed_cur);
