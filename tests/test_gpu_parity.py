@@ -180,12 +180,22 @@ def test_config4_and_5_kernels_full_size():
         assert_liveness_equal(m, an, got[k], m.name)
         want = vlo.verify(m, an, rows[k], threads=16)
         assert_results_equal(want, r, m.name)
-    # recycle the handles: same storage, same answers
-    hl2 = vl.vl_liveness_multi(hm, 0, 0, live=hl)
-    assert [a.value for a in hl2] == [a.value for a in hl]
-    res2 = gpu_verify(hm, hl2, rows)
-    for a, b in zip(res, res2):
-        assert (a == b).all()
+    # recycle the handles: same storage, same answers.  The first recycling call with the
+    # same options reuses the known sizes without waiting, the second also the device tables;
+    # then other options (dense points, another tile length) size everything afresh.
+    for flags, tile_len, dense in ((0, 0, False), (0, 0, False), (vl.VL_DENSE_POINTS, 0, True), (0, 300, False),
+                                   (0, 300, False)):
+        hl2 = vl.vl_liveness_multi(hm, flags, tile_len, live=hl)
+        assert [a.value for a in hl2] == [a.value for a in hl]
+        torch.cuda.synchronize()
+        got2 = [vl.view_to_numpy(vl.vl_live_get(l)) for l in hl2]
+        for k, m in enumerate(mirs[:6]):
+            an = vlo.analyze(m, interference=False, threads=16)
+            assert_liveness_equal(m, an, got2[k], f"{m.name} recycled {flags} {tile_len}")
+            assert (got2[k]["live_after"] is not None) == dense
+        res2 = gpu_verify(hm, hl2, rows)
+        for a, b in zip(res, res2):
+            assert (a == b).all()
     free(hm, hl)
 
 
