@@ -81,6 +81,9 @@ constexpr uint32_t kPlanKeep = 64u;  // (chk) the next occurrence of the vreg is
 // Geometry of the verifier's LDS window, which the analysis needs for kPlanKeep: occurrences
 // are staged kWalkChunk at a time into a ring of kWalkRing.
 constexpr uint32_t kWalkChunk = 64, kWalkRing = 192;
+// While a chunk is processed the next one is being written over the oldest of the three,
+// so what may be read is the chunk itself and the one before it.
+constexpr uint32_t kWalkReach = 2 * kWalkChunk;
 constexpr uint32_t kWalkRingStride = 64 + 4;   // uint16 per ring slot: 64 candidate rows + padding (136 bytes)
 constexpr uint32_t kKeepMaxGap = 4096;   // longer gaps are not worth a slot
 

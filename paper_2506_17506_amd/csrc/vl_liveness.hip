@@ -449,9 +449,9 @@ __global__ void k_events(MIRS) {
   {
     // when an occurrence is checked the ring ends with that occurrence's chunk
     const uint32_t next = e + 1 < hi ? L.vocc[e + 1] : o;
-    const bool keep = o + kWalkRing < (next / kWalkChunk + 1u) * kWalkChunk && next - o <= kKeepMaxGap;
+    const bool keep = o + kWalkReach < (next / kWalkChunk + 1u) * kWalkChunk && next - o <= kKeepMaxGap;
     const uint32_t delta = prev == kNone ? 0u : min(o - prev, 0xFFFFu);
-    const bool near = prev != kNone && delta != 0xFFFFu && prev + kWalkRing >= (o / kWalkChunk + 1u) * kWalkChunk;
+    const bool near = prev != kNone && delta != 0xFFFFu && prev + kWalkReach >= (o / kWalkChunk + 1u) * kWalkChunk;
     const uint32_t attr = m.vattr[v];
     const uint32_t width = attr_width(attr), align = attr_align(attr), F = m.class_size[attr_class(attr)];
     const bool is_first = (role & kRoleFirst) != 0;
@@ -582,9 +582,9 @@ __device__ inline void f_boundary(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &
           uint32_t v = w * 32 + __ffs(bits) - 1;
           bits &= bits - 1;
           const uint32_t src = source_occurrence(L, v, at);
-          // replayed with the block's first instruction, when the ring ends at most 127
-          // occurrences after that instruction's first operand
-          const bool near = src < m.occ_off[at] && src + (kWalkRing - 2 * kWalkChunk + 1) >= m.occ_off[at];
+          // replayed with the block's first instruction, when the readable window ends at
+          // most 127 occurrences after that instruction's first operand
+          const bool near = src < m.occ_off[at] && src + (kWalkReach - 2 * kWalkChunk + 1) >= m.occ_off[at];
           L.plan[pos++] = event_record(m, src, m.vattr[v], false, near);
         }
       }

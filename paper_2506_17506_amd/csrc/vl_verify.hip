@@ -88,60 +88,65 @@ struct Walk {
   const uint16_t VL_GLOBAL *rows;   // first row of the group
   uint64_t ld;
   uint32_t keys, ring16;  // LDS indices
-  uint32_t tid, lane, row, nrows, n_occ, staged_lo, staged_hi, fast;
-  uint32_t pre[2][4];     // the chunk after staged_hi, in flight
+  // readable occurrences: [max(lo, hi - kWalkReach), hi); hi is the end of the chunk being processed
+  uint32_t tid, lane, row, nrows, n_occ, lo, hi, fast;
+  uint32_t pre[3][4];     // check wavefronts: their share of the chunk being fetched
 };
 
-// Each of the 256 threads owns 8 consecutive occurrences (16 bytes) of two rows of a
-// 64-occurrence chunk.  Lane bits: k = lane & 7 picks the 16 bytes inside the row's 128-byte
-// line, rr = lane >> 3 the row pair; the two halves of a line (k < 4, k >= 4) belong to rows
-// 16 apart.  With this assignment the 64 lanes of every LDS store below fall into 64
-// different banks (slot stride 34 dwords: bank = 16 (k & 3) + 8 (row bit 4) + rr + const).
-__device__ inline uint32_t staged_row(uint32_t tid, int h) {
-  const uint32_t k = tid & 7u, rr = (tid >> 3) & 7u, wave = tid >> 6;
-  return (uint32_t)h + 2u * rr + 16u * ((k >> 2) ^ (wave >> 1)) + 32u * (wave & 1u);
+// Staging is done by the three check wavefronts.  A chunk is 64 rows x 8 pieces of 16 bytes
+// (8 occurrences); piece k of row r goes to lane (k, rr) of pass q with
+//   r = y + 2 rr + 16 ((k >> 2) ^ u) + 32 z,   q = y + 2 z + 4 u  (0..7),
+// the two halves of a 128-byte line (k < 4, k >= 4) belonging to rows 16 apart.  With this
+// assignment the 64 lanes of every LDS store below fall into 64 different banks (slot stride
+// 34 dwords: bank = 16 (k & 3) + 8 (row bit 4) + rr + const).  Check wavefront j takes the
+// passes j, j + 3, j + 6.
+__device__ inline uint32_t staged_row(uint32_t lane, uint32_t q) {
+  const uint32_t k = lane & 7u, rr = lane >> 3;
+  return (q & 1u) + 2u * rr + 16u * ((k >> 2) ^ (q >> 2)) + 32u * ((q >> 1) & 1u);
 }
 
-__device__ inline void load_chunk(Walk &w, uint32_t c0) {
-  const uint32_t c = c0 + (w.tid & 7u) * 8u;
+__device__ inline void load_chunk(Walk &w, uint32_t c0, uint32_t j) {
+  const uint32_t c = c0 + (w.lane & 7u) * 8u;
 #pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const uint32_t r = staged_row(w.tid, h);
+  for (int h = 0; h < 3; ++h) {
+    const uint32_t q = j + 3u * h;
     w.pre[h][0] = w.pre[h][1] = w.pre[h][2] = w.pre[h][3] = 0;
+    if (q >= 8u) continue;
+    const uint32_t r = staged_row(w.lane, q);
     if (r < w.nrows && c < w.n_occ) {
       const uint16_t VL_GLOBAL *src = w.rows + (uint64_t)r * w.ld + c;
       if (w.fast && c + 8u <= w.n_occ) {
         const u32x4 x = *reinterpret_cast<const u32x4 VL_GLOBAL *>(src);
         w.pre[h][0] = x.x; w.pre[h][1] = x.y; w.pre[h][2] = x.z; w.pre[h][3] = x.w;
       } else {
-        for (int j = 0; j < 4; ++j) {
-          uint32_t a = (c + 2 * j < w.n_occ) ? src[2 * j] : 0u;
-          uint32_t b = (c + 2 * j + 1 < w.n_occ) ? src[2 * j + 1] : 0u;
-          w.pre[h][j] = a | (b << 16);
+        for (int t = 0; t < 4; ++t) {
+          uint32_t a = (c + 2 * t < w.n_occ) ? src[2 * t] : 0u;
+          uint32_t b = (c + 2 * t + 1 < w.n_occ) ? src[2 * t + 1] : 0u;
+          w.pre[h][t] = a | (b << 16);
         }
       }
     }
   }
 }
 
-// writes the chunk held in registers into the ring as chunk [staged_hi, staged_hi + 64)
-__device__ inline void store_chunk(Walk &w) {
-  const uint32_t c = w.staged_hi + (w.tid & 7u) * 8u;
+// writes the chunk held in registers into the ring as chunk [c0, c0 + 64)
+__device__ inline void store_chunk(const Walk &w, uint32_t c0, uint32_t j) {
+  const uint32_t c = c0 + (w.lane & 7u) * 8u;
 #pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const uint32_t r = staged_row(w.tid, h);
-    const uint32_t dst = w.ring16 + (c % kRing) * kRingStride + r;
+  for (int h = 0; h < 3; ++h) {
+    const uint32_t q = j + 3u * h;
+    if (q >= 8u) continue;
+    const uint32_t dst = w.ring16 + (c % kRing) * kRingStride + staged_row(w.lane, q);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      VL_LDS16[dst + (2 * j) * kRingStride] = (uint16_t)w.pre[h][j];
-      VL_LDS16[dst + (2 * j + 1) * kRingStride] = (uint16_t)(w.pre[h][j] >> 16);
+    for (int t = 0; t < 4; ++t) {
+      VL_LDS16[dst + (2 * t) * kRingStride] = (uint16_t)w.pre[h][t];
+      VL_LDS16[dst + (2 * t + 1) * kRingStride] = (uint16_t)(w.pre[h][t] >> 16);
     }
   }
-  w.staged_hi += kChunk;
 }
 
 __device__ inline bool in_ring(const Walk &w, uint32_t o) {
-  return o < w.staged_hi && o + kRing >= w.staged_hi && o >= w.staged_lo;
+  return o < w.hi && o + kWalkReach >= w.hi && o >= w.lo;
 }
 
 // value of occurrence o (uniform) in this lane's row
@@ -232,15 +237,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k
   const uint32_t ea = g_tile_range[2 * tile], eb = g_tile_range[2 * tile + 1];   // its events
   const uint32_t ca = oa / kChunk;
   const uint32_t c_end = ob > oa ? (ob - 1) / kChunk + 1 : ca;   // chunks [ca, c_end)
-  // start two chunks before the tile's first occurrence, so that nearby history is in LDS
-  const uint32_t c0 = ca > 2 ? ca - 2 : 0;
-  w.staged_lo = w.staged_hi = c0 * kChunk;
-  load_chunk(w, w.staged_hi);
-  while (w.staged_hi < ca * kChunk) {
-    store_chunk(w);
-    load_chunk(w, w.staged_hi);
-  }
-  __syncthreads();
+  // the ring starts one chunk before the tile's first occurrence, so that nearby history is in LDS
+  const uint32_t c_first = ca > 0 ? ca - 1 : 0;
+  w.lo = c_first * kChunk;
+  w.hi = w.lo;      // nothing readable yet
+  __syncthreads();  // masks and keys are cleared
 
   // ---- occupancy events (lane = candidate) ----
   // Events are replayed in instruction order, so the first clash of a row is the one to
@@ -389,7 +390,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k
     const uint32_t fl = rec.x & 0xFFu, attr = rec.y >> 16, delta = rec.y & 0xFFFFu;
     const bool is_chk = (fl & kPlanChk) != 0;
     const uint32_t prev = o - delta;
-    const bool near = (fl & kChkNear) && prev >= w.staged_lo;   // the ring starts at the tile's first staged chunk
+    const bool near = (fl & kChkNear) && prev >= w.lo;   // the ring starts at the tile's first staged chunk
     const bool far = is_chk && !near;
     const bool generic = (fl & kChkGeneric) != 0;
     // Four rows per 8-byte read, two rows per 32-bit operation.  What is wrong in a row
@@ -470,8 +471,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k
     }
   };
 
-  // first the tile's live-in values are occupied; steps ca .. c_end-1 then stage one chunk
-  // each and process what it releases (a tile without operands still replays its events once)
+  // Schedule.  The three check wavefronts do the staging: while chunk c is processed they
+  // write chunk c + 1 over the slots of chunk c - 2 (nobody reads further back than chunk
+  // c - 1 any more: kWalkReach) and fetch chunk c + 2.  The occupancy wavefront only replays
+  // events: first the tile's live-in values, while the others fill the ring, then per chunk
+  // what that chunk releases.  One barrier per chunk; both kinds of wavefront pass the same
+  // number of barriers (a tile without operands still replays its events once).
   const uint32_t c_stop = c_end > ca ? c_end : ca + 1;
   // occupancy wavefront: limits of the current chunk's batch, clamped to the tile, and the
   // next chunk's records.  The limits are read with vector loads (the lane-dependent index
@@ -480,24 +485,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k
   uint32_t lane_zero;   // zero in a vector register the compiler cannot see through
   asm volatile("v_mov_b32 %0, 0" : "=v"(lane_zero));
   auto clamp_cut = [&](uint32_t e) __attribute__((always_inline)) { return min(eb, max(ea, e)); };
-  // All four wavefronts stage; after that the occupancy wavefront and the check wavefronts
-  // run loops of their own (the same number of barriers in each), so that neither carries
-  // the other's registers.
-  auto stage = [&]() __attribute__((always_inline)) {
-    __syncthreads();   // everyone is done with the slots about to be overwritten
-    store_chunk(w);
-    load_chunk(w, w.staged_hi);
-    __syncthreads();
-  };
   if (role == 0) {
     uint32_t cut_lo = ea;
     uint32_t v_cut_next = g_evt_cut[min(ca + 1, n_chunk) + lane_zero];
     u32x4 rec_next = fetch_records(ea, eb);   // the first batch, in flight during the seeds
     if (tile > 0) seed_events(g_seed_off[tile], g_seed_off[tile + 1]);
+    __syncthreads();   // chunks up to ca are in the ring
     for (uint32_t c = ca; c != c_stop; ++c) {
-      if (c < c_end) stage();
-      // what was fetched ahead during the previous chunk has arrived by now (staging
-      // waited for every outstanding load)
+      if (c < c_end) w.hi = (c + 1) * kChunk;
       const uint32_t cut_hi = clamp_cut(__builtin_amdgcn_readfirstlane(v_cut_next));
       const uint32_t from = cut_lo, to = c + 1 >= c_end ? eb : cut_hi;
       const u32x4 first = rec_next;
@@ -507,14 +502,29 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k
       v_cut_next = g_evt_cut[min(c + 2, n_chunk) + lane_zero];
       rec_next = fetch_records(cut_lo, eb);
       events(from, to, first);
+      __syncthreads();
     }
   } else {
+    const uint32_t j = role - 1;
+    for (uint32_t c = c_first; c <= ca && c < c_end; ++c) {   // history chunk and the tile's first chunk
+      load_chunk(w, c * kChunk, j);
+      store_chunk(w, c * kChunk, j);
+    }
+    if (ca + 1 < c_end) load_chunk(w, (ca + 1) * kChunk, j);
     u32x4 chk_next = load_chk(ca);
-    for (uint32_t c = ca; c < c_end; ++c) {
-      stage();
-      const u32x4 raw = chk_next;
-      chk_next = load_chk(c + 1);   // in flight while this chunk is checked
-      checks(c, role - 1, raw);
+    __syncthreads();
+    for (uint32_t c = ca; c != c_stop; ++c) {
+      if (c < c_end) {
+        if (c + 1 < c_end) {
+          store_chunk(w, (c + 1) * kChunk, j);
+          if (c + 2 < c_end) load_chunk(w, (c + 2) * kChunk, j);
+        }
+        w.hi = (c + 1) * kChunk;
+        const u32x4 raw = chk_next;
+        chk_next = load_chk(c + 1);   // in flight while this chunk is checked
+        checks(c, j, raw);
+      }
+      __syncthreads();
     }
   }
   __syncthreads();
