@@ -188,7 +188,7 @@ def main():
                                "1,000-20,000 instructions log-uniform, K=100 candidates each, 20% damaged; "
                                "liveness of every kernel + verification of every candidate per step",
                    "kernels": len(w.kernels), "candidates": w.n_candidates,
-                   "instr_x_candidate_checks": w.n_checks, "tile_len": args.tile or 1024},
+                   "instr_x_candidate_checks": w.n_checks, "tile_len": int(vl.vl_live_get(lives[0]).tile_len)},
         "checks_per_s": w.n_checks * args.steps / dt,
         "liveness_ms": live_ms, "verify_ms": verify_ms, "host_enqueue_ms_per_step": dt_enqueue / args.steps * 1e3,
         "status_histogram": np.bincount(status, minlength=4).tolist(),

@@ -17,7 +17,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr uint32_t kMaxClass = 8;
 constexpr uint32_t kMaxOperands = 64;      // per instruction
 constexpr uint32_t kNone = 0xFFFFFFFFu;
-constexpr uint32_t kDefaultTile = 1024;    // instructions per verification tile
+constexpr uint32_t kDefaultTile = 512;     // instructions per verification tile
 
 // Kernel (program) on the device.  All pointers are device memory.
 struct DevMir {
