@@ -34,6 +34,12 @@ namespace {
 // workgroup then needs about 31 KB, so five workgroups share a compute unit's 160 KB.
 constexpr uint32_t kRing = kWalkRing;
 constexpr uint32_t kRingStride = kWalkRingStride;
+#ifndef VL_CHECK_WAVES
+#define VL_CHECK_WAVES 3
+#endif
+constexpr uint32_t kCheckWaves = VL_CHECK_WAVES;   // wavefronts per workgroup that stage and check
+constexpr uint32_t kWalkThreads = 64 * (1 + kCheckWaves);
+constexpr int kStagePasses = (8 + kCheckWaves - 1) / kCheckWaves;
 constexpr uint32_t kChunk = kWalkChunk;                 // occurrences staged per step (128 B per row)
 constexpr uint32_t kKeyOk = 0xFFFFFFFFu;
 constexpr uint32_t kKeyCons = 0u << 28, kKeyReal = 1u << 28, kKeySafe = 2u << 28, kKeyPos = (1u << 28) - 1;
@@ -90,7 +96,7 @@ struct Walk {
   uint32_t keys, ring16;  // LDS indices
   // readable occurrences: [max(lo, hi - kWalkReach), hi); hi is the end of the chunk being processed
   uint32_t tid, lane, row, nrows, n_occ, lo, hi, fast;
-  uint32_t pre[3][4];     // check wavefronts: their share of the chunk being fetched
+  uint32_t pre[kStagePasses][4];     // check wavefronts: their share of the chunk being fetched
 };
 
 // Staging is done by the three check wavefronts.  A chunk is 64 rows x 8 pieces of 16 bytes
@@ -108,8 +114,8 @@ __device__ inline uint32_t staged_row(uint32_t lane, uint32_t q) {
 __device__ inline void load_chunk(Walk &w, uint32_t c0, uint32_t j) {
   const uint32_t c = c0 + (w.lane & 7u) * 8u;
 #pragma unroll
-  for (int h = 0; h < 3; ++h) {
-    const uint32_t q = j + 3u * h;
+  for (int h = 0; h < kStagePasses; ++h) {
+    const uint32_t q = j + kCheckWaves * h;
     w.pre[h][0] = w.pre[h][1] = w.pre[h][2] = w.pre[h][3] = 0;
     if (q >= 8u) continue;
     const uint32_t r = staged_row(w.lane, q);
@@ -133,8 +139,8 @@ __device__ inline void load_chunk(Walk &w, uint32_t c0, uint32_t j) {
 __device__ inline void store_chunk(const Walk &w, uint32_t c0, uint32_t j) {
   const uint32_t c = c0 + (w.lane & 7u) * 8u;
 #pragma unroll
-  for (int h = 0; h < 3; ++h) {
-    const uint32_t q = j + 3u * h;
+  for (int h = 0; h < kStagePasses; ++h) {
+    const uint32_t q = j + kCheckWaves * h;
     if (q >= 8u) continue;
     const uint32_t dst = w.ring16 + (c % kRing) * kRingStride + staged_row(w.lane, q);
 #pragma unroll
@@ -197,7 +203,7 @@ __device__ inline bool unrealizable(const DevMir VL_GLOBAL &m, uint32_t attr, ui
   return bad;
 }
 
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k_walk(const DevJob *__restrict__ jobs, uint32_t n_jobs) {
+__global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(5))) void k_walk(const DevJob *__restrict__ jobs, uint32_t n_jobs) {
   const DevJob VL_GLOBAL &J = as_global(jobs)[find_job(jobs, n_jobs, blockIdx.x)];
   const DevMir VL_GLOBAL &m = *as_global(J.mir);
   const DevLive VL_GLOBAL &L = *as_global(J.live);
@@ -216,7 +222,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k
   w.lane = threadIdx.x & 63u;
   // the occupancy role moves from wavefront to wavefront with the workgroup index, so
   // that neighbouring workgroups do not all put it on the same SIMD
-  const uint32_t role = __builtin_amdgcn_readfirstlane(((threadIdx.x >> 6) + blockIdx.x) & 3u);
+  const uint32_t role = __builtin_amdgcn_readfirstlane(((threadIdx.x >> 6) + blockIdx.x) % (1u + kCheckWaves));
   w.nrows = min(J.rows, J.K - row0);
   const bool active = w.lane < w.nrows;
   w.row = active ? w.lane : 0u;
@@ -226,7 +232,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k
   w.fast = J.fast;
   w.keys = m.occ_words * 64;
   w.ring16 = (w.keys + 64) * 2;
-  for (uint32_t x = w.tid; x < m.occ_words * 64; x += 256) vl_lds[x] = 0;
+  for (uint32_t x = w.tid; x < m.occ_words * 64; x += kWalkThreads) vl_lds[x] = 0;
   if (w.tid < 64) vl_lds[w.keys + w.tid] = kKeyOk;
   // per-class file size and first mask word, one class per lane, read back by lane index
   const uint32_t cls_tab_v = w.lane < m.C ? ((uint32_t)m.class_size[w.lane] | ((uint32_t)m.class_word[w.lane] << 16)) : 0u;
@@ -410,7 +416,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k
     uint32_t acc = 0;
     // this wavefront's third of the row quads, two quads (one 16-byte read) at a time
     const uint32_t n_quad = (w.nrows + 3) / 4;
-    const uint32_t q_lo = part * n_quad / 3, q_hi = (part + 1) * n_quad / 3;
+    const uint32_t q_lo = part * n_quad / kCheckWaves, q_hi = (part + 1) * n_quad / kCheckWaves;
     uint32_t qd = q_lo;
     for (; qd + 2 <= q_hi; qd += 2) {
       const uint64_t pv0 = lds64[a_p + qd], pv1 = lds64[a_p + qd + 1], qv0 = lds64[a_q + qd], qv1 = lds64[a_q + qd + 1];
@@ -442,7 +448,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k
     // otherwise from memory.  A link belongs to the wavefront that owns its earlier
     // occurrence (index modulo three), which is also the one that cached it.
     const bool sat = delta == 0xFFFFu;
-    uint64_t todo = __ballot(far && (sat ? w.lane % 3u == part : prev % 3u == part));
+    uint64_t todo = __ballot(far && (sat ? w.lane % kCheckWaves == part : prev % kCheckWaves == part));
     while (todo) {
       const uint32_t j = __builtin_ctzll(todo);
       todo &= todo - 1;
@@ -451,7 +457,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k
       const uint32_t pv = VL_LDS16[w.ring16 + (oj % kRing) * kRingStride + w.row];
       uint32_t qv;
       if (dj != 0xFFFFu) {
-        const uint32_t pj = oj - dj, slot = (pj / 3u) % kCacheSlots;
+        const uint32_t pj = oj - dj, slot = (pj / kCheckWaves) % kCacheSlots;
         if ((uint32_t)__builtin_amdgcn_readlane(cache_tag, slot) == pj) qv = (cache[slot >> 1] >> (16u * (slot & 1u))) & 0xFFFFu;
         else qv = w.rows[(uint64_t)w.row * w.ld + pj];
       } else {
@@ -460,11 +466,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k
       if (pv != qv) key = min(key, kKeyCons | oj);
     }
     // occurrences whose successor is likely out of reach: keep their registers
-    uint64_t keep = __ballot((fl & kPlanKeep) && o % 3u == part);
+    uint64_t keep = __ballot((fl & kPlanKeep) && o % kCheckWaves == part);
     while (keep) {
       const uint32_t j = __builtin_ctzll(keep);
       keep &= keep - 1;
-      const uint32_t oj = c * kChunk + j, slot = (oj / 3u) % kCacheSlots;
+      const uint32_t oj = c * kChunk + j, slot = (oj / kCheckWaves) % kCacheSlots;
       const uint32_t val = VL_LDS16[w.ring16 + (oj % kRing) * kRingStride + w.row], both = cache[slot >> 1];
       cache[slot >> 1] = (slot & 1u) ? ((both & 0xFFFFu) | (val << 16)) : ((both & 0xFFFF0000u) | val);
       if (w.lane == slot) cache_tag = oj;
@@ -816,7 +822,7 @@ extern "C" int32_t vl_verify_multi(const vl_job *jobs, uint32_t n_jobs, vl_strea
   const size_t lds = (size_t)L.max_words * 64 * 4 + 64 * 4 + (size_t)kRing * kRingStride * 2;
   k_init<<<dim3((L.maxK + 255) / 256, n_jobs), 256, 0, stream>>>(L.dev);
   if (g_time_start) VL_HIP(hipEventRecord(g_time_start, stream));
-  k_walk<<<L.units, 256, lds, stream>>>(L.dev, n_jobs);
+  k_walk<<<L.units, kWalkThreads, lds, stream>>>(L.dev, n_jobs);
   if (g_time_stop) VL_HIP(hipEventRecord(g_time_stop, stream));
   g_time_start = g_time_stop = nullptr;
   k_finalize<<<dim3((L.maxK + 255) / 256, n_jobs), 256, 0, stream>>>(L.dev);
