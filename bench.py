@@ -67,6 +67,8 @@ def main():
     ap.add_argument("--kernels", type=int, default=256, help="kernels in the sweep (256 = the benchmark)")
     ap.add_argument("--tile", type=int, default=0, help="instructions per verification tile (0 = default)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the step as replays of a recorded HIP graph (reported beside the eager figure)")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
                     help="before the warm-up, run one plain elementwise kernel that reads MIB MiB and writes "
                          "MIB MiB: a dispatch of known traffic to scale hardware byte counters by")
@@ -161,6 +163,29 @@ def main():
     torch.cuda.synchronize()
     verify_ms = (time.perf_counter() - t1) / 5 * 1e3
 
+    # the same step recorded once into a HIP graph and replayed (for the record)
+    graph_ms = None
+    if args.graph:
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            for _ in range(2):   # known sizes and current tables on this stream's first calls too
+                vl.vl_liveness_multi(mirs, 0, args.tile, side, live=lives)
+                vl.vl_verify_multi(jobs, side)
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                cap = torch.cuda.current_stream()
+                vl.vl_liveness_multi(mirs, 0, args.tile, cap, live=lives)
+                vl.vl_verify_multi(jobs, cap)
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t1) / args.steps * 1e3
+
     # the regeneration-loop reductions over the results (not part of the timed step)
     summaries = torch.zeros((len(mirs), 6), dtype=torch.int32, device="cuda")
     loop_dev = torch.zeros((6,), dtype=torch.int64, device="cuda")
@@ -191,6 +216,7 @@ def main():
                    "instr_x_candidate_checks": w.n_checks, "tile_len": int(vl.vl_live_get(lives[0]).tile_len)},
         "checks_per_s": w.n_checks * args.steps / dt,
         "liveness_ms": live_ms, "verify_ms": verify_ms, "host_enqueue_ms_per_step": dt_enqueue / args.steps * 1e3,
+        "graph_replay_ms_per_step": graph_ms,
         "status_histogram": np.bincount(status, minlength=4).tolist(),
         "regeneration_loop": {"kernels_passed": int(loop["n_passed"]), "avg_tries": float(loop["sum_tries"]) / len(mirs),
                               "max_tries": int(loop["max_tries"]), "summarize_us": summarize_us},

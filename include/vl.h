@@ -96,7 +96,10 @@ void vl_mir_destroy(vl_mir *mir);
  * these same kernels returned, whose device storage is then reused (no
  * allocation when it is large enough).  When that call also had the same flags
  * and tile_len, the result sizes are known from it: nothing is read back and
- * the call does not synchronise at all.  On success live[i] describes mirs[i].
+ * the call does not synchronise at all.  From the second such call on it
+ * enqueues kernels only (no copy, no memset): that call, vl_verify_multi and
+ * vl_summarize_multi with an unchanged job table may then be recorded in a
+ * stream capture and replayed.  On success live[i] describes mirs[i].
  * On error no handle is created; recycled handles stay allocated but their
  * contents are undefined until the next successful call.
  * tile_len: instructions per verification tile, 0 = library default.

@@ -805,6 +805,21 @@ __device__ inline void f_seed_src(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &
   L.seeds[k] = r;
 }
 
+// Clears `vecs` 16-byte vectors.  A kernel rather than a memset so that a caller may record
+// the steady-state analysis into a stream capture (the arenas are 256-byte aligned and every
+// region's length is a multiple of 256 bytes).
+__global__ void k_zero(u32x4 VL_GLOBAL *p, size_t vecs) {
+  const u32x4 z = {0, 0, 0, 0};
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < vecs; i += (size_t)gridDim.x * blockDim.x) p[i] = z;
+}
+
+static inline void zero_async(void *p, size_t bytes, hipStream_t stream) {
+  if (!bytes) return;
+  const size_t vecs = bytes / 16;
+  const uint32_t blocks = (uint32_t)std::min<size_t>(8192, (vecs + 255) / 256);
+  k_zero<<<blocks, 256, 0, stream>>>((u32x4 VL_GLOBAL *)p, vecs);
+}
+
 __global__ void k_collect(MIRS, uint32_t n) {
   uint32_t k = blockIdx.x * blockDim.x + threadIdx.x;
   if (k >= n) return;
@@ -1143,7 +1158,8 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
 
   // pinned staging: stage_a / stage_mirs are read by the copies below; when the sizes are not
   // known yet the host waits further down and stage_b carries the second upload after that
-  hipError_t e = hipMemsetAsync(a1, 0, zero_bytes, stream);
+  zero_async(a1, zero_bytes, stream);
+  hipError_t e = hipSuccess;
   // with known sizes the tables on the device are usually the ones this call would upload
   const bool tables_current = known && batch->uploaded.size() == (size_t)n * sizeof(DevLive) &&
                               memcmp(batch->uploaded.data(), h.data(), batch->uploaded.size()) == 0;
@@ -1208,8 +1224,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     if (e != hipSuccess) return fail(hip_fail(e));
   }
   if (dense) {
-    e = hipMemsetAsync((char *)batch->arena2 + zero2_lo, 0, zero2_hi - zero2_lo, stream);
-    if (e != hipSuccess) return fail(hip_fail(e));
+    zero_async((char *)batch->arena2 + zero2_lo, zero2_hi - zero2_lo, stream);
   }
   const StageGrid g_fill = {blocks(maxT, 4), blocks(maxN, TB), blocks(maxO, TB)};
   const StageGrid g_fin = {blocks(maxB, 4), blocks(maxT, TB), blocks(max_seed, TB)};
