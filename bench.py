@@ -69,6 +69,12 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--graph", action="store_true",
                     help="also time the step as replays of a recorded HIP graph (reported beside the eager figure)")
+    ap.add_argument("--no-two-stream", action="store_true",
+                    help="skip the extra leg that alternates the steps over two streams (it lengthens the "
+                         "candidate walk's launches, which a kernel trace of the run would average in)")
+    ap.add_argument("--streams", type=int, default=1,
+                    help="steps alternate over this many streams, each with its own analysis handles and result "
+                         "buffers (steps on different streams may overlap on the device)")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
                     help="before the warm-up, run one plain elementwise kernel that reads MIB MiB and writes "
                          "MIB MiB: a dispatch of known traffic to scale hardware byte counters by")
@@ -113,13 +119,27 @@ def main():
         alg_bytes += 8 * vl.vl_live_get(l).plan_len
     jobs = vl.make_jobs([(m, l, d, r.shape[0], ld, o)
                          for m, l, d, r, ld, o in zip(mirs, lives, dev_rows, w.rows, lds, outs)])
+    # further streams: the same kernels and candidates, analysis handles and results of their own
+    lanes = [(stream, lives, jobs)]
+    keep = []
+    for _ in range(1, max(2, args.streams)):
+        st = torch.cuda.Stream()
+        lv = vl.vl_liveness_multi(mirs, 0, args.tile, st)
+        oo = [torch.zeros_like(o) for o in outs]
+        keep.append(oo)
+        lanes.append((st, lv, vl.make_jobs([(m, l, d, r.shape[0], ld, o)
+                                            for m, l, d, r, ld, o in zip(mirs, lv, dev_rows, w.rows, lds, oo)])))
+    torch.cuda.synchronize()
+    turn, n_lanes = 0, args.streams
 
     def step(ev=None):
-        nonlocal lives
-        lives = vl.vl_liveness_multi(mirs, 0, args.tile, stream, live=lives)
+        nonlocal turn
+        st, lv, jb = lanes[turn % n_lanes]
+        turn += 1
+        vl.vl_liveness_multi(mirs, 0, args.tile, st, live=lv)
         if ev is not None:
             vl.vl_verify_time_next(ev[0].value, ev[1].value)
-        vl.vl_verify_multi(jobs, stream)
+        vl.vl_verify_multi(jb, st)
 
     events = []
     for _ in range(args.steps):
@@ -163,6 +183,20 @@ def main():
     torch.cuda.synchronize()
     verify_ms = (time.perf_counter() - t1) / 5 * 1e3
 
+    # the same steps alternating over two streams (for the record): the analysis of one step
+    # then overlaps the candidate walk of the step before it
+    two_stream_ms = None
+    if not args.no_two_stream:
+        n_lanes = 2
+        for _ in range(max(2, args.warmup)):
+            step()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        two_stream_ms = (time.perf_counter() - t1) / args.steps * 1e3
+
     # the same step recorded once into a HIP graph and replayed (for the record)
     graph_ms = None
     if args.graph:
@@ -199,6 +233,8 @@ def main():
     loop = loop_dev.cpu().numpy().view(np.uint8).view(vl.LOOP_DTYPE)[0]
 
     status = np.concatenate([o.cpu().numpy()[:, 0] for o in outs])
+    for oo in keep:   # every stream's results are the first stream's
+        assert all(bool((a == b).all()) for a, b in zip(oo, outs)), "results differ between streams"
     achieved = alg_bytes / walk_avg_s / 1e9
     src = os.path.join(ROOT, "paper_2506_17506_amd", "csrc", "vl_verify.hip")
     rec = {
@@ -216,7 +252,8 @@ def main():
                    "instr_x_candidate_checks": w.n_checks, "tile_len": int(vl.vl_live_get(lives[0]).tile_len)},
         "checks_per_s": w.n_checks * args.steps / dt,
         "liveness_ms": live_ms, "verify_ms": verify_ms, "host_enqueue_ms_per_step": dt_enqueue / args.steps * 1e3,
-        "graph_replay_ms_per_step": graph_ms,
+        "graph_replay_ms_per_step": graph_ms, "streams": args.streams,
+        "two_stream_ms_per_step": two_stream_ms, "two_stream_value": w.n_candidates / two_stream_ms * 1e3 if two_stream_ms else None,
         "status_histogram": np.bincount(status, minlength=4).tolist(),
         "regeneration_loop": {"kernels_passed": int(loop["n_passed"]), "avg_tries": float(loop["sum_tries"]) / len(mirs),
                               "max_tries": int(loop["max_tries"]), "summarize_us": summarize_us},

@@ -662,14 +662,23 @@ __global__ __launch_bounds__(256) void k_resolve(const DevJob *__restrict__ jobs
   }
 }
 
-// per-device scratch for job tables
-struct Scratch {
-  std::mutex mu;
-  int device = -1;
+// Job tables on the device: per device a few slots, one per stream that has called, so
+// that calls alternating between streams neither wait for each other's table nor overwrite
+// a table that kernels of the other stream still read.
+struct Slot {
+  bool used = false;
+  hipStream_t stream = nullptr;
   DevJob *dev = nullptr;
   DevJob *host = nullptr;   // pinned
   uint32_t cap = 0, n_valid = 0;
   hipEvent_t copied = nullptr;
+  uint64_t tick = 0;
+};
+constexpr int kSlots = 4;
+struct Scratch {
+  std::mutex mu;
+  Slot slot[kSlots];
+  uint64_t clock = 0;
 };
 Scratch g_scratch[16];
 
@@ -690,9 +699,28 @@ struct Launch {
 };
 
 // Validates the jobs, lays out the device job table and makes sure the device copy is
-// current (the copy is skipped when the table is the one already there).  Called with the
-// device's scratch locked.
-int32_t prepare_jobs(const vl_job *jobs, uint32_t n_jobs, hipStream_t stream, Scratch &s, Launch &out) {
+// current (the copy is skipped when the table is the one the stream's slot already holds).
+// Called with the device's scratch locked.
+int32_t prepare_jobs(const vl_job *jobs, uint32_t n_jobs, hipStream_t stream, Scratch &sc, Launch &out) {
+  // the calling stream's slot, else a free one, else the least recently used one (whose
+  // earlier kernels may be anywhere: the device is drained before the slot changes hands)
+  Slot *found = nullptr;
+  for (Slot &c : sc.slot)
+    if (c.used && c.stream == stream) found = &c;
+  if (!found)
+    for (Slot &c : sc.slot)
+      if (!c.used && !found) found = &c;
+  if (!found) {
+    found = &sc.slot[0];
+    for (Slot &c : sc.slot)
+      if (c.tick < found->tick) found = &c;
+    VL_HIP(hipDeviceSynchronize());
+    found->n_valid = 0;
+  }
+  Slot &s = *found;
+  s.used = true;
+  s.stream = stream;
+  s.tick = ++sc.clock;
   std::vector<DevJob> tab(n_jobs);
   for (uint32_t j = 0; j < n_jobs; ++j) {
     const vl_job &u = jobs[j];
@@ -728,8 +756,8 @@ int32_t prepare_jobs(const vl_job *jobs, uint32_t n_jobs, hipStream_t stream, Sc
     // the previous table may still be on its way to the device
     if (s.n_valid) VL_HIP(hipEventSynchronize(s.copied));
     memcpy(s.host, tab.data(), (size_t)n_jobs * sizeof(DevJob));
-    // kernels of an earlier call that still read the old device table run on a stream the
-    // caller must order before this one; on the same stream the copy below is ordered
+    // kernels of an earlier call that still read the old device table run on this same
+    // stream: the copy below is ordered after them
     VL_HIP(hipMemcpyAsync(s.dev, s.host, (size_t)n_jobs * sizeof(DevJob), hipMemcpyHostToDevice, stream));
     VL_HIP(hipEventRecord(s.copied, stream));
     s.n_valid = n_jobs;

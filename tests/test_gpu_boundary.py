@@ -88,3 +88,32 @@ def test_argument_errors_are_codes_not_faults():
         vl.vl_live_destroy(h)
     for h in (hm, ho):
         vl.vl_mir_destroy(h)
+
+
+def test_calls_alternating_over_streams():
+    """Each stream has its own job table on the device: calls with different tables that
+    alternate over streams without waiting for one another give every stream its own
+    answers, also with more streams than the library keeps tables for."""
+    w = gen.config(5, n_kernels=6)
+    want = []
+    for k, rows in zip(w.kernels, w.rows):
+        want.append(vlo.verify(k.mir, vlo.analyze(k.mir, threads=8), rows, threads=8))
+    hm = [vl.vl_mir_create(k.mir) for k in w.kernels]
+    hl = vl.vl_liveness_multi(hm)
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream() for _ in range(6)]
+    devs = [vl.rows_to_device(rows) for rows in w.rows]
+    outs = [torch.full((rows.shape[0], 4), -1, dtype=torch.int32, device="cuda") for rows in w.rows]
+    torch.cuda.synchronize()
+    # stream j verifies kernel j only (six different one-job tables); three rounds, no waits
+    jobs = [vl.make_jobs([(hm[j], hl[j], devs[j][0], w.rows[j].shape[0], devs[j][1], outs[j])]) for j in range(6)]
+    for _ in range(3):
+        for j, st in enumerate(streams):
+            vl.vl_verify_multi(jobs[j], stream=st)
+    torch.cuda.synchronize()
+    for j in range(6):
+        assert (results(outs[j]) == want[j]).all(), j
+    for l in hl:
+        vl.vl_live_destroy(l)
+    for m in hm:
+        vl.vl_mir_destroy(m)

@@ -82,7 +82,9 @@ class Kernel:
         self.range, self.sure = a["range"], a["sure"]
 
     def __del__(self):
-        if getattr(self, "_h", None):
+        # at interpreter shutdown the module's globals may already be gone: then the
+        # process is ending and the handle goes with it
+        if getattr(self, "_h", None) and lib is not None:
             lib().vlgen_free(self._h)
             self._h = None
 
