@@ -116,6 +116,7 @@ struct DevLive {
   uint32_t VL_GLOBAL *vocc_tmp;   // [O] occurrences grouped by vreg, unordered
   uint32_t VL_GLOBAL *vocc;       // [O] occurrences grouped by vreg, ascending
   uint32_t VL_GLOBAL *ent_instr;  // [O] instruction << 2 | occurrence flags of each sorted entry (ascending per vreg)
+  uint32_t VL_GLOBAL *ent_v;      // [O] vreg of each sorted entry
   uint8_t VL_GLOBAL *ent_info;    // [O] kEnt* bits of each sorted entry
   uint32_t VL_GLOBAL *first;      // [V] first occurrence or kNone
   uint32_t VL_GLOBAL *prev_occ;   // [O] previous occurrence of the same vreg, written only where the 16-bit

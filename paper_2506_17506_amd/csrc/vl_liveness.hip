@@ -178,6 +178,12 @@ __device__ inline void f_sort_short(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL
   const uint32_t lo = L.vcnt[v], len = L.vcnt[v + 1] - lo;
   if (len == 0) { L.first[v] = kNone; return; }
   if (len > kShortList) return;
+  // (the vreg of each sorted entry is recorded too, for the kernels that walk the entries)
+  auto put = [&](uint32_t at, uint32_t x) {
+    L.vocc[at] = x;
+    L.ent_v[at] = v;
+    if (at == lo) L.first[v] = x;
+  };
   if (len <= 8) {
     // the common case: all loads issued at once, ranks computed in registers (absent
     // elements are larger than any occurrence index)
@@ -189,18 +195,15 @@ __device__ inline void f_sort_short(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL
       uint32_t r = 0;
 #pragma unroll
       for (uint32_t k = 0; k < 8; ++k) r += a[k] < a[j];
-      if (j < len) {
-        L.vocc[lo + r] = a[j];
-        if (r == 0) L.first[v] = a[j];
-      }
+      if (j < len) put(lo + r, a[j]);
     }
     return;
   }
   for (uint32_t j = 0; j < len; ++j) {
-    uint32_t x = L.vocc_tmp[lo + j], r = 0;
+    const uint32_t x = L.vocc_tmp[lo + j];
+    uint32_t r = 0;
     for (uint32_t k = 0; k < len; ++k) r += L.vocc_tmp[lo + k] < x;
-    L.vocc[lo + r] = x;
-    if (r == 0) L.first[v] = x;
+    put(lo + r, x);
   }
 }
 
@@ -254,6 +257,7 @@ __device__ inline void f_sort_long(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL 
           bits &= bits - 1;
           uint32_t x = wb + w * 32 + b;
           if (pos == lo) L.first[v] = x;
+          L.ent_v[pos] = v;
           L.vocc[pos++] = x;
         }
       }
@@ -274,56 +278,91 @@ __global__ __launch_bounds__(256) void k_sort(MIRS) {
 // ---- 2. block summaries ---------------------------------------------------------------
 // def[b]: vregs written in b.  use[b]: vregs whose first mention in b reads them
 // (an instruction reads before it writes).
-__global__ void k_summary(MIRS) {
+// Each workgroup takes a slice of the sorted entries, whose vregs span a narrow range of
+// bitset words.  The bits are collected in an LDS table [block][word of the range] and each
+// non-zero word goes to memory once; when the table would not fit, runs of equal
+// (block, word) are combined by shuffles and every run issues its own atomics.
+constexpr uint32_t kSumSlice = 4096, kSumThreads = 1024;
+constexpr uint32_t kSumWords = kSumSlice / 32 + 1;   // most words a slice can touch
+
+__global__ __launch_bounds__(kSumThreads) void k_summary(MIRS, const uint32_t lds_words) {
   const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
   DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
-  uint32_t e = blockIdx.x * blockDim.x + threadIdx.x;
-  uint32_t b = kNone, w = 0, dbits = 0, ubits = 0, v = kNone, i = kNone, fl = 0;
+  extern __shared__ uint32_t sm[];
+  const uint32_t s0 = blockIdx.x * kSumSlice;
+  if (s0 >= m.O) return;
+  const uint32_t s1 = min(m.O, s0 + kSumSlice);
   const int lane = threadIdx.x & 63;
-  if (e < m.O) {
-    // also records instruction and flags of each sorted entry for the kernels that follow
-    const uint64_t rec = m.occ_rec[L.vocc[e]];
-    v = (uint32_t)rec;
-    const uint32_t ifl = (uint32_t)(rec >> 32);
-    L.ent_instr[e] = ifl;
-    i = ifl >> 2;
-    fl = ifl & 3u;
-    b = m.instr_blk[i];
-    w = v >> 5;
-    if (fl & VL_OCC_DEF) dbits = 1u << (v & 31);
+  // (vregs that are never mentioned take no entries but widen the range: a slice whose
+  // table would not fit in the LDS given takes the other path)
+  const uint32_t w_lo = L.ent_v[s0] >> 5, nw = (L.ent_v[s1 - 1] >> 5) - w_lo + 1;
+  const bool lds = (size_t)2 * m.B * nw <= lds_words;
+  if (lds) {
+    for (uint32_t x = threadIdx.x; x < 2 * m.B * nw; x += kSumThreads) sm[x] = 0;
+    __syncthreads();
   }
-  // Is this mention group the first of its vreg in the block?  The nearest earlier entry
-  // with another instruction decides; it usually sits a lane or two below.
-  bool decided = !(fl & VL_OCC_USE), first_in_block = false;
-  for (int d = 1; d <= 3; ++d) {
-    const uint32_t pv = __shfl_up(v, d, 64), pi = __shfl_up(i, d, 64), pb = __shfl_up(b, d, 64);
-    if (!decided && lane >= d) {
-      if (pv != v) { first_in_block = true; decided = true; }
-      else if (pi != i) { first_in_block = pb != b; decided = true; }
+  uint32_t *def_l = sm, *use_l = sm + m.B * nw;
+  for (uint32_t e0 = s0; e0 < s1; e0 += kSumThreads) {
+    const uint32_t e = e0 + threadIdx.x;
+    uint32_t b = kNone, w = 0, dbits = 0, ubits = 0, v = kNone, i = kNone, fl = 0;
+    if (e < s1) {
+      // also records instruction and flags of each sorted entry for the kernels that follow
+      const uint64_t rec = m.occ_rec[L.vocc[e]];
+      v = (uint32_t)rec;
+      const uint32_t ifl = (uint32_t)(rec >> 32);
+      L.ent_instr[e] = ifl;
+      i = ifl >> 2;
+      fl = ifl & 3u;
+      b = m.instr_blk[i];
+      w = v >> 5;
+      if (fl & VL_OCC_DEF) dbits = 1u << (v & 31);
+    }
+    // Is this mention group the first of its vreg in the block?  The nearest earlier entry
+    // with another instruction decides; it usually sits a lane or two below.
+    bool decided = !(fl & VL_OCC_USE), first_in_block = false;
+    for (int d = 1; d <= 3; ++d) {
+      const uint32_t pv = __shfl_up(v, d, 64), pi = __shfl_up(i, d, 64), pb = __shfl_up(b, d, 64);
+      if (!decided && lane >= d) {
+        if (pv != v) { first_in_block = true; decided = true; }
+        else if (pi != i) { first_in_block = pb != b; decided = true; }
+      }
+    }
+    if (!decided) {   // the group reaches below this wavefront's first lane, or is long: look it up
+      const uint32_t lo = L.vcnt[v];
+      uint32_t gs = e;
+      while (gs > lo && (uint32_t)(m.occ_rec[L.vocc[gs - 1]] >> 34) == i) --gs;
+      first_in_block = gs == lo || m.instr_blk[(uint32_t)(m.occ_rec[L.vocc[gs - 1]] >> 34)] != b;
+    }
+    if ((fl & VL_OCC_USE) && first_in_block) ubits = 1u << (v & 31);
+    if (lds) {
+      if (dbits) atomicOr(&def_l[b * nw + (w - w_lo)], dbits);
+      if (ubits) atomicOr(&use_l[b * nw + (w - w_lo)], ubits);
+      continue;
+    }
+    // entries are sorted by vreg, then instruction: neighbours in a wavefront mostly hit
+    // the same word of the same block.  OR them together along runs of equal (block, word)
+    // and let the last lane of each run issue the atomics.
+    for (int d = 1; d < 64; d <<= 1) {
+      const uint32_t pb = __shfl_up(b, d, 64), pw = __shfl_up(w, d, 64);
+      const uint32_t pd = __shfl_up(dbits, d, 64), pu = __shfl_up(ubits, d, 64);
+      // a run of equal keys is contiguous, so equality with the lane d below means the
+      // whole span in between belongs to the run
+      if (lane >= d && pb == b && pw == w) { dbits |= pd; ubits |= pu; }
+    }
+    const uint32_t nb = __shfl_down(b, 1, 64), nxw = __shfl_down(w, 1, 64);
+    const bool last = lane == 63 || nb != b || nxw != w;
+    if (b != kNone && last) {
+      if (dbits) atomicOr(&L.def[(size_t)b * m.W + w], dbits);
+      if (ubits) atomicOr(&L.use[(size_t)b * m.W + w], ubits);
     }
   }
-  if (!decided) {   // the group reaches below this wavefront's first lane, or is long: look it up
-    const uint32_t lo = L.vcnt[v];
-    uint32_t gs = e;
-    while (gs > lo && (uint32_t)(m.occ_rec[L.vocc[gs - 1]] >> 34) == i) --gs;
-    first_in_block = gs == lo || m.instr_blk[(uint32_t)(m.occ_rec[L.vocc[gs - 1]] >> 34)] != b;
-  }
-  if ((fl & VL_OCC_USE) && first_in_block) ubits = 1u << (v & 31);
-  // entries are sorted by vreg, then instruction: neighbours in a wavefront mostly hit
-  // the same word of the same block.  OR them together along runs of equal (block, word)
-  // and let the last lane of each run issue the atomics.
-  for (int d = 1; d < 64; d <<= 1) {
-    const uint32_t pb = __shfl_up(b, d, 64), pw = __shfl_up(w, d, 64);
-    const uint32_t pd = __shfl_up(dbits, d, 64), pu = __shfl_up(ubits, d, 64);
-    // a run of equal keys is contiguous, so equality with the lane d below means the
-    // whole span in between belongs to the run
-    if (lane >= d && pb == b && pw == w) { dbits |= pd; ubits |= pu; }
-  }
-  const uint32_t nb = __shfl_down(b, 1, 64), nw = __shfl_down(w, 1, 64);
-  const bool last = lane == 63 || nb != b || nw != w;
-  if (b != kNone && last) {
-    if (dbits) atomicOr(&L.def[(size_t)b * m.W + w], dbits);
-    if (ubits) atomicOr(&L.use[(size_t)b * m.W + w], ubits);
+  if (!lds) return;
+  __syncthreads();
+  // the first and the last word of the range may be shared with the neighbouring slices
+  for (uint32_t x = threadIdx.x; x < m.B * nw; x += kSumThreads) {
+    const uint32_t blk = x / nw, w = w_lo + x % nw;
+    if (def_l[x]) atomicOr(&L.def[(size_t)blk * m.W + w], def_l[x]);
+    if (use_l[x]) atomicOr(&L.use[(size_t)blk * m.W + w], use_l[x]);
   }
 }
 
@@ -407,29 +446,49 @@ constexpr uint8_t kStartI = 1, kStartI1 = 2, kEndI = 4, kEndI1 = 8, kEndN = 16, 
 // For the mentions of v at instruction i (its "group"): v is live after i iff the next
 // mention of v in the same block reads it, or, with no later mention in the block, v is
 // in the block's live-out.  P(i) contains v iff it is live after i or written at i.
-__global__ void k_events(MIRS) {
+constexpr uint32_t kEvtThreads = 256, kEvtHalo = 16, kEvtWindow = kEvtThreads + 2 * kEvtHalo;
+
+__global__ __launch_bounds__(kEvtThreads) void k_events(MIRS) {
   const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
   DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
-  uint32_t e = blockIdx.x * blockDim.x + threadIdx.x;
+  // The neighbours of an entry in the sorted order (its own mention group, the groups before
+  // and after it) are looked at many times: the workgroup's stretch of entries plus a halo
+  // on both sides is staged in LDS once, and only what lies beyond the halo is read from
+  // memory.
+  __shared__ uint32_t s_ifl[kEvtWindow], s_occ[kEvtWindow], s_v[kEvtWindow];
+  const uint32_t base = blockIdx.x * kEvtThreads;
+  if (base >= m.O) return;
+  const uint32_t win_lo = base - kEvtHalo;   // may wrap below zero: window indices are taken modulo 2^32
+  for (uint32_t r = threadIdx.x; r < kEvtWindow; r += kEvtThreads) {
+    const uint32_t x = win_lo + r;
+    const bool in = x < m.O;   // false for the wrapped indices too
+    s_ifl[r] = in ? L.ent_instr[x] : 0u;
+    s_occ[r] = in ? L.vocc[x] : 0u;
+    s_v[r] = in ? L.ent_v[x] : kNone;
+  }
+  __syncthreads();
+  const uint32_t e = base + threadIdx.x;
   if (e >= m.O) return;
-  const uint32_t o = L.vocc[e], v = m.occ_vreg[o];
+  auto ent = [&](uint32_t x) { const uint32_t r = x - win_lo; return r < kEvtWindow ? s_ifl[r] : L.ent_instr[x]; };
+  auto occ_at = [&](uint32_t x) { const uint32_t r = x - win_lo; return r < kEvtWindow ? s_occ[r] : L.vocc[x]; };
+  const uint32_t o = s_occ[threadIdx.x + kEvtHalo], v = s_v[threadIdx.x + kEvtHalo];
   const uint32_t lo = L.vcnt[v], hi = L.vcnt[v + 1];
-  const uint32_t ifl = L.ent_instr[e], i = ifl >> 2, b = m.instr_blk[i];
+  const uint32_t ifl = s_ifl[threadIdx.x + kEvtHalo], i = ifl >> 2, b = m.instr_blk[i];
   uint32_t gs = e, ge = e + 1;
-  while (gs > lo && (L.ent_instr[gs - 1] >> 2) == i) --gs;
-  while (ge < hi && (L.ent_instr[ge] >> 2) == i) ++ge;
+  while (gs > lo && (ent(gs - 1) >> 2) == i) --gs;
+  while (ge < hi && (ent(ge) >> 2) == i) ++ge;
   bool has_use = false, has_def = false;
   uint32_t first_use = kNone, first_def = kNone;
   for (uint32_t x = gs; x < ge; ++x) {
-    const uint32_t f = x == e ? ifl : L.ent_instr[x];
+    const uint32_t f = x == e ? ifl : ent(x);
     if (f & VL_OCC_USE) { has_use = true; if (first_use == kNone) first_use = x; }
     if (f & VL_OCC_DEF) { has_def = true; if (first_def == kNone) first_def = x; }
   }
   bool la;
-  const uint32_t nxt = ge < hi ? L.ent_instr[ge] : 0u;
+  const uint32_t nxt = ge < hi ? ent(ge) : 0u;
   if (ge < hi && m.instr_blk[nxt >> 2] == b) {
     la = (nxt & VL_OCC_USE) != 0;
-    for (uint32_t x = ge + 1; x < hi && (L.ent_instr[x] >> 2) == (nxt >> 2); ++x) la |= (L.ent_instr[x] & VL_OCC_USE) != 0;
+    for (uint32_t x = ge + 1; x < hi && (ent(x) >> 2) == (nxt >> 2); ++x) la |= (ent(x) & VL_OCC_USE) != 0;
   } else {
     la = bit_get(L.live_out + (size_t)b * m.W, v);
   }
@@ -443,12 +502,12 @@ __global__ void k_events(MIRS) {
   }
   if (e == lo) role |= kRoleFirst;
   L.occ_role[o] = role | (kill ? kRoleKill : 0);
-  const uint32_t prev = e > lo ? L.vocc[e - 1] : kNone;
+  const uint32_t prev = e > lo ? occ_at(e - 1) : kNone;
   if (prev != kNone && o - prev >= 0xFFFFu) L.prev_occ[o] = prev;
-  // the occurrence's check record; its events are counted into its instruction's item further down
+  // the occurrence's check record (its events are counted per instruction by a later pass over the roles)
   {
     // when an occurrence is checked the ring ends with that occurrence's chunk
-    const uint32_t next = e + 1 < hi ? L.vocc[e + 1] : o;
+    const uint32_t next = e + 1 < hi ? occ_at(e + 1) : o;
     const bool keep = o + kWalkReach < (next / kWalkChunk + 1u) * kWalkChunk && next - o <= kKeepMaxGap;
     const uint32_t delta = prev == kNone ? 0u : min(o - prev, 0xFFFFu);
     const bool near = prev != kNone && delta != 0xFFFFu && prev + kWalkReach >= (o / kWalkChunk + 1u) * kWalkChunk;
@@ -466,8 +525,6 @@ __global__ void k_events(MIRS) {
     r.w = simple ? min(F - width, 0xFFFFu) * 0x10001u : 0xFFFFFFFFu;
     L.chk[o] = r;
   }
-  const uint32_t n_evt = __popc(role & (kRolePreKill | kRoleTestSet | kRolePostKill));
-  if (n_evt) atomicAdd(&L.item_off[i + b + 1], n_evt);
   L.ent_info[e] = (uint8_t)((la ? kEntLiveAfter : 0) | (has_use ? kEntHasUse : 0) | (has_def ? kEntHasDef : 0) |
                             (e == gs ? kEntGroupStart : 0));
 
@@ -478,9 +535,9 @@ __global__ void k_events(MIRS) {
   if (e != gs) { L.ent_seg[e] = 0; L.ent_sf[e] = 0; return; }
   bool cur;   // was v occupied just before this stretch?
   if (i == 0) cur = false;
-  else if (gs > lo && (L.ent_instr[gs - 1] >> 2) == i - 1) {
+  else if (gs > lo && (ent(gs - 1) >> 2) == i - 1) {
     bool prev_def = false;
-    for (uint32_t x = gs; x-- > lo && (L.ent_instr[x] >> 2) == i - 1;) prev_def |= (L.ent_instr[x] & VL_OCC_DEF) != 0;
+    for (uint32_t x = gs; x-- > lo && (ent(x) >> 2) == i - 1;) prev_def |= (ent(x) & VL_OCC_DEF) != 0;
     const uint32_t pb = m.instr_blk[i - 1];
     // live after i - 1: this group is the next mention; in another block the block's live-out decides
     const bool prev_la = pb == b ? has_use : bit_get(L.live_out + (size_t)pb * m.W, v);
@@ -499,7 +556,7 @@ __global__ void k_events(MIRS) {
     cur = member;
   };
   span(i, i + 1, has_def || la);
-  const uint32_t i2 = ge < hi ? L.ent_instr[ge] >> 2 : m.N;
+  const uint32_t i2 = ge < hi ? ent(ge) >> 2 : m.N;
   const uint32_t b2 = ge < hi ? m.instr_blk[i2] : m.B;
   if (b2 == b) {
     span(i + 1, i2, la);
@@ -512,7 +569,7 @@ __global__ void k_events(MIRS) {
     if (xe < b2) span(m.blk_start[xe], m.blk_start[xe + 1], false);
     if (ge < hi) {
       bool next_use = false;
-      for (uint32_t x = ge; x < hi && (L.ent_instr[x] >> 2) == i2; ++x) next_use |= (L.ent_instr[x] & VL_OCC_USE) != 0;
+      for (uint32_t x = ge; x < hi && (ent(x) >> 2) == i2; ++x) next_use |= (ent(x) & VL_OCC_USE) != 0;
       span(m.blk_start[b2], i2, next_use);
     }
   }
@@ -618,6 +675,18 @@ __device__ inline void f_plan_fill(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL 
     if (L.occ_role[o] & kRolePostKill) put(o, false, kEvtPost);
 }
 
+// number of events of each instruction: the roles of its operands (the counterpart of the
+// filling pass above)
+__device__ inline void f_item_count(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L, const uint32_t bx, const uint32_t tx,
+                                    const uint32_t bdim) {
+  const uint32_t i = bx * bdim + tx;
+  if (i >= m.N) return;
+  uint32_t n_evt = 0;
+  for (uint32_t o = m.occ_off[i]; o < m.occ_off[i + 1]; ++o)
+    n_evt += __popc(L.occ_role[o] & (kRolePreKill | kRoleTestSet | kRolePostKill));
+  L.item_off[item_of_instr(m, i)] = n_evt;
+}
+
 // evt_cut[c] = index of the first event of the first item whose operands end in chunk c or
 // later (an item's events may be replayed once occurrences [0, 64 (c + 1)) are staged).
 __device__ inline void f_evt_cut(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L, const uint32_t bx, const uint32_t tx,
@@ -671,7 +740,7 @@ __device__ inline void f_seg_fill(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &
     return;
   }
   const uint8_t info = L.ent_info[e];
-  const uint32_t v = m.occ_vreg[L.vocc[e]];
+  const uint32_t v = L.ent_v[e];
   const uint32_t hi = L.vcnt[v + 1], b = m.instr_blk[i];
   bool cur = (sf & kOpenBefore) != 0;
   auto span = [&](uint32_t s, uint32_t t, bool member) {
@@ -861,7 +930,8 @@ __global__ __launch_bounds__(256) void k_stage_count(MIRS, StageGrid g) {
   DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
   const uint32_t bx = blockIdx.x, tx = threadIdx.x;
   if (bx < g.a) f_tile_delta(m, L, bx, tx, 256);
-  else f_boundary<false>(m, L, (bx - g.a) * 4 + (tx >> 6), tx & 63u, 64);
+  else if (bx < g.a + g.b) f_boundary<false>(m, L, (bx - g.a) * 4 + (tx >> 6), tx & 63u, 64);
+  else f_item_count(m, L, bx - g.a - g.b, tx, 256);
 }
 
 __global__ __launch_bounds__(1024) void k_stage_scan(MIRS, StageGrid g) {
@@ -1034,7 +1104,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
 
   // ---- arena 1 layout: [zeroed zone | counters | rest | device tables] ----
   std::vector<DevLive> h(n);
-  struct Off1 { size_t last_live, vcnt, vcur, use, def, in, seed_off, seed_cur, out, tmp, vocc, ent_instr, ent_info, first, prev,
+  struct Off1 { size_t last_live, vcnt, vcur, use, def, in, seed_off, seed_cur, out, tmp, vocc, ent_instr, ent_v, ent_info, first, prev,
                 role, kill, item, seg_off, hull, queue, bitmap, ent_seg, ent_sf, chk, evt_cut, tile_live; };
   std::vector<Off1> off(n);
   Bump bump;
@@ -1061,6 +1131,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     const size_t O1 = std::max(1u, m.O), bw = (size_t)m.B * std::max(1u, m.W) * 4;
     off[k].out = bump.take(bw);
     off[k].tmp = bump.take(O1 * 4); off[k].vocc = bump.take(O1 * 4); off[k].ent_instr = bump.take(O1 * 4);
+    off[k].ent_v = bump.take(O1 * 4);
     off[k].ent_info = bump.take(O1); off[k].first = bump.take((size_t)(m.V + 1) * 4); off[k].prev = bump.take(O1 * 4);
     off[k].role = bump.take(O1); off[k].kill = bump.take(O1);
     off[k].seg_off = bump.take((size_t)(m.V + 1) * 4); off[k].hull = bump.take((size_t)(m.V + 1) * 8);
@@ -1089,7 +1160,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     L.use = (uint32_t VL_GLOBAL *)(a1 + off[k].use); L.def = (uint32_t VL_GLOBAL *)(a1 + off[k].def);
     L.live_in = (uint32_t VL_GLOBAL *)(a1 + off[k].in); L.live_out = (uint32_t VL_GLOBAL *)(a1 + off[k].out);
     L.seed_off = (uint32_t VL_GLOBAL *)(a1 + off[k].seed_off); L.seed_cur = (uint32_t VL_GLOBAL *)(a1 + off[k].seed_cur);
-    L.vocc_tmp = (uint32_t VL_GLOBAL *)(a1 + off[k].tmp); L.vocc = (uint32_t VL_GLOBAL *)(a1 + off[k].vocc);
+    L.vocc_tmp = (uint32_t VL_GLOBAL *)(a1 + off[k].tmp); L.ent_v = (uint32_t VL_GLOBAL *)(a1 + off[k].ent_v); L.vocc = (uint32_t VL_GLOBAL *)(a1 + off[k].vocc);
     L.ent_instr = (uint32_t VL_GLOBAL *)(a1 + off[k].ent_instr); L.ent_info = (uint8_t VL_GLOBAL *)(a1 + off[k].ent_info);
     L.first = (uint32_t VL_GLOBAL *)(a1 + off[k].first); L.prev_occ = (uint32_t VL_GLOBAL *)(a1 + off[k].prev);
     L.occ_role = (uint8_t VL_GLOBAL *)(a1 + off[k].role); L.occ_kill = (uint8_t VL_GLOBAL *)(a1 + off[k].kill);
@@ -1188,15 +1259,18 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
   if (hist_lds) k_place<true><<<slices, 1024, (size_t)maxV * 8, stream>>>(dm, dl);
   else k_place<false><<<slices, 1024, 0, stream>>>(dm, dl);
   k_sort<<<dim3(kLongBlocks + (maxV + 255) / 256, n), 256, 0, stream>>>(dm, dl);
-  k_summary<<<grid1(maxO, TB, n), TB, 0, stream>>>(dm, dl);
+  {
+    const size_t lds = std::min<size_t>((size_t)maxB * std::min(maxW, kSumWords) * 8, 48 * 1024);
+    k_summary<<<grid1(maxO, kSumSlice, n), kSumThreads, lds, stream>>>(dm, dl, (uint32_t)(lds / 4));
+  }
   {
     const size_t lds = (size_t)maxB * 64 * 3 * 4;
     if (lds <= 64 * 1024) k_fixpoint<true><<<grid1(maxW, 64, n), 64, lds, stream>>>(dm, dl);
     else k_fixpoint<false><<<grid1(maxW, 64, n), 64, 0, stream>>>(dm, dl);
   }
-  k_events<<<grid1(maxO, TB, n), TB, 0, stream>>>(dm, dl);
+  k_events<<<grid1(maxO, kEvtThreads, n), kEvtThreads, 0, stream>>>(dm, dl);
   auto blocks = [](uint32_t items, uint32_t per) { return std::max(1u, (items + per - 1) / per); };
-  const StageGrid g_count = {maxT, blocks(maxB, 4), 0};
+  const StageGrid g_count = {maxT, blocks(maxB, 4), blocks(maxN, TB)};
   const StageGrid g_scan = {1, 1, blocks(maxW, 1024)};
   const StageGrid g_off = {blocks(maxT, 4), blocks(maxO / 64 + 2, TB), blocks(maxV + 1, TB)};
   k_stage_count<<<dim3(g_count.a + g_count.b + g_count.c, n), 256, (size_t)maxW * 4, stream>>>(dm, dl, g_count);
