@@ -103,3 +103,17 @@ def test_mixed_shape_programs_meet_the_input_contract():
             worst = max(worst, o - last[v])
         last[v] = o
     assert worst > 65535
+
+
+def test_many_block_programs_meet_the_input_contract():
+    from vlgen.mixed import many_blocks_mir
+    for seed in range(3):
+        m = many_blocks_mir(seed, n_blocks=60, gap=5)
+        an = vlo.analyze(m, interference=False)
+        assert an.contract == 0, seed
+        assert not an.live_in[0].any()
+        assert m.n_block == 60
+        # extra edges exist, some of them backwards, and some vreg numbers are never mentioned
+        succ = [list(m.succ[m.succ_off[b]:m.succ_off[b + 1]]) for b in range(m.n_block)]
+        assert any(len(s) == 2 for s in succ) and any(t <= b for b, s in enumerate(succ) for t in s)
+        assert (np.bincount(m.occ_vreg, minlength=m.n_vreg) == 0).sum() >= 60 * 5

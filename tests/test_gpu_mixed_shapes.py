@@ -66,6 +66,7 @@ def disturbed_rows(m, an, seed, K):
     rng = np.random.default_rng(seed)
     rows = np.zeros((K, m.n_occ), np.uint16)
     counts = np.bincount(m.occ_vreg, minlength=m.n_vreg)
+    mentioned = np.nonzero(counts > 0)[0]
     for k in range(K):
         table = coloured_table(m, an, rng)
         row = table[m.occ_vreg].astype(np.int64)
@@ -75,19 +76,19 @@ def disturbed_rows(m, an, seed, K):
             occ = np.nonzero(m.occ_vreg == v)[0]
             row[occ[int(rng.integers(1, len(occ)))]] += 1
         elif kind == 2:    # the last occurrence of a value differs (longest link)
-            v = int(rng.integers(0, m.n_vreg))
+            v = int(rng.choice(mentioned))
             occ = np.nonzero(m.occ_vreg == v)[0]
             row[occ[-1]] ^= 1
         elif kind == 3:    # a whole value moved onto its neighbour's register
-            v = int(rng.integers(0, m.n_vreg))
+            v = int(rng.choice(mentioned))
             row[m.occ_vreg == v] = (table[v] + int(m.vreg_width[v]) - 1) % int(m.class_size[m.vreg_class[v]])
         elif kind == 4:    # values outside any file
-            v = int(rng.integers(0, m.n_vreg))
+            v = int(rng.choice(mentioned))
             row[m.occ_vreg == v] = int(rng.choice([511, 512, 600, 4095, 65535]))
         elif kind == 5:    # one occurrence outside any file
             row[int(rng.integers(0, m.n_occ))] = int(rng.choice([513, 1023, 65535]))
         elif kind == 6:    # two values swapped
-            a, b = rng.integers(0, m.n_vreg, 2)
+            a, b = rng.choice(mentioned, 2)
             row[m.occ_vreg == a], row[m.occ_vreg == b] = table[b], table[a]
         rows[k] = row.astype(np.uint16)
     return rows
@@ -129,3 +130,13 @@ def test_gap_beyond_the_distance_field():
     m = mixed_mir(0xC001, n_instr=700, stretch=23000)
     assert m.n_occ > 70000
     run_case(m, K=16, seed=21, tile_lens=[0])
+
+
+def test_many_blocks_times_many_words():
+    """150 blocks and over 200 bitset words, with vreg numbers that are never mentioned: the
+    block summaries of most slices of the sorted entries do not fit the on-chip table and
+    take the other path, the last slice fits."""
+    from vlgen.mixed import many_blocks_mir
+    m = many_blocks_mir(7, gap=24)
+    assert m.n_block == 150 and (m.n_vreg + 31) // 32 > 200 and m.n_occ > 3 * 4096
+    run_case(m, K=24, seed=31, tile_lens=[0, 100])

@@ -98,3 +98,47 @@ def mixed_mir(seed: int, n_instr: int = 2500, n_global: int = 24, reserved: bool
             for r in rng.integers(0, F, 3):
                 res[c, int(r) >> 5] |= np.uint32(1 << (int(r) & 31))
     return Mir.build(blocks, succ, V, (40, 300, 512), vclass, width, align, res, name=f"mixed{seed}")
+
+
+def many_blocks_mir(seed: int, n_blocks: int = 150, per: int = 40, n_global: int = 12, gap: int = 8) -> Mir:
+    """A long chain of small blocks with extra forward and backward edges: many
+    blocks times many bitset words.  Each block writes its own locals before it
+    reads them and reads the globals (written in the entry block); `gap` vreg
+    numbers after each block's locals are never mentioned at all."""
+    rng = np.random.default_rng(seed)
+    n_local = per // 2
+    stride = n_local + gap
+    V = n_global + n_blocks * stride
+    vclass, width, align = _attrs(rng, V)
+    width[:] = np.minimum(width, 4)
+    align[:] = np.where(align > width, 1, align)
+    width[:n_global] = 1
+    align[:n_global] = 1
+    succ, blocks = [], []
+    for b in range(n_blocks):
+        s = [b + 1] if b + 1 < n_blocks else []
+        if s and rng.random() < 0.3:
+            t = int(rng.integers(1, n_blocks))
+            if t not in s:
+                s.append(t)
+        succ.append(s)
+        blk = []
+        lo = n_global + b * stride
+        born = []
+        if b == 0:
+            for g in range(0, n_global, 3):
+                blk.append((list(range(g, min(n_global, g + 3))), []))
+        for _ in range(per):
+            uses = []
+            for _ in range(int(rng.choice([1, 2, 2, 3]))):
+                if born and rng.random() < 0.85:
+                    uses.append(born[-min(len(born), 1 + int(rng.geometric(0.3)))])
+                else:
+                    uses.append(int(rng.integers(0, n_global)))
+            defs = []
+            if len(born) < n_local and rng.random() < 0.7:
+                defs.append(lo + len(born))
+            blk.append((defs, uses))
+            born.extend(defs)
+        blocks.append(blk)
+    return Mir.build(blocks, succ, V, (40, 300, 512), vclass, width, align, None, name=f"chain{seed}")
