@@ -57,8 +57,8 @@ __host__ __device__ inline uint64_t entry_pack(uint32_t x, uint32_t y) { return 
 // "chk": one 16-byte record per occurrence, in occurrence order, everything a consistency /
 //   realizability check needs that does not depend on the candidate:
 //   x: flags (kPlanChk or kPlanFirst, kPlanKeep, kChkNear, kChkGeneric)
-//      | ring offset of the occurrence << 8 | ring offset of the previous occurrence of the
-//      same vreg << 20, both in 8-byte units: (index % kWalkRing) * kWalkRingStride / 4
+//      | ring slot of the occurrence << 8 | ring slot of the previous occurrence of the
+//      same vreg << 20 (slot = index % kWalkRing; the verifier scales it by its row pitch)
 //   y: distance to that previous occurrence (16 bits, saturated) | packed attributes << 16
 //   z: alignment - 1 in both halves (two candidates per 32-bit operation); 0 when nothing is to be tested
 //   w: the largest base that fits, in both halves; all ones when there is no limit
@@ -84,12 +84,11 @@ constexpr uint32_t kWalkChunk = 64, kWalkRing = 192;
 // While a chunk is processed the next one is being written over the oldest of the three,
 // so what may be read is the chunk itself and the one before it.
 constexpr uint32_t kWalkReach = 2 * kWalkChunk;
-constexpr uint32_t kWalkRingStride = 64 + 4;   // uint16 per ring slot: 64 candidate rows + padding (136 bytes)
 constexpr uint32_t kKeepMaxGap = 4096;   // longer gaps are not worth a slot
 
 // An occupancy event in the form the verifier's occupancy wavefront consumes it, four
 // scalar registers that need no further decoding:
-//   x  byte offset, inside the ring, of the slot of the occurrence that carries the register
+//   x  ring slot (index % kWalkRing) of the occurrence that carries the register
 //   y  the tuple's mask at bit 0 (width ones)
 //   z  byte offset of the first mask word of the vreg's class (class_word * 256)
 //   w  that occurrence (24 bits) | kEvtPost | kEvtSlow | kEvtTested

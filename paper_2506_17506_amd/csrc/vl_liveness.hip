@@ -516,10 +516,9 @@ __global__ __launch_bounds__(kEvtThreads) void k_events(MIRS) {
     const bool is_first = (role & kRoleFirst) != 0;
     const bool generic = is_first && ((align & (align - 1u)) != 0 || m.has_reserved || width > F);
     const bool simple = is_first && !generic;
-    constexpr uint32_t slot8 = kWalkRingStride / 4;
     u32x4 r;
     r.x = (is_first ? kPlanFirst : kPlanChk) | (keep ? kPlanKeep : 0u) | (near ? kChkNear : 0u) | (generic ? kChkGeneric : 0u) |
-          (((o % kWalkRing) * slot8) << 8) | ((((near ? prev : o) % kWalkRing) * slot8) << 20);
+          ((o % kWalkRing) << 8) | (((near ? prev : o) % kWalkRing) << 20);
     r.y = delta | (attr << 16);
     r.z = simple ? (align - 1u) * 0x10001u : 0u;
     r.w = simple ? min(F - width, 0xFFFFu) * 0x10001u : 0xFFFFFFFFu;
@@ -603,7 +602,7 @@ __device__ inline u32x4 event_record(const DevMir VL_GLOBAL &m, uint32_t o, uint
   const uint32_t width = attr_width(attr);
   const bool slow = !near || attr_straddle(attr) || width == 32;
   u32x4 r;
-  r.x = (o % kWalkRing) * (kWalkRingStride * 2u);
+  r.x = o % kWalkRing;
   r.y = width == 32 ? 0xFFFFFFFFu : ((1u << width) - 1u);
   r.z = (uint32_t)m.class_word[attr_class(attr)] * 256u;
   r.w = o | (slow ? kEvtSlow : 0u) | (tested ? kEvtTested : 0u);

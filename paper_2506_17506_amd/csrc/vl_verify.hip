@@ -30,10 +30,14 @@ using namespace vl;
 
 namespace {
 
-// Occurrences kept per candidate in LDS: three chunks.  With two register classes a
-// workgroup then needs about 31 KB, so five workgroups share a compute unit's 160 KB.
+// Occurrences kept per candidate in LDS: three chunks.  A ring slot holds one uint16 per
+// candidate row plus padding; its pitch is a compile-time parameter of the walk: 68 (136
+// bytes) for up to 64 rows, 52 (104 bytes) for up to 52 rows, e.g. the 50-row halves of 100
+// candidates.  With two register classes a workgroup then needs about 31 KB or 25 KB, and
+// five or six workgroups share a compute unit's 160 KB.  Both pitches are 2 modulo 8
+// dwords, which is what the bank assignment of the staging stores relies on.
 constexpr uint32_t kRing = kWalkRing;
-constexpr uint32_t kRingStride = kWalkRingStride;
+constexpr uint32_t kPitchWide = 68, kPitchNarrow = 52;
 #ifndef VL_CHECK_WAVES
 #define VL_CHECK_WAVES 3
 #endif
@@ -136,13 +140,16 @@ __device__ inline void load_chunk(Walk &w, uint32_t c0, uint32_t j) {
 }
 
 // writes the chunk held in registers into the ring as chunk [c0, c0 + 64)
+template <uint32_t kRingStride>
 __device__ inline void store_chunk(const Walk &w, uint32_t c0, uint32_t j) {
   const uint32_t c = c0 + (w.lane & 7u) * 8u;
 #pragma unroll
   for (int h = 0; h < kStagePasses; ++h) {
     const uint32_t q = j + kCheckWaves * h;
     if (q >= 8u) continue;
-    const uint32_t dst = w.ring16 + (c % kRing) * kRingStride + staged_row(w.lane, q);
+    const uint32_t r = staged_row(w.lane, q);
+    if (kRingStride < 64u && r >= kRingStride) continue;   // rows the narrow ring has no room for (none of them is in use)
+    const uint32_t dst = w.ring16 + (c % kRing) * kRingStride + r;
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       VL_LDS16[dst + (2 * t) * kRingStride] = (uint16_t)w.pre[h][t];
@@ -156,6 +163,7 @@ __device__ inline bool in_ring(const Walk &w, uint32_t o) {
 }
 
 // value of occurrence o (uniform) in this lane's row
+template <uint32_t kRingStride>
 __device__ inline uint32_t fetch(const Walk &w, uint32_t o) {
   if (in_ring(w, o)) return VL_LDS16[w.ring16 + (o % kRing) * kRingStride + w.row];
   return w.rows[(uint64_t)w.row * w.ld + o];
@@ -203,7 +211,8 @@ __device__ inline bool unrealizable(const DevMir VL_GLOBAL &m, uint32_t attr, ui
   return bad;
 }
 
-__global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(5))) void k_walk(const DevJob *__restrict__ jobs, uint32_t n_jobs) {
+template <uint32_t kRingStride>
+__global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(6))) void k_walk(const DevJob *__restrict__ jobs, uint32_t n_jobs) {
   const DevJob VL_GLOBAL &J = as_global(jobs)[find_job(jobs, n_jobs, blockIdx.x)];
   const DevMir VL_GLOBAL &m = *as_global(J.mir);
   const DevLive VL_GLOBAL &L = *as_global(J.live);
@@ -269,9 +278,11 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(5)
   const uint32_t my_ring = (w.ring16 + w.row) * 2u;   // byte offset of this lane's row in ring slot 0
   const uint32_t my_occ = w.lane * 4;                 // byte offset of this lane's column of mask words
   char *const lds_bytes = reinterpret_cast<char *>(vl_lds);
+  // (the ring slot of each record is turned into a byte offset here, once per lane)
   auto fetch_records = [&](uint32_t from, uint32_t to) __attribute__((always_inline)) {
     u32x4 r = 0;
     if (from + w.lane < to) r = g_plan[from + w.lane];
+    r.x *= kRingStride * 2u;
     return r;
   };
   // Replays a batch of up to 64 records held one per lane (lanes past the batch hold zero
@@ -288,7 +299,7 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(5)
         const uint32_t sw = __builtin_amdgcn_readlane(r.w, j), o = sw & 0xFFFFFFu;
         const bool slow = (sw & kEvtSlow) != 0;
         const uint32_t attr = slow ? g_chk[o].y >> 16 : 0u;
-        const uint32_t p = slow ? fetch(w, o) : *reinterpret_cast<const uint16_t *>(lds_bytes + my_ring + __builtin_amdgcn_readlane(r.x, j));
+        const uint32_t p = slow ? fetch<kRingStride>(w, o) : *reinterpret_cast<const uint16_t *>(lds_bytes + my_ring + __builtin_amdgcn_readlane(r.x, j));
         if (slow) {
           apply1(o, attr, (sw & kEvtTested) != 0, p);
         } else {
@@ -406,8 +417,9 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(5)
     // at one by one.
     typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
     const uint32_t amask2 = rec.z, limit2 = rec.w;
-    const uint32_t a_p = (w.ring16 >> 2) + ((rec.x >> 8) & 0xFFFu);          // in 8-byte units
-    const uint32_t a_q = near ? (w.ring16 >> 2) + (rec.x >> 20) : a_p;
+    constexpr uint32_t slot8 = kRingStride / 4;   // a ring slot in 8-byte units
+    const uint32_t a_p = (w.ring16 >> 2) + ((rec.x >> 8) & 0xFFFu) * slot8;          // in 8-byte units
+    const uint32_t a_q = near ? (w.ring16 >> 2) + (rec.x >> 20) * slot8 : a_p;
     const uint64_t *lds64 = reinterpret_cast<const uint64_t *>(vl_lds);
     auto wrong2 = [&](uint32_t pp, uint32_t qq) __attribute__((always_inline)) {
       const u16x2 mn = __builtin_elementwise_min(__builtin_bit_cast(u16x2, pp), __builtin_bit_cast(u16x2, limit2));
@@ -514,7 +526,7 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(5)
     const uint32_t j = role - 1;
     for (uint32_t c = c_first; c <= ca && c < c_end; ++c) {   // history chunk and the tile's first chunk
       load_chunk(w, c * kChunk, j);
-      store_chunk(w, c * kChunk, j);
+      store_chunk<kRingStride>(w, c * kChunk, j);
     }
     if (ca + 1 < c_end) load_chunk(w, (ca + 1) * kChunk, j);
     u32x4 chk_next = load_chk(ca);
@@ -522,7 +534,7 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(5)
     for (uint32_t c = ca; c != c_stop; ++c) {
       if (c < c_end) {
         if (c + 1 < c_end) {
-          store_chunk(w, (c + 1) * kChunk, j);
+          store_chunk<kRingStride>(w, (c + 1) * kChunk, j);
           if (c + 2 < c_end) load_chunk(w, (c + 2) * kChunk, j);
         }
         w.hi = (c + 1) * kChunk;
@@ -695,7 +707,7 @@ extern "C" int32_t vl_verify_time_next(void *start, void *stop) {
 namespace {
 struct Launch {
   DevJob *dev = nullptr;
-  uint32_t units = 0, maxK = 0, max_words = 0, max_w = 1;
+  uint32_t units = 0, maxK = 0, max_words = 0, max_w = 1, max_rows = 0;
 };
 
 // Validates the jobs, lays out the device job table and makes sure the device copy is
@@ -737,6 +749,7 @@ int32_t prepare_jobs(const vl_job *jobs, uint32_t n_jobs, hipStream_t stream, Sc
     d.fast = (((uintptr_t)u.cand & 15) == 0 && (u.ld & 7) == 0) ? 1u : 0u;
     out.units += d.n_units;
     out.maxK = std::max(out.maxK, u.K);
+    out.max_rows = std::max(out.max_rows, d.rows);
     out.max_words = std::max(out.max_words, u.mir->h.occ_words);
     out.max_w = std::max(out.max_w, u.mir->h.W);
   }
@@ -847,10 +860,12 @@ extern "C" int32_t vl_verify_multi(const vl_job *jobs, uint32_t n_jobs, vl_strea
   Launch L;
   const int32_t rc = prepare_jobs(jobs, n_jobs, stream, s, L);
   if (rc != VL_OK) return rc;
-  const size_t lds = (size_t)L.max_words * 64 * 4 + 64 * 4 + (size_t)kRing * kRingStride * 2;
+  const bool narrow = L.max_rows <= kPitchNarrow;   // every group of every job fits the narrow ring
+  const size_t lds = (size_t)L.max_words * 64 * 4 + 64 * 4 + (size_t)kRing * (narrow ? kPitchNarrow : kPitchWide) * 2;
   k_init<<<dim3((L.maxK + 255) / 256, n_jobs), 256, 0, stream>>>(L.dev);
   if (g_time_start) VL_HIP(hipEventRecord(g_time_start, stream));
-  k_walk<<<L.units, kWalkThreads, lds, stream>>>(L.dev, n_jobs);
+  if (narrow) k_walk<kPitchNarrow><<<L.units, kWalkThreads, lds, stream>>>(L.dev, n_jobs);
+  else k_walk<kPitchWide><<<L.units, kWalkThreads, lds, stream>>>(L.dev, n_jobs);
   if (g_time_stop) VL_HIP(hipEventRecord(g_time_stop, stream));
   g_time_start = g_time_stop = nullptr;
   k_finalize<<<dim3((L.maxK + 255) / 256, n_jobs), 256, 0, stream>>>(L.dev);
