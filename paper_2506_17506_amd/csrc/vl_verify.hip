@@ -312,23 +312,22 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(6)
       }
       return;
     }
-    uint32_t pc[G], pn[G] = {};
     auto ring_reads = [&](uint32_t g0, uint32_t (&p)[G]) __attribute__((always_inline)) {
 #pragma unroll
       for (int t = 0; t < G; ++t)
         p[t] = *reinterpret_cast<const uint16_t *>(lds_bytes + my_ring + __builtin_amdgcn_readlane(r.x, g0 + t));
     };
-    ring_reads(0, pc);
-    for (uint32_t g0 = 0; g0 < cnt; g0 += G) {
+    // one group: `cur` holds its registers, `nxt` receives the next group's
+    auto group_step = [&](uint32_t g0, uint32_t (&cur)[G], uint32_t (&nxt)[G]) __attribute__((always_inline)) {
       uint32_t old[G], msk[G];
 #pragma unroll
       for (int t = 0; t < G; ++t) {
-        msk[t] = (uint32_t)__builtin_amdgcn_readlane(r.y, g0 + t) << (pc[t] & 31u);
+        msk[t] = (uint32_t)__builtin_amdgcn_readlane(r.y, g0 + t) << (cur[t] & 31u);
         old[t] = __hip_atomic_fetch_xor(
-            reinterpret_cast<uint32_t *>(lds_bytes + ((((pc[t] >> 5) & 15u) << 8) + my_occ + __builtin_amdgcn_readlane(r.z, g0 + t))),
+            reinterpret_cast<uint32_t *>(lds_bytes + ((((cur[t] >> 5) & 15u) << 8) + my_occ + __builtin_amdgcn_readlane(r.z, g0 + t))),
             msk[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
       }
-      if (g0 + G < cnt) ring_reads(g0 + G, pn);
+      if (g0 + G < cnt) ring_reads(g0 + G, nxt);
       uint32_t any_hit = 0;
 #pragma unroll
       for (int t = 0; t < G; ++t) {
@@ -339,8 +338,12 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(6)
 #pragma unroll
         for (int t = 0; t < G; ++t) clash(old[t], __builtin_amdgcn_readlane(r.w, g0 + t) & 0xFFFFFFu);
       }
-#pragma unroll
-      for (int t = 0; t < G; ++t) pc[t] = pn[t];
+    };
+    uint32_t pa[G], pb[G] = {};
+    ring_reads(0, pa);
+    for (uint32_t g0 = 0; g0 < cnt; g0 += 2 * G) {   // two groups per turn: the register sets swap roles
+      group_step(g0, pa, pb);
+      if (g0 + G < cnt) group_step(g0 + G, pb, pa);
     }
   };
   // events [from, to); `first` holds the records [from, from + 64) fetched ahead
@@ -504,6 +507,9 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(6)
   asm volatile("v_mov_b32 %0, 0" : "=v"(lane_zero));
   auto clamp_cut = [&](uint32_t e) __attribute__((always_inline)) { return min(eb, max(ea, e)); };
   if (role == 0) {
+    // the occupancy wavefront has the longest chain of dependent steps per chunk: it goes
+    // first when it competes for issue with the check wavefronts of other workgroups
+    __builtin_amdgcn_s_setprio(3);
     uint32_t cut_lo = ea;
     uint32_t v_cut_next = g_evt_cut[min(ca + 1, n_chunk) + lane_zero];
     u32x4 rec_next = fetch_records(ea, eb);   // the first batch, in flight during the seeds
