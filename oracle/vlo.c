@@ -328,3 +328,36 @@ void vlo_loop(const vlo_summary *s, const uint32_t *K, uint32_t n, vlo_loop_stat
     for (int t = 0; t < 4; ++t) out->hist[t] += s[j].hist[t];
   }
 }
+
+/* ---- constrained decoding (Section 4.5, error analysis: masking occupied registers) ---- */
+void vlo_free_bases(const vlo_mir *m, const uint32_t *P, const uint16_t *cand, uint32_t q, uint32_t out[16]) {
+  const uint32_t W = words_per_row(m), V = m->n_vreg;
+  uint32_t *first = (uint32_t *)malloc(((size_t)V + 1) * 4);
+  vlo_first_occurrence(m, first);
+  const uint32_t v = m->occ_vreg[q];
+  uint32_t i = 0;
+  while (m->instr_occ_off[i + 1] <= q) ++i; /* the instruction of occurrence q */
+  const uint32_t cls = m->vreg_class[v], w = m->vreg_width[v], al = m->vreg_align[v], F = m->class_size[cls];
+  uint8_t blocked[512];
+  memset(blocked, 0, sizeof blocked);
+  if (m->class_reserved)
+    for (uint32_t r = 0; r < 512; ++r)
+      if ((m->class_reserved[cls * 16 + (r >> 5)] >> (r & 31)) & 1u) blocked[r] = 1;
+  const uint32_t *row = P + (size_t)i * W;
+  for (uint32_t b = 0; b < V; ++b) {
+    if (first[v] < q) break; /* a later mention of v: consistency alone decides */
+    if (b == v || !bit_get(row, b) || m->vreg_class[b] != cls || first[b] >= q) continue;
+    const uint32_t pb = cand[first[b]];
+    for (uint32_t r = pb; r < pb + m->vreg_width[b]; ++r)
+      if (r < 512) blocked[r] = 1;
+  }
+  for (int t = 0; t < 16; ++t) out[t] = 0;
+  for (uint32_t p = 0; p < 512; ++p) {
+    int ok = p % al == 0 && p + w <= F;
+    for (uint32_t r = p; ok && r < p + w; ++r)
+      if (r >= 512 || blocked[r]) ok = 0;
+    if (first[v] < q && p != cand[first[v]]) ok = 0;
+    if (ok) out[p >> 5] |= 1u << (p & 31);
+  }
+  free(first);
+}

@@ -129,6 +129,27 @@ void vlo_summarize(const vlo_result *res, uint32_t K, vlo_summary *out);
 typedef struct { uint32_t n_passed, max_tries; uint64_t sum_tries; uint64_t hist[4]; } vlo_loop_stats;
 void vlo_loop(const vlo_summary *s, const uint32_t *K, uint32_t n, vlo_loop_stats *out);
 
+/* Constrained decoding (Section 4.5, last sentence of the error analysis: mask
+ * out the registers that are occupied while the allocation is generated).  A
+ * decoder emits the candidate one occurrence after the other; when it reaches
+ * occurrence q, of vreg v at instruction i, the occurrences before q are
+ * fixed.  out[16] receives the 512-bit set of bases p that keep the three
+ * conditions of Section 3.4 intact against what is fixed:
+ *   Realizability  p is a multiple of v's alignment, p + width fits the file
+ *                  of v's class, no register of the tuple is reserved;
+ *   Consistency    if v has an earlier occurrence, only that occurrence's
+ *                  register remains (and nothing else is asked of it: what v
+ *                  may share was settled when v got its register);
+ *   Safety         otherwise (q is v's first occurrence) the tuple is disjoint
+ *                  from the tuple of every other vreg b of the class that is
+ *                  in P(i) and already has a register (its first occurrence
+ *                  lies before q), b's register being the one of its first
+ *                  occurrence.  A value that dies at i is not in P(i): its
+ *                  register may be given to a value written at i.
+ * P: the occupancy rows of vlo_occupancy.  Registers from 512 on are never
+ * offered. */
+void vlo_free_bases(const vlo_mir *m, const uint32_t *P, const uint16_t *cand, uint32_t q, uint32_t out[16]);
+
 #ifdef __cplusplus
 }
 #endif

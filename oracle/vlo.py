@@ -187,3 +187,15 @@ def loop_stats(summaries: np.ndarray, Ks) -> np.ndarray:
     out = np.zeros(1, LOOP_DTYPE)
     lib().vlo_loop(C.c_void_p(s.ctypes.data), C.c_void_p(K.ctypes.data), C.c_uint32(len(s)), C.c_void_p(out.ctypes.data))
     return out
+
+
+def free_bases(m, an: Analysis, row: np.ndarray, q: int) -> np.ndarray:
+    """Bases a decoder may still give occurrence q of `row` (whose occurrences before q
+    are fixed) without breaking consistency, realizability or safety against them
+    (Section 4.5, error analysis: masking occupied registers).  uint32 [16]."""
+    s, keep = _marshal(m)
+    row = np.ascontiguousarray(row, np.uint16)
+    P = np.ascontiguousarray(an.P)
+    out = np.zeros(16, np.uint32)
+    lib().vlo_free_bases(C.byref(s), _p(P), _p(row), C.c_uint32(q), _p(out))
+    return out

@@ -28,12 +28,13 @@ def _attrs(rng, V: int):
 
 
 def mixed_mir(seed: int, n_instr: int = 2500, n_global: int = 24, reserved: bool = False,
-              wide_instr: int = 4, stretch: int = 0) -> Mir:
+              wide_instr: int = 4, stretch: int = 0, redefine: bool = True) -> Mir:
     """n_instr instructions (about) in 7 blocks: entry, a loop of two blocks, a
     diamond, a second loop, exit.  `wide_instr` instructions carry 40-60
     operands.  `stretch` > 0 appends that many filler instructions before the
     exit block, which reads the globals once more (a gap of many operand slots
-    between two mentions of one value)."""
+    between two mentions of one value).  With redefine=False no value is written
+    twice (no redefinitions, no read-modify-write operands)."""
     rng = np.random.default_rng(seed)
     n_blocks = 7
     per = max(8, n_instr // n_blocks)
@@ -81,6 +82,8 @@ def mixed_mir(seed: int, n_instr: int = 2500, n_global: int = 24, reserved: bool
                     v = lo + len(born)
                     born.append(v)
                     defs.append(v)
+                elif not redefine:
+                    pass
                 elif n_before and r < 0.9:
                     defs.append(born[n_before - min(n_before, int(rng.integers(1, 40)))])        # redefinition
                 elif n_before:
