@@ -232,6 +232,23 @@ def main():
     summarize_us = (time.perf_counter() - t1) / 5 * 1e6
     loop = loop_dev.cpu().numpy().view(np.uint8).view(vl.LOOP_DTYPE)[0]
 
+    # constrained-decoding masks (not part of the timed step): one query per candidate, at the
+    # first mention of a vreg halfway through its kernel
+    mask_queries = []
+    for k, m, l, d in zip(w.kernels, mirs, lives, dev_rows):
+        _, firsts = np.unique(k.mir.occ_vreg, return_index=True)
+        q = int(firsts[np.argmin(np.abs(firsts.astype(np.int64) - k.mir.n_occ // 2))])
+        mask_queries += [(m, l, d[r], q) for r in range(d.shape[0])]
+    mask_queries = vl.make_mask_queries(mask_queries)
+    masks = torch.zeros((len(mask_queries), 16), dtype=torch.int32, device="cuda")
+    vl.vl_free_bases_multi(mask_queries, masks, stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(5):
+        vl.vl_free_bases_multi(mask_queries, masks, stream)
+    torch.cuda.synchronize()
+    mask_us = (time.perf_counter() - t1) / 5 * 1e6
+
     status = np.concatenate([o.cpu().numpy()[:, 0] for o in outs])
     for oo in keep[:max(args.streams, 1 if args.no_two_stream else 2) - 1]:   # every stream used gave the first stream's results
         assert all(bool((a == b).all()) for a, b in zip(oo, outs)), "results differ between streams"
@@ -257,6 +274,8 @@ def main():
         "status_histogram": np.bincount(status, minlength=4).tolist(),
         "regeneration_loop": {"kernels_passed": int(loop["n_passed"]), "avg_tries": float(loop["sum_tries"]) / len(mirs),
                               "max_tries": int(loop["max_tries"]), "summarize_us": summarize_us},
+        "decoding_mask": {"queries": len(mask_queries), "us_per_call": mask_us,
+                          "masks_per_s": len(mask_queries) / mask_us * 1e6},
         "roofline": {"bound": "hbm", "kernel": "k_walk", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic_from_profile(src),

@@ -174,6 +174,30 @@ typedef struct { uint32_t n_passed, max_tries; uint64_t sum_tries; uint64_t hist
 int32_t vl_summarize_multi(const vl_job *jobs, uint32_t n_jobs, vl_summary *summaries, vl_loop_stats *stats,
                            vl_stream stream);
 
+/* Constrained decoding (Section 4.5, last sentence of the error analysis: mask out the
+ * registers that are occupied while the allocation is generated).  A decoder emits a
+ * candidate one occurrence after the other; query j asks which bases it may give occurrence
+ * `occ` (of vreg v, at instruction i) of the row `cand`, whose occurrences before `occ` are
+ * fixed and the only ones read.  masks [device]: 16 words per query, bit p set iff
+ *   p is a multiple of v's alignment, p + width fits the file of v's class and no register
+ *   of the tuple is reserved (Section 3.4 Realizability), and
+ *   when v has an earlier occurrence: p is that occurrence's register (Consistency), else:
+ *   the tuple is disjoint from that of every other vreg of the class that is in P(i) and
+ *   whose first occurrence lies before `occ`, taken at its first occurrence's register
+ *   (Safety; a value that dies at i is not in P(i)).
+ * queries is [host]; cand and masks are [device].  Asynchronous on `stream`; the call waits
+ * on the host for the previous call's queries to have been consumed.
+ * Errors: VL_E_NULL, VL_E_ARG (handles of different programs), VL_E_SHAPE (n == 0, occ past
+ * the program's occurrences); nothing is launched on error. */
+typedef struct {
+  const vl_mir *mir;
+  const vl_live *live;
+  const uint16_t *cand;
+  uint32_t occ;
+  uint32_t reserved0; /* must be 0 */
+} vl_mask_query;
+int32_t vl_free_bases_multi(const vl_mask_query *queries, uint32_t n, uint32_t *masks, vl_stream stream);
+
 /* Measurement aid for callers that cannot allocate inside the timed region: the next
  * vl_verify_multi / vl_verify_batch call on this thread records the two hipEvent_t
  * (caller-owned, either may be NULL) on its stream immediately before and after the

@@ -42,6 +42,11 @@ class _View(C.Structure):
                 ("live_in", "live_out", "live_after", "occ_kill", "seg_off", "seg", "hull")]
 
 
+class _MaskQuery(C.Structure):
+    _fields_ = [("mir", C.c_void_p), ("live", C.c_void_p), ("cand", C.c_void_p), ("occ", C.c_uint32),
+                ("reserved0", C.c_uint32)]
+
+
 class _Job(C.Structure):
     _fields_ = [("mir", C.c_void_p), ("live", C.c_void_p), ("cand", C.c_void_p), ("K", C.c_uint32),
                 ("ld", C.c_uint64), ("out", C.c_void_p)]
@@ -79,6 +84,8 @@ def load():
         L.vl_verify_multi.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p]
         L.vl_summarize_multi.restype = C.c_int32
         L.vl_summarize_multi.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.vl_free_bases_multi.restype = C.c_int32
+        L.vl_free_bases_multi.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p]
         L.vl_verify_time_next.restype = C.c_int32
         L.vl_verify_time_next.argtypes = [C.c_void_p, C.c_void_p]
         L.vl_strerror.restype = C.c_char_p
@@ -210,6 +217,23 @@ def vl_summarize_multi(jobs, summaries, stats=None, stream=None) -> None:
                                    C.c_void_p(_dev_ptr(stats)) if stats is not None else None, _stream_ptr(stream))
     if rc != 0:
         raise VlError(rc, "vl_summarize_multi")
+
+
+def make_mask_queries(queries):
+    """queries: sequence of (mir, live, row, occ), row a device pointer or tensor holding one
+    candidate row -> ctypes array (reusable)."""
+    arr = (_MaskQuery * len(queries))()
+    for j, (mir, live, row, occ) in enumerate(queries):
+        arr[j].mir, arr[j].live, arr[j].cand, arr[j].occ, arr[j].reserved0 = mir.value, live.value, _dev_ptr(row), occ, 0
+    return arr
+
+
+def vl_free_bases_multi(queries, masks, stream=None) -> None:
+    """masks: device buffer of 16 uint32 per query."""
+    arr = queries if isinstance(queries, C.Array) else make_mask_queries(queries)
+    rc = load().vl_free_bases_multi(arr, len(arr), C.c_void_p(_dev_ptr(masks)), _stream_ptr(stream))
+    if rc != 0:
+        raise VlError(rc, "vl_free_bases_multi")
 
 
 def vl_verify_time_next(start_event, stop_event) -> None:

@@ -174,6 +174,31 @@ enum { kCtrLong = 0, kCtrNotStrict = 1, kCtrSweeps = 2, kCtrPlanLen = 3, kCtrSeg
 }  // namespace vl
 
 // host-side handles
+namespace vl {
+// P(i) = live_after(i) + defs(i) as a vreg bitset: the live-in list of i's tile, then every
+// event up to those of i, flips one bit each (in any order); the releases of values dead once
+// i has executed are left out, since such values still belong to P(i).  in_p: [W] words in
+// LDS, cleared by the caller (with a barrier in between); the caller also adds the barrier
+// after this call.
+__device__ inline void flip_members_of_p(const DevMir VL_GLOBAL &m, const DevLive VL_GLOBAL &L, const uint32_t i, uint32_t *in_p,
+                                         const uint32_t tid, const uint32_t n_threads) {
+  const uint32_t tile = i / L.tile_len;
+  auto flip_vreg = [&](uint32_t o) {
+    const uint32_t v = m.occ_vreg[o];
+    __hip_atomic_fetch_xor(&in_p[v >> 5], 1u << (v & 31), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  };
+  if (tile > 0)
+    for (uint32_t s = L.seed_off[tile] + tid; s < L.seed_off[tile + 1]; s += n_threads) flip_vreg(L.seeds[s].w & 0xFFFFFFu);
+  const uint32_t item = i + m.instr_blk[i] + 1;   // boundary items come before their block's instructions
+  const uint32_t e_own = L.item_off[item], e_end = L.item_off[item + 1];
+  for (uint32_t e = L.tile_range[2 * tile] + tid; e < e_end; e += n_threads) {
+    const uint32_t w = L.plan[e].w;
+    if (e >= e_own && (w & kEvtPost)) continue;
+    flip_vreg(w & 0xFFFFFFu);
+  }
+}
+}  // namespace vl
+
 struct vl_mir {
   vl::DevMir h;        // host mirror (device pointers inside)
   vl::DevMir *dev;     // device copy

@@ -107,9 +107,9 @@ struct Walk {
 // (8 occurrences); piece k of row r goes to lane (k, rr) of pass q with
 //   r = y + 2 rr + 16 ((k >> 2) ^ u) + 32 z,   q = y + 2 z + 4 u  (0..7),
 // the two halves of a 128-byte line (k < 4, k >= 4) belonging to rows 16 apart.  With this
-// assignment the 64 lanes of every LDS store below fall into 64 different banks (slot stride
-// 34 dwords: bank = 16 (k & 3) + 8 (row bit 4) + rr + const).  Check wavefront j takes the
-// passes j, j + 3, j + 6.
+// assignment the 64 lanes of every LDS store below fall into 64 different banks (slot pitch
+// 34 or 26 dwords, both 2 modulo 8: bank = 16 (k & 3) + 8 (row bit 4) + rr + const).  Check
+// wavefront j takes the passes j, j + 3, j + 6.
 __device__ inline uint32_t staged_row(uint32_t lane, uint32_t q) {
   const uint32_t k = lane & 7u, rr = lane >> 3;
   return (q & 1u) + 2u * rr + 16u * ((k >> 2) ^ (q >> 2)) + 32u * ((q >> 1) & 1u);
@@ -602,9 +602,7 @@ __global__ void k_finalize(const DevJob *__restrict__ jobs) {
 // with overlapping ranges.  At the first clashing instruction every clashing pair contains a
 // vreg that the instruction defines, so only pairs (definition, anything in P(i)) are
 // examined.  P(i) is rebuilt as a bitset in LDS the way the walk builds occupancy, but over
-// vregs instead of registers: the live-in list of i's tile, then every event up to those of
-// i, flips one bit each (in any order); the releases of values dead after i are left out,
-// since such values still belong to P(i).
+// vregs instead of registers (flip_members_of_p).
 __global__ __launch_bounds__(256) void k_resolve(const DevJob *__restrict__ jobs) {
   const DevJob &J = jobs[blockIdx.y];
   const uint32_t k = blockIdx.x;
@@ -637,20 +635,7 @@ __global__ __launch_bounds__(256) void k_resolve(const DevJob *__restrict__ jobs
     }
   }
   __syncthreads();
-  const uint32_t tile = i / L.tile_len;
-  auto flip_vreg = [&](uint32_t o) {
-    const uint32_t v = m.occ_vreg[o];
-    atomicXor(&in_p[v >> 5], 1u << (v & 31));
-  };
-  if (tile > 0)
-    for (uint32_t s = L.seed_off[tile] + threadIdx.x; s < L.seed_off[tile + 1]; s += blockDim.x) flip_vreg(L.seeds[s].w & 0xFFFFFFu);
-  const uint32_t item = i + m.instr_blk[i] + 1;   // boundary items come before their block's instructions
-  const uint32_t e_own = L.item_off[item], e_end = L.item_off[item + 1];
-  for (uint32_t e = L.tile_range[2 * tile] + threadIdx.x; e < e_end; e += blockDim.x) {
-    const uint32_t w = L.plan[e].w;
-    if (e >= e_own && (w & kEvtPost)) continue;
-    flip_vreg(w & 0xFFFFFFu);
-  }
+  flip_members_of_p(m, L, i, in_p, threadIdx.x, blockDim.x);
   __syncthreads();
   unsigned long long mine = ~0ull;
   for (uint32_t xw = threadIdx.x; xw < m.W; xw += blockDim.x) {
