@@ -361,3 +361,30 @@ void vlo_free_bases(const vlo_mir *m, const uint32_t *P, const uint16_t *cand, u
   }
   free(first);
 }
+
+/* ---- all violations (Section 4.5 error taxonomy; Section 6 verifier as reward) ---------- */
+void vlo_count_violations(const vlo_mir *m, const vlo_edge *edges, uint64_t n_edges,
+                          const uint16_t *cand, uint32_t K, uint64_t ld, vlo_counts *out,
+                          int n_threads) {
+  uint32_t *first = (uint32_t *)malloc(((size_t)m->n_vreg + 1) * 4);
+  vlo_first_occurrence(m, first);
+  if (n_threads < 1) n_threads = 1;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(n_threads)
+  for (uint32_t k = 0; k < K; ++k) {
+    const uint16_t *c = cand + (size_t)k * ld;
+    vlo_counts r;
+    memset(&r, 0, sizeof r);
+    for (uint32_t o = 0; o < m->n_occ; ++o)
+      if (c[o] != c[first[m->occ_vreg[o]]]) r.n_cons += 1;
+    for (uint32_t v = 0; v < m->n_vreg; ++v) {
+      if (first[v] == UINT32_MAX) continue;
+      uint32_t bits = realizability_bits(m, v, c[first[v]]);
+      if (bits) { r.n_real += 1; r.real_bits |= bits; }
+    }
+    for (uint64_t e = 0; e < n_edges; ++e)
+      if (ranges_meet(m, first, c, edges[e].a, edges[e].b)) r.n_safe += 1;
+    r.kinds = (r.n_cons ? 1u : 0u) | (r.n_real ? 2u : 0u) | (r.n_safe ? 4u : 0u);
+    out[k] = r;
+  }
+  free(first);
+}

@@ -129,6 +129,22 @@ void vlo_summarize(const vlo_result *res, uint32_t K, vlo_summary *out);
 typedef struct { uint32_t n_passed, max_tries; uint64_t sum_tries; uint64_t hist[4]; } vlo_loop_stats;
 void vlo_loop(const vlo_summary *s, const uint32_t *K, uint32_t n, vlo_loop_stats *out);
 
+/* All violations of a candidate instead of the first (Section 4.5 sorts the failures of
+ * the model into dataflow and hardware-constraint violations; Section 6 proposes the
+ * verifier as feedback or reward during training).  With T(v) = the register of v's first
+ * occurrence:
+ *   n_cons    occurrences whose register differs from T(their vreg)   (Consistency)
+ *   n_real    mentioned vregs for which T(v) breaks a hardware rule; real_bits = the
+ *             rules broken, OR-ed (VLO_BAD_*)                          (Realizability)
+ *   n_safe    pairs a < b of one class that are in P(i) together for some i and whose
+ *             tuples at T(a), T(b) overlap (the edges of vlo_interference)  (Safety)
+ *   kinds     bit 0: n_cons > 0, bit 1: n_real > 0, bit 2: n_safe > 0
+ * The status of vlo_verify is the lowest bit set in kinds (0 if none). */
+typedef struct { uint32_t kinds, n_cons, n_real, n_safe, real_bits, pad[3]; } vlo_counts;
+void vlo_count_violations(const vlo_mir *m, const vlo_edge *edges, uint64_t n_edges,
+                          const uint16_t *cand, uint32_t K, uint64_t ld, vlo_counts *out,
+                          int n_threads);
+
 /* Constrained decoding (Section 4.5, last sentence of the error analysis: mask
  * out the registers that are occupied while the allocation is generated).  A
  * decoder emits the candidate one occurrence after the other; when it reaches

@@ -199,3 +199,21 @@ def free_bases(m, an: Analysis, row: np.ndarray, q: int) -> np.ndarray:
     out = np.zeros(16, np.uint32)
     lib().vlo_free_bases(C.byref(s), _p(P), _p(row), C.c_uint32(q), _p(out))
     return out
+
+
+COUNTS_DTYPE = np.dtype([("kinds", "<u4"), ("n_cons", "<u4"), ("n_real", "<u4"), ("n_safe", "<u4"), ("real_bits", "<u4"),
+                         ("pad", "<u4", (3,))])
+
+
+def count_violations(m, an: Analysis, cand: np.ndarray, threads: int = 1) -> np.ndarray:
+    """Every violation of each candidate row, by kind (Section 4.5 error taxonomy;
+    Section 6: the verifier as feedback or reward).  Returns COUNTS_DTYPE [K]."""
+    s, keep = _marshal(m)
+    cand = np.ascontiguousarray(np.atleast_2d(cand), np.uint16)
+    out = np.zeros(cand.shape[0], COUNTS_DTYPE)
+    edges = an.edges if an.edges is not None else interference_edges(m, an, threads)
+    e = np.ascontiguousarray(edges if len(edges) else np.zeros(1, EDGE_DTYPE))
+    lib().vlo_count_violations(C.byref(s), _p(e), C.c_uint64(len(edges)), _p(cand),
+                               C.c_uint32(cand.shape[0]), C.c_uint64(cand.shape[1]), C.c_void_p(out.ctypes.data),
+                               C.c_int(threads))
+    return out
