@@ -249,6 +249,21 @@ def main():
     torch.cuda.synchronize()
     mask_us = (time.perf_counter() - t1) / 5 * 1e6
 
+    # all-violations mode over the same candidates (not part of the timed step); the first
+    # call also enumerates every kernel's interfering pairs
+    count_outs = [torch.zeros((r.shape[0], 8), dtype=torch.int32, device="cuda") for r in w.rows]
+    count_jobs = [(m, l, d, r.shape[0], ld, o) for m, l, d, r, ld, o in zip(mirs, lives, dev_rows, w.rows, lds, count_outs)]
+    t1 = time.perf_counter()
+    vl.vl_count_violations_multi(count_jobs, stream)
+    torch.cuda.synchronize()
+    count_first_ms = (time.perf_counter() - t1) * 1e3
+    t1 = time.perf_counter()
+    for _ in range(3):
+        vl.vl_count_violations_multi(count_jobs, stream)
+    torch.cuda.synchronize()
+    count_ms = (time.perf_counter() - t1) / 3 * 1e3
+    kinds = np.concatenate([o.cpu().numpy()[:, 0] for o in count_outs])
+
     status = np.concatenate([o.cpu().numpy()[:, 0] for o in outs])
     for oo in keep[:max(args.streams, 1 if args.no_two_stream else 2) - 1]:   # every stream used gave the first stream's results
         assert all(bool((a == b).all()) for a, b in zip(oo, outs)), "results differ between streams"
@@ -274,6 +289,9 @@ def main():
         "status_histogram": np.bincount(status, minlength=4).tolist(),
         "regeneration_loop": {"kernels_passed": int(loop["n_passed"]), "avg_tries": float(loop["sum_tries"]) / len(mirs),
                               "max_tries": int(loop["max_tries"]), "summarize_us": summarize_us},
+        "all_violations": {"ms_per_pass": count_ms, "first_pass_ms": count_first_ms,
+                           "candidates_per_s": w.n_candidates / count_ms * 1e3,
+                           "kinds_histogram": np.bincount(kinds, minlength=8).tolist()},
         "decoding_mask": {"queries": len(mask_queries), "us_per_call": mask_us,
                           "masks_per_s": len(mask_queries) / mask_us * 1e6},
         "roofline": {"bound": "hbm", "kernel": "k_walk", "achieved": achieved, "peak": HBM_PEAK_GBS,

@@ -174,6 +174,34 @@ typedef struct { uint32_t n_passed, max_tries; uint64_t sum_tries; uint64_t hist
 int32_t vl_summarize_multi(const vl_job *jobs, uint32_t n_jobs, vl_summary *summaries, vl_loop_stats *stats,
                            vl_stream stream);
 
+/* All violations of each candidate instead of the first (Section 4.5 sorts the model's
+ * failures into dataflow and hardware-constraint violations; Section 6 proposes the verifier
+ * as feedback or reward during training).  With T(v) = the register of v's first occurrence:
+ *   n_cons    occurrences whose register differs from T(their vreg)       (Consistency)
+ *   n_real    mentioned vregs for which T(v) breaks a hardware rule;
+ *             real_bits = the rules broken, OR-ed (VL_BAD_*)              (Realizability)
+ *   n_safe    pairs a < b of one class that are in P(i) together for some i and whose
+ *             tuples at T(a), T(b) overlap                                (Safety)
+ *   kinds     bit 0: n_cons > 0, bit 1: n_real > 0, bit 2: n_safe > 0
+ * The status vl_verify_batch reports is the lowest bit set in kinds (0 if none).
+ * jobs is [host]; cand and out inside are [device]; out receives K records.  The first call
+ * that sees a program enumerates its interfering pairs from `live` (whose analysis must be
+ * complete or enqueued on `stream`), synchronising the stream, and keeps them with the
+ * vl_mir handle; later calls are asynchronous on `stream` but wait on the host until the
+ * previous call's kernels have finished with the library's workspace.
+ * Errors: VL_E_NULL, VL_E_ARG (handles of different programs), VL_E_SHAPE (n_jobs == 0 or
+ * above 65535, K == 0 or above 65535, ld < n_occ); nothing is launched on error. */
+typedef struct { uint32_t kinds, n_cons, n_real, n_safe, real_bits, reserved[3]; } vl_counts;
+typedef struct {
+  const vl_mir *mir;
+  const vl_live *live;
+  const uint16_t *cand;
+  uint32_t K;
+  uint64_t ld;
+  vl_counts *out;
+} vl_count_job;
+int32_t vl_count_violations_multi(const vl_count_job *jobs, uint32_t n_jobs, vl_stream stream);
+
 /* Constrained decoding (Section 4.5, last sentence of the error analysis: mask out the
  * registers that are occupied while the allocation is generated).  A decoder emits a
  * candidate one occurrence after the other; query j asks which bases it may give occurrence

@@ -42,6 +42,11 @@ class _View(C.Structure):
                 ("live_in", "live_out", "live_after", "occ_kill", "seg_off", "seg", "hull")]
 
 
+class _CountJob(C.Structure):
+    _fields_ = [("mir", C.c_void_p), ("live", C.c_void_p), ("cand", C.c_void_p), ("K", C.c_uint32),
+                ("ld", C.c_uint64), ("out", C.c_void_p)]
+
+
 class _MaskQuery(C.Structure):
     _fields_ = [("mir", C.c_void_p), ("live", C.c_void_p), ("cand", C.c_void_p), ("occ", C.c_uint32),
                 ("reserved0", C.c_uint32)]
@@ -84,6 +89,8 @@ def load():
         L.vl_verify_multi.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p]
         L.vl_summarize_multi.restype = C.c_int32
         L.vl_summarize_multi.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.vl_count_violations_multi.restype = C.c_int32
+        L.vl_count_violations_multi.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p]
         L.vl_free_bases_multi.restype = C.c_int32
         L.vl_free_bases_multi.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p]
         L.vl_verify_time_next.restype = C.c_int32
@@ -217,6 +224,22 @@ def vl_summarize_multi(jobs, summaries, stats=None, stream=None) -> None:
                                    C.c_void_p(_dev_ptr(stats)) if stats is not None else None, _stream_ptr(stream))
     if rc != 0:
         raise VlError(rc, "vl_summarize_multi")
+
+
+COUNTS_DTYPE = np.dtype([("kinds", "<u4"), ("n_cons", "<u4"), ("n_real", "<u4"), ("n_safe", "<u4"), ("real_bits", "<u4"),
+                         ("reserved", "<u4", (3,))])
+
+
+def vl_count_violations_multi(jobs, stream=None) -> None:
+    """jobs: sequence of (mir, live, cand, K, ld, out) with out a device buffer of K records
+    of 32 bytes (COUNTS_DTYPE)."""
+    arr = (_CountJob * len(jobs))()
+    for i, (mir, live, cand, K, ld, out) in enumerate(jobs):
+        arr[i].mir, arr[i].live = mir.value, live.value
+        arr[i].cand, arr[i].K, arr[i].ld, arr[i].out = _dev_ptr(cand), K, ld, _dev_ptr(out)
+    rc = load().vl_count_violations_multi(arr, len(arr), _stream_ptr(stream))
+    if rc != 0:
+        raise VlError(rc, "vl_count_violations_multi")
 
 
 def make_mask_queries(queries):

@@ -1,0 +1,314 @@
+// All violations of each candidate instead of the first (Section 4.5 sorts the model's
+// failures into dataflow and hardware-constraint violations; Section 6 proposes the
+// verifier as feedback or reward).  With T(v) = the register of v's first occurrence:
+//   n_cons  occurrences whose register differs from T(their vreg)
+//   n_real  mentioned vregs whose T(v) breaks a hardware rule, real_bits the rules broken
+//   n_safe  pairs of one class that are in some P(i) together and whose tuples overlap
+// The pairs (the interference relation) depend on the program only: they are enumerated
+// once per program from the live intervals and kept with the program handle.  Per call the
+// registers T are gathered into a table [vreg][candidate], so that a wavefront that walks
+// the pairs with one candidate per lane reads one line per endpoint.
+#include <algorithm>
+#include <cstring>
+#include <mutex>
+#include <vector>
+
+#include "vl_dev.h"
+
+using namespace vl;
+
+namespace {
+
+// ---- interference pairs ------------------------------------------------------------------
+// do the interval lists [a0, a1) and [b0, b1) of `seg` (ascending runs [start, end)) share a point?
+__device__ inline bool lists_meet(const uint32_t VL_GLOBAL *seg, uint32_t a0, uint32_t a1, uint32_t b0, uint32_t b1) {
+  uint32_t x = a0, y = b0;
+  while (x < a1 && y < b1) {
+    const uint32_t xs = seg[2 * (size_t)x], xe = seg[2 * (size_t)x + 1], ys = seg[2 * (size_t)y], ye = seg[2 * (size_t)y + 1];
+    if (max(xs, ys) < min(xe, ye)) return true;
+    if (xe <= ye) ++x; else ++y;
+  }
+  return false;
+}
+
+// One wavefront per vreg a, its lanes striding over b > a.  kFill = false: cnt[a] = number
+// of partners; kFill = true: the pairs are written from off[a] on, in ascending b.
+template <bool kFill>
+__global__ __launch_bounds__(256) void k_pairs(const DevMir *mir, const DevLive *live, uint32_t *cnt, const uint64_t *off,
+                                               uint32_t *pairs) {
+  const DevMir VL_GLOBAL &m = *as_global(mir);
+  const DevLive VL_GLOBAL &L = *as_global(live);
+  const uint32_t lane = threadIdx.x & 63u, a = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (a >= m.V) return;   // whole wavefronts leave; nothing below synchronises the workgroup
+  const uint32_t h0 = L.hull[2 * (size_t)a], h1 = L.hull[2 * (size_t)a + 1];
+  const uint32_t s0 = L.seg_off[a], s1 = L.seg_off[a + 1], cls = attr_class(m.vattr[a]);
+  uint64_t at = kFill ? off[a] : 0;
+  uint32_t n = 0;
+  for (uint32_t b0 = a + 1; b0 < m.V; b0 += 64) {
+    const uint32_t b = b0 + lane;
+    bool hit = false;
+    if (b < m.V && attr_class(m.vattr[b]) == cls && L.hull[2 * (size_t)b] < h1 && h0 < L.hull[2 * (size_t)b + 1])
+      hit = lists_meet(L.seg, s0, s1, L.seg_off[b], L.seg_off[b + 1]);
+    const uint64_t hits = __ballot(hit);
+    if (kFill) {
+      if (hit) {
+        const uint64_t pos = at + __popcll(hits & ((1ull << lane) - 1ull));
+        pairs[2 * pos] = a;
+        pairs[2 * pos + 1] = b;
+      }
+      at += __popcll(hits);
+    } else {
+      n += __popcll(hits);
+    }
+  }
+  if (!kFill && lane == 0) cnt[a] = n;
+}
+
+// ---- per call ----------------------------------------------------------------------------
+struct DevCountJob {
+  const DevMir *mir;
+  const DevLive *live;
+  const uint16_t *cand;
+  vl_counts *out;
+  uint16_t *table;         // [V][k_pad] registers of the first occurrences
+  const uint32_t *pairs;   // [n_pairs][2]
+  uint64_t ld, n_pairs;
+  uint32_t K, k_pad, pad0, pad1;
+};
+
+__global__ void k_cnt_clear(const DevCountJob *__restrict__ jobs) {
+  const DevCountJob &J = jobs[blockIdx.y];
+  const uint32_t k = blockIdx.x * blockDim.x + threadIdx.x;
+  if (k < J.K) J.out[k] = vl_counts{0, 0, 0, 0, 0, {0, 0, 0}};
+}
+
+// table[v][k] = cand[k][first[v]] through a 64 x 64 tile in LDS: reads run along a candidate
+// row (first occurrences mostly ascend with the vreg), writes along the candidates
+__global__ __launch_bounds__(256) void k_cnt_table(const DevCountJob *__restrict__ jobs, uint32_t tiles_k) {
+  const DevCountJob &J = jobs[blockIdx.y];
+  const DevMir VL_GLOBAL &m = *as_global(J.mir);
+  const DevLive VL_GLOBAL &L = *as_global(J.live);
+  const uint32_t v0 = (blockIdx.x / tiles_k) * 64, k0 = (blockIdx.x % tiles_k) * 64;
+  if (v0 >= m.V || k0 >= J.k_pad) return;
+  __shared__ uint16_t tile[64][66];
+  const uint32_t tx = threadIdx.x & 63u, ty = threadIdx.x >> 6;
+  const uint32_t v = v0 + tx;
+  const uint32_t fo = v < m.V ? L.first[v] : kNone;
+  for (uint32_t kk = ty; kk < 64; kk += 4) {
+    const uint32_t k = k0 + kk;
+    tile[kk][tx] = (k < J.K && fo != kNone) ? J.cand[(uint64_t)k * J.ld + fo] : (uint16_t)0;
+  }
+  __syncthreads();
+  for (uint32_t vv = ty; vv < 64; vv += 4)
+    if (v0 + vv < m.V && k0 + tx < J.k_pad) J.table[(size_t)(v0 + vv) * J.k_pad + k0 + tx] = tile[tx][vv];
+}
+
+// consistency: one candidate per blockIdx.y, 1024 occurrences per workgroup
+__global__ __launch_bounds__(256) void k_cnt_cons(const DevCountJob *__restrict__ jobs) {
+  const DevCountJob &J = jobs[blockIdx.z];
+  const DevMir VL_GLOBAL &m = *as_global(J.mir);
+  const DevLive VL_GLOBAL &L = *as_global(J.live);
+  const uint32_t k = blockIdx.y, o0 = blockIdx.x * 1024;
+  if (k >= J.K || o0 >= m.O) return;
+  const uint16_t *row = J.cand + (uint64_t)k * J.ld;
+  uint32_t n = 0;
+  for (uint32_t o = o0 + threadIdx.x; o < min(m.O, o0 + 1024u); o += 256) n += row[o] != row[L.first[m.occ_vreg[o]]];
+  for (int d = 32; d >= 1; d >>= 1) n += (uint32_t)__shfl_xor((int)n, d, 64);
+  if ((threadIdx.x & 63u) == 0 && n) atomicAdd(&J.out[k].n_cons, n);
+}
+
+// realizability: one candidate per blockIdx.y, one vreg per lane
+__global__ __launch_bounds__(256) void k_cnt_real(const DevCountJob *__restrict__ jobs) {
+  const DevCountJob &J = jobs[blockIdx.z];
+  const DevMir VL_GLOBAL &m = *as_global(J.mir);
+  const DevLive VL_GLOBAL &L = *as_global(J.live);
+  const uint32_t k = blockIdx.y, v = blockIdx.x * 256 + threadIdx.x;
+  if (k >= J.K || blockIdx.x * 256 >= m.V) return;
+  uint32_t bits = 0;
+  if (v < m.V && L.first[v] != kNone) bits = bad_bits(m, m.vattr[v], J.cand[(uint64_t)k * J.ld + L.first[v]]);
+  uint32_t n = bits != 0;
+  for (int d = 32; d >= 1; d >>= 1) {
+    n += (uint32_t)__shfl_xor((int)n, d, 64);
+    bits |= (uint32_t)__shfl_xor((int)bits, d, 64);
+  }
+  if ((threadIdx.x & 63u) == 0 && n) {
+    atomicAdd(&J.out[k].n_real, n);
+    atomicOr(&J.out[k].real_bits, bits);
+  }
+}
+
+// safety: a workgroup takes 64 candidates (one per lane) and a stretch of the pairs, 1024
+// pairs per wavefront, fetched 64 at a time (one pair per lane, read out of the lanes)
+constexpr uint32_t kPairsPerWave = 1024, kPairsPerGroup = 4 * kPairsPerWave;
+__global__ __launch_bounds__(256) void k_cnt_safe(const DevCountJob *__restrict__ jobs, uint32_t groups) {
+  const DevCountJob &J = jobs[blockIdx.y];
+  const DevMir VL_GLOBAL &m = *as_global(J.mir);
+  const uint32_t g = blockIdx.x % groups, stretch = blockIdx.x / groups;
+  const uint32_t lane = threadIdx.x & 63u, k = g * 64 + lane;
+  if (g * 64 >= J.K) return;
+  const uint64_t e0 = (uint64_t)stretch * kPairsPerGroup + (uint64_t)(threadIdx.x >> 6) * kPairsPerWave;
+  if (e0 >= J.n_pairs) return;
+  const uint64_t e1 = min(J.n_pairs, e0 + kPairsPerWave);
+  uint32_t n = 0;
+  for (uint64_t e = e0; e < e1; e += 64) {
+    uint32_t pa = 0, pb = 0, wa = 0, wb = 0;
+    if (e + lane < e1) {
+      pa = J.pairs[2 * (e + lane)];
+      pb = J.pairs[2 * (e + lane) + 1];
+      wa = attr_width(m.vattr[pa]);
+      wb = attr_width(m.vattr[pb]);
+    }
+    // Eight pairs at a time, their sixteen table reads in flight together.  Lanes past the
+    // last pair hold the pair (0, 0) with widths 0, which never overlaps, so no tail is needed.
+    const uint32_t cnt = (uint32_t)min((uint64_t)64, e1 - e);
+    for (uint32_t j = 0; j < cnt; j += 8) {
+      uint32_t ra[8], rb[8];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const uint32_t a = __builtin_amdgcn_readlane(pa, j + t), b = __builtin_amdgcn_readlane(pb, j + t);
+        ra[t] = J.table[(size_t)a * J.k_pad + k];   // k < k_pad always
+        rb[t] = J.table[(size_t)b * J.k_pad + k];
+      }
+#pragma unroll
+      for (int t = 0; t < 8; ++t)
+        n += ra[t] < rb[t] + (uint32_t)__builtin_amdgcn_readlane(wb, j + t) && rb[t] < ra[t] + (uint32_t)__builtin_amdgcn_readlane(wa, j + t);
+    }
+  }
+  if (k < J.K && n) atomicAdd(&J.out[k].n_safe, n);
+}
+
+__global__ void k_cnt_kinds(const DevCountJob *__restrict__ jobs) {
+  const DevCountJob &J = jobs[blockIdx.y];
+  const uint32_t k = blockIdx.x * blockDim.x + threadIdx.x;
+  if (k >= J.K) return;
+  vl_counts &c = J.out[k];
+  c.kinds = (c.n_cons ? 1u : 0u) | (c.n_real ? 2u : 0u) | (c.n_safe ? 4u : 0u);
+}
+
+// per-device workspace: the job table (device + pinned copy) and the register tables
+struct Work {
+  std::mutex mu;
+  DevCountJob *dev = nullptr, *host = nullptr;
+  uint32_t cap = 0;
+  void *tables = nullptr;
+  size_t tables_cap = 0;
+  hipEvent_t consumed = nullptr;   // recorded after the last kernel of a call
+};
+Work g_work[16];
+
+// Enumerates the interference pairs of u.mir from the intervals of `live` (whose analysis
+// must be complete on `stream`).  Synchronises the stream.
+int32_t build_pairs(vl_mir *mir, const vl_live *live, hipStream_t stream) {
+  const uint32_t V = mir->h.V;
+  uint32_t *cnt = nullptr;
+  uint64_t *off = nullptr;
+  VL_HIP(hipMalloc((void **)&cnt, (size_t)(V + 1) * 4));
+  hipError_t e = hipMalloc((void **)&off, (size_t)(V + 1) * 8);
+  if (e != hipSuccess) { (void)hipFree(cnt); return hip_fail(e); }
+  auto fail = [&](hipError_t err) { (void)hipFree(cnt); (void)hipFree(off); return hip_fail(err); };
+  const uint32_t blocks = (V + 3) / 4;
+  k_pairs<false><<<blocks, 256, 0, stream>>>(mir->dev, live->dev, cnt, nullptr, nullptr);
+  std::vector<uint32_t> h_cnt(V);
+  e = hipMemcpyAsync(h_cnt.data(), cnt, (size_t)V * 4, hipMemcpyDeviceToHost, stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(stream);
+  if (e != hipSuccess) return fail(e);
+  std::vector<uint64_t> h_off(V + 1);
+  uint64_t total = 0;
+  for (uint32_t a = 0; a < V; ++a) { h_off[a] = total; total += h_cnt[a]; }
+  h_off[V] = total;
+  void *pairs = nullptr;
+  if (total) {
+    e = hipMalloc(&pairs, (size_t)total * 8);
+    if (e != hipSuccess) return fail(e);
+    e = hipMemcpyAsync(off, h_off.data(), (size_t)(V + 1) * 8, hipMemcpyHostToDevice, stream);
+    if (e == hipSuccess) {
+      k_pairs<true><<<blocks, 256, 0, stream>>>(mir->dev, live->dev, nullptr, off, (uint32_t *)pairs);
+      e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);   // h_off and the scratch arrays go away below
+    if (e != hipSuccess) { (void)hipFree(pairs); return fail(e); }
+  }
+  (void)hipFree(cnt);
+  (void)hipFree(off);
+  mir->edges = pairs;
+  mir->n_edges = total;
+  mir->edges_built = true;
+  return VL_OK;
+}
+
+}  // namespace
+
+extern "C" int32_t vl_count_violations_multi(const vl_count_job *jobs, uint32_t n_jobs, vl_stream stream_) {
+  if (!jobs) return VL_E_NULL;
+  if (n_jobs == 0 || n_jobs > 65535) return VL_E_SHAPE;
+  for (uint32_t j = 0; j < n_jobs; ++j) {
+    const vl_count_job &u = jobs[j];
+    if (!u.mir || !u.live || !u.cand || !u.out) return VL_E_NULL;
+    if (u.mir->magic != kMirMagic || u.live->magic != kLiveMagic || u.live->mir != u.mir) return VL_E_ARG;
+    if (u.K == 0 || u.K > 65535 || u.ld < u.mir->h.O) return VL_E_SHAPE;
+  }
+  hipStream_t stream = (hipStream_t)stream_;
+  int device = 0;
+  VL_HIP(hipGetDevice(&device));
+  if (device < 0 || device >= 16) return VL_E_ARG;
+  Work &w = g_work[device];
+  std::lock_guard<std::mutex> lock(w.mu);
+  // the pairs of programs seen for the first time (the handle is the cache: not const here)
+  for (uint32_t j = 0; j < n_jobs; ++j) {
+    vl_mir *mir = const_cast<vl_mir *>(jobs[j].mir);
+    if (!mir->edges_built) {
+      const int32_t rc = build_pairs(mir, jobs[j].live, stream);
+      if (rc != VL_OK) return rc;
+    }
+  }
+  // the previous call's kernels must be done with the job table and the register tables
+  if (w.consumed) VL_HIP(hipEventSynchronize(w.consumed));
+  if (w.cap < n_jobs) {
+    if (w.dev) (void)hipFree(w.dev);
+    if (w.host) (void)hipHostFree(w.host);
+    w.dev = nullptr; w.host = nullptr; w.cap = 0;
+    const uint32_t cap = std::max(256u, n_jobs);
+    VL_HIP(hipMalloc((void **)&w.dev, (size_t)cap * sizeof(DevCountJob)));
+    VL_HIP(hipHostMalloc((void **)&w.host, (size_t)cap * sizeof(DevCountJob), hipHostMallocDefault));
+    w.cap = cap;
+  }
+  if (!w.consumed) VL_HIP(hipEventCreateWithFlags(&w.consumed, hipEventDisableTiming));
+  size_t bytes = 0;
+  std::vector<size_t> at(n_jobs);
+  uint32_t maxK = 0, maxV = 1, maxO = 1, max_kpad = 64;
+  uint64_t max_pairs = 0;
+  for (uint32_t j = 0; j < n_jobs; ++j) {
+    const uint32_t k_pad = (jobs[j].K + 63u) & ~63u;
+    at[j] = bytes;
+    bytes += (((size_t)jobs[j].mir->h.V * k_pad * 2) + 255) & ~(size_t)255;
+    maxK = std::max(maxK, jobs[j].K); maxV = std::max(maxV, jobs[j].mir->h.V); maxO = std::max(maxO, jobs[j].mir->h.O);
+    max_kpad = std::max(max_kpad, k_pad);
+    max_pairs = std::max(max_pairs, jobs[j].mir->n_edges);
+  }
+  if (bytes > w.tables_cap) {
+    if (w.tables) (void)hipFree(w.tables);
+    w.tables = nullptr; w.tables_cap = 0;
+    VL_HIP(hipMalloc(&w.tables, bytes));
+    w.tables_cap = bytes;
+  }
+  for (uint32_t j = 0; j < n_jobs; ++j) {
+    DevCountJob &d = w.host[j];
+    memset(&d, 0, sizeof(d));
+    d.mir = jobs[j].mir->dev; d.live = jobs[j].live->dev; d.cand = jobs[j].cand; d.out = jobs[j].out;
+    d.table = (uint16_t *)((char *)w.tables + at[j]);
+    d.pairs = (const uint32_t *)jobs[j].mir->edges; d.n_pairs = jobs[j].mir->n_edges;
+    d.ld = jobs[j].ld; d.K = jobs[j].K; d.k_pad = (jobs[j].K + 63u) & ~63u;
+  }
+  VL_HIP(hipMemcpyAsync(w.dev, w.host, (size_t)n_jobs * sizeof(DevCountJob), hipMemcpyHostToDevice, stream));
+  const uint32_t tiles_k = max_kpad / 64, tiles_v = (maxV + 63) / 64, groups = max_kpad / 64;
+  const uint32_t stretches = (uint32_t)std::max<uint64_t>(1, (max_pairs + kPairsPerGroup - 1) / kPairsPerGroup);
+  k_cnt_clear<<<dim3((maxK + 255) / 256, n_jobs), 256, 0, stream>>>(w.dev);
+  k_cnt_table<<<dim3(tiles_v * tiles_k, n_jobs), 256, 0, stream>>>(w.dev, tiles_k);
+  k_cnt_cons<<<dim3((maxO + 1023) / 1024, maxK, n_jobs), 256, 0, stream>>>(w.dev);
+  k_cnt_real<<<dim3((maxV + 255) / 256, maxK, n_jobs), 256, 0, stream>>>(w.dev);
+  k_cnt_safe<<<dim3(groups * stretches, n_jobs), 256, 0, stream>>>(w.dev, groups);
+  k_cnt_kinds<<<dim3((maxK + 255) / 256, n_jobs), 256, 0, stream>>>(w.dev);
+  VL_HIP(hipGetLastError());
+  VL_HIP(hipEventRecord(w.consumed, stream));
+  return VL_OK;
+}

@@ -175,6 +175,18 @@ enum { kCtrLong = 0, kCtrNotStrict = 1, kCtrSweeps = 2, kCtrPlanLen = 3, kCtrSeg
 
 // host-side handles
 namespace vl {
+// Which hardware rules a base register breaks for a vreg with these attributes (VL_BAD_*).
+__device__ inline uint32_t bad_bits(const DevMir VL_GLOBAL &m, uint32_t attr, uint32_t p) {
+  const uint32_t cls = attr_class(attr), width = attr_width(attr), align = attr_align(attr);
+  uint32_t bad = 0;
+  if (p + width > m.class_size[cls]) bad |= VL_BAD_BOUNDS;
+  if (p % align != 0) bad |= VL_BAD_ALIGN;
+  if (m.has_reserved)
+    for (uint32_t r = p; r < p + width; ++r)
+      if (r < 512 && ((m.reserved[cls][r >> 5] >> (r & 31)) & 1u)) bad |= VL_BAD_RESERVED;
+  return bad;
+}
+
 // P(i) = live_after(i) + defs(i) as a vreg bitset: the live-in list of i's tile, then every
 // event up to those of i, flips one bit each (in any order); the releases of values dead once
 // i has executed are left out, since such values still belong to P(i).  in_p: [W] words in
@@ -205,6 +217,11 @@ struct vl_mir {
   void *arena;         // single allocation holding every array
   int device;
   uint64_t magic;
+  // interference pairs (a < b, one class, some point in common), built on first use by the
+  // all-violations mode and kept for the life of the handle: they depend on the program only
+  void *edges = nullptr;       // device: n_edges pairs of uint32
+  uint64_t n_edges = 0;
+  bool edges_built = false;
 };
 
 struct vl_batch;

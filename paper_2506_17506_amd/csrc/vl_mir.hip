@@ -178,5 +178,6 @@ extern "C" void vl_mir_destroy(vl_mir *m) {
   if (!m || m->magic != vl::kMirMagic) return;
   m->magic = 0;
   if (m->arena) (void)hipFree(m->arena);
+  if (m->edges) (void)hipFree(m->edges);
   delete m;
 }

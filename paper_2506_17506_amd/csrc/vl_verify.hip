@@ -557,17 +557,6 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(6)
   if (w.tid < w.nrows && vl_lds[w.keys + w.tid] != kKeyOk) atomicMin(&J.out[row0 + w.tid].status, vl_lds[w.keys + w.tid]);
 }
 
-__device__ inline uint32_t bad_bits(const DevMir VL_GLOBAL &m, uint32_t attr, uint32_t p) {
-  const uint32_t cls = attr_class(attr), width = attr_width(attr), align = attr_align(attr);
-  uint32_t bad = 0;
-  if (p + width > m.class_size[cls]) bad |= VL_BAD_BOUNDS;
-  if (p % align != 0) bad |= VL_BAD_ALIGN;
-  if (m.has_reserved)
-    for (uint32_t r = p; r < p + width; ++r)
-      if (r < 512 && ((m.reserved[cls][r >> 5] >> (r & 31)) & 1u)) bad |= VL_BAD_RESERVED;
-  return bad;
-}
-
 // Turns the winning key of each candidate into its result record.  Safety results
 // get their pair from k_resolve.
 __global__ void k_finalize(const DevJob *__restrict__ jobs) {
