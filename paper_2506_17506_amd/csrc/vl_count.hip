@@ -200,6 +200,7 @@ Work g_work[16];
 // must be complete on `stream`).  Synchronises the stream.
 int32_t build_pairs(vl_mir *mir, const vl_live *live, hipStream_t stream) {
   const uint32_t V = mir->h.V;
+  if (V == 0) { mir->edges = nullptr; mir->n_edges = 0; mir->edges_built = true; return VL_OK; }
   uint32_t *cnt = nullptr;
   uint64_t *off = nullptr;
   VL_HIP(hipMalloc((void **)&cnt, (size_t)(V + 1) * 4));
