@@ -388,3 +388,31 @@ void vlo_count_violations(const vlo_mir *m, const vlo_edge *edges, uint64_t n_ed
   }
   free(first);
 }
+
+/* ---- register-bank conflicts (Section 2: banks, the FFMA example) ----------------------- */
+void vlo_bank_conflicts(const vlo_mir *m, const uint16_t *cand, uint32_t K, uint64_t ld,
+                        uint32_t n_banks, uint32_t *out) {
+  uint32_t *per_bank = (uint32_t *)malloc((size_t)n_banks * 4);
+  for (uint32_t k = 0; k < K; ++k) {
+    const uint16_t *c = cand + (size_t)k * ld;
+    uint32_t total = 0;
+    for (uint32_t i = 0; i < m->n_instr; ++i) {
+      for (uint32_t b = 0; b < n_banks; ++b) per_bank[b] = 0;
+      for (uint32_t o = m->instr_occ_off[i]; o < m->instr_occ_off[i + 1]; ++o) {
+        if (!(m->occ_flags[o] & VLO_OCC_USE)) continue;
+        const uint32_t v = m->occ_vreg[o];
+        int seen = 0; /* an earlier USE operand of this instruction with the same vreg */
+        for (uint32_t x = m->instr_occ_off[i]; x < o; ++x)
+          if ((m->occ_flags[x] & VLO_OCC_USE) && m->occ_vreg[x] == v) seen = 1;
+        if (seen) continue;
+        for (uint32_t j = 0; j < m->vreg_width[v]; ++j) per_bank[((uint32_t)c[o] + j) % n_banks] += 1;
+      }
+      uint32_t worst = 0;
+      for (uint32_t b = 0; b < n_banks; ++b)
+        if (per_bank[b] > worst) worst = per_bank[b];
+      if (worst > 1) total += worst - 1;
+    }
+    out[k] = total;
+  }
+  free(per_bank);
+}

@@ -145,6 +145,18 @@ void vlo_count_violations(const vlo_mir *m, const vlo_edge *edges, uint64_t n_ed
                           const uint16_t *cand, uint32_t K, uint64_t ld, vlo_counts *out,
                           int n_threads);
 
+/* Register-bank conflicts, a quality measure beside validity (Section 2: registers are
+ * organised in banks, four on NVIDIA GPUs; reading several values from one bank stalls
+ * the pipeline one cycle per extra value, and the compiler picks R4, R6, R9 for an FFMA
+ * because they lie in different banks).  Register r is in bank r mod n_banks.  For each
+ * instruction the 32-bit registers it reads are those of its distinct USE vregs (a tuple of
+ * width w at base p reads p .. p + w - 1; the base is the one of the vreg's first USE
+ * operand of that instruction); the banks deliver in parallel, so the instruction stalls
+ * max over banks of (registers read from that bank) - 1 cycles, 0 if it reads nothing.
+ * out[k] = the sum over all instructions for candidate k. */
+void vlo_bank_conflicts(const vlo_mir *m, const uint16_t *cand, uint32_t K, uint64_t ld,
+                        uint32_t n_banks, uint32_t *out);
+
 /* Constrained decoding (Section 4.5, last sentence of the error analysis: mask
  * out the registers that are occupied while the allocation is generated).  A
  * decoder emits the candidate one occurrence after the other; when it reaches

@@ -217,3 +217,14 @@ def count_violations(m, an: Analysis, cand: np.ndarray, threads: int = 1) -> np.
                                C.c_uint32(cand.shape[0]), C.c_uint64(cand.shape[1]), C.c_void_p(out.ctypes.data),
                                C.c_int(threads))
     return out
+
+
+def bank_conflicts(m, cand: np.ndarray, n_banks: int = 4) -> np.ndarray:
+    """Stall cycles from register-bank conflicts per candidate row (Section 2: banks and
+    the FFMA example).  uint32 [K]."""
+    s, keep = _marshal(m)
+    cand = np.ascontiguousarray(np.atleast_2d(cand), np.uint16)
+    out = np.zeros(cand.shape[0], np.uint32)
+    lib().vlo_bank_conflicts(C.byref(s), _p(cand), C.c_uint32(cand.shape[0]), C.c_uint64(cand.shape[1]),
+                             C.c_uint32(n_banks), _p(out))
+    return out
