@@ -202,6 +202,20 @@ typedef struct {
 } vl_count_job;
 int32_t vl_count_violations_multi(const vl_count_job *jobs, uint32_t n_jobs, vl_stream stream);
 
+/* Register-bank conflicts, a quality measure beside validity (Section 2: registers are
+ * organised in banks, four on NVIDIA GPUs; reading several values from one bank stalls the
+ * pipeline one cycle per extra value, which is why the FFMA of the overview figure reads R4,
+ * R6 and R9).  Register r is in bank r mod n_banks.  An instruction reads the registers of its
+ * distinct USE vregs (a tuple of width w at base p reads p .. p + w - 1, the base taken from
+ * the vreg's first USE operand of that instruction); the banks deliver in parallel, so it
+ * stalls max over banks of (registers read from that bank) - 1 cycles, 0 if it reads nothing.
+ * out [device]: K sums over all instructions, one per candidate row of cand [device].  Needs
+ * no analysis.  Asynchronous on `stream`.
+ * Errors: VL_E_NULL, VL_E_ARG, VL_E_SHAPE (K == 0 or above 65535, ld < n_occ), VL_E_RANGE
+ * (n_banks == 0 or above 64). */
+int32_t vl_bank_conflicts(const vl_mir *mir, const uint16_t *cand, uint32_t K, uint64_t ld, uint32_t n_banks,
+                          uint32_t *out, vl_stream stream);
+
 /* Constrained decoding (Section 4.5, last sentence of the error analysis: mask out the
  * registers that are occupied while the allocation is generated).  A decoder emits a
  * candidate one occurrence after the other; query j asks which bases it may give occurrence

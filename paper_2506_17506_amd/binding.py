@@ -91,6 +91,8 @@ def load():
         L.vl_summarize_multi.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.vl_count_violations_multi.restype = C.c_int32
         L.vl_count_violations_multi.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p]
+        L.vl_bank_conflicts.restype = C.c_int32
+        L.vl_bank_conflicts.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint64, C.c_uint32, C.c_void_p, C.c_void_p]
         L.vl_free_bases_multi.restype = C.c_int32
         L.vl_free_bases_multi.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p]
         L.vl_verify_time_next.restype = C.c_int32
@@ -240,6 +242,14 @@ def vl_count_violations_multi(jobs, stream=None) -> None:
     rc = load().vl_count_violations_multi(arr, len(arr), _stream_ptr(stream))
     if rc != 0:
         raise VlError(rc, "vl_count_violations_multi")
+
+
+def vl_bank_conflicts(mir, cand, K: int, ld: int, n_banks: int, out, stream=None) -> None:
+    """out: device buffer of K uint32."""
+    rc = load().vl_bank_conflicts(mir, C.c_void_p(_dev_ptr(cand)), K, ld, n_banks, C.c_void_p(_dev_ptr(out)),
+                                  _stream_ptr(stream))
+    if rc != 0:
+        raise VlError(rc, "vl_bank_conflicts")
 
 
 def make_mask_queries(queries):

@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol():
     lib = vl.load()
     names = declared_symbols()
     assert {"vl_mir_create", "vl_liveness", "vl_liveness_multi", "vl_verify_batch", "vl_verify_multi",
-            "vl_live_get", "vl_strerror", "vl_summarize_multi", "vl_free_bases_multi", "vl_count_violations_multi"} <= set(names)
+            "vl_live_get", "vl_strerror", "vl_summarize_multi", "vl_free_bases_multi", "vl_count_violations_multi", "vl_bank_conflicts"} <= set(names)
     for n in names:
         assert getattr(lib, n) is not None, n
 
@@ -77,6 +77,7 @@ def test_null_arguments():
     assert lib.vl_summarize_multi(None, 1, None, None, None) == -1
     assert lib.vl_free_bases_multi(None, 1, None, None) == -1
     assert lib.vl_count_violations_multi(None, 1, None) == -1
+    assert lib.vl_bank_conflicts(None, None, 1, 1, 4, None, None) == -1
     assert lib.vl_liveness_multi(None, 1, 0, 0, None, None) == -1
     assert lib.vl_live_get(None, None) == -1
     lib.vl_mir_destroy(None)
