@@ -2,6 +2,9 @@
 four on NVIDIA GPUs; reading several values from one bank costs a cycle per extra value;
 the FFMA of the overview figure reads R4, R6 and R9 because they lie in different banks).  Expected
 values: the paper's example, hand-written cases, closed forms, and a plain Python count."""
+import json
+import os
+
 import numpy as np
 
 from oracle import vlo
@@ -22,8 +25,10 @@ def row_for(m, regs):
 
 def test_the_example_of_the_paper():
     m = ffma()
+    with open(os.path.join(os.path.dirname(__file__), "golden", "paper_cases.json")) as f:
+        case = json.load(f)["ffma_banks"]
     # R4, R6, R9: banks 0, 2, 1 of four: no stall.  (The destination is not read.)
-    assert vlo.bank_conflicts(m, row_for(m, [4, 6, 9, 4]), 4)[0] == 0
+    assert vlo.bank_conflicts(m, row_for(m, case["reads"] + [4]), case["n_banks"])[0] == case["stalls"] == 0
     # R4, R8, R9: two values from bank 0: one extra cycle
     assert vlo.bank_conflicts(m, row_for(m, [4, 8, 9, 5]), 4)[0] == 1
     # R4, R8, R12: all three from bank 0: two extra cycles
