@@ -264,6 +264,19 @@ def main():
     count_ms = (time.perf_counter() - t1) / 3 * 1e3
     kinds = np.concatenate([o.cpu().numpy()[:, 0] for o in count_outs])
 
+    # what a plain streaming read reaches on this device (context for the roofline figure):
+    # the library's read-only probe over 1 GiB, best of five
+    probe = torch.ones(1 << 28, dtype=torch.int32, device="cuda")
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    stream_read = 0.0
+    for _ in range(6):
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        vl.vl_stream_read_probe(probe, probe.numel() * 4, sink, stream)
+        torch.cuda.synchronize()
+        stream_read = max(stream_read, probe.numel() * 4 / (time.perf_counter() - t1) / 1e9)
+    del probe
+
     status = np.concatenate([o.cpu().numpy()[:, 0] for o in outs])
     for oo in keep[:max(args.streams, 1 if args.no_two_stream else 2) - 1]:   # every stream used gave the first stream's results
         assert all(bool((a == b).all()) for a, b in zip(oo, outs)), "results differ between streams"
@@ -297,7 +310,8 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "k_walk", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic_from_profile(src),
-                     "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_ms": walk_avg_s * 1e3},
+                     "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_ms": walk_avg_s * 1e3,
+                     "measured_stream_read": stream_read, "frac_of_measured_stream_read": achieved / stream_read},
     }
     if not args.no_cpu:
         rec["cpu_baseline"] = cpu_baseline(w)

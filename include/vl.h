@@ -202,6 +202,12 @@ typedef struct {
 } vl_count_job;
 int32_t vl_count_violations_multi(const vl_count_job *jobs, uint32_t n_jobs, vl_stream stream);
 
+/* Measurement hook: one launch that only reads `bytes` bytes (a multiple of 16, 16-byte
+ * aligned) of buf [device] with 16-byte loads, for the benchmark's "what does a plain
+ * streaming read reach" figure.  sink [device]: one word, practically never written.
+ * Asynchronous on `stream`.  Errors: VL_E_NULL, VL_E_SHAPE. */
+int32_t vl_stream_read_probe(const void *buf, uint64_t bytes, uint32_t *sink, vl_stream stream);
+
 /* Register-bank conflicts, a quality measure beside validity (Section 2: registers are
  * organised in banks, four on NVIDIA GPUs; reading several values from one bank stalls the
  * pipeline one cycle per extra value, which is why the FFMA of the overview figure reads R4,

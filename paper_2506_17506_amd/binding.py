@@ -91,6 +91,8 @@ def load():
         L.vl_summarize_multi.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.vl_count_violations_multi.restype = C.c_int32
         L.vl_count_violations_multi.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p]
+        L.vl_stream_read_probe.restype = C.c_int32
+        L.vl_stream_read_probe.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]
         L.vl_bank_conflicts.restype = C.c_int32
         L.vl_bank_conflicts.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint64, C.c_uint32, C.c_void_p, C.c_void_p]
         L.vl_free_bases_multi.restype = C.c_int32
@@ -242,6 +244,12 @@ def vl_count_violations_multi(jobs, stream=None) -> None:
     rc = load().vl_count_violations_multi(arr, len(arr), _stream_ptr(stream))
     if rc != 0:
         raise VlError(rc, "vl_count_violations_multi")
+
+
+def vl_stream_read_probe(buf, n_bytes: int, sink, stream=None) -> None:
+    rc = load().vl_stream_read_probe(C.c_void_p(_dev_ptr(buf)), n_bytes, C.c_void_p(_dev_ptr(sink)), _stream_ptr(stream))
+    if rc != 0:
+        raise VlError(rc, "vl_stream_read_probe")
 
 
 def vl_bank_conflicts(mir, cand, K: int, ld: int, n_banks: int, out, stream=None) -> None:

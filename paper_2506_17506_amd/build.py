@@ -4,7 +4,7 @@ import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
-SOURCES = ["vl_mir.hip", "vl_liveness.hip", "vl_verify.hip", "vl_mask.hip", "vl_count.hip", "vl_score.hip"]
+SOURCES = ["vl_mir.hip", "vl_liveness.hip", "vl_verify.hip", "vl_mask.hip", "vl_count.hip", "vl_score.hip", "vl_probe.hip"]
 LIB = os.path.join(HERE, "libvl.so")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

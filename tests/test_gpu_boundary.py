@@ -117,3 +117,18 @@ def test_calls_alternating_over_streams():
         vl.vl_live_destroy(l)
     for m in hm:
         vl.vl_mir_destroy(m)
+
+
+def test_stream_read_probe_arguments():
+    buf = torch.ones(1 << 20, dtype=torch.int32, device="cuda")
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    vl.vl_stream_read_probe(buf, buf.numel() * 4, sink)
+    vl.vl_stream_read_probe(buf, 16 * 1000 + 16, sink)        # a length that leaves a tail for the last loop
+    torch.cuda.synchronize()
+    assert int(sink.cpu()[0]) == 0
+    with pytest.raises(vl.VlError) as e:
+        vl.vl_stream_read_probe(buf[1:], 64, sink)            # not 16-byte aligned
+    assert e.value.code == -2
+    with pytest.raises(vl.VlError) as e:
+        vl.vl_stream_read_probe(buf, 8, sink)
+    assert e.value.code == -2
