@@ -381,7 +381,11 @@ __global__ __launch_bounds__(64) void k_fixpoint(MIRS) {
   const bool act = w < m.W;
   const uint32_t B = m.B, W = m.W;
   uint32_t *in_l = sm, *use_l = sm + (size_t)B * 64, *def_l = sm + (size_t)2 * B * 64;
+  // the successor lists are walked once per block and sweep: they sit in LDS too
+  uint32_t *succ_off_l = sm + (size_t)3 * B * 64, *succ_l = succ_off_l + B + 1;
   if (kLds) {
+    for (uint32_t x = lane; x <= B; x += 64) succ_off_l[x] = m.succ_off[x];
+    for (uint32_t x = lane; x < m.E; x += 64) succ_l[x] = m.succ[x];
     for (uint32_t b = 0; b < B; ++b) {
       in_l[b * 64 + lane] = 0;
       use_l[b * 64 + lane] = act ? L.use[(size_t)b * W + w] : 0;
@@ -395,8 +399,9 @@ __global__ __launch_bounds__(64) void k_fixpoint(MIRS) {
     ++sweeps;
     for (uint32_t b = B; b-- > 0;) {
       uint32_t out = 0;
-      for (uint32_t e = m.succ_off[b]; e < m.succ_off[b + 1]; ++e) {
-        uint32_t s = m.succ[e];
+      const uint32_t e0 = kLds ? succ_off_l[b] : m.succ_off[b], e1 = kLds ? succ_off_l[b + 1] : m.succ_off[b + 1];
+      for (uint32_t e = e0; e < e1; ++e) {
+        uint32_t s = kLds ? succ_l[e] : m.succ[e];
         out |= kLds ? in_l[s * 64 + lane] : (act ? L.live_in[(size_t)s * W + w] : 0);
       }
       uint32_t u = kLds ? use_l[b * 64 + lane] : (act ? L.use[(size_t)b * W + w] : 0);
@@ -412,8 +417,9 @@ __global__ __launch_bounds__(64) void k_fixpoint(MIRS) {
   // write-out: in (when it lived in LDS) and out
   for (uint32_t b = 0; b < B; ++b) {
     uint32_t out = 0;
-    for (uint32_t e = m.succ_off[b]; e < m.succ_off[b + 1]; ++e) {
-      uint32_t s = m.succ[e];
+    const uint32_t e0 = kLds ? succ_off_l[b] : m.succ_off[b], e1 = kLds ? succ_off_l[b + 1] : m.succ_off[b + 1];
+    for (uint32_t e = e0; e < e1; ++e) {
+      uint32_t s = kLds ? succ_l[e] : m.succ[e];
       out |= kLds ? in_l[s * 64 + lane] : (act ? L.live_in[(size_t)s * W + w] : 0);
     }
     if (act) {
@@ -1107,7 +1113,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
                 role, kill, item, seg_off, hull, queue, bitmap, ent_seg, ent_sf, chk, evt_cut, tile_live; };
   std::vector<Off1> off(n);
   Bump bump;
-  uint32_t maxO = 1, maxV = 1, maxN = 1, maxB = 1, maxW = 1, maxT = 1;
+  uint32_t maxO = 1, maxV = 1, maxN = 1, maxB = 1, maxW = 1, maxT = 1, maxE = 0;
   for (uint32_t k = 0; k < n; ++k) {
     const DevMir &m = mirs[k]->h;
     const uint32_t T = (m.N + tile_len - 1) / tile_len;
@@ -1121,7 +1127,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     off[k].seed_off = bump.take((size_t)(T + 1) * 4); off[k].seed_cur = bump.take((size_t)(T + 1) * 4);
     off[k].item = bump.take((size_t)(m.N + m.B + 1) * 4);   // event counts are accumulated with atomics
     maxO = std::max(maxO, m.O); maxV = std::max(maxV, m.V); maxN = std::max(maxN, m.N);
-    maxB = std::max(maxB, m.B); maxW = std::max(maxW, m.W); maxT = std::max(maxT, T);
+    maxB = std::max(maxB, m.B); maxW = std::max(maxW, m.W); maxT = std::max(maxT, T); maxE = std::max(maxE, m.E);
   }
   const size_t o_counters = bump.take((size_t)n * kCounters * 4);
   const size_t zero_bytes = bump.off;
@@ -1263,7 +1269,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     k_summary<<<grid1(maxO, kSumSlice, n), kSumThreads, lds, stream>>>(dm, dl, (uint32_t)(lds / 4));
   }
   {
-    const size_t lds = (size_t)maxB * 64 * 3 * 4;
+    const size_t lds = (size_t)maxB * 64 * 3 * 4 + ((size_t)maxB + 1 + maxE) * 4;
     if (lds <= 64 * 1024) k_fixpoint<true><<<grid1(maxW, 64, n), 64, lds, stream>>>(dm, dl);
     else k_fixpoint<false><<<grid1(maxW, 64, n), 64, 0, stream>>>(dm, dl);
   }
