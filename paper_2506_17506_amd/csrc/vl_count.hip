@@ -11,6 +11,7 @@
 #include <algorithm>
 #include <cstring>
 #include <mutex>
+#include <utility>
 #include <vector>
 
 #include "vl_dev.h"
@@ -31,18 +32,26 @@ __device__ inline bool lists_meet(const uint32_t VL_GLOBAL *seg, uint32_t a0, ui
   return false;
 }
 
-// One wavefront per vreg a, its lanes striding over b > a.  kFill = false: cnt[a] = number
-// of partners; kFill = true: the pairs are written from off[a] on, in ascending b.
+// One wavefront per vreg a, its lanes striding over b > a; blockIdx.y = program.  kFill = false:
+// cnt[a] = number of partners; kFill = true: the pairs are written from off[a] on, in ascending b.
+struct PairJob {
+  const DevMir *mir;
+  const DevLive *live;
+  uint32_t *cnt;         // [V]
+  const uint64_t *off;   // [V]
+  uint32_t *pairs;       // [n_pairs][2]
+};
+
 template <bool kFill>
-__global__ __launch_bounds__(256) void k_pairs(const DevMir *mir, const DevLive *live, uint32_t *cnt, const uint64_t *off,
-                                               uint32_t *pairs) {
-  const DevMir VL_GLOBAL &m = *as_global(mir);
-  const DevLive VL_GLOBAL &L = *as_global(live);
+__global__ __launch_bounds__(256) void k_pairs(const PairJob *__restrict__ jobs) {
+  const PairJob &J = jobs[blockIdx.y];
+  const DevMir VL_GLOBAL &m = *as_global(J.mir);
+  const DevLive VL_GLOBAL &L = *as_global(J.live);
   const uint32_t lane = threadIdx.x & 63u, a = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (a >= m.V) return;   // whole wavefronts leave; nothing below synchronises the workgroup
   const uint32_t h0 = L.hull[2 * (size_t)a], h1 = L.hull[2 * (size_t)a + 1];
   const uint32_t s0 = L.seg_off[a], s1 = L.seg_off[a + 1], cls = attr_class(m.vattr[a]);
-  uint64_t at = kFill ? off[a] : 0;
+  uint64_t at = kFill ? J.off[a] : 0;
   uint32_t n = 0;
   for (uint32_t b0 = a + 1; b0 < m.V; b0 += 64) {
     const uint32_t b = b0 + lane;
@@ -53,15 +62,15 @@ __global__ __launch_bounds__(256) void k_pairs(const DevMir *mir, const DevLive 
     if (kFill) {
       if (hit) {
         const uint64_t pos = at + __popcll(hits & ((1ull << lane) - 1ull));
-        pairs[2 * pos] = a;
-        pairs[2 * pos + 1] = b;
+        J.pairs[2 * pos] = a;
+        J.pairs[2 * pos + 1] = b;
       }
       at += __popcll(hits);
     } else {
       n += __popcll(hits);
     }
   }
-  if (!kFill && lane == 0) cnt[a] = n;
+  if (!kFill && lane == 0) J.cnt[a] = n;
 }
 
 // ---- per call ----------------------------------------------------------------------------
@@ -196,44 +205,75 @@ struct Work {
 };
 Work g_work[16];
 
-// Enumerates the interference pairs of u.mir from the intervals of `live` (whose analysis
-// must be complete on `stream`).  Synchronises the stream.
-int32_t build_pairs(vl_mir *mir, const vl_live *live, hipStream_t stream) {
-  const uint32_t V = mir->h.V;
-  if (V == 0) { mir->edges = nullptr; mir->n_edges = 0; mir->edges_built = true; return VL_OK; }
+// Enumerates the interference pairs of the programs that do not have them yet, from the
+// intervals of their analyses (which must be complete or enqueued on `stream`): one counting
+// launch over all of them, the offsets summed on the host, one filling launch.  Synchronises
+// the stream twice.
+int32_t build_pairs(const std::vector<std::pair<vl_mir *, const vl_live *>> &todo, hipStream_t stream) {
+  const size_t n = todo.size();
+  size_t total_v = 0;
+  uint32_t max_v = 0;
+  std::vector<size_t> base(n);
+  for (size_t j = 0; j < n; ++j) {
+    base[j] = total_v;
+    total_v += todo[j].first->h.V;
+    max_v = std::max(max_v, todo[j].first->h.V);
+  }
+  if (total_v == 0) {
+    for (auto &t : todo) { t.first->edges = nullptr; t.first->n_edges = 0; t.first->edges_built = true; }
+    return VL_OK;
+  }
+  // device scratch: counts, offsets, the job table; host: the same, pageable (copies wait for the stream)
   uint32_t *cnt = nullptr;
   uint64_t *off = nullptr;
-  VL_HIP(hipMalloc((void **)&cnt, (size_t)(V + 1) * 4));
-  hipError_t e = hipMalloc((void **)&off, (size_t)(V + 1) * 8);
-  if (e != hipSuccess) { (void)hipFree(cnt); return hip_fail(e); }
-  auto fail = [&](hipError_t err) { (void)hipFree(cnt); (void)hipFree(off); return hip_fail(err); };
-  const uint32_t blocks = (V + 3) / 4;
-  k_pairs<false><<<blocks, 256, 0, stream>>>(mir->dev, live->dev, cnt, nullptr, nullptr);
-  std::vector<uint32_t> h_cnt(V);
-  e = hipMemcpyAsync(h_cnt.data(), cnt, (size_t)V * 4, hipMemcpyDeviceToHost, stream);
+  PairJob *jobs_dev = nullptr;
+  std::vector<void *> fresh;   // pair buffers allocated here, handed to the programs on success
+  auto cleanup = [&]() { (void)hipFree(cnt); (void)hipFree(off); (void)hipFree(jobs_dev); };
+  auto fail = [&](hipError_t err) {
+    cleanup();
+    for (void *p : fresh) (void)hipFree(p);
+    return hip_fail(err);
+  };
+  hipError_t e = hipMalloc((void **)&cnt, total_v * 4);
+  if (e == hipSuccess) e = hipMalloc((void **)&off, total_v * 8);
+  if (e == hipSuccess) e = hipMalloc((void **)&jobs_dev, n * sizeof(PairJob));
+  if (e != hipSuccess) return fail(e);
+  std::vector<PairJob> jobs(n);
+  for (size_t j = 0; j < n; ++j) jobs[j] = PairJob{todo[j].first->dev, todo[j].second->dev, cnt + base[j], off + base[j], nullptr};
+  e = hipMemcpyAsync(jobs_dev, jobs.data(), n * sizeof(PairJob), hipMemcpyHostToDevice, stream);
+  if (e != hipSuccess) return fail(e);
+  const dim3 grid((max_v + 3) / 4, (uint32_t)n);
+  k_pairs<false><<<grid, 256, 0, stream>>>(jobs_dev);
+  std::vector<uint32_t> h_cnt(total_v);
+  e = hipMemcpyAsync(h_cnt.data(), cnt, total_v * 4, hipMemcpyDeviceToHost, stream);
   if (e == hipSuccess) e = hipStreamSynchronize(stream);
   if (e != hipSuccess) return fail(e);
-  std::vector<uint64_t> h_off(V + 1);
-  uint64_t total = 0;
-  for (uint32_t a = 0; a < V; ++a) { h_off[a] = total; total += h_cnt[a]; }
-  h_off[V] = total;
-  void *pairs = nullptr;
-  if (total) {
-    e = hipMalloc(&pairs, (size_t)total * 8);
-    if (e != hipSuccess) return fail(e);
-    e = hipMemcpyAsync(off, h_off.data(), (size_t)(V + 1) * 8, hipMemcpyHostToDevice, stream);
-    if (e == hipSuccess) {
-      k_pairs<true><<<blocks, 256, 0, stream>>>(mir->dev, live->dev, nullptr, off, (uint32_t *)pairs);
-      e = hipGetLastError();
+  std::vector<uint64_t> h_off(total_v), totals(n);
+  fresh.assign(n, nullptr);
+  for (size_t j = 0; j < n; ++j) {
+    uint64_t total = 0;
+    for (uint32_t a = 0; a < todo[j].first->h.V; ++a) { h_off[base[j] + a] = total; total += h_cnt[base[j] + a]; }
+    totals[j] = total;
+    if (total) {
+      e = hipMalloc(&fresh[j], (size_t)total * 8);
+      if (e != hipSuccess) return fail(e);
     }
-    if (e == hipSuccess) e = hipStreamSynchronize(stream);   // h_off and the scratch arrays go away below
-    if (e != hipSuccess) { (void)hipFree(pairs); return fail(e); }
+    jobs[j].pairs = (uint32_t *)fresh[j];
   }
-  (void)hipFree(cnt);
-  (void)hipFree(off);
-  mir->edges = pairs;
-  mir->n_edges = total;
-  mir->edges_built = true;
+  e = hipMemcpyAsync(off, h_off.data(), total_v * 8, hipMemcpyHostToDevice, stream);
+  if (e == hipSuccess) e = hipMemcpyAsync(jobs_dev, jobs.data(), n * sizeof(PairJob), hipMemcpyHostToDevice, stream);
+  if (e == hipSuccess) {
+    k_pairs<true><<<grid, 256, 0, stream>>>(jobs_dev);
+    e = hipGetLastError();
+  }
+  if (e == hipSuccess) e = hipStreamSynchronize(stream);   // the host vectors and the scratch go away below
+  if (e != hipSuccess) return fail(e);
+  cleanup();
+  for (size_t j = 0; j < n; ++j) {
+    todo[j].first->edges = fresh[j];
+    todo[j].first->n_edges = totals[j];
+    todo[j].first->edges_built = true;
+  }
   return VL_OK;
 }
 
@@ -255,10 +295,17 @@ extern "C" int32_t vl_count_violations_multi(const vl_count_job *jobs, uint32_t 
   Work &w = g_work[device];
   std::lock_guard<std::mutex> lock(w.mu);
   // the pairs of programs seen for the first time (the handle is the cache: not const here)
-  for (uint32_t j = 0; j < n_jobs; ++j) {
-    vl_mir *mir = const_cast<vl_mir *>(jobs[j].mir);
-    if (!mir->edges_built) {
-      const int32_t rc = build_pairs(mir, jobs[j].live, stream);
+  {
+    std::vector<std::pair<vl_mir *, const vl_live *>> todo;
+    for (uint32_t j = 0; j < n_jobs; ++j) {
+      vl_mir *mir = const_cast<vl_mir *>(jobs[j].mir);
+      if (!mir->edges_built) todo.emplace_back(mir, jobs[j].live);
+    }
+    // the same program may appear in several jobs
+    std::sort(todo.begin(), todo.end(), [](const auto &x, const auto &y) { return x.first < y.first; });
+    todo.erase(std::unique(todo.begin(), todo.end(), [](const auto &x, const auto &y) { return x.first == y.first; }), todo.end());
+    if (!todo.empty()) {
+      const int32_t rc = build_pairs(todo, stream);
       if (rc != VL_OK) return rc;
     }
   }
