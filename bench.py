@@ -18,11 +18,12 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
+ALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12  # plain (unpacked, non-FMA) vector operations: 39.3 T lane-operations/s
 
 
-def traffic_from_profile(kernel_source: str):
-    """HBM bytes per launch of the walk kernel from the committed counter runs,
-    or None when there are none for the kernel as it is now."""
+def from_profile(kernel_source: str, key: str):
+    """A per-launch figure of the walk kernel from the committed counter runs (HBM bytes,
+    vector instructions), or None when there is none for the kernel as it is now."""
     path = os.path.join(ROOT, "profiles", "k_walk_config5_traffic.json")
     if not os.path.exists(path):
         return None
@@ -32,7 +33,7 @@ def traffic_from_profile(kernel_source: str):
         sha = hashlib.sha256(f.read()).hexdigest()
     if rec.get("source_sha256") != sha:
         return None
-    return rec.get("hbm_bytes_per_launch")
+    return rec.get(key)
 
 
 def cpu_baseline(workload, min_seconds=10.0, max_seconds=30.0):
@@ -282,6 +283,13 @@ def main():
         assert all(bool((a == b).all()) for a, b in zip(oo, outs)), "results differ between streams"
     achieved = alg_bytes / walk_avg_s / 1e9
     src = os.path.join(ROOT, "paper_2506_17506_amd", "csrc", "vl_verify.hip")
+    # the other bound: vector instructions of the launch (counted once with the profiler,
+    # 64 lane-operations each) against 256 compute units x 64 lanes x 2.4 GHz
+    valu = from_profile(src, "valu_insts_per_launch")
+    alu = None
+    if valu:
+        alu = {"achieved": valu * 64 / walk_avg_s / 1e12, "peak": ALU_PEAK_TOPS, "unit": "T lane-op/s",
+               "frac": valu * 64 / walk_avg_s / 1e12 / ALU_PEAK_TOPS, "vector_instructions_per_launch": valu}
     rec = {
         "metric": "candidate allocations verified/sec at K=100",
         "value": w.n_candidates * args.steps / dt,
@@ -309,9 +317,10 @@ def main():
                           "masks_per_s": len(mask_queries) / mask_us * 1e6},
         "roofline": {"bound": "hbm", "kernel": "k_walk", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": traffic_from_profile(src),
+                     "traffic": from_profile(src, "hbm_bytes_per_launch"),
                      "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_ms": walk_avg_s * 1e3,
-                     "measured_stream_read": stream_read, "frac_of_measured_stream_read": achieved / stream_read},
+                     "measured_stream_read": stream_read, "frac_of_measured_stream_read": achieved / stream_read,
+                     "alu": alu},
     }
     if not args.no_cpu:
         rec["cpu_baseline"] = cpu_baseline(w)
