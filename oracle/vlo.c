@@ -82,17 +82,30 @@ void vlo_points(const vlo_mir *m, const uint8_t *live_out, uint32_t *live_after)
 void vlo_occupancy(const vlo_mir *m, const uint32_t *live_after, uint32_t *P) {
   const uint32_t W = words_per_row(m);
   memcpy(P, live_after, (size_t)m->n_instr * W * 4);
-  for (uint32_t i = 0; i < m->n_instr; ++i)
-    for (uint32_t o = m->instr_occ_off[i]; o < m->instr_occ_off[i + 1]; ++o)
+  for (uint32_t i = 0; i < m->n_instr; ++i) {
+    int early = 0;
+    for (uint32_t o = m->instr_occ_off[i]; o < m->instr_occ_off[i + 1]; ++o) {
       if (m->occ_flags[o] & VLO_OCC_DEF) bit_set(P + (size_t)i * W, m->occ_vreg[o]);
+      if (m->occ_flags[o] & VLO_OCC_EARLY) early = 1;
+    }
+    /* an early-clobber definition: what the instruction reads is still occupied */
+    if (early)
+      for (uint32_t o = m->instr_occ_off[i]; o < m->instr_occ_off[i + 1]; ++o)
+        if (m->occ_flags[o] & VLO_OCC_USE) bit_set(P + (size_t)i * W, m->occ_vreg[o]);
+  }
 }
 
-void vlo_kill_flags(const vlo_mir *m, const uint32_t *P, uint8_t *occ_kill) {
+/* a USE of v at i is the last one iff v is neither live after i nor written at i */
+void vlo_kill_flags(const vlo_mir *m, const uint32_t *live_after, uint8_t *occ_kill) {
   const uint32_t W = words_per_row(m);
   for (uint32_t i = 0; i < m->n_instr; ++i)
-    for (uint32_t o = m->instr_occ_off[i]; o < m->instr_occ_off[i + 1]; ++o)
-      occ_kill[o] = (uint8_t)((m->occ_flags[o] & VLO_OCC_USE) &&
-                              !bit_get(P + (size_t)i * W, m->occ_vreg[o]));
+    for (uint32_t o = m->instr_occ_off[i]; o < m->instr_occ_off[i + 1]; ++o) {
+      int written = 0;
+      for (uint32_t x = m->instr_occ_off[i]; x < m->instr_occ_off[i + 1]; ++x)
+        if ((m->occ_flags[x] & VLO_OCC_DEF) && m->occ_vreg[x] == m->occ_vreg[o]) written = 1;
+      occ_kill[o] = (uint8_t)((m->occ_flags[o] & VLO_OCC_USE) && !written &&
+                              !bit_get(live_after + (size_t)i * W, m->occ_vreg[o]));
+    }
 }
 
 /* ---- live intervals ----------------------------------------------------- */

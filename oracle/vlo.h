@@ -41,6 +41,11 @@ extern "C" {
 
 #define VLO_OCC_DEF 1u
 #define VLO_OCC_USE 2u
+/* Early-clobber: a DEF with this bit is written before the instruction has read its
+ * operands, so it may not share a register with any of them.  Reading taken: the
+ * values an instruction with such a definition reads stay occupied through it, i.e.
+ * they belong to P(i) even when they die there (the bit acts on the whole instruction). */
+#define VLO_OCC_EARLY 4u
 
 typedef struct {
   uint32_t n_instr, n_vreg, n_block, n_occ, n_class, n_edge;
@@ -78,7 +83,7 @@ void vlo_occupancy(const vlo_mir *m, const uint32_t *live_after, uint32_t *P);
 
 /* Kill flag of each occurrence: 1 iff it is a USE of v at i and v is not in
  * P(i); 0 otherwise (in particular for pure DEF occurrences). [n_occ] */
-void vlo_kill_flags(const vlo_mir *m, const uint32_t *P, uint8_t *occ_kill);
+void vlo_kill_flags(const vlo_mir *m, const uint32_t *live_after, uint8_t *occ_kill);
 
 /* Live intervals: for each vreg the maximal runs of {i : v in P(i)} in linear
  * order as half-open [start,end).  seg_off[V+1]; seg holds up to cap pairs.

@@ -114,7 +114,7 @@ def analyze(m, interference: bool = True, threads: int = 1) -> Analysis:
     P = np.zeros((N, W), np.uint32)
     L.vlo_occupancy(C.byref(s), _p(live_after), _p(P))
     kill = np.zeros(O, np.uint8)
-    L.vlo_kill_flags(C.byref(s), _p(P), _p(kill))
+    L.vlo_kill_flags(C.byref(s), _p(live_after), _p(kill))
     seg_off = np.zeros(V + 1, np.uint32)
     hull = np.zeros((V, 2), np.uint32)
     n = L.vlo_segments(C.byref(s), _p(P), _p(seg_off), None, C.c_uint64(0), _p(hull))

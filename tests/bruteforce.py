@@ -87,9 +87,15 @@ def live_after_by_search(m):
     return res
 
 
+def has_early_clobber(m, i):
+    return any(m.occ_flags[o] & 4 for o in range(m.instr_occ_off[i], m.instr_occ_off[i + 1]))
+
+
 def occupancy(m, live_after):
-    _, defs = uses_defs(m)
-    return [live_after[i] | defs[i] for i in range(m.n_instr)]
+    """P(i): live after i, or written at i, or (an early-clobber definition at i is written
+    before the operands are read) read at i."""
+    uses, defs = uses_defs(m)
+    return [live_after[i] | defs[i] | (uses[i] if has_early_clobber(m, i) else set()) for i in range(m.n_instr)]
 
 
 def first_occ(m):

@@ -14,6 +14,7 @@ import numpy as np
 
 OCC_DEF = 1
 OCC_USE = 2
+OCC_EARLY = 4   # on a DEF: written before the instruction has read its operands
 
 
 @dataclass
@@ -88,7 +89,8 @@ class Mir:
         blocks[b] is a list of instructions; an instruction is a tuple
         (defs, uses) of vreg-id sequences, operands listed defs first.
         A vreg id may be given as ('du', v) inside defs to make a single
-        occurrence that is both DEF and USE."""
+        occurrence that is both DEF and USE, or as ('ec', v) to make an
+        early-clobber DEF."""
         blk_start = [0]
         occ_off = [0]
         occ_v, occ_f = [], []
@@ -97,7 +99,7 @@ class Mir:
                 for d in defs:
                     if isinstance(d, tuple):
                         occ_v.append(d[1])
-                        occ_f.append(OCC_DEF | OCC_USE)
+                        occ_f.append(OCC_DEF | (OCC_EARLY if d[0] == "ec" else OCC_USE))
                     else:
                         occ_v.append(d)
                         occ_f.append(OCC_DEF)

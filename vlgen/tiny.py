@@ -12,10 +12,11 @@ from .mir import Mir, OCC_DEF, OCC_USE
 
 def tiny_mir(seed: int, strict: bool = True, max_blocks: int = 4, max_instr: int = 4,
              max_vreg: int = 6, two_classes: bool = True, wide: bool = True,
-             reserved: bool = False) -> Mir:
+             reserved: bool = False, early: float = 0.0) -> Mir:
     """A random CFG of up to max_blocks blocks in which every non-entry block
     has a predecessor placed before it.  With strict, the entry block first
-    defines every vreg, so nothing is live into the program."""
+    defines every vreg, so nothing is live into the program.  `early`: share of
+    the defining instructions whose first plain definition is early-clobber."""
     rng = np.random.default_rng(seed)
     nb = int(rng.integers(1, max_blocks + 1))
     V = int(rng.integers(1, max_vreg + 1))
@@ -52,6 +53,15 @@ def tiny_mir(seed: int, strict: bool = True, max_blocks: int = 4, max_instr: int
             uses = [int(x) for x in rng.integers(0, V, nu)]
             blk.append((defs, uses))
         blocks.append(blk)
+    if early > 0:   # marks drawn from a stream of their own: the programs stay what they were
+        rng_e = np.random.default_rng([seed, 0xEC])
+        for blk in blocks:
+            for k, (defs, uses) in enumerate(blk):
+                plain = [j for j, d in enumerate(defs) if not isinstance(d, tuple)]
+                if plain and rng_e.random() < early:
+                    defs = list(defs)
+                    defs[plain[0]] = ("ec", defs[plain[0]])
+                    blk[k] = (defs, uses)
     res = None
     if reserved:
         res = np.zeros((n_class, 16), np.uint32)
