@@ -27,7 +27,8 @@
  * contiguous range [blk_start[b], blk_start[b+1]), block 0 is the entry;
  * operand occurrences are numbered in instruction order, then operand order.
  * An instruction reads its USE operands before it writes its DEF operands
- * (a DEF may reuse the register of an operand that dies at that instruction).
+ * (a DEF may reuse the register of an operand that dies at that instruction),
+ * unless a DEF is flagged VL_OCC_EARLY.
  * Bitset rows have W = ceil(n_vreg/32) words; vreg v is bit (v & 31) of word
  * (v >> 5).
  */
@@ -56,6 +57,11 @@ enum {
 
 #define VL_OCC_DEF 1u
 #define VL_OCC_USE 2u
+/* Early-clobber, on a DEF only: the value is written before the instruction has read its
+ * operands, so it cannot share a register with any of them.  The values an instruction
+ * with such a definition reads stay occupied through it: they belong to P(i) even when
+ * they die there (the bit acts on the whole instruction). */
+#define VL_OCC_EARLY 4u
 
 /* vl_liveness flags */
 #define VL_DENSE_POINTS 1u /* also materialise live_after[N][W] */
@@ -68,7 +74,7 @@ typedef struct {
   const uint32_t *succ;           /* [n_edge] successor block ids */
   const uint32_t *instr_occ_off;  /* [n_instr+1] CSR offsets into occurrences */
   const uint32_t *occ_vreg;       /* [n_occ] */
-  const uint8_t *occ_flags;       /* [n_occ] VL_OCC_DEF | VL_OCC_USE */
+  const uint8_t *occ_flags;       /* [n_occ] VL_OCC_DEF | VL_OCC_USE, VL_OCC_EARLY on a DEF */
   const uint8_t *vreg_class;      /* [n_vreg] */
   const uint8_t *vreg_width;      /* [n_vreg] width in 32-bit registers, 1..32 */
   const uint8_t *vreg_align;      /* [n_vreg] base must be a multiple of this, 1..32 */
@@ -121,7 +127,7 @@ typedef struct {
   const uint32_t *live_in;        /* [n_block][W] */
   const uint32_t *live_out;       /* [n_block][W] */
   const uint32_t *live_after;     /* [n_instr][W], NULL unless VL_DENSE_POINTS */
-  const uint8_t *occ_kill;        /* [n_occ] 1 iff a USE of v at i and v not in P(i) */
+  const uint8_t *occ_kill;        /* [n_occ] 1 iff a USE of v at i, v neither live after i nor written at i */
   const uint32_t *seg_off;        /* [n_vreg+1] CSR offsets into seg */
   const uint32_t *seg;            /* [n_seg][2] maximal runs of {i : v in P(i)} as [start,end) */
   const uint32_t *hull;           /* [n_vreg][2] [min start, max end) or [0,0) */

@@ -34,7 +34,9 @@ struct DevMir {
   const uint32_t VL_GLOBAL *instr_blk;       // [N] block of each instruction
   const uint32_t VL_GLOBAL *vattr;           // [V] packed attributes, see attr_* below
   const uint8_t VL_GLOBAL *occ_flags;        // [O]
-  const uint64_t VL_GLOBAL *occ_rec;         // [O] vreg | (instruction << 2 | flags) << 32: one read instead of three
+  const uint64_t VL_GLOBAL *occ_rec;         // [O] vreg | (instruction << 2 | DEF/USE flags) << 32: one read instead of three
+  const uint8_t VL_GLOBAL *instr_keep;       // [N] 1 iff the instruction has an early-clobber definition: what it reads
+                                             // stays occupied through it
   uint32_t has_reserved;
   uint16_t class_size[kMaxClass];
   uint16_t class_word[kMaxClass];  // first occupancy word of the class
@@ -104,7 +106,8 @@ constexpr uint32_t kEvtTested = 1u << 31;  // occupy with test (a definition); o
 constexpr uint8_t kRolePreKill = 1, kRoleTestSet = 2, kRolePostKill = 4, kRoleFirst = 8;
 constexpr uint8_t kRoleKill = 16;   // the occurrence's kill flag, copied to occ_kill in occurrence order later
 // Per sorted-entry info bits.
-constexpr uint8_t kEntLiveAfter = 1, kEntHasUse = 2, kEntHasDef = 4, kEntGroupStart = 8;
+constexpr uint8_t kEntLiveAfter = 1, kEntHasUse = 2, kEntHasDef = 4, kEntGroupStart = 8,
+                  kEntKept = 16;   // read by an instruction with an early-clobber definition: in P(i) whatever follows
 
 // Liveness analysis of one kernel on the device.
 struct DevLive {

@@ -501,7 +501,10 @@ __global__ __launch_bounds__(kEvtThreads) void k_events(MIRS) {
   const uint32_t fl = ifl & 3u;
   const bool kill = (fl & VL_OCC_USE) && !has_def && !la;
   uint8_t role = 0;
-  if (!has_def && !la && e == first_use) role |= kRolePreKill;
+  // an instruction with an early-clobber definition keeps what it reads occupied until it has
+  // written: the operand that dies here is released after the definitions have been tested
+  const bool keeps = m.instr_keep[i] != 0;
+  if (!has_def && !la && e == first_use) role |= keeps ? kRolePostKill : kRolePreKill;
   if (has_def && e == first_def) {
     if (!has_use) role |= kRoleTestSet;
     if (!la) role |= kRolePostKill;
@@ -531,7 +534,7 @@ __global__ __launch_bounds__(kEvtThreads) void k_events(MIRS) {
     L.chk[o] = r;
   }
   L.ent_info[e] = (uint8_t)((la ? kEntLiveAfter : 0) | (has_use ? kEntHasUse : 0) | (has_def ? kEntHasDef : 0) |
-                            (e == gs ? kEntGroupStart : 0));
+                            (e == gs ? kEntGroupStart : 0) | (keeps && has_use ? kEntKept : 0));
 
   // ---- live intervals, counting pass (the filling pass and the reasoning are at f_seg) ----
   // The first entry of each mention group owns the stretch from i up to the next mention of v
@@ -541,12 +544,15 @@ __global__ __launch_bounds__(kEvtThreads) void k_events(MIRS) {
   bool cur;   // was v occupied just before this stretch?
   if (i == 0) cur = false;
   else if (gs > lo && (ent(gs - 1) >> 2) == i - 1) {
-    bool prev_def = false;
-    for (uint32_t x = gs; x-- > lo && (ent(x) >> 2) == i - 1;) prev_def |= (ent(x) & VL_OCC_DEF) != 0;
+    bool prev_def = false, prev_use = false;
+    for (uint32_t x = gs; x-- > lo && (ent(x) >> 2) == i - 1;) {
+      prev_def |= (ent(x) & VL_OCC_DEF) != 0;
+      prev_use |= (ent(x) & VL_OCC_USE) != 0;
+    }
     const uint32_t pb = m.instr_blk[i - 1];
     // live after i - 1: this group is the next mention; in another block the block's live-out decides
     const bool prev_la = pb == b ? has_use : bit_get(L.live_out + (size_t)pb * m.W, v);
-    cur = prev_def || prev_la;
+    cur = prev_def || prev_la || (prev_use && m.instr_keep[i - 1]);
   } else if (i > m.blk_start[b]) cur = has_use;
   else cur = bit_get(L.live_out + (size_t)(b - 1) * m.W, v);
   uint8_t sf = cur ? kOpenBefore : 0;
@@ -560,7 +566,7 @@ __global__ __launch_bounds__(kEvtThreads) void k_events(MIRS) {
     if (!member && cur) sf |= s == i ? kEndI : s == i + 1 ? kEndI1 : kAgain;
     cur = member;
   };
-  span(i, i + 1, has_def || la);
+  span(i, i + 1, has_def || la || (keeps && has_use));
   const uint32_t i2 = ge < hi ? ent(ge) >> 2 : m.N;
   const uint32_t b2 = ge < hi ? m.instr_blk[i2] : m.B;
   if (b2 == b) {
@@ -757,7 +763,7 @@ __device__ inline void f_seg_fill(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &
   uint32_t ge = e + 1;
   while (ge < hi && (L.ent_instr[ge] >> 2) == i) ++ge;
   const bool la = (info & kEntLiveAfter) != 0;
-  span(i, i + 1, (info & kEntHasDef) || la);
+  span(i, i + 1, (info & (kEntHasDef | kEntKept)) || la);
   const uint32_t i2 = ge < hi ? L.ent_instr[ge] >> 2 : m.N;
   const uint32_t b2 = ge < hi ? m.instr_blk[i2] : m.B;
   if (b2 == b) {

@@ -56,7 +56,9 @@ static int32_t validate(const vl_mir_desc *d) {
   }
   for (uint32_t o = 0; o < d->n_occ; ++o) {
     if (d->occ_vreg[o] >= d->n_vreg) return VL_E_RANGE;
-    if (d->occ_flags[o] == 0 || (d->occ_flags[o] & ~(VL_OCC_DEF | VL_OCC_USE))) return VL_E_RANGE;
+    const uint8_t f = d->occ_flags[o];
+    if ((f & (VL_OCC_DEF | VL_OCC_USE)) == 0 || (f & ~(VL_OCC_DEF | VL_OCC_USE | VL_OCC_EARLY))) return VL_E_RANGE;
+    if ((f & VL_OCC_EARLY) && !(f & VL_OCC_DEF)) return VL_E_RANGE;
   }
   for (uint32_t v = 0; v < d->n_vreg; ++v) {
     if (d->vreg_class[v] >= d->n_class) return VL_E_RANGE;
@@ -98,7 +100,10 @@ extern "C" int32_t vl_mir_create(const vl_mir_desc *d, vl_mir **out) {
   for (uint32_t v = 0; v < V; ++v) vattr[v] = vl::attr_pack(d->vreg_class[v], d->vreg_width[v], d->vreg_align[v]);
   std::vector<uint64_t> occ_rec(O ? O : 1);
   for (uint32_t o = 0; o < O; ++o)
-    occ_rec[o] = (uint64_t)d->occ_vreg[o] | ((uint64_t)((occ_instr[o] << 2) | d->occ_flags[o]) << 32);
+    occ_rec[o] = (uint64_t)d->occ_vreg[o] | ((uint64_t)((occ_instr[o] << 2) | (d->occ_flags[o] & 3u)) << 32);
+  std::vector<uint8_t> instr_keep(N, 0);
+  for (uint32_t o = 0; o < O; ++o)
+    if (d->occ_flags[o] & VL_OCC_EARLY) instr_keep[occ_instr[o]] = 1;
 
   Bump bump;
   size_t o_blk = bump.take((B + 1) * 4), o_soff = bump.take((B + 1) * 4), o_succ = bump.take((size_t)(E ? E : 1) * 4);
@@ -106,6 +111,7 @@ extern "C" int32_t vl_mir_create(const vl_mir_desc *d, vl_mir **out) {
   size_t o_oi = bump.take((size_t)(O ? O : 1) * 4), o_ib = bump.take((size_t)N * 4);
   size_t o_va = bump.take((size_t)(V ? V : 1) * 4), o_of = bump.take((size_t)(O ? O : 1));
   size_t o_rec = bump.take((size_t)(O ? O : 1) * 8);
+  size_t o_keep = bump.take((size_t)N);
   size_t o_dev = bump.take(sizeof(vl::DevMir));
 
   vl_mir *m = new (std::nothrow) vl_mir;
@@ -130,6 +136,7 @@ extern "C" int32_t vl_mir_create(const vl_mir_desc *d, vl_mir **out) {
   up(o_va, vattr.data(), (size_t)V * 4);
   up(o_of, d->occ_flags, (size_t)O);
   up(o_rec, occ_rec.data(), (size_t)O * 8);
+  up(o_keep, instr_keep.data(), (size_t)N);
 
   vl::DevMir &h = m->h;
   h.N = N; h.V = V; h.B = B; h.O = O; h.C = d->n_class; h.E = E; h.W = (V + 31) / 32;
@@ -143,6 +150,7 @@ extern "C" int32_t vl_mir_create(const vl_mir_desc *d, vl_mir **out) {
   h.vattr = (const uint32_t VL_GLOBAL *)(base + o_va);
   h.occ_flags = (const uint8_t VL_GLOBAL *)(base + o_of);
   h.occ_rec = (const uint64_t VL_GLOBAL *)(base + o_rec);
+  h.instr_keep = (const uint8_t VL_GLOBAL *)(base + o_keep);
   // mask words: classes smallest first, so that the 16 words every class may address from
   // its first one mostly fall on words of later classes
   std::vector<uint32_t> order(d->n_class);

@@ -28,13 +28,14 @@ def _attrs(rng, V: int):
 
 
 def mixed_mir(seed: int, n_instr: int = 2500, n_global: int = 24, reserved: bool = False,
-              wide_instr: int = 4, stretch: int = 0, redefine: bool = True) -> Mir:
+              wide_instr: int = 4, stretch: int = 0, redefine: bool = True, early: float = 0.0) -> Mir:
     """n_instr instructions (about) in 7 blocks: entry, a loop of two blocks, a
     diamond, a second loop, exit.  `wide_instr` instructions carry 40-60
     operands.  `stretch` > 0 appends that many filler instructions before the
     exit block, which reads the globals once more (a gap of many operand slots
     between two mentions of one value).  With redefine=False no value is written
-    twice (no redefinitions, no read-modify-write operands)."""
+    twice (no redefinitions, no read-modify-write operands).  `early`: share of the
+    defining instructions whose first plain definition is early-clobber."""
     rng = np.random.default_rng(seed)
     n_blocks = 7
     per = max(8, n_instr // n_blocks)
@@ -94,6 +95,15 @@ def mixed_mir(seed: int, n_instr: int = 2500, n_global: int = 24, reserved: bool
         if b == n_blocks - 1:
             blk.append(([], list(range(n_global))))
         blocks.append(blk)
+    if early > 0:   # marks drawn from a stream of their own: the programs stay what they were
+        rng_e = np.random.default_rng([seed, 0xEC])
+        for blk in blocks:
+            for k, (defs, uses) in enumerate(blk):
+                plain = [j for j, d in enumerate(defs) if not isinstance(d, tuple)]
+                if plain and uses and rng_e.random() < early:
+                    defs = list(defs)
+                    defs[plain[0]] = ("ec", defs[plain[0]])
+                    blk[k] = (defs, uses)
     res = None
     if reserved:
         res = np.zeros((3, 16), np.uint32)
