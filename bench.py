@@ -265,6 +265,36 @@ def main():
     count_ms = (time.perf_counter() - t1) / 3 * 1e3
     kinds = np.concatenate([o.cpu().numpy()[:, 0] for o in count_outs])
 
+    # the same candidates stored occurrence-major (how a batched decoder leaves them), not part
+    # of the timed step: verification only, results compared with the row-major ones
+    t_jobs, t_keep, t_outs = [], [], []
+    for m, l, d, r in zip(mirs, lives, dev_rows, w.rows):
+        K, O = r.shape
+        ld_t = (K + 7) // 8 * 8
+        t = torch.zeros((max(O, 1), ld_t), dtype=torch.int16, device="cuda")
+        t[:O, :K] = d[:, :O].t()
+        o = torch.zeros((K, 4), dtype=torch.int32, device="cuda")
+        t_keep.append(t)
+        t_outs.append(o)
+        t_jobs.append((m, l, t, K, ld_t, o))
+    t_jobs = vl.make_jobs(t_jobs)
+    vl.vl_verify_multi(jobs, stream)                 # fresh row-major results to compare with
+    vl.vl_verify_multi_occ_major(t_jobs, stream)
+    torch.cuda.synchronize()
+    assert all(bool((a == b).all()) for a, b in zip(t_outs, outs)), "occurrence-major results differ"
+    ev_a, ev_b = C.c_void_p(), C.c_void_p()
+    assert hip.hipEventCreate(C.byref(ev_a)) == 0 and hip.hipEventCreate(C.byref(ev_b)) == 0
+    t1 = time.perf_counter()
+    for _ in range(5):
+        vl.vl_verify_time_next(ev_a.value, ev_b.value)
+        vl.vl_verify_multi_occ_major(t_jobs, stream)
+    torch.cuda.synchronize()
+    occ_major_ms = (time.perf_counter() - t1) / 5 * 1e3
+    ms = C.c_float()
+    assert hip.hipEventElapsedTime(C.byref(ms), ev_a, ev_b) == 0
+    occ_major_walk_ms = ms.value
+    del t_keep, t_jobs
+
     # what a plain streaming read reaches on this device (context for the roofline figure):
     # the library's read-only probe over 1 GiB, best of five
     probe = torch.ones(1 << 28, dtype=torch.int32, device="cuda")
@@ -313,6 +343,7 @@ def main():
         "all_violations": {"ms_per_pass": count_ms, "first_pass_ms": count_first_ms,
                            "candidates_per_s": w.n_candidates / count_ms * 1e3,
                            "kinds_histogram": np.bincount(kinds, minlength=8).tolist()},
+        "occurrence_major": {"verify_ms": occ_major_ms, "walk_ms": occ_major_walk_ms},
         "decoding_mask": {"queries": len(mask_queries), "us_per_call": mask_us,
                           "masks_per_s": len(mask_queries) / mask_us * 1e6},
         "roofline": {"bound": "hbm", "kernel": "k_walk", "achieved": achieved, "peak": HBM_PEAK_GBS,

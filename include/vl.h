@@ -167,6 +167,14 @@ typedef struct {
 } vl_job;
 int32_t vl_verify_multi(const vl_job *jobs, uint32_t n_jobs, vl_stream stream);
 
+/* The same for candidates stored occurrence-major, which is how a batched decoder leaves
+ * them (one step emits one occurrence of all K samples): jobs[j].cand is [n_occ][ld] with
+ * cand[o * ld + k] the register of occurrence o in candidate k, ld >= K.  Requires cand on a
+ * 16-byte boundary and ld a multiple of 8 (VL_E_SHAPE otherwise); the up to 7 elements of
+ * padding after the K-th candidate of each occurrence are read and ignored.  Results as for
+ * vl_verify_multi. */
+int32_t vl_verify_multi_occ_major(const vl_job *jobs, uint32_t n_jobs, vl_stream stream);
+
 /* Regeneration-loop reductions (Section 3.4, last paragraph: samples are tried until the
  * verifier accepts one or the attempts are exhausted; Section 4.2: Pass@K, average and
  * maximum number of attempts).  Reads the results a preceding vl_verify_multi /

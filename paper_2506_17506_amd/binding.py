@@ -87,6 +87,8 @@ def load():
         L.vl_verify_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint64, C.c_void_p, C.c_void_p]
         L.vl_verify_multi.restype = C.c_int32
         L.vl_verify_multi.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p]
+        L.vl_verify_multi_occ_major.restype = C.c_int32
+        L.vl_verify_multi_occ_major.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p]
         L.vl_summarize_multi.restype = C.c_int32
         L.vl_summarize_multi.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.vl_count_violations_multi.restype = C.c_int32
@@ -218,6 +220,14 @@ def vl_verify_multi(jobs, stream=None) -> None:
     rc = load().vl_verify_multi(arr, len(arr), _stream_ptr(stream))
     if rc != 0:
         raise VlError(rc, "vl_verify_multi")
+
+
+def vl_verify_multi_occ_major(jobs, stream=None) -> None:
+    """jobs as for vl_verify_multi, but cand is [n_occ][ld] (occurrence-major), ld >= K."""
+    arr = jobs if isinstance(jobs, C.Array) else make_jobs(jobs)
+    rc = load().vl_verify_multi_occ_major(arr, len(arr), _stream_ptr(stream))
+    if rc != 0:
+        raise VlError(rc, "vl_verify_multi_occ_major")
 
 
 def vl_summarize_multi(jobs, summaries, stats=None, stream=None) -> None:

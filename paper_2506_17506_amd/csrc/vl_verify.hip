@@ -54,7 +54,7 @@ struct DevJob {
   const uint16_t *cand;
   vl_result *out;
   uint64_t ld;
-  uint32_t K, rows, n_groups, unit_base, n_units, fast, pad0, pad1;
+  uint32_t K, rows, n_groups, unit_base, n_units, fast, transposed, pad1;   // transposed: cand is [occurrence][candidate]
 };
 
 __device__ inline uint32_t find_job(const DevJob *jobs, uint32_t n_jobs, uint32_t unit) {
@@ -64,6 +64,11 @@ __device__ inline uint32_t find_job(const DevJob *jobs, uint32_t n_jobs, uint32_
     if (jobs[mid].unit_base <= unit) lo = mid; else hi = mid;
   }
   return lo;
+}
+
+// register of occurrence o in candidate k, in either layout
+__device__ inline uint32_t cand_at(const DevJob &J, uint32_t k, uint32_t o) {
+  return J.transposed ? J.cand[(uint64_t)o * J.ld + k] : J.cand[(uint64_t)k * J.ld + o];
 }
 
 __global__ void k_init(const DevJob *__restrict__ jobs) {
@@ -115,6 +120,11 @@ __device__ inline uint32_t staged_row(uint32_t lane, uint32_t q) {
   return (q & 1u) + 2u * rr + 16u * ((k >> 2) ^ (q >> 2)) + 32u * ((q >> 1) & 1u);
 }
 
+// kT: the candidates are stored occurrence-major, cand[occurrence][candidate] with pitch ld.
+// A chunk is then 64 occurrences x 8 pieces of 16 bytes (8 candidates) that already have the
+// ring's layout: lane (occurrence o8, piece k) of pass q copies piece k of occurrence
+// 8 q + o8, eight lanes reading one 128-byte line.
+template <bool kT>
 __device__ inline void load_chunk(Walk &w, uint32_t c0, uint32_t j) {
   const uint32_t c = c0 + (w.lane & 7u) * 8u;
 #pragma unroll
@@ -122,6 +132,14 @@ __device__ inline void load_chunk(Walk &w, uint32_t c0, uint32_t j) {
     const uint32_t q = j + kCheckWaves * h;
     w.pre[h][0] = w.pre[h][1] = w.pre[h][2] = w.pre[h][3] = 0;
     if (q >= 8u) continue;
+    if (kT) {
+      const uint32_t o = c0 + q * 8u + (w.lane >> 3), piece = w.lane & 7u;
+      if (piece * 8u < w.nrows && o < w.n_occ) {   // the 16 bytes lie inside the occurrence's pitch (a multiple of 8)
+        const u32x4 x = *reinterpret_cast<const u32x4 VL_GLOBAL *>(w.rows + (uint64_t)o * w.ld + piece * 8u);
+        w.pre[h][0] = x.x; w.pre[h][1] = x.y; w.pre[h][2] = x.z; w.pre[h][3] = x.w;
+      }
+      continue;
+    }
     const uint32_t r = staged_row(w.lane, q);
     if (r < w.nrows && c < w.n_occ) {
       const uint16_t VL_GLOBAL *src = w.rows + (uint64_t)r * w.ld + c;
@@ -140,13 +158,23 @@ __device__ inline void load_chunk(Walk &w, uint32_t c0, uint32_t j) {
 }
 
 // writes the chunk held in registers into the ring as chunk [c0, c0 + 64)
-template <uint32_t kRingStride>
+template <uint32_t kRingStride, bool kT>
 __device__ inline void store_chunk(const Walk &w, uint32_t c0, uint32_t j) {
   const uint32_t c = c0 + (w.lane & 7u) * 8u;
 #pragma unroll
   for (int h = 0; h < kStagePasses; ++h) {
     const uint32_t q = j + kCheckWaves * h;
     if (q >= 8u) continue;
+    if (kT) {
+      // 8 candidates of one occurrence: two 8-byte stores (ring slots start on 8-byte
+      // boundaries); what would fall beyond the slot's pitch is left out
+      const uint32_t o = c0 + q * 8u + (w.lane >> 3), piece = w.lane & 7u;
+      const uint32_t dst = (w.ring16 + (o % kRing) * kRingStride + piece * 8u) >> 2;   // in 8-byte units
+      uint64_t *lds64 = reinterpret_cast<uint64_t *>(vl_lds);
+      if (piece * 8u + 4u <= kRingStride) lds64[dst] = (uint64_t)w.pre[h][0] | ((uint64_t)w.pre[h][1] << 32);
+      if (piece * 8u + 8u <= kRingStride) lds64[dst + 1] = (uint64_t)w.pre[h][2] | ((uint64_t)w.pre[h][3] << 32);
+      continue;
+    }
     const uint32_t r = staged_row(w.lane, q);
     if (kRingStride < 64u && r >= kRingStride) continue;   // rows the narrow ring has no room for (none of them is in use)
     const uint32_t dst = w.ring16 + (c % kRing) * kRingStride + r;
@@ -163,10 +191,16 @@ __device__ inline bool in_ring(const Walk &w, uint32_t o) {
 }
 
 // value of occurrence o (uniform) in this lane's row
-template <uint32_t kRingStride>
+// value of occurrence o in this lane's row, from memory
+template <bool kT>
+__device__ inline uint32_t from_memory(const Walk &w, uint32_t o) {
+  return kT ? w.rows[(uint64_t)o * w.ld + w.row] : w.rows[(uint64_t)w.row * w.ld + o];
+}
+
+template <uint32_t kRingStride, bool kT>
 __device__ inline uint32_t fetch(const Walk &w, uint32_t o) {
   if (in_ring(w, o)) return VL_LDS16[w.ring16 + (o % kRing) * kRingStride + w.row];
-  return w.rows[(uint64_t)w.row * w.ld + o];
+  return from_memory<kT>(w, o);
 }
 
 // Address of the mask word holding register p of a class, and the mask of the tuple.
@@ -211,7 +245,7 @@ __device__ inline bool unrealizable(const DevMir VL_GLOBAL &m, uint32_t attr, ui
   return bad;
 }
 
-template <uint32_t kRingStride>
+template <uint32_t kRingStride, bool kT>
 __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(6))) void k_walk(const DevJob *__restrict__ jobs, uint32_t n_jobs) {
   const DevJob VL_GLOBAL &J = as_global(jobs)[find_job(jobs, n_jobs, blockIdx.x)];
   const DevMir VL_GLOBAL &m = *as_global(J.mir);
@@ -232,10 +266,10 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(6)
   // the occupancy role moves from wavefront to wavefront with the workgroup index, so
   // that neighbouring workgroups do not all put it on the same SIMD
   const uint32_t role = __builtin_amdgcn_readfirstlane(((threadIdx.x >> 6) + blockIdx.x) % (1u + kCheckWaves));
-  w.nrows = min(J.rows, J.K - row0);
+  w.nrows = group + 1 == J.n_groups ? J.K - row0 : J.rows;   // the last group takes what is left
   const bool active = w.lane < w.nrows;
   w.row = active ? w.lane : 0u;
-  w.rows = as_global(J.cand) + (uint64_t)row0 * J.ld;
+  w.rows = as_global(J.cand) + (kT ? (uint64_t)row0 : (uint64_t)row0 * J.ld);
   w.ld = J.ld;
   w.n_occ = m.O;
   w.fast = J.fast;
@@ -299,7 +333,7 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(6)
         const uint32_t sw = __builtin_amdgcn_readlane(r.w, j), o = sw & 0xFFFFFFu;
         const bool slow = (sw & kEvtSlow) != 0;
         const uint32_t attr = slow ? g_chk[o].y >> 16 : 0u;
-        const uint32_t p = slow ? fetch<kRingStride>(w, o) : *reinterpret_cast<const uint16_t *>(lds_bytes + my_ring + __builtin_amdgcn_readlane(r.x, j));
+        const uint32_t p = slow ? fetch<kRingStride, kT>(w, o) : *reinterpret_cast<const uint16_t *>(lds_bytes + my_ring + __builtin_amdgcn_readlane(r.x, j));
         if (slow) {
           apply1(o, attr, (sw & kEvtTested) != 0, p);
         } else {
@@ -366,7 +400,7 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(6)
         uint32_t p[G];
 #pragma unroll
         for (int t = 0; t < G; ++t)
-          p[t] = w.rows[(uint64_t)w.row * w.ld + (__builtin_amdgcn_readlane(r.w, (g0 + t) & 63u) & 0xFFFFFFu)];
+          p[t] = from_memory<kT>(w, __builtin_amdgcn_readlane(r.w, (g0 + t) & 63u) & 0xFFFFFFu);
         if (any_slow) {
 #pragma unroll
           for (int t = 0; t < G; ++t)
@@ -474,9 +508,9 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(6)
       if (dj != 0xFFFFu) {
         const uint32_t pj = oj - dj, slot = (pj / kCheckWaves) % kCacheSlots;
         if ((uint32_t)__builtin_amdgcn_readlane(cache_tag, slot) == pj) qv = (cache[slot >> 1] >> (16u * (slot & 1u))) & 0xFFFFu;
-        else qv = w.rows[(uint64_t)w.row * w.ld + pj];
+        else qv = from_memory<kT>(w, pj);
       } else {
-        qv = w.rows[(uint64_t)w.row * w.ld + g_prev_occ[oj]];
+        qv = from_memory<kT>(w, g_prev_occ[oj]);
       }
       if (pv != qv) key = min(key, kKeyCons | oj);
     }
@@ -531,17 +565,17 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(6)
   } else {
     const uint32_t j = role - 1;
     for (uint32_t c = c_first; c <= ca && c < c_end; ++c) {   // history chunk and the tile's first chunk
-      load_chunk(w, c * kChunk, j);
-      store_chunk<kRingStride>(w, c * kChunk, j);
+      load_chunk<kT>(w, c * kChunk, j);
+      store_chunk<kRingStride, kT>(w, c * kChunk, j);
     }
-    if (ca + 1 < c_end) load_chunk(w, (ca + 1) * kChunk, j);
+    if (ca + 1 < c_end) load_chunk<kT>(w, (ca + 1) * kChunk, j);
     u32x4 chk_next = load_chk(ca);
     __syncthreads();
     for (uint32_t c = ca; c != c_stop; ++c) {
       if (c < c_end) {
         if (c + 1 < c_end) {
-          store_chunk<kRingStride>(w, (c + 1) * kChunk, j);
-          if (c + 2 < c_end) load_chunk(w, (c + 2) * kChunk, j);
+          store_chunk<kRingStride, kT>(w, (c + 1) * kChunk, j);
+          if (c + 2 < c_end) load_chunk<kT>(w, (c + 2) * kChunk, j);
         }
         w.hi = (c + 1) * kChunk;
         const u32x4 raw = chk_next;
@@ -577,7 +611,7 @@ __global__ void k_finalize(const DevJob *__restrict__ jobs) {
       }
       case 1: {
         const uint32_t v = m.occ_vreg[pos];
-        r = {VL_STATUS_REALIZABILITY, pos, v, bad_bits(m, m.vattr[v], J.cand[(uint64_t)k * J.ld + pos])};
+        r = {VL_STATUS_REALIZABILITY, pos, v, bad_bits(m, m.vattr[v], cand_at(J, k, pos))};
         break;
       }
       default: r = {VL_STATUS_SAFETY, pos, kNone, kNone}; break;
@@ -598,7 +632,6 @@ __global__ __launch_bounds__(256) void k_resolve(const DevJob *__restrict__ jobs
   if (k >= J.K || J.out[k].status != VL_STATUS_SAFETY) return;
   const DevMir VL_GLOBAL &m = *as_global(J.mir);
   const DevLive VL_GLOBAL &L = *as_global(J.live);
-  const uint16_t *row = J.cand + (uint64_t)k * J.ld;
   const uint32_t i = J.out[k].where;
   extern __shared__ uint32_t in_p[];   // [W]
   __shared__ unsigned long long best;
@@ -609,7 +642,7 @@ __global__ __launch_bounds__(256) void k_resolve(const DevJob *__restrict__ jobs
   uint32_t my_v = kNone, my_p = 0;
   if (threadIdx.x < n_ops && (m.occ_flags[o_lo + threadIdx.x] & VL_OCC_DEF)) {
     my_v = m.occ_vreg[o_lo + threadIdx.x];
-    my_p = row[L.first[my_v]];
+    my_p = cand_at(J, k, L.first[my_v]);
   }
   if (threadIdx.x < kMaxOperands) all_v[threadIdx.x] = my_v;
   if (threadIdx.x == 0) { best = ~0ull; nd = 0; }
@@ -632,7 +665,7 @@ __global__ __launch_bounds__(256) void k_resolve(const DevJob *__restrict__ jobs
     while (word) {
       const uint32_t x = xw * 32 + __ffs(word) - 1;
       word &= word - 1;
-      const uint32_t ax = m.vattr[x], px = row[L.first[x]], wx = attr_width(ax);
+      const uint32_t ax = m.vattr[x], px = cand_at(J, k, L.first[x]), wx = attr_width(ax);
       for (uint32_t t = 0; t < nd; ++t) {
         const uint32_t d = dv[t];
         if (d == x) continue;
@@ -693,7 +726,7 @@ struct Launch {
 // Validates the jobs, lays out the device job table and makes sure the device copy is
 // current (the copy is skipped when the table is the one the stream's slot already holds).
 // Called with the device's scratch locked.
-int32_t prepare_jobs(const vl_job *jobs, uint32_t n_jobs, hipStream_t stream, Scratch &sc, Launch &out) {
+int32_t prepare_jobs(const vl_job *jobs, uint32_t n_jobs, hipStream_t stream, Scratch &sc, Launch &out, bool transposed = false) {
   // the calling stream's slot, else a free one, else the least recently used one (whose
   // earlier kernels may be anywhere: the device is drained before the slot changes hands)
   Slot *found = nullptr;
@@ -718,18 +751,33 @@ int32_t prepare_jobs(const vl_job *jobs, uint32_t n_jobs, hipStream_t stream, Sc
     const vl_job &u = jobs[j];
     if (!u.mir || !u.live || !u.cand || !u.out) return VL_E_NULL;
     if (u.mir->magic != kMirMagic || u.live->magic != kLiveMagic || u.live->mir != u.mir) return VL_E_ARG;
-    if (u.K == 0 || u.ld < u.mir->h.O) return VL_E_SHAPE;
+    if (u.K == 0 || u.ld < (transposed ? u.K : u.mir->h.O)) return VL_E_SHAPE;
     DevJob &d = tab[j];
     memset(&d, 0, sizeof(d));
     d.mir = u.mir->dev; d.live = u.live->dev; d.cand = u.cand; d.out = u.out; d.ld = u.ld; d.K = u.K;
+    d.fast = (((uintptr_t)u.cand & 15) == 0 && (u.ld & 7) == 0) ? 1u : 0u;
+    d.transposed = transposed ? 1u : 0u;
+    // groups of up to 64 candidates; every group but the last has d.rows of them
     d.n_groups = (u.K + 63) / 64;
     d.rows = (u.K + d.n_groups - 1) / d.n_groups;
+    if (transposed) {
+      // occurrence-major: a group is copied in 16-byte pieces of 8 candidates, so groups
+      // start at multiples of 8; rounding the group size down keeps the groups small
+      // (100 candidates: 48 + 52) unless the last one then outgrows a wavefront
+      if (!d.fast) return VL_E_SHAPE;
+      uint32_t base = (u.K / d.n_groups) & ~7u;
+      if (base == 0 || u.K - (d.n_groups - 1) * base > 64) {
+        base = ((u.K + d.n_groups - 1) / d.n_groups + 7u) & ~7u;
+        d.n_groups = (u.K + base - 1) / base;
+      }
+      d.rows = base;
+    }
+    const uint32_t last = u.K - (d.n_groups - 1) * d.rows;
     d.unit_base = out.units;
     d.n_units = d.n_groups * u.live->h.T;
-    d.fast = (((uintptr_t)u.cand & 15) == 0 && (u.ld & 7) == 0) ? 1u : 0u;
     out.units += d.n_units;
     out.maxK = std::max(out.maxK, u.K);
-    out.max_rows = std::max(out.max_rows, d.rows);
+    out.max_rows = std::max(out.max_rows, std::max(d.rows, last));
     out.max_words = std::max(out.max_words, u.mir->h.occ_words);
     out.max_w = std::max(out.max_w, u.mir->h.W);
   }
@@ -828,30 +876,44 @@ extern "C" int32_t vl_summarize_multi(const vl_job *jobs, uint32_t n_jobs, vl_su
   return VL_OK;
 }
 
-extern "C" int32_t vl_verify_multi(const vl_job *jobs, uint32_t n_jobs, vl_stream stream_) {
+namespace {
+int32_t verify_jobs(const vl_job *jobs, uint32_t n_jobs, hipStream_t stream, bool transposed) {
   if (!jobs) return VL_E_NULL;
   if (n_jobs == 0 || n_jobs > 65535) return VL_E_SHAPE;
-  hipStream_t stream = (hipStream_t)stream_;
   int device = 0;
   VL_HIP(hipGetDevice(&device));
   if (device < 0 || device >= 16) return VL_E_ARG;
   Scratch &s = g_scratch[device];
   std::lock_guard<std::mutex> lock(s.mu);
   Launch L;
-  const int32_t rc = prepare_jobs(jobs, n_jobs, stream, s, L);
+  const int32_t rc = prepare_jobs(jobs, n_jobs, stream, s, L, transposed);
   if (rc != VL_OK) return rc;
   const bool narrow = L.max_rows <= kPitchNarrow;   // every group of every job fits the narrow ring
   const size_t lds = (size_t)L.max_words * 64 * 4 + 64 * 4 + (size_t)kRing * (narrow ? kPitchNarrow : kPitchWide) * 2;
   k_init<<<dim3((L.maxK + 255) / 256, n_jobs), 256, 0, stream>>>(L.dev);
   if (g_time_start) VL_HIP(hipEventRecord(g_time_start, stream));
-  if (narrow) k_walk<kPitchNarrow><<<L.units, kWalkThreads, lds, stream>>>(L.dev, n_jobs);
-  else k_walk<kPitchWide><<<L.units, kWalkThreads, lds, stream>>>(L.dev, n_jobs);
+  if (transposed) {
+    if (narrow) k_walk<kPitchNarrow, true><<<L.units, kWalkThreads, lds, stream>>>(L.dev, n_jobs);
+    else k_walk<kPitchWide, true><<<L.units, kWalkThreads, lds, stream>>>(L.dev, n_jobs);
+  } else {
+    if (narrow) k_walk<kPitchNarrow, false><<<L.units, kWalkThreads, lds, stream>>>(L.dev, n_jobs);
+    else k_walk<kPitchWide, false><<<L.units, kWalkThreads, lds, stream>>>(L.dev, n_jobs);
+  }
   if (g_time_stop) VL_HIP(hipEventRecord(g_time_stop, stream));
   g_time_start = g_time_stop = nullptr;
   k_finalize<<<dim3((L.maxK + 255) / 256, n_jobs), 256, 0, stream>>>(L.dev);
   k_resolve<<<dim3(L.maxK, n_jobs), 256, (size_t)L.max_w * 4, stream>>>(L.dev);
   VL_HIP(hipGetLastError());
   return VL_OK;
+}
+}  // namespace
+
+extern "C" int32_t vl_verify_multi(const vl_job *jobs, uint32_t n_jobs, vl_stream stream) {
+  return verify_jobs(jobs, n_jobs, (hipStream_t)stream, false);
+}
+
+extern "C" int32_t vl_verify_multi_occ_major(const vl_job *jobs, uint32_t n_jobs, vl_stream stream) {
+  return verify_jobs(jobs, n_jobs, (hipStream_t)stream, true);
 }
 
 extern "C" int32_t vl_verify_batch(const vl_mir *mir, const vl_live *live, const uint16_t *cand, uint32_t K,

@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol():
     lib = vl.load()
     names = declared_symbols()
     assert {"vl_mir_create", "vl_liveness", "vl_liveness_multi", "vl_verify_batch", "vl_verify_multi",
-            "vl_live_get", "vl_strerror", "vl_summarize_multi", "vl_free_bases_multi", "vl_count_violations_multi", "vl_bank_conflicts"} <= set(names)
+            "vl_live_get", "vl_strerror", "vl_summarize_multi", "vl_free_bases_multi", "vl_count_violations_multi", "vl_bank_conflicts", "vl_verify_multi_occ_major"} <= set(names)
     for n in names:
         assert getattr(lib, n) is not None, n
 
@@ -74,6 +74,7 @@ def test_null_arguments():
     lib = vl.load()
     assert lib.vl_mir_create(None, None) == -1
     assert lib.vl_verify_multi(None, 1, None) == -1
+    assert lib.vl_verify_multi_occ_major(None, 1, None) == -1
     assert lib.vl_summarize_multi(None, 1, None, None, None) == -1
     assert lib.vl_free_bases_multi(None, 1, None, None) == -1
     assert lib.vl_count_violations_multi(None, 1, None) == -1
