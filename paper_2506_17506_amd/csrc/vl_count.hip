@@ -146,44 +146,54 @@ __global__ __launch_bounds__(256) void k_cnt_real(const DevCountJob *__restrict_
   }
 }
 
-// safety: a workgroup takes 64 candidates (one per lane) and a stretch of the pairs, 1024
-// pairs per wavefront, fetched 64 at a time (one pair per lane, read out of the lanes)
+// safety: a wavefront takes 1024 of the pairs, fetched 64 at a time (one pair per lane, read
+// out of the lanes), and walks them once for every group of 64 candidates (one per lane): the
+// two table rows of a pair are then read for all groups back to back
 constexpr uint32_t kPairsPerWave = 1024, kPairsPerGroup = 4 * kPairsPerWave;
-__global__ __launch_bounds__(256) void k_cnt_safe(const DevCountJob *__restrict__ jobs, uint32_t groups) {
+__global__ __launch_bounds__(256) void k_cnt_safe(const DevCountJob *__restrict__ jobs) {
   const DevCountJob &J = jobs[blockIdx.y];
   const DevMir VL_GLOBAL &m = *as_global(J.mir);
-  const uint32_t g = blockIdx.x % groups, stretch = blockIdx.x / groups;
-  const uint32_t lane = threadIdx.x & 63u, k = g * 64 + lane;
-  if (g * 64 >= J.K) return;
-  const uint64_t e0 = (uint64_t)stretch * kPairsPerGroup + (uint64_t)(threadIdx.x >> 6) * kPairsPerWave;
+  const uint32_t lane = threadIdx.x & 63u;
+  const uint64_t e0 = (uint64_t)blockIdx.x * kPairsPerGroup + (uint64_t)(threadIdx.x >> 6) * kPairsPerWave;
   if (e0 >= J.n_pairs) return;
   const uint64_t e1 = min(J.n_pairs, e0 + kPairsPerWave);
-  uint32_t n = 0;
-  for (uint64_t e = e0; e < e1; e += 64) {
-    uint32_t pa = 0, pb = 0, wa = 0, wb = 0;
-    if (e + lane < e1) {
-      pa = J.pairs[2 * (e + lane)];
-      pb = J.pairs[2 * (e + lane) + 1];
-      wa = attr_width(m.vattr[pa]);
-      wb = attr_width(m.vattr[pb]);
-    }
-    // Eight pairs at a time, their sixteen table reads in flight together.  Lanes past the
-    // last pair hold the pair (0, 0) with widths 0, which never overlaps, so no tail is needed.
-    const uint32_t cnt = (uint32_t)min((uint64_t)64, e1 - e);
-    for (uint32_t j = 0; j < cnt; j += 8) {
-      uint32_t ra[8], rb[8];
-#pragma unroll
-      for (int t = 0; t < 8; ++t) {
-        const uint32_t a = __builtin_amdgcn_readlane(pa, j + t), b = __builtin_amdgcn_readlane(pb, j + t);
-        ra[t] = J.table[(size_t)a * J.k_pad + k];   // k < k_pad always
-        rb[t] = J.table[(size_t)b * J.k_pad + k];
+  const uint32_t groups = J.k_pad / 64;
+  for (uint32_t g0 = 0; g0 < groups; g0 += 2) {   // two groups of candidates per pass over the pairs
+    const uint32_t k0 = g0 * 64 + lane, k1 = min(k0 + 64, J.k_pad - 64 + lane);   // an odd last group is counted once
+    const bool second = g0 + 1 < groups;
+    uint32_t n0 = 0, n1 = 0;
+    for (uint64_t e = e0; e < e1; e += 64) {
+      uint32_t pa = 0, pb = 0, wa = 0, wb = 0;
+      if (e + lane < e1) {
+        pa = J.pairs[2 * (e + lane)];
+        pb = J.pairs[2 * (e + lane) + 1];
+        wa = attr_width(m.vattr[pa]);
+        wb = attr_width(m.vattr[pb]);
       }
+      // Four pairs at a time, their table reads in flight together.  Lanes past the last
+      // pair hold the pair (0, 0) with widths 0, which never overlaps, so no tail is needed.
+      const uint32_t cnt = (uint32_t)min((uint64_t)64, e1 - e);
+      for (uint32_t j = 0; j < cnt; j += 4) {
+        uint32_t ra0[4], rb0[4], ra1[4], rb1[4];
 #pragma unroll
-      for (int t = 0; t < 8; ++t)
-        n += ra[t] < rb[t] + (uint32_t)__builtin_amdgcn_readlane(wb, j + t) && rb[t] < ra[t] + (uint32_t)__builtin_amdgcn_readlane(wa, j + t);
+        for (int t = 0; t < 4; ++t) {
+          const uint32_t a = __builtin_amdgcn_readlane(pa, j + t), b = __builtin_amdgcn_readlane(pb, j + t);
+          ra0[t] = J.table[(size_t)a * J.k_pad + k0];   // k0, k1 < k_pad always
+          rb0[t] = J.table[(size_t)b * J.k_pad + k0];
+          ra1[t] = J.table[(size_t)a * J.k_pad + k1];
+          rb1[t] = J.table[(size_t)b * J.k_pad + k1];
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const uint32_t sa = __builtin_amdgcn_readlane(wa, j + t), sb = __builtin_amdgcn_readlane(wb, j + t);
+          n0 += ra0[t] < rb0[t] + sb && rb0[t] < ra0[t] + sa;
+          n1 += ra1[t] < rb1[t] + sb && rb1[t] < ra1[t] + sa;
+        }
+      }
     }
+    if (k0 < J.K && n0) atomicAdd(&J.out[k0].n_safe, n0);
+    if (second && k0 + 64 < J.K && n1) atomicAdd(&J.out[k0 + 64].n_safe, n1);
   }
-  if (k < J.K && n) atomicAdd(&J.out[k].n_safe, n);
 }
 
 __global__ void k_cnt_kinds(const DevCountJob *__restrict__ jobs) {
@@ -348,13 +358,13 @@ extern "C" int32_t vl_count_violations_multi(const vl_count_job *jobs, uint32_t 
     d.ld = jobs[j].ld; d.K = jobs[j].K; d.k_pad = (jobs[j].K + 63u) & ~63u;
   }
   VL_HIP(hipMemcpyAsync(w.dev, w.host, (size_t)n_jobs * sizeof(DevCountJob), hipMemcpyHostToDevice, stream));
-  const uint32_t tiles_k = max_kpad / 64, tiles_v = (maxV + 63) / 64, groups = max_kpad / 64;
+  const uint32_t tiles_k = max_kpad / 64, tiles_v = (maxV + 63) / 64;
   const uint32_t stretches = (uint32_t)std::max<uint64_t>(1, (max_pairs + kPairsPerGroup - 1) / kPairsPerGroup);
   k_cnt_clear<<<dim3((maxK + 255) / 256, n_jobs), 256, 0, stream>>>(w.dev);
   k_cnt_table<<<dim3(tiles_v * tiles_k, n_jobs), 256, 0, stream>>>(w.dev, tiles_k);
   k_cnt_cons<<<dim3((maxO + 1023) / 1024, maxK, n_jobs), 256, 0, stream>>>(w.dev);
   k_cnt_real<<<dim3((maxV + 255) / 256, maxK, n_jobs), 256, 0, stream>>>(w.dev);
-  k_cnt_safe<<<dim3(groups * stretches, n_jobs), 256, 0, stream>>>(w.dev, groups);
+  k_cnt_safe<<<dim3(stretches, n_jobs), 256, 0, stream>>>(w.dev);
   k_cnt_kinds<<<dim3((maxK + 255) / 256, n_jobs), 256, 0, stream>>>(w.dev);
   VL_HIP(hipGetLastError());
   VL_HIP(hipEventRecord(w.consumed, stream));
