@@ -64,7 +64,7 @@ __host__ __device__ inline uint64_t entry_pack(uint32_t x, uint32_t y) { return 
 //   y: distance to that previous occurrence (16 bits, saturated) | packed attributes << 16
 //   z: alignment - 1 in both halves (two candidates per 32-bit operation); 0 when nothing is to be tested
 //   w: the largest base that fits, in both halves; all ones when there is no limit
-// "seeds": per tile, the values live into it, as event records (below) whose x is unused:
+// "seeds": per tile, the values live into it, as event records (below) whose x holds only the vreg:
 //   w names an occurrence of the vreg, from which the candidate's register is taken
 // "plan": the occupancy events in the order they take effect, as 16-byte records (below).
 // For each instruction: releases of operands that die there, then test-and-occupy of the
@@ -90,7 +90,7 @@ constexpr uint32_t kKeepMaxGap = 4096;   // longer gaps are not worth a slot
 
 // An occupancy event in the form the verifier's occupancy wavefront consumes it, four
 // scalar registers that need no further decoding:
-//   x  ring slot (index % kWalkRing) of the occurrence that carries the register
+//   x  ring slot (index % kWalkRing) of the occurrence that carries the register | vreg << 8
 //   y  the tuple's mask at bit 0 (width ones)
 //   z  byte offset of the first mask word of the vreg's class (class_word * 256)
 //   w  that occurrence (24 bits) | kEvtPost | kEvtSlow | kEvtTested
@@ -198,18 +198,17 @@ __device__ inline uint32_t bad_bits(const DevMir VL_GLOBAL &m, uint32_t attr, ui
 __device__ inline void flip_members_of_p(const DevMir VL_GLOBAL &m, const DevLive VL_GLOBAL &L, const uint32_t i, uint32_t *in_p,
                                          const uint32_t tid, const uint32_t n_threads) {
   const uint32_t tile = i / L.tile_len;
-  auto flip_vreg = [&](uint32_t o) {
-    const uint32_t v = m.occ_vreg[o];
+  auto flip_vreg = [&](uint32_t v) {   // records carry their vreg in x (above the ring slot)
     __hip_atomic_fetch_xor(&in_p[v >> 5], 1u << (v & 31), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
   };
   if (tile > 0)
-    for (uint32_t s = L.seed_off[tile] + tid; s < L.seed_off[tile + 1]; s += n_threads) flip_vreg(L.seeds[s].w & 0xFFFFFFu);
+    for (uint32_t s = L.seed_off[tile] + tid; s < L.seed_off[tile + 1]; s += n_threads) flip_vreg(L.seeds[s].x >> 8);
   const uint32_t item = i + m.instr_blk[i] + 1;   // boundary items come before their block's instructions
   const uint32_t e_own = L.item_off[item], e_end = L.item_off[item + 1];
   for (uint32_t e = L.tile_range[2 * tile] + tid; e < e_end; e += n_threads) {
-    const uint32_t w = L.plan[e].w;
-    if (e >= e_own && (w & kEvtPost)) continue;
-    flip_vreg(w & 0xFFFFFFu);
+    const u32x4 r = L.plan[e];
+    if (e >= e_own && (r.w & kEvtPost)) continue;
+    flip_vreg(r.x >> 8);
   }
 }
 }  // namespace vl

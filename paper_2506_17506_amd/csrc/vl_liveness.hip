@@ -610,11 +610,12 @@ __device__ inline uint32_t source_occurrence(const DevLive VL_GLOBAL &L, uint32_
 
 // The record of one occupancy event (layout in vl_dev.h).  `near`: the occurrence is
 // certainly inside the verifier's ring when the event is replayed.
-__device__ inline u32x4 event_record(const DevMir VL_GLOBAL &m, uint32_t o, uint32_t attr, bool tested, bool near) {
+__device__ inline u32x4 event_record(const DevMir VL_GLOBAL &m, uint32_t o, uint32_t v, bool tested, bool near) {
+  const uint32_t attr = m.vattr[v];
   const uint32_t width = attr_width(attr);
   const bool slow = !near || attr_straddle(attr) || width == 32;
   u32x4 r;
-  r.x = o % kWalkRing;
+  r.x = (o % kWalkRing) | (v << 8);
   r.y = width == 32 ? 0xFFFFFFFFu : ((1u << width) - 1u);
   r.z = (uint32_t)m.class_word[attr_class(attr)] * 256u;
   r.w = o | (slow ? kEvtSlow : 0u) | (tested ? kEvtTested : 0u);
@@ -653,7 +654,7 @@ __device__ inline void f_boundary(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &
           // replayed with the block's first instruction, when the readable window ends at
           // most 127 occurrences after that instruction's first operand
           const bool near = src < m.occ_off[at] && src + (kWalkReach - 2 * kWalkChunk + 1) >= m.occ_off[at];
-          L.plan[pos++] = event_record(m, src, m.vattr[v], false, near);
+          L.plan[pos++] = event_record(m, src, v, false, near);
         }
       }
       total += __shfl(incl, 63, 64);
@@ -674,7 +675,7 @@ __device__ inline void f_plan_fill(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL 
   for (uint32_t o = o0; o < o1; ++o) L.occ_kill[o] = (L.occ_role[o] & kRoleKill) ? 1 : 0;   // kill flags, in occurrence order
   // an instruction's own operands are always inside the ring when its events are replayed
   auto put = [&](uint32_t o, bool tested, uint32_t extra) {
-    u32x4 r = event_record(m, o, m.vattr[m.occ_vreg[o]], tested, true);
+    u32x4 r = event_record(m, o, m.occ_vreg[o], tested, true);
     r.w |= extra;
     L.plan[pos++] = r;
   };
@@ -880,8 +881,8 @@ __device__ inline void f_seed_src(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &
   const u32x4 raw = L.seeds[k];
   const uint32_t v = raw.x, t = raw.y;
   // the register is always gathered from memory: the ring offset stays unused
-  u32x4 r = event_record(m, source_occurrence(L, v, t * L.tile_len), m.vattr[v], false, true);
-  r.x = 0;
+  u32x4 r = event_record(m, source_occurrence(L, v, t * L.tile_len), v, false, true);
+  r.x &= ~0xFFu;   // only the vreg: the register is always gathered from memory
   L.seeds[k] = r;
 }
 
@@ -1002,7 +1003,7 @@ __global__ void k_dense_delta(MIRS) {
   // a tile that starts exactly at this block start takes its row from the seed instead
   if (q == m.blk_start[b] + b && row % L.tile_len == 0) return;
   for (uint32_t e = L.item_off[q]; e < L.item_off[q + 1]; ++e) {
-    const uint32_t v = m.occ_vreg[L.plan[e].w & 0xFFFFFFu];
+    const uint32_t v = L.plan[e].x >> 8;
     atomicXor(&L.live_after[(size_t)row * m.W + (v >> 5)], 1u << (v & 31));
   }
 }

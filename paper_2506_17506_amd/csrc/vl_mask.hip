@@ -39,16 +39,12 @@ __global__ __launch_bounds__(256) void k_free_bases(const DevQuery *__restrict__
   if (first_v >= q) {   // the first mention of v: everything in P(i) that already has a register is in the way
     flip_members_of_p(m, L, i, in_p, threadIdx.x, blockDim.x);
     __syncthreads();
-    for (uint32_t xw = threadIdx.x; xw < m.W; xw += blockDim.x) {
-      uint32_t word = in_p[xw];
-      while (word) {
-        const uint32_t b = xw * 32 + __ffs(word) - 1;
-        word &= word - 1;
-        const uint32_t ab = m.vattr[b], fb = L.first[b];
-        if (b == v || attr_class(ab) != cls || fb >= q) continue;
-        const uint32_t pb = row[fb], wb = attr_width(ab);
-        for (uint32_t r = pb; r < pb + wb && r < 512u; ++r) atomicOr(&blocked[r >> 5], 1u << (r & 31));
-      }
+    for (uint32_t b = threadIdx.x; b < m.V; b += blockDim.x) {   // one vreg per lane
+      if (!((in_p[b >> 5] >> (b & 31)) & 1u)) continue;
+      const uint32_t ab = m.vattr[b], fb = L.first[b];
+      if (b == v || attr_class(ab) != cls || fb >= q) continue;
+      const uint32_t pb = row[fb], wb = attr_width(ab);
+      for (uint32_t r = pb; r < pb + wb && r < 512u; ++r) atomicOr(&blocked[r >> 5], 1u << (r & 31));
     }
     __syncthreads();
   }

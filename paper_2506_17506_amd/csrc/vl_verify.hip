@@ -71,10 +71,11 @@ __device__ inline uint32_t cand_at(const DevJob &J, uint32_t k, uint32_t o) {
   return J.transposed ? J.cand[(uint64_t)o * J.ld + k] : J.cand[(uint64_t)k * J.ld + o];
 }
 
-__global__ void k_init(const DevJob *__restrict__ jobs) {
+__global__ void k_init(const DevJob *__restrict__ jobs, uint2 *__restrict__ work) {
   const DevJob &J = jobs[blockIdx.y];
   uint32_t k = blockIdx.x * blockDim.x + threadIdx.x;
   if (k < J.K) J.out[k].status = kKeyOk;
+  if ((blockIdx.x | blockIdx.y | threadIdx.x) == 0) work[0].x = 0;   // the list k_finalize fills starts empty
 }
 
 // ---- the candidate walk -----------------------------------------------------------------
@@ -316,7 +317,7 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(6)
   auto fetch_records = [&](uint32_t from, uint32_t to) __attribute__((always_inline)) {
     u32x4 r = 0;
     if (from + w.lane < to) r = g_plan[from + w.lane];
-    r.x *= kRingStride * 2u;
+    r.x = (r.x & 0xFFu) * (kRingStride * 2u);   // (the vreg above the slot is for the kernels that rebuild P(i))
     return r;
   };
   // Replays a batch of up to 64 records held one per lane (lanes past the batch hold zero
@@ -592,8 +593,9 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(6)
 }
 
 // Turns the winning key of each candidate into its result record.  Safety results
-// get their pair from k_resolve.
-__global__ void k_finalize(const DevJob *__restrict__ jobs) {
+// get their pair from k_resolve: their (job, candidate) go onto the list work[1..], whose
+// length is work[0].x (one atomic per wavefront; the order of the list does not matter).
+__global__ void k_finalize(const DevJob *__restrict__ jobs, uint2 *__restrict__ work) {
   const DevJob &J = jobs[blockIdx.y];
   uint32_t k = blockIdx.x * blockDim.x + threadIdx.x;
   if (k >= J.K) return;
@@ -618,6 +620,15 @@ __global__ void k_finalize(const DevJob *__restrict__ jobs) {
     }
   }
   J.out[k] = r;
+  const bool listed = r.status == VL_STATUS_SAFETY;
+  const uint64_t peers = __ballot(listed);
+  if (peers) {
+    const uint32_t lane = __lane_id(), leader = (uint32_t)__ffsll((unsigned long long)peers) - 1u;
+    uint32_t at = 0;
+    if (lane == leader) at = atomicAdd(&work[0].x, (uint32_t)__popcll(peers));
+    at = __shfl(at, leader);
+    if (listed) work[1 + at + __popcll(peers & ((1ull << lane) - 1ull))] = make_uint2(blockIdx.y, k);
+  }
 }
 
 // For a candidate whose first violation is a register clash at instruction i: the
@@ -625,46 +636,48 @@ __global__ void k_finalize(const DevJob *__restrict__ jobs) {
 // with overlapping ranges.  At the first clashing instruction every clashing pair contains a
 // vreg that the instruction defines, so only pairs (definition, anything in P(i)) are
 // examined.  P(i) is rebuilt as a bitset in LDS the way the walk builds occupancy, but over
-// vregs instead of registers (flip_members_of_p).
-__global__ __launch_bounds__(256) void k_resolve(const DevJob *__restrict__ jobs) {
-  const DevJob &J = jobs[blockIdx.y];
-  const uint32_t k = blockIdx.x;
-  if (k >= J.K || J.out[k].status != VL_STATUS_SAFETY) return;
-  const DevMir VL_GLOBAL &m = *as_global(J.mir);
-  const DevLive VL_GLOBAL &L = *as_global(J.live);
-  const uint32_t i = J.out[k].where;
+// vregs instead of registers (flip_members_of_p).  The workgroups share out the list of
+// such candidates that k_finalize wrote.
+__global__ __launch_bounds__(256) void k_resolve(const DevJob *__restrict__ jobs, const uint2 *__restrict__ work) {
   extern __shared__ uint32_t in_p[];   // [W]
   __shared__ unsigned long long best;
   __shared__ uint32_t dv[kMaxOperands], dp[kMaxOperands], all_v[kMaxOperands], nd;
-  for (uint32_t x = threadIdx.x; x < m.W; x += blockDim.x) in_p[x] = 0;
-  // the vregs the instruction writes (each once) and their registers: one operand per lane
-  const uint32_t o_lo = m.occ_off[i], n_ops = m.occ_off[i + 1] - o_lo;
-  uint32_t my_v = kNone, my_p = 0;
-  if (threadIdx.x < n_ops && (m.occ_flags[o_lo + threadIdx.x] & VL_OCC_DEF)) {
-    my_v = m.occ_vreg[o_lo + threadIdx.x];
-    my_p = cand_at(J, k, L.first[my_v]);
-  }
-  if (threadIdx.x < kMaxOperands) all_v[threadIdx.x] = my_v;
-  if (threadIdx.x == 0) { best = ~0ull; nd = 0; }
-  __syncthreads();
-  if (my_v != kNone) {
-    bool seen = false;
-    for (uint32_t t = 0; t < threadIdx.x; ++t) seen |= all_v[t] == my_v;
-    if (!seen) {
-      const uint32_t slot = atomicAdd(&nd, 1u);
-      dv[slot] = my_v;
-      dp[slot] = my_p;
+  const uint32_t n_listed = work[0].x;
+  for (uint32_t at = blockIdx.x; at < n_listed; at += gridDim.x) {
+    const uint2 item = work[1 + at];
+    const DevJob &J = jobs[item.x];
+    const uint32_t k = item.y;
+    const DevMir VL_GLOBAL &m = *as_global(J.mir);
+    const DevLive VL_GLOBAL &L = *as_global(J.live);
+    const uint32_t i = J.out[k].where;
+    for (uint32_t x = threadIdx.x; x < m.W; x += blockDim.x) in_p[x] = 0;
+    // the vregs the instruction writes (each once) and their registers: one operand per lane
+    const uint32_t o_lo = m.occ_off[i], n_ops = m.occ_off[i + 1] - o_lo;
+    uint32_t my_v = kNone, my_p = 0;
+    if (threadIdx.x < n_ops && (m.occ_flags[o_lo + threadIdx.x] & VL_OCC_DEF)) {
+      my_v = m.occ_vreg[o_lo + threadIdx.x];
+      my_p = cand_at(J, k, L.first[my_v]);
     }
-  }
-  __syncthreads();
-  flip_members_of_p(m, L, i, in_p, threadIdx.x, blockDim.x);
-  __syncthreads();
-  unsigned long long mine = ~0ull;
-  for (uint32_t xw = threadIdx.x; xw < m.W; xw += blockDim.x) {
-    uint32_t word = in_p[xw];
-    while (word) {
-      const uint32_t x = xw * 32 + __ffs(word) - 1;
-      word &= word - 1;
+    if (threadIdx.x < kMaxOperands) all_v[threadIdx.x] = my_v;
+    if (threadIdx.x == 0) { best = ~0ull; nd = 0; }
+    __syncthreads();
+    if (my_v != kNone) {
+      bool seen = false;
+      for (uint32_t t = 0; t < threadIdx.x; ++t) seen |= all_v[t] == my_v;
+      if (!seen) {
+        const uint32_t slot = atomicAdd(&nd, 1u);
+        dv[slot] = my_v;
+        dp[slot] = my_p;
+      }
+    }
+    __syncthreads();
+    flip_members_of_p(m, L, i, in_p, threadIdx.x, blockDim.x);
+    __syncthreads();
+    unsigned long long mine = ~0ull;
+    // one vreg per lane (members of P(i) have neighbouring numbers: a lane that walked the
+    // bits of a word would fetch their registers one after the other)
+    for (uint32_t x = threadIdx.x; x < m.V; x += blockDim.x) {
+      if (!((in_p[x >> 5] >> (x & 31)) & 1u)) continue;
       const uint32_t ax = m.vattr[x], px = cand_at(J, k, L.first[x]), wx = attr_width(ax);
       for (uint32_t t = 0; t < nd; ++t) {
         const uint32_t d = dv[t];
@@ -678,12 +691,13 @@ __global__ __launch_bounds__(256) void k_resolve(const DevJob *__restrict__ jobs
         }
       }
     }
-  }
-  if (mine != ~0ull) atomicMin(&best, mine);
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    J.out[k].a = (uint32_t)(best >> 32);
-    J.out[k].b = (uint32_t)best;
+    if (mine != ~0ull) atomicMin(&best, mine);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      J.out[k].a = (uint32_t)(best >> 32);
+      J.out[k].b = (uint32_t)best;
+    }
+    __syncthreads();   // the shared arrays are reused by the next listed candidate
   }
 }
 
@@ -696,10 +710,13 @@ struct Slot {
   DevJob *dev = nullptr;
   DevJob *host = nullptr;   // pinned
   uint32_t cap = 0, n_valid = 0;
+  uint2 *work = nullptr;    // [0].x = length, then (job, candidate) of the clashes to resolve
+  uint64_t work_cap = 0;    // candidates the list has room for
   hipEvent_t copied = nullptr;
   uint64_t tick = 0;
 };
 constexpr int kSlots = 4;
+constexpr uint64_t kResolveGroups = 4096;   // workgroups that share out the clashes to resolve
 struct Scratch {
   std::mutex mu;
   Slot slot[kSlots];
@@ -720,6 +737,8 @@ extern "C" int32_t vl_verify_time_next(void *start, void *stop) {
 namespace {
 struct Launch {
   DevJob *dev = nullptr;
+  uint2 *work = nullptr;
+  uint64_t total_rows = 0;
   uint32_t units = 0, maxK = 0, max_words = 0, max_w = 1, max_rows = 0;
 };
 
@@ -777,6 +796,7 @@ int32_t prepare_jobs(const vl_job *jobs, uint32_t n_jobs, hipStream_t stream, Sc
     d.n_units = d.n_groups * u.live->h.T;
     out.units += d.n_units;
     out.maxK = std::max(out.maxK, u.K);
+    out.total_rows += u.K;
     out.max_rows = std::max(out.max_rows, std::max(d.rows, last));
     out.max_words = std::max(out.max_words, u.mir->h.occ_words);
     out.max_w = std::max(out.max_w, u.mir->h.W);
@@ -803,7 +823,16 @@ int32_t prepare_jobs(const vl_job *jobs, uint32_t n_jobs, hipStream_t stream, Sc
     VL_HIP(hipEventRecord(s.copied, stream));
     s.n_valid = n_jobs;
   }
+  if (s.work_cap < out.total_rows) {
+    VL_HIP(hipStreamSynchronize(stream));   // earlier kernels of the stream may still read the old list
+    if (s.work) (void)hipFree(s.work);
+    s.work = nullptr; s.work_cap = 0;
+    const uint64_t cap = std::max<uint64_t>(65536, out.total_rows + out.total_rows / 2);
+    VL_HIP(hipMalloc((void **)&s.work, (size_t)(cap + 1) * sizeof(uint2)));
+    s.work_cap = cap;
+  }
   out.dev = s.dev;
+  out.work = s.work;
   return VL_OK;
 }
 
@@ -890,7 +919,7 @@ int32_t verify_jobs(const vl_job *jobs, uint32_t n_jobs, hipStream_t stream, boo
   if (rc != VL_OK) return rc;
   const bool narrow = L.max_rows <= kPitchNarrow;   // every group of every job fits the narrow ring
   const size_t lds = (size_t)L.max_words * 64 * 4 + 64 * 4 + (size_t)kRing * (narrow ? kPitchNarrow : kPitchWide) * 2;
-  k_init<<<dim3((L.maxK + 255) / 256, n_jobs), 256, 0, stream>>>(L.dev);
+  k_init<<<dim3((L.maxK + 255) / 256, n_jobs), 256, 0, stream>>>(L.dev, L.work);
   if (g_time_start) VL_HIP(hipEventRecord(g_time_start, stream));
   if (transposed) {
     if (narrow) k_walk<kPitchNarrow, true><<<L.units, kWalkThreads, lds, stream>>>(L.dev, n_jobs);
@@ -901,8 +930,8 @@ int32_t verify_jobs(const vl_job *jobs, uint32_t n_jobs, hipStream_t stream, boo
   }
   if (g_time_stop) VL_HIP(hipEventRecord(g_time_stop, stream));
   g_time_start = g_time_stop = nullptr;
-  k_finalize<<<dim3((L.maxK + 255) / 256, n_jobs), 256, 0, stream>>>(L.dev);
-  k_resolve<<<dim3(L.maxK, n_jobs), 256, (size_t)L.max_w * 4, stream>>>(L.dev);
+  k_finalize<<<dim3((L.maxK + 255) / 256, n_jobs), 256, 0, stream>>>(L.dev, L.work);
+  k_resolve<<<(uint32_t)std::min<uint64_t>(L.total_rows, kResolveGroups), 256, (size_t)L.max_w * 4, stream>>>(L.dev, L.work);
   VL_HIP(hipGetLastError());
   return VL_OK;
 }
