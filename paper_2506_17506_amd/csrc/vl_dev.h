@@ -53,6 +53,8 @@ __host__ __device__ inline uint32_t attr_class(uint32_t a) { return a & 7u; }
 __host__ __device__ inline uint32_t attr_width(uint32_t a) { return ((a >> 3) & 31u) + 1u; }
 __host__ __device__ inline uint32_t attr_align(uint32_t a) { return ((a >> 8) & 31u) + 1u; }
 __host__ __device__ inline uint32_t attr_straddle(uint32_t a) { return (a >> 13) & 1u; }
+// bits 16 and up of a program's vattr[]: the first occupancy-mask word of the vreg's class
+__host__ __device__ inline uint32_t attr_word(uint32_t a) { return a >> 16; }
 __host__ __device__ inline uint64_t entry_pack(uint32_t x, uint32_t y) { return (uint64_t)x | ((uint64_t)y << 32); }
 
 // The verifier reads

@@ -617,7 +617,7 @@ __device__ inline u32x4 event_record(const DevMir VL_GLOBAL &m, uint32_t o, uint
   u32x4 r;
   r.x = (o % kWalkRing) | (v << 8);
   r.y = width == 32 ? 0xFFFFFFFFu : ((1u << width) - 1u);
-  r.z = (uint32_t)m.class_word[attr_class(attr)] * 256u;
+  r.z = attr_word(attr) * 256u;
   r.w = o | (slow ? kEvtSlow : 0u) | (tested ? kEvtTested : 0u);
   return r;
 }
@@ -639,25 +639,43 @@ __device__ inline void f_boundary(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &
   const uint32_t VL_GLOBAL *out_prev = L.live_out + (size_t)(b - 1) * W;
   const uint32_t VL_GLOBAL *in_cur = L.live_in + (size_t)b * W;
   uint32_t base = kFill ? L.item_off[item] : 0, total = 0;
+  // Filling: a lane first lists the vregs of its word in LDS; then the wavefront completes
+  // one record per lane, so that the look-ups of the source occurrences run side by side.
+  constexpr uint32_t kList = 512;
+  __shared__ uint32_t s_list[kFill ? 4 * kList : 1];
+  uint32_t *list = s_list + (kFill ? (threadIdx.x >> 6) * kList : 0);
+  auto record = [&](uint32_t v) {
+    const uint32_t src = source_occurrence(L, v, at);
+    // replayed with the block's first instruction, when the readable window ends at
+    // most 127 occurrences after that instruction's first operand
+    const bool near = src < m.occ_off[at] && src + (kWalkReach - 2 * kWalkChunk + 1) >= m.occ_off[at];
+    return event_record(m, src, v, false, near);
+  };
   for (int pass = 0; pass < 2; ++pass) {  // 0: leaving, 1: entering
     for (uint32_t w0 = 0; w0 < W; w0 += 64) {
       const uint32_t w = w0 + lane;
       uint32_t bits = 0;
       if (w < W) bits = pass == 0 ? (out_prev[w] & ~in_cur[w]) : (in_cur[w] & ~out_prev[w]);
       const uint32_t c = __popc(bits), incl = wave_incl_scan(c);
-      if (kFill) {
-        uint32_t pos = base + total + incl - c;
+      const uint32_t n_here = __shfl(incl, 63, 64);
+      if (kFill && n_here) {
+        uint32_t pos = incl - c;
+        const bool listed = n_here <= kList;   // the same in every lane
         while (bits) {
-          uint32_t v = w * 32 + __ffs(bits) - 1;
+          const uint32_t v = w * 32 + __ffs(bits) - 1;
           bits &= bits - 1;
-          const uint32_t src = source_occurrence(L, v, at);
-          // replayed with the block's first instruction, when the readable window ends at
-          // most 127 occurrences after that instruction's first operand
-          const bool near = src < m.occ_off[at] && src + (kWalkReach - 2 * kWalkChunk + 1) >= m.occ_off[at];
-          L.plan[pos++] = event_record(m, src, v, false, near);
+          if (listed) list[pos++] = v;
+          else L.plan[base + total + pos++] = record(v);
+        }
+        if (listed) {
+          __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+          __builtin_amdgcn_wave_barrier();
+          for (uint32_t x = lane; x < n_here; x += 64) L.plan[base + total + x] = record(list[x]);
+          __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+          __builtin_amdgcn_wave_barrier();
         }
       }
-      total += __shfl(incl, 63, 64);
+      total += n_here;
     }
   }
   if (!kFill && lane == 0) L.item_off[item] = total;
@@ -670,21 +688,25 @@ __device__ inline void f_plan_fill(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL 
                                    const uint32_t bdim) {
   uint32_t i = bx * bdim + tx;
   if (i >= m.N) return;
-  uint32_t pos = L.item_off[item_of_instr(m, i)];
+  const uint32_t base = L.item_off[item_of_instr(m, i)];
   const uint32_t o0 = m.occ_off[i], o1 = m.occ_off[i + 1];
-  for (uint32_t o = o0; o < o1; ++o) L.occ_kill[o] = (L.occ_role[o] & kRoleKill) ? 1 : 0;   // kill flags, in occurrence order
-  // an instruction's own operands are always inside the ring when its events are replayed
-  auto put = [&](uint32_t o, bool tested, uint32_t extra) {
-    u32x4 r = event_record(m, o, m.occ_vreg[o], tested, true);
-    r.w |= extra;
-    L.plan[pos++] = r;
-  };
-  for (uint32_t o = o0; o < o1; ++o)
-    if (L.occ_role[o] & kRolePreKill) put(o, false, 0u);
-  for (uint32_t o = o0; o < o1; ++o)
-    if (L.occ_role[o] & kRoleTestSet) put(o, true, 0u);
-  for (uint32_t o = o0; o < o1; ++o)
-    if (L.occ_role[o] & kRolePostKill) put(o, false, kEvtPost);
+  uint32_t n_pre = 0, n_set = 0;
+  for (uint32_t o = o0; o < o1; ++o) {
+    const uint32_t role = L.occ_role[o];
+    L.occ_kill[o] = (role & kRoleKill) ? 1 : 0;   // kill flags, in occurrence order
+    n_pre += (role & kRolePreKill) ? 1u : 0u;
+    n_set += (role & kRoleTestSet) ? 1u : 0u;
+  }
+  uint32_t at_pre = base, at_set = base + n_pre, at_post = base + n_pre + n_set;
+  for (uint32_t o = o0; o < o1; ++o) {
+    const uint32_t role = L.occ_role[o];
+    if (!(role & (kRolePreKill | kRoleTestSet | kRolePostKill))) continue;
+    // an instruction's own operands are always inside the ring when its events are replayed
+    const u32x4 r = event_record(m, o, m.occ_vreg[o], false, true);
+    if (role & kRolePreKill) L.plan[at_pre++] = r;
+    if (role & kRoleTestSet) { u32x4 q = r; q.w |= kEvtTested; L.plan[at_set++] = q; }
+    if (role & kRolePostKill) { u32x4 q = r; q.w |= kEvtPost; L.plan[at_post++] = q; }
+  }
 }
 
 // number of events of each instruction: the roles of its operands (the counterpart of the

@@ -97,13 +97,38 @@ extern "C" int32_t vl_mir_create(const vl_mir_desc *d, vl_mir **out) {
     for (uint32_t o = d->instr_occ_off[i]; o < d->instr_occ_off[i + 1]; ++o) occ_instr[o] = i;
   for (uint32_t b = 0; b < B; ++b)
     for (uint32_t i = d->blk_start[b]; i < d->blk_start[b + 1]; ++i) instr_blk[i] = b;
-  for (uint32_t v = 0; v < V; ++v) vattr[v] = vl::attr_pack(d->vreg_class[v], d->vreg_width[v], d->vreg_align[v]);
   std::vector<uint64_t> occ_rec(O ? O : 1);
   for (uint32_t o = 0; o < O; ++o)
     occ_rec[o] = (uint64_t)d->occ_vreg[o] | ((uint64_t)((occ_instr[o] << 2) | (d->occ_flags[o] & 3u)) << 32);
   std::vector<uint8_t> instr_keep(N, 0);
   for (uint32_t o = 0; o < O; ++o)
     if (d->occ_flags[o] & VL_OCC_EARLY) instr_keep[occ_instr[o]] = 1;
+
+  // the device header's class tables come first: the packed attributes carry the class's mask word
+  vl::DevMir hh;
+  memset(&hh, 0, sizeof(hh));
+  // mask words: classes smallest first, so that the 16 words every class may address from
+  // its first one mostly fall on words of later classes
+  std::vector<uint32_t> order(d->n_class);
+  for (uint32_t c = 0; c < d->n_class; ++c) order[c] = c;
+  std::stable_sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) { return d->class_size[a] < d->class_size[b]; });
+  uint32_t words = 0, reach = 0;
+  for (uint32_t c : order) {
+    hh.class_word[c] = (uint16_t)words;
+    reach = std::max(reach, words + 16u);
+    words += (d->class_size[c] + 31u) / 32u;
+  }
+  hh.occ_words = reach;
+  for (uint32_t c = 0; c < d->n_class; ++c) {
+    hh.class_size[c] = d->class_size[c];
+    if (d->class_reserved)
+      for (int w = 0; w < 16; ++w) {
+        hh.reserved[c][w] = d->class_reserved[c * 16 + w];
+        if (hh.reserved[c][w]) hh.has_reserved = 1;
+      }
+  }
+  for (uint32_t v = 0; v < V; ++v)
+    vattr[v] = vl::attr_pack(d->vreg_class[v], d->vreg_width[v], d->vreg_align[v]) | ((uint32_t)hh.class_word[d->vreg_class[v]] << 16);
 
   Bump bump;
   size_t o_blk = bump.take((B + 1) * 4), o_soff = bump.take((B + 1) * 4), o_succ = bump.take((size_t)(E ? E : 1) * 4);
@@ -116,7 +141,7 @@ extern "C" int32_t vl_mir_create(const vl_mir_desc *d, vl_mir **out) {
 
   vl_mir *m = new (std::nothrow) vl_mir;
   if (!m) return VL_E_SHAPE;
-  memset(&m->h, 0, sizeof(m->h));
+  m->h = hh;
   m->arena = nullptr;
   m->magic = vl::kMirMagic;
   hipError_t e = hipGetDevice(&m->device);
@@ -151,26 +176,6 @@ extern "C" int32_t vl_mir_create(const vl_mir_desc *d, vl_mir **out) {
   h.occ_flags = (const uint8_t VL_GLOBAL *)(base + o_of);
   h.occ_rec = (const uint64_t VL_GLOBAL *)(base + o_rec);
   h.instr_keep = (const uint8_t VL_GLOBAL *)(base + o_keep);
-  // mask words: classes smallest first, so that the 16 words every class may address from
-  // its first one mostly fall on words of later classes
-  std::vector<uint32_t> order(d->n_class);
-  for (uint32_t c = 0; c < d->n_class; ++c) order[c] = c;
-  std::stable_sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) { return d->class_size[a] < d->class_size[b]; });
-  uint32_t words = 0, reach = 0;
-  for (uint32_t c : order) {
-    h.class_word[c] = (uint16_t)words;
-    reach = std::max(reach, words + 16u);
-    words += (d->class_size[c] + 31u) / 32u;
-  }
-  h.occ_words = reach;
-  for (uint32_t c = 0; c < d->n_class; ++c) {
-    h.class_size[c] = d->class_size[c];
-    if (d->class_reserved)
-      for (int w = 0; w < 16; ++w) {
-        h.reserved[c][w] = d->class_reserved[c * 16 + w];
-        if (h.reserved[c][w]) h.has_reserved = 1;
-      }
-  }
   m->dev = (vl::DevMir *)(base + o_dev);
   up(o_dev, &h, sizeof(h));
   if (e != hipSuccess) {
