@@ -958,6 +958,11 @@ __device__ inline void f_tile_range(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL
 // steps of one chain (scans, prefixes) overlap the bandwidth-heavy steps of another.  A
 // part made of one wavefront per item gets four items per 256-thread block.
 struct StageGrid { uint32_t a, b, c; };   // blocks of the three parts, in launch order
+// The grids are sized for the largest kernel of the batch, so most blocks belong to smaller
+// kernels and exit at once.  A block of the part that counts each instruction's events (light
+// work) takes this many stretches of 256 instructions, which keeps their number down; the
+// heavier parts are faster with one stretch per block.
+constexpr uint32_t kStageReps = 4;
 
 __global__ __launch_bounds__(256) void k_stage_count(MIRS, StageGrid g) {
   const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
@@ -965,7 +970,8 @@ __global__ __launch_bounds__(256) void k_stage_count(MIRS, StageGrid g) {
   const uint32_t bx = blockIdx.x, tx = threadIdx.x;
   if (bx < g.a) f_tile_delta(m, L, bx, tx, 256);
   else if (bx < g.a + g.b) f_boundary<false>(m, L, (bx - g.a) * 4 + (tx >> 6), tx & 63u, 64);
-  else f_item_count(m, L, bx - g.a - g.b, tx, 256);
+  else
+    for (uint32_t r = 0; r < kStageReps; ++r) f_item_count(m, L, (bx - g.a - g.b) * kStageReps + r, tx, 256);
 }
 
 __global__ __launch_bounds__(1024) void k_stage_scan(MIRS, StageGrid g) {
@@ -1304,7 +1310,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
   }
   k_events<<<grid1(maxO, kEvtThreads, n), kEvtThreads, 0, stream>>>(dm, dl);
   auto blocks = [](uint32_t items, uint32_t per) { return std::max(1u, (items + per - 1) / per); };
-  const StageGrid g_count = {maxT, blocks(maxB, 4), blocks(maxN, TB)};
+  const StageGrid g_count = {maxT, blocks(maxB, 4), blocks(maxN, TB * kStageReps)};
   const StageGrid g_scan = {1, 1, blocks(maxW, 1024)};
   const StageGrid g_off = {blocks(maxT, 4), blocks(maxO / 64 + 2, TB), blocks(maxV + 1, TB)};
   k_stage_count<<<dim3(g_count.a + g_count.b + g_count.c, n), 256, (size_t)maxW * 4, stream>>>(dm, dl, g_count);
