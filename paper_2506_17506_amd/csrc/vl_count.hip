@@ -112,35 +112,75 @@ __global__ __launch_bounds__(256) void k_cnt_table(const DevCountJob *__restrict
     if (v0 + vv < m.V && k0 + tx < J.k_pad) J.table[(size_t)(v0 + vv) * J.k_pad + k0 + tx] = tile[tx][vv];
 }
 
-// consistency: one candidate per blockIdx.y, 1024 occurrences per workgroup
+// consistency: a workgroup takes 64 candidates (blockIdx.y) and 1024 occurrences.  64
+// occurrences of the 64 rows at a time go through LDS, read along the rows; then a lane is a
+// candidate and compares, occurrence by occurrence, its register with its entry in the
+// table row of the occurrence's vreg (one coalesced read for the 64 candidates).
 __global__ __launch_bounds__(256) void k_cnt_cons(const DevCountJob *__restrict__ jobs) {
   const DevCountJob &J = jobs[blockIdx.z];
   const DevMir VL_GLOBAL &m = *as_global(J.mir);
-  const DevLive VL_GLOBAL &L = *as_global(J.live);
-  const uint32_t k = blockIdx.y, o0 = blockIdx.x * 1024;
-  if (k >= J.K || o0 >= m.O) return;
-  const uint16_t *row = J.cand + (uint64_t)k * J.ld;
+  const uint32_t k0 = blockIdx.y * 64, o0 = blockIdx.x * 1024;
+  if (k0 >= J.K || o0 >= m.O) return;
+  __shared__ uint16_t tile[64][66];
+  const uint32_t lane = threadIdx.x & 63u, first = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6) * 16u;
+  const uint32_t o_end = min(m.O, o0 + 1024u);
   uint32_t n = 0;
-  for (uint32_t o = o0 + threadIdx.x; o < min(m.O, o0 + 1024u); o += 256) n += row[o] != row[L.first[m.occ_vreg[o]]];
-  for (int d = 32; d >= 1; d >>= 1) n += (uint32_t)__shfl_xor((int)n, d, 64);
-  if ((threadIdx.x & 63u) == 0 && n) atomicAdd(&J.out[k].n_cons, n);
+  for (uint32_t oc = o0; oc < o_end; oc += 64) {
+    const bool in = oc + lane < o_end;
+    // this wavefront's 16 rows, all loads in flight together
+    uint16_t mine[16];
+#pragma unroll
+    for (uint32_t u = 0; u < 16; ++u) {
+      const uint32_t k = k0 + first + u;
+      mine[u] = (in && k < J.K) ? J.cand[(uint64_t)k * J.ld + oc + lane] : (uint16_t)0;
+    }
+    const uint32_t my_v = in ? m.occ_vreg[oc + lane] : 0u;
+#pragma unroll
+    for (uint32_t u = 0; u < 16; ++u) tile[first + u][lane] = mine[u];
+    __syncthreads();
+    const uint32_t cnt = min(64u, o_end - oc);
+    // this wavefront's quarter of the 64 occurrences; rows past the last candidate hold zeros
+    // in the tile and in the table
+    uint32_t q[16];
+#pragma unroll
+    for (uint32_t u = 0; u < 16; ++u)
+      q[u] = J.table[(size_t)__builtin_amdgcn_readlane(my_v, first + u) * J.k_pad + k0 + lane];
+#pragma unroll
+    for (uint32_t u = 0; u < 16; ++u) n += (first + u < cnt && tile[lane][first + u] != q[u]) ? 1u : 0u;
+    __syncthreads();
+  }
+  if (k0 + lane < J.K && n) atomicAdd(&J.out[k0 + lane].n_cons, n);
 }
 
-// realizability: one candidate per blockIdx.y, one vreg per lane
+// realizability: a wavefront takes 64 candidates (one per lane) and 64 vregs, whose table
+// rows it reads one after the other
 __global__ __launch_bounds__(256) void k_cnt_real(const DevCountJob *__restrict__ jobs) {
   const DevCountJob &J = jobs[blockIdx.z];
   const DevMir VL_GLOBAL &m = *as_global(J.mir);
   const DevLive VL_GLOBAL &L = *as_global(J.live);
-  const uint32_t k = blockIdx.y, v = blockIdx.x * 256 + threadIdx.x;
-  if (k >= J.K || blockIdx.x * 256 >= m.V) return;
-  uint32_t bits = 0;
-  if (v < m.V && L.first[v] != kNone) bits = bad_bits(m, m.vattr[v], J.cand[(uint64_t)k * J.ld + L.first[v]]);
-  uint32_t n = bits != 0;
-  for (int d = 32; d >= 1; d >>= 1) {
-    n += (uint32_t)__shfl_xor((int)n, d, 64);
-    bits |= (uint32_t)__shfl_xor((int)bits, d, 64);
+  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+  const uint32_t k = blockIdx.y * 64 + lane, v0 = blockIdx.x * 256 + wave * 64;
+  if (blockIdx.y * 64 >= J.K || v0 >= m.V) return;
+  // one vreg per lane: its attributes, or none when it is never mentioned
+  const uint32_t my_v = v0 + lane;
+  const bool mentioned = my_v < m.V && L.first[my_v] != kNone;
+  const uint32_t my_attr = mentioned ? m.vattr[my_v] : kNone;
+  uint32_t n = 0, bits = 0;
+  const uint32_t v_end = min(64u, m.V - v0);
+  for (uint32_t t0 = 0; t0 < v_end; t0 += 16) {   // 16 table rows in flight
+    uint32_t p[16];
+#pragma unroll
+    for (uint32_t u = 0; u < 16; ++u) p[u] = J.table[(size_t)min(v0 + t0 + u, m.V - 1) * J.k_pad + k];
+#pragma unroll
+    for (uint32_t u = 0; u < 16; ++u) {
+      const uint32_t attr = __builtin_amdgcn_readlane(my_attr, t0 + u);   // none past the last vreg
+      if (attr == kNone) continue;
+      const uint32_t bad = bad_bits(m, attr, p[u]);
+      n += bad != 0;
+      bits |= bad;
+    }
   }
-  if ((threadIdx.x & 63u) == 0 && n) {
+  if (k < J.K && n) {
     atomicAdd(&J.out[k].n_real, n);
     atomicOr(&J.out[k].real_bits, bits);
   }
@@ -362,8 +402,8 @@ extern "C" int32_t vl_count_violations_multi(const vl_count_job *jobs, uint32_t 
   const uint32_t stretches = (uint32_t)std::max<uint64_t>(1, (max_pairs + kPairsPerGroup - 1) / kPairsPerGroup);
   k_cnt_clear<<<dim3((maxK + 255) / 256, n_jobs), 256, 0, stream>>>(w.dev);
   k_cnt_table<<<dim3(tiles_v * tiles_k, n_jobs), 256, 0, stream>>>(w.dev, tiles_k);
-  k_cnt_cons<<<dim3((maxO + 1023) / 1024, maxK, n_jobs), 256, 0, stream>>>(w.dev);
-  k_cnt_real<<<dim3((maxV + 255) / 256, maxK, n_jobs), 256, 0, stream>>>(w.dev);
+  k_cnt_cons<<<dim3((maxO + 1023) / 1024, tiles_k, n_jobs), 256, 0, stream>>>(w.dev);
+  k_cnt_real<<<dim3((maxV + 255) / 256, tiles_k, n_jobs), 256, 0, stream>>>(w.dev);
   k_cnt_safe<<<dim3(stretches, n_jobs), 256, 0, stream>>>(w.dev);
   k_cnt_kinds<<<dim3((maxK + 255) / 256, n_jobs), 256, 0, stream>>>(w.dev);
   VL_HIP(hipGetLastError());
