@@ -187,8 +187,8 @@ __global__ __launch_bounds__(256) void k_cnt_real(const DevCountJob *__restrict_
 }
 
 // safety: a wavefront takes 1024 of the pairs, fetched 64 at a time (one pair per lane, read
-// out of the lanes), and walks them once for every group of 64 candidates (one per lane): the
-// two table rows of a pair are then read for all groups back to back
+// out of the lanes), and walks them once for every group of 128 candidates: a lane holds two
+// neighbouring candidates, whose registers are one 32-bit word of a table row
 constexpr uint32_t kPairsPerWave = 1024, kPairsPerGroup = 4 * kPairsPerWave;
 __global__ __launch_bounds__(256) void k_cnt_safe(const DevCountJob *__restrict__ jobs) {
   const DevCountJob &J = jobs[blockIdx.y];
@@ -197,11 +197,11 @@ __global__ __launch_bounds__(256) void k_cnt_safe(const DevCountJob *__restrict_
   const uint64_t e0 = (uint64_t)blockIdx.x * kPairsPerGroup + (uint64_t)(threadIdx.x >> 6) * kPairsPerWave;
   if (e0 >= J.n_pairs) return;
   const uint64_t e1 = min(J.n_pairs, e0 + kPairsPerWave);
-  const uint32_t groups = J.k_pad / 64;
-  for (uint32_t g0 = 0; g0 < groups; g0 += 2) {   // two groups of candidates per pass over the pairs
-    const uint32_t k0 = g0 * 64 + lane, k1 = min(k0 + 64, J.k_pad - 64 + lane);   // an odd last group is counted once
-    const bool second = g0 + 1 < groups;
-    uint32_t n0 = 0, n1 = 0;
+  const uint32_t words = J.k_pad / 2;   // 32-bit words per table row (k_pad is a multiple of 64)
+  const uint32_t *table32 = reinterpret_cast<const uint32_t *>(J.table);
+  for (uint32_t w0 = 0; w0 < words; w0 += 64) {
+    const uint32_t wi = min(w0 + lane, words - 1);   // lanes past the row repeat its last word; not counted
+    uint32_t n_lo = 0, n_hi = 0;
     for (uint64_t e = e0; e < e1; e += 64) {
       uint32_t pa = 0, pb = 0, wa = 0, wb = 0;
       if (e + lane < e1) {
@@ -210,29 +210,31 @@ __global__ __launch_bounds__(256) void k_cnt_safe(const DevCountJob *__restrict_
         wa = attr_width(m.vattr[pa]);
         wb = attr_width(m.vattr[pb]);
       }
-      // Four pairs at a time, their table reads in flight together.  Lanes past the last
+      // Eight pairs at a time, their table reads in flight together.  Lanes past the last
       // pair hold the pair (0, 0) with widths 0, which never overlaps, so no tail is needed.
       const uint32_t cnt = (uint32_t)min((uint64_t)64, e1 - e);
-      for (uint32_t j = 0; j < cnt; j += 4) {
-        uint32_t ra0[4], rb0[4], ra1[4], rb1[4];
+      for (uint32_t j = 0; j < cnt; j += 8) {
+        uint32_t ra[8], rb[8];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          const uint32_t a = __builtin_amdgcn_readlane(pa, j + t), b = __builtin_amdgcn_readlane(pb, j + t);
-          ra0[t] = J.table[(size_t)a * J.k_pad + k0];   // k0, k1 < k_pad always
-          rb0[t] = J.table[(size_t)b * J.k_pad + k0];
-          ra1[t] = J.table[(size_t)a * J.k_pad + k1];
-          rb1[t] = J.table[(size_t)b * J.k_pad + k1];
+        for (int t = 0; t < 8; ++t) {
+          const uint32_t a = __builtin_amdgcn_readlane(pa, (j + t) & 63u), b = __builtin_amdgcn_readlane(pb, (j + t) & 63u);
+          ra[t] = table32[(size_t)a * words + wi];
+          rb[t] = table32[(size_t)b * words + wi];
         }
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          const uint32_t sa = __builtin_amdgcn_readlane(wa, j + t), sb = __builtin_amdgcn_readlane(wb, j + t);
-          n0 += ra0[t] < rb0[t] + sb && rb0[t] < ra0[t] + sa;
-          n1 += ra1[t] < rb1[t] + sb && rb1[t] < ra1[t] + sa;
+        for (int t = 0; t < 8; ++t) {
+          const uint32_t sa = __builtin_amdgcn_readlane(wa, (j + t) & 63u), sb = __builtin_amdgcn_readlane(wb, (j + t) & 63u);
+          const uint32_t al = ra[t] & 0xFFFFu, ah = ra[t] >> 16, bl = rb[t] & 0xFFFFu, bh = rb[t] >> 16;
+          n_lo += al < bl + sb && bl < al + sa;
+          n_hi += ah < bh + sb && bh < ah + sa;
         }
       }
     }
-    if (k0 < J.K && n0) atomicAdd(&J.out[k0].n_safe, n0);
-    if (second && k0 + 64 < J.K && n1) atomicAdd(&J.out[k0 + 64].n_safe, n1);
+    const uint32_t k = 2 * (w0 + lane);
+    if (w0 + lane < words) {
+      if (k < J.K && n_lo) atomicAdd(&J.out[k].n_safe, n_lo);
+      if (k + 1 < J.K && n_hi) atomicAdd(&J.out[k + 1].n_safe, n_hi);
+    }
   }
 }
 
