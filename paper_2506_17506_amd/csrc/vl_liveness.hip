@@ -302,18 +302,38 @@ __global__ __launch_bounds__(kSumThreads) void k_summary(MIRS, const uint32_t ld
     __syncthreads();
   }
   uint32_t *def_l = sm, *use_l = sm + m.B * nw;
-  for (uint32_t e0 = s0; e0 < s1; e0 += kSumThreads) {
+  // the lane's entries of the slice, each a chain of three dependent reads (occurrence, its
+  // record, its block): the chains run side by side
+  constexpr uint32_t kPer = kSumSlice / kSumThreads;
+  uint64_t recs[kPer];
+  uint32_t blks[kPer];
+  {
+    uint32_t occ[kPer];
+#pragma unroll
+    for (uint32_t u = 0; u < kPer; ++u) {
+      const uint32_t e = s0 + u * kSumThreads + threadIdx.x;
+      occ[u] = e < s1 ? L.vocc[e] : kNone;
+    }
+#pragma unroll
+    for (uint32_t u = 0; u < kPer; ++u) recs[u] = occ[u] != kNone ? m.occ_rec[occ[u]] : 0ull;
+#pragma unroll
+    for (uint32_t u = 0; u < kPer; ++u) blks[u] = occ[u] != kNone ? m.instr_blk[(uint32_t)(recs[u] >> 34)] : kNone;
+  }
+#pragma unroll
+  for (uint32_t u = 0; u < kPer; ++u) {
+    const uint32_t e0 = s0 + u * kSumThreads;
+    if (e0 >= s1) break;
     const uint32_t e = e0 + threadIdx.x;
     uint32_t b = kNone, w = 0, dbits = 0, ubits = 0, v = kNone, i = kNone, fl = 0;
     if (e < s1) {
       // also records instruction and flags of each sorted entry for the kernels that follow
-      const uint64_t rec = m.occ_rec[L.vocc[e]];
+      const uint64_t rec = recs[u];
       v = (uint32_t)rec;
       const uint32_t ifl = (uint32_t)(rec >> 32);
       L.ent_instr[e] = ifl;
       i = ifl >> 2;
       fl = ifl & 3u;
-      b = m.instr_blk[i];
+      b = blks[u];
       w = v >> 5;
       if (fl & VL_OCC_DEF) dbits = 1u << (v & 31);
     }
