@@ -140,3 +140,35 @@ def test_many_blocks_times_many_words():
     m = many_blocks_mir(7, gap=24)
     assert m.n_block == 150 and (m.n_vreg + 31) // 32 > 200 and m.n_occ > 3 * 4096
     run_case(m, K=24, seed=31, tile_lens=[0, 100])
+
+
+def test_thousands_of_clashes_in_one_call():
+    """Two programs with 5,000 candidates each, nearly all of which fail on safety (one value
+    moved onto the register of a value it interferes with): the pairs of far more failing
+    candidates than there are workgroups to look for them."""
+    mirs = [mixed_mir(0xD001, n_instr=500), mixed_mir(0xD002, n_instr=700)]
+    rows_list, wants = [], []
+    for j, m in enumerate(mirs):
+        an = vlo.analyze(m, threads=8)
+        assert an.contract == 0
+        rng = np.random.default_rng(100 + j)
+        table = coloured_table(m, an, rng)
+        a, b = np.asarray(an.edges["a"]), np.asarray(an.edges["b"])
+        same = ((m.vreg_class[a] == m.vreg_class[b]) & (m.vreg_width[a] == m.vreg_width[b]) &
+                (m.vreg_align[a] == m.vreg_align[b]))
+        a, b = a[same], b[same]
+        assert len(a) > 100
+        K = 5000
+        rows = np.tile(table[m.occ_vreg].astype(np.uint16), (K, 1))
+        for k in range(1, K):   # row 0 stays as coloured
+            e = int(rng.integers(0, len(a)))
+            rows[k, m.occ_vreg == a[e]] = table[b[e]]
+        rows_list.append(rows)
+        wants.append(vlo.verify(m, an, rows, threads=8))
+    assert sum(int((w["status"] == 3).sum()) for w in wants) > 8000
+    hm, hl, _, _ = gpu_analyze(mirs, dense=False)
+    try:
+        for res, want, m in zip(gpu_verify(hm, hl, rows_list), wants, mirs):
+            assert_results_equal(want, res, m.name)
+    finally:
+        free(hm, hl)
