@@ -248,7 +248,13 @@ __device__ inline bool unrealizable(const DevMir VL_GLOBAL &m, uint32_t attr, ui
 
 template <uint32_t kRingStride, bool kT>
 __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(6))) void k_walk(const DevJob *__restrict__ jobs, uint32_t n_jobs) {
-  const DevJob VL_GLOBAL &J = as_global(jobs)[find_job(jobs, n_jobs, blockIdx.x)];
+  // Workgroups go to the eight dies of the device in turn, each die with an L2 of its own.
+  // Inside every 16 consecutive workgroup indices, units 2x and 2x + 1 are given to indices
+  // x and x + 8: the two candidate groups of one tile (neighbouring units when a job has two
+  // groups) then run on the same die and read the tile's stream records through one L2.
+  uint32_t unit = blockIdx.x;
+  if ((unit | 15u) < gridDim.x) unit = (unit & ~15u) | ((unit & 7u) << 1) | ((unit >> 3) & 1u);
+  const DevJob VL_GLOBAL &J = as_global(jobs)[find_job(jobs, n_jobs, unit)];
   const DevMir VL_GLOBAL &m = *as_global(J.mir);
   const DevLive VL_GLOBAL &L = *as_global(J.live);
   // arrays of the kernel and of its analysis, as global pointers
@@ -258,7 +264,7 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(6)
   // 8-byte stream entries are read as one 64-bit word: x in the low half, y in the high half
   const u32x4 VL_GLOBAL *g_chk = L.chk, *g_seeds = L.seeds;
   const u32x4 VL_GLOBAL *g_plan = L.plan;
-  const uint32_t local = blockIdx.x - J.unit_base;
+  const uint32_t local = unit - J.unit_base;
   const uint32_t tile = local / J.n_groups, group = local % J.n_groups;
   const uint32_t row0 = group * J.rows;
   Walk w;
