@@ -156,7 +156,17 @@ enum { VL_BAD_BOUNDS = 1, VL_BAD_ALIGN = 2, VL_BAD_RESERVED = 4 };
 int32_t vl_verify_batch(const vl_mir *mir, const vl_live *live, const uint16_t *cand, uint32_t K,
                         uint64_t ld, vl_result *out, vl_stream stream);
 
-/* Many kernels in one launch.  jobs is [host]; cand/out inside are [device]. */
+/* Many kernels in one launch.  jobs is [host] and is copied before the call returns;
+ * cand/out inside are [device].  Asynchronous on `stream`; calls on different streams may
+ * overlap on the device.  Device memory owned by the library: per device and calling
+ * stream (up to four streams at a time; a fifth takes over the least recently used slot
+ * after waiting for the device) a copy of the job table and a list of the candidates whose
+ * clashing pair has to be found.  Both grow on demand, which waits for the stream and
+ * allocates; a call whose jobs are no more, and whose candidates in total are no more, than
+ * in an earlier call on that stream allocates nothing, and when its job table is unchanged
+ * it only enqueues kernels.  Errors: VL_E_NULL (a pointer missing), VL_E_ARG (a handle that
+ * is not a live handle of its program, or more than 16 devices), VL_E_SHAPE (n_jobs = 0 or
+ * above 65,535, K = 0, ld below n_occ), VL_E_HIP. */
 typedef struct {
   const vl_mir *mir;
   const vl_live *live;
