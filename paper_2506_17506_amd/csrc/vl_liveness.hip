@@ -199,11 +199,17 @@ __device__ inline void f_sort_short(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL
     }
     return;
   }
-  for (uint32_t j = 0; j < len; ++j) {
-    const uint32_t x = L.vocc_tmp[lo + j];
+  // up to kShortList: the same with twice the registers (a lane or two of most wavefronts)
+  static_assert(kShortList <= 16, "the register sort holds 16 occurrences");
+  uint32_t a[16];
+#pragma unroll
+  for (uint32_t k = 0; k < 16; ++k) a[k] = k < len ? L.vocc_tmp[lo + k] : kNone;
+#pragma unroll
+  for (uint32_t j = 0; j < 16; ++j) {
     uint32_t r = 0;
-    for (uint32_t k = 0; k < len; ++k) r += L.vocc_tmp[lo + k] < x;
-    put(lo + r, x);
+#pragma unroll
+    for (uint32_t k = 0; k < 16; ++k) r += a[k] < a[j];
+    if (j < len) put(lo + r, a[j]);
   }
 }
 
