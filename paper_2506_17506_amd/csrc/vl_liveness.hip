@@ -325,6 +325,22 @@ __global__ __launch_bounds__(kSumThreads) void k_summary(MIRS, const uint32_t ld
 #pragma unroll
     for (uint32_t u = 0; u < kPer; ++u) blks[u] = occ[u] != kNone ? m.instr_blk[(uint32_t)(recs[u] >> 34)] : kNone;
   }
+  // the three entries below the wavefront's first one, held by lanes 0..2 (lane l: the entry
+  // l + 1 below), for the lanes whose earlier neighbours are not in this wavefront
+  uint64_t below_rec[kPer];
+  uint32_t below_blk[kPer];
+  {
+    uint32_t occ[kPer];
+#pragma unroll
+    for (uint32_t u = 0; u < kPer; ++u) {
+      const uint32_t wave_first = s0 + u * kSumThreads + (threadIdx.x & ~63u);
+      occ[u] = (lane < 3 && wave_first < s1 && wave_first >= (uint32_t)lane + 1u) ? L.vocc[wave_first - 1u - lane] : kNone;
+    }
+#pragma unroll
+    for (uint32_t u = 0; u < kPer; ++u) below_rec[u] = occ[u] != kNone ? m.occ_rec[occ[u]] : ~0ull;   // none: another vreg
+#pragma unroll
+    for (uint32_t u = 0; u < kPer; ++u) below_blk[u] = occ[u] != kNone ? m.instr_blk[(uint32_t)(below_rec[u] >> 34)] : kNone;
+  }
 #pragma unroll
   for (uint32_t u = 0; u < kPer; ++u) {
     const uint32_t e0 = s0 + u * kSumThreads;
@@ -344,16 +360,20 @@ __global__ __launch_bounds__(kSumThreads) void k_summary(MIRS, const uint32_t ld
       if (fl & VL_OCC_DEF) dbits = 1u << (v & 31);
     }
     // Is this mention group the first of its vreg in the block?  The nearest earlier entry
-    // with another instruction decides; it usually sits a lane or two below.
+    // with another instruction decides; it usually sits an entry or two below.
     bool decided = !(fl & VL_OCC_USE), first_in_block = false;
+    const uint32_t bv = (uint32_t)below_rec[u], bi = (uint32_t)(below_rec[u] >> 34), bb = below_blk[u];
     for (int d = 1; d <= 3; ++d) {
-      const uint32_t pv = __shfl_up(v, d, 64), pi = __shfl_up(i, d, 64), pb = __shfl_up(b, d, 64);
-      if (!decided && lane >= d) {
+      uint32_t pv = __shfl_up(v, d, 64), pi = __shfl_up(i, d, 64), pb = __shfl_up(b, d, 64);
+      const int src = (d - 1 - lane) & 63;   // for the lanes below d: the lane that holds their entry d below
+      const uint32_t hv = __shfl(bv, src, 64), hi = __shfl(bi, src, 64), hb = __shfl(bb, src, 64);
+      if (lane < d) { pv = hv; pi = hi; pb = hb; }
+      if (!decided) {
         if (pv != v) { first_in_block = true; decided = true; }
         else if (pi != i) { first_in_block = pb != b; decided = true; }
       }
     }
-    if (!decided) {   // the group reaches below this wavefront's first lane, or is long: look it up
+    if (!decided) {   // four or more mentions in one instruction: look the start of the group up
       const uint32_t lo = L.vcnt[v];
       uint32_t gs = e;
       while (gs > lo && (uint32_t)(m.occ_rec[L.vocc[gs - 1]] >> 34) == i) --gs;
