@@ -524,8 +524,14 @@ __global__ __launch_bounds__(kEvtThreads) void k_events(MIRS) {
   auto ent = [&](uint32_t x) { const uint32_t r = x - win_lo; return r < kEvtWindow ? s_ifl[r] : L.ent_instr[x]; };
   auto occ_at = [&](uint32_t x) { const uint32_t r = x - win_lo; return r < kEvtWindow ? s_occ[r] : L.vocc[x]; };
   const uint32_t o = s_occ[threadIdx.x + kEvtHalo], v = s_v[threadIdx.x + kEvtHalo];
+  const uint32_t ifl = s_ifl[threadIdx.x + kEvtHalo], i = ifl >> 2;
+  // What is read from memory depends on (v, i) first and on the blocks found second: the reads
+  // of each level are issued together, with indices clamped where the value may not be needed,
+  // so that a lane waits for memory twice instead of once per branch taken.
   const uint32_t lo = L.vcnt[v], hi = L.vcnt[v + 1];
-  const uint32_t ifl = s_ifl[threadIdx.x + kEvtHalo], i = ifl >> 2, b = m.instr_blk[i];
+  const uint32_t b = m.instr_blk[i], blk_before = m.instr_blk[i > 0 ? i - 1 : 0];
+  const bool keeps = m.instr_keep[i] != 0, kept_before = m.instr_keep[i > 0 ? i - 1 : 0] != 0;
+  const uint32_t attr = m.vattr[v], last_live_v = L.last_live[v];
   uint32_t gs = e, ge = e + 1;
   while (gs > lo && (ent(gs - 1) >> 2) == i) --gs;
   while (ge < hi && (ent(ge) >> 2) == i) ++ge;
@@ -536,20 +542,27 @@ __global__ __launch_bounds__(kEvtThreads) void k_events(MIRS) {
     if (f & VL_OCC_USE) { has_use = true; if (first_use == kNone) first_use = x; }
     if (f & VL_OCC_DEF) { has_def = true; if (first_def == kNone) first_def = x; }
   }
-  bool la;
   const uint32_t nxt = ge < hi ? ent(ge) : 0u;
-  if (ge < hi && m.instr_blk[nxt >> 2] == b) {
+  // second level
+  const uint32_t vw = v >> 5, vbit = 1u << (v & 31);
+  const uint32_t blk_next = m.instr_blk[nxt >> 2];
+  const bool out_b = (L.live_out[(size_t)b * m.W + vw] & vbit) != 0;
+  const bool out_below = (L.live_out[(size_t)(b > 0 ? b - 1 : 0) * m.W + vw] & vbit) != 0;
+  const bool out_before = (L.live_out[(size_t)blk_before * m.W + vw] & vbit) != 0;
+  const uint32_t start_b = m.blk_start[b], start_b1 = m.blk_start[b + 1];
+  const uint32_t F = m.class_size[attr_class(attr)];
+  bool la;
+  if (ge < hi && blk_next == b) {
     la = (nxt & VL_OCC_USE) != 0;
     for (uint32_t x = ge + 1; x < hi && (ent(x) >> 2) == (nxt >> 2); ++x) la |= (ent(x) & VL_OCC_USE) != 0;
   } else {
-    la = bit_get(L.live_out + (size_t)b * m.W, v);
+    la = out_b;
   }
   const uint32_t fl = ifl & 3u;
   const bool kill = (fl & VL_OCC_USE) && !has_def && !la;
   uint8_t role = 0;
   // an instruction with an early-clobber definition keeps what it reads occupied until it has
   // written: the operand that dies here is released after the definitions have been tested
-  const bool keeps = m.instr_keep[i] != 0;
   if (!has_def && !la && e == first_use) role |= keeps ? kRolePostKill : kRolePreKill;
   if (has_def && e == first_def) {
     if (!has_use) role |= kRoleTestSet;
@@ -566,8 +579,7 @@ __global__ __launch_bounds__(kEvtThreads) void k_events(MIRS) {
     const bool keep = o + kWalkReach < (next / kWalkChunk + 1u) * kWalkChunk && next - o <= kKeepMaxGap;
     const uint32_t delta = prev == kNone ? 0u : min(o - prev, 0xFFFFu);
     const bool near = prev != kNone && delta != 0xFFFFu && prev + kWalkReach >= (o / kWalkChunk + 1u) * kWalkChunk;
-    const uint32_t attr = m.vattr[v];
-    const uint32_t width = attr_width(attr), align = attr_align(attr), F = m.class_size[attr_class(attr)];
+    const uint32_t width = attr_width(attr), align = attr_align(attr);
     const bool is_first = (role & kRoleFirst) != 0;
     const bool generic = is_first && ((align & (align - 1u)) != 0 || m.has_reserved || width > F);
     const bool simple = is_first && !generic;
@@ -595,12 +607,11 @@ __global__ __launch_bounds__(kEvtThreads) void k_events(MIRS) {
       prev_def |= (ent(x) & VL_OCC_DEF) != 0;
       prev_use |= (ent(x) & VL_OCC_USE) != 0;
     }
-    const uint32_t pb = m.instr_blk[i - 1];
     // live after i - 1: this group is the next mention; in another block the block's live-out decides
-    const bool prev_la = pb == b ? has_use : bit_get(L.live_out + (size_t)pb * m.W, v);
-    cur = prev_def || prev_la || (prev_use && m.instr_keep[i - 1]);
-  } else if (i > m.blk_start[b]) cur = has_use;
-  else cur = bit_get(L.live_out + (size_t)(b - 1) * m.W, v);
+    const bool prev_la = blk_before == b ? has_use : out_before;
+    cur = prev_def || prev_la || (prev_use && kept_before);
+  } else if (i > start_b) cur = has_use;
+  else cur = out_below;
   uint8_t sf = cur ? kOpenBefore : 0;
   uint32_t n_start = 0;
   auto span = [&](uint32_t s, uint32_t t, bool member) {
@@ -613,14 +624,14 @@ __global__ __launch_bounds__(kEvtThreads) void k_events(MIRS) {
     cur = member;
   };
   span(i, i + 1, has_def || la || (keeps && has_use));
-  const uint32_t i2 = ge < hi ? ent(ge) >> 2 : m.N;
-  const uint32_t b2 = ge < hi ? m.instr_blk[i2] : m.B;
+  const uint32_t i2 = ge < hi ? nxt >> 2 : m.N;
+  const uint32_t b2 = ge < hi ? blk_next : m.B;
   if (b2 == b) {
     span(i + 1, i2, la);
   } else {
-    span(i + 1, m.blk_start[b + 1], la);
+    span(i + 1, start_b1, la);
     // blocks in between: v is live into none of them after its last live block
-    const uint32_t xe = min(b2, max(b + 1, L.last_live[v] + 1));
+    const uint32_t xe = min(b2, max(b + 1, last_live_v + 1));
     for (uint32_t x = b + 1; x < xe; ++x)
       span(m.blk_start[x], m.blk_start[x + 1], bit_get(L.live_in + (size_t)x * m.W, v));
     if (xe < b2) span(m.blk_start[xe], m.blk_start[xe + 1], false);
