@@ -667,8 +667,7 @@ __device__ inline uint32_t source_occurrence(const DevLive VL_GLOBAL &L, uint32_
 
 // The record of one occupancy event (layout in vl_dev.h).  `near`: the occurrence is
 // certainly inside the verifier's ring when the event is replayed.
-__device__ inline u32x4 event_record(const DevMir VL_GLOBAL &m, uint32_t o, uint32_t v, bool tested, bool near) {
-  const uint32_t attr = m.vattr[v];
+__device__ inline u32x4 event_record(uint32_t o, uint32_t v, uint32_t attr, bool tested, bool near) {
   const uint32_t width = attr_width(attr);
   const bool slow = !near || attr_straddle(attr) || width == 32;
   u32x4 r;
@@ -677,6 +676,9 @@ __device__ inline u32x4 event_record(const DevMir VL_GLOBAL &m, uint32_t o, uint
   r.z = attr_word(attr) * 256u;
   r.w = o | (slow ? kEvtSlow : 0u) | (tested ? kEvtTested : 0u);
   return r;
+}
+__device__ inline u32x4 event_record(const DevMir VL_GLOBAL &m, uint32_t o, uint32_t v, bool tested, bool near) {
+  return event_record(o, v, m.vattr[v], tested, near);
 }
 
 // Between two blocks adjacent in the linear order the occupied set changes from the
@@ -748,6 +750,35 @@ __device__ inline void f_plan_fill(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL 
   const uint32_t base = L.item_off[item_of_instr(m, i)];
   const uint32_t o0 = m.occ_off[i], o1 = m.occ_off[i + 1];
   uint32_t n_pre = 0, n_set = 0;
+  if (o1 - o0 <= 4) {
+    // the common case: roles and vregs of all operands are read together, then their
+    // attributes, so that the lane waits once per level instead of once per operand
+    const uint32_t n = o1 - o0;
+    uint32_t role[4], vv[4], aa[4];
+#pragma unroll
+    for (uint32_t u = 0; u < 4; ++u) {
+      role[u] = u < n ? (uint32_t)L.occ_role[o0 + u] : 0u;
+      vv[u] = u < n ? m.occ_vreg[o0 + u] : 0u;
+    }
+#pragma unroll
+    for (uint32_t u = 0; u < 4; ++u) aa[u] = m.vattr[vv[u]];
+#pragma unroll
+    for (uint32_t u = 0; u < 4; ++u) {
+      if (u < n) L.occ_kill[o0 + u] = (role[u] & kRoleKill) ? 1 : 0;
+      n_pre += (role[u] & kRolePreKill) ? 1u : 0u;
+      n_set += (role[u] & kRoleTestSet) ? 1u : 0u;
+    }
+    uint32_t at_pre = base, at_set = base + n_pre, at_post = base + n_pre + n_set;
+#pragma unroll
+    for (uint32_t u = 0; u < 4; ++u) {
+      if (!(role[u] & (kRolePreKill | kRoleTestSet | kRolePostKill))) continue;
+      const u32x4 r = event_record(o0 + u, vv[u], aa[u], false, true);
+      if (role[u] & kRolePreKill) L.plan[at_pre++] = r;
+      if (role[u] & kRoleTestSet) { u32x4 q = r; q.w |= kEvtTested; L.plan[at_set++] = q; }
+      if (role[u] & kRolePostKill) { u32x4 q = r; q.w |= kEvtPost; L.plan[at_post++] = q; }
+    }
+    return;
+  }
   for (uint32_t o = o0; o < o1; ++o) {
     const uint32_t role = L.occ_role[o];
     L.occ_kill[o] = (role & kRoleKill) ? 1 : 0;   // kill flags, in occurrence order
@@ -894,11 +925,18 @@ __device__ inline void f_tile_delta(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL
   const uint32_t W = m.W, i0 = t * L.tile_len, i1 = min(m.N, i0 + L.tile_len);
   for (uint32_t w = tx; w < W; w += 256) row[w] = 0;
   __syncthreads();
-  for (uint32_t o = m.occ_off[i0] + tx; o < m.occ_off[i1]; o += 256) {
-    if (__popc(L.occ_role[o] & (kRolePreKill | kRoleTestSet | kRolePostKill)) & 1) {
-      const uint32_t v = m.occ_vreg[o];
-      atomicXor(&row[v >> 5], 1u << (v & 31));
+  const uint32_t o_end = m.occ_off[i1];
+  for (uint32_t o = m.occ_off[i0] + tx; o < o_end; o += 4 * 256) {   // four reads of each kind in flight
+    uint32_t role[4], vv[4];
+#pragma unroll
+    for (uint32_t u = 0; u < 4; ++u) {
+      const uint32_t x = o + u * 256;
+      role[u] = x < o_end ? (uint32_t)L.occ_role[x] : 0u;
+      vv[u] = x < o_end ? m.occ_vreg[x] : 0u;
     }
+#pragma unroll
+    for (uint32_t u = 0; u < 4; ++u)
+      if (__popc(role[u] & (kRolePreKill | kRoleTestSet | kRolePostKill)) & 1) atomicXor(&row[vv[u] >> 5], 1u << (vv[u] & 31));
   }
   // boundaries b whose last earlier instruction (blk_start[b] - 1) lies in this tile
   const uint32_t b_lo = m.instr_blk[i0] + 1, b_hi = m.instr_blk[i1 - 1] + 1;   // blocks starting in (i0, i1]
