@@ -816,12 +816,8 @@ __device__ inline void f_evt_cut(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L
   const uint32_t c = bx * bdim + tx;
   const uint32_t n_chunk = (m.O + 63) / 64;
   if (c > n_chunk) return;
-  // first instruction i with occ_off[i + 1] > 64 c
-  uint32_t lo = 0, hi = m.N;
-  while (lo < hi) {
-    const uint32_t mid = (lo + hi) >> 1;
-    if (m.occ_off[mid + 1] > 64 * c) hi = mid; else lo = mid + 1;
-  }
+  // first instruction i with occ_off[i + 1] > 64 c: the one that occurrence 64 c belongs to
+  const uint32_t lo = 64 * c < m.O ? m.occ_instr[64 * c] : m.N;
   uint32_t cut;
   if (lo >= m.N || c == n_chunk) cut = L.item_off[m.N + m.B];
   else {
