@@ -710,6 +710,13 @@ __device__ inline void f_boundary(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &
     const bool near = src < m.occ_off[at] && src + (kWalkReach - 2 * kWalkChunk + 1) >= m.occ_off[at];
     return event_record(m, src, v, false, near);
   };
+  if (!kFill) {   // counting needs no positions: both directions at once, one reduction at the end
+    uint32_t mine = 0;
+    for (uint32_t w = lane; w < W; w += 64) mine += __popc(out_prev[w] ^ in_cur[w]);
+    for (int d = 32; d >= 1; d >>= 1) mine += (uint32_t)__shfl_xor((int)mine, d, 64);
+    if (lane == 0) L.item_off[item] = mine;
+    return;
+  }
   for (int pass = 0; pass < 2; ++pass) {  // 0: leaving, 1: entering
     for (uint32_t w0 = 0; w0 < W; w0 += 64) {
       const uint32_t w = w0 + lane;
@@ -968,6 +975,14 @@ __device__ inline void f_seed(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L, c
   const uint32_t W = m.W;
   uint32_t total = 0;
   const uint32_t base = kFill ? L.seed_off[t] : 0;
+  if (!kFill) {   // counting needs no positions: one reduction at the end
+    uint32_t mine = 0;
+    if (t > 0)
+      for (uint32_t w = lane; w < W; w += 64) mine += __popc(L.tile_live[(size_t)t * W + w]);
+    for (int d = 32; d >= 1; d >>= 1) mine += (uint32_t)__shfl_xor((int)mine, d, 64);
+    if (lane == 0) L.seed_off[t] = mine;
+    return;
+  }
   for (uint32_t w0 = 0; w0 < W; w0 += 64) {
     const uint32_t w = w0 + lane;
     uint32_t bits = (w < W && t > 0) ? L.tile_live[(size_t)t * W + w] : 0u;
