@@ -426,12 +426,21 @@ __global__ __launch_bounds__(64) void k_fixpoint(MIRS) {
   if (blockIdx.x * 64 >= m.W) return;
   const bool act = w < m.W;
   const uint32_t B = m.B, W = m.W;
-  uint32_t *in_l = sm, *use_l = sm + (size_t)B * 64, *def_l = sm + (size_t)2 * B * 64;
-  // the successor lists are walked once per block and sweep: they sit in LDS too
-  uint32_t *succ_off_l = sm + (size_t)3 * B * 64, *succ_l = succ_off_l + B + 1;
+  // in_l has one row more than there are blocks: row B stays empty and stands for "no successor"
+  uint32_t *in_l = sm, *use_l = sm + (size_t)(B + 1) * 64, *def_l = use_l + (size_t)B * 64;
+  // the successor lists are walked once per block and sweep: they sit in LDS too, and the
+  // first two successors of each block (absent ones: row B) in arrays of their own
+  uint32_t *succ_off_l = def_l + (size_t)B * 64, *succ_l = succ_off_l + B + 1;
+  uint32_t *s0_l = succ_l + m.E, *s1_l = s0_l + B;
   if (kLds) {
     for (uint32_t x = lane; x <= B; x += 64) succ_off_l[x] = m.succ_off[x];
     for (uint32_t x = lane; x < m.E; x += 64) succ_l[x] = m.succ[x];
+    for (uint32_t x = lane; x < B; x += 64) {
+      const uint32_t e0 = m.succ_off[x], e1 = m.succ_off[x + 1];
+      s0_l[x] = e0 < e1 ? m.succ[e0] : B;
+      s1_l[x] = e0 + 1 < e1 ? m.succ[e0 + 1] : B;
+    }
+    in_l[B * 64 + lane] = 0;
     for (uint32_t b = 0; b < B; ++b) {
       in_l[b * 64 + lane] = 0;
       use_l[b * 64 + lane] = act ? L.use[(size_t)b * W + w] : 0;
@@ -440,7 +449,32 @@ __global__ __launch_bounds__(64) void k_fixpoint(MIRS) {
   }
   uint32_t sweeps = 0;
   bool changed = true;
-  while (__any(changed)) {   // monotone on a finite lattice: terminates
+  while (kLds && __any(changed)) {   // monotone on a finite lattice: terminates
+    // A block's step is: read the rows of its successors, combine, write its own row.  What
+    // does not depend on the row just written (the successors' indices, use, def and the old
+    // row of the next block) is fetched one block ahead.
+    changed = false;
+    ++sweeps;
+    uint32_t s0 = s0_l[B - 1], s1 = s1_l[B - 1], u = use_l[(B - 1) * 64 + lane], d = def_l[(B - 1) * 64 + lane];
+    uint32_t n_succ = succ_off_l[B] - succ_off_l[B - 1];
+    for (uint32_t b = B; b-- > 0;) {
+      uint32_t out = in_l[s0 * 64 + lane] | in_l[s1 * 64 + lane];
+      const uint32_t old = in_l[b * 64 + lane];
+      if (n_succ > 2)
+        for (uint32_t e = succ_off_l[b] + 2; e < succ_off_l[b + 1]; ++e) out |= in_l[succ_l[e] * 64 + lane];
+      const uint32_t nin = u | (out & ~d);
+      if (b > 0) {
+        s0 = s0_l[b - 1]; s1 = s1_l[b - 1];
+        u = use_l[(b - 1) * 64 + lane]; d = def_l[(b - 1) * 64 + lane];
+        n_succ = succ_off_l[b] - succ_off_l[b - 1];
+      }
+      if (nin != old) {
+        changed = true;
+        in_l[b * 64 + lane] = nin;
+      }
+    }
+  }
+  while (!kLds && __any(changed)) {
     changed = false;
     ++sweeps;
     for (uint32_t b = B; b-- > 0;) {
@@ -1410,7 +1444,7 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     k_summary<<<grid1(maxO, kSumSlice, n), kSumThreads, lds, stream>>>(dm, dl, (uint32_t)(lds / 4));
   }
   {
-    const size_t lds = (size_t)maxB * 64 * 3 * 4 + ((size_t)maxB + 1 + maxE) * 4;
+    const size_t lds = ((size_t)maxB * 3 + 1) * 64 * 4 + ((size_t)maxB * 3 + 1 + maxE) * 4;
     if (lds <= 64 * 1024) k_fixpoint<true><<<grid1(maxW, 64, n), 64, lds, stream>>>(dm, dl);
     else k_fixpoint<false><<<grid1(maxW, 64, n), 64, 0, stream>>>(dm, dl);
   }

@@ -723,6 +723,7 @@ struct Slot {
 };
 constexpr int kSlots = 4;
 constexpr uint64_t kResolveGroups = 4096;   // workgroups that share out the clashes to resolve
+constexpr uint32_t kResolveThreads = 128;   // at least kMaxOperands; 64 and 256 were measured slower
 struct Scratch {
   std::mutex mu;
   Slot slot[kSlots];
@@ -937,7 +938,7 @@ int32_t verify_jobs(const vl_job *jobs, uint32_t n_jobs, hipStream_t stream, boo
   if (g_time_stop) VL_HIP(hipEventRecord(g_time_stop, stream));
   g_time_start = g_time_stop = nullptr;
   k_finalize<<<dim3((L.maxK + 255) / 256, n_jobs), 256, 0, stream>>>(L.dev, L.work);
-  k_resolve<<<(uint32_t)std::min<uint64_t>(L.total_rows, kResolveGroups), 256, (size_t)L.max_w * 4, stream>>>(L.dev, L.work);
+  k_resolve<<<(uint32_t)std::min<uint64_t>(L.total_rows, kResolveGroups), kResolveThreads, (size_t)L.max_w * 4, stream>>>(L.dev, L.work);
   VL_HIP(hipGetLastError());
   return VL_OK;
 }
