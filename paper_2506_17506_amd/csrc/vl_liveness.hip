@@ -441,10 +441,21 @@ __global__ __launch_bounds__(64) void k_fixpoint(MIRS) {
       s1_l[x] = e0 + 1 < e1 ? m.succ[e0 + 1] : B;
     }
     in_l[B * 64 + lane] = 0;
-    for (uint32_t b = 0; b < B; ++b) {
-      in_l[b * 64 + lane] = 0;
-      use_l[b * 64 + lane] = act ? L.use[(size_t)b * W + w] : 0;
-      def_l[b * 64 + lane] = act ? L.def[(size_t)b * W + w] : 0;
+    for (uint32_t b0 = 0; b0 < B; b0 += 8) {   // the rows of eight blocks in flight
+      uint32_t uu[8], dd[8];
+#pragma unroll
+      for (uint32_t t = 0; t < 8; ++t) {
+        const bool in = act && b0 + t < B;
+        uu[t] = in ? L.use[(size_t)(b0 + t) * W + w] : 0;
+        dd[t] = in ? L.def[(size_t)(b0 + t) * W + w] : 0;
+      }
+#pragma unroll
+      for (uint32_t t = 0; t < 8; ++t)
+        if (b0 + t < B) {
+          in_l[(b0 + t) * 64 + lane] = 0;
+          use_l[(b0 + t) * 64 + lane] = uu[t];
+          def_l[(b0 + t) * 64 + lane] = dd[t];
+        }
     }
   }
   uint32_t sweeps = 0;
@@ -495,7 +506,19 @@ __global__ __launch_bounds__(64) void k_fixpoint(MIRS) {
     }
   }
   // write-out: in (when it lived in LDS) and out
-  for (uint32_t b = 0; b < B; ++b) {
+  if (kLds) {
+#pragma unroll 4
+    for (uint32_t b = 0; b < B; ++b) {
+      uint32_t out = in_l[s0_l[b] * 64 + lane] | in_l[s1_l[b] * 64 + lane];
+      if (succ_off_l[b + 1] - succ_off_l[b] > 2)
+        for (uint32_t e = succ_off_l[b] + 2; e < succ_off_l[b + 1]; ++e) out |= in_l[succ_l[e] * 64 + lane];
+      if (act) {
+        L.live_out[(size_t)b * W + w] = out;
+        L.live_in[(size_t)b * W + w] = in_l[b * 64 + lane];
+      }
+    }
+  }
+  for (uint32_t b = 0; !kLds && b < B; ++b) {
     uint32_t out = 0;
     const uint32_t e0 = kLds ? succ_off_l[b] : m.succ_off[b], e1 = kLds ? succ_off_l[b + 1] : m.succ_off[b + 1];
     for (uint32_t e = e0; e < e1; ++e) {
