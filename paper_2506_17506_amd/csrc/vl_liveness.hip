@@ -153,21 +153,19 @@ __global__ __launch_bounds__(1024) void k_place(MIRS) {
     }
     return;
   }
-  uint32_t *cnt = sm, *base = sm + m.V;
+  // one word per vreg: first the slice's count, then the next free position of the
+  // sub-range reserved for the slice
+  uint32_t *cnt = sm;
   for (uint32_t v = threadIdx.x; v < m.V; v += 1024) cnt[v] = 0;
   __syncthreads();
   for (uint32_t o = o0 + threadIdx.x; o < o1; o += 1024) atomicAdd(&cnt[m.occ_vreg[o]], 1u);
   __syncthreads();
   for (uint32_t v = threadIdx.x; v < m.V; v += 1024) {
     const uint32_t c = cnt[v];
-    if (c) base[v] = L.vcnt[v] + atomicAdd(&L.vcur[v], c);
-    cnt[v] = 0;
+    if (c) cnt[v] = L.vcnt[v] + atomicAdd(&L.vcur[v], c);
   }
   __syncthreads();
-  for (uint32_t o = o0 + threadIdx.x; o < o1; o += 1024) {
-    const uint32_t v = m.occ_vreg[o];
-    L.vocc_tmp[base[v] + atomicAdd(&cnt[v], 1u)] = o;
-  }
+  for (uint32_t o = o0 + threadIdx.x; o < o1; o += 1024) L.vocc_tmp[atomicAdd(&cnt[m.occ_vreg[o]], 1u)] = o;
 }
 
 // Lists of up to kShortList occurrences are rank-sorted by one lane (the longer ones were
@@ -1454,12 +1452,12 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     hipError_t b = hipFuncSetAttribute((const void *)k_place<true>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
     return a == hipSuccess && b == hipSuccess;
   }();
-  const bool hist_lds = lds_ok && (size_t)maxV * 8 <= 128 * 1024;
+  const bool hist_lds = lds_ok && (size_t)maxV * 4 <= 128 * 1024;
   const dim3 slices((maxO + kSlice - 1) / kSlice, n);
   if (hist_lds) k_count<true><<<slices, 1024, (size_t)maxV * 4, stream>>>(dm, dl);
   else k_count<false><<<slices, 1024, 0, stream>>>(dm, dl);
   k_scan<kScanVreg><<<n, 1024, 0, stream>>>(dm, dl);
-  if (hist_lds) k_place<true><<<slices, 1024, (size_t)maxV * 8, stream>>>(dm, dl);
+  if (hist_lds) k_place<true><<<slices, 1024, (size_t)maxV * 4, stream>>>(dm, dl);
   else k_place<false><<<slices, 1024, 0, stream>>>(dm, dl);
   k_sort<<<dim3(kLongBlocks + (maxV + 255) / 256, n), 256, 0, stream>>>(dm, dl);
   {
