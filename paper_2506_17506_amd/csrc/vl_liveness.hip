@@ -286,7 +286,7 @@ __global__ __launch_bounds__(256) void k_sort(MIRS) {
 // bitset words.  The bits are collected in an LDS table [block][word of the range] and each
 // non-zero word goes to memory once; when the table would not fit, runs of equal
 // (block, word) are combined by shuffles and every run issues its own atomics.
-constexpr uint32_t kSumSlice = 4096, kSumThreads = 1024;
+constexpr uint32_t kSumSlice = 1024, kSumThreads = 256;   // measured: 4096 / 1024 took 58 us, this 45 us, smaller no less
 constexpr uint32_t kSumWords = kSumSlice / 32 + 1;   // most words a slice can touch
 
 __global__ __launch_bounds__(kSumThreads) void k_summary(MIRS, const uint32_t lds_words) {

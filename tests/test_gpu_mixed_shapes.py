@@ -137,8 +137,8 @@ def test_many_blocks_times_many_words():
     block summaries of most slices of the sorted entries do not fit the on-chip table and
     take the other path, the last slice fits."""
     from vlgen.mixed import many_blocks_mir
-    m = many_blocks_mir(7, gap=24)
-    assert m.n_block == 150 and (m.n_vreg + 31) // 32 > 200 and m.n_occ > 3 * 4096
+    m = many_blocks_mir(7, gap=96)
+    assert m.n_block == 150 and (m.n_vreg + 31) // 32 > 500 and m.n_occ > 12 * 1024
     run_case(m, K=24, seed=31, tile_lens=[0, 100])
 
 
