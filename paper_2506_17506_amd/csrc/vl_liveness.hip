@@ -604,7 +604,8 @@ __global__ __launch_bounds__(kEvtThreads) void k_events(MIRS) {
   const bool out_b = (L.live_out[(size_t)b * m.W + vw] & vbit) != 0;
   const bool out_below = (L.live_out[(size_t)(b > 0 ? b - 1 : 0) * m.W + vw] & vbit) != 0;
   const bool out_before = (L.live_out[(size_t)blk_before * m.W + vw] & vbit) != 0;
-  const uint32_t start_b = m.blk_start[b], start_b1 = m.blk_start[b + 1];
+  const uint32_t start_b = m.blk_start[b], start_b1 = m.blk_start[b + 1], start_b2 = m.blk_start[min(b + 2, m.B)];
+  const bool in_after = (L.live_in[(size_t)min(b + 1, m.B - 1) * m.W + vw] & vbit) != 0;   // live into the block after b
   const uint32_t F = m.class_size[attr_class(attr)];
   bool la;
   if (ge < hi && blk_next == b) {
@@ -681,19 +682,25 @@ __global__ __launch_bounds__(kEvtThreads) void k_events(MIRS) {
   span(i, i + 1, has_def || la || (keeps && has_use));
   const uint32_t i2 = ge < hi ? nxt >> 2 : m.N;
   const uint32_t b2 = ge < hi ? blk_next : m.B;
+  const uint32_t start_next = m.blk_start[b2];   // third level; only needed when the next mention is in another block
   if (b2 == b) {
     span(i + 1, i2, la);
   } else {
     span(i + 1, start_b1, la);
-    // blocks in between: v is live into none of them after its last live block
+    // blocks in between: v is live into none of them after its last live block.  The block
+    // right after b (nearly always the only one) was read with the second level.
     const uint32_t xe = min(b2, max(b + 1, last_live_v + 1));
-    for (uint32_t x = b + 1; x < xe; ++x)
+    if (b + 1 < xe) span(start_b1, start_b2, in_after);
+    for (uint32_t x = b + 2; x < xe; ++x)
       span(m.blk_start[x], m.blk_start[x + 1], bit_get(L.live_in + (size_t)x * m.W, v));
-    if (xe < b2) span(m.blk_start[xe], m.blk_start[xe + 1], false);
+    if (xe < b2) {
+      if (xe == b + 1) span(start_b1, start_b2, false);
+      else span(m.blk_start[xe], m.blk_start[xe + 1], false);
+    }
     if (ge < hi) {
       bool next_use = false;
       for (uint32_t x = ge; x < hi && (ent(x) >> 2) == i2; ++x) next_use |= (ent(x) & VL_OCC_USE) != 0;
-      span(m.blk_start[b2], i2, next_use);
+      span(start_next, i2, next_use);
     }
   }
   if (ge >= hi && cur) sf |= kEndN;
