@@ -1020,10 +1020,15 @@ __device__ inline void f_tile_prefix(const DevMir VL_GLOBAL &m, DevLive VL_GLOBA
   const uint32_t w = bx * bdim + tx;
   if (w >= m.W) return;
   uint32_t acc = 0;
-  for (uint32_t t = 0; t < L.T; ++t) {
-    const uint32_t d = L.tile_live[(size_t)t * m.W + w];
-    L.tile_live[(size_t)t * m.W + w] = acc;
-    acc ^= d;
+  for (uint32_t t0 = 0; t0 < L.T; t0 += 8) {   // eight tiles' words in flight
+    uint32_t d[8];
+#pragma unroll
+    for (uint32_t u = 0; u < 8; ++u) d[u] = t0 + u < L.T ? L.tile_live[(size_t)(t0 + u) * m.W + w] : 0u;
+#pragma unroll
+    for (uint32_t u = 0; u < 8; ++u) {
+      if (t0 + u < L.T) L.tile_live[(size_t)(t0 + u) * m.W + w] = acc;
+      acc ^= d[u];
+    }
   }
 }
 
