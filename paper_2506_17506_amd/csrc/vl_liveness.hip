@@ -90,9 +90,12 @@ __device__ inline void f_scan(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L) {
     return x;
   };
   uint32_t sum = 0;
-  for (uint32_t i = lo + lane * 4; i < hi; i += 256) {
-    const u32x4 x = load4(i);
-    sum += x.x + x.y + x.z + x.w;
+  for (uint32_t i = lo + lane * 4; i < hi; i += 4 * 256) {   // four reads in flight
+    u32x4 x[4];
+#pragma unroll
+    for (uint32_t u = 0; u < 4; ++u) x[u] = load4(i + u * 256);   // zeros beyond hi
+#pragma unroll
+    for (uint32_t u = 0; u < 4; ++u) sum += x[u].x + x[u].y + x[u].z + x[u].w;
   }
   for (int d = 32; d >= 1; d >>= 1) sum += (uint32_t)__shfl_xor((int)sum, d, 64);
   if (lane == 0) part[wave] = sum;
@@ -102,30 +105,38 @@ __device__ inline void f_scan(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &L) {
     if (k < wave) base += part[k];
     total += part[k];
   }
-  for (uint32_t i0 = lo; i0 < hi; i0 += 256) {
-    const uint32_t i = i0 + lane * 4;
-    const u32x4 x = load4(i);
-    const uint32_t s4 = x.x + x.y + x.z + x.w;
-    uint32_t incl = s4;
-    for (int d = 1; d < 64; d <<= 1) {
-      const uint32_t y = (uint32_t)__shfl_up((int)incl, d, 64);
-      if ((int)lane >= d) incl += y;
+  for (uint32_t i00 = lo; i00 < hi; i00 += 4 * 256) {
+    u32x4 ahead[4];   // the array is rewritten in place: the reads of four rounds go before their writes
+#pragma unroll
+    for (uint32_t u = 0; u < 4; ++u) ahead[u] = load4(i00 + u * 256 + lane * 4);
+#pragma unroll
+    for (uint32_t u = 0; u < 4; ++u) {
+      const uint32_t i0 = i00 + u * 256;
+      if (i0 >= hi) break;
+      const uint32_t i = i0 + lane * 4;
+      const u32x4 x = ahead[u];
+      const uint32_t s4 = x.x + x.y + x.z + x.w;
+      uint32_t incl = s4;
+      for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t y = (uint32_t)__shfl_up((int)incl, d, 64);
+        if ((int)lane >= d) incl += y;
+      }
+      const uint32_t e0 = base + incl - s4;
+      const u32x4 out = {e0, e0 + x.x, e0 + x.x + x.y, e0 + x.x + x.y + x.z};
+      if (kWhich == kScanVreg) {   // the counts are list lengths: queue the lists the bitmap sort will take
+        if (x.x > kShortList) L.long_queue[atomicAdd(&L.counters[kCtrLong], 1u)] = i;
+        if (x.y > kShortList) L.long_queue[atomicAdd(&L.counters[kCtrLong], 1u)] = i + 1;
+        if (x.z > kShortList) L.long_queue[atomicAdd(&L.counters[kCtrLong], 1u)] = i + 2;
+        if (x.w > kShortList) L.long_queue[atomicAdd(&L.counters[kCtrLong], 1u)] = i + 3;
+      }
+      if (i + 4 <= hi) *reinterpret_cast<u32x4 VL_GLOBAL *>(p + i) = out;
+      else {
+        if (i < hi) p[i] = out.x;
+        if (i + 1 < hi) p[i + 1] = out.y;
+        if (i + 2 < hi) p[i + 2] = out.z;
+      }
+      base += (uint32_t)__shfl((int)incl, 63, 64);
     }
-    const uint32_t e0 = base + incl - s4;
-    const u32x4 out = {e0, e0 + x.x, e0 + x.x + x.y, e0 + x.x + x.y + x.z};
-    if (kWhich == kScanVreg) {   // the counts are list lengths: queue the lists the bitmap sort will take
-      if (x.x > kShortList) L.long_queue[atomicAdd(&L.counters[kCtrLong], 1u)] = i;
-      if (x.y > kShortList) L.long_queue[atomicAdd(&L.counters[kCtrLong], 1u)] = i + 1;
-      if (x.z > kShortList) L.long_queue[atomicAdd(&L.counters[kCtrLong], 1u)] = i + 2;
-      if (x.w > kShortList) L.long_queue[atomicAdd(&L.counters[kCtrLong], 1u)] = i + 3;
-    }
-    if (i + 4 <= hi) *reinterpret_cast<u32x4 VL_GLOBAL *>(p + i) = out;
-    else {
-      if (i < hi) p[i] = out.x;
-      if (i + 1 < hi) p[i + 1] = out.y;
-      if (i + 2 < hi) p[i + 2] = out.z;
-    }
-    base += (uint32_t)__shfl((int)incl, 63, 64);
   }
   if (threadIdx.x == 0) p[n] = total;
 }
