@@ -566,15 +566,18 @@ constexpr uint8_t kStartI = 1, kStartI1 = 2, kEndI = 4, kEndI1 = 8, kEndN = 16, 
 // in the block's live-out.  P(i) contains v iff it is live after i or written at i.
 constexpr uint32_t kEvtThreads = 256, kEvtHalo = 16, kEvtWindow = kEvtThreads + 2 * kEvtHalo;
 
-__global__ __launch_bounds__(kEvtThreads) void k_events(MIRS) {
-  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
-  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
+// (One-dimensional grid: block_map names the kernel and the stretch of 256 entries of every
+// workgroup, so that no workgroup is launched for stretches a smaller kernel does not have.)
+__global__ __launch_bounds__(kEvtThreads) void k_events(MIRS, const uint2 *__restrict__ block_map) {
+  const uint2 where = block_map[blockIdx.x];
+  const DevMir VL_GLOBAL &m = *as_global(mirs[where.x]);
+  DevLive VL_GLOBAL &L = *as_global_rw(&lives[where.x]);
   // The neighbours of an entry in the sorted order (its own mention group, the groups before
   // and after it) are looked at many times: the workgroup's stretch of entries plus a halo
   // on both sides is staged in LDS once, and only what lies beyond the halo is read from
   // memory.
   __shared__ uint32_t s_ifl[kEvtWindow], s_occ[kEvtWindow], s_v[kEvtWindow];
-  const uint32_t base = blockIdx.x * kEvtThreads;
+  const uint32_t base = where.y * kEvtThreads;
   if (base >= m.O) return;
   const uint32_t win_lo = base - kEvtHalo;   // may wrap below zero: window indices are taken modulo 2^32
   for (uint32_t r = threadIdx.x; r < kEvtWindow; r += kEvtThreads) {
@@ -1176,13 +1179,20 @@ __global__ __launch_bounds__(256) void k_stage_offsets(MIRS, StageGrid g) {
   else f_seg_off(m, L, bx - g.a - g.b, tx, 256);
 }
 
-__global__ __launch_bounds__(256) void k_stage_fill(MIRS, StageGrid g) {
-  const DevMir VL_GLOBAL &m = *as_global(mirs[blockIdx.y]);
-  DevLive VL_GLOBAL &L = *as_global_rw(&lives[blockIdx.y]);
+// One-dimensional grid.  Part a: per_a workgroups for every kernel; parts b and c: one
+// workgroup per stretch of 256 instructions / entries that exists, named by the block maps.
+__global__ __launch_bounds__(256) void k_stage_fill(MIRS, StageGrid g, uint32_t per_a, const uint2 *__restrict__ map_instr,
+                                                    const uint2 *__restrict__ map_occ) {
   const uint32_t bx = blockIdx.x, tx = threadIdx.x;
-  if (bx < g.a) f_seed<true>(m, L, bx * 4 + (tx >> 6), tx & 63u, 64);
-  else if (bx < g.a + g.b) f_plan_fill(m, L, bx - g.a, tx, 256);
-  else f_seg_fill(m, L, bx - g.a - g.b, tx, 256);
+  uint2 where;
+  if (bx < g.a) where = make_uint2(bx / per_a, bx % per_a);
+  else if (bx < g.a + g.b) where = map_instr[bx - g.a];
+  else where = map_occ[bx - g.a - g.b];
+  const DevMir VL_GLOBAL &m = *as_global(mirs[where.x]);
+  DevLive VL_GLOBAL &L = *as_global_rw(&lives[where.x]);
+  if (bx < g.a) f_seed<true>(m, L, where.y * 4 + (tx >> 6), tx & 63u, 64);
+  else if (bx < g.a + g.b) f_plan_fill(m, L, where.y, tx, 256);
+  else f_seg_fill(m, L, where.y, tx, 256);
 }
 
 __global__ __launch_bounds__(256) void k_stage_finish(MIRS, StageGrid g) {
@@ -1262,6 +1272,8 @@ struct vl_batch {
   uint32_t sized_tile_len = 0;
   std::vector<uint32_t> sizes;   // [n][3]: events, interval segments, tile live-ins
   std::vector<char> uploaded;    // the DevLive table as it stands on the device after the last successful call
+  uint2 *stage_map = nullptr;    // pinned: the block maps (kernel, stretch of 256) of the per-instruction and per-entry launches
+  size_t map_cap = 0;
 };
 
 static void batch_free(vl_batch *b) {
@@ -1271,6 +1283,7 @@ static void batch_free(vl_batch *b) {
   if (b->stage_mirs) (void)hipHostFree(b->stage_mirs);
   if (b->stage_a) (void)hipHostFree(b->stage_a);
   if (b->stage_b) (void)hipHostFree(b->stage_b);
+  if (b->stage_map) (void)hipHostFree(b->stage_map);
   delete b;
 }
 
@@ -1369,6 +1382,14 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
   }
   const size_t o_mirs = bump.take((size_t)n * sizeof(DevMir *));
   const size_t o_lives = bump.take((size_t)n * sizeof(DevLive));
+  // block maps: one entry per stretch of 256 instructions, then one per stretch of 256 entries
+  size_t blocks_instr = 0, blocks_occ = 0;
+  for (uint32_t k = 0; k < n; ++k) {
+    blocks_instr += (mirs[k]->h.N + 255u) / 256u;
+    blocks_occ += (mirs[k]->h.O + 255u) / 256u;
+  }
+  if (blocks_instr + blocks_occ > 0x7FFFFFFFull) return fail(VL_E_RANGE);
+  const size_t o_map = bump.take((blocks_instr + blocks_occ + 1) * sizeof(uint2));
   if (bump.off > batch->cap1) {
     if (batch->arena1) { VL_HIP(hipStreamSynchronize(stream)); (void)hipFree(batch->arena1); batch->arena1 = nullptr; batch->cap1 = 0; }
     hipError_t e = hipMalloc(&batch->arena1, bump.off);
@@ -1463,8 +1484,25 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     memcpy(batch->stage_a, h.data(), (size_t)n * sizeof(DevLive));
     if (e == hipSuccess) e = hipMemcpyAsync(a1 + o_mirs, mir_ptrs, (size_t)n * sizeof(DevMir *), hipMemcpyHostToDevice, stream);
     if (e == hipSuccess) e = hipMemcpyAsync(a1 + o_lives, batch->stage_a, (size_t)n * sizeof(DevLive), hipMemcpyHostToDevice, stream);
+    if (e == hipSuccess && batch->map_cap < blocks_instr + blocks_occ + 1) {
+      // (an earlier copy out of the old buffer is complete: growing means other kernels, and
+      // then the sizes were not known and that call waited for the stream)
+      if (batch->stage_map) (void)hipHostFree(batch->stage_map);
+      batch->stage_map = nullptr; batch->map_cap = 0;
+      e = hipHostMalloc((void **)&batch->stage_map, (blocks_instr + blocks_occ + 1) * sizeof(uint2), hipHostMallocDefault);
+      if (e == hipSuccess) batch->map_cap = blocks_instr + blocks_occ + 1;
+    }
+    if (e == hipSuccess) {
+      uint2 *at = batch->stage_map;
+      for (uint32_t k = 0; k < n; ++k)
+        for (uint32_t x = 0; x < (mirs[k]->h.N + 255u) / 256u; ++x) *at++ = make_uint2(k, x);
+      for (uint32_t k = 0; k < n; ++k)
+        for (uint32_t x = 0; x < (mirs[k]->h.O + 255u) / 256u; ++x) *at++ = make_uint2(k, x);
+      e = hipMemcpyAsync(a1 + o_map, batch->stage_map, (blocks_instr + blocks_occ) * sizeof(uint2), hipMemcpyHostToDevice, stream);
+    }
   }
   if (e != hipSuccess) return fail(hip_fail(e));
+  const uint2 *map_instr = (const uint2 *)(a1 + o_map), *map_occ = map_instr + blocks_instr;
 
   const DevMir *const *dm = batch->dev_mirs;
   DevLive *dl = batch->dev_lives;
@@ -1492,7 +1530,8 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
     if (lds <= 64 * 1024) k_fixpoint<true><<<grid1(maxW, 64, n), 64, lds, stream>>>(dm, dl);
     else k_fixpoint<false><<<grid1(maxW, 64, n), 64, 0, stream>>>(dm, dl);
   }
-  k_events<<<grid1(maxO, kEvtThreads, n), kEvtThreads, 0, stream>>>(dm, dl);
+  static_assert(kEvtThreads == 256, "the block map counts stretches of 256 entries");
+  if (blocks_occ) k_events<<<(uint32_t)blocks_occ, kEvtThreads, 0, stream>>>(dm, dl, map_occ);
   auto blocks = [](uint32_t items, uint32_t per) { return std::max(1u, (items + per - 1) / per); };
   const StageGrid g_count = {maxT, blocks(maxB, 4), blocks(maxN, TB * kStageReps)};
   const StageGrid g_scan = {1, 1, blocks(maxW, 1024)};
@@ -1524,9 +1563,10 @@ extern "C" int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint
   if (dense) {
     zero_async((char *)batch->arena2 + zero2_lo, zero2_hi - zero2_lo, stream);
   }
-  const StageGrid g_fill = {blocks(maxT, 4), blocks(maxN, TB), blocks(maxO, TB)};
+  const uint32_t per_a = blocks(maxT, 4);
+  const StageGrid g_fill = {per_a * n, (uint32_t)blocks_instr, (uint32_t)blocks_occ};
   const StageGrid g_fin = {blocks(maxB, 4), blocks(maxT, TB), blocks(max_seed, TB)};
-  k_stage_fill<<<dim3(g_fill.a + g_fill.b + g_fill.c, n), 256, 0, stream>>>(dm, dl, g_fill);
+  k_stage_fill<<<g_fill.a + g_fill.b + g_fill.c, 256, 0, stream>>>(dm, dl, g_fill, per_a, map_instr, map_occ);
   k_stage_finish<<<dim3(g_fin.a + g_fin.b + g_fin.c + blocks(maxV, TB), n), 256, 0, stream>>>(dm, dl, g_fin);
   if (dense) {
     k_dense_delta<<<grid1(maxN + maxB, TB, n), TB, 0, stream>>>(dm, dl);
