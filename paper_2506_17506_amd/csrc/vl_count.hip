@@ -34,13 +34,34 @@ __device__ inline bool lists_meet(const uint32_t VL_GLOBAL *seg, uint32_t a0, ui
 
 // One wavefront per vreg a, its lanes striding over b > a; blockIdx.y = program.  kFill = false:
 // cnt[a] = number of partners; kFill = true: the pairs are written from off[a] on, in ascending b.
+// Vregs are taken 64 at a time, and a group whose hulls taken together ([earliest start, latest
+// end), from k_hull_groups) miss a's hull is passed over: vregs are mostly numbered in the
+// order they are first written, so most groups lie entirely before or after a.
 struct PairJob {
   const DevMir *mir;
   const DevLive *live;
   uint32_t *cnt;         // [V]
   const uint64_t *off;   // [V]
   uint32_t *pairs;       // [n_pairs][2]
+  uint2 *groups;         // [(V + 63) / 64] (earliest start, latest end) of the group's non-empty hulls
 };
+
+// one wavefront per group of 64 vregs
+__global__ __launch_bounds__(256) void k_hull_groups(const PairJob *__restrict__ jobs) {
+  const PairJob &J = jobs[blockIdx.y];
+  const DevMir VL_GLOBAL &m = *as_global(J.mir);
+  const DevLive VL_GLOBAL &L = *as_global(J.live);
+  const uint32_t lane = threadIdx.x & 63u, g = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if ((size_t)g * 64 >= m.V) return;
+  const uint32_t v = g * 64 + lane;
+  uint32_t lo = 0xFFFFFFFFu, hi = 0;
+  if (v < m.V && L.hull[2 * (size_t)v + 1] != 0) { lo = L.hull[2 * (size_t)v]; hi = L.hull[2 * (size_t)v + 1]; }   // (0, 0): never in any P(i)
+  for (int d = 32; d >= 1; d >>= 1) {
+    lo = min(lo, (uint32_t)__shfl_xor((int)lo, d, 64));
+    hi = max(hi, (uint32_t)__shfl_xor((int)hi, d, 64));
+  }
+  if (lane == 0) J.groups[g] = make_uint2(lo, hi);
+}
 
 template <bool kFill>
 __global__ __launch_bounds__(256) void k_pairs(const PairJob *__restrict__ jobs) {
@@ -53,21 +74,28 @@ __global__ __launch_bounds__(256) void k_pairs(const PairJob *__restrict__ jobs)
   const uint32_t s0 = L.seg_off[a], s1 = L.seg_off[a + 1], cls = attr_class(m.vattr[a]);
   uint64_t at = kFill ? J.off[a] : 0;
   uint32_t n = 0;
-  for (uint32_t b0 = a + 1; b0 < m.V; b0 += 64) {
-    const uint32_t b = b0 + lane;
-    bool hit = false;
-    if (b < m.V && attr_class(m.vattr[b]) == cls && L.hull[2 * (size_t)b] < h1 && h0 < L.hull[2 * (size_t)b + 1])
-      hit = lists_meet(L.seg, s0, s1, L.seg_off[b], L.seg_off[b + 1]);
-    const uint64_t hits = __ballot(hit);
-    if (kFill) {
-      if (hit) {
-        const uint64_t pos = at + __popcll(hits & ((1ull << lane) - 1ull));
-        J.pairs[2 * pos] = a;
-        J.pairs[2 * pos + 1] = b;
+  const uint32_t n_groups = (m.V + 63u) / 64u;
+  for (uint32_t g0 = a / 64; g0 < n_groups; g0 += 64) {   // 64 groups at a time, one per lane
+    uint2 span = make_uint2(0xFFFFFFFFu, 0u);
+    if (g0 + lane < n_groups) span = J.groups[g0 + lane];
+    uint64_t todo = __ballot(span.x < h1 && h0 < span.y);
+    while (todo) {
+      const uint32_t b = (g0 + (uint32_t)__builtin_ctzll(todo)) * 64 + lane;
+      todo &= todo - 1;
+      bool hit = false;
+      if (b > a && b < m.V && attr_class(m.vattr[b]) == cls && L.hull[2 * (size_t)b] < h1 && h0 < L.hull[2 * (size_t)b + 1])
+        hit = lists_meet(L.seg, s0, s1, L.seg_off[b], L.seg_off[b + 1]);
+      const uint64_t hits = __ballot(hit);
+      if (kFill) {
+        if (hit) {
+          const uint64_t pos = at + __popcll(hits & ((1ull << lane) - 1ull));
+          J.pairs[2 * pos] = a;
+          J.pairs[2 * pos + 1] = b;
+        }
+        at += __popcll(hits);
+      } else {
+        n += __popcll(hits);
       }
-      at += __popcll(hits);
-    } else {
-      n += __popcll(hits);
     }
   }
   if (!kFill && lane == 0) J.cnt[a] = n;
@@ -278,23 +306,28 @@ int32_t build_pairs(const std::vector<std::pair<vl_mir *, const vl_live *>> &tod
   // device scratch: counts, offsets, the job table; host: the same, pageable (copies wait for the stream)
   uint32_t *cnt = nullptr;
   uint64_t *off = nullptr;
+  uint2 *groups = nullptr;
   PairJob *jobs_dev = nullptr;
   std::vector<void *> fresh;   // pair buffers allocated here, handed to the programs on success
-  auto cleanup = [&]() { (void)hipFree(cnt); (void)hipFree(off); (void)hipFree(jobs_dev); };
+  auto cleanup = [&]() { (void)hipFree(cnt); (void)hipFree(off); (void)hipFree(groups); (void)hipFree(jobs_dev); };
   auto fail = [&](hipError_t err) {
     cleanup();
     for (void *p : fresh) (void)hipFree(p);
     return hip_fail(err);
   };
+  // (a kernel's groups start at base / 64 + its index: at most one entry per kernel is left unused)
   hipError_t e = hipMalloc((void **)&cnt, total_v * 4);
   if (e == hipSuccess) e = hipMalloc((void **)&off, total_v * 8);
+  if (e == hipSuccess) e = hipMalloc((void **)&groups, (total_v / 64 + n + 1) * sizeof(uint2));
   if (e == hipSuccess) e = hipMalloc((void **)&jobs_dev, n * sizeof(PairJob));
   if (e != hipSuccess) return fail(e);
   std::vector<PairJob> jobs(n);
-  for (size_t j = 0; j < n; ++j) jobs[j] = PairJob{todo[j].first->dev, todo[j].second->dev, cnt + base[j], off + base[j], nullptr};
+  for (size_t j = 0; j < n; ++j)
+    jobs[j] = PairJob{todo[j].first->dev, todo[j].second->dev, cnt + base[j], off + base[j], nullptr, groups + base[j] / 64 + j};
   e = hipMemcpyAsync(jobs_dev, jobs.data(), n * sizeof(PairJob), hipMemcpyHostToDevice, stream);
   if (e != hipSuccess) return fail(e);
   const dim3 grid((max_v + 3) / 4, (uint32_t)n);
+  k_hull_groups<<<dim3(((max_v + 63) / 64 + 3) / 4, (uint32_t)n), 256, 0, stream>>>(jobs_dev);
   k_pairs<false><<<grid, 256, 0, stream>>>(jobs_dev);
   std::vector<uint32_t> h_cnt(total_v);
   e = hipMemcpyAsync(h_cnt.data(), cnt, total_v * 4, hipMemcpyDeviceToHost, stream);
