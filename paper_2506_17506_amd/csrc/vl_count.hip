@@ -308,11 +308,11 @@ int32_t build_pairs(const std::vector<std::pair<vl_mir *, const vl_live *>> &tod
   uint64_t *off = nullptr;
   uint2 *groups = nullptr;
   PairJob *jobs_dev = nullptr;
-  std::vector<void *> fresh;   // pair buffers allocated here, handed to the programs on success
+  void *all_pairs = nullptr;   // one allocation for the pairs of every program of this call, handed to them on success
   auto cleanup = [&]() { (void)hipFree(cnt); (void)hipFree(off); (void)hipFree(groups); (void)hipFree(jobs_dev); };
   auto fail = [&](hipError_t err) {
     cleanup();
-    for (void *p : fresh) (void)hipFree(p);
+    (void)hipFree(all_pairs);
     return hip_fail(err);
   };
   // (a kernel's groups start at base / 64 + its index: at most one entry per kernel is left unused)
@@ -333,18 +333,20 @@ int32_t build_pairs(const std::vector<std::pair<vl_mir *, const vl_live *>> &tod
   e = hipMemcpyAsync(h_cnt.data(), cnt, total_v * 4, hipMemcpyDeviceToHost, stream);
   if (e == hipSuccess) e = hipStreamSynchronize(stream);
   if (e != hipSuccess) return fail(e);
-  std::vector<uint64_t> h_off(total_v), totals(n);
-  fresh.assign(n, nullptr);
+  std::vector<uint64_t> h_off(total_v), totals(n), first_pair(n);
+  uint64_t all = 0;
   for (size_t j = 0; j < n; ++j) {
     uint64_t total = 0;
     for (uint32_t a = 0; a < todo[j].first->h.V; ++a) { h_off[base[j] + a] = total; total += h_cnt[base[j] + a]; }
     totals[j] = total;
-    if (total) {
-      e = hipMalloc(&fresh[j], (size_t)total * 8);
-      if (e != hipSuccess) return fail(e);
-    }
-    jobs[j].pairs = (uint32_t *)fresh[j];
+    first_pair[j] = all;
+    all += (total + 31) & ~(uint64_t)31;   // every program's pairs start on a 256-byte boundary
   }
+  if (all) {
+    e = hipMalloc(&all_pairs, (size_t)all * 8);
+    if (e != hipSuccess) return fail(e);
+  }
+  for (size_t j = 0; j < n; ++j) jobs[j].pairs = totals[j] ? (uint32_t *)all_pairs + 2 * first_pair[j] : nullptr;
   e = hipMemcpyAsync(off, h_off.data(), total_v * 8, hipMemcpyHostToDevice, stream);
   if (e == hipSuccess) e = hipMemcpyAsync(jobs_dev, jobs.data(), n * sizeof(PairJob), hipMemcpyHostToDevice, stream);
   if (e == hipSuccess) {
@@ -354,9 +356,17 @@ int32_t build_pairs(const std::vector<std::pair<vl_mir *, const vl_live *>> &tod
   if (e == hipSuccess) e = hipStreamSynchronize(stream);   // the host vectors and the scratch go away below
   if (e != hipSuccess) return fail(e);
   cleanup();
+  EdgeBlock *block = nullptr;
+  if (all_pairs) {
+    uint32_t holders = 0;
+    for (size_t j = 0; j < n; ++j) holders += totals[j] != 0;
+    block = new (std::nothrow) EdgeBlock{all_pairs, {holders}};
+    if (!block) { (void)hipFree(all_pairs); return VL_E_SHAPE; }
+  }
   for (size_t j = 0; j < n; ++j) {
-    todo[j].first->edges = fresh[j];
+    todo[j].first->edges = jobs[j].pairs;
     todo[j].first->n_edges = totals[j];
+    todo[j].first->edge_block = totals[j] ? block : nullptr;
     todo[j].first->edges_built = true;
   }
   return VL_OK;

@@ -2,6 +2,8 @@
 #ifndef VL_DEV_H
 #define VL_DEV_H
 #include <hip/hip_runtime.h>
+
+#include <atomic>
 #include <stdint.h>
 
 #include "../../include/vl.h"
@@ -215,6 +217,15 @@ __device__ inline void flip_members_of_p(const DevMir VL_GLOBAL &m, const DevLiv
 }
 }  // namespace vl
 
+namespace vl {
+// One device allocation that holds the interference pairs of several programs; freed with the
+// last of them.
+struct EdgeBlock {
+  void *mem;
+  std::atomic<uint32_t> refs;
+};
+}  // namespace vl
+
 struct vl_mir {
   vl::DevMir h;        // host mirror (device pointers inside)
   vl::DevMir *dev;     // device copy
@@ -223,9 +234,10 @@ struct vl_mir {
   uint64_t magic;
   // interference pairs (a < b, one class, some point in common), built on first use by the
   // all-violations mode and kept for the life of the handle: they depend on the program only
-  void *edges = nullptr;       // device: n_edges pairs of uint32
+  void *edges = nullptr;       // device: n_edges pairs of uint32, inside edge_block
   uint64_t n_edges = 0;
   bool edges_built = false;
+  vl::EdgeBlock *edge_block = nullptr;   // the allocation the pairs sit in, shared with the other programs of that call
 };
 
 struct vl_batch;

@@ -191,6 +191,9 @@ extern "C" void vl_mir_destroy(vl_mir *m) {
   if (!m || m->magic != vl::kMirMagic) return;
   m->magic = 0;
   if (m->arena) (void)hipFree(m->arena);
-  if (m->edges) (void)hipFree(m->edges);
+  if (m->edge_block && m->edge_block->refs.fetch_sub(1) == 1) {
+    (void)hipFree(m->edge_block->mem);
+    delete m->edge_block;
+  }
   delete m;
 }
