@@ -63,6 +63,33 @@ __global__ __launch_bounds__(256) void k_hull_groups(const PairJob *__restrict__
   if (lane == 0) J.groups[g] = make_uint2(lo, hi);
 }
 
+// off[a] = number of pairs of the vregs below a, totals[program] = all of them: one workgroup
+// per program, a contiguous run of vregs per thread
+__global__ __launch_bounds__(1024) void k_pair_offsets(const PairJob *__restrict__ jobs, uint64_t *__restrict__ totals) {
+  const PairJob &J = jobs[blockIdx.x];
+  const uint32_t V = as_global(J.mir)->V;
+  uint64_t *off = const_cast<uint64_t *>(J.off);   // written here, read by the filling launch
+  __shared__ uint64_t part[16];
+  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+  const uint32_t per = (V + 1023u) / 1024u, lo = min(V, threadIdx.x * per), hi = min(V, lo + per);
+  uint64_t mine = 0;
+  for (uint32_t a = lo; a < hi; ++a) mine += J.cnt[a];
+  uint64_t incl = mine;
+  for (int d = 1; d < 64; d <<= 1) {
+    const uint64_t y = __shfl_up(incl, d, 64);
+    if ((int)lane >= d) incl += y;
+  }
+  if (lane == 63) part[wave] = incl;
+  __syncthreads();
+  uint64_t run = incl - mine, total = 0;
+  for (uint32_t k = 0; k < 16; ++k) {
+    if (k < wave) run += part[k];
+    total += part[k];
+  }
+  for (uint32_t a = lo; a < hi; ++a) { off[a] = run; run += J.cnt[a]; }
+  if (threadIdx.x == 0) totals[blockIdx.x] = total;
+}
+
 template <bool kFill>
 __global__ __launch_bounds__(256) void k_pairs(const PairJob *__restrict__ jobs) {
   const PairJob &J = jobs[blockIdx.y];
@@ -287,7 +314,7 @@ Work g_work[16];
 
 // Enumerates the interference pairs of the programs that do not have them yet, from the
 // intervals of their analyses (which must be complete or enqueued on `stream`): one counting
-// launch over all of them, the offsets summed on the host, one filling launch.  Synchronises
+// launch over all of them, the offsets summed per program on the device, one filling launch.  Synchronises
 // the stream twice.
 int32_t build_pairs(const std::vector<std::pair<vl_mir *, const vl_live *>> &todo, hipStream_t stream) {
   const size_t n = todo.size();
@@ -307,9 +334,10 @@ int32_t build_pairs(const std::vector<std::pair<vl_mir *, const vl_live *>> &tod
   uint32_t *cnt = nullptr;
   uint64_t *off = nullptr;
   uint2 *groups = nullptr;
+  uint64_t *totals_dev = nullptr;
   PairJob *jobs_dev = nullptr;
   void *all_pairs = nullptr;   // one allocation for the pairs of every program of this call, handed to them on success
-  auto cleanup = [&]() { (void)hipFree(cnt); (void)hipFree(off); (void)hipFree(groups); (void)hipFree(jobs_dev); };
+  auto cleanup = [&]() { (void)hipFree(cnt); (void)hipFree(off); (void)hipFree(groups); (void)hipFree(totals_dev); (void)hipFree(jobs_dev); };
   auto fail = [&](hipError_t err) {
     cleanup();
     (void)hipFree(all_pairs);
@@ -319,6 +347,7 @@ int32_t build_pairs(const std::vector<std::pair<vl_mir *, const vl_live *>> &tod
   hipError_t e = hipMalloc((void **)&cnt, total_v * 4);
   if (e == hipSuccess) e = hipMalloc((void **)&off, total_v * 8);
   if (e == hipSuccess) e = hipMalloc((void **)&groups, (total_v / 64 + n + 1) * sizeof(uint2));
+  if (e == hipSuccess) e = hipMalloc((void **)&totals_dev, n * 8);
   if (e == hipSuccess) e = hipMalloc((void **)&jobs_dev, n * sizeof(PairJob));
   if (e != hipSuccess) return fail(e);
   std::vector<PairJob> jobs(n);
@@ -329,26 +358,22 @@ int32_t build_pairs(const std::vector<std::pair<vl_mir *, const vl_live *>> &tod
   const dim3 grid((max_v + 3) / 4, (uint32_t)n);
   k_hull_groups<<<dim3(((max_v + 63) / 64 + 3) / 4, (uint32_t)n), 256, 0, stream>>>(jobs_dev);
   k_pairs<false><<<grid, 256, 0, stream>>>(jobs_dev);
-  std::vector<uint32_t> h_cnt(total_v);
-  e = hipMemcpyAsync(h_cnt.data(), cnt, total_v * 4, hipMemcpyDeviceToHost, stream);
+  k_pair_offsets<<<(uint32_t)n, 1024, 0, stream>>>(jobs_dev, totals_dev);
+  std::vector<uint64_t> totals(n), first_pair(n);
+  e = hipMemcpyAsync(totals.data(), totals_dev, n * 8, hipMemcpyDeviceToHost, stream);
   if (e == hipSuccess) e = hipStreamSynchronize(stream);
   if (e != hipSuccess) return fail(e);
-  std::vector<uint64_t> h_off(total_v), totals(n), first_pair(n);
   uint64_t all = 0;
   for (size_t j = 0; j < n; ++j) {
-    uint64_t total = 0;
-    for (uint32_t a = 0; a < todo[j].first->h.V; ++a) { h_off[base[j] + a] = total; total += h_cnt[base[j] + a]; }
-    totals[j] = total;
     first_pair[j] = all;
-    all += (total + 31) & ~(uint64_t)31;   // every program's pairs start on a 256-byte boundary
+    all += (totals[j] + 31) & ~(uint64_t)31;   // every program's pairs start on a 256-byte boundary
   }
   if (all) {
     e = hipMalloc(&all_pairs, (size_t)all * 8);
     if (e != hipSuccess) return fail(e);
   }
   for (size_t j = 0; j < n; ++j) jobs[j].pairs = totals[j] ? (uint32_t *)all_pairs + 2 * first_pair[j] : nullptr;
-  e = hipMemcpyAsync(off, h_off.data(), total_v * 8, hipMemcpyHostToDevice, stream);
-  if (e == hipSuccess) e = hipMemcpyAsync(jobs_dev, jobs.data(), n * sizeof(PairJob), hipMemcpyHostToDevice, stream);
+  e = hipMemcpyAsync(jobs_dev, jobs.data(), n * sizeof(PairJob), hipMemcpyHostToDevice, stream);
   if (e == hipSuccess) {
     k_pairs<true><<<grid, 256, 0, stream>>>(jobs_dev);
     e = hipGetLastError();
