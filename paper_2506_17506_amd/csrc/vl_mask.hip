@@ -106,7 +106,7 @@ extern "C" int32_t vl_free_bases_multi(const vl_mask_query *queries, uint32_t n,
     d.mir = queries[j].mir->dev; d.live = queries[j].live->dev; d.cand = queries[j].cand; d.occ = queries[j].occ; d.pad = 0;
   }
   VL_HIP(hipMemcpyAsync(t.dev, t.host, (size_t)n * sizeof(DevQuery), hipMemcpyHostToDevice, stream));
-  k_free_bases<<<n, 256, (size_t)max_w * 4, stream>>>(t.dev, masks);
+  k_free_bases<<<n, 128, (size_t)max_w * 4, stream>>>(t.dev, masks);
   VL_HIP(hipGetLastError());
   VL_HIP(hipEventRecord(t.consumed, stream));
   return VL_OK;
