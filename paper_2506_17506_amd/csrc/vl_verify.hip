@@ -230,8 +230,8 @@ __device__ inline Touch locate(const Walk &w, uint32_t attr, uint32_t cls_tab, u
 // bits are both an exclusive-or, exact up to the first clash, which is all that is
 // reported.  Returns the bits that were already set (meaningful for occupy-with-test).
 __device__ inline uint32_t flip(const Touch &t, bool straddle) {
-  uint32_t hit = __hip_atomic_fetch_xor(&vl_lds[t.addr], t.mlo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT) & t.mlo;
-  if (straddle) hit |= __hip_atomic_fetch_xor(&vl_lds[t.addr + 64], t.mhi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT) & t.mhi;
+  uint32_t hit = __hip_atomic_fetch_xor(&vl_lds[t.addr], t.mlo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) & t.mlo;
+  if (straddle) hit |= __hip_atomic_fetch_xor(&vl_lds[t.addr + 64], t.mhi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) & t.mhi;
   return hit;
 }
 
@@ -397,13 +397,15 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(6)
   };
   // The values live into the tile: their registers mostly lie before the ring and are
   // gathered from memory, eight gathers in flight.  Lanes past the list hold zero records.
-  auto seed_events = [&](uint32_t from, uint32_t to) __attribute__((always_inline)) {
+  // Every entry flips its own bits, in any order: all four wavefronts take a share (`part`
+  // of kWalkThreads / 64), each with one candidate per lane, before the first barrier.
+  auto seed_events = [&](uint32_t from, uint32_t to, uint32_t part) __attribute__((always_inline)) {
     for (uint32_t base = from; base < to; base += 64) {
       const uint32_t cnt = min(64u, to - base);
       u32x4 r = 0;
       if (w.lane < cnt) r = g_seeds[base + w.lane];
       const bool any_slow = __any((r.w & kEvtSlow) != 0);
-      for (uint32_t g0 = 0; g0 < cnt; g0 += G) {
+      for (uint32_t g0 = part * G; g0 < cnt; g0 += (kWalkThreads / 64u) * G) {
         uint32_t p[G];
 #pragma unroll
         for (int t = 0; t < G; ++t)
@@ -421,7 +423,7 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(6)
             const uint32_t msk = (uint32_t)__builtin_amdgcn_readlane(r.y, (g0 + t) & 63u) << (p[t] & 31u);
             __hip_atomic_fetch_xor(reinterpret_cast<uint32_t *>(lds_bytes + ((((p[t] >> 5) & 15u) << 8) + my_occ +
                                                                                __builtin_amdgcn_readlane(r.z, (g0 + t) & 63u))),
-                                   msk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+                                   msk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
           }
         }
       }
@@ -554,7 +556,7 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(6)
     uint32_t cut_lo = ea;
     uint32_t v_cut_next = g_evt_cut[min(ca + 1, n_chunk) + lane_zero];
     u32x4 rec_next = fetch_records(ea, eb);   // the first batch, in flight during the seeds
-    if (tile > 0) seed_events(g_seed_off[tile], g_seed_off[tile + 1]);
+    if (tile > 0) seed_events(g_seed_off[tile], g_seed_off[tile + 1], 0u);
     __syncthreads();   // chunks up to ca are in the ring
     for (uint32_t c = ca; c != c_stop; ++c) {
       if (c < c_end) w.hi = (c + 1) * kChunk;
@@ -577,6 +579,7 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(6)
     }
     if (ca + 1 < c_end) load_chunk<kT>(w, (ca + 1) * kChunk, j);
     u32x4 chk_next = load_chk(ca);
+    if (tile > 0) seed_events(g_seed_off[tile], g_seed_off[tile + 1], role);   // this wavefront's share of the live-in list
     __syncthreads();
     for (uint32_t c = ca; c != c_stop; ++c) {
       if (c < c_end) {
