@@ -172,3 +172,40 @@ def test_thousands_of_clashes_in_one_call():
             assert_results_equal(want, res, m.name)
     finally:
         free(hm, hl)
+
+
+def test_more_candidates_than_the_list_of_clashes_holds_at_first():
+    """Calls with 70,000 and then 120,000 candidates on one stream, most of them failing on
+    safety: the library's list of candidates whose pair has to be found grows twice (it
+    starts with room for 65,536), each time after the stream has drained."""
+    from vlgen.tiny import tiny_mir
+    m = None
+    for seed in range(500, 600):
+        c = tiny_mir(seed, max_blocks=4, max_instr=8, max_vreg=10)
+        an = vlo.analyze(c)
+        if an.contract == 0 and len(an.edges["a"]) >= 6 and c.n_occ >= 30:
+            m = c
+            break
+    assert m is not None
+    rng = np.random.default_rng(9)
+    table = coloured_table(m, an, rng)
+    a, b = np.asarray(an.edges["a"]), np.asarray(an.edges["b"])
+    same = ((m.vreg_class[a] == m.vreg_class[b]) & (m.vreg_width[a] == m.vreg_width[b]) &
+            (m.vreg_align[a] == m.vreg_align[b]))
+    a, b = a[same], b[same]
+    assert len(a) >= 2
+    hm, hl, _, _ = gpu_analyze([m], dense=False)
+    try:
+        for K in (70000, 120000, 300):
+            rows = np.tile(table[m.occ_vreg].astype(np.uint16), (K, 1))
+            pick = rng.integers(0, len(a), K)
+            for e in range(len(a)):   # row k: value a[pick] moved onto the register of b[pick]
+                sel = np.nonzero(pick == e)[0]
+                sel = sel[sel % 5 != 0]   # every fifth row stays as coloured
+                cols = np.nonzero(m.occ_vreg == a[e])[0]
+                rows[np.ix_(sel, cols)] = table[b[e]]
+            want = vlo.verify(m, an, rows, threads=8)
+            assert (want["status"] == 3).sum() > K // 2
+            assert_results_equal(want, gpu_verify(hm, hl, [rows])[0], f"K {K}")
+    finally:
+        free(hm, hl)
