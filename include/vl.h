@@ -108,7 +108,8 @@ void vl_mir_destroy(vl_mir *mir);
  * stream capture and replayed.  On success live[i] describes mirs[i].
  * On error no handle is created; recycled handles stay allocated but their
  * contents are undefined until the next successful call.
- * tile_len: instructions per verification tile, 0 = library default.
+ * tile_len: instructions per verification tile, 0 = library default (512, less for batches of
+ * fewer than half a million instructions in total, down to 128).
  * Errors: VL_E_NOT_STRICT / VL_E_LAYOUT refer to the first offending kernel. */
 int32_t vl_liveness_multi(const vl_mir *const *mirs, uint32_t n, uint32_t flags, uint32_t tile_len,
                           vl_stream stream, vl_live **live);
