@@ -148,8 +148,10 @@ extern "C" int32_t vl_mir_create(const vl_mir_desc *d, vl_mir **out) {
   if (e == hipSuccess) e = hipMalloc(&m->arena, bump.off);
   if (e != hipSuccess) { delete m; return vl::hip_fail(e); }
   char *base = (char *)m->arena;
+  // the arena is put together on the host and sent in one copy
+  std::vector<char> image(bump.off, 0);
   auto up = [&](size_t off, const void *src, size_t bytes) {
-    if (e == hipSuccess && bytes) e = hipMemcpy(base + off, src, bytes, hipMemcpyHostToDevice);
+    if (bytes) memcpy(image.data() + off, src, bytes);
   };
   up(o_blk, d->blk_start, (B + 1) * 4);
   up(o_soff, d->succ_off, (B + 1) * 4);
@@ -178,6 +180,7 @@ extern "C" int32_t vl_mir_create(const vl_mir_desc *d, vl_mir **out) {
   h.instr_keep = (const uint8_t VL_GLOBAL *)(base + o_keep);
   m->dev = (vl::DevMir *)(base + o_dev);
   up(o_dev, &h, sizeof(h));
+  e = hipMemcpy(base, image.data(), bump.off, hipMemcpyHostToDevice);
   if (e != hipSuccess) {
     (void)hipFree(m->arena);
     delete m;
