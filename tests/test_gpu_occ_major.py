@@ -59,7 +59,7 @@ def test_group_shapes(K):
 def test_benchmark_kernels_full_size():
     w = gen.config(5, n_kernels=12)
     mirs = [k.mir for k in w.kernels]
-    hm, hl, _, _ = gpu_analyze(mirs, dense=False)
+    hm, hl, _, _ = gpu_analyze(mirs, tile_len=512, dense=False)   # the tile length of the benchmark's batch of 256
     try:
         res = verify_occ_major(hm, hl, w.rows)
         for k, m in enumerate(mirs):

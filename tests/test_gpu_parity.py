@@ -138,7 +138,7 @@ def test_configs_full_size(cfg):
     k, rows = w.kernels[0], w.rows[0]
     an = vlo.analyze(k.mir, threads=16)
     want = vlo.verify(k.mir, an, rows, threads=16)
-    for tile_len in (0, 97):
+    for tile_len in (0, 97, 512):   # the default (which follows the size of the batch), an odd one, the benchmark's
         hm, hl, got, views = gpu_analyze([k.mir], tile_len)
         assert_liveness_equal(k.mir, an, got[0], f"config {cfg}")
         for aligned in (True, False):
@@ -173,7 +173,7 @@ def test_config4_and_5_kernels_full_size():
     kernels = w4.kernels + w5.kernels
     rows = w4.rows + w5.rows
     mirs = [k.mir for k in kernels]
-    hm, hl, got, views = gpu_analyze(mirs, 0, dense=False)
+    hm, hl, got, views = gpu_analyze(mirs, 512, dense=False)   # the tile length of the benchmark's batch of 256
     res = gpu_verify(hm, hl, rows)
     for k, (m, r) in enumerate(zip(mirs, res)):
         an = vlo.analyze(m, threads=16)
@@ -183,8 +183,8 @@ def test_config4_and_5_kernels_full_size():
     # recycle the handles: same storage, same answers.  The first recycling call with the
     # same options reuses the known sizes without waiting, the second also the device tables;
     # then other options (dense points, another tile length) size everything afresh.
-    for flags, tile_len, dense in ((0, 0, False), (0, 0, False), (vl.VL_DENSE_POINTS, 0, True), (0, 300, False),
-                                   (0, 300, False)):
+    for flags, tile_len, dense in ((0, 512, False), (0, 512, False), (vl.VL_DENSE_POINTS, 512, True), (0, 300, False),
+                                   (0, 300, False), (0, 0, False)):
         hl2 = vl.vl_liveness_multi(hm, flags, tile_len, live=hl)
         assert [a.value for a in hl2] == [a.value for a in hl]
         torch.cuda.synchronize()
