@@ -118,13 +118,8 @@ uint64_t vlo_segments(const vlo_mir *m, const uint32_t *P, uint32_t *seg_off,
   const uint32_t W = words_per_row(m), N = m->n_instr, V = m->n_vreg;
   uint32_t *cnt = (uint32_t *)calloc((size_t)V + 1, 4);
   for (uint32_t i = 0; i < N; ++i)
-    for (uint32_t v = 0; v < V; ++v) {
-      if ((v & 31) == 0) {  /* skip words with no rising bit */
-        uint32_t now = P[(size_t)i * W + (v >> 5)], was = i ? P[(size_t)(i - 1) * W + (v >> 5)] : 0;
-        if ((now & ~was) == 0) { v += 31; continue; }
-      }
+    for (uint32_t v = 0; v < V; ++v)
       if (bit_get(P + (size_t)i * W, v) && !(i && bit_get(P + (size_t)(i - 1) * W, v))) ++cnt[v];
-    }
   uint64_t n = 0;
   for (uint32_t v = 0; v < V; ++v) { seg_off[v] = (uint32_t)n; n += cnt[v]; cnt[v] = 0; }
   seg_off[V] = (uint32_t)n;
@@ -132,10 +127,6 @@ uint64_t vlo_segments(const vlo_mir *m, const uint32_t *P, uint32_t *seg_off,
   if (n <= cap && seg) {
     for (uint32_t i = 0; i <= N; ++i)
       for (uint32_t v = 0; v < V; ++v) {
-        if ((v & 31) == 0) {  /* skip words where nothing changes */
-          uint32_t now = i < N ? P[(size_t)i * W + (v >> 5)] : 0, was = i ? P[(size_t)(i - 1) * W + (v >> 5)] : 0;
-          if (now == was) { v += 31; continue; }
-        }
         int in_now = i < N && bit_get(P + (size_t)i * W, v);
         int in_was = i && bit_get(P + (size_t)(i - 1) * W, v);
         if (in_now && !in_was) {

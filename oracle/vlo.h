@@ -21,8 +21,10 @@
  * here come from the textbook backward may-liveness over the CFG.
  *
  * Parity status: every function below is pinned by tests that do not use the
- * function itself (path enumeration on tiny CFGs, a literal per-point
- * all-pairs checker, hand-worked examples, allocator/mutation invariants).
+ * function itself (path enumeration on tiny CFGs with one and with several
+ * bitset words per row, a literal per-point all-pairs checker, a register-marking
+ * check in Python at thousands of instructions, hand-worked examples,
+ * allocator/mutation invariants).
  * Agreement with the paper's own Z3 verdicts is UNPINNED: the SMT encoding is
  * not published and no solver or dataset is available.
  *

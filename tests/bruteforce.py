@@ -147,3 +147,57 @@ def verify(m, P, row, def_points_only=False):
         if hits:
             return (3, i) + min(hits)
     return (0, 0, 0, 0)
+
+
+def verify_rows_by_marking(m, member, rows):
+    """(status, where, a, b) per row, again from the definition but usable at thousands of
+    instructions: at every instruction the registers of the tuples of P(i)'s members are
+    marked, class by class, and a register marked twice is a clash (two members of one class
+    whose ranges meet).  `member`: [N, V] 0/1 membership of P(i), every v at most once per i.
+    Consistency and realizability as in verify(); the pair of a clash by enumeration at the
+    first clashing instruction only."""
+    rows = np.asarray(rows).astype(np.int64)
+    K = rows.shape[0]
+    occ_vreg = np.asarray(m.occ_vreg).astype(np.int64)
+    first = np.full(m.n_vreg, -1, np.int64)
+    for o in range(m.n_occ - 1, -1, -1):
+        first[occ_vreg[o]] = o
+    width = np.asarray(m.vreg_width).astype(np.int64)
+    align = np.asarray(m.vreg_align).astype(np.int64)
+    cls = np.asarray(m.vreg_class).astype(np.int64)
+    size = np.asarray(m.class_size).astype(np.int64)
+    C = len(size)
+    mentioned = np.nonzero(first >= 0)[0]
+    pi, pv = np.nonzero(member)          # every (instruction, member of P) once
+    # one entry per register of every member's tuple: where register 0 of the class file of
+    # that instruction sits in the array of marks, plus the offset inside the tuple
+    sel = [np.nonzero(width[pv] > j)[0] for j in range(int(width.max()) if len(pv) else 0)]
+    slot0 = np.concatenate([(pi[x] * C + cls[pv[x]]) * 512 + j for j, x in enumerate(sel)] or [np.zeros(0, np.int64)])
+    who = np.concatenate([pv[x] for x in sel] or [np.zeros(0, np.int64)])
+    out = []
+    for k in range(K):
+        row = rows[k]
+        stray = np.nonzero(row != row[first[occ_vreg]])[0]
+        if len(stray):
+            o = int(stray[0])
+            out.append((1, o, int(occ_vreg[o]), int(first[occ_vreg[o]])))
+            continue
+        base = np.zeros(m.n_vreg, np.int64)
+        base[mentioned] = row[first[mentioned]]
+        bad = [(int(first[v]), int(v), realizability_bits(m, int(v), int(base[v]))) for v in mentioned
+               if base[v] + width[v] > size[cls[v]] or base[v] % align[v] or m.class_reserved is not None]
+        bad = [t for t in bad if t[2]]
+        if bad:
+            out.append((2,) + min(bad))
+            continue
+        marks = np.bincount(slot0 + base[who], minlength=m.n_instr * C * 512)
+        twice = np.nonzero(marks > 1)[0]
+        if len(twice) == 0:
+            out.append((0, 0, 0, 0))
+            continue
+        i = int(twice[0]) // (C * 512)
+        here = [int(v) for v in np.nonzero(member[i])[0]]
+        hits = [(a, b) for a in here for b in here
+                if a < b and cls[a] == cls[b] and base[a] < base[b] + width[b] and base[b] < base[a] + width[a]]
+        out.append((3, i) + min(hits))
+    return out

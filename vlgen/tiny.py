@@ -12,14 +12,15 @@ from .mir import Mir, OCC_DEF, OCC_USE
 
 def tiny_mir(seed: int, strict: bool = True, max_blocks: int = 4, max_instr: int = 4,
              max_vreg: int = 6, two_classes: bool = True, wide: bool = True,
-             reserved: bool = False, early: float = 0.0) -> Mir:
+             reserved: bool = False, early: float = 0.0, min_vreg: int = 1) -> Mir:
     """A random CFG of up to max_blocks blocks in which every non-entry block
     has a predecessor placed before it.  With strict, the entry block first
     defines every vreg, so nothing is live into the program.  `early`: share of
-    the defining instructions whose first plain definition is early-clobber."""
+    the defining instructions whose first plain definition is early-clobber.
+    `min_vreg` above 32 gives bitset rows of several words."""
     rng = np.random.default_rng(seed)
     nb = int(rng.integers(1, max_blocks + 1))
-    V = int(rng.integers(1, max_vreg + 1))
+    V = int(rng.integers(min_vreg, max_vreg + 1))
     n_class = 2 if (two_classes and V >= 2 and rng.random() < 0.5) else 1
     vclass = rng.integers(0, n_class, V).astype(np.uint8)
     width = np.ones(V, np.uint8)
