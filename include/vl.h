@@ -47,13 +47,18 @@ enum {
   VL_E_RANGE = -3,      /* vreg id >= n_vreg, class >= n_class, file > 512, width 0 or > 32,
                            align 0 or > 32, more than 8 classes, more than 64 operands in one
                            instruction, unknown occurrence flag bits, successor >= n_block,
-                           2^24 or more occurrences, 2^28 or more instructions, more than 2^19 vregs */
+                           2^24 or more occurrences, 2^28 or more instructions, more than
+                           VL_MAX_VREG vregs */
   VL_E_LAYOUT = -4,     /* blocks do not tile 0..N-1, a block is empty, or a non-entry block has
                            no predecessor placed before it in the linear order */
   VL_E_NOT_STRICT = -5, /* some value is live into the entry block */
   VL_E_HIP = -6,        /* a HIP runtime call failed; see vl_last_hip_error */
   VL_E_ARG = -7         /* handle does not belong to this call (wrong program, stale, ...) */
 };
+
+/* Most vregs a program may have: a bitset row over them (15,360 words, 60 KB) must fit the
+ * 64 KB of LDS a workgroup gets without further arrangement, beside a few KB of other use. */
+#define VL_MAX_VREG 491520u
 
 #define VL_OCC_DEF 1u
 #define VL_OCC_USE 2u

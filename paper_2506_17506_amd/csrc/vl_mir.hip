@@ -38,7 +38,7 @@ static int32_t validate(const vl_mir_desc *d) {
   if (d->n_vreg && (!d->vreg_class || !d->vreg_width || !d->vreg_align)) return VL_E_NULL;
   if (d->n_instr == 0 || d->n_block == 0 || d->n_class == 0) return VL_E_SHAPE;
   if (d->n_class > vl::kMaxClass) return VL_E_RANGE;
-  if (d->n_occ >= (1u << 24) || d->n_instr >= (1u << 28) || d->n_vreg > (1u << 19)) return VL_E_RANGE;
+  if (d->n_occ >= (1u << 24) || d->n_instr >= (1u << 28) || d->n_vreg > VL_MAX_VREG) return VL_E_RANGE;
   for (uint32_t c = 0; c < d->n_class; ++c)
     if (d->class_size[c] == 0 || d->class_size[c] > 512) return VL_E_RANGE;
   if (d->blk_start[0] != 0 || d->blk_start[d->n_block] != d->n_instr) return VL_E_LAYOUT;

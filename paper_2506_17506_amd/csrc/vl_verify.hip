@@ -752,10 +752,49 @@ struct Launch {
   uint32_t units = 0, maxK = 0, max_words = 0, max_w = 1, max_rows = 0;
 };
 
+// Validates one job, lays out its entry of the device job table and adds it to the launch.
+// results_only: for the kernels that read nothing but the jobs' results (cand and ld are
+// neither checked nor used).
+int32_t fill_job(const vl_job &u, bool transposed, DevJob &d, Launch &out, bool results_only = false) {
+  if (!u.mir || !u.live || !u.out || (!u.cand && !results_only)) return VL_E_NULL;
+  if (u.mir->magic != kMirMagic || u.live->magic != kLiveMagic || u.live->mir != u.mir) return VL_E_ARG;
+  if (u.K == 0 || (!results_only && u.ld < (transposed ? u.K : u.mir->h.O))) return VL_E_SHAPE;
+  memset(&d, 0, sizeof(d));
+  d.mir = u.mir->dev; d.live = u.live->dev; d.cand = u.cand; d.out = u.out; d.ld = u.ld; d.K = u.K;
+  d.fast = (((uintptr_t)u.cand & 15) == 0 && (u.ld & 7) == 0) ? 1u : 0u;
+  d.transposed = transposed ? 1u : 0u;
+  // groups of up to 64 candidates; every group but the last has d.rows of them
+  d.n_groups = (u.K + 63) / 64;
+  d.rows = (u.K + d.n_groups - 1) / d.n_groups;
+  if (transposed) {
+    // occurrence-major: a group is copied in 16-byte pieces of 8 candidates, so groups
+    // start at multiples of 8; rounding the group size down keeps the groups small
+    // (100 candidates: 48 + 52) unless the last one then outgrows a wavefront
+    if (!d.fast) return VL_E_SHAPE;
+    uint32_t base = (u.K / d.n_groups) & ~7u;
+    if (base == 0 || u.K - (d.n_groups - 1) * base > 64) {
+      base = ((u.K + d.n_groups - 1) / d.n_groups + 7u) & ~7u;
+      d.n_groups = (u.K + base - 1) / base;
+    }
+    d.rows = base;
+  }
+  const uint32_t last = u.K - (d.n_groups - 1) * d.rows;
+  d.unit_base = out.units;
+  d.n_units = d.n_groups * u.live->h.T;
+  out.units += d.n_units;
+  out.maxK = std::max(out.maxK, u.K);
+  out.total_rows += u.K;
+  out.max_rows = std::max(out.max_rows, std::max(d.rows, last));
+  out.max_words = std::max(out.max_words, u.mir->h.occ_words);
+  out.max_w = std::max(out.max_w, u.mir->h.W);
+  return VL_OK;
+}
+
 // Validates the jobs, lays out the device job table and makes sure the device copy is
 // current (the copy is skipped when the table is the one the stream's slot already holds).
 // Called with the device's scratch locked.
-int32_t prepare_jobs(const vl_job *jobs, uint32_t n_jobs, hipStream_t stream, Scratch &sc, Launch &out, bool transposed = false) {
+int32_t prepare_jobs(const vl_job *jobs, uint32_t n_jobs, hipStream_t stream, Scratch &sc, Launch &out, bool transposed = false,
+                     bool results_only = false) {
   // the calling stream's slot, else a free one, else the least recently used one (whose
   // earlier kernels may be anywhere: the device is drained before the slot changes hands)
   Slot *found = nullptr;
@@ -777,39 +816,19 @@ int32_t prepare_jobs(const vl_job *jobs, uint32_t n_jobs, hipStream_t stream, Sc
   s.tick = ++sc.clock;
   std::vector<DevJob> tab(n_jobs);
   for (uint32_t j = 0; j < n_jobs; ++j) {
-    const vl_job &u = jobs[j];
-    if (!u.mir || !u.live || !u.cand || !u.out) return VL_E_NULL;
-    if (u.mir->magic != kMirMagic || u.live->magic != kLiveMagic || u.live->mir != u.mir) return VL_E_ARG;
-    if (u.K == 0 || u.ld < (transposed ? u.K : u.mir->h.O)) return VL_E_SHAPE;
-    DevJob &d = tab[j];
-    memset(&d, 0, sizeof(d));
-    d.mir = u.mir->dev; d.live = u.live->dev; d.cand = u.cand; d.out = u.out; d.ld = u.ld; d.K = u.K;
-    d.fast = (((uintptr_t)u.cand & 15) == 0 && (u.ld & 7) == 0) ? 1u : 0u;
-    d.transposed = transposed ? 1u : 0u;
-    // groups of up to 64 candidates; every group but the last has d.rows of them
-    d.n_groups = (u.K + 63) / 64;
-    d.rows = (u.K + d.n_groups - 1) / d.n_groups;
-    if (transposed) {
-      // occurrence-major: a group is copied in 16-byte pieces of 8 candidates, so groups
-      // start at multiples of 8; rounding the group size down keeps the groups small
-      // (100 candidates: 48 + 52) unless the last one then outgrows a wavefront
-      if (!d.fast) return VL_E_SHAPE;
-      uint32_t base = (u.K / d.n_groups) & ~7u;
-      if (base == 0 || u.K - (d.n_groups - 1) * base > 64) {
-        base = ((u.K + d.n_groups - 1) / d.n_groups + 7u) & ~7u;
-        d.n_groups = (u.K + base - 1) / base;
-      }
-      d.rows = base;
+    const int32_t rc = fill_job(jobs[j], transposed, tab[j], out, results_only);
+    if (rc != VL_OK) return rc;
+  }
+  if (results_only && s.n_valid == n_jobs) {
+    // the table a verification call on this stream left behind serves, whatever its candidate
+    // layout, when it names the same results
+    bool same = true;
+    for (uint32_t j = 0; j < n_jobs && same; ++j) same = s.host[j].out == jobs[j].out && s.host[j].K == jobs[j].K;
+    if (same) {
+      out.dev = s.dev;
+      out.work = s.work;
+      return VL_OK;
     }
-    const uint32_t last = u.K - (d.n_groups - 1) * d.rows;
-    d.unit_base = out.units;
-    d.n_units = d.n_groups * u.live->h.T;
-    out.units += d.n_units;
-    out.maxK = std::max(out.maxK, u.K);
-    out.total_rows += u.K;
-    out.max_rows = std::max(out.max_rows, std::max(d.rows, last));
-    out.max_words = std::max(out.max_words, u.mir->h.occ_words);
-    out.max_w = std::max(out.max_w, u.mir->h.W);
   }
   if (s.cap < n_jobs) {
     if (s.copied) VL_HIP(hipEventSynchronize(s.copied));
@@ -907,7 +926,7 @@ extern "C" int32_t vl_summarize_multi(const vl_job *jobs, uint32_t n_jobs, vl_su
   Scratch &s = g_scratch[device];
   std::lock_guard<std::mutex> lock(s.mu);
   Launch L;
-  const int32_t rc = prepare_jobs(jobs, n_jobs, stream, s, L);
+  const int32_t rc = prepare_jobs(jobs, n_jobs, stream, s, L, false, true);
   if (rc != VL_OK) return rc;
   k_summarize<<<n_jobs, 256, 0, stream>>>(L.dev, summaries);
   if (stats) k_loop_stats<<<1, 256, 0, stream>>>(L.dev, n_jobs, summaries, stats);
@@ -916,17 +935,8 @@ extern "C" int32_t vl_summarize_multi(const vl_job *jobs, uint32_t n_jobs, vl_su
 }
 
 namespace {
-int32_t verify_jobs(const vl_job *jobs, uint32_t n_jobs, hipStream_t stream, bool transposed) {
-  if (!jobs) return VL_E_NULL;
-  if (n_jobs == 0 || n_jobs > 65535) return VL_E_SHAPE;
-  int device = 0;
-  VL_HIP(hipGetDevice(&device));
-  if (device < 0 || device >= 16) return VL_E_ARG;
-  Scratch &s = g_scratch[device];
-  std::lock_guard<std::mutex> lock(s.mu);
-  Launch L;
-  const int32_t rc = prepare_jobs(jobs, n_jobs, stream, s, L, transposed);
-  if (rc != VL_OK) return rc;
+// k_init, the walk, k_finalize and k_resolve over the job table L.dev with the list L.work
+int32_t launch_all(const Launch &L, uint32_t n_jobs, hipStream_t stream, bool transposed) {
   const bool narrow = L.max_rows <= kPitchNarrow;   // every group of every job fits the narrow ring
   const size_t lds = (size_t)L.max_words * 64 * 4 + 64 * 4 + (size_t)kRing * (narrow ? kPitchNarrow : kPitchWide) * 2;
   k_init<<<dim3((L.maxK + 255) / 256, n_jobs), 256, 0, stream>>>(L.dev, L.work);
@@ -944,6 +954,20 @@ int32_t verify_jobs(const vl_job *jobs, uint32_t n_jobs, hipStream_t stream, boo
   k_resolve<<<(uint32_t)std::min<uint64_t>(L.total_rows, kResolveGroups), kResolveThreads, (size_t)L.max_w * 4, stream>>>(L.dev, L.work);
   VL_HIP(hipGetLastError());
   return VL_OK;
+}
+
+int32_t verify_jobs(const vl_job *jobs, uint32_t n_jobs, hipStream_t stream, bool transposed) {
+  if (!jobs) return VL_E_NULL;
+  if (n_jobs == 0 || n_jobs > 65535) return VL_E_SHAPE;
+  int device = 0;
+  VL_HIP(hipGetDevice(&device));
+  if (device < 0 || device >= 16) return VL_E_ARG;
+  Scratch &s = g_scratch[device];
+  std::lock_guard<std::mutex> lock(s.mu);
+  Launch L;
+  const int32_t rc = prepare_jobs(jobs, n_jobs, stream, s, L, transposed);
+  if (rc != VL_OK) return rc;
+  return launch_all(L, n_jobs, stream, transposed);
 }
 }  // namespace
 

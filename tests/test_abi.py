@@ -66,6 +66,12 @@ def test_validation_rejects_malformed_programs_before_touching_the_device():
     m = Mir.build([[(tuple(range(40)), tuple(range(40)))]], [[]], 40, [64]); cases.append((m, -3))  # 80 operands
     for m, want in cases:
         assert create_code(m) == want, (want, m)
+    # more vregs than a bitset row in LDS has room for: refused here, so that no launch can
+    # fail for want of LDS later
+    big = 491520 + 1
+    m = ok_mir()
+    m.vreg_class, m.vreg_width, m.vreg_align = np.zeros(big, np.uint8), np.ones(big, np.uint8), np.ones(big, np.uint8)
+    assert create_code(m) == -3
     # a well-formed program passes validation; without a GPU the device copy then fails
     assert create_code(ok_mir()) in (0, -6)
 

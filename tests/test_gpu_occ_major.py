@@ -116,3 +116,40 @@ def test_argument_errors():
         assert (out.cpu().numpy() == 7).all()
     finally:
         free(hm, hl)
+
+
+def test_loop_reductions_follow_occurrence_major_verification():
+    """the regeneration-loop reductions read only the results, so the same jobs serve them
+    after either entry point (here: pitch K rounded up to 8, far below the occurrence count)"""
+    ks = [gen.Kernel(gen.LOOP3, 0xAC0 + j, 400 + 100 * j, 300 + 75 * j) for j in range(3)]
+    rl = [k.candidates(5 + j, 40 + 30 * j, 25, 2)[0] for j, k in enumerate(ks)]
+    hm, hl, _, _ = gpu_analyze([k.mir for k in ks], dense=False)
+    try:
+        jobs, keep = [], []
+        for m, l, rows in zip(hm, hl, rl):
+            K, O = rows.shape
+            ld = (K + 7) // 8 * 8
+            host = np.zeros((O, ld), np.uint16)
+            host[:, :K] = rows.T
+            dev = torch.from_numpy(host.view(np.int16)).cuda()
+            out = torch.full((K, 4), -1, dtype=torch.int32, device="cuda")
+            keep.append((dev, out))
+            jobs.append((m, l, dev, K, ld, out))
+        jobs = vl.make_jobs(jobs)
+        summaries = torch.full((3, 6), -1, dtype=torch.int32, device="cuda")
+        stats = torch.full((6,), -1, dtype=torch.int64, device="cuda")
+        for _ in range(2):
+            vl.vl_verify_multi_occ_major(jobs)
+            vl.vl_summarize_multi(jobs, summaries, stats)
+        torch.cuda.synchronize()
+        got_s = summaries.cpu().numpy().view(np.uint32).reshape(-1).view(vl.SUMMARY_DTYPE)
+        got_l = stats.cpu().numpy().view(np.uint8).view(vl.LOOP_DTYPE)[0]
+    finally:
+        free(hm, hl)
+    want_s = np.array([vlo.summarize(vlo.verify(k.mir, vlo.analyze(k.mir), rows))[0] for k, rows in zip(ks, rl)],
+                      vlo.SUMMARY_DTYPE)
+    want_l = vlo.loop_stats(want_s, [r.shape[0] for r in rl])[0]
+    for f in ("first_ok", "passed", "hist"):
+        assert (got_s[f] == want_s[f]).all(), f
+    for f in ("n_passed", "max_tries", "sum_tries", "hist"):
+        assert (got_l[f] == want_l[f]).all(), f

@@ -199,6 +199,38 @@ def test_config4_and_5_kernels_full_size():
     free(hm, hl)
 
 
+def oracle_light(m, rows):
+    """the oracle's results for one kernel without the per-point rows (which take 75 MB at
+    20,000 instructions): what assert_liveness_equal compares when no dense rows are asked
+    for, and the verdicts"""
+    an = vlo.analyze(m, threads=1)
+    want = vlo.verify(m, an, rows, threads=1)
+    an.live_after = an.P = None
+    return an, want
+
+
+def test_config4_every_kernel():
+    """All 64 attention-shaped kernels of 20,000 instructions with their 100 candidates each,
+    in one batch as the library is meant to take them: liveness results and every verdict."""
+    from concurrent.futures import ThreadPoolExecutor
+    w = gen.config(4)
+    assert len(w.kernels) == 64 and all(r.shape[0] == 100 for r in w.rows)
+    mirs = [k.mir for k in w.kernels]
+    hm, hl, got, views = gpu_analyze(mirs, 0, dense=False)
+    assert views[0].tile_len == 512
+    res = gpu_verify(hm, hl, w.rows)
+    with ThreadPoolExecutor(16) as pool:   # the oracle releases the interpreter lock while it runs
+        ref = list(pool.map(oracle_light, mirs, w.rows))
+    hist = np.zeros(4, int)
+    for k, (m, (an, want)) in enumerate(zip(mirs, ref)):
+        got[k]["live_after"] = None
+        assert_liveness_equal(m, an, got[k], m.name)
+        assert_results_equal(want, res[k], m.name)
+        hist += np.bincount(want["status"], minlength=4)
+    assert hist.sum() == 6400 and (hist > 0).all(), hist
+    free(hm, hl)
+
+
 def test_dense_points_on_a_large_kernel():
     k = gen.Kernel(gen.MHA, 77, 6000, 4500)
     an = vlo.analyze(k.mir, interference=False)
