@@ -53,7 +53,8 @@ enum {
                            no predecessor placed before it in the linear order */
   VL_E_NOT_STRICT = -5, /* some value is live into the entry block */
   VL_E_HIP = -6,        /* a HIP runtime call failed; see vl_last_hip_error */
-  VL_E_ARG = -7         /* handle does not belong to this call (wrong program, stale, ...) */
+  VL_E_ARG = -7,        /* handle does not belong to this call (wrong program, stale, ...) */
+  VL_E_LIMIT = -8       /* vl_verify_batch_static: more than VL_STATIC_MAX_K candidates */
 };
 
 /* Most vregs a program may have: a bitset row over them (15,360 words, 60 KB) must fit the
@@ -161,6 +162,20 @@ enum { VL_BAD_BOUNDS = 1, VL_BAD_ALIGN = 2, VL_BAD_RESERVED = 4 };
  * out [device]: K results.  Asynchronous on `stream`. */
 int32_t vl_verify_batch(const vl_mir *mir, const vl_live *live, const uint16_t *cand, uint32_t K,
                         uint64_t ld, vl_result *out, vl_stream stream);
+
+/* vl_verify_batch for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid it.  Same arguments, same results.
+ * Its job table and the list of candidates whose clashing pair is still to be found live in
+ * a fixed device array inside the library (8 bytes per candidate, VL_STATIC_MAX_K of them:
+ * 512 KB per GPU the library runs on, held until the process ends); the call allocates and
+ * frees nothing, on the host or the device, and copies nothing from host memory: it only
+ * enqueues kernels on `stream`.  Every call on a GPU uses that GPU's one array: calls that
+ * overlap on one GPU (different streams, or threads) race; calls on one stream are ordered.
+ * Errors: as vl_verify_batch, and VL_E_LIMIT for K above VL_STATIC_MAX_K (nothing is
+ * launched then). */
+#define VL_STATIC_MAX_K 65536u
+int32_t vl_verify_batch_static(const vl_mir *mir, const vl_live *live, const uint16_t *cand, uint32_t K,
+                               uint64_t ld, vl_result *out, vl_stream stream);
 
 /* Many kernels in one launch.  jobs is [host] and is copied before the call returns;
  * cand/out inside are [device].  Asynchronous on `stream`; calls on different streams may

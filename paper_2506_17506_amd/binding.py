@@ -85,6 +85,8 @@ def load():
         L.vl_live_get.argtypes = [C.c_void_p, C.c_void_p]
         L.vl_verify_batch.restype = C.c_int32
         L.vl_verify_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint64, C.c_void_p, C.c_void_p]
+        L.vl_verify_batch_static.restype = C.c_int32
+        L.vl_verify_batch_static.argtypes = L.vl_verify_batch.argtypes
         L.vl_verify_multi.restype = C.c_int32
         L.vl_verify_multi.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p]
         L.vl_verify_multi_occ_major.restype = C.c_int32
@@ -204,6 +206,14 @@ def vl_verify_batch(mir, live, cand, K: int, ld: int, out, stream=None) -> None:
                                 _stream_ptr(stream))
     if rc != 0:
         raise VlError(rc, "vl_verify_batch")
+
+
+def vl_verify_batch_static(mir, live, cand, K: int, ld: int, out, stream=None) -> None:
+    """vl_verify_batch without any allocation inside the library."""
+    rc = load().vl_verify_batch_static(mir, live, C.c_void_p(_dev_ptr(cand)), K, ld, C.c_void_p(_dev_ptr(out)),
+                                       _stream_ptr(stream))
+    if rc != 0:
+        raise VlError(rc, "vl_verify_batch_static")
 
 
 def make_jobs(jobs):

@@ -27,6 +27,7 @@ extern "C" const char *vl_strerror(int32_t code) {
     case VL_E_NOT_STRICT: return "a value is live into the entry block";
     case VL_E_HIP: return "a HIP runtime call failed";
     case VL_E_ARG: return "handle does not belong to this call";
+    case VL_E_LIMIT: return "more candidates than the entry point that allocates nothing has room for (VL_STATIC_MAX_K)";
   }
   return "unknown error code";
 }

@@ -984,3 +984,51 @@ extern "C" int32_t vl_verify_batch(const vl_mir *mir, const vl_live *live, const
   vl_job j = {mir, live, cand, K, ld, out};
   return vl_verify_multi(&j, 1, stream);
 }
+
+// ---- the entry point that allocates nothing ----------------------------------------------
+// Its job table (one job) and its list of candidates to resolve live in a file-scope device
+// array instead of memory the library allocates.  The array's name is only a host-side handle:
+// its device address is looked up once per device and kept.
+namespace {
+constexpr uint32_t kStaticMaxK = VL_STATIC_MAX_K;
+struct StaticScratch {
+  DevJob job;
+  uint2 work[kStaticMaxK + 1];
+};
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[sizeof(StaticScratch)];
+namespace {
+std::mutex g_static_mu;
+void *g_static_ptr[16] = {};
+
+__global__ void k_put_job(DevJob job, DevJob *dst) { *dst = job; }
+}  // namespace
+
+extern "C" int32_t vl_verify_batch_static(const vl_mir *mir, const vl_live *live, const uint16_t *cand, uint32_t K,
+                                          uint64_t ld, vl_result *out, vl_stream stream_) {
+  if (K > kStaticMaxK) return VL_E_LIMIT;
+  const vl_job u = {mir, live, cand, K, ld, out};
+  DevJob d;
+  Launch L;
+  const int32_t rc = fill_job(u, false, d, L);
+  if (rc != VL_OK) return rc;
+  hipStream_t stream = (hipStream_t)stream_;
+  int device = 0;
+  VL_HIP(hipGetDevice(&device));
+  if (device < 0 || device >= 16) return VL_E_ARG;
+  StaticScratch *sc;
+  {
+    // the array's address on this device, looked up on the first call made with it current
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    if (!g_static_ptr[device]) {
+      void *ptr = nullptr;
+      VL_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+      g_static_ptr[device] = ptr;
+    }
+    sc = (StaticScratch *)g_static_ptr[device];
+  }
+  L.dev = &sc->job;
+  L.work = sc->work;
+  k_put_job<<<1, 1, 0, stream>>>(d, &sc->job);
+  return launch_all(L, 1, stream, false);
+}

@@ -31,7 +31,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_error_strings():
-    for code in range(0, -8, -1):
+    for code in range(0, -9, -1):
         assert vl.vl_strerror(code) and "unknown" not in vl.vl_strerror(code)
     assert "unknown" in vl.vl_strerror(-99)
 
@@ -80,6 +80,8 @@ def test_null_arguments():
     lib = vl.load()
     assert lib.vl_mir_create(None, None) == -1
     assert lib.vl_verify_multi(None, 1, None) == -1
+    assert lib.vl_verify_batch_static(None, None, None, 1, 1, None, None) in (-1, -6)
+    assert lib.vl_verify_batch_static(None, None, None, 65537, 1, None, None) == -8
     assert lib.vl_verify_multi_occ_major(None, 1, None) == -1
     assert lib.vl_summarize_multi(None, 1, None, None, None) == -1
     assert lib.vl_free_bases_multi(None, 1, None, None) == -1
