@@ -94,6 +94,7 @@ __global__ void k_init(const DevJob *__restrict__ jobs, uint2 *__restrict__ work
 // access is a DS instruction rather than a flat one):
 //   [0, occ_words * 64)            occupancy masks [word][lane]
 //   [keys, keys + 64)              per-row violation keys
+//   [keys + 64, keys + 320)        the occupancy wavefront's event buffer (64 records of 16 bytes)
 //   [ring32, ...)                  the ring [occurrence % 192][row], addressed in uint16 from
 //                                  ring16 = 2 * ring32; a lane of the check wavefronts reads four
 //                                  rows of one occurrence with one 8-byte read
@@ -281,7 +282,8 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(6)
   w.n_occ = m.O;
   w.fast = J.fast;
   w.keys = m.occ_words * 64;
-  w.ring16 = (w.keys + 64) * 2;
+  const uint32_t evb = (w.keys + 64) * 4;   // byte offset of the occupancy wavefront's event buffer: 64 records of 16 bytes
+  w.ring16 = (w.keys + 64 + 256) * 2;
   for (uint32_t x = w.tid; x < m.occ_words * 64; x += kWalkThreads) vl_lds[x] = 0;
   if (w.tid < 64) vl_lds[w.keys + w.tid] = kKeyOk;
   // per-class file size and first mask word, one class per lane, read back by lane index
@@ -327,11 +329,9 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(6)
     return r;
   };
   // Replays a batch of up to 64 records held one per lane (lanes past the batch hold zero
-  // records, which flip nothing).  The fields of event j are read out of lane j; they are
-  // ready to use.  Eight events at a time: the eight mask updates are issued back to back
-  // (LDS executes them in order), and before their old bits are awaited the eight registers
-  // of the next group are already requested from the ring, so that one LDS round trip per
-  // group is exposed instead of two.
+  // records, which flip nothing).  Four events at a time, two groups in flight: the mask
+  // updates of a group are issued back to back (LDS executes them in order), and before their
+  // old bits are awaited the records and registers of the next group are already requested.
   constexpr int G = 8;
   auto replay = [&](const u32x4 r, uint32_t cnt) __attribute__((always_inline)) {
     if (__any((r.w & kEvtSlow) != 0)) {
@@ -353,39 +353,66 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(6)
       }
       return;
     }
-    auto ring_reads = [&](uint32_t g0, uint32_t (&p)[G]) __attribute__((always_inline)) {
+    typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
+    typedef __attribute__((address_space(3))) uint16_t lds_u16;
+    typedef __attribute__((address_space(3))) uint32_t lds_u32;
+    // LDS addresses as integers with the array's own address folded in once
+    const uint32_t lds0 = (uint32_t)(size_t)(lds_u32 *)vl_lds;
+    const uint32_t a_ev = lds0 + evb, a_ring = lds0 + my_ring, a_occ = lds0 + my_occ;
+    // The batch goes through LDS: every lane writes its record in the form the replay uses
+    // (x: byte offset of the carrying occurrence's ring slot, y: the tuple's mask at bit 0,
+    // z: byte offset of the class's first mask word, w: all ones for an occupy that is
+    // tested), and event j is then read back by all lanes at once from one address, so that
+    // its fields arrive in vector registers without lane reads or scalar traffic.
+    {
+      u32x4 t = r;
+      t.w = (uint32_t)((int32_t)r.w >> 31);
+      *(lds_u32x4 *)(size_t)(a_ev + w.lane * 16u) = t;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    constexpr int H = 4;   // events per group; two groups in flight
+    struct Ev { uint32_t y, zb, t, p; };
+    auto fetch_group = [&](uint32_t g0, Ev (&e)[H]) __attribute__((always_inline)) {
 #pragma unroll
-      for (int t = 0; t < G; ++t)
-        p[t] = *reinterpret_cast<const uint16_t *>(lds_bytes + my_ring + __builtin_amdgcn_readlane(r.x, g0 + t));
-    };
-    // one group: `cur` holds its registers, `nxt` receives the next group's
-    auto group_step = [&](uint32_t g0, uint32_t (&cur)[G], uint32_t (&nxt)[G]) __attribute__((always_inline)) {
-      uint32_t old[G], msk[G];
-#pragma unroll
-      for (int t = 0; t < G; ++t) {
-        msk[t] = (uint32_t)__builtin_amdgcn_readlane(r.y, g0 + t) << (cur[t] & 31u);
-        old[t] = __hip_atomic_fetch_xor(
-            reinterpret_cast<uint32_t *>(lds_bytes + ((((cur[t] >> 5) & 15u) << 8) + my_occ + __builtin_amdgcn_readlane(r.z, g0 + t))),
-            msk[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+      for (int t = 0; t < H; ++t) {
+        const u32x4 x = *(lds_u32x4 *)(size_t)(a_ev + (g0 + t) * 16u);
+        e[t].y = x.y; e[t].zb = x.z; e[t].t = x.w;
+        e[t].p = *(lds_u16 *)(size_t)(a_ring + x.x);
       }
-      if (g0 + G < cnt) ring_reads(g0 + G, nxt);
+    };
+    auto apply_group = [&](uint32_t g0, Ev (&e)[H], uint32_t (&hit)[H]) __attribute__((always_inline)) {
+#pragma unroll
+      for (int t = 0; t < H; ++t) {
+        const uint32_t msk = e[t].y << (e[t].p & 31u);
+        const uint32_t old = __hip_atomic_fetch_xor((lds_u32 *)(size_t)(((e[t].p << 3) & 0xF00u) + e[t].zb + a_occ), msk,
+                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+        hit[t] = old & msk & e[t].t;
+      }
+    };
+    auto settle = [&](uint32_t g0, uint32_t (&hit)[H]) __attribute__((always_inline)) {
       uint32_t any_hit = 0;
 #pragma unroll
-      for (int t = 0; t < G; ++t) {
-        old[t] &= msk[t] & (uint32_t)((int32_t)__builtin_amdgcn_readlane(r.w, g0 + t) >> 31);   // kEvtTested is the sign bit
-        any_hit |= old[t];
-      }
+      for (int t = 0; t < H; ++t) any_hit |= hit[t];
       if (__any((any_hit & alive) != 0)) {
 #pragma unroll
-        for (int t = 0; t < G; ++t) clash(old[t], __builtin_amdgcn_readlane(r.w, g0 + t) & 0xFFFFFFu);
+        for (int t = 0; t < H; ++t) clash(hit[t], __builtin_amdgcn_readlane(r.w, g0 + t) & 0xFFFFFFu);
       }
     };
-    uint32_t pa[G], pb[G] = {};
-    ring_reads(0, pa);
-    for (uint32_t g0 = 0; g0 < cnt; g0 += 2 * G) {   // two groups per turn: the register sets swap roles
-      group_step(g0, pa, pb);
-      if (g0 + G < cnt) group_step(g0 + G, pb, pa);
+    Ev ea_[H], eb_[H];
+    uint32_t ha[H], hb[H];
+    fetch_group(0, ea_);
+    for (uint32_t g0 = 0; g0 < cnt; g0 += 2 * H) {
+      apply_group(g0, ea_, ha);
+      if (g0 + H < cnt) fetch_group(g0 + H, eb_);
+      settle(g0, ha);
+      if (g0 + H < cnt) {
+        apply_group(g0 + H, eb_, hb);
+        if (g0 + 2 * H < cnt) fetch_group(g0 + 2 * H, ea_);
+        settle(g0 + H, hb);
+      }
     }
+    __builtin_amdgcn_wave_barrier();   // the buffer is rewritten by the next batch
   };
   // events [from, to); `first` holds the records [from, from + 64) fetched ahead
   auto events = [&](uint32_t from, uint32_t to, u32x4 first) __attribute__((always_inline)) {
@@ -938,7 +965,7 @@ namespace {
 // k_init, the walk, k_finalize and k_resolve over the job table L.dev with the list L.work
 int32_t launch_all(const Launch &L, uint32_t n_jobs, hipStream_t stream, bool transposed) {
   const bool narrow = L.max_rows <= kPitchNarrow;   // every group of every job fits the narrow ring
-  const size_t lds = (size_t)L.max_words * 64 * 4 + 64 * 4 + (size_t)kRing * (narrow ? kPitchNarrow : kPitchWide) * 2;
+  const size_t lds = (size_t)L.max_words * 64 * 4 + 64 * 4 + 1024 + (size_t)kRing * (narrow ? kPitchNarrow : kPitchWide) * 2;
   k_init<<<dim3((L.maxK + 255) / 256, n_jobs), 256, 0, stream>>>(L.dev, L.work);
   if (g_time_start) VL_HIP(hipEventRecord(g_time_start, stream));
   if (transposed) {
