@@ -105,6 +105,8 @@ constexpr uint32_t kEvtPost = 1u << 29;    // release of a value that is dead on
 constexpr uint32_t kEvtSlow = 1u << 30;    // not for the fast path: the tuple may cross a mask word, is 32 wide,
                                            // or its register has to come from outside the ring
 constexpr uint32_t kEvtTested = 1u << 31;  // occupy with test (a definition); otherwise a plain flip
+constexpr uint32_t kSeedLinked = 1u << 28; // (tile live-in lists only) the vreg's next mention after the source occurrence lies
+                                           // inside the tile: that mention's consistency link reaches back across the tile's start
 
 // Per-occurrence roles computed by the event kernel.
 constexpr uint8_t kRolePreKill = 1, kRoleTestSet = 2, kRolePostKill = 4, kRoleFirst = 8;

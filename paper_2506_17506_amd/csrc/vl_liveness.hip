@@ -1090,8 +1090,12 @@ __device__ inline void f_seed_src(const DevMir VL_GLOBAL &m, DevLive VL_GLOBAL &
   const u32x4 raw = L.seeds[k];
   const uint32_t v = raw.x, t = raw.y;
   // the register is always gathered from memory: the ring offset stays unused
-  u32x4 r = event_record(m, source_occurrence(L, v, t * L.tile_len), v, false, true);
+  const uint32_t at = t * L.tile_len, lo = L.vcnt[v], hi = L.vcnt[v + 1];
+  const uint32_t x = lower_bound(L.ent_instr, lo, hi, at << 2);   // first mention at or after the tile's start
+  u32x4 r = event_record(m, x > lo ? L.vocc[x - 1] : (x < hi ? L.vocc[x] : 0u), v, false, true);
   r.x &= ~0xFFu;   // only the vreg: the register is always gathered from memory
+  // the verifier keeps the gathered registers at hand for the link of that first mention
+  if (x > lo && x < hi && (L.ent_instr[x] >> 2) < min(m.N, at + L.tile_len)) r.w |= kSeedLinked;
   L.seeds[k] = r;
 }
 

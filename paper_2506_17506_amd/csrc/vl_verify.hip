@@ -422,48 +422,63 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(6)
       replay(r, min(64u, to - e));
     }
   };
+  // Register cache of a check wavefront, for consistency links that reach back beyond the
+  // ring: slot s holds, one candidate per lane (16 bits, two slots per register), the
+  // registers of the occurrence named by lane s of cache_tag.  Slots are filled in turn (the
+  // oldest entry goes) and found by comparing all tags at once; a miss only means that the
+  // value is gathered from memory instead.
+  constexpr uint32_t kCacheSlots = 32;   // two per register
+  typedef uint32_t cache_t __attribute__((ext_vector_type(kCacheSlots / 2)));   // a vector, so that it stays in registers
+  cache_t cache = 0;
+  uint32_t cache_tag = kNone, cache_next = 0;
+  auto cache_put = [&](uint32_t o, uint32_t val) __attribute__((always_inline)) {
+    const uint32_t slot = cache_next;
+    cache_next = (cache_next + 1u) % kCacheSlots;
+    const uint32_t both = cache[slot >> 1];
+    cache[slot >> 1] = (slot & 1u) ? ((both & 0xFFFFu) | (val << 16)) : ((both & 0xFFFF0000u) | val);
+    if (w.lane == slot) cache_tag = o;
+  };
+
   // The values live into the tile: their registers mostly lie before the ring and are
-  // gathered from memory, eight gathers in flight.  Lanes past the list hold zero records.
-  // Every entry flips its own bits, in any order: all four wavefronts take a share (`part`
-  // of kWalkThreads / 64), each with one candidate per lane, before the first barrier.
+  // gathered from memory, eight gathers in flight.  Every entry flips its own bits, in any
+  // order, before the first barrier: the three check wavefronts share the list by the owner
+  // of the source occurrence (index modulo three), one candidate per lane, and keep the
+  // registers of the values whose first mention in the tile they will check (kSeedLinked),
+  // so that such a link is not gathered a second time long after the line has left the caches.
   auto seed_events = [&](uint32_t from, uint32_t to, uint32_t part) __attribute__((always_inline)) {
     for (uint32_t base = from; base < to; base += 64) {
       const uint32_t cnt = min(64u, to - base);
       u32x4 r = 0;
       if (w.lane < cnt) r = g_seeds[base + w.lane];
       const bool any_slow = __any((r.w & kEvtSlow) != 0);
-      for (uint32_t g0 = part * G; g0 < cnt; g0 += (kWalkThreads / 64u) * G) {
-        uint32_t p[G];
+      uint64_t mine = __ballot(w.lane < cnt && (r.w & 0xFFFFFFu) % kCheckWaves == part);
+      while (mine) {
+        uint32_t idx[G], p[G];
+#pragma unroll
+        for (int t = 0; t < G; ++t) {
+          idx[t] = mine ? (uint32_t)__builtin_ctzll(mine) : 64u;   // 64: no entry
+          mine &= mine - 1;   // (zero stays zero)
+        }
 #pragma unroll
         for (int t = 0; t < G; ++t)
-          p[t] = from_memory<kT>(w, __builtin_amdgcn_readlane(r.w, (g0 + t) & 63u) & 0xFFFFFFu);
-        if (any_slow) {
+          p[t] = from_memory<kT>(w, __builtin_amdgcn_readlane(r.w, idx[t] & 63u) & 0xFFFFFFu);
 #pragma unroll
-          for (int t = 0; t < G; ++t)
-            if (g0 + t < cnt) {
-              const uint32_t o = __builtin_amdgcn_readlane(r.w, (g0 + t) & 63u) & 0xFFFFFFu;
-              apply1(o, g_chk[o].y >> 16, false, p[t]);
-            }
-        } else {
-#pragma unroll
-          for (int t = 0; t < G; ++t) {
-            const uint32_t msk = (uint32_t)__builtin_amdgcn_readlane(r.y, (g0 + t) & 63u) << (p[t] & 31u);
+        for (int t = 0; t < G; ++t) {
+          if (idx[t] == 64u) continue;
+          const uint32_t sw = __builtin_amdgcn_readlane(r.w, idx[t]), o = sw & 0xFFFFFFu;
+          if (any_slow) {
+            apply1(o, g_chk[o].y >> 16, false, p[t]);
+          } else {
+            const uint32_t msk = (uint32_t)__builtin_amdgcn_readlane(r.y, idx[t]) << (p[t] & 31u);
             __hip_atomic_fetch_xor(reinterpret_cast<uint32_t *>(lds_bytes + ((((p[t] >> 5) & 15u) << 8) + my_occ +
-                                                                               __builtin_amdgcn_readlane(r.z, (g0 + t) & 63u))),
+                                                                               __builtin_amdgcn_readlane(r.z, idx[t]))),
                                    msk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
           }
+          if (sw & kSeedLinked) cache_put(o, p[t]);
         }
       }
     }
   };
-
-  // Register cache of a check wavefront: slot s holds, one candidate per lane (16 bits, two
-  // slots per register), the registers of the occurrence named by lane s of cache_tag.  Direct-mapped; a stale or foreign tag
-  // only means the value is fetched from memory instead.
-  constexpr uint32_t kCacheSlots = 32;   // two per register
-  typedef uint32_t cache_t __attribute__((ext_vector_type(kCacheSlots / 2)));   // a vector, so that it stays in registers
-  cache_t cache = 0;
-  uint32_t cache_tag = kNone;
 
   // ---- checks of one chunk (lane = check, loop over rows) ----
   // Per lane: ring offsets of the occurrence and of the previous occurrence of its vreg,
@@ -542,9 +557,14 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(6)
       const uint32_t pv = VL_LDS16[w.ring16 + (oj % kRing) * kRingStride + w.row];
       uint32_t qv;
       if (dj != 0xFFFFu) {
-        const uint32_t pj = oj - dj, slot = (pj / kCheckWaves) % kCacheSlots;
-        if ((uint32_t)__builtin_amdgcn_readlane(cache_tag, slot) == pj) qv = (cache[slot >> 1] >> (16u * (slot & 1u))) & 0xFFFFu;
-        else qv = from_memory<kT>(w, pj);
+        const uint32_t pj = oj - dj;
+        const uint64_t at = __ballot(cache_tag == pj);
+        if (at) {
+          const uint32_t slot = __builtin_ctzll(at);
+          qv = (cache[slot >> 1] >> (16u * (slot & 1u))) & 0xFFFFu;
+        } else {
+          qv = from_memory<kT>(w, pj);
+        }
       } else {
         qv = from_memory<kT>(w, g_prev_occ[oj]);
       }
@@ -555,10 +575,8 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(6)
     while (keep) {
       const uint32_t j = __builtin_ctzll(keep);
       keep &= keep - 1;
-      const uint32_t oj = c * kChunk + j, slot = (oj / kCheckWaves) % kCacheSlots;
-      const uint32_t val = VL_LDS16[w.ring16 + (oj % kRing) * kRingStride + w.row], both = cache[slot >> 1];
-      cache[slot >> 1] = (slot & 1u) ? ((both & 0xFFFFu) | (val << 16)) : ((both & 0xFFFF0000u) | val);
-      if (w.lane == slot) cache_tag = oj;
+      const uint32_t oj = c * kChunk + j;
+      cache_put(oj, VL_LDS16[w.ring16 + (oj % kRing) * kRingStride + w.row]);
     }
   };
 
@@ -583,7 +601,6 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(6)
     uint32_t cut_lo = ea;
     uint32_t v_cut_next = g_evt_cut[min(ca + 1, n_chunk) + lane_zero];
     u32x4 rec_next = fetch_records(ea, eb);   // the first batch, in flight during the seeds
-    if (tile > 0) seed_events(g_seed_off[tile], g_seed_off[tile + 1], 0u);
     __syncthreads();   // chunks up to ca are in the ring
     for (uint32_t c = ca; c != c_stop; ++c) {
       if (c < c_end) w.hi = (c + 1) * kChunk;
@@ -606,7 +623,7 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(6)
     }
     if (ca + 1 < c_end) load_chunk<kT>(w, (ca + 1) * kChunk, j);
     u32x4 chk_next = load_chk(ca);
-    if (tile > 0) seed_events(g_seed_off[tile], g_seed_off[tile + 1], role);   // this wavefront's share of the live-in list
+    if (tile > 0) seed_events(g_seed_off[tile], g_seed_off[tile + 1], j);   // this wavefront's share of the live-in list
     __syncthreads();
     for (uint32_t c = ca; c != c_stop; ++c) {
       if (c < c_end) {
