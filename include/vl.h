@@ -177,7 +177,9 @@ int32_t vl_verify_batch(const vl_mir *mir, const vl_live *live, const uint16_t *
 int32_t vl_verify_batch_static(const vl_mir *mir, const vl_live *live, const uint16_t *cand, uint32_t K,
                                uint64_t ld, vl_result *out, vl_stream stream);
 
-/* Many kernels in one launch.  jobs is [host] and is copied before the call returns;
+/* Many kernels in one launch: the K samples that Section 3.4's regeneration loop draws for
+ * every kernel of a suite (Section 4.2 evaluates Pass@100), checked as vl_verify_batch checks
+ * one kernel's.  jobs is [host] and is copied before the call returns;
  * cand/out inside are [device].  Asynchronous on `stream`; calls on different streams may
  * overlap on the device.  Device memory owned by the library: per device and calling
  * stream (up to four streams at a time; a fifth takes over the least recently used slot
@@ -198,8 +200,8 @@ typedef struct {
 } vl_job;
 int32_t vl_verify_multi(const vl_job *jobs, uint32_t n_jobs, vl_stream stream);
 
-/* The same for candidates stored occurrence-major, which is how a batched decoder leaves
- * them (one step emits one occurrence of all K samples): jobs[j].cand is [n_occ][ld] with
+/* The same (Section 3.4, the samples of the regeneration loop) for candidates stored
+ * occurrence-major, which is how a batched decoder leaves them (one step emits one occurrence of all K samples): jobs[j].cand is [n_occ][ld] with
  * cand[o * ld + k] the register of occurrence o in candidate k, ld >= K.  Requires cand on a
  * 16-byte boundary and ld a multiple of 8 (VL_E_SHAPE otherwise); the up to 7 elements of
  * padding after the K-th candidate of each occurrence are read and ignored.  Results as for
@@ -247,12 +249,6 @@ typedef struct {
 } vl_count_job;
 int32_t vl_count_violations_multi(const vl_count_job *jobs, uint32_t n_jobs, vl_stream stream);
 
-/* Measurement hook: one launch that only reads `bytes` bytes (a multiple of 16, 16-byte
- * aligned) of buf [device] with 16-byte loads, for the benchmark's "what does a plain
- * streaming read reach" figure.  sink [device]: one word, practically never written.
- * Asynchronous on `stream`.  Errors: VL_E_NULL, VL_E_SHAPE. */
-int32_t vl_stream_read_probe(const void *buf, uint64_t bytes, uint32_t *sink, vl_stream stream);
-
 /* Register-bank conflicts, a quality measure beside validity (Section 2: registers are
  * organised in banks, four on NVIDIA GPUs; reading several values from one bank stalls the
  * pipeline one cycle per extra value, which is why the FFMA of the overview figure reads R4,
@@ -290,12 +286,6 @@ typedef struct {
   uint32_t reserved0; /* must be 0 */
 } vl_mask_query;
 int32_t vl_free_bases_multi(const vl_mask_query *queries, uint32_t n, uint32_t *masks, vl_stream stream);
-
-/* Measurement aid for callers that cannot allocate inside the timed region: the next
- * vl_verify_multi / vl_verify_batch call on this thread records the two hipEvent_t
- * (caller-owned, either may be NULL) on its stream immediately before and after the
- * candidate-walk kernel, the one that reads the candidate rows.  One-shot. */
-int32_t vl_verify_time_next(void *start_event, void *stop_event);
 
 const char *vl_strerror(int32_t code);
 /* hipError_t of the last failed runtime call on this thread (0 if none). */

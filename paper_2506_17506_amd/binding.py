@@ -95,14 +95,10 @@ def load():
         L.vl_summarize_multi.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.vl_count_violations_multi.restype = C.c_int32
         L.vl_count_violations_multi.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p]
-        L.vl_stream_read_probe.restype = C.c_int32
-        L.vl_stream_read_probe.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]
         L.vl_bank_conflicts.restype = C.c_int32
         L.vl_bank_conflicts.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint64, C.c_uint32, C.c_void_p, C.c_void_p]
         L.vl_free_bases_multi.restype = C.c_int32
         L.vl_free_bases_multi.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p]
-        L.vl_verify_time_next.restype = C.c_int32
-        L.vl_verify_time_next.argtypes = [C.c_void_p, C.c_void_p]
         L.vl_strerror.restype = C.c_char_p
         L.vl_strerror.argtypes = [C.c_int32]
         L.vl_last_hip_error.restype = C.c_int32
@@ -266,12 +262,6 @@ def vl_count_violations_multi(jobs, stream=None) -> None:
         raise VlError(rc, "vl_count_violations_multi")
 
 
-def vl_stream_read_probe(buf, n_bytes: int, sink, stream=None) -> None:
-    rc = load().vl_stream_read_probe(C.c_void_p(_dev_ptr(buf)), n_bytes, C.c_void_p(_dev_ptr(sink)), _stream_ptr(stream))
-    if rc != 0:
-        raise VlError(rc, "vl_stream_read_probe")
-
-
 def vl_bank_conflicts(mir, cand, K: int, ld: int, n_banks: int, out, stream=None) -> None:
     """out: device buffer of K uint32."""
     rc = load().vl_bank_conflicts(mir, C.c_void_p(_dev_ptr(cand)), K, ld, n_banks, C.c_void_p(_dev_ptr(out)),
@@ -295,11 +285,6 @@ def vl_free_bases_multi(queries, masks, stream=None) -> None:
     rc = load().vl_free_bases_multi(arr, len(arr), C.c_void_p(_dev_ptr(masks)), _stream_ptr(stream))
     if rc != 0:
         raise VlError(rc, "vl_free_bases_multi")
-
-
-def vl_verify_time_next(start_event, stop_event) -> None:
-    """start_event / stop_event: raw hipEvent_t handles (ints) or None."""
-    load().vl_verify_time_next(C.c_void_p(start_event), C.c_void_p(stop_event))
 
 
 def _dev_ptr(x) -> int:

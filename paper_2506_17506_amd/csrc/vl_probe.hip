@@ -1,10 +1,14 @@
-// Measurement hook: a plain streaming read, to put the verifier's achieved bytes per second
-// beside what a kernel that does nothing but read reaches on the same device.
-#include "vl_dev.h"
+// Measurement hook (include/vl_bench.h), built into a library of its own: a plain streaming
+// read, to put the verifier's achieved bytes per second beside what a kernel that does nothing
+// but read reaches on the same device.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
 
-using namespace vl;
+#include "../../include/vl_bench.h"
 
 namespace {
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 __global__ __launch_bounds__(256) void k_stream_read(const u32x4 *__restrict__ buf, uint64_t vecs, uint32_t *__restrict__ sink) {
   u32x4 acc = {0, 0, 0, 0};
   // each thread keeps four 16-byte loads in flight
@@ -20,10 +24,9 @@ __global__ __launch_bounds__(256) void k_stream_read(const u32x4 *__restrict__ b
 }
 }  // namespace
 
-extern "C" int32_t vl_stream_read_probe(const void *buf, uint64_t bytes, uint32_t *sink, vl_stream stream) {
-  if (!buf || !sink) return VL_E_NULL;
-  if (bytes < 16 || ((uintptr_t)buf & 15)) return VL_E_SHAPE;
+extern "C" int32_t vl_stream_read_probe(const void *buf, uint64_t bytes, uint32_t *sink, void *stream) {
+  if (!buf || !sink) return -1;
+  if (bytes < 16 || ((uintptr_t)buf & 15)) return -2;
   k_stream_read<<<256 * 32, 256, 0, (hipStream_t)stream>>>((const u32x4 *)buf, bytes / 16, sink);
-  VL_HIP(hipGetLastError());
-  return VL_OK;
+  return hipGetLastError() == hipSuccess ? 0 : -6;
 }
