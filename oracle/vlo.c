@@ -420,3 +420,179 @@ void vlo_bank_conflicts(const vlo_mir *m, const uint16_t *cand, uint32_t K, uint
   }
   free(per_bank);
 }
+
+/* ---- liveness of parts of a tuple (see vlo.h) -------------------------------------------- */
+void vlo_lane_base(const vlo_mir *m, uint32_t *lane_base) {
+  uint32_t n = 0;
+  for (uint32_t v = 0; v < m->n_vreg; ++v) { lane_base[v] = n; n += m->vreg_width[v]; }
+  lane_base[m->n_vreg] = n;
+}
+
+/* does occurrence o access lane j of its vreg? */
+static int touches(const vlo_mir *m, const uint32_t *occ_lanes, uint32_t o, uint32_t j) {
+  if (!occ_lanes || occ_lanes[o] == 0) return 1;
+  (void)m;
+  return (occ_lanes[o] >> j) & 1u;
+}
+
+int vlo_block_liveness_lanes(const vlo_mir *m, const uint32_t *occ_lanes, uint8_t *live_in, uint8_t *live_out) {
+  const uint32_t B = m->n_block;
+  uint32_t *base = (uint32_t *)malloc(((size_t)m->n_vreg + 1) * 4);
+  vlo_lane_base(m, base);
+  const uint32_t Lt = base[m->n_vreg];
+  uint8_t *use = (uint8_t *)calloc((size_t)B * Lt + 1, 1);
+  uint8_t *def = (uint8_t *)calloc((size_t)B * Lt + 1, 1);
+  for (uint32_t b = 0; b < B; ++b) {
+    uint8_t *u = use + (size_t)b * Lt, *d = def + (size_t)b * Lt;
+    for (uint32_t i = m->blk_start[b]; i < m->blk_start[b + 1]; ++i) {
+      for (uint32_t o = m->instr_occ_off[i]; o < m->instr_occ_off[i + 1]; ++o)
+        if (m->occ_flags[o] & VLO_OCC_USE)
+          for (uint32_t j = 0; j < m->vreg_width[m->occ_vreg[o]]; ++j)
+            if (touches(m, occ_lanes, o, j) && !d[base[m->occ_vreg[o]] + j]) u[base[m->occ_vreg[o]] + j] = 1;
+      for (uint32_t o = m->instr_occ_off[i]; o < m->instr_occ_off[i + 1]; ++o)
+        if (m->occ_flags[o] & VLO_OCC_DEF)
+          for (uint32_t j = 0; j < m->vreg_width[m->occ_vreg[o]]; ++j)
+            if (touches(m, occ_lanes, o, j)) d[base[m->occ_vreg[o]] + j] = 1;
+    }
+  }
+  memset(live_in, 0, (size_t)B * Lt);
+  memset(live_out, 0, (size_t)B * Lt);
+  int sweeps = 0, changed = 1;
+  while (changed) {
+    changed = 0;
+    ++sweeps;
+    for (uint32_t b = 0; b < B; ++b) {
+      uint8_t *in = live_in + (size_t)b * Lt, *out = live_out + (size_t)b * Lt;
+      for (uint32_t e = m->succ_off[b]; e < m->succ_off[b + 1]; ++e) {
+        const uint8_t *sin = live_in + (size_t)m->succ[e] * Lt;
+        for (uint32_t x = 0; x < Lt; ++x)
+          if (sin[x] && !out[x]) { out[x] = 1; changed = 1; }
+      }
+      for (uint32_t x = 0; x < Lt; ++x) {
+        uint8_t nv = (uint8_t)(use[(size_t)b * Lt + x] | (out[x] & !def[(size_t)b * Lt + x]));
+        if (nv && !in[x]) { in[x] = 1; changed = 1; }
+      }
+    }
+  }
+  free(use);
+  free(def);
+  free(base);
+  return sweeps;
+}
+
+void vlo_points_lanes(const vlo_mir *m, const uint32_t *occ_lanes, const uint8_t *live_out, uint8_t *live_after) {
+  uint32_t *base = (uint32_t *)malloc(((size_t)m->n_vreg + 1) * 4);
+  vlo_lane_base(m, base);
+  const uint32_t Lt = base[m->n_vreg];
+  uint8_t *cur = (uint8_t *)calloc((size_t)Lt + 1, 1);
+  for (uint32_t b = 0; b < m->n_block; ++b) {
+    memcpy(cur, live_out + (size_t)b * Lt, Lt);
+    for (uint32_t i = m->blk_start[b + 1]; i-- > m->blk_start[b];) {
+      memcpy(live_after + (size_t)i * Lt, cur, Lt);
+      for (uint32_t o = m->instr_occ_off[i]; o < m->instr_occ_off[i + 1]; ++o)
+        if (m->occ_flags[o] & VLO_OCC_DEF)
+          for (uint32_t j = 0; j < m->vreg_width[m->occ_vreg[o]]; ++j)
+            if (touches(m, occ_lanes, o, j)) cur[base[m->occ_vreg[o]] + j] = 0;
+      for (uint32_t o = m->instr_occ_off[i]; o < m->instr_occ_off[i + 1]; ++o)
+        if (m->occ_flags[o] & VLO_OCC_USE)
+          for (uint32_t j = 0; j < m->vreg_width[m->occ_vreg[o]]; ++j)
+            if (touches(m, occ_lanes, o, j)) cur[base[m->occ_vreg[o]] + j] = 1;
+    }
+  }
+  free(cur);
+  free(base);
+}
+
+void vlo_occupancy_lanes(const vlo_mir *m, const uint32_t *occ_lanes, const uint8_t *live_after, uint8_t *P) {
+  uint32_t *base = (uint32_t *)malloc(((size_t)m->n_vreg + 1) * 4);
+  vlo_lane_base(m, base);
+  const uint32_t Lt = base[m->n_vreg];
+  memcpy(P, live_after, (size_t)m->n_instr * Lt);
+  for (uint32_t i = 0; i < m->n_instr; ++i) {
+    int early = 0;
+    for (uint32_t o = m->instr_occ_off[i]; o < m->instr_occ_off[i + 1]; ++o)
+      if (m->occ_flags[o] & VLO_OCC_EARLY) early = 1;
+    for (uint32_t o = m->instr_occ_off[i]; o < m->instr_occ_off[i + 1]; ++o)
+      if ((m->occ_flags[o] & VLO_OCC_DEF) || (early && (m->occ_flags[o] & VLO_OCC_USE)))
+        for (uint32_t j = 0; j < m->vreg_width[m->occ_vreg[o]]; ++j)
+          if (touches(m, occ_lanes, o, j)) P[(size_t)i * Lt + base[m->occ_vreg[o]] + j] = 1;
+  }
+  free(base);
+}
+
+void vlo_kill_lanes(const vlo_mir *m, const uint32_t *occ_lanes, const uint8_t *live_after, uint32_t *occ_kill) {
+  uint32_t *base = (uint32_t *)malloc(((size_t)m->n_vreg + 1) * 4);
+  vlo_lane_base(m, base);
+  const uint32_t Lt = base[m->n_vreg];
+  for (uint32_t i = 0; i < m->n_instr; ++i)
+    for (uint32_t o = m->instr_occ_off[i]; o < m->instr_occ_off[i + 1]; ++o) {
+      const uint32_t v = m->occ_vreg[o];
+      uint32_t killed = 0;
+      for (uint32_t j = 0; j < m->vreg_width[v]; ++j) {
+        if (!(m->occ_flags[o] & VLO_OCC_USE) || !touches(m, occ_lanes, o, j)) continue;
+        int written = 0;
+        for (uint32_t x = m->instr_occ_off[i]; x < m->instr_occ_off[i + 1]; ++x)
+          if ((m->occ_flags[x] & VLO_OCC_DEF) && m->occ_vreg[x] == v && touches(m, occ_lanes, x, j)) written = 1;
+        if (!written && !live_after[(size_t)i * Lt + base[v] + j]) killed |= 1u << j;
+      }
+      occ_kill[o] = killed;
+    }
+  free(base);
+}
+
+uint64_t vlo_segments_lanes(const vlo_mir *m, const uint8_t *P, uint32_t *seg_off, uint32_t *seg, uint64_t cap,
+                            uint32_t *hull) {
+  uint32_t *base = (uint32_t *)malloc(((size_t)m->n_vreg + 1) * 4);
+  vlo_lane_base(m, base);
+  const uint32_t Lt = base[m->n_vreg], N = m->n_instr;
+  free(base);
+  uint64_t n = 0;
+  /* lane by lane, the maximal runs of membership in order */
+  for (uint32_t x = 0; x < Lt; ++x) {
+    seg_off[x] = (uint32_t)n;
+    hull[2 * x] = hull[2 * x + 1] = 0;
+    int first = 1;
+    for (uint32_t i = 0; i < N; ++i) {
+      if (!P[(size_t)i * Lt + x] || (i && P[(size_t)(i - 1) * Lt + x])) continue;
+      uint32_t e = i;
+      while (e < N && P[(size_t)e * Lt + x]) ++e;
+      if (seg && n < cap) { seg[2 * n] = i; seg[2 * n + 1] = e; }
+      if (first) { hull[2 * x] = i; first = 0; }
+      hull[2 * x + 1] = e;
+      ++n;
+    }
+  }
+  seg_off[Lt] = (uint32_t)n;
+  return n;
+}
+
+void vlo_verify_lanes(const vlo_mir *m, const uint8_t *P, const uint16_t *c, vlo_result *out) {
+  const uint32_t V = m->n_vreg;
+  uint32_t *first = (uint32_t *)malloc(((size_t)V + 1) * 4);
+  uint32_t *base = (uint32_t *)malloc(((size_t)V + 1) * 4);
+  vlo_first_occurrence(m, first);
+  vlo_lane_base(m, base);
+  const uint32_t Lt = base[V];
+  vlo_result r = {VLO_OK, 0, 0, 0};
+  if (!check_table(m, first, c, &r)) {
+    /* Safety on the lanes in use: who claims each register of each file at i */
+    uint32_t *owner = (uint32_t *)malloc((size_t)m->n_class * 512 * 4);
+    for (uint32_t i = 0; i < m->n_instr && r.status == VLO_OK; ++i) {
+      for (uint32_t x = 0; x < m->n_class * 512; ++x) owner[x] = UINT32_MAX;
+      uint32_t ba = UINT32_MAX, bb = UINT32_MAX;
+      for (uint32_t v = 0; v < V; ++v)          /* ascending: the first claimant of a register is its smallest vreg */
+        for (uint32_t j = 0; j < m->vreg_width[v]; ++j) {
+          if (!P[(size_t)i * Lt + base[v] + j]) continue;
+          const uint32_t reg = (uint32_t)c[first[v]] + j;   /* in bounds: realizability holds */
+          uint32_t *w = &owner[m->vreg_class[v] * 512 + reg];
+          if (*w == UINT32_MAX) *w = v;
+          else if (*w != v && (*w < ba || (*w == ba && v < bb))) { ba = *w; bb = v; }
+        }
+      if (ba != UINT32_MAX) { r.status = VLO_SAFETY; r.where = i; r.a = ba; r.b = bb; }
+    }
+    free(owner);
+  }
+  *out = r;
+  free(first);
+  free(base);
+}

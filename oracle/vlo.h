@@ -185,6 +185,39 @@ void vlo_bank_conflicts(const vlo_mir *m, const uint16_t *cand, uint32_t K, uint
  * offered. */
 void vlo_free_bases(const vlo_mir *m, const uint32_t *P, const uint16_t *cand, uint32_t q, uint32_t out[16]);
 
+/* ---- liveness of parts of a tuple (sub-register liveness) -------------------------------
+ * Section 2: a wide value lives in consecutive 32-bit registers; the paper treats a vreg as
+ * one unit.  Reading taken for instructions that read or write only part of a tuple: lane j
+ * (0 <= j < width) of vreg v is the 32-bit register at base + j, and every occurrence carries
+ * a mask of the lanes it accesses (occ_lanes[o], bit j = lane j; NULL, or a mask of 0, means
+ * all lanes).  A DEF writes the lanes of its mask and leaves the others as they were; a USE
+ * reads the lanes of its mask.  Everything is then the textbook analysis per (vreg, lane):
+ *   lane liveness     backward may-analysis with use / def sets of (vreg, lane) pairs
+ *   P(i)              the lanes live after i or written at i (or read at i, when the
+ *                     instruction has an early-clobber definition)
+ *   Safety            at every i the registers base(v) + j of the lanes in P(i) are claimed by
+ *                     at most one vreg per class; the first violation is the smallest
+ *                     (i, a, b), a < b two vregs of one class that claim the same register at i
+ *   Consistency, Realizability   per vreg and whole tuple, as without lanes (the hardware
+ *                     rules speak of the tuple, whatever part of it is in use)
+ * Lane (v, j) has the index lane_base[v] + j, lane_base = exclusive prefix sums of the widths;
+ * Lt = lane_base[V] lanes in all.  With all masks full the lanes of a vreg behave alike and
+ * everything reduces to the functions above (which is one of the pins). */
+void vlo_lane_base(const vlo_mir *m, uint32_t *lane_base /* [V+1] */);
+/* live_in / live_out: [n_block][Lt] bytes.  Returns the number of sweeps. */
+int vlo_block_liveness_lanes(const vlo_mir *m, const uint32_t *occ_lanes, uint8_t *live_in, uint8_t *live_out);
+/* live_after, P: [n_instr][Lt] bytes */
+void vlo_points_lanes(const vlo_mir *m, const uint32_t *occ_lanes, const uint8_t *live_out, uint8_t *live_after);
+void vlo_occupancy_lanes(const vlo_mir *m, const uint32_t *occ_lanes, const uint8_t *live_after, uint8_t *P);
+/* occ_kill[o]: the lanes that the USE occurrence o reads for the last time: read at i,
+ * neither live after i nor written at i. */
+void vlo_kill_lanes(const vlo_mir *m, const uint32_t *occ_lanes, const uint8_t *live_after, uint32_t *occ_kill);
+/* maximal runs of {i : lane in P(i)} per lane, as vlo_segments per vreg */
+uint64_t vlo_segments_lanes(const vlo_mir *m, const uint8_t *P, uint32_t *seg_off /* [Lt+1] */, uint32_t *seg,
+                            uint64_t cap, uint32_t *hull /* [Lt][2] */);
+/* one candidate against P (bytes [n_instr][Lt]) */
+void vlo_verify_lanes(const vlo_mir *m, const uint8_t *P, const uint16_t *cand, vlo_result *out);
+
 #ifdef __cplusplus
 }
 #endif

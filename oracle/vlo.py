@@ -228,3 +228,68 @@ def bank_conflicts(m, cand: np.ndarray, n_banks: int = 4) -> np.ndarray:
     lib().vlo_bank_conflicts(C.byref(s), _p(cand), C.c_uint32(cand.shape[0]), C.c_uint64(cand.shape[1]),
                              C.c_uint32(n_banks), _p(out))
     return out
+
+
+# ---- liveness of parts of a tuple (sub-register liveness) ----
+
+@dataclass
+class LaneAnalysis:
+    """Per (vreg, lane); lane (v, j) has the index lane_base[v] + j."""
+    lane_base: np.ndarray    # uint32 [V+1]
+    live_in: np.ndarray      # uint8 [n_block, Lt]
+    live_out: np.ndarray     # uint8 [n_block, Lt]
+    live_after: np.ndarray   # uint8 [N, Lt]
+    P: np.ndarray            # uint8 [N, Lt]
+    occ_kill: np.ndarray     # uint32 [O]: lanes read for the last time
+    seg_off: np.ndarray      # uint32 [Lt+1]
+    seg: np.ndarray          # uint32 [S, 2]
+    hull: np.ndarray         # uint32 [Lt, 2]
+    sweeps: int
+
+
+def _lanes(m, occ_lanes):
+    if occ_lanes is None:
+        return None
+    a = np.ascontiguousarray(occ_lanes, np.uint32)
+    assert a.shape == (len(m.occ_vreg),)
+    return a
+
+
+def analyze_lanes(m, occ_lanes=None) -> LaneAnalysis:
+    """occ_lanes: uint32 [n_occ], bit j = the occurrence accesses lane j of its vreg; None
+    or 0 = all lanes."""
+    s, keep = _marshal(m)
+    L = lib()
+    L.vlo_block_liveness_lanes.restype = C.c_int
+    L.vlo_segments_lanes.restype = C.c_uint64
+    lanes = _lanes(m, occ_lanes)
+    N, V, B, O = s.n_instr, s.n_vreg, s.n_block, s.n_occ
+    base = np.zeros(V + 1, np.uint32)
+    L.vlo_lane_base(C.byref(s), _p(base))
+    Lt = int(base[V])
+    live_in = np.zeros((B, Lt), np.uint8)
+    live_out = np.zeros((B, Lt), np.uint8)
+    sweeps = L.vlo_block_liveness_lanes(C.byref(s), _p(lanes), _p(live_in), _p(live_out))
+    live_after = np.zeros((N, Lt), np.uint8)
+    L.vlo_points_lanes(C.byref(s), _p(lanes), _p(live_out), _p(live_after))
+    P = np.zeros((N, Lt), np.uint8)
+    L.vlo_occupancy_lanes(C.byref(s), _p(lanes), _p(live_after), _p(P))
+    kill = np.zeros(O, np.uint32)
+    L.vlo_kill_lanes(C.byref(s), _p(lanes), _p(live_after), _p(kill))
+    seg_off = np.zeros(Lt + 1, np.uint32)
+    hull = np.zeros((max(Lt, 1), 2), np.uint32)
+    n = L.vlo_segments_lanes(C.byref(s), _p(P), _p(seg_off), None, C.c_uint64(0), _p(hull))
+    seg = np.zeros((max(n, 1), 2), np.uint32)
+    L.vlo_segments_lanes(C.byref(s), _p(P), _p(seg_off), _p(seg), C.c_uint64(n), _p(hull))
+    return LaneAnalysis(base, live_in, live_out, live_after, P, kill, seg_off, seg[:n], hull[:Lt], sweeps)
+
+
+def verify_lanes(m, an: LaneAnalysis, cand: np.ndarray) -> np.ndarray:
+    """Consistency and realizability per vreg, safety on the lanes in use.  RESULT_DTYPE [K]."""
+    s, keep = _marshal(m)
+    cand = np.ascontiguousarray(np.atleast_2d(cand), np.uint16)
+    out = np.zeros(cand.shape[0], RESULT_DTYPE)
+    P = np.ascontiguousarray(an.P)
+    for k in range(cand.shape[0]):
+        lib().vlo_verify_lanes(C.byref(s), _p(P), _p(cand[k]), C.c_void_p(out[k:k + 1].ctypes.data))
+    return out

@@ -201,3 +201,82 @@ def verify_rows_by_marking(m, member, rows):
                 if a < b and cls[a] == cls[b] and base[a] < base[b] + width[b] and base[b] < base[a] + width[a]]
         out.append((3, i) + min(hits))
     return out
+
+
+# ---- with lane masks: every (vreg, lane) pair is a value of its own ----
+
+def lane_touch(m, occ_lanes, o, j):
+    return occ_lanes is None or int(occ_lanes[o]) == 0 or (int(occ_lanes[o]) >> j) & 1
+
+
+def uses_defs_lanes(m, occ_lanes):
+    """per instruction the sets of (vreg, lane) read and written"""
+    uses, defs = [], []
+    for i in range(m.n_instr):
+        u, d = set(), set()
+        for o in range(m.instr_occ_off[i], m.instr_occ_off[i + 1]):
+            v = int(m.occ_vreg[o])
+            for j in range(int(m.vreg_width[v])):
+                if not lane_touch(m, occ_lanes, o, j):
+                    continue
+                if m.occ_flags[o] & USE:
+                    u.add((v, j))
+                if m.occ_flags[o] & DEF:
+                    d.add((v, j))
+        uses.append(u)
+        defs.append(d)
+    return uses, defs
+
+
+def live_after_lanes_by_search(m, occ_lanes):
+    """(v, j) is live after i iff some path leaves i, reaches an instruction that reads lane j
+    of v, and no instruction strictly in between writes that lane."""
+    succ = instr_succ(m)
+    uses, defs = uses_defs_lanes(m, occ_lanes)
+    lanes = [(v, j) for v in range(m.n_vreg) for j in range(int(m.vreg_width[v]))]
+    res = []
+    for i in range(m.n_instr):
+        live = set()
+        for x in lanes:
+            seen, stack, hit = set(), list(succ[i]), False
+            while stack and not hit:
+                k = stack.pop()
+                if k in seen:
+                    continue
+                seen.add(k)
+                if x in uses[k]:
+                    hit = True
+                elif x not in defs[k]:
+                    stack.extend(succ[k])
+            if hit:
+                live.add(x)
+        res.append(live)
+    return res
+
+
+def occupancy_lanes(m, occ_lanes, live_after):
+    uses, defs = uses_defs_lanes(m, occ_lanes)
+    return [live_after[i] | defs[i] | (uses[i] if has_early_clobber(m, i) else set()) for i in range(m.n_instr)]
+
+
+def verify_lanes(m, P, row):
+    """(status, where, a, b): consistency and realizability per vreg as in verify(); safety by
+    enumerating, at every instruction, every pair of lanes of different vregs of one class."""
+    first = first_occ(m)
+    for o in range(m.n_occ):
+        v = int(m.occ_vreg[o])
+        if row[o] != row[first[v]]:
+            return (1, o, v, first[v])
+    bad = [(first[v], v, realizability_bits(m, v, int(row[first[v]]))) for v in first]
+    bad = [t for t in bad if t[2]]
+    if bad:
+        return (2,) + min(bad)
+    for i in range(m.n_instr):
+        hits = []
+        for (a, ja) in P[i]:
+            for (b, jb) in P[i]:
+                if a < b and m.vreg_class[a] == m.vreg_class[b] and int(row[first[a]]) + ja == int(row[first[b]]) + jb:
+                    hits.append((a, b))
+        if hits:
+            return (3, i) + min(hits)
+    return (0, 0, 0, 0)

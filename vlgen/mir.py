@@ -34,6 +34,8 @@ class Mir:
     class_size: np.ndarray     # uint16 [n_class]
     class_reserved: np.ndarray | None = None  # uint32 [n_class,16] or None
     name: str = ""
+    occ_lanes: np.ndarray | None = None       # uint32 [n_occ]: lanes of the vreg's tuple the occurrence accesses
+                                              # (bit j = lane j; 0 = all), or None: every occurrence accesses all
     meta: dict = field(default_factory=dict)
 
     def __post_init__(self):
@@ -50,6 +52,8 @@ class Mir:
         self.class_size = c(self.class_size, dtype=np.uint16)
         if self.class_reserved is not None:
             self.class_reserved = c(self.class_reserved, dtype=np.uint32).reshape(-1, 16)
+        if self.occ_lanes is not None:
+            self.occ_lanes = c(self.occ_lanes, dtype=np.uint32)
 
     @property
     def n_instr(self) -> int:

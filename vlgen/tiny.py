@@ -97,3 +97,21 @@ def tiny_rows(m: Mir, seed: int, K: int = 8) -> np.ndarray:
 
 
 __all__ = ["tiny_mir", "tiny_rows", "OCC_DEF", "OCC_USE"]
+
+
+def tiny_lanes(m: Mir, seed: int, share: float = 0.5, keep_first_block: bool = True) -> np.ndarray:
+    """Random lane masks for the occurrences of a program: with probability `share` an
+    occurrence of a vreg wider than one register accesses a random non-empty subset of its
+    lanes, otherwise all of them (mask 0).  With keep_first_block the entry block is left
+    alone, so that a program whose entry block writes every vreg whole stays strict."""
+    rng = np.random.default_rng([seed, 0x1A])
+    lanes = np.zeros(m.n_occ, np.uint32)
+    first_block_end = int(m.instr_occ_off[m.blk_start[1]]) if keep_first_block else 0
+    for o in range(first_block_end, m.n_occ):
+        w = int(m.vreg_width[m.occ_vreg[o]])
+        if w > 1 and rng.random() < share:
+            lanes[o] = int(rng.integers(1, 1 << w))
+    return lanes
+
+
+__all__ += ["tiny_lanes"]
