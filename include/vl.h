@@ -98,6 +98,44 @@ typedef void *vl_stream;        /* a hipStream_t (NULL = the default stream) */
 int32_t vl_mir_create(const vl_mir_desc *desc, vl_mir **out);
 void vl_mir_destroy(vl_mir *mir);
 
+/* Liveness of parts of a tuple.  The paper treats a vreg as one unit; Section 2 places a wide
+ * value in consecutive 32-bit registers.  Reading taken for instructions that read or write
+ * only part of a tuple: lane j (0 <= j < width) of a vreg is the register at base + j, and
+ * occ_lanes [host] [n_occ] names the lanes each occurrence accesses (bit j = lane j; 0, or a
+ * NULL array, = all of them; a bit at or above the width is VL_E_RANGE).  A DEF writes its
+ * lanes and leaves the others as they were, a USE reads its lanes; liveness, P(i) and the
+ * live intervals are the analysis per (vreg, lane), Safety is tested on the registers of the
+ * lanes in P(i), Consistency and Realizability stay per vreg and whole tuple.
+ *
+ * The handle holds a rewritten program: every vreg that is accessed in part somewhere is
+ * followed by one value per lane (one register wide, no alignment), vregs never accessed in
+ * part stay as they are; values are numbered vreg by vreg, a vreg before its lanes.  An
+ * occurrence of a split vreg becomes a mention of the whole vreg (it neither reads nor
+ * writes) followed by one occurrence per lane accessed (at most 64 occurrences per
+ * instruction afterwards, VL_E_RANGE otherwise).  vl_liveness and vl_live_get describe that
+ * program (vl_mir_lanes_get gives the maps back to the caller's numbering); vl_verify_batch /
+ * vl_verify_multi take candidate rows in its numbering, which vl_lanes_expand makes from the
+ * caller's rows, and report results in the caller's numbering: occurrences and vregs of the
+ * description given here, SAFETY with the smallest pair of the caller's vregs.
+ * vl_count_violations_multi, vl_free_bases_multi and vl_bank_conflicts do not take such a
+ * handle (VL_E_ARG). */
+int32_t vl_mir_create_lanes(const vl_mir_desc *desc, const uint32_t *occ_lanes, vl_mir **out);
+typedef struct {
+  uint32_t n_occ, n_vreg;          /* of the caller's description */
+  uint32_t n_occ_low, n_vreg_low;  /* of the rewritten program */
+  const uint32_t *occ_src;         /* [device] [n_occ_low] the caller's occurrence */
+  const uint8_t *occ_add;          /* [device] [n_occ_low] the lane: added to the caller's register */
+  const uint32_t *val_vreg;        /* [device] [n_vreg_low] the caller's vreg */
+  const uint8_t *val_lane;         /* [device] [n_vreg_low] the lane, 0xFF for a whole vreg */
+} vl_lanes_view;
+int32_t vl_mir_lanes_get(const vl_mir *mir, vl_lanes_view *out);
+/* cand_low[k][o'] = cand[k][occ_src[o']] + occ_add[o'] for K rows (16-bit arithmetic);
+ * cand [device] K rows of pitch ld >= n_occ, cand_low [device] K rows of pitch
+ * ld_low >= n_occ_low, caller-owned.  Asynchronous on `stream`.  Errors: VL_E_NULL, VL_E_ARG
+ * (not such a handle), VL_E_SHAPE (K == 0 or above 65535, a pitch too small). */
+int32_t vl_lanes_expand(const vl_mir *mir, const uint16_t *cand, uint32_t K, uint64_t ld, uint16_t *cand_low,
+                        uint64_t ld_low, vl_stream stream);
+
 /* Liveness analysis of n kernels in one batch of launches (Section 3.2: the
  * control flow and data dependency of the input; Section 3.4 Safety: which
  * lifetimes overlap).  Enqueues on `stream`, synchronises it once to read the

@@ -42,6 +42,11 @@ class _View(C.Structure):
                 ("live_in", "live_out", "live_after", "occ_kill", "seg_off", "seg", "hull")]
 
 
+class _LanesView(C.Structure):
+    _fields_ = [(n, C.c_uint32) for n in ("n_occ", "n_vreg", "n_occ_low", "n_vreg_low")] + \
+               [(n, C.c_void_p) for n in ("occ_src", "occ_add", "val_vreg", "val_lane")]
+
+
 class _CountJob(C.Structure):
     _fields_ = [("mir", C.c_void_p), ("live", C.c_void_p), ("cand", C.c_void_p), ("K", C.c_uint32),
                 ("ld", C.c_uint64), ("out", C.c_void_p)]
@@ -73,6 +78,12 @@ def load():
         L = C.CDLL(LIB_PATH)
         L.vl_mir_create.restype = C.c_int32
         L.vl_mir_create.argtypes = [C.c_void_p, C.POINTER(C.c_void_p)]
+        L.vl_mir_create_lanes.restype = C.c_int32
+        L.vl_mir_create_lanes.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p)]
+        L.vl_mir_lanes_get.restype = C.c_int32
+        L.vl_mir_lanes_get.argtypes = [C.c_void_p, C.c_void_p]
+        L.vl_lanes_expand.restype = C.c_int32
+        L.vl_lanes_expand.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint64, C.c_void_p, C.c_uint64, C.c_void_p]
         L.vl_mir_destroy.restype = None
         L.vl_mir_destroy.argtypes = [C.c_void_p]
         L.vl_liveness_multi.restype = C.c_int32
@@ -158,6 +169,47 @@ def vl_mir_create(m) -> C.c_void_p:
     if rc != 0:
         raise VlError(rc, "vl_mir_create")
     return out
+
+
+def vl_mir_create_lanes(m, occ_lanes=None) -> C.c_void_p:
+    """occ_lanes: uint32 [n_occ] (bit j = lane j, 0 = all) or None; defaults to m.occ_lanes."""
+    d, keep = m if isinstance(m, tuple) else make_desc(m)
+    if occ_lanes is None and not isinstance(m, tuple):
+        occ_lanes = getattr(m, "occ_lanes", None)
+    lanes = None if occ_lanes is None else np.ascontiguousarray(occ_lanes, np.uint32)
+    out = C.c_void_p()
+    rc = load().vl_mir_create_lanes(C.byref(d), _p(lanes), C.byref(out))
+    if rc != 0:
+        raise VlError(rc, "vl_mir_create_lanes")
+    return out
+
+
+def vl_mir_lanes_get(mir) -> dict:
+    """The maps of a handle made by vl_mir_create_lanes, copied to numpy (synchronises)."""
+    v = _LanesView()
+    rc = load().vl_mir_lanes_get(mir, C.byref(v))
+    if rc != 0:
+        raise VlError(rc, "vl_mir_lanes_get")
+    import torch
+    torch.cuda.synchronize()
+    hip = hip_runtime()
+
+    def grab(ptr, n, dtype):
+        a = np.zeros(n, dtype)
+        if ptr and a.nbytes:
+            assert hip.hipMemcpy(_p(a), C.c_void_p(ptr), a.nbytes, 2) == 0
+        return a
+    return dict(n_occ=v.n_occ, n_vreg=v.n_vreg, n_occ_low=v.n_occ_low, n_vreg_low=v.n_vreg_low,
+                occ_src=grab(v.occ_src, v.n_occ_low, np.uint32), occ_add=grab(v.occ_add, v.n_occ_low, np.uint8),
+                val_vreg=grab(v.val_vreg, v.n_vreg_low, np.uint32), val_lane=grab(v.val_lane, v.n_vreg_low, np.uint8))
+
+
+def vl_lanes_expand(mir, cand, K: int, ld: int, cand_low, ld_low: int, stream=None) -> None:
+    """cand, cand_low: device pointers or tensors of uint16 rows."""
+    rc = load().vl_lanes_expand(mir, C.c_void_p(_dev_ptr(cand)), K, ld, C.c_void_p(_dev_ptr(cand_low)), ld_low,
+                                _stream_ptr(stream))
+    if rc != 0:
+        raise VlError(rc, "vl_lanes_expand")
 
 
 def vl_mir_destroy(mir) -> None:

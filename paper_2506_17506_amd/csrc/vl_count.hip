@@ -405,7 +405,7 @@ extern "C" int32_t vl_count_violations_multi(const vl_count_job *jobs, uint32_t 
   for (uint32_t j = 0; j < n_jobs; ++j) {
     const vl_count_job &u = jobs[j];
     if (!u.mir || !u.live || !u.cand || !u.out) return VL_E_NULL;
-    if (u.mir->magic != kMirMagic || u.live->magic != kLiveMagic || u.live->mir != u.mir) return VL_E_ARG;
+    if (u.mir->magic != kMirMagic || u.live->magic != kLiveMagic || u.live->mir != u.mir || u.mir->lowered) return VL_E_ARG;
     if (u.K == 0 || u.K > 65535 || u.ld < u.mir->h.O) return VL_E_SHAPE;
   }
   hipStream_t stream = (hipStream_t)stream_;

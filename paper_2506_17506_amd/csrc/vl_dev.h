@@ -39,6 +39,10 @@ struct DevMir {
   const uint64_t VL_GLOBAL *occ_rec;         // [O] vreg | (instruction << 2 | DEF/USE flags) << 32: one read instead of three
   const uint8_t VL_GLOBAL *instr_keep;       // [N] 1 iff the instruction has an early-clobber definition: what it reads
                                              // stays occupied through it
+  // a program made by vl_mir_create_lanes (every lane of a partly accessed vreg a value of its own): for
+  // each of its occurrences the caller's occurrence, for each of its values the caller's vreg; else null
+  const uint32_t VL_GLOBAL *occ_src;         // [O]
+  const uint32_t VL_GLOBAL *val_vreg;        // [V]
   uint32_t has_reserved;
   uint16_t class_size[kMaxClass];
   uint16_t class_word[kMaxClass];  // first occupancy word of the class
@@ -240,6 +244,13 @@ struct vl_mir {
   uint64_t n_edges = 0;
   bool edges_built = false;
   vl::EdgeBlock *edge_block = nullptr;   // the allocation the pairs sit in, shared with the other programs of that call
+  // vl_mir_create_lanes: the caller's sizes and the device maps between the two numberings
+  bool lowered = false;
+  uint32_t src_occ = 0, src_vreg = 0;
+  const uint32_t *occ_src = nullptr;    // [O] device
+  const uint8_t *occ_add = nullptr;     // [O] device: the lane, i.e. what is added to the caller's register
+  const uint32_t *val_vreg = nullptr;   // [V] device
+  const uint8_t *val_lane = nullptr;    // [V] device: lane, or 0xFF for a whole vreg
 };
 
 struct vl_batch;

@@ -79,7 +79,7 @@ extern "C" int32_t vl_free_bases_multi(const vl_mask_query *queries, uint32_t n,
   for (uint32_t j = 0; j < n; ++j) {
     const vl_mask_query &u = queries[j];
     if (!u.mir || !u.live || !u.cand) return VL_E_NULL;
-    if (u.mir->magic != kMirMagic || u.live->magic != kLiveMagic || u.live->mir != u.mir || u.reserved0 != 0) return VL_E_ARG;
+    if (u.mir->magic != kMirMagic || u.live->magic != kLiveMagic || u.live->mir != u.mir || u.reserved0 != 0 || u.mir->lowered) return VL_E_ARG;
     if (u.occ >= u.mir->h.O) return VL_E_SHAPE;
     max_w = std::max(max_w, u.mir->h.W);
   }

@@ -32,7 +32,8 @@ extern "C" const char *vl_strerror(int32_t code) {
   return "unknown error code";
 }
 
-static int32_t validate(const vl_mir_desc *d) {
+// mentions: occurrences that neither read nor write are allowed (programs made by vl_mir_create_lanes)
+static int32_t validate(const vl_mir_desc *d, bool mentions) {
   if (!d->blk_start || !d->succ_off || !d->instr_occ_off || !d->class_size) return VL_E_NULL;
   if (d->n_edge && !d->succ) return VL_E_NULL;
   if (d->n_occ && (!d->occ_vreg || !d->occ_flags)) return VL_E_NULL;
@@ -58,7 +59,7 @@ static int32_t validate(const vl_mir_desc *d) {
   for (uint32_t o = 0; o < d->n_occ; ++o) {
     if (d->occ_vreg[o] >= d->n_vreg) return VL_E_RANGE;
     const uint8_t f = d->occ_flags[o];
-    if ((f & (VL_OCC_DEF | VL_OCC_USE)) == 0 || (f & ~(VL_OCC_DEF | VL_OCC_USE | VL_OCC_EARLY))) return VL_E_RANGE;
+    if (((f & (VL_OCC_DEF | VL_OCC_USE)) == 0 && !mentions) || (f & ~(VL_OCC_DEF | VL_OCC_USE | VL_OCC_EARLY))) return VL_E_RANGE;
     if ((f & VL_OCC_EARLY) && !(f & VL_OCC_DEF)) return VL_E_RANGE;
   }
   for (uint32_t v = 0; v < d->n_vreg; ++v) {
@@ -87,9 +88,19 @@ struct Bump {
 };
 }  // namespace
 
-extern "C" int32_t vl_mir_create(const vl_mir_desc *d, vl_mir **out) {
+namespace {
+// the maps of a program made by vl_mir_create_lanes (host arrays), or null
+struct LaneMaps {
+  const uint32_t *occ_src;
+  const uint8_t *occ_add;
+  const uint32_t *val_vreg;
+  const uint8_t *val_lane;
+  uint32_t src_occ, src_vreg;
+};
+
+int32_t create_impl(const vl_mir_desc *d, const LaneMaps *maps, vl_mir **out) {
   if (!d || !out) return VL_E_NULL;
-  int32_t rc = validate(d);
+  int32_t rc = validate(d, maps != nullptr);
   if (rc != VL_OK) return rc;
   const uint32_t N = d->n_instr, V = d->n_vreg, B = d->n_block, O = d->n_occ, E = d->n_edge;
   // derived index arrays (plain expansions of the CSR offsets) and packed attributes
@@ -138,6 +149,11 @@ extern "C" int32_t vl_mir_create(const vl_mir_desc *d, vl_mir **out) {
   size_t o_va = bump.take((size_t)(V ? V : 1) * 4), o_of = bump.take((size_t)(O ? O : 1));
   size_t o_rec = bump.take((size_t)(O ? O : 1) * 8);
   size_t o_keep = bump.take((size_t)N);
+  size_t o_src = 0, o_add = 0, o_vv = 0, o_vl = 0;
+  if (maps) {
+    o_src = bump.take((size_t)(O ? O : 1) * 4); o_add = bump.take((size_t)(O ? O : 1));
+    o_vv = bump.take((size_t)(V ? V : 1) * 4); o_vl = bump.take((size_t)(V ? V : 1));
+  }
   size_t o_dev = bump.take(sizeof(vl::DevMir));
 
   vl_mir *m = new (std::nothrow) vl_mir;
@@ -165,6 +181,10 @@ extern "C" int32_t vl_mir_create(const vl_mir_desc *d, vl_mir **out) {
   up(o_of, d->occ_flags, (size_t)O);
   up(o_rec, occ_rec.data(), (size_t)O * 8);
   up(o_keep, instr_keep.data(), (size_t)N);
+  if (maps) {
+    up(o_src, maps->occ_src, (size_t)O * 4); up(o_add, maps->occ_add, (size_t)O);
+    up(o_vv, maps->val_vreg, (size_t)V * 4); up(o_vl, maps->val_lane, (size_t)V);
+  }
 
   vl::DevMir &h = m->h;
   h.N = N; h.V = V; h.B = B; h.O = O; h.C = d->n_class; h.E = E; h.W = (V + 31) / 32;
@@ -179,6 +199,14 @@ extern "C" int32_t vl_mir_create(const vl_mir_desc *d, vl_mir **out) {
   h.occ_flags = (const uint8_t VL_GLOBAL *)(base + o_of);
   h.occ_rec = (const uint64_t VL_GLOBAL *)(base + o_rec);
   h.instr_keep = (const uint8_t VL_GLOBAL *)(base + o_keep);
+  if (maps) {
+    h.occ_src = (const uint32_t VL_GLOBAL *)(base + o_src);
+    h.val_vreg = (const uint32_t VL_GLOBAL *)(base + o_vv);
+    m->lowered = true;
+    m->src_occ = maps->src_occ; m->src_vreg = maps->src_vreg;
+    m->occ_src = (const uint32_t *)(base + o_src); m->occ_add = (const uint8_t *)(base + o_add);
+    m->val_vreg = (const uint32_t *)(base + o_vv); m->val_lane = (const uint8_t *)(base + o_vl);
+  }
   m->dev = (vl::DevMir *)(base + o_dev);
   up(o_dev, &h, sizeof(h));
   e = hipMemcpy(base, image.data(), bump.off, hipMemcpyHostToDevice);
@@ -188,6 +216,99 @@ extern "C" int32_t vl_mir_create(const vl_mir_desc *d, vl_mir **out) {
     return vl::hip_fail(e);
   }
   *out = m;
+  return VL_OK;
+}
+}  // namespace
+
+extern "C" int32_t vl_mir_create(const vl_mir_desc *d, vl_mir **out) { return create_impl(d, nullptr, out); }
+
+// Lane masks: the program is rewritten on the host so that every lane of a vreg that is
+// accessed in part somewhere is a value of its own (one register wide), and everything
+// else in the library runs on the rewritten program as it stands.  An occurrence of such a
+// vreg becomes a mention of the whole vreg, which neither reads nor writes but carries the
+// register (consistency and realizability stay per vreg and whole tuple), followed by one
+// occurrence per lane it accesses, whose register is the vreg's plus the lane.  Values are
+// numbered vreg by vreg, the whole vreg before its lanes.
+extern "C" int32_t vl_mir_create_lanes(const vl_mir_desc *d, const uint32_t *occ_lanes, vl_mir **out) {
+  if (!d || !out) return VL_E_NULL;
+  int32_t rc = validate(d, false);
+  if (rc != VL_OK) return rc;
+  const uint32_t N = d->n_instr, V = d->n_vreg, O = d->n_occ;
+  std::vector<uint8_t> split(V ? V : 1, 0);
+  for (uint32_t o = 0; o < O && occ_lanes; ++o) {
+    const uint32_t v = d->occ_vreg[o], w = d->vreg_width[v];
+    const uint32_t full = w == 32 ? 0xFFFFFFFFu : ((1u << w) - 1u);
+    if (occ_lanes[o] & ~full) return VL_E_RANGE;   // a lane the vreg does not have
+    if (occ_lanes[o] != 0 && occ_lanes[o] != full) split[v] = 1;
+  }
+  std::vector<uint32_t> id(V + 1), val_vreg;
+  std::vector<uint8_t> val_lane, vclass, vwidth, valign;
+  for (uint32_t v = 0; v < V; ++v) {
+    id[v] = (uint32_t)val_vreg.size();
+    val_vreg.push_back(v); val_lane.push_back(0xFF);
+    vclass.push_back(d->vreg_class[v]); vwidth.push_back(d->vreg_width[v]); valign.push_back(d->vreg_align[v]);
+    if (split[v])
+      for (uint32_t j = 0; j < d->vreg_width[v]; ++j) {
+        val_vreg.push_back(v); val_lane.push_back((uint8_t)j);
+        vclass.push_back(d->vreg_class[v]); vwidth.push_back(1); valign.push_back(1);
+      }
+  }
+  std::vector<uint32_t> off(N + 1, 0), occ_v, occ_src;
+  std::vector<uint8_t> occ_f, occ_add;
+  for (uint32_t i = 0; i < N; ++i) {
+    for (uint32_t o = d->instr_occ_off[i]; o < d->instr_occ_off[i + 1]; ++o) {
+      const uint32_t v = d->occ_vreg[o], w = d->vreg_width[v];
+      if (!split[v]) {
+        occ_v.push_back(id[v]); occ_f.push_back(d->occ_flags[o]); occ_src.push_back(o); occ_add.push_back(0);
+        continue;
+      }
+      occ_v.push_back(id[v]); occ_f.push_back(0); occ_src.push_back(o); occ_add.push_back(0);
+      const uint32_t lanes = (occ_lanes && occ_lanes[o]) ? occ_lanes[o] : (w == 32 ? 0xFFFFFFFFu : ((1u << w) - 1u));
+      for (uint32_t j = 0; j < w; ++j)
+        if ((lanes >> j) & 1u) {
+          occ_v.push_back(id[v] + 1 + j); occ_f.push_back(d->occ_flags[o]); occ_src.push_back(o); occ_add.push_back((uint8_t)j);
+        }
+    }
+    off[i + 1] = (uint32_t)occ_v.size();
+    if (off[i + 1] - off[i] > vl::kMaxOperands) return VL_E_RANGE;   // too many operands once the lanes are spelt out
+  }
+  if (val_vreg.size() > VL_MAX_VREG || occ_v.size() >= (1u << 24)) return VL_E_RANGE;
+  vl_mir_desc low = *d;
+  low.n_vreg = (uint32_t)val_vreg.size();
+  low.n_occ = (uint32_t)occ_v.size();
+  low.instr_occ_off = off.data();
+  low.occ_vreg = occ_v.data(); low.occ_flags = occ_f.data();
+  low.vreg_class = vclass.data(); low.vreg_width = vwidth.data(); low.vreg_align = valign.data();
+  const LaneMaps maps = {occ_src.data(), occ_add.data(), val_vreg.data(), val_lane.data(), O, V};
+  return create_impl(&low, &maps, out);
+}
+
+extern "C" int32_t vl_mir_lanes_get(const vl_mir *m, vl_lanes_view *v) {
+  if (!m || !v) return VL_E_NULL;
+  if (m->magic != vl::kMirMagic || !m->lowered) return VL_E_ARG;
+  v->n_occ = m->src_occ; v->n_vreg = m->src_vreg; v->n_occ_low = m->h.O; v->n_vreg_low = m->h.V;
+  v->occ_src = m->occ_src; v->occ_add = m->occ_add; v->val_vreg = m->val_vreg; v->val_lane = m->val_lane;
+  return VL_OK;
+}
+
+namespace {
+__global__ __launch_bounds__(256) void k_lanes_expand(const uint16_t *__restrict__ cand, uint64_t ld, uint16_t *__restrict__ low,
+                                                      uint64_t ld_low, const uint32_t *__restrict__ occ_src,
+                                                      const uint8_t *__restrict__ occ_add, uint32_t n_low) {
+  const uint32_t o = blockIdx.x * blockDim.x + threadIdx.x, k = blockIdx.y;
+  if (o < n_low) low[(uint64_t)k * ld_low + o] = (uint16_t)(cand[(uint64_t)k * ld + occ_src[o]] + occ_add[o]);
+}
+}  // namespace
+
+extern "C" int32_t vl_lanes_expand(const vl_mir *m, const uint16_t *cand, uint32_t K, uint64_t ld, uint16_t *cand_low,
+                                   uint64_t ld_low, vl_stream stream) {
+  if (!m || !cand || !cand_low) return VL_E_NULL;
+  if (m->magic != vl::kMirMagic || !m->lowered) return VL_E_ARG;
+  if (K == 0 || K > 65535 || ld < m->src_occ || ld_low < m->h.O) return VL_E_SHAPE;
+  if (m->h.O == 0) return VL_OK;
+  k_lanes_expand<<<dim3((m->h.O + 255) / 256, K), 256, 0, (hipStream_t)stream>>>(cand, ld, cand_low, ld_low, m->occ_src, m->occ_add,
+                                                                                   m->h.O);
+  VL_HIP(hipGetLastError());
   return VL_OK;
 }
 

@@ -54,7 +54,7 @@ __global__ void k_score_clear(uint32_t *out, uint32_t K) {
 extern "C" int32_t vl_bank_conflicts(const vl_mir *mir, const uint16_t *cand, uint32_t K, uint64_t ld, uint32_t n_banks,
                                      uint32_t *out, vl_stream stream_) {
   if (!mir || !cand || !out) return VL_E_NULL;
-  if (mir->magic != kMirMagic) return VL_E_ARG;
+  if (mir->magic != kMirMagic || mir->lowered) return VL_E_ARG;
   if (K == 0 || K > 65535 || ld < mir->h.O) return VL_E_SHAPE;
   if (n_banks == 0 || n_banks > 64) return VL_E_RANGE;
   hipStream_t stream = (hipStream_t)stream_;

@@ -663,11 +663,13 @@ __global__ void k_finalize(const DevJob *__restrict__ jobs, uint2 *__restrict__ 
       case 0: {
         const uint32_t v = m.occ_vreg[pos];
         r = {VL_STATUS_CONSISTENCY, pos, v, L.first[v]};
+        if (m.occ_src) r = {VL_STATUS_CONSISTENCY, m.occ_src[pos], m.val_vreg[v], m.occ_src[L.first[v]]};   // in the caller's numbering
         break;
       }
       case 1: {
         const uint32_t v = m.occ_vreg[pos];
         r = {VL_STATUS_REALIZABILITY, pos, v, bad_bits(m, m.vattr[v], cand_at(J, k, pos))};
+        if (m.occ_src) { r.where = m.occ_src[pos]; r.a = m.val_vreg[v]; }
         break;
       }
       default: r = {VL_STATUS_SAFETY, pos, kNone, kNone}; break;
@@ -740,7 +742,9 @@ __global__ __launch_bounds__(256) void k_resolve(const DevJob *__restrict__ jobs
         if (attr_class(ad) != attr_class(ax)) continue;
         const uint32_t pd = dp[t], wd = attr_width(ad);
         if (pd < px + wx && px < pd + wd) {
-          const unsigned long long pr = ((unsigned long long)min(d, x) << 32) | max(d, x);
+          // (a program with lanes as values reports the caller's vregs: the smallest pair of those)
+          const uint32_t da = m.val_vreg ? m.val_vreg[d] : d, xa = m.val_vreg ? m.val_vreg[x] : x;
+          const unsigned long long pr = ((unsigned long long)min(da, xa) << 32) | max(da, xa);
           mine = pr < mine ? pr : mine;
         }
       }

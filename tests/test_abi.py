@@ -76,10 +76,37 @@ def test_validation_rejects_malformed_programs_before_touching_the_device():
     assert create_code(ok_mir()) in (0, -6)
 
 
+def test_lane_masks_are_validated_before_touching_the_device():
+    lib = vl.load()
+
+    def code(m, lanes):
+        d, keep = binding.make_desc(m)
+        out = C.c_void_p()
+        a = np.ascontiguousarray(lanes, np.uint32)
+        rc = lib.vl_mir_create_lanes(C.byref(d), a.ctypes.data_as(C.c_void_p), C.byref(out))
+        if rc == 0:
+            lib.vl_mir_destroy(out)
+        return rc
+    m = Mir.build([[((0,), ()), ((1,), (0,))], [((), (1,))]], [[1], []], 2, [8], vreg_width=[2, 1], vreg_align=[2, 1])
+    assert code(m, [0, 0, 1, 0]) in (0, -6)          # lane 0 of the two-register vreg: fine (no GPU: the copy fails)
+    assert code(m, [0, 0, 4, 0]) == -3               # lane 2 of a vreg of width 2
+    assert code(m, [0, 2, 0, 0]) == -3               # lane 1 of a vreg of width 1
+    # five operands of width 16, one of them accessed in part: 5 x 17 occurrences after rewriting
+    wide = Mir.build([[((0, 1, 2, 3, 4), ()), ((), (0, 1, 2, 3, 4))]], [[]], 5, [512], vreg_width=[16] * 5, vreg_align=[16] * 5)
+    lanes = np.zeros(10, np.uint32)
+    assert code(wide, lanes) in (0, -6)
+    for o in range(5, 10):
+        lanes[o] = 1
+    assert code(wide, lanes) == -3
+
+
 def test_null_arguments():
     lib = vl.load()
     assert lib.vl_mir_create(None, None) == -1
     assert lib.vl_verify_multi(None, 1, None) == -1
+    assert lib.vl_mir_create_lanes(None, None, None) == -1
+    assert lib.vl_mir_lanes_get(None, None) == -1
+    assert lib.vl_lanes_expand(None, None, 1, 1, None, 1, None) == -1
     assert lib.vl_verify_batch_static(None, None, None, 1, 1, None, None) in (-1, -6)
     assert lib.vl_verify_batch_static(None, None, None, 65537, 1, None, None) == -8
     assert lib.vl_verify_multi_occ_major(None, 1, None) == -1
