@@ -330,9 +330,7 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(6)
     return r;
   };
   // Replays a batch of up to 64 records held one per lane (lanes past the batch hold zero
-  // records, which flip nothing).  Four events at a time, two groups in flight: the mask
-  // updates of a group are issued back to back (LDS executes them in order), and before their
-  // old bits are awaited the records and registers of the next group are already requested.
+  // records, which flip nothing).
   constexpr int G = 8;
   auto replay = [&](const u32x4 r, uint32_t cnt) __attribute__((always_inline)) {
     if (__any((r.w & kEvtSlow) != 0)) {
@@ -372,7 +370,11 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(6)
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
-    constexpr int H = 4;   // events per group; two groups in flight
+    // Eight events per turn of the loop: their records, their registers, their mask updates
+    // and their tests are each issued back to back.  (What bounds this wavefront is the number
+    // of instructions it has to issue, not the LDS round trips: keeping a second group in
+    // flight, or a four-stage software pipeline over groups of four, made it no faster.)
+    constexpr int H = 8;
     struct Ev { uint32_t y, zb, t, p; };
     auto fetch_group = [&](uint32_t g0, Ev (&e)[H]) __attribute__((always_inline)) {
 #pragma unroll
@@ -400,18 +402,12 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(6)
         for (int t = 0; t < H; ++t) clash(hit[t], __builtin_amdgcn_readlane(r.w, g0 + t) & 0xFFFFFFu);
       }
     };
-    Ev ea_[H], eb_[H];
-    uint32_t ha[H], hb[H];
-    fetch_group(0, ea_);
-    for (uint32_t g0 = 0; g0 < cnt; g0 += 2 * H) {
-      apply_group(g0, ea_, ha);
-      if (g0 + H < cnt) fetch_group(g0 + H, eb_);
-      settle(g0, ha);
-      if (g0 + H < cnt) {
-        apply_group(g0 + H, eb_, hb);
-        if (g0 + 2 * H < cnt) fetch_group(g0 + 2 * H, ea_);
-        settle(g0 + H, hb);
-      }
+    for (uint32_t g0 = 0; g0 < cnt; g0 += H) {
+      Ev e_[H];
+      uint32_t h_[H];
+      fetch_group(g0, e_);
+      apply_group(g0, e_, h_);
+      settle(g0, h_);
     }
     __builtin_amdgcn_wave_barrier();   // the buffer is rewritten by the next batch
   };
