@@ -33,7 +33,8 @@ __device__ inline bool lists_meet(const uint32_t VL_GLOBAL *seg, uint32_t a0, ui
 }
 
 // One wavefront per vreg a, its lanes striding over b > a; blockIdx.y = program.  kFill = false:
-// cnt[a] = number of partners; kFill = true: the pairs are written from off[a] on, in ascending b.
+// cnt[a] = number of partners; kFill = true: the pairs are written from off[a] on, in ascending b,
+// each vreg with its width in the upper byte (vreg numbers stay below 2^24: VL_MAX_VREG).
 // Vregs are taken 64 at a time, and a group whose hulls taken together ([earliest start, latest
 // end), from k_hull_groups) miss a's hull is passed over: vregs are mostly numbered in the
 // order they are first written, so most groups lie entirely before or after a.
@@ -42,7 +43,7 @@ struct PairJob {
   const DevLive *live;
   uint32_t *cnt;         // [V]
   const uint64_t *off;   // [V]
-  uint32_t *pairs;       // [n_pairs][2]
+  uint32_t *pairs;       // [n_pairs rounded up to 32][2]: vreg | width << 24
   uint2 *groups;         // [(V + 63) / 64] (earliest start, latest end) of the group's non-empty hulls
 };
 
@@ -98,7 +99,7 @@ __global__ __launch_bounds__(256) void k_pairs(const PairJob *__restrict__ jobs)
   const uint32_t lane = threadIdx.x & 63u, a = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (a >= m.V) return;   // whole wavefronts leave; nothing below synchronises the workgroup
   const uint32_t h0 = L.hull[2 * (size_t)a], h1 = L.hull[2 * (size_t)a + 1];
-  const uint32_t s0 = L.seg_off[a], s1 = L.seg_off[a + 1], cls = attr_class(m.vattr[a]);
+  const uint32_t s0 = L.seg_off[a], s1 = L.seg_off[a + 1], cls = attr_class(m.vattr[a]), width_a = attr_width(m.vattr[a]);
   uint64_t at = kFill ? J.off[a] : 0;
   uint32_t n = 0;
   const uint32_t n_groups = (m.V + 63u) / 64u;
@@ -110,14 +111,15 @@ __global__ __launch_bounds__(256) void k_pairs(const PairJob *__restrict__ jobs)
       const uint32_t b = (g0 + (uint32_t)__builtin_ctzll(todo)) * 64 + lane;
       todo &= todo - 1;
       bool hit = false;
-      if (b > a && b < m.V && attr_class(m.vattr[b]) == cls && L.hull[2 * (size_t)b] < h1 && h0 < L.hull[2 * (size_t)b + 1])
+      const uint32_t attr_b = b > a && b < m.V ? m.vattr[b] : 0u;
+      if (b > a && b < m.V && attr_class(attr_b) == cls && L.hull[2 * (size_t)b] < h1 && h0 < L.hull[2 * (size_t)b + 1])
         hit = lists_meet(L.seg, s0, s1, L.seg_off[b], L.seg_off[b + 1]);
       const uint64_t hits = __ballot(hit);
       if (kFill) {
         if (hit) {
           const uint64_t pos = at + __popcll(hits & ((1ull << lane) - 1ull));
-          J.pairs[2 * pos] = a;
-          J.pairs[2 * pos + 1] = b;
+          J.pairs[2 * pos] = a | (width_a << 24);
+          J.pairs[2 * pos + 1] = b | (attr_width(attr_b) << 24);
         }
         at += __popcll(hits);
       } else {
@@ -126,6 +128,13 @@ __global__ __launch_bounds__(256) void k_pairs(const PairJob *__restrict__ jobs)
     }
   }
   if (!kFill && lane == 0) J.cnt[a] = n;
+  // the list ends with pairs of the last vreg with itself, widths 0 (they overlap nothing and
+  // keep a ascending), up to the next multiple of 32 pairs, so that it can be read in pieces
+  // without a tail
+  if (kFill && a == m.V - 1 && (at & 31u) && lane < 32u - (uint32_t)(at & 31u)) {
+    J.pairs[2 * (at + lane)] = a;
+    J.pairs[2 * (at + lane) + 1] = a;
+  }
 }
 
 // ---- per call ----------------------------------------------------------------------------
@@ -135,9 +144,9 @@ struct DevCountJob {
   const uint16_t *cand;
   vl_counts *out;
   uint16_t *table;         // [V][k_pad] registers of the first occurrences
-  const uint32_t *pairs;   // [n_pairs][2]
+  const uint32_t *pairs;   // [n_pairs rounded up to 32][2]: vreg | width << 24, the padding of width 0
   uint64_t ld, n_pairs;
-  uint32_t K, k_pad, pad0, pad1;
+  uint32_t K, k_pad, V, pad1;
 };
 
 __global__ void k_cnt_clear(const DevCountJob *__restrict__ jobs) {
@@ -241,49 +250,108 @@ __global__ __launch_bounds__(256) void k_cnt_real(const DevCountJob *__restrict_
   }
 }
 
-// safety: a wavefront takes 1024 of the pairs, fetched 64 at a time (one pair per lane, read
-// out of the lanes), and walks them once for every group of 128 candidates: a lane holds two
-// neighbouring candidates, whose registers are one 32-bit word of a table row
-constexpr uint32_t kPairsPerWave = 1024, kPairsPerGroup = 4 * kPairsPerWave;
+// safety: the wavefronts of a program take its pairs in stretches of 256 and walk each once
+// for every group of 128 candidates: a lane holds two neighbouring candidates, whose registers
+// are one 32-bit word of a table row.  Both are tested at once with saturating 16-bit
+// arithmetic, exact for any 16-bit register number: with u = max(pa - pb, 0) and
+// v = max(pb - pa, 0), the tuples overlap iff u < width(b) and v < width(a).  What bounds the
+// kernel is the number of instructions a pair takes, of any kind: seven vector ones for the
+// test; the pairs (with the widths in their upper bytes) arrive through scalar loads, sixteen
+// pairs at a time and the next sixteen fetched ahead, and a table row is addressed by a scalar
+// offset plus the lane's own.  The pairs are stored in ascending (a, b), so the sixteen mostly
+// share a, whose row is then read once.
+// A program has at most 1024 workgroups, whose wavefronts take its stretches in turn.  (Running
+// all workgroups of a program on one of the eight dies, so that its table stays in one L2, cut
+// the memory traffic by ten and made the kernel slower: the dies were then unevenly loaded.)
+constexpr uint32_t kPairsPerWave = 256, kPairsPerGroup = 4 * kPairsPerWave, kSafeGroupsPerProgram = 1024;
+constexpr uint32_t kPairsAtOnce = 16;   // the pair list of a program is padded with empty pairs to a multiple of this
+typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
+#define VL_CONSTANT __attribute__((address_space(4)))
+__device__ inline u16x2 both(uint32_t x) { return __builtin_bit_cast(u16x2, x); }
+template <bool kBig>
 __global__ __launch_bounds__(256) void k_cnt_safe(const DevCountJob *__restrict__ jobs) {
   const DevCountJob &J = jobs[blockIdx.y];
-  const DevMir VL_GLOBAL &m = *as_global(J.mir);
   const uint32_t lane = threadIdx.x & 63u;
-  const uint64_t e0 = (uint64_t)blockIdx.x * kPairsPerGroup + (uint64_t)(threadIdx.x >> 6) * kPairsPerWave;
-  if (e0 >= J.n_pairs) return;
-  const uint64_t e1 = min(J.n_pairs, e0 + kPairsPerWave);
+  const uint32_t n_waves = gridDim.x * 4u;
+  const uint32_t wave = blockIdx.x * 4u + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  if ((uint64_t)wave * kPairsPerWave >= J.n_pairs) return;
   const uint32_t words = J.k_pad / 2;   // 32-bit words per table row (k_pad is a multiple of 64)
-  const uint32_t *table32 = reinterpret_cast<const uint32_t *>(J.table);
+  const uint32_t row_bytes = words * 4u;
+  // 1 in both halves, in a form the compiler cannot see through: a minimum with a known 1 is
+  // turned into two compares and a merge instead of one packed instruction
+  u16x2 one;
+  asm volatile("v_mov_b32 %0, 0x10001" : "=v"(one));
   for (uint32_t w0 = 0; w0 < words; w0 += 64) {
-    const uint32_t wi = min(w0 + lane, words - 1);   // lanes past the row repeat its last word; not counted
+    // lanes past the row repeat its last word; not counted
+    const uint32_t lane_off = min(w0 + lane, words - 1) * 4u;
+    // A row is fetched with a buffer read: descriptor and row offset in scalar registers, the
+    // lane brings its offset inside the row.  The scalar offset has 32 bits; for a table of
+    // 4 GB or more (kBig) every row gets a descriptor of its own instead.
+    const __amdgpu_buffer_rsrc_t whole = __builtin_amdgcn_make_buffer_rsrc((void *)J.table, 0, kBig ? 0 : (int)(J.V * row_bytes), 0x00020000);
+    auto row = [&](uint32_t packed) __attribute__((always_inline)) {   // this lane's word of the row of vreg (packed & 0xFFFFFF)
+      const uint32_t v = packed & 0xFFFFFFu;
+      if (kBig) {
+        const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((char *)J.table + (uint64_t)v * row_bytes, 0, (int)row_bytes, 0x00020000);
+        return both(__builtin_amdgcn_raw_buffer_load_b32(r, lane_off, 0, 0));
+      }
+      return both(__builtin_amdgcn_raw_buffer_load_b32(whole, lane_off, v * row_bytes, 0));
+    };
+    auto width2 = [&](uint32_t packed) __attribute__((always_inline)) {
+      const uint16_t width = (uint16_t)(packed >> 24);
+      return u16x2{width, width};
+    };
     uint32_t n_lo = 0, n_hi = 0;
-    for (uint64_t e = e0; e < e1; e += 64) {
-      uint32_t pa = 0, pb = 0, wa = 0, wb = 0;
-      if (e + lane < e1) {
-        pa = J.pairs[2 * (e + lane)];
-        pb = J.pairs[2 * (e + lane) + 1];
-        wa = attr_width(m.vattr[pa]);
-        wb = attr_width(m.vattr[pb]);
-      }
-      // Eight pairs at a time, their table reads in flight together.  Lanes past the last
-      // pair hold the pair (0, 0) with widths 0, which never overlaps, so no tail is needed.
-      const uint32_t cnt = (uint32_t)min((uint64_t)64, e1 - e);
-      for (uint32_t j = 0; j < cnt; j += 8) {
-        uint32_t ra[8], rb[8];
+    for (uint64_t e0 = (uint64_t)wave * kPairsPerWave; e0 < J.n_pairs; e0 += (uint64_t)n_waves * kPairsPerWave) {
+      const uint64_t e1 = min(J.n_pairs, e0 + kPairsPerWave);
+      // eight pairs per 64-byte piece; e0 is a multiple of 256
+      const u32x16 VL_CONSTANT *pieces = (const u32x16 VL_CONSTANT *)(uintptr_t)(J.pairs + 2 * e0);
+      u16x2 n = {0, 0};   // at most 256 per half
+      auto count = [&](u16x2 ra, u16x2 rb, u16x2 sa, u16x2 sb) __attribute__((always_inline)) {
+        const u16x2 u = __builtin_elementwise_sub_sat(ra, rb), v = __builtin_elementwise_sub_sat(rb, ra);
+        const u16x2 room = __builtin_elementwise_min(__builtin_elementwise_sub_sat(sb, u), __builtin_elementwise_sub_sat(sa, v));
+        n += __builtin_elementwise_min(room, one);
+      };
+      const uint32_t n_groups = (uint32_t)((e1 - e0 + kPairsAtOnce - 1) / kPairsAtOnce);
+      auto group = [&](const u32x16 lo, const u32x16 hi) __attribute__((always_inline)) {
+        u16x2 rb[kPairsAtOnce];
+        if ((lo[0] & 0xFFFFFFu) == (hi[14] & 0xFFFFFFu)) {
+          // the usual case: one row for a
+          const u16x2 ra = row(lo[0]), sa = width2(lo[0]);
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
-          const uint32_t a = __builtin_amdgcn_readlane(pa, (j + t) & 63u), b = __builtin_amdgcn_readlane(pb, (j + t) & 63u);
-          ra[t] = table32[(size_t)a * words + wi];
-          rb[t] = table32[(size_t)b * words + wi];
-        }
+          for (uint32_t t = 0; t < 8; ++t) { rb[t] = row(lo[2 * t + 1]); rb[8 + t] = row(hi[2 * t + 1]); }
+          __builtin_amdgcn_s_waitcnt(0x0F70);   // all rows at once (vmcnt 0) rather than one wait per pair
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
-          const uint32_t sa = __builtin_amdgcn_readlane(wa, (j + t) & 63u), sb = __builtin_amdgcn_readlane(wb, (j + t) & 63u);
-          const uint32_t al = ra[t] & 0xFFFFu, ah = ra[t] >> 16, bl = rb[t] & 0xFFFFu, bh = rb[t] >> 16;
-          n_lo += al < bl + sb && bl < al + sa;
-          n_hi += ah < bh + sb && bh < ah + sa;
+          for (uint32_t t = 0; t < 8; ++t) count(ra, rb[t], sa, width2(lo[2 * t + 1]));
+#pragma unroll
+          for (uint32_t t = 0; t < 8; ++t) count(ra, rb[8 + t], sa, width2(hi[2 * t + 1]));
+        } else {
+          u16x2 ra[kPairsAtOnce];
+#pragma unroll
+          for (uint32_t t = 0; t < 8; ++t) {
+            ra[t] = row(lo[2 * t]); rb[t] = row(lo[2 * t + 1]);
+            ra[8 + t] = row(hi[2 * t]); rb[8 + t] = row(hi[2 * t + 1]);
+          }
+          __builtin_amdgcn_s_waitcnt(0x0F70);
+#pragma unroll
+          for (uint32_t t = 0; t < 8; ++t) count(ra[t], rb[t], width2(lo[2 * t]), width2(lo[2 * t + 1]));
+#pragma unroll
+          for (uint32_t t = 0; t < 8; ++t) count(ra[8 + t], rb[8 + t], width2(hi[2 * t]), width2(hi[2 * t + 1]));
+        }
+      };
+      // two groups per turn, each one's pairs fetched while the other is counted
+      u32x16 a_lo = pieces[0], a_hi = pieces[1];
+      for (uint32_t g = 0; g < n_groups; g += 2) {
+        u32x16 b_lo = a_lo, b_hi = a_hi;
+        if (g + 1 < n_groups) { b_lo = pieces[2 * g + 2]; b_hi = pieces[2 * g + 3]; }
+        group(a_lo, a_hi);
+        if (g + 1 < n_groups) {
+          if (g + 2 < n_groups) { a_lo = pieces[2 * g + 4]; a_hi = pieces[2 * g + 5]; }
+          group(b_lo, b_hi);
         }
       }
+      n_lo += n.x;
+      n_hi += n.y;
     }
     const uint32_t k = 2 * (w0 + lane);
     if (w0 + lane < words) {
@@ -445,6 +513,7 @@ extern "C" int32_t vl_count_violations_multi(const vl_count_job *jobs, uint32_t 
   std::vector<size_t> at(n_jobs);
   uint32_t maxK = 0, maxV = 1, maxO = 1, max_kpad = 64;
   uint64_t max_pairs = 0;
+  bool big_table = false;   // some table has 4 GB or more
   for (uint32_t j = 0; j < n_jobs; ++j) {
     const uint32_t k_pad = (jobs[j].K + 63u) & ~63u;
     at[j] = bytes;
@@ -452,6 +521,7 @@ extern "C" int32_t vl_count_violations_multi(const vl_count_job *jobs, uint32_t 
     maxK = std::max(maxK, jobs[j].K); maxV = std::max(maxV, jobs[j].mir->h.V); maxO = std::max(maxO, jobs[j].mir->h.O);
     max_kpad = std::max(max_kpad, k_pad);
     max_pairs = std::max(max_pairs, jobs[j].mir->n_edges);
+    big_table |= (uint64_t)jobs[j].mir->h.V * k_pad * 2 >= (1ull << 32);
   }
   if (bytes > w.tables_cap) {
     if (w.tables) (void)hipFree(w.tables);
@@ -465,16 +535,20 @@ extern "C" int32_t vl_count_violations_multi(const vl_count_job *jobs, uint32_t 
     d.mir = jobs[j].mir->dev; d.live = jobs[j].live->dev; d.cand = jobs[j].cand; d.out = jobs[j].out;
     d.table = (uint16_t *)((char *)w.tables + at[j]);
     d.pairs = (const uint32_t *)jobs[j].mir->edges; d.n_pairs = jobs[j].mir->n_edges;
-    d.ld = jobs[j].ld; d.K = jobs[j].K; d.k_pad = (jobs[j].K + 63u) & ~63u;
+    d.ld = jobs[j].ld; d.K = jobs[j].K; d.k_pad = (jobs[j].K + 63u) & ~63u; d.V = jobs[j].mir->h.V;
   }
   VL_HIP(hipMemcpyAsync(w.dev, w.host, (size_t)n_jobs * sizeof(DevCountJob), hipMemcpyHostToDevice, stream));
   const uint32_t tiles_k = max_kpad / 64, tiles_v = (maxV + 63) / 64;
-  const uint32_t stretches = (uint32_t)std::max<uint64_t>(1, (max_pairs + kPairsPerGroup - 1) / kPairsPerGroup);
+  const uint32_t stretches = (uint32_t)std::min<uint64_t>(1u << 20, std::max<uint64_t>(1, (max_pairs + kPairsPerGroup - 1) / kPairsPerGroup));
   k_cnt_clear<<<dim3((maxK + 255) / 256, n_jobs), 256, 0, stream>>>(w.dev);
   k_cnt_table<<<dim3(tiles_v * tiles_k, n_jobs), 256, 0, stream>>>(w.dev, tiles_k);
   k_cnt_cons<<<dim3((maxO + 1023) / 1024, tiles_k, n_jobs), 256, 0, stream>>>(w.dev);
   k_cnt_real<<<dim3((maxV + 255) / 256, tiles_k, n_jobs), 256, 0, stream>>>(w.dev);
-  k_cnt_safe<<<dim3(stretches, n_jobs), 256, 0, stream>>>(w.dev);
+  {
+    const dim3 grid(std::min(stretches, kSafeGroupsPerProgram), n_jobs);
+    if (big_table) k_cnt_safe<true><<<grid, 256, 0, stream>>>(w.dev);
+    else k_cnt_safe<false><<<grid, 256, 0, stream>>>(w.dev);
+  }
   k_cnt_kinds<<<dim3((maxK + 255) / 256, n_jobs), 256, 0, stream>>>(w.dev);
   VL_HIP(hipGetLastError());
   VL_HIP(hipEventRecord(w.consumed, stream));
