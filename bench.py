@@ -361,6 +361,23 @@ def extras(args, vl, measure, hip, torch, np, w, mirs, lives, jobs, dev_rows, ld
                              "candidates_per_s": w.n_candidates / count_ms * 1e3,
                              "kinds_histogram": np.bincount(kinds, minlength=8).tolist()}
 
+    # register-bank conflict score of every candidate (four banks, as in the paper's example):
+    # one call per kernel
+    score_outs = [torch.zeros(r.shape[0], dtype=torch.int32, device="cuda") for r in w.rows]
+    def score_pass():
+        for m, d, r, ld, o in zip(mirs, dev_rows, w.rows, lds, score_outs):
+            vl.vl_bank_conflicts(m, d, r.shape[0], ld, 4, o, stream)
+    score_pass()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(3):
+        score_pass()
+    torch.cuda.synchronize()
+    score_ms = (time.perf_counter() - t1) / 3 * 1e3
+    stalls = np.concatenate([o.cpu().numpy() for o in score_outs]).astype(np.int64)
+    out["bank_score"] = {"ms_per_pass": score_ms, "candidates_per_s": w.n_candidates / score_ms * 1e3,
+                         "banks": 4, "mean_stall_cycles_per_instruction": float(stalls.sum()) / w.n_checks}
+
     # the same candidates stored occurrence-major (how a batched decoder leaves them):
     # verification only, results compared with the row-major ones
     t_jobs, t_keep, t_outs = [], [], []
