@@ -196,7 +196,10 @@ enum { VL_BAD_BOUNDS = 1, VL_BAD_ALIGN = 2, VL_BAD_RESERVED = 4 };
 /* Checks K candidates of one kernel (Section 3.4; Section 3.4's regeneration
  * loop supplies the K samples).  cand [device]: K rows of uint16, row k at
  * cand + k*ld, one physical base register per operand occurrence; ld >= n_occ.
- * Rows are read fastest when cand is 16-byte aligned and ld is a multiple of 8.
+ * Rows are read fastest when cand is 16-byte aligned and ld is a multiple of 8; when ld is
+ * also at least n_occ rounded up to a multiple of 64, rows are fetched in whole 128-byte
+ * lines up to that bound, so all K x ld elements must then belong to the buffer (what the
+ * padding holds is ignored).
  * out [device]: K results.  Asynchronous on `stream`. */
 int32_t vl_verify_batch(const vl_mir *mir, const vl_live *live, const uint16_t *cand, uint32_t K,
                         uint64_t ld, vl_result *out, vl_stream stream);

@@ -55,7 +55,9 @@ struct DevJob {
   const uint16_t *cand;
   vl_result *out;
   uint64_t ld;
-  uint32_t K, rows, n_groups, unit_base, n_units, fast, transposed, pad1;   // transposed: cand is [occurrence][candidate]
+  uint32_t K, rows, n_groups, unit_base, n_units, fast, transposed, direct;   // transposed: cand is [occurrence][candidate]
+  // direct: row-major, aligned, every row holds whole chunks up to its pitch, and a group of rows spans less than
+  // 4 GB (its chunks are fetched with 32-bit offsets and no bounds)
 };
 
 __device__ inline uint32_t find_job(const DevJob *jobs, uint32_t n_jobs, uint32_t unit) {
@@ -109,6 +111,9 @@ struct Walk {
   // readable occurrences: [max(lo, hi - kWalkReach), hi); hi is the end of the chunk being processed
   uint32_t tid, lane, row, nrows, n_occ, lo, hi, fast;
   uint32_t pre[kStagePasses][4];     // check wavefronts: their share of the chunk being fetched
+  // direct staging: per pass, this lane's byte offset into the group's rows and its uint16 index into
+  // ring slot 0 (kNone in from_row: the pass has no row for this lane)
+  uint32_t from_row[kStagePasses], to_ring[kStagePasses];
 };
 
 // Staging is done by the three check wavefronts.  A chunk is 64 rows x 8 pieces of 16 bytes
@@ -189,6 +194,37 @@ __device__ inline void store_chunk(const Walk &w, uint32_t c0, uint32_t j) {
   }
 }
 
+// Direct staging, when every job of the launch allows it (DevJob::direct): without the
+// per-lane bounds of the general path, a buffer read per pass (descriptor of the group's rows
+// and the chunk's byte offset in scalar registers, the lane's row offset from set-up) and
+// eight 2-byte stores from an address that only needs the chunk's slot added.  Rows past the
+// group's last are never written; their ring entries are cleared once at the start.  What a
+// row holds beyond the program's last occurrence (up to its pitch) lands in the ring and is
+// never looked at.
+__device__ inline void load_chunk_direct(Walk &w, uint32_t c0, __amdgpu_buffer_rsrc_t rows) {
+#pragma unroll
+  for (int h = 0; h < kStagePasses; ++h) {
+    if (w.from_row[h] == kNone) continue;
+    const u32x4 x = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rows, w.from_row[h], c0 * 2u, 0));
+    w.pre[h][0] = x.x; w.pre[h][1] = x.y; w.pre[h][2] = x.z; w.pre[h][3] = x.w;
+  }
+}
+
+template <uint32_t kRingStride>
+__device__ inline void store_chunk_direct(const Walk &w, uint32_t c0) {
+  const uint32_t slot = (c0 % kRing) * kRingStride;
+#pragma unroll
+  for (int h = 0; h < kStagePasses; ++h) {
+    if (w.from_row[h] == kNone) continue;
+    const uint32_t dst = w.to_ring[h] + slot;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      VL_LDS16[dst + (2 * t) * kRingStride] = (uint16_t)w.pre[h][t];
+      VL_LDS16[dst + (2 * t + 1) * kRingStride] = (uint16_t)(w.pre[h][t] >> 16);
+    }
+  }
+}
+
 __device__ inline bool in_ring(const Walk &w, uint32_t o) {
   return o < w.hi && o + kWalkReach >= w.hi && o >= w.lo;
 }
@@ -248,7 +284,7 @@ __device__ inline bool unrealizable(const DevMir VL_GLOBAL &m, uint32_t attr, ui
   return bad;
 }
 
-template <uint32_t kRingStride, bool kT>
+template <uint32_t kRingStride, bool kT, bool kDirect>
 __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(6))) void k_walk(const DevJob *__restrict__ jobs, uint32_t n_jobs) {
   // Workgroups go to the eight dies of the device in turn, each die with an L2 of its own.
   // Inside every 16 consecutive workgroup indices, units 2x and 2x + 1 are given to indices
@@ -287,6 +323,11 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(6)
   w.ring16 = (w.keys + 64 + 256) * 2;
   for (uint32_t x = w.tid; x < m.occ_words * 64; x += kWalkThreads) vl_lds[x] = 0;
   if (w.tid < 64) vl_lds[w.keys + w.tid] = kKeyOk;
+  if (kDirect) {
+    // ring entries of the rows past the group's last: zero, and never written again
+    const uint32_t spare = kRingStride - w.nrows;
+    for (uint32_t x = w.tid; x < spare * kRing; x += kWalkThreads) VL_LDS16[w.ring16 + (x / spare) * kRingStride + w.nrows + x % spare] = 0;
+  }
   // per-class file size and first mask word, one class per lane, read back by lane index
   const uint32_t cls_tab_v = w.lane < m.C ? ((uint32_t)m.class_size[w.lane] | ((uint32_t)m.class_word[w.lane] << 16)) : 0u;
   uint32_t key = kKeyOk;   // event role and far checks: this lane's row
@@ -614,19 +655,36 @@ __global__ __launch_bounds__(kWalkThreads) __attribute__((amdgpu_waves_per_eu(6)
     }
   } else {
     const uint32_t j = role - 1;
-    for (uint32_t c = c_first; c <= ca && c < c_end; ++c) {   // history chunk and the tile's first chunk
-      load_chunk<kT>(w, c * kChunk, j);
-      store_chunk<kRingStride, kT>(w, c * kChunk, j);
+    // direct staging: this lane's row of every pass
+    const __amdgpu_buffer_rsrc_t rows_desc = __builtin_amdgcn_make_buffer_rsrc((void *)w.rows, 0, -1, 0x00020000);
+#pragma unroll
+    for (int h = 0; h < kStagePasses; ++h) {
+      const uint32_t q = j + kCheckWaves * h, r = staged_row(w.lane, q);
+      const bool has_row = kDirect && q < 8u && r < w.nrows;
+      w.from_row[h] = has_row ? (uint32_t)((r * w.ld + (w.lane & 7u) * 8u) * 2u) : kNone;
+      w.to_ring[h] = w.ring16 + (w.lane & 7u) * 8u * kRingStride + r;
     }
-    if (ca + 1 < c_end) load_chunk<kT>(w, (ca + 1) * kChunk, j);
+    auto stage_load = [&](uint32_t c0) __attribute__((always_inline)) {
+      if (kDirect) load_chunk_direct(w, c0, rows_desc);
+      else load_chunk<kT>(w, c0, j);
+    };
+    auto stage_store = [&](uint32_t c0) __attribute__((always_inline)) {
+      if (kDirect) store_chunk_direct<kRingStride>(w, c0);
+      else store_chunk<kRingStride, kT>(w, c0, j);
+    };
+    for (uint32_t c = c_first; c <= ca && c < c_end; ++c) {   // history chunk and the tile's first chunk
+      stage_load(c * kChunk);
+      stage_store(c * kChunk);
+    }
+    if (ca + 1 < c_end) stage_load((ca + 1) * kChunk);
     u32x4 chk_next = load_chk(ca);
     if (tile > 0) seed_events(g_seed_off[tile], g_seed_off[tile + 1], j);   // this wavefront's share of the live-in list
     __syncthreads();
     for (uint32_t c = ca; c != c_stop; ++c) {
       if (c < c_end) {
         if (c + 1 < c_end) {
-          store_chunk<kRingStride, kT>(w, (c + 1) * kChunk, j);
-          if (c + 2 < c_end) load_chunk<kT>(w, (c + 2) * kChunk, j);
+          stage_store((c + 1) * kChunk);
+          if (c + 2 < c_end) stage_load((c + 2) * kChunk);
         }
         w.hi = (c + 1) * kChunk;
         const u32x4 raw = chk_next;
@@ -796,6 +854,7 @@ struct Launch {
   uint2 *work = nullptr;
   uint64_t total_rows = 0;
   uint32_t units = 0, maxK = 0, max_words = 0, max_w = 1, max_rows = 0;
+  bool all_direct = true;   // every job can be staged with 32-bit offsets and without bounds (DevJob::direct)
 };
 
 // Validates one job, lays out its entry of the device job table and adds it to the launch.
@@ -809,6 +868,10 @@ int32_t fill_job(const vl_job &u, bool transposed, DevJob &d, Launch &out, bool 
   d.mir = u.mir->dev; d.live = u.live->dev; d.cand = u.cand; d.out = u.out; d.ld = u.ld; d.K = u.K;
   d.fast = (((uintptr_t)u.cand & 15) == 0 && (u.ld & 7) == 0) ? 1u : 0u;
   d.transposed = transposed ? 1u : 0u;
+  // whole chunks can be read from every row: the pitch covers the last chunk, and a group spans less than 4 GB
+  d.direct = (d.fast && !transposed && u.ld >= (((uint64_t)u.mir->h.O + kChunk - 1) / kChunk) * kChunk &&
+              64ull * u.ld * 2 + 4096 < (1ull << 32)) ? 1u : 0u;
+  out.all_direct = out.all_direct && d.direct;
   // groups of up to 64 candidates; every group but the last has d.rows of them
   d.n_groups = (u.K + 63) / 64;
   d.rows = (u.K + d.n_groups - 1) / d.n_groups;
@@ -988,11 +1051,16 @@ int32_t launch_all(const Launch &L, uint32_t n_jobs, hipStream_t stream, bool tr
   k_init<<<dim3((L.maxK + 255) / 256, n_jobs), 256, 0, stream>>>(L.dev, L.work);
   if (g_time_start) VL_HIP(hipEventRecord(g_time_start, stream));
   if (transposed) {
-    if (narrow) k_walk<kPitchNarrow, true><<<L.units, kWalkThreads, lds, stream>>>(L.dev, n_jobs);
-    else k_walk<kPitchWide, true><<<L.units, kWalkThreads, lds, stream>>>(L.dev, n_jobs);
+    if (narrow) k_walk<kPitchNarrow, true, false><<<L.units, kWalkThreads, lds, stream>>>(L.dev, n_jobs);
+    else k_walk<kPitchWide, true, false><<<L.units, kWalkThreads, lds, stream>>>(L.dev, n_jobs);
   } else {
-    if (narrow) k_walk<kPitchNarrow, false><<<L.units, kWalkThreads, lds, stream>>>(L.dev, n_jobs);
-    else k_walk<kPitchWide, false><<<L.units, kWalkThreads, lds, stream>>>(L.dev, n_jobs);
+    if (L.all_direct) {
+      if (narrow) k_walk<kPitchNarrow, false, true><<<L.units, kWalkThreads, lds, stream>>>(L.dev, n_jobs);
+      else k_walk<kPitchWide, false, true><<<L.units, kWalkThreads, lds, stream>>>(L.dev, n_jobs);
+    } else {
+      if (narrow) k_walk<kPitchNarrow, false, false><<<L.units, kWalkThreads, lds, stream>>>(L.dev, n_jobs);
+      else k_walk<kPitchWide, false, false><<<L.units, kWalkThreads, lds, stream>>>(L.dev, n_jobs);
+    }
   }
   if (g_time_stop) VL_HIP(hipEventRecord(g_time_stop, stream));
   g_time_start = g_time_stop = nullptr;
