@@ -38,10 +38,18 @@ def gpu_analyze(mirs, tile_len=0, dense=True):
 
 
 def gpu_verify(hm, hl, rows_list, aligned=True):
+    """aligned: True = rows padded to whole 128-byte lines (staged without bounds), "pitch8" =
+    16-byte aligned rows whose pitch is the next multiple of 8 (16-byte reads with bounds),
+    False = odd pitch from a 2-byte aligned start (element by element)"""
     jobs, outs, keep = [], [], []
     for m, l, rows in zip(hm, hl, rows_list):
         K, O = rows.shape
-        if aligned:
+        if aligned == "pitch8":
+            ld = (O + 7) // 8 * 8
+            host = np.zeros((K, ld), np.uint16)
+            host[:, :O] = rows
+            dev = torch.from_numpy(host.view(np.int16)).cuda()
+        elif aligned:
             dev, ld = vl.rows_to_device(rows)
         else:  # odd pitch, 2-byte aligned start: the element-wise staging path
             ld = O + 1 if (O + 1) % 2 else O + 2
@@ -141,7 +149,7 @@ def test_configs_full_size(cfg):
     for tile_len in (0, 97, 512):   # the default (which follows the size of the batch), an odd one, the benchmark's
         hm, hl, got, views = gpu_analyze([k.mir], tile_len)
         assert_liveness_equal(k.mir, an, got[0], f"config {cfg}")
-        for aligned in (True, False):
+        for aligned in (True, "pitch8", False):
             res = gpu_verify(hm, hl, [rows], aligned)
             assert_results_equal(want, res[0], f"config {cfg} tile {tile_len} aligned {aligned}")
         free(hm, hl)
