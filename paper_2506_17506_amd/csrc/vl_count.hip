@@ -156,7 +156,9 @@ __global__ void k_cnt_clear(const DevCountJob *__restrict__ jobs) {
 }
 
 // table[v][k] = cand[k][first[v]] through a 64 x 64 tile in LDS: reads run along a candidate
-// row (first occurrences mostly ascend with the vreg), writes along the candidates
+// row (first occurrences mostly ascend with the vreg), writes along the candidates.  The
+// thread that writes a candidate's entries also tests them against the hardware rules
+// (realizability: the vregs that are mentioned, each once).
 __global__ __launch_bounds__(256) void k_cnt_table(const DevCountJob *__restrict__ jobs, uint32_t tiles_k) {
   const DevCountJob &J = jobs[blockIdx.y];
   const DevMir VL_GLOBAL &m = *as_global(J.mir);
@@ -164,16 +166,30 @@ __global__ __launch_bounds__(256) void k_cnt_table(const DevCountJob *__restrict
   const uint32_t v0 = (blockIdx.x / tiles_k) * 64, k0 = (blockIdx.x % tiles_k) * 64;
   if (v0 >= m.V || k0 >= J.k_pad) return;
   __shared__ uint16_t tile[64][66];
+  __shared__ uint32_t attrs[64];   // kNone: never mentioned, or past the last vreg
   const uint32_t tx = threadIdx.x & 63u, ty = threadIdx.x >> 6;
   const uint32_t v = v0 + tx;
   const uint32_t fo = v < m.V ? L.first[v] : kNone;
+  if (ty == 0) attrs[tx] = fo != kNone ? m.vattr[v] : kNone;
   for (uint32_t kk = ty; kk < 64; kk += 4) {
     const uint32_t k = k0 + kk;
     tile[kk][tx] = (k < J.K && fo != kNone) ? J.cand[(uint64_t)k * J.ld + fo] : (uint16_t)0;
   }
   __syncthreads();
-  for (uint32_t vv = ty; vv < 64; vv += 4)
-    if (v0 + vv < m.V && k0 + tx < J.k_pad) J.table[(size_t)(v0 + vv) * J.k_pad + k0 + tx] = tile[tx][vv];
+  uint32_t n = 0, bits = 0;
+  for (uint32_t vv = ty; vv < 64; vv += 4) {
+    if (v0 + vv >= m.V || k0 + tx >= J.k_pad) continue;
+    const uint32_t p = tile[tx][vv];
+    J.table[(size_t)(v0 + vv) * J.k_pad + k0 + tx] = (uint16_t)p;
+    if (attrs[vv] == kNone) continue;
+    const uint32_t bad = bad_bits(m, attrs[vv], p);
+    n += bad != 0;
+    bits |= bad;
+  }
+  if (k0 + tx < J.K && n) {
+    atomicAdd(&J.out[k0 + tx].n_real, n);
+    atomicOr(&J.out[k0 + tx].real_bits, bits);
+  }
 }
 
 // consistency: a workgroup takes 64 candidates (blockIdx.y) and 1024 occurrences.  64
@@ -214,40 +230,6 @@ __global__ __launch_bounds__(256) void k_cnt_cons(const DevCountJob *__restrict_
     __syncthreads();
   }
   if (k0 + lane < J.K && n) atomicAdd(&J.out[k0 + lane].n_cons, n);
-}
-
-// realizability: a wavefront takes 64 candidates (one per lane) and 64 vregs, whose table
-// rows it reads one after the other
-__global__ __launch_bounds__(256) void k_cnt_real(const DevCountJob *__restrict__ jobs) {
-  const DevCountJob &J = jobs[blockIdx.z];
-  const DevMir VL_GLOBAL &m = *as_global(J.mir);
-  const DevLive VL_GLOBAL &L = *as_global(J.live);
-  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-  const uint32_t k = blockIdx.y * 64 + lane, v0 = blockIdx.x * 256 + wave * 64;
-  if (blockIdx.y * 64 >= J.K || v0 >= m.V) return;
-  // one vreg per lane: its attributes, or none when it is never mentioned
-  const uint32_t my_v = v0 + lane;
-  const bool mentioned = my_v < m.V && L.first[my_v] != kNone;
-  const uint32_t my_attr = mentioned ? m.vattr[my_v] : kNone;
-  uint32_t n = 0, bits = 0;
-  const uint32_t v_end = min(64u, m.V - v0);
-  for (uint32_t t0 = 0; t0 < v_end; t0 += 16) {   // 16 table rows in flight
-    uint32_t p[16];
-#pragma unroll
-    for (uint32_t u = 0; u < 16; ++u) p[u] = J.table[(size_t)min(v0 + t0 + u, m.V - 1) * J.k_pad + k];
-#pragma unroll
-    for (uint32_t u = 0; u < 16; ++u) {
-      const uint32_t attr = __builtin_amdgcn_readlane(my_attr, t0 + u);   // none past the last vreg
-      if (attr == kNone) continue;
-      const uint32_t bad = bad_bits(m, attr, p[u]);
-      n += bad != 0;
-      bits |= bad;
-    }
-  }
-  if (k < J.K && n) {
-    atomicAdd(&J.out[k].n_real, n);
-    atomicOr(&J.out[k].real_bits, bits);
-  }
 }
 
 // safety: the wavefronts of a program take its pairs in stretches of 256 and walk each once
@@ -543,7 +525,6 @@ extern "C" int32_t vl_count_violations_multi(const vl_count_job *jobs, uint32_t 
   k_cnt_clear<<<dim3((maxK + 255) / 256, n_jobs), 256, 0, stream>>>(w.dev);
   k_cnt_table<<<dim3(tiles_v * tiles_k, n_jobs), 256, 0, stream>>>(w.dev, tiles_k);
   k_cnt_cons<<<dim3((maxO + 1023) / 1024, tiles_k, n_jobs), 256, 0, stream>>>(w.dev);
-  k_cnt_real<<<dim3((maxV + 255) / 256, tiles_k, n_jobs), 256, 0, stream>>>(w.dev);
   {
     const dim3 grid(std::min(stretches, kSafeGroupsPerProgram), n_jobs);
     if (big_table) k_cnt_safe<true><<<grid, 256, 0, stream>>>(w.dev);
