@@ -120,9 +120,10 @@ struct Walk {
 // (8 occurrences); piece k of row r goes to lane (k, rr) of pass q with
 //   r = y + 2 rr + 16 ((k >> 2) ^ u) + 32 z,   q = y + 2 z + 4 u  (0..7),
 // the two halves of a 128-byte line (k < 4, k >= 4) belonging to rows 16 apart.  With this
-// assignment the 64 lanes of every LDS store below fall into 64 different banks (slot pitch
-// 34 or 26 dwords, both 2 modulo 8: bank = 16 (k & 3) + 8 (row bit 4) + rr + const).  Check
-// wavefront j takes the passes j, j + 3, j + 6.
+// assignment the 64 lanes of every LDS store below write into 64 different 4-byte words,
+// two per bank (slot pitch 34 or 26 dwords, both 2 modulo 8: word = 16 (k & 3) + 8 (row bit
+// 4) + rr + const modulo 64), which the 32 banks take in two passes: the least a 64-lane
+// store can take.  Check wavefront j takes the passes j, j + 3, j + 6.
 __device__ inline uint32_t staged_row(uint32_t lane, uint32_t q) {
   const uint32_t k = lane & 7u, rr = lane >> 3;
   return (q & 1u) + 2u * rr + 16u * ((k >> 2) ^ (q >> 2)) + 32u * ((q >> 1) & 1u);
